@@ -1,0 +1,333 @@
+"""Pins for the CPU oracle: each test checks it against something fixed by the paper or by
+mathematics (brute force from eq. 5, special cases, invariants, closed forms, a library conv).
+CPU only.  The paper prints no numeric worked example of the mechanism, so there is no golden
+value file for it; tests/golden/ holds only the hyper-parameters the paper states."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import ltea_oracle as orc
+from tests.helpers import (brute_force_keep, dense_masked_attention, oracle_cfg, oracle_cnn, small_prefill)
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def run_prefill(w):
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    return cfg, cnn, orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+
+
+# ---- P1: dense masked softmax from eq. 5 == sparse path --------------------------------------
+@pytest.mark.parametrize("seed,n,window,budget,sink,G", [(0, 40, 12, 5, 0, 1), (1, 57, 9, 7, 2, 2),
+                                                         (2, 33, 16, 3, 4, 1), (3, 64, 8, 40, 0, 2)])
+def test_p1_dense_mask_equals_sparse(seed, n, window, budget, sink, G):
+    w = small_prefill(seed=seed, seqlens=(n,), Hq=2 * G, Hkv=2, window=window, budget=budget, sink=sink)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    keep = [brute_force_keep(orc.selection_key(z[h], sink), n, window, budget, sink, 0.0) for h in range(2)]
+    for h in range(2):
+        assert list(kept[0][h]) == keep[h]
+    ref = dense_masked_attention(w.q, w.k, w.v, keep, window, cfg.sigma, G)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+
+
+# ---- P2 / P3: special cases ------------------------------------------------------------------
+def test_p2_budget_zero_is_sliding_window():
+    w = small_prefill(seed=4, seqlens=(50,), window=10, budget=0, sink=3)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    assert all(len(r) == 0 for r in kept[0])
+    ref = dense_masked_attention(w.q, w.k, w.v, [[], []], 10, cfg.sigma, 1)
+    np.testing.assert_allclose(out, ref, atol=1e-12)
+    # textbook SWA row: query 30 sees exactly positions 21..30
+    q = w.q.astype(np.float64); k = w.k.astype(np.float64); v = w.v.astype(np.float64)
+    s = cfg.sigma * (k[21:31, 0] @ q[30, 0]); p = np.exp(s - s.max()); p /= p.sum()
+    np.testing.assert_allclose(out[30, 0], p @ v[21:31, 0], atol=1e-12)
+
+
+def test_p3_window_covers_sequence_is_full_causal():
+    w = small_prefill(seed=5, seqlens=(30,), window=30, budget=8)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    assert all(len(r) == 0 for r in kept[0])
+    n = 30
+    q = w.q.astype(np.float64); k = w.k.astype(np.float64); v = w.v.astype(np.float64)
+    for h in range(2):
+        s = cfg.sigma * (q[:, h] @ k[:, h].T)
+        s = np.where(np.tril(np.ones((n, n), bool)), s, -np.inf)
+        p = np.exp(s - s.max(1, keepdims=True)); p /= p.sum(1, keepdims=True)
+        np.testing.assert_allclose(out[:, h], p @ v[:, h], atol=1e-12)
+
+
+# ---- P4: budget invariants -------------------------------------------------------------------
+def test_p4_budget_invariants():
+    w = small_prefill(seed=6, seqlens=(80,), window=10, budget=6, sink=2)
+    cnn = oracle_cnn(w.cnn)
+    z = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    for h in range(2):
+        prev = set()
+        for b in range(0, 75):
+            R = orc.retain(z[h], 80, 10, b, 2, 0.0)
+            assert len(R) <= b
+            assert all(0 <= j < 70 for j in R)
+            assert all((j < 2) or np.float32(z[h, j]) > 0 for j in R)
+            assert prev <= set(R)                       # nested in the budget
+            if b >= 2:
+                assert {0, 1} <= set(R)                 # sinks are never displaced
+            prev = set(R)
+            assert list(R) == brute_force_keep(orc.selection_key(z[h], 2), 80, 10, b, 2, 0.0)
+
+
+def test_p4_ties_and_nan():
+    z = np.array([0.5, 0.5, np.nan, 0.5, 0.7, 0.5, -1.0, 0.5] + [0.0] * 4, dtype=np.float64)
+    # n=12, window=4 -> evictable 0..7; candidates: 0,1,3,4,5,7 (NaN and -1 never)
+    assert list(orc.retain(z, 12, 4, 10, 0, 0.0)) == [0, 1, 3, 4, 5, 7]
+    # cap 3: best key 0.7 (pos 4), then equal keys by ascending position: 0, 1
+    assert list(orc.retain(z, 12, 4, 3, 0, 0.0)) == [0, 1, 4]
+    # tau = -inf: pure top-b, NaN still never a candidate
+    assert list(orc.retain(z, 12, 4, 7, 0, -np.inf)) == [0, 1, 3, 4, 5, 6, 7]
+    # +inf logits are legal and tie with sinks by position
+    z2 = np.array([0.1, np.inf, 0.2, np.inf, 0.3, 0.0, 0.0, 0.0], dtype=np.float64)
+    assert list(orc.retain(z2, 8, 3, 2, 1, 0.0)) == [0, 1]
+
+
+# ---- P5: streaming retention == batch retention; prefill + decode == longer prefill ---------
+@pytest.mark.parametrize("seed,n,window,budget,sink,kernel,dil", [(7, 45, 9, 4, 0, (3,), None), (8, 60, 13, 6, 2, (5,), None),
+                                                                  (9, 50, 15, 5, 1, (3, 3), (2, 1))])
+def test_p5_decode_from_empty_matches_prefill_state(seed, n, window, budget, sink, kernel, dil):
+    ch = (4,) * len(kernel)
+    w = small_prefill(seed=seed, seqlens=(n,), window=window, budget=budget, sink=sink, kernel=kernel, channels=ch, dilation=dil)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    st = orc.empty_state(cfg)
+    for t in range(n):
+        orc.decode_step(st, w.q[t], w.k[t], w.v[t], cfg, cnn)
+        # streaming set after token t == batch rule on the prefix of length t+1
+        for h in range(cfg.Hkv):
+            ref = orc.retain(z[h, :t + 1], t + 1, window, budget, sink, 0.0)
+            assert list(orc.retained_positions(st)[h]) == list(ref), (t, h)
+    ref_state = states[0]
+    assert st.n_seen == ref_state.n_seen and st.n_scored == ref_state.n_scored
+    for h in range(cfg.Hkv):
+        a, b = st.heads[h], ref_state.heads[h]
+        assert a.win_pos == b.win_pos
+        assert sorted(a.ret_pos) == sorted(b.ret_pos)
+        for j in b.win_z:
+            assert abs(a.win_z[j] - b.win_z[j]) < 1e-12
+        ia, ib = np.argsort(a.ret_pos), np.argsort(b.ret_pos)
+        np.testing.assert_array_equal(np.array(a.ret_key)[ia], np.array(b.ret_key)[ib])
+        np.testing.assert_allclose(np.stack(a.win_k), np.stack(b.win_k))
+        if b.ret_pos:
+            np.testing.assert_allclose(np.stack(a.ret_k)[ia], np.stack(b.ret_k)[ib])
+            np.testing.assert_allclose(np.stack(a.ret_v)[ia], np.stack(b.ret_v)[ib])
+
+
+def test_p5_prefill_then_decode_equals_longer_prefill():
+    n, extra = 40, 17
+    w = small_prefill(seed=10, seqlens=(n + extra,), window=11, budget=5, sink=1, kernel=(5,))
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    _, st_long, z_long, kept_long = orc.prefill(w.q, w.k, w.v, cfg, cnn, [0, n + extra])
+    _, st_short, _, _ = orc.prefill(w.q[:n], w.k[:n], w.v[:n], cfg, cnn, [0, n])
+    st = st_short[0]
+    for t in range(n, n + extra):
+        orc.decode_step(st, w.q[t], w.k[t], w.v[t], cfg, cnn)
+    for h in range(cfg.Hkv):
+        assert list(orc.retained_positions(st)[h]) == list(kept_long[0][h])
+        assert st.heads[h].win_pos == st_long[0].heads[h].win_pos
+        for j, zj in st_long[0].heads[h].win_z.items():
+            assert abs(st.heads[h].win_z[j] - zj) < 1e-12
+
+
+# ---- P6: when the cap never binds, prefill == step-by-step decode == uncapped eq. 5 ---------
+def test_p6_cap_not_binding_prefill_equals_decode():
+    n = 48
+    w = small_prefill(seed=11, seqlens=(n,), window=10, budget=n, sink=2)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    st = orc.empty_state(cfg)
+    dec = np.stack([orc.decode_step(st, w.q[t], w.k[t], w.v[t], cfg, cnn) for t in range(n)])
+    np.testing.assert_allclose(dec, out, atol=1e-12)
+    keep = [[j for j in range(n) if j < 2 or np.float32(z[h, j]) > 0] for h in range(2)]   # eq. 5, no cap
+    ref = dense_masked_attention(w.q, w.k, w.v, keep, 10, cfg.sigma, 1)
+    np.testing.assert_allclose(out, ref, atol=1e-12)
+
+
+# ---- P7: library grouped convolution ---------------------------------------------------------
+@pytest.mark.parametrize("kernel,dil,ch", [((5,), (1,), (6,)), ((3, 3, 3), (2, 2, 2), (8, 4, 2)), ((7,), (1,), (3,))])
+def test_p7_library_grouped_conv(kernel, dil, ch):
+    import torch
+    import torch.nn.functional as F
+    n, Hkv, D = 37, 3, 4
+    w = small_prefill(seed=12, seqlens=(n,), Hq=Hkv, Hkv=Hkv, D=D, kernel=kernel, channels=ch, dilation=dil, window=20)
+    cnn = oracle_cnn(w.cnn)
+    z = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    x = torch.from_numpy(np.concatenate([w.k, w.v], axis=2).astype(np.float64))      # [n, Hkv, 2D]
+    x = x.permute(1, 2, 0).reshape(1, Hkv * 2 * D, n)
+    for l, (ks, d) in enumerate(zip(kernel, dil)):
+        W = torch.from_numpy(w.cnn.w[l].astype(np.float64))                          # [Hkv, Co, Ci, ks]
+        Wg = W.reshape(Hkv * W.shape[1], W.shape[2], ks)
+        b = torch.from_numpy(w.cnn.bias[l].astype(np.float64)).reshape(-1)
+        x = F.silu(F.conv1d(x, Wg, b, padding=d * (ks - 1) // 2, dilation=d, groups=Hkv))
+    Wo = torch.from_numpy(w.cnn.w_out.astype(np.float64)).reshape(Hkv, -1, 1)
+    zz = F.conv1d(x, Wo, torch.from_numpy(w.cnn.b_out.astype(np.float64)), groups=Hkv)[0].numpy()
+    np.testing.assert_allclose(z, zz, atol=1e-12)
+
+
+# ---- P8: closed forms of the CNN --------------------------------------------------------------
+def test_p8_cnn_closed_forms():
+    n, Hkv, D, C, ks = 20, 2, 3, 2, 5
+    rng = np.random.default_rng(13)
+    k = rng.standard_normal((n, Hkv, D)); v = rng.standard_normal((n, Hkv, D))
+    W = np.zeros((Hkv, C, 2 * D, ks)); bias = np.zeros((Hkv, C))
+    w_out = np.array([[1.5, 0.0], [0.0, -2.0]]); b_out = np.array([0.25, -0.5])
+    # all-zero conv weights: z == b_out everywhere
+    z = orc.score(k, v, orc.cnn_from_arrays([ks], [1], [W], [bias], w_out, b_out), [0, n])
+    np.testing.assert_allclose(z, np.repeat(b_out[:, None], n, 1), atol=0)
+    # ... so with b_out > tau the kept set is the budget's lowest positions; with b_out <= tau only sinks
+    assert list(orc.retain(z[0], n, 4, 3, 0, 0.0)) == [0, 1, 2]
+    assert list(orc.retain(z[1], n, 4, 3, 2, 0.0)) == [0, 1]
+    sil = lambda x: x / (1 + np.exp(-x))
+    # one-hot centre tap on key channel 1 (head 0, out channel 0) / value channel 2 (head 1, channel 1)
+    W1 = W.copy(); W1[0, 0, 1, 2] = 1.0; W1[1, 1, D + 2, 2] = 1.0
+    z = orc.score(k, v, orc.cnn_from_arrays([ks], [1], [W1], [bias], w_out, b_out), [0, n])
+    np.testing.assert_allclose(z[0], 0.25 + 1.5 * sil(k[:, 0, 1]), atol=1e-14)
+    np.testing.assert_allclose(z[1], -0.5 - 2.0 * sil(v[:, 1, 2]), atol=1e-14)
+    # one-hot tap 0 reads position j-2 (past), tap 4 reads j+2 (future); outside -> zero
+    W2 = W.copy(); W2[0, 0, 1, 0] = 1.0; W2[1, 1, D + 2, 4] = 1.0
+    z = orc.score(k, v, orc.cnn_from_arrays([ks], [1], [W2], [bias], w_out, b_out), [0, n])
+    past = np.concatenate([np.zeros(2), k[:-2, 0, 1]])
+    fut = np.concatenate([v[2:, 1, 2], np.zeros(2)])
+    np.testing.assert_allclose(z[0], 0.25 + 1.5 * sil(past), atol=1e-14)
+    np.testing.assert_allclose(z[1], -0.5 - 2.0 * sil(fut), atol=1e-14)
+    # dilation 3 on tap 0 reads j-6
+    z = orc.score(k, v, orc.cnn_from_arrays([ks], [3], [W2], [bias], w_out, b_out), [0, n])
+    np.testing.assert_allclose(z[0], 0.25 + 1.5 * sil(np.concatenate([np.zeros(6), k[:-6, 0, 1]])), atol=1e-14)
+    # bias path and sigmoid
+    bias2 = np.array([[0.3, 0.0], [0.0, -0.7]])
+    z = orc.score(k, v, orc.cnn_from_arrays([ks], [1], [W], [bias2], w_out, b_out), [0, n])
+    np.testing.assert_allclose(z[0], 0.25 + 1.5 * sil(0.3), atol=1e-14)
+    np.testing.assert_allclose(orc.retention_score(np.array([0.0, np.log(3.0)])), [0.5, 0.75], atol=1e-15)
+
+
+def test_p8_paper_stack_receptive_field():
+    with open(os.path.join(GOLDEN, "paper_hyperparameters.json")) as f:
+        hp = json.load(f)
+    ks, dil = hp["lte_cnn"]["kernel"], hp["lte_cnn"]["dilation"]
+    n, D = 40, 4
+    ch = [2 * D // 2, 2 * D // 4, 2 * D // 8]
+    w = small_prefill(seed=14, seqlens=(n,), Hq=1, Hkv=1, D=D, kernel=ks, channels=ch, dilation=dil, window=20)
+    cnn = oracle_cnn(w.cnn)
+    assert 2 * cnn.rho + 1 == hp["lte_cnn"]["receptive_field"]
+    z0 = orc.score(w.k, w.v, cnn, [0, n])[0]
+    # perturbing one token changes exactly the logits within rho of it (and no others)
+    k2 = w.k.copy(); k2[20, 0, 1] += 1.0
+    z1 = orc.score(k2, w.v, cnn, [0, n])[0]
+    changed = np.nonzero(np.abs(z1 - z0) > 0)[0]
+    assert changed.min() >= 20 - cnn.rho and changed.max() <= 20 + cnn.rho
+    assert set(changed) >= {20 - cnn.rho, 20, 20 + cnn.rho}
+
+
+# ---- P9: closed forms of the softmax ----------------------------------------------------------
+def test_p9_softmax_closed_forms():
+    n, window, D = 30, 6, 4
+    w = small_prefill(seed=15, seqlens=(n,), Hq=1, Hkv=1, D=D, window=window, budget=4)
+    cfg = oracle_cfg(w)
+    k = np.tile(np.array([[0.3, -0.2, 0.1, 0.5]]), (n, 1))[:, None, :]
+    kept = [np.array([1, 5, 20])]
+    out = orc.sparse_attention_sequence(w.q, k, w.v, cfg, kept)
+    v = w.v.astype(np.float64)
+    for i in (0, 3, 9, 29):
+        S = [j for j in kept[0] if j <= i - window] + list(range(max(0, i - window + 1), i + 1))
+        np.testing.assert_allclose(out[i, 0], v[S, 0].mean(axis=0), atol=1e-13)
+    # one dominant key: output is (almost exactly) that key's value
+    k2 = np.zeros((n, 1, D)); k2[5, 0, 0] = 1000.0
+    q2 = np.zeros((n, 1, D)); q2[:, 0, 0] = 1.0
+    out = orc.sparse_attention_sequence(q2, k2, w.v, cfg, kept)
+    np.testing.assert_allclose(out[25, 0], v[5, 0], atol=1e-12)          # 5 is kept and out of window
+    np.testing.assert_allclose(out[7, 0], v[5, 0], atol=1e-12)           # 5 is inside the window
+    out_nokeep = orc.sparse_attention_sequence(q2, k2, w.v, cfg, [np.array([1, 20])])
+    assert np.abs(out_nokeep[25, 0] - v[5, 0]).max() > 1e-3              # evicted -> invisible
+
+
+# ---- P10: physical order of the cache is irrelevant ------------------------------------------
+def test_p10_cache_order_irrelevant():
+    n = 50
+    w = small_prefill(seed=16, seqlens=(n + 1,), window=9, budget=6)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    _, sts, _, _ = orc.prefill(w.q[:n], w.k[:n], w.v[:n], cfg, cnn, [0, n])
+    _, sts2, _, _ = orc.prefill(w.q[:n], w.k[:n], w.v[:n], cfg, cnn, [0, n])
+    rng = np.random.default_rng(0)
+    for hs in sts2[0].heads:
+        perm = rng.permutation(len(hs.ret_pos))
+        hs.ret_pos = [hs.ret_pos[i] for i in perm]; hs.ret_key = [hs.ret_key[i] for i in perm]
+        hs.ret_k = [hs.ret_k[i] for i in perm]; hs.ret_v = [hs.ret_v[i] for i in perm]
+    o1 = orc.decode_step(sts[0], w.q[n], w.k[n], w.v[n], cfg, cnn)
+    o2 = orc.decode_step(sts2[0], w.q[n], w.k[n], w.v[n], cfg, cnn)
+    np.testing.assert_allclose(o1, o2, atol=1e-12)
+    assert [sorted(h.ret_pos) for h in sts[0].heads] == [sorted(h.ret_pos) for h in sts2[0].heads]
+
+
+# ---- P11: packed sequences == each sequence alone --------------------------------------------
+def test_p11_varlen_packing():
+    lens = (23, 1, 40, 7, 0, 31)
+    w = small_prefill(seed=17, seqlens=lens, window=8, budget=4, sink=1)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    cu = w.cu_seqlens
+    for s, n in enumerate(lens):
+        lo, hi = cu[s], cu[s + 1]
+        o, st, zz, kk = orc.prefill(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], cfg, cnn, [0, n])
+        np.testing.assert_allclose(out[lo:hi], o, atol=0)
+        np.testing.assert_allclose(z[:, lo:hi], zz, atol=0)
+        for h in range(cfg.Hkv):
+            assert list(kept[s][h]) == list(kk[0][h])
+        assert states[s].n_seen == n
+
+
+# ---- P12: uniform-stride keep pattern fed straight to the attention --------------------------
+def test_p12_uniform_stride_keep_mask():
+    n, window, stride = 70, 10, 7
+    w = small_prefill(seed=18, seqlens=(n,), window=window, budget=0)
+    cfg = oracle_cfg(w)
+    keep = [np.arange(0, n, stride), np.arange(3, n, stride)]
+    out = orc.sparse_attention_sequence(w.q, w.k, w.v, cfg, keep)
+    ref = dense_masked_attention(w.q, w.k, w.v, keep, window, cfg.sigma, 1)
+    np.testing.assert_allclose(out, ref, atol=1e-12)
+
+
+# ---- P13: grouped queries share their KV head's kept set -------------------------------------
+def test_p13_gqa_shares_kept_set():
+    n = 44
+    w = small_prefill(seed=19, seqlens=(n,), Hq=6, Hkv=2, window=9, budget=5)
+    cfg, cnn, (out, states, z, kept) = run_prefill(w)
+    assert z.shape == (2, n) and len(kept[0]) == 2
+    # a query head moved to another slot of the same group gives the same output row
+    q2 = w.q.copy(); q2[:, 1] = w.q[:, 0]
+    out2, *_ = orc.prefill(q2, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    np.testing.assert_allclose(out2[:, 1], out[:, 0], atol=0)
+    keepb = [brute_force_keep(orc.selection_key(z[h], 0), n, 9, 5, 0, 0.0) for h in range(2)]
+    np.testing.assert_allclose(out, dense_masked_attention(w.q, w.k, w.v, keepb, 9, cfg.sigma, 3), atol=1e-12)
+
+
+# ---- planted mistakes: the pins above must notice them ---------------------------------------
+def test_pins_catch_planted_mistakes(monkeypatch):
+    w = small_prefill(seed=20, seqlens=(40,), window=8, budget=4)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    good, _, z, kept = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    keep = [brute_force_keep(orc.selection_key(z[h], 0), 40, 8, 4, 0, 0.0) for h in range(2)]
+    ref = dense_masked_attention(w.q, w.k, w.v, keep, 8, cfg.sigma, 1)
+    # (a) off-by-one window in the oracle
+    cfg_bad = orc.OracleCfg(cfg.Hq, cfg.Hkv, cfg.D, cfg.window + 1, cfg.budget)
+    bad = orc.sparse_attention_sequence(w.q, w.k, w.v, cfg_bad, kept[0])
+    assert np.abs(bad - ref).max() > 1e-6
+    # (b) missing softmax scale
+    monkeypatch.setattr(orc, "attend", lambda qv, K, V, s: _unscaled(qv, K, V))
+    bad = orc.sparse_attention_sequence(w.q, w.k, w.v, cfg, kept[0])
+    assert np.abs(bad - ref).max() > 1e-6
+    monkeypatch.undo()
+    # (c) mirrored conv taps
+    flipped = orc.cnn_from_arrays(cnn.kernel, cnn.dilation, [x[..., ::-1] for x in cnn.w], cnn.bias, cnn.w_out, cnn.b_out)
+    assert np.abs(orc.score(w.k, w.v, flipped, w.cu_seqlens) - z).max() > 1e-6
+    assert np.abs(good - ref).max() < 1e-12
+
+
+def _unscaled(qv, K, V):
+    s = K @ qv
+    p = np.exp(s - s.max())
+    return (p / p.sum()) @ V
