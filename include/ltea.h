@@ -1,0 +1,182 @@
+/*
+ * ltea.h — C ABI of the SWA + learnable-token-eviction (LTE) token mixer for
+ * AMD MI355X (gfx950).
+ *
+ * The method (paper Sections 3.1.1 and 3.1.3): per KV head a small 1-D CNN over
+ * neighbouring past and future tokens scores every KV pair; when a token leaves
+ * the sliding window it is kept only if its score passes the threshold (or it
+ * is an attention sink), and at most `budget` such pairs per head survive (the
+ * highest-scoring ones); each query attends to its window plus its head's
+ * retained set.
+ *
+ * General rules of this boundary
+ *   - plain C: no C++ types, no exceptions, no global state; reentrant.
+ *   - every pointer that is not a pointer to one of the config structs below is
+ *     a DEVICE pointer, allocated, owned and freed by the caller.  The config
+ *     structs themselves (ltea_cfg, ltea_cnn, ltea_cache) live in HOST memory
+ *     and are read during the call only.
+ *   - the library never allocates device memory, never synchronises and never
+ *     touches the default stream: kernels are enqueued on `stream` (a
+ *     hipStream_t passed as void*, NULL = the null stream) and the call
+ *     returns at once.
+ *   - all arguments are validated on the host before anything is enqueued: a
+ *     negative return value means nothing was launched and no state changed.
+ *   - results are deterministic: same inputs, same bits.
+ *   - positions are 0-based inside each sequence.  `window` counts the current
+ *     token (query i sees i-window+1 .. i).  Token j is an eviction candidate
+ *     iff j < sink or logit_j > tau_logit (tau_logit = 0 is the paper's
+ *     "retention score > 0.5"); NaN logits never pass.  Candidates are ranked by
+ *     (key descending, position ascending) with key = +inf for sinks, else the
+ *     fp32 logit; the first `budget` are kept.
+ *   - activations (Q, K, V, O, caches, conv weights) are all of cfg->dtype;
+ *     logits, scores and biases are fp32; accumulation is fp32.
+ */
+#ifndef LTEA_H
+#define LTEA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LTEA_MAX_CNN_LAYERS 4
+
+typedef enum { LTEA_F32 = 0, LTEA_BF16 = 1 } ltea_dtype;
+
+typedef enum {
+  LTEA_OK = 0,
+  LTEA_EINVAL = -1,        /* null pointer, bad size, bad stride, inconsistent config      */
+  LTEA_EUNSUPPORTED = -2,  /* valid request outside what the kernels implement             */
+  LTEA_EWORKSPACE = -3,    /* workspace missing or smaller than ltea_*workspace_bytes says */
+  LTEA_EHIP = -4           /* a kernel launch was rejected by the HIP runtime              */
+} ltea_status;
+
+/* Scoring CNN of the LTE module (Section 3.1.1; Appendix A): per KV head, a
+ * stack of 1-D convolutions over concat(key, value) features (keys in channels
+ * 0..D-1, values in D..2D-1), each followed by Swish (beta = 1), then a
+ * per-head linear map to one logit.  Each conv is a cross-correlation with
+ * "same" zero padding: tap t of layer l reads position
+ * j + (t - (kernel[l]-1)/2) * dilation[l]; positions outside the sequence
+ * contribute zero at every layer. */
+typedef struct ltea_cnn {
+  int32_t n_layers;                       /* 1 .. LTEA_MAX_CNN_LAYERS                        */
+  int32_t kernel[LTEA_MAX_CNN_LAYERS];    /* odd, >= 1                                       */
+  int32_t dilation[LTEA_MAX_CNN_LAYERS];  /* >= 1                                            */
+  int32_t c_out[LTEA_MAX_CNN_LAYERS];     /* output channels; input of layer 0 is 2*D        */
+  const void *w[LTEA_MAX_CNN_LAYERS];     /* [Hkv][c_out][c_in][kernel], cfg->dtype, device  */
+  const float *bias[LTEA_MAX_CNN_LAYERS]; /* [Hkv][c_out] fp32, device                       */
+  const void *w_out;                      /* [Hkv][c_out of last layer], cfg->dtype, device  */
+  const float *b_out;                     /* [Hkv] fp32, device                              */
+} ltea_cnn;
+
+typedef struct ltea_cfg {
+  int32_t Hq, Hkv, D;      /* query heads, KV heads (Hq % Hkv == 0), head dim in {64, 128}  */
+  int32_t window;          /* >= 2*rho+1 where rho = sum_l dilation[l]*(kernel[l]-1)/2       */
+  int32_t budget;          /* >= 0, retained KV pairs per (sequence, KV head)                */
+  int32_t sink;            /* >= 0, first `sink` positions are always candidates             */
+  float tau_logit;         /* candidate iff logit > tau_logit; -INFINITY = pure top-budget   */
+  float softmax_scale;     /* <= 0 selects 1/sqrt(D)                                         */
+  int32_t dtype;           /* ltea_dtype                                                     */
+} ltea_cfg;
+
+/* Cache state of B sequences (Section 3.1.3, cache-layout figure): a circular
+ * sliding-window segment plus a compact out-of-window segment per
+ * (sequence, KV head).  All arrays are device memory owned by the caller and
+ * are updated in place.  The physical order inside the compact segment is not
+ * part of the contract (prefill leaves it ascending by position; decode
+ * appends or overwrites single slots). */
+typedef struct ltea_cache {
+  void *k_win, *v_win;   /* [B][Hkv][window][D]  ring; position p lives in slot p % window   */
+  float *win_score;      /* [B][Hkv][window]     logits of ring tokens; final for p < n_scored */
+  void *k_ret, *v_ret;   /* [B][Hkv][budget][D]  retained KV pairs                            */
+  float *ret_score;      /* [B][Hkv][budget]     their selection keys (+inf for sinks)        */
+  int32_t *ret_pos;      /* [B][Hkv][budget]     their positions                              */
+  int32_t *ret_count;    /* [B][Hkv]             valid entries, <= budget                     */
+  int32_t *n_seen;       /* [B]                  tokens consumed so far                       */
+  int32_t *n_scored;     /* [B]                  = max(0, n_seen - rho) after every call      */
+} ltea_cache;
+
+/* Human-readable text for a status code (static storage). */
+const char *ltea_strerror(int status);
+
+/* Bytes of device workspace ltea_score / ltea_retain / ltea_sparse_attention /
+ * ltea_prefill need for these sizes (0 is a valid answer).  Returns 0 on
+ * invalid arguments as well; the entry points report those themselves. */
+size_t ltea_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
+                            int32_t max_seqlen);
+
+/* Bytes of device workspace ltea_decode_step needs for n_seqs sequences. */
+size_t ltea_decode_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs);
+
+/* (a) Scoring (Section 3.1.1): logits[h][t] for every packed token t and KV
+ * head h.  k, v: [total_tokens][Hkv][D] views with element strides stride_tok
+ * and stride_head (innermost dimension contiguous).  cu_seqlens: device int32
+ * [n_seqs+1], non-decreasing, cu_seqlens[0] = 0, cu_seqlens[n_seqs] =
+ * total_tokens; max_seqlen >= every length.  The convolution never crosses a
+ * sequence boundary.  logits: [Hkv][total_tokens] fp32 (the last rho logits of
+ * each sequence are provisional: their right context is zero padding). */
+int ltea_score(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *k, const void *v, int64_t stride_tok,
+               int64_t stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+               int32_t max_seqlen, float *logits, void *workspace, size_t workspace_bytes, void *stream);
+
+/* (b) Retention and cache fill (eq. 5; Section 3.1.3 "Capped capacity" and
+ * "Cached prefilling"): from given logits [Hkv][total_tokens], select per
+ * (sequence, KV head) the kept out-of-window positions, gather their K, V, key
+ * and position ascending by position into the compact segment, copy the last
+ * min(n, window) tokens and their logits into the ring, and set ret_count,
+ * n_seen = n and n_scored = max(0, n - rho).  Unused compact slots are left
+ * untouched.  cache arrays are sized for B = n_seqs. */
+int ltea_retain(const ltea_cfg *cfg, const float *logits, const void *k, const void *v, int64_t stride_tok,
+                int64_t stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                int32_t max_seqlen, int32_t rho, const ltea_cache *cache, void *workspace, size_t workspace_bytes,
+                void *stream);
+
+/* (c) Prefill attention over window + retained set (Section 3.1.3): for query
+ * i of a sequence and query head hq (KV head hq / (Hq/Hkv)),
+ *   out_i = softmax_j(scale * q_i . k_j) v_j  over
+ *   { max(0, i-window+1) <= j <= i }  union  { retained j : j <= i - window }.
+ * Reads only ret_pos / ret_count / k_ret / v_ret of `cache`.  q: view
+ * [total_tokens][Hq][D] with element strides q_stride_tok / q_stride_head;
+ * out: contiguous [total_tokens][Hq][D]. */
+int ltea_sparse_attention(const ltea_cfg *cfg, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                          const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                          const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen,
+                          const ltea_cache *cache, void *out, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/* (a)+(b)+(c): scores every token, fills the cache state of all n_seqs
+ * sequences, and writes the attention output of every token.  Mid-sequence
+ * queries see the FINAL capped retained set of their sequence, restricted to
+ * positions that have left their window.  logits_or_null, if given, receives
+ * the [Hkv][total_tokens] logits. */
+int ltea_prefill(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
+                 int64_t q_stride_head, const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                 const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen, void *out,
+                 const ltea_cache *cache, float *logits_or_null, void *workspace, size_t workspace_bytes,
+                 void *stream);
+
+/* (d) One decode step for n_seqs sequences (Section 3.1.3, cache replacement
+ * and lazy scoring paragraphs): for sequence b with t = n_seen[b],
+ *   1. the logit of position t - rho becomes final (its receptive field
+ *      t-2rho .. t is the 2*rho newest ring rows plus the incoming token);
+ *   2. position e = t - window leaves the window: if it is a candidate it is
+ *      appended to the compact segment, or, when that is full, overwrites the
+ *      entry with the lowest key (among equal keys the latest position) iff
+ *      its own key is strictly higher;
+ *   3. k_t, v_t go to ring slot t % window; n_seen, n_scored advance;
+ *   4. out = attention of q_t over the ring's valid rows plus the compact rows.
+ * q: contiguous [n_seqs][Hq][D]; k, v: contiguous [n_seqs][Hkv][D]; out:
+ * contiguous [n_seqs][Hq][D].  Requires the invariant n_scored = max(0,
+ * n_seen - rho) on entry (true after ltea_retain / ltea_prefill / a previous
+ * step, and for an all-zero fresh cache).  Concurrent calls on the same cache
+ * race. */
+int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
+                     void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LTEA_H */

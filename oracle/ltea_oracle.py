@@ -171,23 +171,28 @@ def attend(qv: np.ndarray, K: np.ndarray, V: np.ndarray, sigma: float) -> np.nda
 # --------------------------------------------------------------------------
 # O3: prefill outputs for given retained sets (Section 3.1.3)
 # --------------------------------------------------------------------------
+def attention_row(q_seq, k_seq, v_seq, cfg: OracleCfg, retained_h: np.ndarray, i: int, hq: int) -> np.ndarray:
+    """Output of query i, query head hq: attention over its window i-w+1..i plus the kept positions
+    j <= i-w of its KV head (kept entries still inside the window are not counted twice)."""
+    h = hq // cfg.G
+    R = np.asarray(retained_h, dtype=np.int64)
+    lo = max(0, i - cfg.window + 1)
+    far = R[R <= i - cfg.window]
+    idx = np.concatenate([far, np.arange(lo, i + 1)])
+    return attend(np.asarray(q_seq[i, hq], dtype=np.float64), np.asarray(k_seq[idx, h], dtype=np.float64),
+                  np.asarray(v_seq[idx, h], dtype=np.float64), cfg.sigma)
+
+
 def sparse_attention_sequence(q_seq, k_seq, v_seq, cfg: OracleCfg, retained: List[np.ndarray]) -> np.ndarray:
-    """q_seq [n,Hq,D], k_seq/v_seq [n,Hkv,D], retained[h] = ascending kept positions of KV head h.
-    Query i attends to its window i-w+1..i plus the kept positions j <= i-w
-    (kept entries still inside the window are not counted twice)."""
+    """q_seq [n,Hq,D], k_seq/v_seq [n,Hkv,D], retained[h] = ascending kept positions of KV head h."""
     q_seq = np.asarray(q_seq, dtype=np.float64)
     k_seq = np.asarray(k_seq, dtype=np.float64)
     v_seq = np.asarray(v_seq, dtype=np.float64)
     n = q_seq.shape[0]
     out = np.zeros((n, cfg.Hq, cfg.D), dtype=np.float64)
     for hq in range(cfg.Hq):
-        h = hq // cfg.G
-        R = np.asarray(retained[h], dtype=np.int64)
         for i in range(n):
-            lo = max(0, i - cfg.window + 1)
-            far = R[R <= i - cfg.window]
-            idx = np.concatenate([far, np.arange(lo, i + 1)])
-            out[i, hq] = attend(q_seq[i, hq], k_seq[idx, h], v_seq[idx, h], cfg.sigma)
+            out[i, hq] = attention_row(q_seq, k_seq, v_seq, cfg, retained[hq // cfg.G], i, hq)
     return out
 
 

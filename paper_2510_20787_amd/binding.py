@@ -1,0 +1,272 @@
+"""Thin ctypes binding over libltea.so (C ABI in include/ltea.h).
+
+Argument marshalling only: tensors are PyTorch device tensors (PyTorch is used for device memory and
+streams, nothing else); every computation happens inside the library's HIP kernels.  There is no CPU
+or PyTorch fallback: if the shared library is missing, or a call returns an error status, an exception
+is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libltea.so")
+
+LTEA_F32, LTEA_BF16 = 0, 1
+LTEA_OK, LTEA_EINVAL, LTEA_EUNSUPPORTED, LTEA_EWORKSPACE, LTEA_EHIP = 0, -1, -2, -3, -4
+MAX_LAYERS = 4
+
+
+class LteaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+class ltea_cnn(C.Structure):
+    _fields_ = [("n_layers", C.c_int32),
+                ("kernel", C.c_int32 * MAX_LAYERS), ("dilation", C.c_int32 * MAX_LAYERS),
+                ("c_out", C.c_int32 * MAX_LAYERS),
+                ("w", C.c_void_p * MAX_LAYERS), ("bias", C.c_void_p * MAX_LAYERS),
+                ("w_out", C.c_void_p), ("b_out", C.c_void_p)]
+
+
+class ltea_cfg(C.Structure):
+    _fields_ = [("Hq", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32),
+                ("window", C.c_int32), ("budget", C.c_int32), ("sink", C.c_int32),
+                ("tau_logit", C.c_float), ("softmax_scale", C.c_float), ("dtype", C.c_int32)]
+
+
+class ltea_cache(C.Structure):
+    _fields_ = [("k_win", C.c_void_p), ("v_win", C.c_void_p), ("win_score", C.c_void_p),
+                ("k_ret", C.c_void_p), ("v_ret", C.c_void_p), ("ret_score", C.c_void_p),
+                ("ret_pos", C.c_void_p), ("ret_count", C.c_void_p), ("n_seen", C.c_void_p),
+                ("n_scored", C.c_void_p)]
+
+
+EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
+           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step"]
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libltea.so once; fail loudly if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2510_20787_amd.build` "
+                           "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    i32, i64, vp, sz = C.c_int32, C.c_int64, C.c_void_p, C.c_size_t
+    P = C.POINTER
+    L.ltea_strerror.restype = C.c_char_p
+    L.ltea_strerror.argtypes = [C.c_int]
+    L.ltea_workspace_bytes.restype = sz
+    L.ltea_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
+    L.ltea_decode_workspace_bytes.restype = sz
+    L.ltea_decode_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32]
+    L.ltea_score.restype = C.c_int
+    L.ltea_score.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, i64, i64, vp, i32, i64, i32, vp, vp, sz, vp]
+    L.ltea_retain.restype = C.c_int
+    L.ltea_retain.argtypes = [P(ltea_cfg), vp, vp, vp, i64, i64, vp, i32, i64, i32, i32, P(ltea_cache), vp, sz, vp]
+    L.ltea_sparse_attention.restype = C.c_int
+    L.ltea_sparse_attention.argtypes = [P(ltea_cfg), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32,
+                                        P(ltea_cache), vp, vp, sz, vp]
+    L.ltea_prefill.restype = C.c_int
+    L.ltea_prefill.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp,
+                               P(ltea_cache), vp, vp, sz, vp]
+    L.ltea_decode_step.restype = C.c_int
+    L.ltea_decode_step.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def strerror(status: int) -> str:
+    return lib().ltea_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != LTEA_OK:
+        raise LteaError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def torch_dtype(dtype: str) -> torch.dtype:
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def make_cfg(Hq: int, Hkv: int, D: int, window: int, budget: int, sink: int = 0, tau: float = 0.0,
+             softmax_scale: float = 0.0, dtype: str = "bf16") -> ltea_cfg:
+    return ltea_cfg(Hq, Hkv, D, window, budget, sink, float(tau), float(softmax_scale),
+                    LTEA_F32 if dtype == "f32" else LTEA_BF16)
+
+
+@dataclass
+class Cnn:
+    """Device copies of the scoring CNN plus the C struct pointing at them."""
+    struct: ltea_cnn
+    tensors: List[torch.Tensor]
+    rho: int
+
+
+def upload_cnn(kernel: Sequence[int], dilation: Sequence[int], w: Sequence, bias: Sequence, w_out, b_out,
+               dtype: str, device="cuda") -> Cnn:
+    """w[l]: [Hkv, C_out, C_in, kernel]; bias[l]: [Hkv, C_out]; w_out: [Hkv, C]; b_out: [Hkv] (host arrays)."""
+    td = torch_dtype(dtype)
+    s = ltea_cnn()
+    s.n_layers = len(kernel)
+    keep: List[torch.Tensor] = []
+    for l in range(len(kernel)):
+        s.kernel[l], s.dilation[l], s.c_out[l] = int(kernel[l]), int(dilation[l]), int(w[l].shape[1])
+        wt = torch.as_tensor(w[l]).to(device=device, dtype=td).contiguous()
+        bt = torch.as_tensor(bias[l]).to(device=device, dtype=torch.float32).contiguous()
+        keep += [wt, bt]
+        s.w[l], s.bias[l] = wt.data_ptr(), bt.data_ptr()
+    wo = torch.as_tensor(w_out).to(device=device, dtype=td).contiguous()
+    bo = torch.as_tensor(b_out).to(device=device, dtype=torch.float32).contiguous()
+    keep += [wo, bo]
+    s.w_out, s.b_out = wo.data_ptr(), bo.data_ptr()
+    rho = sum(int(d) * (int(k) - 1) // 2 for k, d in zip(kernel, dilation))
+    return Cnn(s, keep, rho)
+
+
+@dataclass
+class Cache:
+    """Device arrays of the cache state for B sequences plus the C struct pointing at them."""
+    struct: ltea_cache
+    k_win: torch.Tensor
+    v_win: torch.Tensor
+    win_score: torch.Tensor
+    k_ret: torch.Tensor
+    v_ret: torch.Tensor
+    ret_score: torch.Tensor
+    ret_pos: torch.Tensor
+    ret_count: torch.Tensor
+    n_seen: torch.Tensor
+    n_scored: torch.Tensor
+
+
+def alloc_cache(cfg: ltea_cfg, B: int, device="cuda") -> Cache:
+    """A zeroed cache (n_seen = 0: also the valid start state for decoding from scratch)."""
+    td = torch.float32 if cfg.dtype == LTEA_F32 else torch.bfloat16
+    z = lambda shape, dt: torch.zeros(shape, dtype=dt, device=device)
+    bmin = max(cfg.budget, 1)
+    t = dict(k_win=z((B, cfg.Hkv, cfg.window, cfg.D), td), v_win=z((B, cfg.Hkv, cfg.window, cfg.D), td),
+             win_score=z((B, cfg.Hkv, cfg.window), torch.float32),
+             k_ret=z((B, cfg.Hkv, bmin, cfg.D), td), v_ret=z((B, cfg.Hkv, bmin, cfg.D), td),
+             ret_score=z((B, cfg.Hkv, bmin), torch.float32), ret_pos=z((B, cfg.Hkv, bmin), torch.int32),
+             ret_count=z((B, cfg.Hkv), torch.int32), n_seen=z((B,), torch.int32), n_scored=z((B,), torch.int32))
+    return wrap_cache(**t)
+
+
+def wrap_cache(k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored) -> Cache:
+    s = ltea_cache(k_win.data_ptr(), v_win.data_ptr(), win_score.data_ptr(), k_ret.data_ptr(), v_ret.data_ptr(),
+                   ret_score.data_ptr(), ret_pos.data_ptr(), ret_count.data_ptr(), n_seen.data_ptr(),
+                   n_scored.data_ptr())
+    return Cache(s, k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored)
+
+
+def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
+
+
+def _tok_head_strides(x: torch.Tensor):
+    assert x.dim() == 3 and x.stride(2) == 1, "expected a [T, H, D] view with contiguous last dimension"
+    return x.stride(0), x.stride(1)
+
+
+def ltea_workspace_bytes(cfg: ltea_cfg, cnn: Optional[Cnn], n_seqs: int, total_tokens: int, max_seqlen: int) -> int:
+    return int(lib().ltea_workspace_bytes(C.byref(cfg), C.byref(cnn.struct) if cnn else None, n_seqs, total_tokens,
+                                          max_seqlen))
+
+
+def ltea_decode_workspace_bytes(cfg: ltea_cfg, cnn: Optional[Cnn], n_seqs: int) -> int:
+    return int(lib().ltea_decode_workspace_bytes(C.byref(cfg), C.byref(cnn.struct) if cnn else None, n_seqs))
+
+
+def ltea_score(cfg: ltea_cfg, cnn: Cnn, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+               max_seqlen: int, logits: Optional[torch.Tensor] = None,
+               workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T = k.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    if logits is None:
+        logits = torch.empty((cfg.Hkv, T), dtype=torch.float32, device=k.device)
+    if workspace is None:
+        workspace = _workspace(ltea_workspace_bytes(cfg, cnn, n_seqs, T, max_seqlen), k.device)
+    _check(lib().ltea_score(C.byref(cfg), C.byref(cnn.struct), _ptr(k), _ptr(v), st, sh, _ptr(cu_seqlens), n_seqs, T,
+                            max_seqlen, _ptr(logits), _ptr(workspace), workspace.numel(), _stream()), "ltea_score")
+    return logits
+
+
+def ltea_retain(cfg: ltea_cfg, logits: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+                max_seqlen: int, rho: int, cache: Cache) -> Cache:
+    T = k.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    _check(lib().ltea_retain(C.byref(cfg), _ptr(logits), _ptr(k), _ptr(v), st, sh, _ptr(cu_seqlens), n_seqs, T,
+                             max_seqlen, rho, C.byref(cache.struct), None, 0, _stream()), "ltea_retain")
+    return cache
+
+
+def ltea_sparse_attention(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+                          max_seqlen: int, cache: Cache, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T = q.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    if out is None:
+        out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    _check(lib().ltea_sparse_attention(C.byref(cfg), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh, _ptr(cu_seqlens),
+                                       n_seqs, T, max_seqlen, C.byref(cache.struct), _ptr(out), None, 0, _stream()),
+           "ltea_sparse_attention")
+    return out
+
+
+def ltea_prefill(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                 cu_seqlens: torch.Tensor, max_seqlen: int, cache: Cache, out: Optional[torch.Tensor] = None,
+                 logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    T = q.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    if out is None:
+        out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = _workspace(ltea_workspace_bytes(cfg, cnn, n_seqs, T, max_seqlen), q.device)
+    _check(lib().ltea_prefill(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
+                              _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), C.byref(cache.struct), _ptr(logits),
+                              _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill")
+    return out
+
+
+def ltea_decode_step(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cache: Cache,
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    B = q.shape[0]
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    if out is None:
+        out = torch.empty((B, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = _workspace(ltea_decode_workspace_bytes(cfg, cnn, B), q.device)
+    _check(lib().ltea_decode_step(C.byref(cfg), C.byref(cnn.struct), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                  C.byref(cache.struct), B, _ptr(workspace), workspace.numel(), _stream()),
+           "ltea_decode_step")
+    return out

@@ -1,0 +1,240 @@
+// C ABI of libltea (declared in include/ltea.h): host-side argument validation, workspace carving and
+// dispatch to the kernel launchers.  Nothing here allocates, synchronises or keeps state.
+#include <math.h>
+#include <string.h>
+
+#include "ltea_kernels.h"
+
+using namespace ltea;
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int elem_size(int dtype) { return dtype == LTEA_F32 ? 4 : 2; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_cfg(const ltea_cfg* cfg) {
+  if (!cfg) return LTEA_EINVAL;
+  if (cfg->dtype != LTEA_F32 && cfg->dtype != LTEA_BF16) return LTEA_EINVAL;
+  if (cfg->Hq < 1 || cfg->Hkv < 1 || cfg->Hq % cfg->Hkv != 0) return LTEA_EINVAL;
+  if (cfg->window < 1 || cfg->budget < 0 || cfg->sink < 0) return LTEA_EINVAL;
+  if (isnan(cfg->tau_logit) || isnan(cfg->softmax_scale)) return LTEA_EINVAL;
+  if (cfg->D != 64 && cfg->D != 128) return LTEA_EUNSUPPORTED;
+  return LTEA_OK;
+}
+
+int check_cnn(const ltea_cfg* cfg, const ltea_cnn* cnn) {
+  if (!cnn) return LTEA_EINVAL;
+  if (cnn->n_layers < 1 || cnn->n_layers > LTEA_MAX_CNN_LAYERS) return LTEA_EINVAL;
+  for (int l = 0; l < cnn->n_layers; ++l) {
+    if (cnn->kernel[l] < 1 || cnn->kernel[l] % 2 == 0) return LTEA_EINVAL;
+    if (cnn->dilation[l] < 1 || cnn->c_out[l] < 1) return LTEA_EINVAL;
+    if (!cnn->w[l] || !cnn->bias[l]) return LTEA_EINVAL;
+  }
+  if (!cnn->w_out || !cnn->b_out) return LTEA_EINVAL;
+  if (cfg->window < 2 * cnn_rho(cnn) + 1) return LTEA_EINVAL;  // look-ahead must stay inside the window
+  return LTEA_OK;
+}
+
+int check_seqs(const int32_t* cu, int32_t n_seqs, int64_t total, int32_t max_seqlen) {
+  if (n_seqs < 0 || total < 0 || max_seqlen < 0) return LTEA_EINVAL;
+  if (!cu) return LTEA_EINVAL;
+  if (total > 0 && (n_seqs == 0 || max_seqlen == 0)) return LTEA_EINVAL;
+  if (total > (int64_t)n_seqs * max_seqlen) return LTEA_EINVAL;
+  if (total >= (int64_t)1 << 31) return LTEA_EUNSUPPORTED;  // cu_seqlens is int32
+  return LTEA_OK;
+}
+
+// rows are moved in 16-byte pieces: base pointers and strides must keep every row 16-byte aligned
+int check_view(const void* p, int64_t st, int64_t sh, int D, int esz) {
+  if (!p) return LTEA_EINVAL;
+  if (st < D || sh < D) return LTEA_EINVAL;
+  const int64_t per16 = 16 / esz;
+  if (st % per16 != 0 || sh % per16 != 0 || !aligned16(p)) return LTEA_EINVAL;
+  return LTEA_OK;
+}
+
+int check_cache(const ltea_cfg* cfg, const ltea_cache* c, bool need_window) {
+  if (!c) return LTEA_EINVAL;
+  if (!c->ret_count || !c->n_seen || !c->n_scored) return LTEA_EINVAL;
+  if (cfg->budget > 0 && (!c->k_ret || !c->v_ret || !c->ret_score || !c->ret_pos)) return LTEA_EINVAL;
+  if (need_window && (!c->k_win || !c->v_win || !c->win_score)) return LTEA_EINVAL;
+  if (!aligned16(c->k_ret) || !aligned16(c->v_ret) || !aligned16(c->k_win) || !aligned16(c->v_win)) return LTEA_EINVAL;
+  return LTEA_OK;
+}
+
+bool use_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn) { return score_mfma_supported(cfg, cnn); }
+
+size_t score_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total) {
+  return use_score_mfma(cfg, cnn) ? 0 : align_up(score_generic_workspace(cfg, cnn, total), 256);
+}
+
+int hip_status(hipError_t e) { return e == hipSuccess ? LTEA_OK : LTEA_EHIP; }
+
+int do_score(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
+             const SeqView& sv, float* logits, void* ws, hipStream_t stream) {
+  if (use_score_mfma(cfg, cnn)) return hip_status(launch_score_mfma(cfg, cnn, k, v, st, sh, sv, logits, stream));
+  return hip_status(launch_score_generic(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
+}
+
+int do_attention(const ltea_cfg& cfg, const void* q, int64_t qst, int64_t qsh, const void* k, const void* v,
+                 int64_t st, int64_t sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream) {
+  if (attention_mfma_supported(cfg))
+    return hip_status(launch_attention_mfma(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
+  return hip_status(launch_attention_generic(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ltea_strerror(int status) {
+  switch (status) {
+    case LTEA_OK: return "ok";
+    case LTEA_EINVAL: return "invalid argument (null pointer, size, stride, alignment or inconsistent config)";
+    case LTEA_EUNSUPPORTED: return "configuration not supported by the gfx950 kernels";
+    case LTEA_EWORKSPACE: return "workspace missing or too small";
+    case LTEA_EHIP: return "HIP runtime rejected a kernel launch";
+    default: return "unknown ltea status";
+  }
+}
+
+size_t ltea_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs, int64_t total_tokens,
+                            int32_t max_seqlen) {
+  (void)n_seqs; (void)max_seqlen;
+  if (check_cfg(cfg) != LTEA_OK || total_tokens < 0) return 0;
+  size_t bytes = 0;
+  if (cnn) {
+    if (check_cnn(cfg, cnn) != LTEA_OK) return 0;
+    bytes += align_up((size_t)cfg->Hkv * (size_t)total_tokens * sizeof(float), 256);  // logits when not returned
+    bytes += score_workspace(*cfg, *cnn, total_tokens);
+  }
+  return bytes;
+}
+
+size_t ltea_decode_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
+  if (check_cfg(cfg) != LTEA_OK || n_seqs < 0) return 0;
+  if (cnn && check_cnn(cfg, cnn) != LTEA_OK) return 0;
+  return align_up(decode_workspace(*cfg, n_seqs), 256);
+}
+
+int ltea_score(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k, const void* v, int64_t stride_tok,
+               int64_t stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+               int32_t max_seqlen, float* logits, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st != LTEA_OK) return st;
+  if (total_tokens == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if ((st = check_view(k, stride_tok, stride_head, cfg->D, esz)) != LTEA_OK) return st;
+  if ((st = check_view(v, stride_tok, stride_head, cfg->D, esz)) != LTEA_OK) return st;
+  if (!logits) return LTEA_EINVAL;
+  const size_t need = score_workspace(*cfg, *cnn, total_tokens);
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LTEA_EWORKSPACE;
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  return do_score(*cfg, *cnn, k, v, stride_tok, stride_head, sv, logits, workspace, static_cast<hipStream_t>(stream));
+}
+
+int ltea_retain(const ltea_cfg* cfg, const float* logits, const void* k, const void* v, int64_t stride_tok,
+                int64_t stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                int32_t max_seqlen, int32_t rho, const ltea_cache* cache, void* workspace, size_t workspace_bytes,
+                void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (rho < 0 || cfg->window < 2 * rho + 1) return LTEA_EINVAL;
+  if (n_seqs == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if (total_tokens > 0) {
+    if ((st = check_view(k, stride_tok, stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(v, stride_tok, stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (!logits) return LTEA_EINVAL;
+  }
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  return hip_status(launch_retain(*cfg, logits, k, v, stride_tok, stride_head, sv, rho, *cache,
+                                  static_cast<hipStream_t>(stream)));
+}
+
+int ltea_sparse_attention(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
+                          const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                          const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen,
+                          const ltea_cache* cache, void* out, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, false);
+  if (st != LTEA_OK) return st;
+  if (total_tokens == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+  if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+  if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+  if (!out || !aligned16(out)) return LTEA_EINVAL;
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  return do_attention(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, *cache, out,
+                      static_cast<hipStream_t>(stream));
+}
+
+int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
+                 const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                 const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen, void* out,
+                 const ltea_cache* cache, float* logits_or_null, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (n_seqs == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if (total_tokens > 0) {
+    if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (!out || !aligned16(out)) return LTEA_EINVAL;
+  }
+  const size_t logits_bytes = align_up((size_t)cfg->Hkv * (size_t)total_tokens * sizeof(float), 256);
+  const size_t score_ws = score_workspace(*cfg, *cnn, total_tokens);
+  const size_t need = (logits_or_null ? 0 : logits_bytes) + score_ws;
+  if (need > 0 && (!workspace || workspace_bytes < need)) return LTEA_EWORKSPACE;
+  char* ws = static_cast<char*>(workspace);
+  float* logits = logits_or_null;
+  if (!logits) { logits = reinterpret_cast<float*>(ws); ws += logits_bytes; }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  if (total_tokens > 0) {
+    st = do_score(*cfg, *cnn, k, v, kv_stride_tok, kv_stride_head, sv, logits, ws, s);
+    if (st != LTEA_OK) return st;
+  }
+  st = hip_status(launch_retain(*cfg, logits, k, v, kv_stride_tok, kv_stride_head, sv, cnn_rho(cnn), *cache, s));
+  if (st != LTEA_OK) return st;
+  if (total_tokens == 0) return LTEA_OK;
+  return do_attention(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, *cache, out, s);
+}
+
+int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, const void* k, const void* v, void* out,
+                     const ltea_cache* cache, int32_t n_seqs, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (n_seqs < 0) return LTEA_EINVAL;
+  if (n_seqs == 0) return LTEA_OK;
+  if (!q || !k || !v || !out) return LTEA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return LTEA_EINVAL;
+  int row_floats = 2 * cfg->D;
+  for (int l = 0; l < cnn->n_layers; ++l) row_floats = cnn->c_out[l] > row_floats ? cnn->c_out[l] : row_floats;
+  const size_t lds = (size_t)2 * (2 * cnn_rho(cnn) + 1) * row_floats * sizeof(float);
+  if (lds > 60 * 1024) return LTEA_EUNSUPPORTED;  // activation pyramid of the per-step scoring must fit LDS
+  const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
+  if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace,
+                                       static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

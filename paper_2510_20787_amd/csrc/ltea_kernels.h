@@ -1,0 +1,57 @@
+// Host-side launcher declarations: one per kernel family. All pointers are device pointers unless
+// stated otherwise; every launcher enqueues on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ltea.h"
+
+namespace ltea {
+
+struct SeqView {              // packed-token description shared by all prefill launchers
+  const int32_t* cu_seqlens;  // device [n_seqs+1]
+  int32_t n_seqs;
+  int64_t total_tokens;
+  int32_t max_seqlen;
+};
+
+inline int cnn_rho(const ltea_cnn* c) {
+  int r = 0;
+  for (int l = 0; l < c->n_layers; ++l) r += c->dilation[l] * (c->kernel[l] - 1) / 2;
+  return r;
+}
+
+// ---- (a) scoring -------------------------------------------------------------------------------
+// Generic layered path (any depth, fp32 or bf16 storage, VALU): needs 2 * Hkv * T * max(c_out) floats
+// of scratch when n_layers > 1, Hkv * T * c_out[0] floats when n_layers == 1.
+size_t score_generic_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total_tokens);
+hipError_t launch_score_generic(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                                int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
+                                void* workspace, hipStream_t stream);
+// Single-layer bf16 path on MFMA (fused conv + Swish + output projection, no scratch).
+bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                             int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
+                             hipStream_t stream);
+
+// ---- (b) retention + cache fill -------------------------------------------------------------------
+hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k, const void* v,
+                         int64_t stride_tok, int64_t stride_head, const SeqView& sv, int rho,
+                         const ltea_cache& cache, hipStream_t stream);
+
+// ---- (c) prefill attention -------------------------------------------------------------------------
+hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
+                                    const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                                    const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
+bool attention_mfma_supported(const ltea_cfg& cfg);
+hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
+                                 const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                                 const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
+
+// ---- (d) decode step -------------------------------------------------------------------------------
+int decode_num_splits(const ltea_cfg& cfg, int n_seqs);
+size_t decode_workspace(const ltea_cfg& cfg, int n_seqs);
+hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v,
+                              void* out, const ltea_cache& cache, int n_seqs, void* workspace, hipStream_t stream);
+
+}  // namespace ltea

@@ -1,0 +1,132 @@
+"""CPU-only checks of the boundary: the library loads, exports exactly what include/ltea.h declares, and
+rejects bad arguments on the host before anything could be launched (no compute call is made here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_20787_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "ltea.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ltea_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_functions()
+    assert names == sorted(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_strerror():
+    assert B.strerror(0) == "ok"
+    for s in (-1, -2, -3, -4, -99):
+        assert len(B.strerror(s)) > 3
+
+
+def good_cfg(**kw):
+    d = dict(Hq=4, Hkv=2, D=64, window=16, budget=8, sink=0, tau=0.0, softmax_scale=0.0, dtype="bf16")
+    d.update(kw)
+    return B.make_cfg(**d)
+
+
+def fake_cnn(kernel=(5,), dilation=(1,), c_out=(16,), n_layers=None):
+    s = B.ltea_cnn()
+    s.n_layers = len(kernel) if n_layers is None else n_layers
+    for l in range(len(kernel)):
+        s.kernel[l], s.dilation[l], s.c_out[l] = kernel[l], dilation[l], c_out[l]
+        s.w[l] = 0x1000
+        s.bias[l] = 0x1000
+    s.w_out = 0x1000
+    s.b_out = 0x1000
+    return s
+
+
+def score_status(cfg, cnn, k=0x1000, v=0x1000, st=128, sh=64, cu=0x1000, n_seqs=1, total=32, max_len=32, logits=0x1000,
+                 ws=0x1000, ws_bytes=1 << 30):
+    return B.lib().ltea_score(C.byref(cfg) if cfg else None, C.byref(cnn) if cnn else None, k, v, st, sh, cu, n_seqs,
+                              total, max_len, logits, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("case,expect", [
+    ("null_cfg", B.LTEA_EINVAL), ("null_cnn", B.LTEA_EINVAL), ("bad_D", B.LTEA_EUNSUPPORTED),
+    ("gqa_mismatch", B.LTEA_EINVAL), ("window0", B.LTEA_EINVAL), ("neg_budget", B.LTEA_EINVAL),
+    ("even_kernel", B.LTEA_EINVAL), ("layers0", B.LTEA_EINVAL), ("layers5", B.LTEA_EINVAL),
+    ("window_lt_field", B.LTEA_EINVAL), ("null_k", B.LTEA_EINVAL), ("null_cu", B.LTEA_EINVAL),
+    ("small_stride", B.LTEA_EINVAL), ("odd_stride", B.LTEA_EINVAL), ("misaligned", B.LTEA_EINVAL),
+    ("null_logits", B.LTEA_EINVAL), ("no_workspace", B.LTEA_EWORKSPACE), ("neg_total", B.LTEA_EINVAL),
+    ("total_gt_cap", B.LTEA_EINVAL), ("bad_dtype", B.LTEA_EINVAL), ("null_weight", B.LTEA_EINVAL),
+])
+def test_score_argument_errors(case, expect):
+    cfg, cnn, kw = good_cfg(), fake_cnn(), {}
+    if case == "null_cfg": cfg = None
+    elif case == "null_cnn": cnn = None
+    elif case == "bad_D": cfg = good_cfg(D=96)
+    elif case == "gqa_mismatch": cfg = good_cfg(Hq=5)
+    elif case == "window0": cfg = good_cfg(window=0)
+    elif case == "neg_budget": cfg = good_cfg(budget=-1)
+    elif case == "even_kernel": cnn = fake_cnn(kernel=(4,))
+    elif case == "layers0": cnn = fake_cnn(n_layers=0)
+    elif case == "layers5": cnn = fake_cnn(n_layers=5)
+    elif case == "window_lt_field": cfg = good_cfg(window=4)          # needs >= 2*2+1
+    elif case == "null_k": kw = dict(k=None)
+    elif case == "null_cu": kw = dict(cu=None)
+    elif case == "small_stride": kw = dict(sh=32)
+    elif case == "odd_stride": kw = dict(st=132)                      # not a multiple of 8 bf16 elements
+    elif case == "misaligned": kw = dict(v=0x1004)
+    elif case == "null_logits": kw = dict(logits=None)
+    elif case == "no_workspace": cfg = good_cfg(dtype="f32"); kw = dict(ws=None, ws_bytes=0)   # fp32 uses the layered path
+    elif case == "neg_total": kw = dict(total=-1)
+    elif case == "total_gt_cap": kw = dict(total=64, max_len=32)
+    elif case == "bad_dtype": cfg = good_cfg(); cfg.dtype = 7
+    elif case == "null_weight": cnn = fake_cnn(); cnn.w[0] = None
+    assert score_status(cfg, cnn, **kw) == expect
+
+
+def test_empty_inputs_are_ok_without_touching_the_device():
+    cfg, cnn = good_cfg(), fake_cnn()
+    assert score_status(cfg, cnn, total=0, n_seqs=0, max_len=0) == B.LTEA_OK
+    cache = B.ltea_cache()
+    for f, _ in B.ltea_cache._fields_:
+        setattr(cache, f, 0x1000)
+    L = B.lib()
+    assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), 0, None, 0, None) == 0
+    assert L.ltea_prefill(C.byref(cfg), C.byref(cnn), None, 0, 0, None, None, 0, 0, 0x1000, 0, 0, 0, None,
+                          C.byref(cache), None, None, 0, None) == 0
+
+
+def test_decode_and_prefill_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    cache = B.ltea_cache()
+    for f, _ in B.ltea_cache._fields_:
+        setattr(cache, f, 0x1000)
+    # workspace too small
+    assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, 16, None) == B.LTEA_EWORKSPACE
+    # null cache member
+    bad = B.ltea_cache()
+    assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(bad), 2, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
+    assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), None, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
+    assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), -1, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
+    # per-step scoring pyramid too large for LDS
+    big = fake_cnn(kernel=(63,), c_out=(16,))
+    cfgw = good_cfg(window=256, D=128)
+    assert L.ltea_decode_step(C.byref(cfgw), C.byref(big), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, 1 << 30, None) == B.LTEA_EUNSUPPORTED
+    # prefill: null out
+    assert L.ltea_prefill(C.byref(cfg), C.byref(cnn), 0x1000, 256, 64, 0x1000, 0x1000, 128, 64, 0x1000, 1, 32, 32, None,
+                          C.byref(cache), None, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
+    # retain: rho inconsistent with window
+    assert L.ltea_retain(C.byref(cfg), 0x1000, 0x1000, 0x1000, 128, 64, 0x1000, 1, 32, 32, 9, C.byref(cache), None, 0, None) == B.LTEA_EINVAL
+    # workspace sizes: monotone in tokens, zero on bad config
+    a = L.ltea_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 1000, 1000)
+    b = L.ltea_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 2000, 2000)
+    assert 0 < a < b
+    assert L.ltea_workspace_bytes(C.byref(good_cfg(D=96)), C.byref(cnn), 1, 1000, 1000) == 0
+    assert L.ltea_decode_workspace_bytes(C.byref(cfg), C.byref(cnn), 4) > 0

@@ -1,0 +1,282 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded inputs.
+
+Bars: retained-index sets, positions, counters and copied K/V rows bit-exact (sets identical wherever the
+oracle's own decision margin exceeds twice the measured logit difference); logits within LOGIT_TOL;
+outputs within OUT_TOL (max-abs, absolute and relative to the largest reference magnitude).
+Sizes here are ones the oracle finishes in seconds, spanning several tiles and ragged tails; the
+full-size configurations are in test_gpu_full_size.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import (LOGIT_TOL, DeviceWorkload, check_output, check_sets, dev, gpu_retained_sets, to_np)
+from tests.helpers import oracle_cfg, oracle_cnn
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # name: (dtype, seqlens, Hq, Hkv, D, window, budget, sink, tau, kernel, channels, dilation, qkv_scale, w_std)
+    "tiny_f32": None,  # the named configuration
+    "f32_ragged_gqa": ("f32", [333, 1, 200, 64, 0, 77], 4, 2, 64, 48, 20, 2, 0.0, (5,), (16,), None, 1.0, 0.1),
+    "f32_d128_deep": ("f32", [257, 130], 2, 2, 128, 40, 16, 4, 0.0, (3, 3, 3), (32, 16, 8), (2, 2, 2), 1.0, 0.08),
+    "bf16_d64": ("bf16", [700, 129, 300], 4, 4, 64, 96, 40, 0, 0.0, (5,), (32,), None, 0.125, 0.05),
+    "bf16_d128_gqa": ("bf16", [513, 64, 391], 8, 2, 128, 128, 48, 4, 0.0, (7,), (32,), None, 1.0, 0.05),
+    "bf16_topb": ("bf16", [600], 2, 2, 64, 64, 33, 0, -np.inf, (5,), (32,), None, 1.0, 0.05),
+    "bf16_budget0": ("bf16", [300, 90], 2, 2, 64, 64, 0, 3, 0.0, (5,), (16,), None, 1.0, 0.05),
+    "bf16_window_ge_n": ("bf16", [100, 128], 2, 2, 128, 128, 16, 0, 0.0, (5,), (32,), None, 1.0, 0.05),
+}
+
+
+def make(name):
+    if name == "tiny_f32":
+        return wl.config_tiny_f32()
+    dt, lens, Hq, Hkv, D, w, b, s, tau, ker, ch, dil, sc, ws = CASES[name]
+    return wl.make_prefill(name, sum(map(ord, name)), dt, lens, Hq, Hkv, D, w, b, s,
+                           tau, cnn_kernel=ker, cnn_channels=ch, cnn_dilation=dil, qkv_scale=sc, w_std=ws)
+
+
+_oracle_cache = {}
+
+
+def oracle_prefill(name):
+    if name not in _oracle_cache:
+        w = make(name)
+        cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+        _oracle_cache[name] = (w, cfg, cnn, orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens))
+    return _oracle_cache[name]
+
+
+def logit_eps(zg, z64, dtype):
+    diff = np.abs(zg.astype(np.float64) - z64)
+    bound = LOGIT_TOL[dtype] * np.maximum(1.0, np.abs(z64))
+    assert np.all(diff <= bound), f"logit error {diff.max()} exceeds tolerance"
+    return float(diff.max())
+
+
+# ------------------------------------------------------------------------------------------------
+# (a) scoring
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+def test_score(name):
+    w, cfg, cnn, (out, states, z64, kept) = oracle_prefill(name)
+    d = DeviceWorkload(w)
+    zg = to_np(B.ltea_score(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen))
+    assert zg.shape == z64.shape
+    logit_eps(zg, z64, w.dtype)
+
+
+def test_score_strided_views():
+    """K and V as strided views of one packed [T, 3, H, D] buffer."""
+    w, cfg, cnn, (out, states, z64, kept) = oracle_prefill("bf16_d64")
+    d = DeviceWorkload(w)
+    T = w.total_tokens
+    packed = torch.zeros((T, 3, w.Hkv, w.D), dtype=d.k.dtype, device="cuda")
+    packed[:, 1] = d.k
+    packed[:, 2] = d.v
+    zg = to_np(B.ltea_score(d.cfg, d.cnn, packed[:, 1], packed[:, 2], d.cu, d.max_seqlen))
+    logit_eps(zg, z64, w.dtype)
+
+
+# ------------------------------------------------------------------------------------------------
+# (b) retention on given logits: bit-exact
+# ------------------------------------------------------------------------------------------------
+def run_retain_case(w, z32):
+    """z32: [Hkv, T] float32 logits fed to both sides."""
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    rho = w.cnn.rho
+    B.ltea_retain(d.cfg, torch.from_numpy(z32).cuda(), d.k, d.v, d.cu, d.max_seqlen, rho, cache)
+    torch.cuda.synchronize()
+    kq, vq = to_np(d.k), to_np(d.v)
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        n = hi - lo
+        assert int(cache.n_seen[s]) == n and int(cache.n_scored[s]) == max(0, n - rho)
+        for h in range(w.Hkv):
+            ref = orc.retain(z32[h, lo:hi].astype(np.float64), n, w.window, w.budget, w.sink, w.tau)
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            assert cnt == len(ref)
+            np.testing.assert_array_equal(pos, ref)                      # ascending by position after prefill
+            key = orc.selection_key(z32[h, lo:hi], w.sink)
+            np.testing.assert_array_equal(cache.ret_score[s, h, :cnt].cpu().numpy(), key[ref] + np.float32(0))
+            np.testing.assert_array_equal(to_np(cache.k_ret[s, h, :cnt]), kq[lo + ref, h])
+            np.testing.assert_array_equal(to_np(cache.v_ret[s, h, :cnt]), vq[lo + ref, h])
+            # ring: position p at slot p % window, with its logit
+            ps = np.arange(max(0, n - w.window), n)
+            slots = ps % w.window
+            np.testing.assert_array_equal(to_np(cache.k_win[s, h])[slots], kq[lo + ps, h])
+            np.testing.assert_array_equal(to_np(cache.v_win[s, h])[slots], vq[lo + ps, h])
+            np.testing.assert_array_equal(cache.win_score[s, h].cpu().numpy()[slots], z32[h, lo + ps])
+
+
+@pytest.mark.parametrize("name", ["tiny_f32", "f32_ragged_gqa", "bf16_d128_gqa", "bf16_topb", "bf16_budget0", "bf16_window_ge_n"])
+def test_retain_on_oracle_logits(name):
+    w, cfg, cnn, (out, states, z64, kept) = oracle_prefill(name)
+    run_retain_case(w, z64.astype(np.float32))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_retain_ties_and_specials(seed):
+    """Heavily tied logits (few distinct values), +-0, +-inf and NaN: the tie order (key desc, position asc)
+    and the 'NaN never passes' rule must match exactly. Long enough for several scan chunks."""
+    w = wl.make_prefill("ties", 100 + seed, "bf16", [9000, 5000, 37], 2, 2, 64, 32, 300 + 17 * seed, 2 * seed, 0.0,
+                        cnn_kernel=(5,), cnn_channels=(16,))
+    rng = np.random.default_rng(seed)
+    z = rng.integers(-3, 4, size=(2, w.total_tokens)).astype(np.float32) * np.float32(0.25)
+    idx = rng.integers(0, w.total_tokens, size=60)
+    z[0, idx[:15]] = np.nan
+    z[1, idx[15:30]] = np.inf
+    z[0, idx[30:45]] = -np.inf
+    z[1, idx[45:60]] = -0.0
+    run_retain_case(w, z)
+
+
+def test_retain_large_budget_and_radix_paths():
+    """Cap binding with a budget larger than one scan chunk, distinct random keys (radix select exercised on
+    all four digit passes), plus a tau below every logit."""
+    w = wl.make_prefill("radix", 7, "f32", [20000], 1, 1, 64, 100, 5000, 0, -1e30, cnn_kernel=(3,), cnn_channels=(4,))
+    rng = np.random.default_rng(5)
+    z = (rng.standard_normal((1, 20000)) * 10 ** rng.uniform(-6, 3, size=(1, 20000))).astype(np.float32)
+    run_retain_case(w, z)
+
+
+# ------------------------------------------------------------------------------------------------
+# (c) attention over window + an explicit keep set (uniform stride; no CNN involved)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,D,G", [("f32", 64, 1), ("bf16", 64, 2), ("bf16", 128, 1)])
+def test_sparse_attention_uniform_keep(dtype, D, G):
+    lens = [300, 75, 190]
+    w = wl.make_prefill("unif", 31, dtype, lens, 2 * G, 2, D, 64, 24, qkv_scale=1.0)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    ocfg = oracle_cfg(w)
+    keep = {}
+    pos = np.zeros((w.n_seqs, w.Hkv, w.budget), np.int32)
+    cnt = np.zeros((w.n_seqs, w.Hkv), np.int32)
+    kq, vq = to_np(d.k), to_np(d.v)
+    kr = np.zeros((w.n_seqs, w.Hkv, w.budget, D), np.float32)
+    vr = np.zeros_like(kr)
+    for s, n in enumerate(lens):
+        lo = int(w.cu_seqlens[s])
+        for h in range(w.Hkv):
+            stride = 7 + 3 * h
+            p = np.arange(h, n, stride)[: w.budget]          # may reach into the last window: must be masked
+            keep[(s, h)] = p
+            cnt[s, h] = len(p)
+            pos[s, h, :len(p)] = p
+            kr[s, h, :len(p)] = kq[lo + p, h]
+            vr[s, h, :len(p)] = vq[lo + p, h]
+    cache.ret_pos.copy_(torch.from_numpy(pos))
+    cache.ret_count.copy_(torch.from_numpy(cnt))
+    cache.k_ret.copy_(dev(kr, dtype))
+    cache.v_ret.copy_(dev(vr, dtype))
+    out = to_np(B.ltea_sparse_attention(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, cache))
+    for s, n in enumerate(lens):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        ref = orc.sparse_attention_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], ocfg, [keep[(s, h)] for h in range(w.Hkv)])
+        check_output(out[lo:hi], ref, dtype, f"seq {s}")
+
+
+# ------------------------------------------------------------------------------------------------
+# (a)+(b)+(c) prefill end to end
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", list(CASES))
+def test_prefill(name):
+    w, cfg, cnn, (out64, states, z64, kept) = oracle_prefill(name)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    out = to_np(B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits))
+    eps = logit_eps(to_np(logits), z64, w.dtype)
+    near = check_sets(cache, z64, w, eps)
+    skip = {(s, h) for s, h in near}
+    G = w.Hq // w.Hkv
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        assert int(cache.n_seen[s]) == hi - lo
+        for hq in range(w.Hq):
+            if (s, hq // G) in skip or hi == lo:
+                continue
+            check_output(out[lo:hi, hq], out64[lo:hi, hq], w.dtype, f"{name} seq {s} head {hq}")
+    assert len(near) <= 1, f"too many heads inside the decision margin: {near}"
+    # same call without returning logits (workspace-held) gives the same bits
+    cache2 = d.new_cache()
+    out2 = to_np(B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache2))
+    np.testing.assert_array_equal(out, out2)
+    np.testing.assert_array_equal(cache.ret_pos.cpu().numpy(), cache2.ret_pos.cpu().numpy())
+
+
+def test_prefill_deterministic():
+    w, *_ = oracle_prefill("bf16_d64")
+    d = DeviceWorkload(w)
+    outs = []
+    for _ in range(3):
+        cache = d.new_cache()
+        o = B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache)
+        outs.append((o.clone(), cache.ret_pos.clone(), cache.ret_score.clone(), cache.k_win.clone()))
+    for o in outs[1:]:
+        for a, b in zip(outs[0], o):
+            assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------------
+# (d) decode steps
+# ------------------------------------------------------------------------------------------------
+def compare_state(cache, states, w, step):
+    for s, st in enumerate(states):
+        assert int(cache.n_seen[s]) == st.n_seen, step
+        assert int(cache.n_scored[s]) == st.n_scored, step
+        for h in range(w.Hkv):
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            ref = orc.retained_positions(st)[h]
+            np.testing.assert_array_equal(np.sort(pos), ref, err_msg=f"step {step} seq {s} head {h}")
+
+
+@pytest.mark.parametrize("name,n_steps", [("tiny_f32", 40), ("f32_ragged_gqa", 70), ("f32_d128_deep", 50),
+                                          ("bf16_d64", 110), ("bf16_d128_gqa", 140), ("bf16_topb", 80), ("bf16_budget0", 70)])
+def test_decode_after_prefill(name, n_steps):
+    """Prefill on the GPU, then n_steps single-token steps for every sequence (enough to wrap short rings and
+    to fill and overflow the compact segment); outputs and retained sets against the oracle at every step."""
+    w, cfg, cnn, _ = oracle_prefill(name)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits)
+    _, states, z64, _ = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    eps = logit_eps(to_np(logits), z64, w.dtype)
+    near = check_sets(cache, z64, w, eps)
+    assert not near, "pick another seed: a head sits inside the decision margin"
+    ws = None
+    for step in range(n_steps):
+        q, k, v = wl.decode_inputs(w.seed, step, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+        out = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q, w.dtype), dev(k, w.dtype), dev(v, w.dtype), cache))
+        ref = np.stack([orc.decode_step(states[s], q[s], k[s], v[s], cfg, cnn) for s in range(w.n_seqs)])
+        check_output(out, ref, w.dtype, f"{name} step {step}")
+        compare_state(cache, states, w, step)
+    # final logits held in the ring agree with the oracle's
+    for s, st in enumerate(states):
+        for h in range(w.Hkv):
+            for p, zp in st.heads[h].win_z.items():
+                zg = float(cache.win_score[s, h, p % w.window])
+                assert abs(zg - zp) <= LOGIT_TOL[w.dtype] * max(1.0, abs(zp))
+
+
+@pytest.mark.parametrize("dtype,D", [("f32", 64), ("bf16", 128)])
+def test_decode_from_empty_cache(dtype, D):
+    """Start from a zeroed cache and feed tokens one by one: ring fill-up, first evictions, cap binding."""
+    n, B_ = 150, 3
+    w = wl.make_prefill("from_empty", 77, dtype, [n] * B_, 2, 2, D, 32, 12, 1, 0.0, cnn_kernel=(5,), cnn_channels=(16,),
+                        w_std=0.1)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    states = [orc.empty_state(cfg) for _ in range(B_)]
+    q3 = w.q.reshape(B_, n, w.Hq, D); k3 = w.k.reshape(B_, n, w.Hkv, D); v3 = w.v.reshape(B_, n, w.Hkv, D)
+    for t in range(n):
+        out = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q3[:, t], dtype), dev(k3[:, t], dtype), dev(v3[:, t], dtype), cache))
+        ref = np.stack([orc.decode_step(states[s], q3[s, t], k3[s, t], v3[s, t], cfg, cnn) for s in range(B_)])
+        check_output(out, ref, dtype, f"step {t}")
+        compare_state(cache, states, w, t)
