@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the SWA+LTE hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-decode]
+
+One "step" = one pass of the whole hot path over the prefill_bf16 workload (B=4 sequences x 4096 tokens,
+H=16, D=64, window 512, budget 256, CNN width 5 / 32 channels): ltea_prefill (scoring CNN -> capped
+retention + cache fill -> window + retained attention) followed by one ltea_decode_step that continues
+every sequence by one token on the cache just produced.  Inputs are synthetic, seeded, and resident in HBM
+before the timed region; four rotating copies of the inputs keep the 256 MB Infinity Cache from standing
+in for HBM.  `value` = tokens (prefill + decoded) per second over exactly K timed steps.
+
+Also reported on the same JSON line:
+  roofline      the dominant kernel of the step (the prefill attention kernel) against the bf16 MFMA peak:
+                algorithmic FLOPs (4*D per unmasked query-key pair, counted from the actual retained sets)
+                / its average duration measured with HIP events on the launch stream in an instrumented
+                repeat of the same steps (entry points called one by one).
+  decode        the decode_bf16 workload (B=64, H=16, D=128, window 1024 + 512 retained, n_seen 8192):
+                256 consecutive steps timed as a whole; us/step, us/token, and the streaming attention
+                kernel's achieved HBM bandwidth.
+  cpu_baseline  the fp64 NumPy oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def up(x, dtype):
+    import torch
+    from paper_2510_20787_amd import binding as B
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda", B.torch_dtype(dtype))
+
+
+def attention_pairs(w, ret_pos, ret_count):
+    """Unmasked (query, key) pairs per the index set: window pairs + for every retained j the n-w-j queries
+    that see it, summed over sequences and query heads."""
+    G = w.Hq // w.Hkv
+    pairs = 0
+    for s in range(w.n_seqs):
+        n = int(w.cu_seqlens[s + 1] - w.cu_seqlens[s])
+        i = np.arange(n)
+        win = int(np.minimum(i + 1, w.window).sum())
+        for h in range(w.Hkv):
+            c = int(ret_count[s, h])
+            p = ret_pos[s, h, :c].astype(np.int64)
+            pairs += G * (win + int(np.maximum(n - w.window - p, 0).sum()))
+    return pairs
+
+
+def bench_prefill(args):
+    import torch
+    from paper_2510_20787_amd import binding as B
+    from paper_2510_20787_amd import workloads as wl
+
+    w = wl.config_prefill_bf16()
+    cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
+    c = w.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
+    cu = torch.from_numpy(w.cu_seqlens).cuda()
+    T, nB = w.total_tokens, w.n_seqs
+    n_copies = 4
+    sets = []
+    for _ in range(n_copies):
+        sets.append(dict(q=up(w.q, w.dtype), k=up(w.k, w.dtype), v=up(w.v, w.dtype),
+                         out=torch.empty((T, w.Hq, w.D), dtype=torch.bfloat16, device="cuda"),
+                         cache=B.alloc_cache(cfg, nB)))
+    dq, dk, dv = wl.decode_inputs(w.seed, 0, w.dtype, nB, w.Hq, w.Hkv, w.D, scale=w.D ** -0.5)
+    dq, dk, dv = up(dq, w.dtype), up(dk, w.dtype), up(dv, w.dtype)
+    dout = torch.empty((nB, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(B.ltea_workspace_bytes(cfg, cnn, nB, T, w.max_seqlen), 16), dtype=torch.uint8, device="cuda")
+    dws = torch.empty(max(B.ltea_decode_workspace_bytes(cfg, cnn, nB), 16), dtype=torch.uint8, device="cuda")
+    logits = torch.empty((w.Hkv, T), dtype=torch.float32, device="cuda")
+
+    def step(i):
+        s = sets[i % n_copies]
+        B.ltea_prefill(cfg, cnn, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"], workspace=ws)
+        B.ltea_decode_step(cfg, cnn, dq, dk, dv, s["cache"], out=dout, workspace=dws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_step = T + nB
+    value = tokens_per_step / (ms_per_step * 1e-3)
+
+    # instrumented repeat: same work, entry points one by one, HIP events on the launch stream
+    names = ["score", "retain", "attention", "decode_step"]
+    acc = {n: 0.0 for n in names}
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        s = sets[i % n_copies]
+        e = evs[i]
+        e[0].record()
+        B.ltea_score(cfg, cnn, s["k"], s["v"], cu, w.max_seqlen, logits=logits, workspace=ws)
+        e[1].record()
+        B.ltea_retain(cfg, logits, s["k"], s["v"], cu, w.max_seqlen, cnn.rho, s["cache"])
+        e[2].record()
+        B.ltea_sparse_attention(cfg, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"])
+        e[3].record()
+        B.ltea_decode_step(cfg, cnn, dq, dk, dv, s["cache"], out=dout, workspace=dws)
+        e[4].record()
+    torch.cuda.synchronize()
+    for e in evs:
+        for j, n in enumerate(names):
+            acc[n] += e[j].elapsed_time(e[j + 1])
+    kern_ms = {n: acc[n] / args.steps for n in names}
+
+    # algorithmic work of the attention kernel from the actual retained sets (after a clean prefill)
+    s = sets[0]
+    B.ltea_prefill(cfg, cnn, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"], workspace=ws)
+    torch.cuda.synchronize()
+    pairs = attention_pairs(w, s["cache"].ret_pos.cpu().numpy(), s["cache"].ret_count.cpu().numpy())
+    flops = 4.0 * w.D * pairs
+    achieved = flops / (kern_ms["attention"] * 1e-3) / 1e12
+    score_bytes = 2 * T * w.Hkv * w.D * 2 + 4 * T * w.Hkv
+    res = dict(value=value, ms_per_step=ms_per_step, tokens_per_step=tokens_per_step, kern_ms=kern_ms,
+               roofline=dict(bound="mfma", kernel="prefill attention (window + retained)", achieved=achieved,
+                             peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                             algorithmic_flops=flops, avg_ms=kern_ms["attention"]),
+               scoring=dict(bound="hbm", achieved=score_bytes / (kern_ms["score"] * 1e-3) / 1e9, peak=PEAK_HBM_GBS,
+                            unit="GB/s", frac=score_bytes / (kern_ms["score"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            avg_ms=kern_ms["score"], algorithmic_bytes=score_bytes),
+               workload=w)
+    return res
+
+
+def bench_decode(args):
+    import torch
+    from paper_2510_20787_amd import binding as B
+    from paper_2510_20787_amd import workloads as wl
+
+    t0 = time.time()
+    st = wl.config_decode_bf16()
+    log(f"[bench] decode state generated in {time.time() - t0:.1f}s")
+    cfg = B.make_cfg(st.Hq, st.Hkv, st.D, st.window, st.budget, st.sink, st.tau, 0.0, st.dtype)
+    c = st.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, st.dtype)
+    dt = st.dtype
+    cache = B.wrap_cache(up(st.k_win, dt), up(st.v_win, dt),
+                         torch.zeros((st.B, st.Hkv, st.window), dtype=torch.float32, device="cuda"),
+                         up(st.k_ret, dt), up(st.v_ret, dt), torch.from_numpy(st.ret_score).cuda(),
+                         torch.from_numpy(st.ret_pos).cuda(), torch.from_numpy(st.ret_count).cuda(),
+                         torch.from_numpy(st.n_seen).cuda(),
+                         torch.from_numpy(np.maximum(st.n_seen - c.rho, 0).astype(np.int32)).cuda())
+    # ring logits = scoring kernel on the ring contents (n_seen is a multiple of the window: slot order = position order)
+    cu = torch.tensor([0, st.window], dtype=torch.int32, device="cuda")
+    for b in range(st.B):
+        kb = cache.k_win[b].permute(1, 0, 2)   # [window, Hkv, D] view
+        vb = cache.v_win[b].permute(1, 0, 2)
+        cache.win_score[b].copy_(B.ltea_score(cfg, cnn, kb, vb, cu, st.window))
+    n_steps = 256
+    steps_in = []
+    for i in range(n_steps):
+        q, k, v = wl.decode_inputs(st.seed, i, dt, st.B, st.Hq, st.Hkv, st.D)
+        steps_in.append((up(q, dt), up(k, dt), up(v, dt)))
+    out = torch.empty((st.B, st.Hq, st.D), dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(max(B.ltea_decode_workspace_bytes(cfg, cnn, st.B), 16), dtype=torch.uint8, device="cuda")
+    for i in range(8):   # warm-up steps also advance the state; the ring just keeps rotating
+        q, k, v = steps_in[i]
+        B.ltea_decode_step(cfg, cnn, q, k, v, cache, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(n_steps):
+        q, k, v = steps_in[i]
+        B.ltea_decode_step(cfg, cnn, q, k, v, cache, out=out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) * 1e6 / n_steps
+    us_per_step = e0.elapsed_time(e1) * 1e3 / n_steps
+    cnt = cache.ret_count.cpu().numpy().astype(np.int64)
+    bytes_per_step = int(((st.window + cnt) * 2 * st.D * 2).sum())
+    gbs = bytes_per_step / (us_per_step * 1e-6) / 1e9
+    return dict(workload="decode_bf16: B=64 H=16 D=128 window=1024 retained=512 n_seen=8192, 256 steps, cnn k5 c32",
+                us_per_step=us_per_step, us_per_token=us_per_step / st.B, wall_us_per_step=wall_us,
+                algorithmic_bytes_per_step=bytes_per_step,
+                roofline=dict(bound="hbm", kernel="decode step (all launches)", achieved=gbs, peak=PEAK_HBM_GBS,
+                              unit="GB/s", frac=gbs / PEAK_HBM_GBS, traffic=None))
+
+
+def cpu_baseline(w):
+    """The oracle as it stands on a bounded sample: sequence 0 of the prefill workload, all heads."""
+    import psutil
+    from oracle import ltea_oracle as orc
+    lo, hi = int(w.cu_seqlens[0]), int(w.cu_seqlens[1])
+    cfg = orc.OracleCfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau)
+    c = w.cnn
+    cnn = orc.cnn_from_arrays(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out)
+    proc = psutil.Process()
+    c0, t0 = proc.cpu_times(), time.perf_counter()
+    orc.prefill(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], cfg, cnn, [0, hi - lo])
+    dt = time.perf_counter() - t0
+    c1 = proc.cpu_times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    return dict(value=(hi - lo) / dt, unit="tokens/s", cores=max(1, int(round(cpu / dt))), kind="oracle",
+                sample=f"sequence 0 of 4 ({hi - lo} tokens, all {w.Hq} heads): scoring + retention + attention, "
+                       f"{dt:.1f}s wall; host has {os.cpu_count()} logical cores")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (every (sequence, head) is independent; "
+                 "see DESIGN.md for how the path would shard). Run with --gpus 1.")
+    import torch
+    from paper_2510_20787_amd import binding as B
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()
+    torch.cuda.set_device(0)
+    log(f"[bench] device: {torch.cuda.get_device_name(0)}")
+    pre = bench_prefill(args)
+    log(f"[bench] prefill step {pre['ms_per_step']:.3f} ms; kernels (ms): {pre['kern_ms']}")
+    w = pre.pop("workload")
+    line = {
+        "metric": "SWA+LTE prefill tokens/s (scoring + retention + attention + one decode step per sequence)",
+        "value": pre["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": pre["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "prefill_bf16: B=4 x n=4096, H=16, D=64, window=512, budget=256, CNN k=5 C=32, "
+                               "Q,K,V~N(0,1)/sqrt(D), weights~N(0,0.05); + 1 decode step per sequence",
+                   "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": 4},
+        "roofline": pre["roofline"],
+        "kernel_ms": pre["kern_ms"],
+        "scoring_roofline": pre["scoring"],
+    }
+    if not args.no_decode:
+        dec = bench_decode(args)
+        log(f"[bench] decode {dec['us_per_step']:.1f} us/step")
+        line["decode"] = dec
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
