@@ -38,6 +38,16 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
+WORKLOAD_TEXT = {
+    "prefill": "prefill_bf16: B=4 x n=4096, H=16, D=64, window=512, budget=256, CNN k=5 C=32, "
+               "Q,K,V~N(0,1)/sqrt(D), weights~N(0,0.05); + 1 decode step per sequence",
+    "long": "long_prefill_bf16: B=1 x n=32768, H=32, D=128, window=2048, budget=1024, CNN k=7 C=32, Q,K,V~N(0,1); "
+            "+ 1 decode step",
+    "varlen": "varlen_prefill_bf16: 16 sequences of 1024..16384 tokens packed, H=16, D=128, window=1024, budget=512, "
+              "CNN k=5 C=32, 1% planted near-duplicate keys; + 1 decode step per sequence",
+}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -69,19 +79,20 @@ def bench_prefill(args):
     from paper_2510_20787_amd import binding as B
     from paper_2510_20787_amd import workloads as wl
 
-    w = wl.config_prefill_bf16()
+    w = {"prefill": wl.config_prefill_bf16, "long": wl.config_long_prefill_bf16,
+         "varlen": wl.config_varlen_prefill_bf16}[args.workload]()
     cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
     c = w.cnn
     cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
     cu = torch.from_numpy(w.cu_seqlens).cuda()
     T, nB = w.total_tokens, w.n_seqs
-    n_copies = 4
+    n_copies = 4 if args.workload == "prefill" else 1   # the larger workloads exceed the Infinity Cache on their own
     sets = []
     for _ in range(n_copies):
         sets.append(dict(q=up(w.q, w.dtype), k=up(w.k, w.dtype), v=up(w.v, w.dtype),
                          out=torch.empty((T, w.Hq, w.D), dtype=torch.bfloat16, device="cuda"),
                          cache=B.alloc_cache(cfg, nB)))
-    dq, dk, dv = wl.decode_inputs(w.seed, 0, w.dtype, nB, w.Hq, w.Hkv, w.D, scale=w.D ** -0.5)
+    dq, dk, dv = wl.decode_inputs(w.seed, 0, w.dtype, nB, w.Hq, w.Hkv, w.D)
     dq, dk, dv = up(dq, w.dtype), up(dk, w.dtype), up(dv, w.dtype)
     dout = torch.empty((nB, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
     ws = torch.empty(max(B.ltea_workspace_bytes(cfg, cnn, nB, T, w.max_seqlen), 16), dtype=torch.uint8, device="cuda")
@@ -227,7 +238,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--workload", choices=["prefill", "long", "varlen"], default="prefill",
+                    help="prefill = the benchmark configuration (default); long / varlen = the other prefill "
+                         "configurations, for kernel measurements (no CPU baseline, no decode section)")
     args = ap.parse_args()
+    if args.workload != "prefill":
+        args.no_decode = args.no_cpu_baseline = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every (sequence, head) is independent; "
                  "see DESIGN.md for how the path would shard). Run with --gpus 1.")
@@ -245,9 +261,8 @@ def main():
         "value": pre["value"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": pre["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "prefill_bf16: B=4 x n=4096, H=16, D=64, window=512, budget=256, CNN k=5 C=32, "
-                               "Q,K,V~N(0,1)/sqrt(D), weights~N(0,0.05); + 1 decode step per sequence",
-                   "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": 4},
+        "config": {"workload": WORKLOAD_TEXT[args.workload],
+                   "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": 4 if args.workload == "prefill" else 1},
         "roofline": pre["roofline"],
         "kernel_ms": pre["kern_ms"],
         "scoring_roofline": pre["scoring"],

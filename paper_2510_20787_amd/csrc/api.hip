@@ -81,7 +81,7 @@ int do_score(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void
 
 int do_attention(const ltea_cfg& cfg, const void* q, int64_t qst, int64_t qsh, const void* k, const void* v,
                  int64_t st, int64_t sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream) {
-  if (attention_mfma_supported(cfg))
+  if (attention_mfma_supported(cfg, st, sv.max_seqlen))
     return hip_status(launch_attention_mfma(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
   return hip_status(launch_attention_generic(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
 }

@@ -43,7 +43,7 @@ hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k
 hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                     const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
                                     const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
-bool attention_mfma_supported(const ltea_cfg& cfg);
+bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_t max_seqlen);
 hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                  const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
                                  const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
