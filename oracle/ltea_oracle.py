@@ -295,6 +295,25 @@ def _score_from_window(hs: HeadState, h: int, j: int, cnn: OracleCnn) -> float:
     return float(zz[j - max(lo, 0)])
 
 
+def evict_into_retained(hs: HeadState, e: int, z_e: float, ek, ev, cfg: OracleCfg) -> None:
+    """Position e has just left the window with final logit z_e (Section 3.1.3, cache replacement): if it is a
+    candidate, append it to the retained segment, or, when that is full, let it displace the lowest-key entry
+    (among equal lowest keys the latest position) iff its own key is strictly higher. Decisions in fp32."""
+    ze = np.float32(z_e)
+    ekey = np.float32(np.inf) if e < cfg.sink else ze
+    if cfg.budget <= 0 or not (e < cfg.sink or ze > np.float32(cfg.tau)):
+        return
+    if len(hs.ret_pos) < cfg.budget:
+        hs.ret_pos.append(e); hs.ret_key.append(ekey); hs.ret_k.append(ek); hs.ret_v.append(ev)
+        return
+    m = 0
+    for i in range(1, len(hs.ret_pos)):
+        if (hs.ret_key[i] < hs.ret_key[m]) or (hs.ret_key[i] == hs.ret_key[m] and hs.ret_pos[i] > hs.ret_pos[m]):
+            m = i
+    if ekey > hs.ret_key[m]:
+        hs.ret_pos[m] = e; hs.ret_key[m] = ekey; hs.ret_k[m] = ek; hs.ret_v[m] = ev
+
+
 def decode_step(st: SeqState, q_t, k_t, v_t, cfg: OracleCfg, cnn: OracleCnn) -> np.ndarray:
     """Consume token t = st.n_seen of one sequence. q_t [Hq,D], k_t/v_t [Hkv,D]. Returns o_t [Hq,D].
 
@@ -310,7 +329,6 @@ def decode_step(st: SeqState, q_t, k_t, v_t, cfg: OracleCfg, cnn: OracleCnn) -> 
     t = st.n_seen
     rho = cnn.rho
     out = np.zeros((cfg.Hq, cfg.D), dtype=np.float64)
-    tau32 = np.float32(cfg.tau)
     for h in range(cfg.Hkv):
         hs = st.heads[h]
         hs.win_pos.append(t)
@@ -321,18 +339,7 @@ def decode_step(st: SeqState, q_t, k_t, v_t, cfg: OracleCfg, cnn: OracleCnn) -> 
         if len(hs.win_pos) > cfg.window:
             e = hs.win_pos.pop(0)
             ek, ev = hs.win_k.pop(0), hs.win_v.pop(0)
-            ze = np.float32(hs.win_z.pop(e))
-            ekey = np.float32(np.inf) if e < cfg.sink else ze
-            if cfg.budget > 0 and (e < cfg.sink or ze > tau32):
-                if len(hs.ret_pos) < cfg.budget:
-                    hs.ret_pos.append(e); hs.ret_key.append(ekey); hs.ret_k.append(ek); hs.ret_v.append(ev)
-                else:
-                    m = 0
-                    for i in range(1, len(hs.ret_pos)):
-                        if (hs.ret_key[i] < hs.ret_key[m]) or (hs.ret_key[i] == hs.ret_key[m] and hs.ret_pos[i] > hs.ret_pos[m]):
-                            m = i
-                    if ekey > hs.ret_key[m]:
-                        hs.ret_pos[m] = e; hs.ret_key[m] = ekey; hs.ret_k[m] = ek; hs.ret_v[m] = ev
+            evict_into_retained(hs, e, hs.win_z.pop(e), ek, ev, cfg)
         K = np.stack(hs.ret_k + hs.win_k)
         V = np.stack(hs.ret_v + hs.win_v)
         for g in range(cfg.G):

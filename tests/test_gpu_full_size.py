@@ -1,0 +1,205 @@
+"""GPU parity at the full sizes of the named configurations, in the launch configuration bench.py times.
+
+The oracle scores every token of every head (library matmuls make that seconds), so logits and retained
+sets are checked on ALL heads; attention outputs are checked on sampled query rows the oracle computes one
+by one (first/last rows, window edges, tile edges, random rows); cache contents on sampled slots.
+For the decode configuration the eviction rule is replayed by the oracle for ALL 1024 (sequence, head)
+pairs (it needs only logits), while outputs are compared on sampled sequences."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import (LOGIT_TOL, OUT_TOL, DeviceWorkload, check_sets, dev, gpu_retained_sets, to_np)
+from tests.helpers import oracle_cfg, oracle_cnn
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(n, window, rng, k=6):
+    fixed = [0, 1, window - 2, window - 1, window, window + 1, 63, 64, 127, 128, 129, n // 2, n - 129, n - 2, n - 1]
+    rows = {r for r in fixed if 0 <= r < n}
+    rows |= {int(x) for x in rng.integers(0, n, size=k)}
+    return sorted(rows)
+
+
+def run_full_prefill(w, logit_tol=None):
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    out = B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits)
+    torch.cuda.synchronize()
+    print(f"[{w.name}] gpu prefill done; scoring oracle on {w.total_tokens} tokens x {w.Hkv} heads", flush=True)
+    z64 = orc.score(w.k, w.v, ocnn, w.cu_seqlens)
+    zg = to_np(logits)
+    diff = np.abs(zg.astype(np.float64) - z64)
+    tol = LOGIT_TOL[w.dtype] if logit_tol is None else logit_tol
+    assert np.all(diff <= tol * np.maximum(1.0, np.abs(z64))), f"logit error {diff.max()}"
+    eps = float(diff.max())
+    print(f"[{w.name}] logits ok (max diff {eps:.3e}); checking retained sets on all heads", flush=True)
+    near = check_sets(cache, z64, w, eps)
+    assert len(near) <= max(1, (w.n_seqs * w.Hkv) // 32), f"too many heads inside the decision margin: {near}"
+    skip = set(near)
+    # outputs on sampled rows
+    rng = np.random.default_rng(12345)
+    G = w.Hq // w.Hkv
+    rho = w.cnn.rho
+    worst, scale, n_rows = 0.0, 0.0, 0
+    pairs = []
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        n = hi - lo
+        rows = sample_rows(n, w.window, rng)
+        heads = range(w.Hq) if w.n_seqs * w.Hq <= 64 else sorted({int(x) for x in rng.integers(0, w.Hq, size=4)})
+        kept = {}
+        for hq in heads:
+            h = hq // G
+            if (s, h) in skip:
+                continue
+            if h not in kept:
+                kept[h] = orc.retain(z64[h, lo:hi], n, w.window, w.budget, w.sink, w.tau)
+            got = out[lo + torch.tensor(rows, device="cuda"), hq].float().cpu().numpy()
+            for r, i in enumerate(rows):
+                ref = orc.attention_row(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], ocfg, kept[h], i, hq)
+                worst = max(worst, float(np.abs(got[r] - ref).max()))
+                scale = max(scale, float(np.abs(ref).max()))
+                n_rows += 1
+        # cache contents: counters, a few ring slots and retained rows of a few heads
+        assert int(cache.n_seen[s]) == n and int(cache.n_scored[s]) == max(0, n - rho)
+        for h in sorted({int(x) for x in rng.integers(0, w.Hkv, size=2)}):
+            for p in sorted({max(0, n - w.window), n - 1, n - 1 - rho} | {int(x) for x in rng.integers(max(0, n - w.window), n, size=3)}):
+                slot = p % w.window
+                np.testing.assert_array_equal(to_np(cache.k_win[s, h, slot]), w.k[lo + p, h])
+                np.testing.assert_array_equal(to_np(cache.v_win[s, h, slot]), w.v[lo + p, h])
+                assert float(cache.win_score[s, h, slot]) == float(zg[h, lo + p])
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            if cnt:
+                for r in {0, cnt // 2, cnt - 1}:
+                    np.testing.assert_array_equal(to_np(cache.k_ret[s, h, r]), w.k[lo + pos[r], h])
+                    np.testing.assert_array_equal(to_np(cache.v_ret[s, h, r]), w.v[lo + pos[r], h])
+                    assert float(cache.ret_score[s, h, r]) == float(zg[h, lo + pos[r]]) or pos[r] < w.sink
+    tol = OUT_TOL[w.dtype]
+    print(f"[{w.name}] {n_rows} sampled rows: max-abs err {worst:.3e}, largest reference magnitude {scale:.3e}", flush=True)
+    assert worst <= tol and worst <= tol * scale
+    return cache, z64
+
+
+def test_full_prefill_bf16():
+    run_full_prefill(wl.config_prefill_bf16())
+
+
+def test_full_long_prefill_bf16():
+    run_full_prefill(wl.config_long_prefill_bf16())
+
+
+def test_full_varlen_prefill_bf16():
+    w = wl.config_varlen_prefill_bf16()
+    cache, z64 = run_full_prefill(w)
+    # planted near-duplicate keys: the oracle row for the query each was planted for is covered by the sampled
+    # check only by chance, so check a handful of (planted key, its query) pairs explicitly on KV head 0
+    ocfg = oracle_cfg(w)
+    d = DeviceWorkload(w)
+    cache2 = d.new_cache()
+    out = B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache2)
+    worst = 0.0
+    for s, (js, iq) in enumerate(w.notes["planted"][:4]):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        kept = orc.retain(z64[0, lo:hi], hi - lo, w.window, w.budget, w.sink, w.tau)
+        for i in iq[:5]:
+            ref = orc.attention_row(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], ocfg, kept, int(i - lo), 0)
+            worst = max(worst, float(np.abs(out[int(i), 0].float().cpu().numpy() - ref).max()))
+    assert worst <= OUT_TOL["bf16"]
+
+
+def oracle_state_of_sequence(st, b, win_z64, cfg):
+    """Oracle state of sequence b of a directly filled cache. win_z64[h][i] = oracle logit of ring position
+    n_seen - window + i (ring slot order equals position order when n_seen is a multiple of the window)."""
+    n = int(st.n_seen[b])
+    assert n % st.window == 0
+    rho = st.cnn.rho
+    s = orc.empty_state(cfg)
+    s.n_seen, s.n_scored = n, n - rho
+    for h in range(st.Hkv):
+        hs = s.heads[h]
+        for i in range(st.window):
+            p = n - st.window + i
+            hs.win_pos.append(p)
+            hs.win_k.append(st.k_win[b, h, i].astype(np.float64))
+            hs.win_v.append(st.v_win[b, h, i].astype(np.float64))
+            if p < s.n_scored:
+                hs.win_z[p] = float(win_z64[h][i])
+        for r in range(int(st.ret_count[b, h])):
+            hs.ret_pos.append(int(st.ret_pos[b, h, r]))
+            hs.ret_key.append(np.float32(st.ret_score[b, h, r]))
+            hs.ret_k.append(st.k_ret[b, h, r].astype(np.float64))
+            hs.ret_v.append(st.v_ret[b, h, r].astype(np.float64))
+    return s
+
+
+def test_full_decode_bf16():
+    """decode_bf16 at full size (B=64, H=16, D=128, window 1024, 512 retained): ring logits from the oracle on all
+    1024 rings, 48 steps on the GPU; outputs against the oracle on two sampled sequences at every step; the
+    eviction rule replayed by the oracle on ALL (sequence, head) pairs."""
+    st = wl.config_decode_bf16()
+    ocfg = orc.OracleCfg(st.Hq, st.Hkv, st.D, st.window, st.budget, st.sink, st.tau)
+    ocnn = oracle_cnn(st.cnn)
+    rho = st.cnn.rho
+    print("[decode_bf16] scoring 1024 rings with the oracle", flush=True)
+    win_z = np.zeros((st.B, st.Hkv, st.window), dtype=np.float64)
+    for b in range(st.B):
+        kb = np.transpose(st.k_win[b], (1, 0, 2))   # [window, Hkv, D]
+        vb = np.transpose(st.v_win[b], (1, 0, 2))
+        win_z[b] = orc.score_sequence(kb, vb, ocnn)
+    dt = st.dtype
+    cfg = B.make_cfg(st.Hq, st.Hkv, st.D, st.window, st.budget, st.sink, st.tau, 0.0, dt)
+    c = st.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, dt)
+    cache = B.wrap_cache(dev(st.k_win, dt), dev(st.v_win, dt), torch.from_numpy(win_z.astype(np.float32)).cuda(),
+                         dev(st.k_ret, dt), dev(st.v_ret, dt), torch.from_numpy(st.ret_score).cuda(),
+                         torch.from_numpy(st.ret_pos).cuda(), torch.from_numpy(st.ret_count).cuda(),
+                         torch.from_numpy(st.n_seen).cuda(),
+                         torch.from_numpy((st.n_seen - rho).astype(np.int32)).cuda())
+    sampled = [0, 37]
+    states = {b: oracle_state_of_sequence(st, b, win_z[b], ocfg) for b in sampled}
+    # position-only oracle records for every (sequence, head): the eviction rule needs logits and keys only
+    light = [[orc.HeadState(ret_pos=[int(x) for x in st.ret_pos[b, h, :st.ret_count[b, h]]],
+                            ret_key=[np.float32(x) for x in st.ret_score[b, h, :st.ret_count[b, h]]],
+                            ret_k=[None] * int(st.ret_count[b, h]), ret_v=[None] * int(st.ret_count[b, h]))
+              for h in range(st.Hkv)] for b in range(st.B)]
+    n_steps = 48
+    n0 = int(st.n_seen[0])
+    worst, scale = 0.0, 0.0
+    for step in range(n_steps):
+        q, k, v = wl.decode_inputs(st.seed, step, dt, st.B, st.Hq, st.Hkv, st.D)
+        out = B.ltea_decode_step(cfg, cnn, dev(q, dt), dev(k, dt), dev(v, dt), cache)
+        og = out[sampled].float().cpu().numpy()
+        for i, b in enumerate(sampled):
+            ref = orc.decode_step(states[b], q[b], k[b], v[b], ocfg, ocnn)
+            worst = max(worst, float(np.abs(og[i] - ref).max()))
+            scale = max(scale, float(np.abs(ref).max()))
+        # the token leaving every ring at this step is initial ring position i = step (its logit is final: i < window - rho)
+        e = n0 - st.window + step
+        for b in range(st.B):
+            for h in range(st.Hkv):
+                orc.evict_into_retained(light[b][h], e, win_z[b, h, step], None, None, ocfg)
+        if step % 16 == 15:
+            print(f"[decode_bf16] step {step + 1}/{n_steps}: max-abs err so far {worst:.3e}", flush=True)
+    assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale
+    torch.cuda.synchronize()
+    assert np.all(cache.n_seen.cpu().numpy() == n0 + n_steps)
+    pos = cache.ret_pos.cpu().numpy()
+    cnt = cache.ret_count.cpu().numpy()
+    for b in range(st.B):
+        for h in range(st.Hkv):
+            np.testing.assert_array_equal(np.sort(pos[b, h, :cnt[b, h]]), np.sort(light[b][h].ret_pos),
+                                          err_msg=f"retained set of sequence {b} head {h}")
+    for b in sampled:
+        for h in range(st.Hkv):
+            np.testing.assert_array_equal(np.sort(pos[b, h, :cnt[b, h]]), orc.retained_positions(states[b])[h])
+            for p, zp in states[b].heads[h].win_z.items():
+                if p >= n0 - rho:      # logits finalised by the decode steps themselves
+                    zg = float(cache.win_score[b, h, p % st.window])
+                    assert abs(zg - zp) <= LOGIT_TOL["bf16"] * max(1.0, abs(zp))
