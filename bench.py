@@ -96,7 +96,7 @@ def bench_prefill(args):
     dq, dk, dv = up(dq, w.dtype), up(dk, w.dtype), up(dv, w.dtype)
     dout = torch.empty((nB, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
     ws = torch.empty(max(B.ltea_workspace_bytes(cfg, cnn, nB, T, w.max_seqlen), 16), dtype=torch.uint8, device="cuda")
-    dws = torch.empty(max(B.ltea_decode_workspace_bytes(cfg, cnn, nB), 16), dtype=torch.uint8, device="cuda")
+    dws = B.decode_workspace(cfg, cnn, nB)
     logits = torch.empty((w.Hkv, T), dtype=torch.float32, device="cuda")
 
     def step(i):
@@ -187,7 +187,7 @@ def bench_decode(args):
         q, k, v = wl.decode_inputs(st.seed, i, dt, st.B, st.Hq, st.Hkv, st.D)
         steps_in.append((up(q, dt), up(k, dt), up(v, dt)))
     out = torch.empty((st.B, st.Hq, st.D), dtype=torch.bfloat16, device="cuda")
-    ws = torch.empty(max(B.ltea_decode_workspace_bytes(cfg, cnn, st.B), 16), dtype=torch.uint8, device="cuda")
+    ws = B.decode_workspace(cfg, cnn, st.B)
     for i in range(8):   # warm-up steps also advance the state; the ring just keeps rotating
         q, k, v = steps_in[i]
         B.ltea_decode_step(cfg, cnn, q, k, v, cache, out=out, workspace=ws)

@@ -107,7 +107,8 @@ const char *ltea_strerror(int status);
 size_t ltea_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
                             int32_t max_seqlen);
 
-/* Bytes of device workspace ltea_decode_step needs for n_seqs sequences. */
+/* Bytes of device workspace ltea_decode_step needs for n_seqs sequences (contents need no initialisation
+ * and need not be preserved between steps). */
 size_t ltea_decode_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs);
 
 /* (a) Scoring (Section 3.1.1): logits[h][t] for every packed token t and KV
@@ -170,8 +171,8 @@ int ltea_prefill(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_
  * q: contiguous [n_seqs][Hq][D]; k, v: contiguous [n_seqs][Hkv][D]; out:
  * contiguous [n_seqs][Hq][D].  Requires the invariant n_scored = max(0,
  * n_seen - rho) on entry (true after ltea_retain / ltea_prefill / a previous
- * step, and for an all-zero fresh cache).  Concurrent calls on the same cache
- * race. */
+ * step, and for an all-zero fresh cache).  Concurrent calls on the same cache or
+ * the same workspace race. */
 int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);

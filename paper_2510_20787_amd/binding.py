@@ -184,6 +184,11 @@ def _workspace(nbytes: int, device) -> Optional[torch.Tensor]:
     return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=device)
 
 
+def decode_workspace(cfg: ltea_cfg, cnn: Optional["Cnn"], n_seqs: int, device="cuda") -> torch.Tensor:
+    """A workspace for ltea_decode_step, reusable across steps."""
+    return _workspace(ltea_decode_workspace_bytes(cfg, cnn, n_seqs), device)
+
+
 def _tok_head_strides(x: torch.Tensor):
     assert x.dim() == 3 and x.stride(2) == 1, "expected a [T, H, D] view with contiguous last dimension"
     return x.stride(0), x.stride(1)

@@ -230,7 +230,7 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
   int row_floats = 2 * cfg->D;
   for (int l = 0; l < cnn->n_layers; ++l) row_floats = cnn->c_out[l] > row_floats ? cnn->c_out[l] : row_floats;
   const size_t lds = (size_t)2 * (2 * cnn_rho(cnn) + 1) * row_floats * sizeof(float);
-  if (lds > 60 * 1024) return LTEA_EUNSUPPORTED;  // activation pyramid of the per-step scoring must fit LDS
+  if (lds > 48 * 1024) return LTEA_EUNSUPPORTED;  // activation pyramid of the per-step scoring must fit LDS
   const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
   return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace,

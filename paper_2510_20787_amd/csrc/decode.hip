@@ -1,31 +1,39 @@
 // One decode step of the SWA+LTE cache (paper Section 3.1.3: cache replacement, decode attention and
 // the deferred scoring of Section 3.1.1 item 2).
 //
-// Three launches per step, all on the caller's stream:
-//   decode_update_kernel   one workgroup per (sequence, KV head): finalises the logit of position t-rho
-//                          from the 2*rho newest ring rows plus the incoming token (any CNN depth, the
-//                          activation pyramid lives in LDS), pops position t-window from the ring and
-//                          inserts it into / lets it displace the worst entry of the compact segment,
-//                          then writes k_t, v_t into ring slot t % window.
-//   decode_attention_kernel  the memory-bound part: grid (sequence x KV head, split); every split streams
-//                          its share of the [ring rows ++ compact rows] with 16-byte loads, one row per
-//                          group of D*sizeof(T)/16 lanes, several rows in flight per lane, and keeps an
-//                          online-softmax partial (max, sum, D accumulators) per query head.
-//   decode_combine_kernel  merges the split partials, writes the output row and advances n_seen/n_scored.
+// Two launches per step on the caller's stream:
+//
+//   decode_main_kernel    1-D grid = [scoring workgroups][attention workgroups].  Nothing in the cache is modified.
+//     scoring role        finalises the logit of position t-rho of every (sequence, KV head) from the 2*rho newest
+//                         ring rows plus the incoming token, and parks it in the workspace.  Single-layer bf16:
+//                         one workgroup per (KV head, 64 sequences); the conv over the batch is a small GEMM
+//                         [sequences x taps*2D] . [taps*2D x C] on v_mfma_f32_16x16x32_bf16 with both operands
+//                         read straight from global memory (weights are shared by all sequences of a head).
+//                         Otherwise (fp32, deeper stacks): one workgroup per (sequence, head), activation pyramid
+//                         in LDS.  These few workgroups are dispatched first and hide under the streaming.
+//     attention role      the memory-bound part: grid (sequence x KV head) x splits; each workgroup streams its
+//                         share of the rows the query must see AFTER this step's cache update, without waiting
+//                         for that update: the row of ring slot t % window is taken from the incoming k_t, v_t,
+//                         and the compact slot that will receive the evicted token (decided from the old state:
+//                         one pass over `budget` keys, only by workgroups whose share touches the compact
+//                         segment) is taken from the old ring row.  16-byte loads, one row per D*sizeof(T)/16
+//                         lanes, several rows in flight per lane group, online softmax per group, fixed-order
+//                         merges.
+//   decode_finish_kernel  one workgroup per (sequence, KV head): repeats the eviction decision, moves the evicted
+//                         row into the compact segment, writes k_t, v_t and the new logit into the ring, merges
+//                         the split partials of the group's query heads into the output row and advances
+//                         n_seen / n_scored.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 
 namespace ltea {
 namespace {
 
-constexpr int kUpdThreads = 256;
-constexpr int kConvSplit = 8;    // lanes cooperating on one conv output in the update kernel
-constexpr int kAttnThreads = 256;
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kConvSplit = 8;     // lanes cooperating on one conv output in the scoring role
 constexpr int kRowsInFlight = 4;  // rows per lane group per iteration of the streaming loop
 
-// --------------------------------------------------------------------------------------------------
-// update: scoring of t-rho, eviction of t-window, append of t
-// --------------------------------------------------------------------------------------------------
 struct CnnDev {
   int n_layers;
   int kernel[LTEA_MAX_CNN_LAYERS], dilation[LTEA_MAX_CNN_LAYERS], c_out[LTEA_MAX_CNN_LAYERS];
@@ -35,161 +43,19 @@ struct CnnDev {
   const float* b_out;
 };
 
-template <typename T>
-__global__ void __launch_bounds__(kUpdThreads)
-decode_update_kernel(CnnDev cnn, int rho, int lds_row_floats, const T* __restrict__ k_new,
-                     const T* __restrict__ v_new, int Hkv, int D, int window, int budget, int sink, float tau,
-                     T* __restrict__ k_win, T* __restrict__ v_win, float* __restrict__ win_score,
-                     T* __restrict__ k_ret, T* __restrict__ v_ret, float* __restrict__ ret_score,
-                     int32_t* __restrict__ ret_pos, int32_t* __restrict__ ret_count,
-                     const int32_t* __restrict__ n_seen) {
-  extern __shared__ float lds[];  // two activation buffers of (2*rho+1) rows x lds_row_floats
-  __shared__ unsigned long long red[kUpdThreads / kWave];
-  __shared__ int worst_slot;
-  const int tid = threadIdx.x;
-  const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
-  const int64_t head = (int64_t)b * Hkv + h;
-  const int t = n_seen[b];
-  const int slot = t % window;
-  const int rows0 = 2 * rho + 1;
-  float* buf_a = lds;
-  float* buf_b = lds + (size_t)rows0 * lds_row_floats;
+struct CacheDev {
+  void *k_win, *v_win;
+  float* win_score;
+  void *k_ret, *v_ret;
+  float* ret_score;
+  int32_t *ret_pos, *ret_count, *n_seen, *n_scored;
+};
 
-  // logit of the token that leaves the window; read before anything is written this step
-  const int e_pos = t - window;
-  const float z_e = e_pos >= 0 ? win_score[head * window + slot] : 0.f;
-  const int cnt = ret_count[head];
+struct StepParams {
+  int B, Hq, Hkv, D, window, budget, sink, rho, nsplit, lds_row_floats, n_score_blocks, score_mfma;
+  float tau, scale;
+};
 
-  // ---- 1. final logit of position j = t - rho --------------------------------------------------
-  const int j_fin = t - rho;
-  if (j_fin >= 0) {
-    // layer-0 features: rows r = 0..2rho hold positions t-2rho .. t  (keys then values)
-    const int C0 = 2 * D;
-    for (int idx = tid; idx < rows0 * C0; idx += kUpdThreads) {
-      const int r = idx / C0, m = idx - r * C0;
-      const int p = t - 2 * rho + r;
-      float x = 0.f;
-      if (p >= 0) {
-        const bool is_v = m >= D;
-        const int mm = is_v ? m - D : m;
-        if (p == t) {
-          x = to_f32((is_v ? v_new : k_new)[head * D + mm]);
-        } else {
-          const int64_t row = head * window + (p % window);
-          x = to_f32((is_v ? v_win : k_win)[row * D + mm]);
-        }
-      }
-      buf_a[r * lds_row_floats + m] = x;
-    }
-    __syncthreads();
-    float* cur = buf_a;
-    float* nxt = buf_b;
-    int cur_rows = rows0, cur_lo = t - 2 * rho, cin = C0;
-    for (int l = 0; l < cnn.n_layers; ++l) {
-      const int ks = cnn.kernel[l], dil = cnn.dilation[l], cout = cnn.c_out[l];
-      const int half = dil * (ks - 1) / 2;
-      const int out_rows = cur_rows - 2 * half;
-      const int out_lo = cur_lo + half;
-      const T* W = static_cast<const T*>(cnn.w[l]) + (int64_t)h * cout * cin * ks;
-      // kConvSplit adjacent lanes share one (row, channel): each sums a contiguous slice of the input
-      // channels over all taps, then the slices are added in a fixed order.
-      const int per = (cin + kConvSplit - 1) / kConvSplit;
-      for (int idx = tid; idx < out_rows * cout * kConvSplit; idx += kUpdThreads) {
-        const int sub = idx % kConvSplit, rc = idx / kConvSplit;
-        const int r = rc / cout, c = rc - r * cout;
-        float acc = 0.f;
-        if (out_lo + r >= 0) {
-          const T* Wc = W + (int64_t)c * cin * ks;
-          const int m0 = sub * per, m1 = min(cin, m0 + per);
-          for (int m = m0; m < m1; ++m)
-            for (int tap = 0; tap < ks; ++tap)
-              acc = fmaf(cur[(r + tap * dil) * lds_row_floats + m], to_f32(Wc[m * ks + tap]), acc);
-        }
-#pragma unroll
-        for (int off = kConvSplit / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-        if (sub == 0) {
-          // activations at positions before the sequence start are zero padding, not Swish(bias)
-          nxt[r * lds_row_floats + c] = (out_lo + r >= 0) ? silu_f32(acc + cnn.bias[l][h * cout + c]) : 0.f;
-        }
-      }
-      __syncthreads();
-      float* tmp = cur; cur = nxt; nxt = tmp;
-      cur_rows = out_rows; cur_lo = out_lo; cin = cout;
-    }
-    // cur holds one row (position j_fin) of cin channels
-    if (tid < kWave) {
-      float part = 0.f;
-      for (int c = tid; c < cin; c += kWave) part = fmaf(cur[c], to_f32(static_cast<const T*>(cnn.w_out)[h * cin + c]), part);
-      // fixed-order reduction across the wave (deterministic)
-      part = wave_sum(part);
-      if (tid == 0) win_score[head * window + (j_fin % window)] = part + cnn.b_out[h];
-    }
-  }
-
-  // ---- 2. eviction of position e = t - window ---------------------------------------------------
-  int dst = -1;  // compact slot that receives row e, or -1
-  float key_e = 0.f;
-  if (e_pos >= 0 && budget > 0) {
-    const bool cand = (e_pos < sink) || (z_e > tau);
-    key_e = select_key(z_e, e_pos, sink);
-    if (cand) {
-      if (cnt < budget) {
-        dst = cnt;
-      } else {
-        // worst entry: lowest key, among equal keys the latest position
-        unsigned long long best = ~0ull;
-        for (int r = tid; r < budget; r += kUpdThreads) {
-          const uint32_t u = order_key(ret_score[head * budget + r] + 0.0f);
-          const uint32_t pinv = 0xFFFFFFFFu - (uint32_t)ret_pos[head * budget + r];
-          const unsigned long long comp = ((unsigned long long)u << 32) | pinv;
-          best = comp < best ? comp : best;
-        }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-          unsigned long long o = __shfl_xor(best, off, kWave);
-          best = o < best ? o : best;
-        }
-        if ((tid & (kWave - 1)) == 0) red[tid / kWave] = best;
-        __syncthreads();
-        best = red[0];
-#pragma unroll
-        for (int w = 1; w < kUpdThreads / kWave; ++w) best = red[w] < best ? red[w] : best;
-        const uint32_t worst_u = (uint32_t)(best >> 32);
-        const int worst_pos = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
-        if (tid == 0) worst_slot = -1;
-        __syncthreads();
-        for (int r = tid; r < budget; r += kUpdThreads)
-          if (ret_pos[head * budget + r] == worst_pos) worst_slot = r;  // positions are unique
-        __syncthreads();
-        if (order_key(key_e) > worst_u) dst = worst_slot;
-      }
-    }
-  }
-
-  // ---- 3. move row e into the compact segment, then overwrite its ring slot with token t --------
-  __syncthreads();  // every thread has read z_e, cnt and the ring rows it needs
-  const int pieces = D * (int)sizeof(T) / 16;
-  const int64_t ring_row = (head * window + slot) * D;
-  if (dst >= 0) {
-    const int64_t ret_row = (head * budget + dst) * D;
-    if (tid < pieces) reinterpret_cast<u32x4*>(k_ret + ret_row)[tid] = reinterpret_cast<const u32x4*>(k_win + ring_row)[tid];
-    else if (tid < 2 * pieces)
-      reinterpret_cast<u32x4*>(v_ret + ret_row)[tid - pieces] = reinterpret_cast<const u32x4*>(v_win + ring_row)[tid - pieces];
-    if (tid == 0) {
-      ret_score[head * budget + dst] = key_e;
-      ret_pos[head * budget + dst] = e_pos;
-      if (dst == cnt) ret_count[head] = cnt + 1;
-    }
-  }
-  __syncthreads();
-  if (tid < pieces) reinterpret_cast<u32x4*>(k_win + ring_row)[tid] = reinterpret_cast<const u32x4*>(k_new + head * D)[tid];
-  else if (tid < 2 * pieces)
-    reinterpret_cast<u32x4*>(v_win + ring_row)[tid - pieces] = reinterpret_cast<const u32x4*>(v_new + head * D)[tid - pieces];
-}
-
-// --------------------------------------------------------------------------------------------------
-// attention partials
-// --------------------------------------------------------------------------------------------------
 // exp used by the softmax: library expf for fp32 storage (1e-5 tolerance), hardware exp2 path for bf16.
 template <typename T> __device__ __forceinline__ float soft_exp(float x);
 template <> __device__ __forceinline__ float soft_exp<float>(float x) { return expf(x); }
@@ -198,6 +64,10 @@ template <> __device__ __forceinline__ float soft_exp<bf16_t>(float x) { return 
 template <typename T> struct Piece;  // 16 bytes of a row as fp32 values
 template <> struct Piece<float> {
   static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float (&x)[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(r[i]);
+  }
   static __device__ __forceinline__ void load(const float* p, float (&x)[4]) {
     const f32x4 r = *reinterpret_cast<const f32x4*>(p);
     x[0] = r[0]; x[1] = r[1]; x[2] = r[2]; x[3] = r[3];
@@ -205,6 +75,13 @@ template <> struct Piece<float> {
 };
 template <> struct Piece<bf16_t> {
   static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const u32x4& r, float (&x)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[2 * i] = __uint_as_float(r[i] << 16);
+      x[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
+    }
+  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&x)[8]) {
     const u32x4 r = *reinterpret_cast<const u32x4*>(p);
 #pragma unroll
@@ -215,76 +92,401 @@ template <> struct Piece<bf16_t> {
   }
 };
 
+// Where does the token leaving the window go?  Returns the compact slot that receives it (== cnt for an
+// append), or -1 if it is dropped.  A pure function of the state before the step, evaluated identically by
+// every workgroup that needs it.  All threads of the block must call it; `red`/`slot_out` are LDS scratch.
+__device__ __forceinline__ int eviction_target(int t, int window, int budget, int sink, float tau, int cnt,
+                                               float z_e, const float* __restrict__ ret_score,
+                                               const int32_t* __restrict__ ret_pos, unsigned long long* red,
+                                               int* slot_out) {
+  const int e_pos = t - window;
+  if (e_pos < 0 || budget <= 0) return -1;
+  if (!((e_pos < sink) || (z_e > tau))) return -1;
+  if (cnt < budget) return cnt;
+  // victim: lowest key, among equal keys the latest position
+  const int tid = threadIdx.x;
+  unsigned long long best = ~0ull;
+  for (int r = tid; r < budget; r += kThreads) {
+    const uint32_t u = order_key(ret_score[r] + 0.0f);
+    const uint32_t pinv = 0xFFFFFFFFu - (uint32_t)ret_pos[r];
+    const unsigned long long comp = ((unsigned long long)u << 32) | pinv;
+    best = comp < best ? comp : best;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned long long o = __shfl_xor(best, off, kWave);
+    best = o < best ? o : best;
+  }
+  __syncthreads();
+  if ((tid & (kWave - 1)) == 0) red[tid / kWave] = best;
+  if (tid == 0) *slot_out = -1;
+  __syncthreads();
+  best = red[0];
+#pragma unroll
+  for (int w = 1; w < kWaves; ++w) best = red[w] < best ? red[w] : best;
+  const uint32_t worst_u = (uint32_t)(best >> 32);
+  const int worst_pos = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+  for (int r = tid; r < budget; r += kThreads)
+    if (ret_pos[r] == worst_pos) *slot_out = r;  // positions are unique
+  __syncthreads();
+  const int victim = *slot_out;
+  return order_key(select_key(z_e, e_pos, sink)) > worst_u ? victim : -1;
+}
+
+// ---- scoring role ------------------------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void score_new_token(const CnnDev& cnn, const StepParams& P, const T* __restrict__ k_new,
+                                                const T* __restrict__ v_new, const T* __restrict__ k_win,
+                                                const T* __restrict__ v_win, int64_t head, int h, int t, float* lds,
+                                                float* __restrict__ ws_logit) {
+  const int tid = threadIdx.x;
+  const int rho = P.rho, D = P.D, window = P.window, row_f = P.lds_row_floats;
+  const int j_fin = t - rho;
+  if (j_fin < 0) return;
+  const int rows0 = 2 * rho + 1;
+  float* cur = lds;
+  float* nxt = lds + (size_t)rows0 * row_f;
+  // layer-0 features: rows r = 0..2rho hold positions t-2rho .. t  (keys then values), one 16-byte piece per
+  // thread per pass so that the whole staging costs one memory round trip
+  const int C0 = 2 * D;
+  constexpr int EPP = 16 / (int)sizeof(T);  // elements per piece
+  const int ppr = C0 / EPP;
+  for (int idx = tid; idx < rows0 * ppr; idx += kThreads) {
+    const int r = idx / ppr, piece = idx - r * ppr;
+    const int m = piece * EPP;
+    const int p = t - 2 * rho + r;
+    float x[EPP];
+#pragma unroll
+    for (int i = 0; i < EPP; ++i) x[i] = 0.f;
+    if (p >= 0) {
+      const bool is_v = m >= D;
+      const int mm = is_v ? m - D : m;
+      const T* src = (p == t) ? (is_v ? v_new : k_new) + head * D + mm
+                              : (is_v ? v_win : k_win) + (head * window + (p % window)) * D + mm;
+      Piece<T>::load(src, x);
+    }
+#pragma unroll
+    for (int i = 0; i < EPP; ++i) cur[r * row_f + m + i] = x[i];
+  }
+  __syncthreads();
+  int cur_rows = rows0, cur_lo = t - 2 * rho, cin = C0;
+  for (int l = 0; l < cnn.n_layers; ++l) {
+    const int ks = cnn.kernel[l], dil = cnn.dilation[l], cout = cnn.c_out[l];
+    const int half = dil * (ks - 1) / 2;
+    const int out_rows = cur_rows - 2 * half;
+    const int out_lo = cur_lo + half;
+    const T* W = static_cast<const T*>(cnn.w[l]) + (int64_t)h * cout * cin * ks;
+    // kConvSplit adjacent lanes share one (row, channel): each sums a contiguous slice of the input channels
+    // over all taps (a contiguous run of weights), then the slices are added in a fixed order.
+    const int per = (cin + kConvSplit - 1) / kConvSplit;
+    for (int idx = tid; idx < out_rows * cout * kConvSplit; idx += kThreads) {
+      const int sub = idx % kConvSplit, rc = idx / kConvSplit;
+      const int r = rc / cout, c = rc - r * cout;
+      float acc = 0.f;
+      if (out_lo + r >= 0) {
+        const int m0 = sub * per, m1 = min(cin, m0 + per);
+        const T* Wc = W + ((int64_t)c * cin + m0) * ks;           // weights of (c, m0.., all taps): contiguous
+        const float* xin = cur + r * row_f;
+        const int n_el = (m1 - m0) * ks;
+        int e = 0;
+        if constexpr (sizeof(T) == 2) {
+          if ((reinterpret_cast<uintptr_t>(Wc) & 15u) == 0) {
+            // 16-byte weight loads in register-double-buffered batches: the slice costs about one memory round
+            // trip instead of one per load
+            constexpr int VB = 2;
+            const int n_batches = n_el / (8 * VB);
+            u32x4 wcur[VB], wnxt[VB];
+            if (n_batches > 0) {
+#pragma unroll
+              for (int i = 0; i < VB; ++i) wcur[i] = *reinterpret_cast<const u32x4*>(Wc + 8 * i);
+            }
+            int m = m0, tap = 0;
+            for (int bt = 0; bt < n_batches; ++bt) {
+              if (bt + 1 < n_batches) {
+#pragma unroll
+                for (int i = 0; i < VB; ++i) wnxt[i] = *reinterpret_cast<const u32x4*>(Wc + (bt + 1) * 8 * VB + 8 * i);
+              }
+#pragma unroll
+              for (int i = 0; i < VB; ++i) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                  const float wf = (j & 1) ? __uint_as_float(wcur[i][j / 2] & 0xFFFF0000u) : __uint_as_float(wcur[i][j / 2] << 16);
+                  acc = fmaf(xin[tap * dil * row_f + m], wf, acc);
+                  if (++tap == ks) { tap = 0; ++m; }
+                }
+              }
+#pragma unroll
+              for (int i = 0; i < VB; ++i) wcur[i] = wnxt[i];
+            }
+            e = n_batches * 8 * VB;
+          }
+        }
+        for (; e < n_el; ++e) {
+          const int m = m0 + e / ks, tap = e % ks;
+          acc = fmaf(xin[tap * dil * row_f + m], to_f32(Wc[e]), acc);
+        }
+      }
+#pragma unroll
+      for (int off = kConvSplit / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+      if (sub == 0) {
+        // activations at positions before the sequence start are zero padding, not Swish(bias)
+        nxt[r * row_f + c] = (out_lo + r >= 0) ? silu_f32(acc + cnn.bias[l][h * cout + c]) : 0.f;
+      }
+    }
+    __syncthreads();
+    float* tmp = cur; cur = nxt; nxt = tmp;
+    cur_rows = out_rows; cur_lo = out_lo; cin = cout;
+  }
+  // cur holds one row (position j_fin) of cin channels
+  if (tid < kWave) {
+    float part = 0.f;
+    for (int c = tid; c < cin; c += kWave)
+      part = fmaf(cur[c], to_f32(static_cast<const T*>(cnn.w_out)[h * cin + c]), part);
+    part = wave_sum(part);  // fixed order: deterministic
+    if (tid == 0) ws_logit[head] = part + cnn.b_out[h];
+  }
+}
+
+// ---- scoring role, batched over sequences on MFMA (single conv layer, bf16, kernel size KS) ----------------------
+// Workgroup = (KV head h, group of 64 sequences).  The conv over the batch is the GEMM
+//   out[sequence, channel] = sum_{tap, m} x[sequence][tap][m] * W[channel][m][tap]
+// on v_mfma_f32_16x16x32_bf16: 4 row tiles of 16 sequences, 2 column tiles of 16 channels, K = (tap, m) with 32
+// input channels per instruction.  The four waves split the input channels, so every weight is fetched once per
+// workgroup (KS contiguous 16-byte loads per lane cover all taps of its 8 channels) and reused for all row tiles;
+// features come straight from the ring rows / the incoming token.  Partial sums of the waves meet in LDS.
+// Lane roles: A row / B column = lane % 16, K group kg = lane / 16 supplies 8 consecutive channels;
+// accumulator register r of a lane is (row 4*kg + r, column lane % 16).
+template <int D, int KS>
+__device__ __forceinline__ void score_new_tokens_mfma(const CnnDev& cnn, const StepParams& P, const CacheDev& C,
+                                                      const bf16_t* __restrict__ k_new, const bf16_t* __restrict__ v_new,
+                                                      int h, int b0, float* red /* 2048 floats of LDS */,
+                                                      float* __restrict__ ws_logit, int32_t* __restrict__ ws_t) {
+  constexpr int C2 = 2 * D;
+  constexpr int MCW = C2 / 32 / kWaves;  // 32-channel chunks per wave
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+  const int row = lane & 15, kg = lane >> 4;
+  const int dil = cnn.dilation[0], Cout = cnn.c_out[0];
+  const int rho = P.rho, window = P.window;
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(cnn.w[0]) + (int64_t)h * Cout * C2 * KS;
+
+  const int seq_l = tid / 16, chp = tid % 16;   // finishing thread: sequence seq_l of a row tile, channels chp, chp+16
+  float bias0 = 0.f, bias1 = 0.f, wo0 = 0.f, wo1 = 0.f;
+  if (chp < Cout) { bias0 = cnn.bias[0][h * Cout + chp]; wo0 = to_f32(static_cast<const bf16_t*>(cnn.w_out)[h * Cout + chp]); }
+  if (chp + 16 < Cout) { bias1 = cnn.bias[0][h * Cout + chp + 16]; wo1 = to_f32(static_cast<const bf16_t*>(cnn.w_out)[h * Cout + chp + 16]); }
+
+  // two row tiles (32 sequences) per pass keeps the register footprint of this role below the streaming role's
+#pragma unroll 1
+  for (int mt0 = 0; mt0 < 4; mt0 += 2) {
+    if (b0 + 16 * mt0 >= P.B) break;   // uniform: no sequences left
+    int t_mt[2];
+    const bf16_t *kw_mt[2], *vw_mt[2], *kn_mt[2], *vn_mt[2];
+    bool ok_mt[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int b = b0 + 16 * (mt0 + i) + row;
+      ok_mt[i] = b < P.B;
+      const int bc = ok_mt[i] ? b : P.B - 1;
+      const int64_t head = (int64_t)bc * P.Hkv + h;
+      t_mt[i] = C.n_seen[bc];
+      kw_mt[i] = static_cast<const bf16_t*>(C.k_win) + head * window * D;
+      vw_mt[i] = static_cast<const bf16_t*>(C.v_win) + head * window * D;
+      kn_mt[i] = k_new + head * D;
+      vn_mt[i] = v_new + head * D;
+      if (h == 0 && wv == 0 && kg == 0 && ok_mt[i]) ws_t[b] = t_mt[i];
+    }
+    f32x4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) acc[i][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll 1
+    for (int mcw = 0; mcw < MCW; ++mcw) {
+      const int m = 32 * (wv * MCW + mcw) + 8 * kg;   // first of this lane's 8 input channels
+      // weights of channels m..m+7, all taps, for output channels row and 16+row: KS*8 contiguous elements each
+      uint32_t wraw[2][KS * 4];
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int c = 16 * nb + row;
+        const u32x4* wp = reinterpret_cast<const u32x4*>(W + ((int64_t)(c < Cout ? c : 0) * C2 + m) * KS);
+#pragma unroll
+        for (int i = 0; i < KS; ++i) {
+          u32x4 x = wp[i];
+          if (c >= Cout) x = u32x4{0u, 0u, 0u, 0u};
+          wraw[nb][4 * i] = x[0]; wraw[nb][4 * i + 1] = x[1]; wraw[nb][4 * i + 2] = x[2]; wraw[nb][4 * i + 3] = x[3];
+        }
+      }
+#pragma unroll
+      for (int tap = 0; tap < KS; ++tap) {
+        // B operand: element e is flat index e*KS + tap of the lane's weight run
+        u32x4 bop[2];
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int e2 = 0; e2 < 4; ++e2) {
+            const int f0 = (2 * e2) * KS + tap, f1 = (2 * e2 + 1) * KS + tap;
+            const uint32_t lo16 = (f0 & 1) ? (wraw[nb][f0 / 2] >> 16) : (wraw[nb][f0 / 2] & 0xFFFFu);
+            const uint32_t hi16 = (f1 & 1) ? (wraw[nb][f1 / 2] & 0xFFFF0000u) : (wraw[nb][f1 / 2] << 16);
+            bop[nb][e2] = lo16 | hi16;
+          }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const int p = t_mt[i] - 2 * rho + tap * dil;   // position this tap reads for the token t - rho
+          const bool p_ok = p >= 0 && ok_mt[i];
+          const int slot_p = (p_ok ? p : 0) % window;
+          const bf16_t* src;
+          if (m < D) src = (p == t_mt[i] ? kn_mt[i] : kw_mt[i] + (int64_t)slot_p * D) + m;
+          else src = (p == t_mt[i] ? vn_mt[i] : vw_mt[i] + (int64_t)slot_p * D) + (m - D);
+          u32x4 araw = *reinterpret_cast<const u32x4*>(src);
+          if (!p_ok) araw = u32x4{0u, 0u, 0u, 0u};
+          const bf16x8 a = __builtin_bit_cast(bf16x8, araw);
+          acc[i][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bop[0]), acc[i][0], 0, 0, 0);
+          acc[i][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, bop[1]), acc[i][1], 0, 0, 0);
+        }
+      }
+    }
+    // cross-wave sum, bias, Swish, output projection: one row tile (16 sequences x 32 channels) per round
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      __syncthreads();
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[(wv * 16 + 4 * kg + r) * 32 + 16 * nb + row] = acc[i][nb][r];
+      __syncthreads();
+      float y0 = bias0, y1 = bias1;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        y0 += red[(w * 16 + seq_l) * 32 + chp];
+        y1 += red[(w * 16 + seq_l) * 32 + 16 + chp];
+      }
+      float z = y0 * __frcp_rn(1.0f + __expf(-y0)) * wo0 + y1 * __frcp_rn(1.0f + __expf(-y1)) * wo1;
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) z += __shfl_xor(z, off, kWave);
+      const int bb = b0 + 16 * (mt0 + i) + seq_l;
+      if (chp == 0 && bb < P.B && C.n_seen[bb] - rho >= 0) ws_logit[(int64_t)bb * P.Hkv + h] = z + cnn.b_out[h];
+    }
+  }
+}
+
 // Partial record per (sequence, query head, split): [max, sum, acc[D]] floats.
 template <typename T, int D>
-__global__ void __launch_bounds__(kAttnThreads)
-decode_attention_kernel(const T* __restrict__ q, const T* __restrict__ k_win, const T* __restrict__ v_win,
-                        const T* __restrict__ k_ret, const T* __restrict__ v_ret,
-                        const int32_t* __restrict__ ret_count, const int32_t* __restrict__ n_seen, int Hq, int Hkv,
-                        int window, int budget, float scale, int nsplit, float* __restrict__ partial) {
-  constexpr int EPL = Piece<T>::N;          // elements per lane
-  constexpr int LPR = D / EPL;              // lanes per row
-  constexpr int GPW = kWave / LPR;          // row groups per wave
-  constexpr int GPB = GPW * (kAttnThreads / kWave);
-  constexpr int NW = kAttnThreads / kWave;
-  __shared__ float red_m[NW][GPW], red_l[NW][GPW];
-  __shared__ float red_acc[NW][GPW][D];
+__global__ void __launch_bounds__(kThreads, 4)
+decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q, const T* __restrict__ k_new,
+                   const T* __restrict__ v_new, float* __restrict__ partial, float* __restrict__ ws_logit,
+                   int32_t* __restrict__ ws_t) {
+  constexpr int EPL = Piece<T>::N;  // elements per lane
+  constexpr int LPR = D / EPL;      // lanes per row
+  constexpr int GPW = kWave / LPR;  // row groups per wave
+  constexpr int GPB = GPW * kWaves;
+  extern __shared__ float dyn_lds[];  // per-head scoring role: two activation buffers of (2*rho+1) rows
+  __shared__ float red_m[kWaves][GPW], red_l[kWaves][GPW];
+  __shared__ float red_acc[kWaves][GPW][D];
+  __shared__ unsigned long long red64[kWaves];
+  __shared__ int slot_lds;
 
-  const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
-  const int split = blockIdx.y;
-  const int64_t head = (int64_t)b * Hkv + h;
-  const int G = Hq / Hkv;
+  const int Hkv = P.Hkv, window = P.window, budget = P.budget;
+  if ((int)blockIdx.x < P.n_score_blocks) {
+    if constexpr (sizeof(T) == 2) {
+      if (P.score_mfma) {
+        const int h = blockIdx.x % Hkv, sg = blockIdx.x / Hkv;
+        float* red = &red_acc[0][0][0];
+        static_assert(sizeof(red_acc) >= 2048 * sizeof(float), "cross-wave scoring sums need 2048 floats");
+        if (P.score_mfma == 3) score_new_tokens_mfma<D, 3>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
+        else if (P.score_mfma == 5) score_new_tokens_mfma<D, 5>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
+        else score_new_tokens_mfma<D, 7>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
+        return;
+      }
+    }
+    const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
+    const int t = C.n_seen[b];
+    if (h == 0 && threadIdx.x == 0) ws_t[b] = t;
+    score_new_token<T>(cnn, P, k_new, v_new, static_cast<const T*>(C.k_win), static_cast<const T*>(C.v_win),
+                       (int64_t)b * Hkv + h, h, t, dyn_lds, ws_logit);
+    return;
+  }
+  const int work = blockIdx.x - P.n_score_blocks;
+  const int nsplit = P.nsplit;
+  const int split = work % nsplit;
+  const int64_t head = work / nsplit;
+  const int b = (int)(head / Hkv), h = (int)(head - (int64_t)b * Hkv);
+  const int t = C.n_seen[b];
+  const T* kw = static_cast<const T*>(C.k_win) + head * window * D;
+  const T* vw = static_cast<const T*>(C.v_win) + head * window * D;
+  const int G = P.Hq / Hkv;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int sub = lane % LPR, grp = lane / LPR;
-  const int t = n_seen[b];                                   // the new token already sits in slot t % window
+  const T* kr = static_cast<const T*>(C.k_ret) + head * budget * D;
+  const T* vr = static_cast<const T*>(C.v_ret) + head * budget * D;
+  const T* kn = k_new + head * D;
+  const T* vn = v_new + head * D;
+
+  // The state after this step, described from the state before it.  Rows are addressed in a fixed slot space
+  // [ring slots 0..window) ++ [compact slots 0..budget) split evenly, so a workgroup whose share holds ring
+  // slots only never needs the eviction decision (one pass over `budget` keys plus three barriers).
+  const int slot = t % window;
   const int n_valid = t + 1 < window ? t + 1 : window;
-  const int cnt = budget > 0 ? ret_count[head] : 0;
-  const int n_rows = n_valid + cnt;
-  const int chunk = (n_rows + nsplit - 1) / nsplit;
+  const int chunk = (window + budget + nsplit - 1) / nsplit;
   const int r_begin = split * chunk;
-  const int r_end = r_begin + chunk < n_rows ? r_begin + chunk : n_rows;
-  const T* kw = k_win + head * window * D;
-  const T* vw = v_win + head * window * D;
-  const T* kr = k_ret + head * budget * D;
-  const T* vr = v_ret + head * budget * D;
+  const int r_end = r_begin + chunk < window + budget ? r_begin + chunk : window + budget;
+  int dst = -1, cnt = 0;
+  if (r_end > window && budget > 0) {   // uniform across the workgroup
+    const int cnt_old = C.ret_count[head];
+    const float z_e = t >= window ? C.win_score[head * window + slot] : 0.f;
+    dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
+                          C.ret_pos + head * budget, red64, &slot_lds);
+    cnt = cnt_old + (dst == cnt_old ? 1 : 0);
+  }
+  const T* k_evicted = kw + (int64_t)slot * D;  // old ring row that moves to compact slot dst
+  const T* v_evicted = vw + (int64_t)slot * D;
 
   for (int g = 0; g < G; ++g) {
     const int hq = h * G + g;
     float qf[EPL];
-    Piece<T>::load(q + ((int64_t)b * Hq + hq) * D + sub * EPL, qf);
+    Piece<T>::load(q + ((int64_t)b * P.Hq + hq) * D + sub * EPL, qf);
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) qf[i] *= scale;
+    for (int i = 0; i < EPL; ++i) qf[i] *= P.scale;
     float m_run = -INFINITY, l_run = 0.f, acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
 
     for (int r0 = r_begin + wave * GPW + grp; r0 < r_end; r0 += GPB * kRowsInFlight) {
-      float kf[kRowsInFlight][EPL], vf[kRowsInFlight][EPL], s[kRowsInFlight];
+      u32x4 kraw[kRowsInFlight], vraw[kRowsInFlight];
+      float s[kRowsInFlight];
+      bool live[kRowsInFlight];
 #pragma unroll
       for (int u = 0; u < kRowsInFlight; ++u) {
+        // Branch-free row selection so that all loads of the iteration are issued back to back; rows that do
+        // not exist re-read the incoming token's row and are masked out of the softmax below.
         const int r = r0 + u * GPB;
-        if (r < r_end) {
-          const T* kp = r < n_valid ? kw + (int64_t)r * D : kr + (int64_t)(r - n_valid) * D;
-          const T* vp = r < n_valid ? vw + (int64_t)r * D : vr + (int64_t)(r - n_valid) * D;
-          Piece<T>::load(kp + sub * EPL, kf[u]);
-          Piece<T>::load(vp + sub * EPL, vf[u]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < EPL; ++i) { kf[u][i] = 0.f; vf[u][i] = 0.f; }
-        }
+        const bool in_ring = r < window;
+        const int rr = r - window;
+        live[u] = (r < r_end) && (in_ring ? r < n_valid : rr < cnt);
+        const T* kp = in_ring ? kw + (int64_t)r * D : kr + (int64_t)rr * D;
+        const T* vp = in_ring ? vw + (int64_t)r * D : vr + (int64_t)rr * D;
+        const bool is_new = in_ring && r == slot;
+        const bool is_moved = !in_ring && rr == dst;
+        kp = is_moved ? k_evicted : kp;
+        vp = is_moved ? v_evicted : vp;
+        kp = (is_new || !live[u]) ? kn : kp;
+        vp = (is_new || !live[u]) ? vn : vp;
+        kraw[u] = *reinterpret_cast<const u32x4*>(kp + sub * EPL);
+        vraw[u] = *reinterpret_cast<const u32x4*>(vp + sub * EPL);
       }
       float m_new = m_run;
 #pragma unroll
       for (int u = 0; u < kRowsInFlight; ++u) {
+        float kf[EPL];
+        Piece<T>::unpack(kraw[u], kf);
         float d = 0.f;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[u][i], d);
+        for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
 #pragma unroll
         for (int off = LPR / 2; off > 0; off >>= 1) d += __shfl_xor(d, off, kWave);
-        s[u] = (r0 + u * GPB < r_end) ? d : -INFINITY;
+        s[u] = live[u] ? d : -INFINITY;
         m_new = fmaxf(m_new, s[u]);
       }
-      // r0 < r_end, so row u = 0 is real and m_new is finite
+      if (m_new == -INFINITY) continue;  // nothing live for this lane group yet
       const float alpha = soft_exp<T>(m_run - m_new);
       l_run *= alpha;
 #pragma unroll
@@ -293,8 +495,10 @@ decode_attention_kernel(const T* __restrict__ q, const T* __restrict__ k_win, co
       for (int u = 0; u < kRowsInFlight; ++u) {
         const float p = soft_exp<T>(s[u] - m_new);
         l_run += p;
+        float vf[EPL];
+        Piece<T>::unpack(vraw[u], vf);
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[u][i], acc[i]);
+        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
       }
       m_run = m_new;
     }
@@ -306,18 +510,18 @@ decode_attention_kernel(const T* __restrict__ q, const T* __restrict__ k_win, co
     __syncthreads();
     if (threadIdx.x < D) {
       float M = -INFINITY;
-      for (int w = 0; w < NW; ++w)
+      for (int w = 0; w < kWaves; ++w)
         for (int gg = 0; gg < GPW; ++gg) M = fmaxf(M, red_m[w][gg]);
       float L = 0.f, A = 0.f;
       if (M != -INFINITY) {
-        for (int w = 0; w < NW; ++w)
+        for (int w = 0; w < kWaves; ++w)
           for (int gg = 0; gg < GPW; ++gg) {
             const float f = soft_exp<T>(red_m[w][gg] - M);
             L = fmaf(red_l[w][gg], f, L);
             A = fmaf(red_acc[w][gg][threadIdx.x], f, A);
           }
       }
-      float* rec = partial + (((int64_t)b * Hq + hq) * nsplit + split) * (D + 2);
+      float* rec = partial + (((int64_t)b * P.Hq + hq) * nsplit + split) * (D + 2);
       if (threadIdx.x == 0) { rec[0] = M; rec[1] = L; }
       rec[2 + threadIdx.x] = A;
     }
@@ -326,37 +530,89 @@ decode_attention_kernel(const T* __restrict__ q, const T* __restrict__ k_win, co
 }
 
 template <typename T, int D>
-__global__ void __launch_bounds__(D)
-decode_combine_kernel(const float* __restrict__ partial, int nsplit, int Hq, int rho, T* __restrict__ out,
-                      int32_t* __restrict__ n_seen, int32_t* __restrict__ n_scored) {
-  const int64_t bh = blockIdx.x;  // b * Hq + hq
-  const float* rec = partial + bh * nsplit * (D + 2);
-  float M = -INFINITY;
-  for (int s = 0; s < nsplit; ++s) M = fmaxf(M, rec[s * (D + 2)]);
-  float L = 0.f, A = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
-    const float m = rec[s * (D + 2)];
-    if (m == -INFINITY) continue;
-    const float f = soft_exp<T>(m - M);
-    L = fmaf(rec[s * (D + 2) + 1], f, L);
-    A = fmaf(rec[s * (D + 2) + 2 + threadIdx.x], f, A);
+__global__ void __launch_bounds__(kThreads)
+decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, const T* __restrict__ v_new,
+                     const float* __restrict__ partial, const float* __restrict__ ws_logit,
+                     const int32_t* __restrict__ ws_t, T* __restrict__ out) {
+  __shared__ unsigned long long red64[kWaves];
+  __shared__ int slot_lds;
+  const int Hkv = P.Hkv, window = P.window, budget = P.budget, rho = P.rho;
+  const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
+  const int64_t head = (int64_t)b * Hkv + h;
+  const int tid = threadIdx.x;
+  // t comes from the workspace copy made by the previous kernel: n_seen[b] itself is advanced below by the
+  // h == 0 workgroup while other workgroups of the same sequence may still be starting.
+  const int t = ws_t[b];
+  const int slot = t % window;
+  const int cnt_old = budget > 0 ? C.ret_count[head] : 0;
+  const float z_e = t >= window ? C.win_score[head * window + slot] : 0.f;
+  const float z_new = t - rho >= 0 ? ws_logit[head] : 0.f;
+  __syncthreads();  // every thread holds z_e before the slot's logit can be overwritten (rho == 0)
+  const int dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
+                                  C.ret_pos + head * budget, red64, &slot_lds);
+
+  // ---- merge split partials of the group's query heads ------------------------------------------------------
+  const int G = P.Hq / Hkv, nsplit = P.nsplit;
+  for (int item = tid; item < G * D; item += kThreads) {
+    const int g = item / D, d = item - g * D;
+    const int64_t bh = (int64_t)b * P.Hq + h * G + g;
+    const float* rec = partial + bh * nsplit * (D + 2);
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, rec[s * (D + 2)]);
+    float L = 0.f, A = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+      const float m = rec[s * (D + 2)];
+      if (m == -INFINITY) continue;
+      const float f = soft_exp<T>(m - M);
+      L = fmaf(rec[s * (D + 2) + 1], f, L);
+      A = fmaf(rec[s * (D + 2) + 2 + d], f, A);
+    }
+    out[bh * D + d] = from_f32<T>(A / L);
   }
-  out[bh * D + threadIdx.x] = from_f32<T>(A / L);
-  if (threadIdx.x == 0 && bh % Hq == 0) {
-    const int b = (int)(bh / Hq);
-    const int t1 = n_seen[b] + 1;
-    n_seen[b] = t1;
-    n_scored[b] = t1 > rho ? t1 - rho : 0;
+
+  // ---- cache update: evicted row -> compact slot dst, then token t -> ring slot ------------------------------
+  T* kw = static_cast<T*>(C.k_win) + (head * window + slot) * D;
+  T* vw = static_cast<T*>(C.v_win) + (head * window + slot) * D;
+  constexpr int pieces = D * (int)sizeof(T) / 16;
+  if (dst >= 0) {
+    T* kr = static_cast<T*>(C.k_ret) + (head * budget + dst) * D;
+    T* vr = static_cast<T*>(C.v_ret) + (head * budget + dst) * D;
+    if (tid < pieces) reinterpret_cast<u32x4*>(kr)[tid] = reinterpret_cast<const u32x4*>(kw)[tid];
+    else if (tid < 2 * pieces) reinterpret_cast<u32x4*>(vr)[tid - pieces] = reinterpret_cast<const u32x4*>(vw)[tid - pieces];
+    if (tid == 0) {
+      const int e_pos = t - window;
+      C.ret_score[head * budget + dst] = select_key(z_e, e_pos, P.sink);
+      C.ret_pos[head * budget + dst] = e_pos;
+      if (dst == cnt_old) C.ret_count[head] = cnt_old + 1;
+    }
   }
+  __syncthreads();  // the old ring row has been read
+  if (tid < pieces) reinterpret_cast<u32x4*>(kw)[tid] = reinterpret_cast<const u32x4*>(k_new + head * D)[tid];
+  else if (tid < 2 * pieces) reinterpret_cast<u32x4*>(vw)[tid - pieces] = reinterpret_cast<const u32x4*>(v_new + head * D)[tid - pieces];
+  if (tid == 0) {
+    if (t - rho >= 0) C.win_score[head * window + ((t - rho) % window)] = z_new;
+    if (h == 0) {
+      C.n_seen[b] = t + 1;
+      C.n_scored[b] = t + 1 > rho ? t + 1 - rho : 0;
+    }
+  }
+}
+
+size_t partial_floats(const ltea_cfg& cfg, int n_seqs, int nsplit) {
+  return (size_t)n_seqs * cfg.Hq * nsplit * (cfg.D + 2);
+}
+
+int lds_row_floats(const ltea_cfg& cfg, const ltea_cnn& cnn) {
+  int row_floats = 2 * cfg.D;
+  for (int l = 0; l < cnn.n_layers; ++l) row_floats = cnn.c_out[l] > row_floats ? cnn.c_out[l] : row_floats;
+  return row_floats;
 }
 
 template <typename T, int D>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v, void* out,
                const ltea_cache& c, int n_seqs, void* workspace, hipStream_t stream) {
-  const int rho = cnn_rho(&cnn);
   CnnDev cd;
   cd.n_layers = cnn.n_layers;
-  int row_floats = 2 * cfg.D;
   for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) {
     const bool on = l < cnn.n_layers;
     cd.kernel[l] = on ? cnn.kernel[l] : 1;
@@ -364,30 +620,34 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const vo
     cd.c_out[l] = on ? cnn.c_out[l] : 0;
     cd.w[l] = on ? cnn.w[l] : nullptr;
     cd.bias[l] = on ? cnn.bias[l] : nullptr;
-    if (on && cnn.c_out[l] > row_floats) row_floats = cnn.c_out[l];
   }
   cd.w_out = cnn.w_out;
   cd.b_out = cnn.b_out;
-  const size_t lds_bytes = (size_t)2 * (2 * rho + 1) * row_floats * sizeof(float);
+  CacheDev C{c.k_win, c.v_win, c.win_score, c.k_ret, c.v_ret, c.ret_score, c.ret_pos, c.ret_count, c.n_seen, c.n_scored};
+  StepParams P;
+  P.B = n_seqs; P.Hq = cfg.Hq; P.Hkv = cfg.Hkv; P.D = cfg.D; P.window = cfg.window; P.budget = cfg.budget;
+  P.sink = cfg.sink;
+  P.rho = cnn_rho(&cnn);
+  P.nsplit = decode_num_splits(cfg, n_seqs);
+  P.lds_row_floats = lds_row_floats(cfg, cnn);
+  P.tau = cfg.tau_logit;
+  P.scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   const unsigned heads = (unsigned)n_seqs * (unsigned)cfg.Hkv;
-  hipLaunchKernelGGL(decode_update_kernel<T>, dim3(heads), dim3(kUpdThreads), lds_bytes, stream, cd, rho, row_floats,
-                     static_cast<const T*>(k), static_cast<const T*>(v), cfg.Hkv, cfg.D, cfg.window, cfg.budget,
-                     cfg.sink, cfg.tau_logit, static_cast<T*>(c.k_win), static_cast<T*>(c.v_win), c.win_score,
-                     static_cast<T*>(c.k_ret), static_cast<T*>(c.v_ret), c.ret_score, c.ret_pos, c.ret_count,
-                     c.n_seen);
+  const int ks0 = cnn.kernel[0];
+  P.score_mfma = (cfg.dtype == LTEA_BF16 && cnn.n_layers == 1 && cnn.c_out[0] <= 32 && (ks0 == 3 || ks0 == 5 || ks0 == 7)) ? ks0 : 0;
+  P.n_score_blocks = P.score_mfma ? cfg.Hkv * ((n_seqs + 63) / 64) : (int)heads;
+  const size_t lds_bytes = P.score_mfma ? 0 : (size_t)2 * (2 * P.rho + 1) * P.lds_row_floats * sizeof(float);
+  float* partial = static_cast<float*>(workspace);
+  float* ws_logit = partial + partial_floats(cfg, n_seqs, P.nsplit);
+  int32_t* ws_t = reinterpret_cast<int32_t*>(ws_logit + heads);
+  const unsigned grid = (unsigned)P.n_score_blocks + heads * (unsigned)P.nsplit;
+  hipLaunchKernelGGL((decode_main_kernel<T, D>), dim3(grid), dim3(kThreads), lds_bytes, stream, cd, C, P,
+                     static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit,
+                     ws_t);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int nsplit = decode_num_splits(cfg, n_seqs);
-  const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
-  float* partial = static_cast<float*>(workspace);
-  hipLaunchKernelGGL((decode_attention_kernel<T, D>), dim3(heads, (unsigned)nsplit), dim3(kAttnThreads), 0, stream,
-                     static_cast<const T*>(q), static_cast<const T*>(c.k_win), static_cast<const T*>(c.v_win),
-                     static_cast<const T*>(c.k_ret), static_cast<const T*>(c.v_ret), c.ret_count, c.n_seen, cfg.Hq,
-                     cfg.Hkv, cfg.window, cfg.budget, scale, nsplit, partial);
-  e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((decode_combine_kernel<T, D>), dim3((unsigned)n_seqs * (unsigned)cfg.Hq), dim3(D), 0, stream,
-                     partial, nsplit, cfg.Hq, rho, static_cast<T*>(out), c.n_seen, c.n_scored);
+  hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(heads), dim3(kThreads), 0, stream, C, P,
+                     static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit, ws_t, static_cast<T*>(out));
   return hipGetLastError();
 }
 
@@ -396,7 +656,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const vo
 int decode_num_splits(const ltea_cfg& cfg, int n_seqs) {
   const long heads = (long)n_seqs * cfg.Hkv;
   const int rows = cfg.window + cfg.budget;
-  int by_fill = (int)((2048 + heads - 1) / (heads > 0 ? heads : 1));  // aim for >= 2048 workgroups
+  int by_fill = (int)((4096 + heads - 1) / (heads > 0 ? heads : 1));  // aim for >= 4096 workgroups
   int by_rows = (rows + 127) / 128;                                   // at least 128 rows per split
   int n = by_fill < by_rows ? by_fill : by_rows;
   if (n < 1) n = 1;
@@ -405,13 +665,8 @@ int decode_num_splits(const ltea_cfg& cfg, int n_seqs) {
 }
 
 size_t decode_workspace(const ltea_cfg& cfg, int n_seqs) {
-  return (size_t)n_seqs * cfg.Hq * decode_num_splits(cfg, n_seqs) * (cfg.D + 2) * sizeof(float);
-}
-
-size_t decode_update_lds_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn) {
-  int row_floats = 2 * cfg.D;
-  for (int l = 0; l < cnn.n_layers; ++l) row_floats = cnn.c_out[l] > row_floats ? cnn.c_out[l] : row_floats;
-  return (size_t)2 * (2 * cnn_rho(&cnn) + 1) * row_floats * sizeof(float);
+  return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
+         (size_t)n_seqs * sizeof(int32_t);
 }
 
 hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v,
