@@ -470,8 +470,8 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
         vp = is_moved ? v_evicted : vp;
         kp = (is_new || !live[u]) ? kn : kp;
         vp = (is_new || !live[u]) ? vn : vp;
-        kraw[u] = *reinterpret_cast<const u32x4*>(kp + sub * EPL);
-        vraw[u] = *reinterpret_cast<const u32x4*>(vp + sub * EPL);
+        kraw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + sub * EPL));
+        vraw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + sub * EPL));
       }
       float m_new = m_run;
 #pragma unroll
