@@ -3,22 +3,25 @@
 // Flash-attention-style tiling, two stages per query tile as in the paper's description: stage 1 walks
 // 64-key tiles of the original K/V inside the tile's window range, stage 2 walks 64-slot tiles of the
 // compact retained segment with a per-row mask "position <= i - window" (so entries still inside a
-// query's window are never counted twice).  Tiles wholly outside a wave's window range are skipped and
-// only tiles that straddle a window edge, the causal diagonal or the sequence end pay for masking.
+// query's window are never counted twice).  Per wave, tiles wholly outside its rows' reach are skipped and
+// only tiles that straddle a window edge, the causal diagonal, the sequence end or the visibility frontier of
+// the retained entries pay for masking.
 //
-// Work split: one workgroup = 128 consecutive queries of one (sequence, query head); 4 waves x 32 queries.
+// Work split: one workgroup = 128*QB consecutive queries of one (sequence, query head); 4 waves, each owning
+// QB blocks of 32 queries (QB = 2 for D = 64, 1 for D = 128: what fits the register file at 2 waves/SIMD).
 // MFMA shapes (v_mfma_f32_32x32x16_bf16, wave64):
 //   S^T[key, query] = K[key, :] . Q[query, :]   A = K tile rows from LDS, B = Q fragment held in registers
 //   O^T[d, query]  += V^T[d, key] . P^T[key, query]   A = V^T tile from LDS, B = P^T straight from S^T's
 //                                                     accumulator registers (no shuffle, no LDS round trip)
 // In the 32x32 accumulator layout a lane owns one query column, so the online-softmax statistics are
-// per-lane scalars (the two lanes sharing a query exchange one value per tile).  The contraction index of
+// per-lane scalars (the two lanes sharing a query exchange one value per 32 keys).  The contraction index of
 // the second product is the key index; the rows of the K tile are fed to the first MFMA in a permuted
 // order so that each lane's eight P values per MFMA are eight consecutive keys, which is what lets the
 // V^T operand be read as one 16-byte LDS load.  V is transposed on its way into LDS (4 keys x 8 columns
-// per thread, XOR-swizzled so that both the transposing stores and the operand loads spread over all banks).
-// The running maximum is only raised when a tile exceeds it by more than 2^8 (the result is independent
-// of the stabiliser), which keeps the accumulator rescale off the common path.
+// per thread, XOR-swizzled so that both the transposing stores and the operand loads spread over the 64 banks).
+// K/V tiles are double-buffered in LDS and prefetched two tiles ahead through registers, one barrier per tile.
+// The running maximum is only raised when a block of scores exceeds it by more than 2^8 (the result does not
+// depend on the stabiliser), which keeps the accumulator rescale off the common path.
 #include <type_traits>
 
 #include "ltea_common.h"
@@ -27,7 +30,6 @@
 namespace ltea {
 namespace {
 
-constexpr int BM = 128;  // queries per workgroup
 constexpr int BN = 64;   // keys per tile
 constexpr int kThreads = 256;
 constexpr float kLazyMax = 8.0f;  // log2 units
@@ -45,8 +47,19 @@ __device__ __forceinline__ float pair_sum(float x) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+__device__ __forceinline__ int wave_min_i(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y < x ? y : x; }
+  return x;
+}
+__device__ __forceinline__ int wave_max_i(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y > x ? y : x; }
+  return x;
+}
 
-template <int D> struct Geo {
+template <int D, int QB> struct Geo {
+  static constexpr int BM = 128 * QB;           // queries per workgroup
   static constexpr int KS = D + 8;              // K tile row stride (elements); 16-byte pad
   static constexpr int VS = BN + 8;             // V^T tile row stride (elements)
   static constexpr int PPR = D / 8;             // 16-byte pieces per K row
@@ -54,15 +67,16 @@ template <int D> struct Geo {
   static constexpr int KPASS = BN / RPP;        // passes over the K tile
   static constexpr int CPT = D / 16;            // V columns per thread (4 keys x CPT columns)
   static constexpr int OS = D + 8;              // epilogue staging row stride (elements)
+  static constexpr int kBuf = BN * KS + D * VS; // elements per LDS tile buffer (K tile then V^T tile)
 };
 
 template <int D> struct TileRegs {
-  u32x4 k[Geo<D>::KPASS];
-  uint32_t v[4][Geo<D>::CPT / 2];
+  u32x4 k[BN / (kThreads / (D / 8))];
+  uint32_t v[4][D / 32];
   int pos;
 };
 
-template <int D>
+template <int D, int QB>
 __global__ void __launch_bounds__(kThreads, 2)
 attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, const bf16_t* __restrict__ k,
                       const bf16_t* __restrict__ v, int64_t kv_st, int64_t kv_sh, const int32_t* __restrict__ cu,
@@ -70,15 +84,13 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
                       float scale_log2e, const bf16_t* __restrict__ k_ret, const bf16_t* __restrict__ v_ret,
                       const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count,
                       bf16_t* __restrict__ out) {
-  using G = Geo<D>;
+  using G = Geo<D, QB>;
   using TR = TileRegs<D>;
-  constexpr int KS = G::KS, VS = G::VS;
-  constexpr int kLdsK = BN * KS, kLdsV = D * VS;
-  static_assert(kLdsK + kLdsV >= BM * G::OS, "epilogue staging must fit in the tile buffers");
-  __shared__ __align__(16) bf16_t lds[kLdsK + kLdsV];
-  __shared__ int pos_lds[BN];
-  bf16_t* k_lds = lds;
-  bf16_t* vt_lds = lds + kLdsK;
+  constexpr int BM = G::BM, KS = G::KS, VS = G::VS, kBuf = G::kBuf;
+  static_assert(2 * kBuf >= BM * G::OS, "epilogue staging must fit in the tile buffers");
+  __shared__ __align__(16) bf16_t lds[2 * kBuf];
+  __shared__ int pos_lds[2][BN];
+  __shared__ int pos_rng[2][2];   // min / max position of the tile's valid retained entries
 
   // ---- which (query head, sequence, query tile) is this workgroup? ------------------------------------
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work items so
@@ -104,16 +116,18 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, hb = lane >> 5;
-  const int r0 = i0 + 32 * wv;          // first query row of this wave
-  const int qi = r0 + ql;               // this lane's query row (may be >= n in the last tile)
+  const int r0 = i0 + 32 * QB * wv;         // first query row of this wave
+  const int r_hi = r0 + 32 * QB - 1;        // last query row of this wave
 
-  // ---- Q fragment (B operand of S^T): lane holds Q[qi][16*ks + 8*hb .. +7] ---------------------------
-  bf16x8 qreg[D / 16];
-  {
+  // ---- Q fragments (B operand of S^T): lane holds Q[row][16*ks + 8*hb .. +7] for its QB rows ------------
+  bf16x8 qreg[QB][D / 16];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const int qi = r0 + 32 * qb + ql;
     const int qc = qi < n ? qi : n - 1;
     const bf16_t* qrow = q + (lo + qc) * q_st + (int64_t)hq * q_sh;
 #pragma unroll
-    for (int ks = 0; ks < D / 16; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * hb);
+    for (int ks = 0; ks < D / 16; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * hb);
   }
 
   // ---- tile schedule ------------------------------------------------------------------------------------
@@ -123,75 +137,63 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int n_win_tiles = (i_last - jt0) / BN + 1;
   const int cnt = (budget > 0 && i_last - window >= 0) ? ret_count[head] : 0;
   const int n_ret_tiles = (cnt + BN - 1) / BN;
+  const int n_tiles = n_win_tiles + n_ret_tiles;
 
-  // ---- per-thread load addressing: 32-bit byte offsets from a uniform base -----------------------------
-  const char* kbase = reinterpret_cast<const char*>(k + lo * kv_st + (int64_t)h * kv_sh);
-  const char* vbase = reinterpret_cast<const char*>(v + lo * kv_st + (int64_t)h * kv_sh);
-  const char* krbase = reinterpret_cast<const char*>(k_ret + head * budget * D);
-  const char* vrbase = reinterpret_cast<const char*>(v_ret + head * budget * D);
-  const int32_t* prbase = ret_pos + head * budget;
+  // ---- per-thread load addressing: buffer loads with 32-bit byte offsets; rows past the end of the sequence
+  // (or past ret_count in the compact segment) are out of the descriptor's range and read as zeros ----------
   const uint32_t row_bytes = (uint32_t)kv_st * 2u;
+  const uint32_t win_bytes = (uint32_t)(n - 1) * row_bytes + (uint32_t)(D * 2);
+  const uint32_t ret_bytes = (uint32_t)cnt * (uint32_t)(D * 2);
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k + lo * kv_st + (int64_t)h * kv_sh), 0, win_bytes, 0x00020000);
+  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v + lo * kv_st + (int64_t)h * kv_sh), 0, win_bytes, 0x00020000);
+  const auto rs_kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k_ret + head * budget * D), 0, ret_bytes, 0x00020000);
+  const auto rs_vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v_ret + head * budget * D), 0, ret_bytes, 0x00020000);
+  const int32_t* prbase = ret_pos + head * budget;
   const int k_piece = tid % G::PPR, k_row = tid / G::PPR;
   const int v_g = tid % 16, v_kg = tid / 16;   // 4 keys x CPT columns per thread; columns fastest across lanes
   const uint32_t k_col = (uint32_t)k_piece * 16u, v_col = (uint32_t)(v_g * G::CPT) * 2u;
-  const uint32_t k_lim = (uint32_t)(n - 1) * row_bytes + k_col, v_lim = (uint32_t)(n - 1) * row_bytes + v_col;
   const uint32_t k_loc = (uint32_t)k_row * row_bytes + k_col;          // first pass; later passes add RPP rows
   const uint32_t v_loc = (uint32_t)(4 * v_kg) * row_bytes + v_col;     // key 4*v_kg; next keys add one row each
+  const uint32_t kr_loc = (uint32_t)k_row * (uint32_t)(D * 2) + k_col;
+  const uint32_t vr_loc = (uint32_t)(4 * v_kg) * (uint32_t)(D * 2) + v_col;
 
-  auto load_win = [&](int t, TR& R) {
-    const uint32_t tb = (uint32_t)(jt0 + t * BN) * row_bytes;
+  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t kb0, uint32_t vb0, uint32_t rb, TR& R) {
 #pragma unroll
-    for (int p = 0; p < G::KPASS; ++p) {
-      uint32_t off = tb + k_loc + (uint32_t)(p * G::RPP) * row_bytes;
-      off = off < k_lim ? off : k_lim;   // rows past the sequence end re-read its last row (masked later)
-      R.k[p] = *reinterpret_cast<const u32x4*>(kbase + off);
-    }
+    for (int p = 0; p < G::KPASS; ++p)
+      R.k[p] = __builtin_amdgcn_raw_buffer_load_b128(rk, kb0 + (uint32_t)(p * G::RPP) * rb, 0, 0);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      uint32_t off = tb + v_loc + (uint32_t)i * row_bytes;
-      off = off < v_lim ? off : v_lim;
       if constexpr (G::CPT == 8) {
-        const u32x4 x = *reinterpret_cast<const u32x4*>(vbase + off);
+        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rv, vb0 + (uint32_t)i * rb, 0, 0);
         R.v[i][0] = x[0]; R.v[i][1] = x[1]; R.v[i][2] = x[2]; R.v[i][3] = x[3];
       } else {
-        const u32x2 x = *reinterpret_cast<const u32x2*>(vbase + off);
+        const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rv, vb0 + (uint32_t)i * rb, 0, 0);
         R.v[i][0] = x[0]; R.v[i][1] = x[1];
       }
     }
   };
-  auto load_ret = [&](int t, TR& R) {
-    const int base = t * BN;
-#pragma unroll
-    for (int p = 0; p < G::KPASS; ++p) {
-      int idx = base + p * G::RPP + k_row;
-      idx = idx < cnt - 1 ? idx : cnt - 1;
-      R.k[p] = *reinterpret_cast<const u32x4*>(krbase + (uint32_t)idx * (uint32_t)(D * 2) + k_col);
+  auto load_tile = [&](int t, TR& R) {
+    if (t < n_win_tiles) {
+      const uint32_t tb = (uint32_t)(jt0 + t * BN) * row_bytes;
+      load_rows(rs_k, rs_v, tb + k_loc, tb + v_loc, row_bytes, R);
+    } else {
+      const int base = (t - n_win_tiles) * BN;
+      const uint32_t tb = (uint32_t)base * (uint32_t)(D * 2);
+      load_rows(rs_kr, rs_vr, tb + kr_loc, tb + vr_loc, (uint32_t)(D * 2), R);
+      R.pos = 0x7FFFFFFF;
+      if (tid < BN && base + tid < cnt) R.pos = prbase[base + tid];
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      int idx = base + 4 * v_kg + i;
-      idx = idx < cnt - 1 ? idx : cnt - 1;
-      const char* src = vrbase + (uint32_t)idx * (uint32_t)(D * 2) + v_col;
-      if constexpr (G::CPT == 8) {
-        const u32x4 x = *reinterpret_cast<const u32x4*>(src);
-        R.v[i][0] = x[0]; R.v[i][1] = x[1]; R.v[i][2] = x[2]; R.v[i][3] = x[3];
-      } else {
-        const u32x2 x = *reinterpret_cast<const u32x2*>(src);
-        R.v[i][0] = x[0]; R.v[i][1] = x[1];
-      }
-    }
-    R.pos = 0x7FFFFFFF;
-    if (tid < BN && base + tid < cnt) R.pos = prbase[base + tid];
   };
 
   // LDS store addresses. V^T rows are d, columns keys; the 16-byte column chunk index is XOR-ed with
   // 2*((d >> 4) & 3) on both the store and the load side.
-  bf16_t* k_st_ptr = k_lds + k_row * KS + k_piece * 8;
   const int v_d0 = v_g * G::CPT;
-  bf16_t* v_st_ptr = vt_lds + v_d0 * VS + ((4 * v_kg) ^ (16 * ((v_d0 >> 4) & 3)));
-  auto store_tile = [&](const TR& R, bool with_pos) {
+  const int k_st_off = k_row * KS + k_piece * 8;
+  const int v_st_off = BN * KS + v_d0 * VS + ((4 * v_kg) ^ (16 * ((v_d0 >> 4) & 3)));
+  auto store_tile = [&](int t, const TR& R) {
+    bf16_t* buf = lds + (t & 1) * kBuf;
 #pragma unroll
-    for (int p = 0; p < G::KPASS; ++p) *reinterpret_cast<u32x4*>(k_st_ptr + p * G::RPP * KS) = R.k[p];
+    for (int p = 0; p < G::KPASS; ++p) *reinterpret_cast<u32x4*>(buf + k_st_off + p * G::RPP * KS) = R.k[p];
 #pragma unroll
     for (int c2 = 0; c2 < G::CPT / 2; ++c2) {
       const uint32_t a0 = R.v[0][c2], a1 = R.v[1][c2], a2 = R.v[2][c2], a3 = R.v[3][c2];
@@ -200,137 +202,170 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
       even[1] = (a2 & 0xFFFFu) | (a3 << 16);
       odd[0] = (a0 >> 16) | (a1 & 0xFFFF0000u);
       odd[1] = (a2 >> 16) | (a3 & 0xFFFF0000u);
-      *reinterpret_cast<u32x2*>(v_st_ptr + (2 * c2) * VS) = even;
-      *reinterpret_cast<u32x2*>(v_st_ptr + (2 * c2 + 1) * VS) = odd;
+      *reinterpret_cast<u32x2*>(buf + v_st_off + (2 * c2) * VS) = even;
+      *reinterpret_cast<u32x2*>(buf + v_st_off + (2 * c2 + 1) * VS) = odd;
     }
-    if (with_pos && tid < BN) pos_lds[tid] = R.pos;
+    if (t >= n_win_tiles && wv == 0) {   // wave 0 holds the tile's 64 positions (INT_MAX past ret_count)
+      pos_lds[t & 1][lane] = R.pos;
+      const int mn = wave_min_i(R.pos);
+      const int mx = wave_max_i(R.pos == 0x7FFFFFFF ? (int)0x80000000 : R.pos);
+      if (lane == 0) { pos_rng[t & 1][0] = mn; pos_rng[t & 1][1] = mx; }
+    }
   };
 
-  // operand load addresses
-  const bf16_t* a_k_ptr = k_lds + key_row_of_mfma_row(ql) * KS + 8 * hb;      // + 32*kb*KS + 16*ks
+  // operand load offsets inside a tile buffer
+  const int a_k_off = key_row_of_mfma_row(ql) * KS + 8 * hb;                 // + 32*kb*KS + 16*ks
   const int s4 = ql >> 4;
-  const bf16_t* a_v_ptr0 = vt_lds + ql * VS + 8 * hb + 16 * (0 ^ s4);         // kk = 0
-  const bf16_t* a_v_ptr1 = vt_lds + ql * VS + 8 * hb + 16 * (1 ^ s4);         // kk = 1
+  const int a_v_off0 = BN * KS + ql * VS + 8 * hb + 16 * (0 ^ s4);            // kk = 0
+  const int a_v_off1 = BN * KS + ql * VS + 8 * hb + 16 * (1 ^ s4);            // kk = 1
 
   // ---- online softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
-  float m_run = -INFINITY, l_part = 0.f;
-  f32x16 o[D / 32];
+  float m_run[QB], l_part[QB];
+  f32x16 o[QB][D / 32];
 #pragma unroll
-  for (int db = 0; db < D / 32; ++db)
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_part[qb] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+  }
 
   // mode: 0 = plain, 1 = window-edge mask (keys jt..), 2 = retained mask (positions in pos_lds).
   // The 64-key tile is consumed as two 32-key halves, each with its own softmax update, so that only one
-  // 32x32 score block is live at a time.
-  auto compute = [&](auto mode_tag, int jt) {
-    constexpr int MODE = decltype(mode_tag)::value;
+  // 32x32 score block per query block is live at a time.
+  auto compute = [&](const int mode, const bf16_t* buf, const int* pos, int jt) {
+    const bf16_t* a_k = buf + a_k_off;
+    const bf16_t* a_v0 = buf + a_v_off0;
+    const bf16_t* a_v1 = buf + a_v_off1;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      f32x16 sacc;
+      f32x16 sacc[QB];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_k_ptr + 32 * kb * KS + 16 * ks);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[ks], sacc, 0, 0, 0);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_k + 32 * kb * KS + 16 * ks);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb)
+          sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sacc[qb], 0, 0, 0);
       }
-      // register r is key (local) 32*kb + 16*(r/8) + 8*hb + r%8
-      if constexpr (MODE == 1) {
-        const int jl = qi - jt - 8 * hb;            // key_local_without_hb <= jl  <=> j <= qi
-        const int jw = jl - window;                 // key_local_without_hb >  jw  <=> j >  qi - window
-        const int jn = n - jt - 8 * hb;             // key_local_without_hb <  jn  <=> j <  n
+      bf16x8 pb[QB][2];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const int qi = r0 + 32 * qb + ql;
+        // register r is key (local) 32*kb + 16*(r/8) + 8*hb + r%8
+        if (mode == 1) {
+          // valid local keys c (without the 8*hb term) form the range [c_lo, c_hi]: causal, window and sequence end
+          const int shift = jt + 8 * hb;
+          int c_hi = qi - shift;                                   // j <= qi
+          const int c_end = n - 1 - shift;                         // j <= n-1
+          c_hi = c_hi < c_end ? c_hi : c_end;
+          int c_lo = qi - window + 1 - shift;                      // j >= qi - window + 1
+          const unsigned span = c_hi >= c_lo ? (unsigned)(c_hi - c_lo) : 0u;
+          if (c_hi < c_lo) c_lo = 0x40000000;                      // nothing valid
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int c = 32 * kb + 16 * (r / 8) + (r % 8);
+            sacc[qb][r] = ((unsigned)(c - c_lo) <= span) ? sacc[qb][r] : -INFINITY;
+          }
+        } else if (mode == 2) {
+          const int lim = qi - window;
+#pragma unroll
+          for (int r8 = 0; r8 < 2; ++r8) {
+            const int* pp = pos + 32 * kb + 16 * r8 + 8 * hb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sacc[qb][8 * r8 + e] = (pp[e] <= lim) ? sacc[qb][8 * r8 + e] : -INFINITY;
+          }
+        }
+        // ---- online softmax with a lazily raised maximum ----------------------------------------------------
+        float mx = fmaxf(sacc[qb][0], sacc[qb][1]);
+#pragma unroll
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sacc[qb][r]), sacc[qb][r + 1]);
+        mx = pair_max(mx);
+        const float mcand = mx * scale_log2e;
+        const bool grow = mcand > m_run[qb] + kLazyMax;   // true on the first visible keys (m_run = -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+          const float alpha = grow ? __builtin_amdgcn_exp2f(m_run[qb] - mcand) : 1.0f;
+          m_run[qb] = grow ? mcand : m_run[qb];
+          l_part[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+        }
+        const float m_use = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
+        float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int c = 32 * kb + 16 * (r / 8) + (r % 8);
-          const bool ok = (c <= jl) && (c > jw) && (c < jn);
-          sacc[r] = ok ? sacc[r] : -INFINITY;
+          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][r], scale_log2e, -m_use));
+          if (r & 1) psum1 += p; else psum0 += p;
+          pb[qb][r / 8][r % 8] = static_cast<bf16_t>(p);
         }
-      } else if constexpr (MODE == 2) {
-        const int lim = qi - window;
-#pragma unroll
-        for (int r8 = 0; r8 < 2; ++r8) {
-          const int* pp = &pos_lds[32 * kb + 16 * r8 + 8 * hb];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) sacc[8 * r8 + e] = (pp[e] <= lim) ? sacc[8 * r8 + e] : -INFINITY;  // INT_MAX past ret_count
-        }
+        l_part[qb] += psum0 + psum1;
       }
-      // ---- online softmax with a lazily raised maximum ----------------------------------------------------
-      float mx = fmaxf(sacc[0], sacc[1]);
-#pragma unroll
-      for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sacc[r]), sacc[r + 1]);
-      mx = pair_max(mx);
-      const float mcand = mx * scale_log2e;
-      const bool grow = mcand > m_run + kLazyMax;   // true on the first visible keys (m_run = -inf)
-      if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-        const float alpha = grow ? __builtin_amdgcn_exp2f(m_run - mcand) : 1.0f;
-        m_run = grow ? mcand : m_run;
-        l_part *= alpha;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-      }
-      const float m_use = (m_run == -INFINITY) ? 0.f : m_run;
-      float psum0 = 0.f, psum1 = 0.f;
-      bf16x8 pb[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], scale_log2e, -m_use));
-        if (r & 1) psum1 += p; else psum0 += p;
-        pb[r / 8][r % 8] = static_cast<bf16_t>(p);
-      }
-      l_part += psum0 + psum1;
       // ---- O^T += V^T P^T -----------------------------------------------------------------------------------
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
         const int col = 32 * (kb ^ (db & 1));
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(a_v_ptr0 + 32 * db * VS + col);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[0], o[db], 0, 0, 0);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(a_v_ptr1 + 32 * db * VS + col);
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pb[1], o[db], 0, 0, 0);
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(a_v0 + 32 * db * VS + col);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(a_v1 + 32 * db * VS + col);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[qb][0], o[qb][db], 0, 0, 0);
+          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pb[qb][1], o[qb][db], 0, 0, 0);
+        }
       }
     }
   };
 
+  // ---- software pipeline: tile t is computed from LDS buffer t&1 while tile t+1 is being stored into the other
+  // buffer and tile t+2 is in flight from global memory --------------------------------------------------------
   TR regs;
-  load_win(0, regs);
-  // ---- stage 1: window tiles ------------------------------------------------------------------------------
-  for (int t = 0; t < n_win_tiles; ++t) {
-    __syncthreads();  // everyone is done reading the previous tile
-    store_tile(regs, false);
-    __syncthreads();
-    if (t + 1 < n_win_tiles) load_win(t + 1, regs);      // in flight while this tile is computed
-    else if (n_ret_tiles > 0) load_ret(0, regs);
-    const int jt = jt0 + t * BN;
-    // keys this wave can use at all: [r0 - window + 1, r0 + 31]
-    if (jt > r0 + 31 || jt + BN - 1 < r0 - window + 1) continue;
-    const bool plain = (jt + BN - 1 <= r0) && (jt >= r0 + 31 - window + 1);
-    if (plain) compute(std::integral_constant<int, 0>{}, jt);
-    else compute(std::integral_constant<int, 1>{}, jt);
-  }
-  // ---- stage 2: retained tiles ------------------------------------------------------------------------------
-  for (int t = 0; t < n_ret_tiles; ++t) {
-    __syncthreads();
-    store_tile(regs, true);
-    __syncthreads();
-    if (t + 1 < n_ret_tiles) load_ret(t + 1, regs);
-    compute(std::integral_constant<int, 2>{}, 0);
+  load_tile(0, regs);
+  store_tile(0, regs);
+  if (n_tiles > 1) load_tile(1, regs);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();   // tile t is in LDS; everyone is done with tile t-1 (whose buffer is overwritten next)
+    if (t + 1 < n_tiles) store_tile(t + 1, regs);
+    if (t + 2 < n_tiles) load_tile(t + 2, regs);
+    const bf16_t* buf = lds + (t & 1) * kBuf;
+    // classify the tile for this wave: -1 skip, 0 every (query, key) pair valid, 1 window-edge mask, 2 retained mask
+    int mode = -1, jt = 0;
+    if (r0 < n) {
+      if (t < n_win_tiles) {
+        jt = jt0 + t * BN;
+        // keys this wave can use at all: [r0 - window + 1, r_hi]
+        if (!(jt > r_hi || jt + BN - 1 < r0 - window + 1))
+          mode = ((jt + BN - 1 <= r0) && (jt >= r_hi - window + 1)) ? 0 : 1;
+      } else {
+        const int pmin = pos_rng[t & 1][0], pmax = pos_rng[t & 1][1];
+        if (pmin <= r_hi - window) {                     // some entry has left one of this wave's windows
+          const bool full = (t - n_win_tiles + 1) * BN <= cnt;
+          mode = (full && pmax <= r0 - window) ? 0 : 2;
+        }
+      }
+    }
+    mode = __builtin_amdgcn_readfirstlane(mode);
+    if (mode >= 0) compute(mode, buf, pos_lds[t & 1], jt);
   }
 
   // ---- epilogue: normalise, stage through LDS, store rows coalesced -------------------------------------------
-  const float l_tot = pair_sum(l_part);
-  const float inv = 1.0f / l_tot;
   __syncthreads();  // tile buffers are free
-  {
-    bf16_t* orow = lds + (32 * wv + ql) * G::OS + 4 * hb;
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    const float inv = 1.0f / pair_sum(l_part[qb]);
+    bf16_t* orow = lds + (32 * QB * wv + 32 * qb + ql) * G::OS + 4 * hb;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
         bf16x4 w4;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w4[e] = static_cast<bf16_t>(o[db][4 * g4 + e] * inv);
+        for (int e = 0; e < 4; ++e) w4[e] = static_cast<bf16_t>(o[qb][db][4 * g4 + e] * inv);
         *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g4) = w4;
       }
   }
@@ -348,14 +383,15 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   }
 }
 
-template <int D>
+template <int D, int QB>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
                int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream) {
+  constexpr int BM = Geo<D, QB>::BM;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   const int64_t tiles_upper = (sv.total_tokens + BM - 1) / BM + sv.n_seqs;
   const int64_t n_work = tiles_upper * cfg.Hq;
   const int64_t grid = (n_work + 7) / 8 * 8;
-  hipLaunchKernelGGL(attention_mfma_kernel<D>, dim3((unsigned)grid), dim3(kThreads), 0, stream,
+  hipLaunchKernelGGL((attention_mfma_kernel<D, QB>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
                      static_cast<const bf16_t*>(q), q_st, q_sh, static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), kv_st, kv_sh, sv.cu_seqlens, sv.n_seqs, (int)tiles_upper,
                      (int)n_work, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale * 1.4426950408889634f,
@@ -376,8 +412,8 @@ hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_s
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c,
                                  void* out, hipStream_t stream) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cfg.D == 64 ? run<64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream)
-                     : run<128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream);
+  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream)
+                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream);
 }
 
 }  // namespace ltea
