@@ -28,11 +28,13 @@ size_t score_generic_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t
 hipError_t launch_score_generic(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                                 int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                                 void* workspace, hipStream_t stream);
-// Single-layer bf16 path on MFMA (fused conv + Swish + output projection, no scratch).
+// Single-layer bf16 path on MFMA (fused conv + Swish + output projection); the workspace holds the weights
+// re-laid as tap-major panels.
 bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+size_t score_mfma_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
 hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
-                             hipStream_t stream);
+                             void* workspace, hipStream_t stream);
 
 // ---- (b) retention + cache fill -------------------------------------------------------------------
 hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k, const void* v,

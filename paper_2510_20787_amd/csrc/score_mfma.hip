@@ -7,10 +7,18 @@
 // layout one lane owns one token, so bias, Swish and the output projection are per-lane work on the 16
 // channel values it holds plus one exchange with the lane holding the other 16.
 //
-// One workgroup = 128 consecutive tokens of one (sequence, KV head).  The token tile with its halo of
-// half*dil rows on each side (zeros outside the sequence) is staged once in LDS, K and V rows coalesced in
-// 16-byte pieces; the weights of one tap at a time are staged in a double-buffered LDS panel while the
-// previous tap is being multiplied.
+// Two launches:
+//   score_weight_panels_kernel  re-lays the weights [Hkv][C][2D][k] once per call as tap-major panels
+//                               [Hkv][k][32][2D] (channels zero-padded to 32) in the workspace, so that the main
+//                               kernel can fetch a panel with coalesced 16-byte loads;
+//   score_mfma_kernel           one workgroup = 4 consecutive 128-token tiles of one (sequence, KV head).  Input
+//                               channels are processed in chunks of 128 (D = 64: keys and values together;
+//                               D = 128: keys, then values): all taps' weight panels of the chunk are staged in
+//                               LDS once and reused for the four tiles (one accumulator set per tile); each
+//                               tile's rows with their halo of half*dil rows (zeros outside the sequence) are
+//                               fetched into registers while the previous tile is being multiplied and then
+//                               stored to LDS in 16-byte pieces.  Rows are padded by 16 bytes, which makes the
+//                               16-lane groups of every ds_read_b128 hit 64 distinct banks.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 
@@ -20,124 +28,187 @@ namespace {
 constexpr int TM = 128;       // tokens per workgroup
 constexpr int kThreads = 256;
 constexpr int CP = 32;        // channels padded to one MFMA tile
+constexpr int CH = 128;       // input channels per chunk
+constexpr int XS = CH + 8;    // LDS row stride (elements) of the token tile and of the weight panel
+constexpr int NT = 4;         // consecutive token tiles per workgroup (weights staged once for all of them)
+constexpr int kMaxRho = 8;    // largest half receptive field the staging registers are sized for
+
+// panels[h][tap][c][m] = W[h][c][m][tap] for c < C, 0 for C <= c < 32
+__global__ void __launch_bounds__(256)
+score_weight_panels_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ panels, int C, int C2, int ks,
+                           int64_t total) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [Hkv][ks][32][C2]
+  if (idx >= total) return;
+  const int m = (int)(idx % C2);
+  int64_t r = idx / C2;
+  const int c = (int)(r % CP); r /= CP;
+  const int tap = (int)(r % ks);
+  const int64_t h = r / ks;
+  panels[idx] = c < C ? W[((h * C + c) * C2 + m) * ks + tap] : (uint16_t)0;
+}
 
 template <int D>
 __global__ void __launch_bounds__(kThreads)
 score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int64_t st, int64_t sh,
-                  const bf16_t* __restrict__ W, const float* __restrict__ bias, const bf16_t* __restrict__ w_out,
-                  const float* __restrict__ b_out, int C, int ks, int dil, const int32_t* __restrict__ cu,
-                  int n_seqs, int tiles_upper, int64_t total, float* __restrict__ logits) {
+                  const bf16_t* __restrict__ panels, const float* __restrict__ bias,
+                  const bf16_t* __restrict__ w_out, const float* __restrict__ b_out, int C, int ks, int dil,
+                  const int32_t* __restrict__ cu, int n_seqs, int groups_upper, int64_t total,
+                  float* __restrict__ logits) {
   constexpr int C2 = 2 * D;        // input channels
-  constexpr int XS = C2 + 8;       // LDS row stride (elements) of the token tile and of the weight panel
-  constexpr int PPR = C2 / 8;      // 16-byte pieces per token row
-  constexpr int RPP = kThreads / PPR;
-  constexpr int WPT = C2 * CP / kThreads;  // weight elements per thread per tap
+  constexpr int NCH = C2 / CH;     // chunks
+  constexpr int PPR = CH / 8;      // 16-byte pieces per chunk row (16)
+  constexpr int RPP = kThreads / PPR;   // token rows per staging pass (16)
+  constexpr int XREG = (TM + 2 * kMaxRho + RPP - 1) / RPP;   // staging passes (registers) per tile
   extern __shared__ __align__(16) unsigned char smem[];
   const int half = (ks - 1) / 2, rho = half * dil;
   const int rows = TM + 2 * rho;
   bf16_t* x_lds = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* w_lds = x_lds + (size_t)rows * XS;  // two panels of CP x XS
+  bf16_t* w_lds = x_lds + (size_t)rows * XS;  // ks panels of CP x XS (all taps of the current chunk)
 
   const int h = blockIdx.y;
-  int tile = blockIdx.x, s = 0, n = 0;
+  int grp = blockIdx.x, s = 0, n = 0;
   for (; s < n_seqs; ++s) {
     n = cu[s + 1] - cu[s];
-    const int nt = (n + TM - 1) / TM;
-    if (tile < nt) break;
-    tile -= nt;
+    const int ng = (n + NT * TM - 1) / (NT * TM);
+    if (grp < ng) break;
+    grp -= ng;
   }
   if (s == n_seqs) return;
   const int64_t lo = cu[s];
-  const int j0 = tile * TM;
+  const int g0 = grp * NT * TM;                      // first token of this workgroup's NT tiles
+  int n_tiles = (n - g0 + TM - 1) / TM;
+  n_tiles = n_tiles < NT ? n_tiles : NT;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
 
-  // ---- token tile with halo -> LDS -----------------------------------------------------------------------
-  {
-    const int piece = tid % PPR, r_in = tid / PPR;
-    const bool is_v = piece >= PPR / 2;
-    const bf16_t* base = (is_v ? v : k) + (int64_t)h * sh + (is_v ? piece - PPR / 2 : piece) * 8;
-    for (int r = r_in; r < rows; r += RPP) {
+  const bf16_t* ph = panels + (int64_t)h * ks * CP * C2;
+  // all taps' panels of one chunk -> LDS (coalesced 16-byte pieces)
+  auto stage_panels = [&](int chunk) {
+    const int n_pieces = ks * CP * (CH / 8);
+    constexpr int PB = 8;   // pieces in flight per thread: the whole staging costs a couple of memory round trips
+    for (int i0 = tid; i0 < n_pieces; i0 += kThreads * PB) {
+      u32x4 w[PB];
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const int i = i0 + u * kThreads;
+        const int pm = (i % (CH / 8)) * 8, row = i / (CH / 8);      // row = tap * CP + c
+        w[u] = u32x4{0u, 0u, 0u, 0u};
+        if (i < n_pieces) w[u] = *reinterpret_cast<const u32x4*>(ph + (int64_t)row * C2 + chunk * CH + pm);
+      }
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const int i = i0 + u * kThreads;
+        const int pm = (i % (CH / 8)) * 8, row = i / (CH / 8);
+        if (i < n_pieces) *reinterpret_cast<u32x4*>(w_lds + (size_t)row * XS + pm) = w[u];
+      }
+    }
+  };
+  // token tile of one chunk with halo: global -> registers (issued early), registers -> LDS (after the MFMAs)
+  const int piece = tid % PPR, r_in = tid / PPR;
+  u32x4 xreg[XREG];
+  auto load_tokens = [&](int chunk, int tile) {
+    const int m = chunk * CH + piece * 8;           // first input channel of this piece
+    const bool is_v = m >= D;
+    const bf16_t* base = (is_v ? v : k) + (int64_t)h * sh + (is_v ? m - D : m);
+    const int j0 = g0 + tile * TM;
+#pragma unroll
+    for (int i = 0; i < XREG; ++i) {
+      const int r = r_in + i * RPP;
       const int p = j0 - rho + r;
-      u32x4 x = {0u, 0u, 0u, 0u};
-      if (p >= 0 && p < n) x = *reinterpret_cast<const u32x4*>(base + (lo + p) * st);
-      *reinterpret_cast<u32x4*>(&x_lds[r * XS + piece * 8]) = x;
-    }
-  }
-  // ---- weight panel of one tap: w_panel[c][m] = W[h][c][m][tap] (zero rows for c >= C) -----------------------
-  const bf16_t* Wh = W + (int64_t)h * C * C2 * ks;
-  uint16_t wreg[WPT];
-  auto load_panel = [&](int tap) {
-#pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-      const int e = tid + kThreads * i;
-      const int c = e / C2, m = e - c * C2;
-      wreg[i] = c < C ? reinterpret_cast<const uint16_t*>(Wh)[((int64_t)c * C2 + m) * ks + tap] : (uint16_t)0;
+      xreg[i] = u32x4{0u, 0u, 0u, 0u};
+      if (r < rows && p >= 0 && p < n) xreg[i] = *reinterpret_cast<const u32x4*>(base + (lo + p) * st);
     }
   };
-  auto store_panel = [&](int buf) {
-    uint16_t* dst = reinterpret_cast<uint16_t*>(w_lds + (size_t)buf * CP * XS);
+  auto store_tokens = [&]() {
 #pragma unroll
-    for (int i = 0; i < WPT; ++i) {
-      const int e = tid + kThreads * i;
-      const int c = e / C2, m = e - c * C2;
-      dst[c * XS + m] = wreg[i];
+    for (int i = 0; i < XREG; ++i) {
+      const int r = r_in + i * RPP;
+      if (r < rows) *reinterpret_cast<u32x4*>(&x_lds[r * XS + piece * 8]) = xreg[i];
     }
   };
-  load_panel(0);
-  store_panel(0);
-  __syncthreads();
 
-  f32x16 acc;
+  f32x16 acc[NT];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  for (int tap = 0; tap < ks; ++tap) {
-    if (tap + 1 < ks) load_panel(tap + 1);
-    const bf16_t* a_row = w_lds + (size_t)(tap & 1) * CP * XS + ql * XS + 8 * hb;          // channel ql
-    const bf16_t* b_row = x_lds + (size_t)(32 * wv + ql + tap * dil) * XS + 8 * hb;        // token 32*wv+ql, shifted
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
-    for (int mc = 0; mc < C2 / 16; ++mc) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + 16 * mc);
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(b_row + 16 * mc);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+  load_tokens(0, 0);
+  for (int chunk = 0; chunk < NCH; ++chunk) {
+    __syncthreads();                 // previous chunk's panels and token tile are no longer read
+    stage_panels(chunk);
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (t < n_tiles) {             // uniform
+        if (t > 0) __syncthreads();  // previous tile's rows are no longer read
+        store_tokens();
+        __syncthreads();
+        // prefetch the next token tile (next tile of this chunk, or first tile of the next chunk)
+        if (t + 1 < n_tiles) load_tokens(chunk, t + 1);
+        else if (chunk + 1 < NCH) load_tokens(chunk + 1, 0);
+        for (int tap = 0; tap < ks; ++tap) {
+          const bf16_t* a_row = w_lds + (size_t)(tap * CP + ql) * XS + 8 * hb;                // channel ql
+          const bf16_t* b_row = x_lds + (size_t)(32 * wv + ql + tap * dil) * XS + 8 * hb;     // token, shifted
+#pragma unroll
+          for (int mc = 0; mc < CH / 16; ++mc) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_row + 16 * mc);
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(b_row + 16 * mc);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+          }
+        }
+      }
     }
-    if (tap + 1 < ks) store_panel((tap + 1) & 1);
-    __syncthreads();
   }
 
   // ---- epilogue: accumulator register r of lane half hb is channel 8*(r/4) + 4*hb + r%4 of token ql ----------
-  float z = 0.f;
+  float bs[16], wo[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int c = 8 * (r / 4) + 4 * hb + (r % 4);
-    if (c < C) {
-      const float y = acc[r] + bias[h * C + c];
-      const float a = y * __frcp_rn(1.0f + __expf(-y));
-      z = fmaf(a, to_f32(w_out[h * C + c]), z);
+    bs[r] = c < C ? bias[h * C + c] : 0.f;
+    wo[r] = c < C ? to_f32(w_out[h * C + c]) : 0.f;
+  }
+  const float bo = b_out[h];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if (t < n_tiles) {
+      float z = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float y = acc[t][r] + bs[r];
+        z = fmaf(y * __frcp_rn(1.0f + __expf(-y)), wo[r], z);
+      }
+      z += __shfl_xor(z, 32, kWave);
+      const int j = g0 + t * TM + 32 * wv + ql;
+      if (hb == 0 && j < n) logits[(int64_t)h * total + lo + j] = z + bo;
     }
   }
-  z += __shfl_xor(z, 32, kWave);
-  const int j = j0 + 32 * wv + ql;
-  if (hb == 0 && j < n) logits[(int64_t)h * total + lo + j] = z + b_out[h];
 }
 
-size_t lds_bytes(int D, int ks, int dil) {
+size_t lds_bytes(int ks, int dil) {
   const int rho = (ks - 1) / 2 * dil;
-  return ((size_t)(TM + 2 * rho) + 2 * CP) * (2 * D + 8) * sizeof(uint16_t);
+  return ((size_t)(TM + 2 * rho) + (size_t)ks * CP) * XS * sizeof(uint16_t);
 }
 
 template <int D>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
-               const SeqView& sv, float* logits, hipStream_t stream) {
-  const size_t lds = lds_bytes(D, cnn.kernel[0], cnn.dilation[0]);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+               const SeqView& sv, float* logits, void* workspace, hipStream_t stream) {
+  const int ks = cnn.kernel[0], C2 = 2 * D;
+  const int64_t panel_elems = (int64_t)cfg.Hkv * ks * CP * C2;
+  hipLaunchKernelGGL(score_weight_panels_kernel, dim3((unsigned)((panel_elems + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const uint16_t*>(cnn.w[0]), static_cast<uint16_t*>(workspace), cnn.c_out[0], C2, ks,
+                     panel_elems);
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int64_t tiles_upper = (sv.total_tokens + TM - 1) / TM + sv.n_seqs;
-  hipLaunchKernelGGL(score_mfma_kernel<D>, dim3((unsigned)tiles_upper, (unsigned)cfg.Hkv), dim3(kThreads), lds, stream,
+  const size_t lds = lds_bytes(ks, cnn.dilation[0]);
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  const int64_t groups_upper = (sv.total_tokens + NT * TM - 1) / (NT * TM) + sv.n_seqs;
+  hipLaunchKernelGGL(score_mfma_kernel<D>, dim3((unsigned)groups_upper, (unsigned)cfg.Hkv), dim3(kThreads), lds, stream,
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), st, sh,
-                     static_cast<const bf16_t*>(cnn.w[0]), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out),
-                     cnn.b_out, cnn.c_out[0], cnn.kernel[0], cnn.dilation[0], sv.cu_seqlens, sv.n_seqs,
-                     (int)tiles_upper, sv.total_tokens, logits);
+                     static_cast<const bf16_t*>(workspace), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out),
+                     cnn.b_out, cnn.c_out[0], ks, cnn.dilation[0], sv.cu_seqlens, sv.n_seqs, (int)groups_upper,
+                     sv.total_tokens, logits);
   return hipGetLastError();
 }
 
@@ -146,14 +217,19 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
 bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   if (cfg.dtype != LTEA_BF16 || cnn.n_layers != 1 || cnn.c_out[0] > CP) return false;
   if (cfg.D != 64 && cfg.D != 128) return false;
-  return lds_bytes(cfg.D, cnn.kernel[0], cnn.dilation[0]) <= 150 * 1024;
+  if ((cnn.kernel[0] - 1) / 2 * cnn.dilation[0] > kMaxRho) return false;
+  return lds_bytes(cnn.kernel[0], cnn.dilation[0]) <= 150 * 1024;
+}
+
+size_t score_mfma_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn) {
+  return (size_t)cfg.Hkv * cnn.kernel[0] * CP * 2 * cfg.D * sizeof(uint16_t);
 }
 
 hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
-                             int64_t sh, const SeqView& sv, float* logits, hipStream_t stream) {
+                             int64_t sh, const SeqView& sv, float* logits, void* workspace, hipStream_t stream) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cfg.D == 64 ? run<64>(cfg, cnn, k, v, st, sh, sv, logits, stream)
-                     : run<128>(cfg, cnn, k, v, st, sh, sv, logits, stream);
+  return cfg.D == 64 ? run<64>(cfg, cnn, k, v, st, sh, sv, logits, workspace, stream)
+                     : run<128>(cfg, cnn, k, v, st, sh, sv, logits, workspace, stream);
 }
 
 }  // namespace ltea
