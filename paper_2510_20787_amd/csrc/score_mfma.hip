@@ -31,7 +31,8 @@ constexpr int CP = 32;        // channels padded to one MFMA tile
 constexpr int CH = 128;       // input channels per chunk
 constexpr int XS = CH + 8;    // LDS row stride (elements) of the token tile and of the weight panel
 constexpr int NT = 4;         // consecutive token tiles per workgroup (weights staged once for all of them)
-constexpr int kMaxRho = 8;    // largest half receptive field the staging registers are sized for
+constexpr int kMaxRho = 4;    // largest half receptive field the token tile is sized for
+constexpr int kTileRows = TM + 2 * kMaxRho;   // LDS rows of the token tile
 
 // panels[h][tap][c][m] = W[h][c][m][tap] for c < C, 0 for C <= c < 32
 __global__ void __launch_bounds__(256)
@@ -61,9 +62,8 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   constexpr int XREG = (TM + 2 * kMaxRho + RPP - 1) / RPP;   // staging passes (registers) per tile
   extern __shared__ __align__(16) unsigned char smem[];
   const int half = (ks - 1) / 2, rho = half * dil;
-  const int rows = TM + 2 * rho;
   bf16_t* x_lds = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* w_lds = x_lds + (size_t)rows * XS;  // ks panels of CP x XS (all taps of the current chunk)
+  bf16_t* w_lds = x_lds + (size_t)kTileRows * XS;  // ks panels of CP x XS (all taps of the current chunk)
 
   const int h = blockIdx.y;
   int grp = blockIdx.x, s = 0, n = 0;
@@ -81,49 +81,57 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
 
   const bf16_t* ph = panels + (int64_t)h * ks * CP * C2;
-  // all taps' panels of one chunk -> LDS (coalesced 16-byte pieces)
+  // all taps' panels of one chunk -> LDS: 512 coalesced 16-byte pieces per tap, two per thread, no conditions
   auto stage_panels = [&](int chunk) {
-    const int n_pieces = ks * CP * (CH / 8);
-    constexpr int PB = 8;   // pieces in flight per thread: the whole staging costs a couple of memory round trips
-    for (int i0 = tid; i0 < n_pieces; i0 += kThreads * PB) {
-      u32x4 w[PB];
+    const int pm = (tid % (CH / 8)) * 8, c0 = tid / (CH / 8);           // channels c0 and c0 + 16
+    const bf16_t* src = ph + (int64_t)c0 * C2 + chunk * CH + pm;
+    bf16_t* dst = w_lds + (size_t)c0 * XS + pm;
+    for (int tap0 = 0; tap0 < ks; tap0 += 4) {
+      u32x4 w[4][2];
 #pragma unroll
-      for (int u = 0; u < PB; ++u) {
-        const int i = i0 + u * kThreads;
-        const int pm = (i % (CH / 8)) * 8, row = i / (CH / 8);      // row = tap * CP + c
-        w[u] = u32x4{0u, 0u, 0u, 0u};
-        if (i < n_pieces) w[u] = *reinterpret_cast<const u32x4*>(ph + (int64_t)row * C2 + chunk * CH + pm);
+      for (int u = 0; u < 4; ++u) {
+        const int tap = tap0 + u < ks ? tap0 + u : ks - 1;                // clamp: the extra copies are harmless
+        w[u][0] = *reinterpret_cast<const u32x4*>(src + (int64_t)tap * CP * C2);
+        w[u][1] = *reinterpret_cast<const u32x4*>(src + (int64_t)tap * CP * C2 + 16 * C2);
       }
 #pragma unroll
-      for (int u = 0; u < PB; ++u) {
-        const int i = i0 + u * kThreads;
-        const int pm = (i % (CH / 8)) * 8, row = i / (CH / 8);
-        if (i < n_pieces) *reinterpret_cast<u32x4*>(w_lds + (size_t)row * XS + pm) = w[u];
+      for (int u = 0; u < 4; ++u) {
+        const int tap = tap0 + u < ks ? tap0 + u : ks - 1;
+        *reinterpret_cast<u32x4*>(dst + (size_t)tap * CP * XS) = w[u][0];
+        *reinterpret_cast<u32x4*>(dst + (size_t)tap * CP * XS + 16 * XS) = w[u][1];
       }
     }
   };
-  // token tile of one chunk with halo: global -> registers (issued early), registers -> LDS (after the MFMAs)
-  const int piece = tid % PPR, r_in = tid / PPR;
+  // Token tile of one chunk with halo: global -> registers (issued early), registers -> LDS (after the MFMAs).
+  // Buffer loads: rows before the sequence start or past its end are outside the descriptor and read as zeros,
+  // so the loads carry no conditions and are issued back to back.  For D = 64 a chunk row is 8 key pieces followed
+  // by 8 value pieces; waves 0-1 fetch the key halves and waves 2-3 the value halves (one descriptor per wave).
+  constexpr int HT = D == 64 ? kThreads / 2 : kThreads;   // threads cooperating on one tensor's part of the rows
+  constexpr int PPH = D == 64 ? 8 : 16;                   // 16-byte pieces of that part per row
+  const int t_in = tid % HT, piece = t_in % PPH, r_in = t_in / PPH;   // 16 rows per pass either way
+  const bool v_wave = D == 64 && __builtin_amdgcn_readfirstlane(tid / HT) == 1;
+  const uint32_t row_bytes = (uint32_t)st * 2u;
+  const uint32_t seq_bytes = (uint32_t)(n - 1) * row_bytes + (uint32_t)(D * 2);
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k + lo * st + (int64_t)h * sh), 0, seq_bytes, 0x00020000);
+  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v + lo * st + (int64_t)h * sh), 0, seq_bytes, 0x00020000);
+  const int lds_col = (v_wave ? D : 0) + piece * 8;
   u32x4 xreg[XREG];
   auto load_tokens = [&](int chunk, int tile) {
-    const int m = chunk * CH + piece * 8;           // first input channel of this piece
-    const bool is_v = m >= D;
-    const bf16_t* base = (is_v ? v : k) + (int64_t)h * sh + (is_v ? m - D : m);
+    const bool is_v = D == 64 ? v_wave : chunk == 1;
     const int j0 = g0 + tile * TM;
+    const uint32_t off0 = (uint32_t)(j0 - rho + r_in) * row_bytes + (uint32_t)piece * 16u;   // wraps for rows < 0
 #pragma unroll
     for (int i = 0; i < XREG; ++i) {
-      const int r = r_in + i * RPP;
-      const int p = j0 - rho + r;
-      xreg[i] = u32x4{0u, 0u, 0u, 0u};
-      if (r < rows && p >= 0 && p < n) xreg[i] = *reinterpret_cast<const u32x4*>(base + (lo + p) * st);
+      const uint32_t off = off0 + (uint32_t)(i * RPP) * row_bytes;
+      xreg[i] = is_v ? __builtin_amdgcn_raw_buffer_load_b128(rs_v, off, 0, 0)
+                     : __builtin_amdgcn_raw_buffer_load_b128(rs_k, off, 0, 0);
     }
   };
   auto store_tokens = [&]() {
 #pragma unroll
-    for (int i = 0; i < XREG; ++i) {
-      const int r = r_in + i * RPP;
-      if (r < rows) *reinterpret_cast<u32x4*>(&x_lds[r * XS + piece * 8]) = xreg[i];
-    }
+    for (int i = 0; i < XREG; ++i)
+      if ((i + 1) * RPP <= kTileRows || r_in + i * RPP < kTileRows)   // only the last pass can be partial
+        *reinterpret_cast<u32x4*>(&x_lds[(r_in + i * RPP) * XS + lds_col]) = xreg[i];
   };
 
   f32x16 acc[NT];
@@ -164,8 +172,11 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int c = 8 * (r / 4) + 4 * hb + (r % 4);
-    bs[r] = c < C ? bias[h * C + c] : 0.f;
-    wo[r] = c < C ? to_f32(w_out[h * C + c]) : 0.f;
+    const int cc = c < C ? c : C - 1;            // unconditional loads (no branch per element), then select
+    const float b_ld = bias[h * C + cc];
+    const float w_ld = to_f32(w_out[h * C + cc]);
+    bs[r] = c < C ? b_ld : 0.f;
+    wo[r] = c < C ? w_ld : 0.f;
   }
   const float bo = b_out[h];
 #pragma unroll
@@ -186,7 +197,8 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
 
 size_t lds_bytes(int ks, int dil) {
   const int rho = (ks - 1) / 2 * dil;
-  return ((size_t)(TM + 2 * rho) + (size_t)ks * CP) * XS * sizeof(uint16_t);
+  (void)rho;
+  return ((size_t)kTileRows + (size_t)ks * CP) * XS * sizeof(uint16_t);
 }
 
 template <int D>
