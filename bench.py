@@ -48,6 +48,16 @@ WORKLOAD_TEXT = {
 }
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch (fetch + write) of a kernel from the committed rocprofv3 counter summary, or None."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic_per_launch.json")) as f:
+            t = json.load(f)[workload][kernel]
+        return t["fetch_bytes"] + t["write_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -148,7 +158,8 @@ def bench_prefill(args):
     score_bytes = 2 * T * w.Hkv * w.D * 2 + 4 * T * w.Hkv
     res = dict(value=value, ms_per_step=ms_per_step, tokens_per_step=tokens_per_step, kern_ms=kern_ms,
                roofline=dict(bound="mfma", kernel="prefill attention (window + retained)", achieved=achieved,
-                             peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS, traffic=None,
+                             peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS,
+                             traffic=measured_traffic("prefill_bf16", "attention_mfma_kernel") if args.workload == "prefill" else None,
                              algorithmic_flops=flops, avg_ms=kern_ms["attention"]),
                scoring=dict(bound="hbm", achieved=score_bytes / (kern_ms["score"] * 1e-3) / 1e9, peak=PEAK_HBM_GBS,
                             unit="GB/s", frac=score_bytes / (kern_ms["score"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
@@ -209,7 +220,8 @@ def bench_decode(args):
                 us_per_step=us_per_step, us_per_token=us_per_step / st.B, wall_us_per_step=wall_us,
                 algorithmic_bytes_per_step=bytes_per_step,
                 roofline=dict(bound="hbm", kernel="decode step (all launches)", achieved=gbs, peak=PEAK_HBM_GBS,
-                              unit="GB/s", frac=gbs / PEAK_HBM_GBS, traffic=None))
+                              unit="GB/s", frac=gbs / PEAK_HBM_GBS,
+                              traffic=measured_traffic("decode_bf16", "decode_main_kernel")))
 
 
 def cpu_baseline(w):
@@ -238,6 +250,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--workload", choices=["prefill", "long", "varlen"], default="prefill",
                     help="prefill = the benchmark configuration (default); long / varlen = the other prefill "
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
@@ -253,6 +268,13 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     log(f"[bench] device: {torch.cuda.get_device_name(0)}")
+    if args.calibrate_copy:
+        src = torch.full((256 << 20,), 1, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     pre = bench_prefill(args)
     log(f"[bench] prefill step {pre['ms_per_step']:.3f} ms; kernels (ms): {pre['kern_ms']}")
     w = pre.pop("workload")
