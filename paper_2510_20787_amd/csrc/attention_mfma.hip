@@ -239,23 +239,29 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     const bf16_t* a_k = buf + a_k_off;
     const bf16_t* a_v0 = buf + a_v_off0;
     const bf16_t* a_v1 = buf + a_v_off1;
+    // Both 32-key score blocks are issued before the first one is consumed, so the matrix pipe keeps working on
+    // the second block (and later on the first block's P.V product) while the VALU runs the softmax.
+    f32x16 sacc[2][QB];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      f32x16 sacc[QB];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[qb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_k + 32 * kb * KS + 16 * ks);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-          sacc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sacc[qb], 0, 0, 0);
+          sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sacc[kb][qb], 0, 0, 0);
       }
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
       bf16x8 pb[QB][2];
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
+        f32x16& sc = sacc[kb][qb];
         const int qi = r0 + 32 * qb + ql;
         // register r is key (local) 32*kb + 16*(r/8) + 8*hb + r%8
         if (mode == 1) {
@@ -270,7 +276,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int c = 32 * kb + 16 * (r / 8) + (r % 8);
-            sacc[qb][r] = ((unsigned)(c - c_lo) <= span) ? sacc[qb][r] : -INFINITY;
+            sc[r] = ((unsigned)(c - c_lo) <= span) ? sc[r] : -INFINITY;
           }
         } else if (mode == 2) {
           const int lim = qi - window;
@@ -278,13 +284,13 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
           for (int r8 = 0; r8 < 2; ++r8) {
             const int* pp = pos + 32 * kb + 16 * r8 + 8 * hb;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sacc[qb][8 * r8 + e] = (pp[e] <= lim) ? sacc[qb][8 * r8 + e] : -INFINITY;
+            for (int e = 0; e < 8; ++e) sc[8 * r8 + e] = (pp[e] <= lim) ? sc[8 * r8 + e] : -INFINITY;
           }
         }
         // ---- online softmax with a lazily raised maximum ----------------------------------------------------
-        float mx = fmaxf(sacc[qb][0], sacc[qb][1]);
+        float mx = fmaxf(sc[0], sc[1]);
 #pragma unroll
-        for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sacc[qb][r]), sacc[qb][r + 1]);
+        for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sc[r]), sc[r + 1]);
         mx = pair_max(mx);
         const float mcand = mx * scale_log2e;
         const bool grow = mcand > m_run[qb] + kLazyMax;   // true on the first visible keys (m_run = -inf)
@@ -301,7 +307,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
         float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[qb][r], scale_log2e, -m_use));
+          const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -m_use));
           if (r & 1) psum1 += p; else psum0 += p;
           pb[qb][r / 8][r % 8] = static_cast<bf16_t>(p);
         }
