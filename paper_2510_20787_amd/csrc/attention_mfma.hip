@@ -7,21 +7,23 @@
 // only tiles that straddle a window edge, the causal diagonal, the sequence end or the visibility frontier of
 // the retained entries pay for masking.
 //
-// Work split: one workgroup = 128*QB consecutive queries of one (sequence, query head); 4 waves, each owning
-// QB blocks of 32 queries (QB = 2 for D = 64, 1 for D = 128: what fits the register file at 2 waves/SIMD).
-// MFMA shapes (v_mfma_f32_32x32x16_bf16, wave64):
+// Work split: one workgroup = 128 consecutive queries of one (sequence, query head); 4 waves, each owning a
+// block of 32 queries.  MFMA shapes (v_mfma_f32_32x32x16_bf16, wave64):
 //   S^T[key, query] = K[key, :] . Q[query, :]   A = K tile rows from LDS, B = Q fragment held in registers
-//   O^T[d, query]  += V^T[d, key] . P^T[key, query]   A = V^T tile from LDS, B = P^T straight from S^T's
+//   O^T[d, query]  += V^T[d, key] . P^T[key, query]   A = V^T fragments from LDS, B = P^T straight from S^T's
 //                                                     accumulator registers (no shuffle, no LDS round trip)
 // In the 32x32 accumulator layout a lane owns one query column, so the online-softmax statistics are
 // per-lane scalars (the two lanes sharing a query exchange one value per 32 keys).  The contraction index of
 // the second product is the key index; the rows of the K tile are fed to the first MFMA in a permuted
-// order so that each lane's eight P values per MFMA are eight consecutive keys, which is what lets the
-// V^T operand be read as one 16-byte LDS load.  V is transposed on its way into LDS (4 keys x 8 columns
-// per thread, XOR-swizzled so that both the transposing stores and the operand loads spread over the 64 banks).
-// K/V tiles are double-buffered in LDS and prefetched two tiles ahead through registers, one barrier per tile.
-// The running maximum is only raised when a block of scores exceeds it by more than 2^8 (the result does not
-// depend on the stabiliser), which keeps the accumulator rescale off the common path.
+// order so that each lane's eight P values per MFMA are eight consecutive keys.  V stays row-major in LDS
+// and its A operand (eight consecutive keys of one column per lane) comes out of the transposing LDS load
+// ds_read_b64_tr_b16, two per MFMA; the tile's 64-byte chunks are XOR-swizzled so that those loads and the
+// staging stores spread over the 64 banks without padding.
+// K/V tiles are double-buffered in LDS and prefetched through registers (two tiles ahead for D = 64, one for
+// D = 128 where registers are short), one barrier per tile.  The running maximum is only raised when a block of
+// scores exceeds it by more than 2^8 (the result does not depend on the stabiliser), which keeps the accumulator
+// rescale off the common path.  Inside a tile the matrix work of one 32-key block is placed next to the
+// exponentials of the other, so that they overlap within the wave's in-order instruction stream.
 #include <type_traits>
 
 #include "ltea_common.h"
@@ -37,6 +39,24 @@ constexpr float kLazyMax = 8.0f;  // log2 units
 // Row of the K tile (within a block of 32) that MFMA row m must carry so that accumulator register r of
 // lane half hb holds key 16*(r/8) + 8*hb + r%8: swap bits 2 and 3 of m.
 __device__ __forceinline__ int key_row_of_mfma_row(int m) { return (m & 0x13) | ((m & 0x08) >> 1) | ((m & 0x04) << 1); }
+
+// Swizzle term of the V tile: which 64-byte chunk of its row a key row's chunk c is stored in (c ^ term).
+// Four consecutive rows must land in four different 64-byte bank groups: rows are 128 bytes (D = 64, two
+// chunks, alternate every second row) or 256 bytes (D = 128, four chunks, rotate every row).
+template <int D> __device__ __forceinline__ int v_swizzle(int row) { return D == 64 ? ((row >> 1) & 1) : (row & 3); }
+
+// A operand of O^T += V^T P^T for 8 consecutive keys: two transposing 64-bit LDS loads (keys +0..3, +4..7).
+__device__ __forceinline__ bf16x8 load_v_operand(const bf16_t* p, int row_stride) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
+  s16x8 r;
+  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, r);
+}
 
 // Both lane halves (l, l^32) receive max / sum of the pair.
 __device__ __forceinline__ float pair_max(float x) {
@@ -61,18 +81,17 @@ __device__ __forceinline__ int wave_max_i(int x) {
 template <int D, int QB> struct Geo {
   static constexpr int BM = 128 * QB;           // queries per workgroup
   static constexpr int KS = D + 8;              // K tile row stride (elements); 16-byte pad
-  static constexpr int VS = BN + 8;             // V^T tile row stride (elements)
+  static constexpr int VS = D;                  // V tile row stride (elements): unpadded, 64-byte chunks swizzled
   static constexpr int PPR = D / 8;             // 16-byte pieces per K row
   static constexpr int RPP = kThreads / PPR;    // K rows per pass
   static constexpr int KPASS = BN / RPP;        // passes over the K tile
-  static constexpr int CPT = D / 16;            // V columns per thread (4 keys x CPT columns)
   static constexpr int OS = D + 8;              // epilogue staging row stride (elements)
-  static constexpr int kBuf = BN * KS + D * VS; // elements per LDS tile buffer (K tile then V^T tile)
+  static constexpr int kBuf = BN * KS + BN * VS; // elements per LDS tile buffer (K tile then V tile)
 };
 
 template <int D> struct TileRegs {
   u32x4 k[BN / (kThreads / (D / 8))];
-  uint32_t v[4][D / 32];
+  u32x4 v[BN / (kThreads / (D / 8))];
   int pos;
 };
 
@@ -150,60 +169,42 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const auto rs_vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v_ret + head * budget * D), 0, ret_bytes, 0x00020000);
   const int32_t* prbase = ret_pos + head * budget;
   const int k_piece = tid % G::PPR, k_row = tid / G::PPR;
-  const int v_g = tid % 16, v_kg = tid / 16;   // 4 keys x CPT columns per thread; columns fastest across lanes
-  const uint32_t k_col = (uint32_t)k_piece * 16u, v_col = (uint32_t)(v_g * G::CPT) * 2u;
+  const uint32_t k_col = (uint32_t)k_piece * 16u;
   const uint32_t k_loc = (uint32_t)k_row * row_bytes + k_col;          // first pass; later passes add RPP rows
-  const uint32_t v_loc = (uint32_t)(4 * v_kg) * row_bytes + v_col;     // key 4*v_kg; next keys add one row each
   const uint32_t kr_loc = (uint32_t)k_row * (uint32_t)(D * 2) + k_col;
-  const uint32_t vr_loc = (uint32_t)(4 * v_kg) * (uint32_t)(D * 2) + v_col;
 
-  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t kb0, uint32_t vb0, uint32_t rb, TR& R) {
+  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t b0, uint32_t rb, TR& R) {
 #pragma unroll
-    for (int p = 0; p < G::KPASS; ++p)
-      R.k[p] = __builtin_amdgcn_raw_buffer_load_b128(rk, kb0 + (uint32_t)(p * G::RPP) * rb, 0, 0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if constexpr (G::CPT == 8) {
-        const u32x4 x = __builtin_amdgcn_raw_buffer_load_b128(rv, vb0 + (uint32_t)i * rb, 0, 0);
-        R.v[i][0] = x[0]; R.v[i][1] = x[1]; R.v[i][2] = x[2]; R.v[i][3] = x[3];
-      } else {
-        const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rv, vb0 + (uint32_t)i * rb, 0, 0);
-        R.v[i][0] = x[0]; R.v[i][1] = x[1];
-      }
+    for (int p = 0; p < G::KPASS; ++p) {
+      R.k[p] = __builtin_amdgcn_raw_buffer_load_b128(rk, b0 + (uint32_t)(p * G::RPP) * rb, 0, 0);
+      R.v[p] = __builtin_amdgcn_raw_buffer_load_b128(rv, b0 + (uint32_t)(p * G::RPP) * rb, 0, 0);
     }
   };
   auto load_tile = [&](int t, TR& R) {
     if (t < n_win_tiles) {
       const uint32_t tb = (uint32_t)(jt0 + t * BN) * row_bytes;
-      load_rows(rs_k, rs_v, tb + k_loc, tb + v_loc, row_bytes, R);
+      load_rows(rs_k, rs_v, tb + k_loc, row_bytes, R);
     } else {
       const int base = (t - n_win_tiles) * BN;
       const uint32_t tb = (uint32_t)base * (uint32_t)(D * 2);
-      load_rows(rs_kr, rs_vr, tb + kr_loc, tb + vr_loc, (uint32_t)(D * 2), R);
+      load_rows(rs_kr, rs_vr, tb + kr_loc, (uint32_t)(D * 2), R);
       R.pos = 0x7FFFFFFF;
       if (tid < BN && base + tid < cnt) R.pos = prbase[base + tid];
     }
   };
 
-  // LDS store addresses. V^T rows are d, columns keys; the 16-byte column chunk index is XOR-ed with
-  // 2*((d >> 4) & 3) on both the store and the load side.
-  const int v_d0 = v_g * G::CPT;
+  // LDS store addresses. The V tile stays row-major [key][d] without padding; its 64-byte chunks (32 columns)
+  // are XOR-swizzled with the key row so that the transposing operand loads (4 keys x 16 columns per 16 lanes)
+  // spread over all banks.  Rows of one pass differ by multiples of RPP, which leaves the swizzle term unchanged.
+  static_assert(G::RPP % 4 == 0, "row passes must preserve the swizzle phase");
   const int k_st_off = k_row * KS + k_piece * 8;
-  const int v_st_off = BN * KS + v_d0 * VS + ((4 * v_kg) ^ (16 * ((v_d0 >> 4) & 3)));
+  const int v_st_off = BN * KS + k_row * VS + (((k_piece >> 2) ^ v_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
   auto store_tile = [&](int t, const TR& R) {
     bf16_t* buf = lds + (t & 1) * kBuf;
 #pragma unroll
-    for (int p = 0; p < G::KPASS; ++p) *reinterpret_cast<u32x4*>(buf + k_st_off + p * G::RPP * KS) = R.k[p];
-#pragma unroll
-    for (int c2 = 0; c2 < G::CPT / 2; ++c2) {
-      const uint32_t a0 = R.v[0][c2], a1 = R.v[1][c2], a2 = R.v[2][c2], a3 = R.v[3][c2];
-      u32x2 even, odd;
-      even[0] = (a0 & 0xFFFFu) | (a1 << 16);
-      even[1] = (a2 & 0xFFFFu) | (a3 << 16);
-      odd[0] = (a0 >> 16) | (a1 & 0xFFFF0000u);
-      odd[1] = (a2 >> 16) | (a3 & 0xFFFF0000u);
-      *reinterpret_cast<u32x2*>(buf + v_st_off + (2 * c2) * VS) = even;
-      *reinterpret_cast<u32x2*>(buf + v_st_off + (2 * c2 + 1) * VS) = odd;
+    for (int p = 0; p < G::KPASS; ++p) {
+      *reinterpret_cast<u32x4*>(buf + k_st_off + p * G::RPP * KS) = R.k[p];
+      *reinterpret_cast<u32x4*>(buf + v_st_off + p * G::RPP * VS) = R.v[p];
     }
     if (t >= n_win_tiles && wv == 0) {   // wave 0 holds the tile's 64 positions (INT_MAX past ret_count)
       pos_lds[t & 1][lane] = R.pos;
@@ -215,9 +216,12 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 
   // operand load offsets inside a tile buffer
   const int a_k_off = key_row_of_mfma_row(ql) * KS + 8 * hb;                 // + 32*kb*KS + 16*ks
-  const int s4 = ql >> 4;
-  const int a_v_off0 = BN * KS + ql * VS + 8 * hb + 16 * (0 ^ s4);            // kk = 0
-  const int a_v_off1 = BN * KS + ql * VS + 8 * hb + 16 * (1 ^ s4);            // kk = 1
+  // V operand through the transposing LDS load: in each group of 16 lanes, lane j points at the four columns
+  // d0 + 4*(j%4).. of key row kbase + j/4, and receives column d0 + j of the four keys kbase..kbase+3.
+  const int tr_key = 8 * hb + ((lane & 15) >> 2);           // + 32*kb + 16*kk (+ 4 for the upper half)
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db, inside one 64-byte chunk
+  const int tr_swz = v_swizzle<D>(tr_key);                  // unchanged by adding multiples of 4 to the key
+  const int a_v_off = BN * KS + tr_key * VS + tr_col;
 
   // ---- online softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
   float m_run[QB], l_part[QB];
@@ -237,33 +241,33 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   // 32x32 score block per query block is live at a time.
   auto compute = [&](const int mode, const bf16_t* buf, const int* pos, int jt) {
     const bf16_t* a_k = buf + a_k_off;
-    const bf16_t* a_v0 = buf + a_v_off0;
-    const bf16_t* a_v1 = buf + a_v_off1;
-    // Both 32-key score blocks are issued before the first one is consumed, so the matrix pipe keeps working on
-    // the second block (and later on the first block's P.V product) while the VALU runs the softmax.
-    f32x16 sacc[2][QB];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    const bf16_t* a_v = buf + a_v_off;
+    // The tile is consumed as two 32-key blocks.  Program order puts the matrix work of one block next to the
+    // exponentials of the other (scores of block 1 beside the softmax of block 0, P.V of block 0 beside the
+    // softmax of block 1), because a wave issues in order: only MFMAs that sit between VALU instructions in
+    // the instruction stream run concurrently with them.
+    auto score_block = [&](int kb, f32x16 (&sc)[QB]) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[kb][qb][r] = 0.f;
+        for (int r = 0; r < 16; ++r) sc[qb][r] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_k + 32 * kb * KS + 16 * ks);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-          sacc[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sacc[kb][qb], 0, 0, 0);
+          sc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sc[qb], 0, 0, 0);
       }
-    }
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      bf16x8 pb[QB][2];
+    };
+    // mask (register r is local key 32*kb + 16*(r/8) + 8*hb + r%8), then raise the running maximum if needed.
+    // Returns whether any lane raised it; the factors the output accumulators still have to be scaled by are left
+    // in alpha[] (the caller applies them once every P.V product issued under the old maximum is in).
+    auto mask_and_max = [&](int kb, f32x16 (&scs)[QB], float (&alpha)[QB]) -> bool {
+      bool any = false;
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        f32x16& sc = sacc[kb][qb];
+        f32x16& sc = scs[qb];
         const int qi = r0 + 32 * qb + ql;
-        // register r is key (local) 32*kb + 16*(r/8) + 8*hb + r%8
         if (mode == 1) {
           // valid local keys c (without the 8*hb term) form the range [c_lo, c_hi]: causal, window and sequence end
           const int shift = jt + 8 * hb;
@@ -287,57 +291,84 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
             for (int e = 0; e < 8; ++e) sc[8 * r8 + e] = (pp[e] <= lim) ? sc[8 * r8 + e] : -INFINITY;
           }
         }
-        // ---- online softmax with a lazily raised maximum ----------------------------------------------------
         float mx = fmaxf(sc[0], sc[1]);
 #pragma unroll
         for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sc[r]), sc[r + 1]);
         mx = pair_max(mx);
         const float mcand = mx * scale_log2e;
         const bool grow = mcand > m_run[qb] + kLazyMax;   // true on the first visible keys (m_run = -inf)
+        alpha[qb] = 1.0f;
         if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-          const float alpha = grow ? __builtin_amdgcn_exp2f(m_run[qb] - mcand) : 1.0f;
+          any = true;
+          alpha[qb] = grow ? __builtin_amdgcn_exp2f(m_run[qb] - mcand) : 1.0f;
           m_run[qb] = grow ? mcand : m_run[qb];
-          l_part[qb] *= alpha;
-#pragma unroll
-          for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha;
+          l_part[qb] *= alpha[qb];
         }
+      }
+      return any;
+    };
+    auto rescale = [&](const float (&alpha)[QB]) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha[qb];
+    };
+    auto exp_block = [&](const f32x16 (&scs)[QB], bf16x8 (&pb)[QB][2]) {
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
         const float m_use = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
         float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -m_use));
+          const float p = __builtin_amdgcn_exp2f(fmaf(scs[qb][r], scale_log2e, -m_use));
           if (r & 1) psum1 += p; else psum0 += p;
           pb[qb][r / 8][r % 8] = static_cast<bf16_t>(p);
         }
         l_part[qb] += psum0 + psum1;
+        // Pin the packed probabilities here: without a use in this block the compiler sinks the exponentials
+        // past the following branches, away from the MFMAs they are meant to overlap with.
+        u32x4 w0 = __builtin_bit_cast(u32x4, pb[qb][0]), w1 = __builtin_bit_cast(u32x4, pb[qb][1]);
+        asm volatile("" : "+v"(w0), "+v"(w1), "+v"(l_part[qb]));
+        pb[qb][0] = __builtin_bit_cast(bf16x8, w0);
+        pb[qb][1] = __builtin_bit_cast(bf16x8, w1);
       }
-      // ---- O^T += V^T P^T -----------------------------------------------------------------------------------
+    };
+    auto pv_block = [&](int kb, const bf16x8 (&pb)[QB][2]) {   // O^T += V^T P^T
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
-        const int col = 32 * (kb ^ (db & 1));
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(a_v0 + 32 * db * VS + col);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(a_v1 + 32 * db * VS + col);
+        const bf16_t* ap = a_v + 32 * kb * VS + ((db ^ tr_swz) << 5);
+        const bf16x8 a0 = load_v_operand(ap, VS);
+        const bf16x8 a1 = load_v_operand(ap + 16 * VS, VS);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[qb][0], o[qb][db], 0, 0, 0);
           o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pb[qb][1], o[qb][db], 0, 0, 0);
         }
       }
-    }
+    };
+    f32x16 s0[QB], s1[QB];
+    bf16x8 p0[QB][2], p1[QB][2];
+    float alpha[QB];
+    score_block(0, s0);
+    if (mask_and_max(0, s0, alpha)) rescale(alpha);
+    score_block(1, s1);
+    exp_block(s0, p0);
+    const bool grew = mask_and_max(1, s1, alpha);   // p0 was formed under the previous maximum:
+    pv_block(0, p0);                                //   its product goes in before the accumulators are scaled
+    exp_block(s1, p1);
+    if (grew) rescale(alpha);
+    pv_block(1, p1);
   };
 
   // ---- software pipeline: tile t is computed from LDS buffer t&1 while tile t+1 is being stored into the other
   // buffer and tile t+2 is in flight from global memory --------------------------------------------------------
-  TR regs;
-  load_tile(0, regs);
-  store_tile(0, regs);
-  if (n_tiles > 1) load_tile(1, regs);
-  for (int t = 0; t < n_tiles; ++t) {
+  constexpr int kAhead = D == 64 ? 2 : 1;   // tiles in flight from global memory
+  auto step = [&](int t, TR& R) {   // R holds tile t+1 on entry and tile t+1+kAhead on exit
     __syncthreads();   // tile t is in LDS; everyone is done with tile t-1 (whose buffer is overwritten next)
-    if (t + 1 < n_tiles) store_tile(t + 1, regs);
-    if (t + 2 < n_tiles) load_tile(t + 2, regs);
+    if (t + 1 < n_tiles) store_tile(t + 1, R);
+    if (t + 1 + kAhead < n_tiles) load_tile(t + 1 + kAhead, R);
     const bf16_t* buf = lds + (t & 1) * kBuf;
     // classify the tile for this wave: -1 skip, 0 every (query, key) pair valid, 1 window-edge mask, 2 retained mask
     int mode = -1, jt = 0;
@@ -357,6 +388,19 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     }
     mode = __builtin_amdgcn_readfirstlane(mode);
     if (mode >= 0) compute(mode, buf, pos_lds[t & 1], jt);
+  };
+  TR regs_a, regs_b;
+  load_tile(0, regs_a);
+  store_tile(0, regs_a);
+  if (n_tiles > 1) load_tile(1, regs_a);
+  if constexpr (kAhead == 2) {
+    if (n_tiles > 2) load_tile(2, regs_b);
+    for (int t = 0; t < n_tiles; t += 2) {
+      step(t, regs_a);
+      if (t + 1 < n_tiles) step(t + 1, regs_b);
+    }
+  } else {
+    for (int t = 0; t < n_tiles; ++t) step(t, regs_a);
   }
 
   // ---- epilogue: normalise, stage through LDS, store rows coalesced -------------------------------------------
