@@ -1,13 +1,15 @@
 // Budgeted retention and cache fill (paper eq. 5; Section 3.1.3 "Capped capacity", "Cached prefilling").
 //
-// Kernel 1 (retain_select_kernel), one workgroup per (sequence, KV head):
+// One launch.  Workgroups with blockIdx.y == 0 own one (sequence, KV head) each:
 //   candidates among the out-of-window positions 0 .. n-window-1 are sinks or logits above the threshold;
-//   if more than `budget` exist, an exact radix select (4 passes of 8 bits over an order-preserving
-//   integer image of the fp32 key) finds the budget-th largest key, and ties at that key are resolved
-//   towards lower positions by an ordered scan.  The same ordered scan (wave prefix sums, no atomics on
-//   results) writes the kept positions and keys ascending by position, so the result is deterministic.
-// Kernel 2 (cache_fill_kernel): gathers the kept K/V rows into the compact segment and copies the last
-//   min(n, window) tokens and their logits into the ring (slot = position % window).
+//   their keys (an order-preserving integer image of the fp32 key, 0 for non-candidates) are read once and
+//   stay in registers.  If more than `budget` exist, an exact radix select (up to 4 passes of 8 bits) finds
+//   the budget-th largest key, and ties at that key are resolved towards lower positions by an ordered scan.
+//   The same ordered scan (wave prefix sums, no atomics on results) writes the kept positions and keys
+//   ascending by position, so the result is deterministic; the workgroup then gathers the kept K/V rows into
+//   the compact segment.
+// Workgroups with blockIdx.y >= 1 copy the last min(n, window) tokens and their logits into the ring
+// (slot = position % window); that part does not depend on the selection and overlaps with it.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 
@@ -16,7 +18,14 @@ namespace {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kItems = 4;  // consecutive positions per thread per chunk
+constexpr int kItems = 4;                        // consecutive positions per thread per chunk
+constexpr int kChunk = kSelThreads * kItems;     // positions per chunk
+constexpr int kSub = 8;                          // sub-histograms per digit (spreads same-digit LDS atomics)
+constexpr int kRingRows = 256;                   // ring rows per copy workgroup
+
+__device__ __forceinline__ float key_of_order_key(uint32_t u) {
+  return __uint_as_float((u & 0x80000000u) ? (u ^ 0x80000000u) : ~u);
+}
 
 // Exclusive prefix sum of `val` over the block (thread order); `total` receives the block sum.
 // `scratch` holds kSelWaves+1 ints of LDS. Contains two barriers.
@@ -42,99 +51,166 @@ __device__ __forceinline__ int block_exclusive_scan(int val, int* scratch, int& 
   return before + inc - val;
 }
 
-__global__ void __launch_bounds__(kSelThreads)
-retain_select_kernel(const float* __restrict__ logits, int64_t total, const int32_t* __restrict__ cu, int Hkv,
-                     int window, int budget, int sink, float tau, int rho, float* __restrict__ ret_score,
-                     int32_t* __restrict__ ret_pos, int32_t* __restrict__ ret_count, int32_t* __restrict__ n_seen,
-                     int32_t* __restrict__ n_scored) {
-  __shared__ int scan_scratch[kSelWaves + 1];
-  __shared__ int hist[256];
-  __shared__ int sel_digit, sel_need;
+struct RetainArgs {
+  const float* logits; int64_t total; const int32_t* cu; int Hkv, window, budget, sink; float tau; int rho;
+  const char* k; const char* v; int64_t tok_bytes, head_bytes; int row_bytes;   // K/V views in bytes
+  char* k_win; char* v_win; float* win_score; char* k_ret; char* v_ret;
+  float* ret_score; int32_t* ret_pos; int32_t* ret_count; int32_t* n_seen; int32_t* n_scored;
+};
 
-  const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
-  const int tid = threadIdx.x;
-  const int64_t lo = cu[b];
-  const int n = (int)(cu[b + 1] - lo);
-  const int n_out = n > window ? n - window : 0;
-  const float* z = logits + (int64_t)h * total + lo;
-  if (h == 0 && tid == 0) {
-    n_seen[b] = n;
-    n_scored[b] = n > rho ? n - rho : 0;
-  }
-  const int64_t head = (int64_t)b * Hkv + h;
-  if (budget == 0 || n_out == 0) {
-    if (tid == 0) ret_count[head] = 0;
+// Copies one K row and one V row of row_bytes (a multiple of 16) in 16-byte pieces; piece index `pc`.
+__device__ __forceinline__ void copy_piece(const RetainArgs& a, int64_t src_off, char* dk, char* dv, int pc) {
+  reinterpret_cast<u32x4*>(dk)[pc] = reinterpret_cast<const u32x4*>(a.k + src_off)[pc];
+  reinterpret_cast<u32x4*>(dv)[pc] = reinterpret_cast<const u32x4*>(a.v + src_off)[pc];
+}
+
+// CH > 0: the (sequence, head)'s out-of-window keys fit CH chunks and are held in registers;
+// CH == 0: any length, keys are re-read from memory in every pass.
+template <int CH>
+__global__ void __launch_bounds__(kSelThreads)
+retain_kernel(const RetainArgs a) {
+  __shared__ int scan_scratch[kSelWaves + 1];
+  __shared__ __align__(16) int hist[256 * kSub];
+  __shared__ int sel_digit, sel_need, sel_total;
+
+  const int b = blockIdx.x / a.Hkv, h = blockIdx.x - b * a.Hkv;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int64_t lo = a.cu[b];
+  const int n = (int)(a.cu[b + 1] - lo);
+  const int64_t head = (int64_t)b * a.Hkv + h;
+  const float* z = a.logits + (int64_t)h * a.total + lo;
+  const int pieces = a.row_bytes / 16;
+
+  if (blockIdx.y > 0) {
+    // ---- ring rows: slot -> the position it holds after n tokens ----
+    const int rows_per_pass = kSelThreads / pieces;
+    const int sub = tid / pieces, pc = tid - sub * pieces;
+    const int row_end = min((int)blockIdx.y * kRingRows, a.window);
+    for (int slot = ((int)blockIdx.y - 1) * kRingRows + sub; slot < row_end; slot += rows_per_pass) {
+      int p;
+      if (n >= a.window) {
+        const int first = n - a.window;   // oldest position in the window
+        p = first + (slot - first % a.window + a.window) % a.window;
+      } else {
+        p = slot < n ? slot : -1;
+      }
+      if (p < 0) continue;
+      if (pc == 0) a.win_score[head * a.window + slot] = z[p];
+      copy_piece(a, (lo + p) * a.tok_bytes + h * a.head_bytes, a.k_win + (head * a.window + slot) * a.row_bytes,
+                 a.v_win + (head * a.window + slot) * a.row_bytes, pc);
+    }
     return;
   }
 
-  // ---- count candidates ----
-  int mine = 0;
-  for (int j = tid; j < n_out; j += kSelThreads) {
-    const float zj = z[j];
-    mine += (j < sink) || (zj > tau);
+  const int n_out = n > a.window ? n - a.window : 0;
+  if (h == 0 && tid == 0) {
+    a.n_seen[b] = n;
+    a.n_scored[b] = n > a.rho ? n - a.rho : 0;
   }
-  int n_cand;
-  block_exclusive_scan(mine, scan_scratch, n_cand);
+  if (a.budget == 0 || n_out == 0) {
+    if (tid == 0) a.ret_count[head] = 0;
+    return;
+  }
 
-  // ---- exact budget-th largest key (only when the cap binds) ----
+  // ---- keys: 0 = not a candidate (every candidate's order key is positive) ----
+  auto fetch = [&](int j) -> uint32_t {
+    if (j >= n_out) return 0u;
+    const float zj = z[j];
+    return ((j < a.sink) || (zj > a.tau)) ? order_key(select_key(zj, j, a.sink)) : 0u;
+  };
+  constexpr int kHeld = CH > 0 ? CH : 1;
+  uint32_t held[kHeld][kItems];
+  if constexpr (CH > 0) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+#pragma unroll
+      for (int e = 0; e < kItems; ++e) held[c][e] = fetch(c * kChunk + tid * kItems + e);
+  }
+  int n_chunks = (n_out + kChunk - 1) / kChunk;
+  if (CH > 0 && n_chunks > CH) n_chunks = CH;   // only if max_seqlen understated the lengths
+  auto chunk_keys = [&](int c, uint32_t (&u)[kItems]) {
+    if constexpr (CH > 0) {
+#pragma unroll
+      for (int cc = 0; cc < CH; ++cc)
+        if (cc == c) {
+#pragma unroll
+          for (int e = 0; e < kItems; ++e) u[e] = held[cc][e];
+        }
+    } else {
+#pragma unroll
+      for (int e = 0; e < kItems; ++e) u[e] = fetch(c * kChunk + tid * kItems + e);
+    }
+  };
+
+  // ---- exact budget-th largest key (only when the cap binds); the first pass also counts the candidates ----
   uint32_t thr = 0;      // keep keys strictly above thr ...
   int need_eq = 0;       // ... plus the first need_eq (by position) equal to thr
-  if (n_cand > budget) {
+  {
     uint32_t prefix = 0;
-    int need = budget;
+    int need = a.budget;
     for (int pass = 0; pass < 4; ++pass) {
       const int shift = 24 - 8 * pass;
-      if (tid < 256) hist[tid] = 0;
+      hist[tid] = 0;
+      hist[tid + kSelThreads] = 0;
       __syncthreads();
-      for (int j = tid; j < n_out; j += kSelThreads) {
-        const float zj = z[j];
-        if ((j < sink) || (zj > tau)) {
-          const uint32_t u = order_key(select_key(zj, j, sink));
-          const bool match = (pass == 0) || ((u >> (shift + 8)) == prefix);
-          if (match) atomicAdd(&hist[(u >> shift) & 255u], 1);
+#pragma unroll 1
+      for (int c = 0; c < n_chunks; ++c) {
+        uint32_t u[kItems];
+        chunk_keys(c, u);
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+          const bool match = u[e] != 0u && ((pass == 0) || ((u[e] >> (shift + 8)) == prefix));
+          if (match) atomicAdd(&hist[((u[e] >> shift) & 255u) * kSub + (lane & (kSub - 1))], 1);
         }
       }
       __syncthreads();
-      // threads 0..255 walk the digits from 255 down: thread i owns digit 255-i.
-      int cnt = (tid < 256) ? hist[255 - tid] : 0;
-      int tot;
-      int before = block_exclusive_scan(cnt, scan_scratch, tot);  // elements with a larger digit
-      if (tid < 256 && before < need && need <= before + cnt) {
-        sel_digit = 255 - tid;
-        sel_need = need - before;
+      if (tid < kWave) {
+        // lane l owns digits 255-4l .. 252-4l, so lane order is descending digit order
+        int cnt[4], mine = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int d = 255 - 4 * lane - i;
+          const int4 x = *reinterpret_cast<const int4*>(&hist[d * kSub]);
+          const int4 y = *reinterpret_cast<const int4*>(&hist[d * kSub + 4]);
+          cnt[i] = x.x + x.y + x.z + x.w + y.x + y.y + y.z + y.w;
+          mine += cnt[i];
+        }
+        int inc = mine;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+          const int t = __shfl_up(inc, off, kWave);
+          if (lane >= off) inc += t;
+        }
+        int running = inc - mine;   // elements with a larger digit than this lane's first
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (running < need && need <= running + cnt[i]) {
+            sel_digit = 255 - 4 * lane - i;
+            sel_need = need - running;
+          }
+          running += cnt[i];
+        }
+        if (lane == kWave - 1) sel_total = inc;
       }
       __syncthreads();
+      if (pass == 0 && sel_total <= a.budget) break;   // the cap does not bind: keep every candidate
       prefix = (prefix << 8) | (uint32_t)sel_digit;
       need = sel_need;
-      __syncthreads();
+      if (pass == 3) { thr = prefix; need_eq = need; }
+      __syncthreads();   // hist and sel_* are rewritten by the next pass
     }
-    thr = prefix;
-    need_eq = need;
   }
 
   // ---- ordered compaction: ascending positions ----
   int kept_before = 0, eq_before = 0;
-  const int chunk = kSelThreads * kItems;
-  for (int base = 0; base < n_out; base += chunk) {
-    const int j0 = base + tid * kItems;
+#pragma unroll 1
+  for (int c = 0; c < n_chunks; ++c) {
+    const int j0 = c * kChunk + tid * kItems;
     uint32_t u[kItems];
-    float key[kItems];
-    bool cand[kItems];
+    chunk_keys(c, u);
     int n_eq = 0;
 #pragma unroll
-    for (int e = 0; e < kItems; ++e) {
-      const int j = j0 + e;
-      cand[e] = false;
-      u[e] = 0;
-      key[e] = 0.f;
-      if (j < n_out) {
-        const float zj = z[j];
-        cand[e] = (j < sink) || (zj > tau);
-        key[e] = select_key(zj, j, sink);
-        u[e] = order_key(key[e]);
-      }
-      n_eq += (cand[e] && need_eq > 0 && u[e] == thr);
-    }
+    for (int e = 0; e < kItems; ++e) n_eq += (need_eq > 0 && u[e] == thr);
     int eq_rank = 0, eq_total = 0;
     if (need_eq > 0) eq_rank = eq_before + block_exclusive_scan(n_eq, scan_scratch, eq_total);
     bool keep[kItems];
@@ -142,10 +218,8 @@ retain_select_kernel(const float* __restrict__ logits, int64_t total, const int3
 #pragma unroll
     for (int e = 0; e < kItems; ++e) {
       bool kp = false;
-      if (cand[e]) {
-        if (u[e] > thr) kp = true;
-        else if (need_eq > 0 && u[e] == thr) { kp = eq_rank < need_eq; ++eq_rank; }
-      }
+      if (u[e] > thr) kp = true;
+      else if (need_eq > 0 && u[e] == thr) { kp = eq_rank < need_eq; ++eq_rank; }
       keep[e] = kp;
       n_keep += kp;
     }
@@ -154,60 +228,24 @@ retain_select_kernel(const float* __restrict__ logits, int64_t total, const int3
 #pragma unroll
     for (int e = 0; e < kItems; ++e) {
       if (keep[e]) {
-        ret_pos[head * budget + off] = j0 + e;
-        ret_score[head * budget + off] = key[e];
+        a.ret_pos[head * a.budget + off] = j0 + e;
+        a.ret_score[head * a.budget + off] = key_of_order_key(u[e]);
         ++off;
       }
     }
     kept_before += keep_total;
     eq_before += eq_total;
   }
-  if (tid == 0) ret_count[head] = kept_before;
-}
+  if (tid == 0) a.ret_count[head] = kept_before;
 
-// Rows 0..budget-1 of the grid's row space are compact slots, rows budget..budget+window-1 ring slots.
-// Each row is copied in 16-byte pieces (D*sizeof(T) is a multiple of 16 and rows are 16-byte aligned).
-template <typename T>
-__global__ void __launch_bounds__(256)
-cache_fill_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stride_tok, int64_t stride_head, int D,
-                  const float* __restrict__ logits, int64_t total, const int32_t* __restrict__ cu, int Hkv,
-                  int window, int budget, T* __restrict__ k_win, T* __restrict__ v_win,
-                  float* __restrict__ win_score, T* __restrict__ k_ret, T* __restrict__ v_ret,
-                  const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count, int rows_per_block) {
-  const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
-  const int64_t head = (int64_t)b * Hkv + h;
-  const int64_t lo = cu[b];
-  const int n = (int)(cu[b + 1] - lo);
-  const int pieces = D * (int)sizeof(T) / 16;  // 16-byte pieces per row
-  const int rows_per_pass = 256 / pieces;
-  const int sub = threadIdx.x / pieces, piece = threadIdx.x - sub * pieces;
-  const int cnt = ret_count[head];
-  const int row_end = min((int)(blockIdx.y + 1) * rows_per_block, budget + window);
-  for (int r = blockIdx.y * rows_per_block + sub; r < row_end; r += rows_per_pass) {
-    int p;        // source position inside the sequence, or -1
-    T *dk, *dv;
-    if (r < budget) {
-      p = r < cnt ? ret_pos[head * budget + r] : -1;
-      dk = k_ret + (head * budget + r) * D;
-      dv = v_ret + (head * budget + r) * D;
-    } else {
-      const int slot = r - budget;
-      if (n >= window) {
-        const int first = n - window;                    // oldest position in the window
-        int d = (slot - first % window + window) % window;
-        p = first + d;
-      } else {
-        p = slot < n ? slot : -1;
-      }
-      dk = k_win + (head * window + slot) * D;
-      dv = v_win + (head * window + slot) * D;
-      if (p >= 0 && piece == 0) win_score[head * window + slot] = logits[(int64_t)h * total + lo + p];
-    }
-    if (p < 0) continue;
-    const T* sk = k + (lo + p) * stride_tok + (int64_t)h * stride_head;
-    const T* sv = v + (lo + p) * stride_tok + (int64_t)h * stride_head;
-    reinterpret_cast<u32x4*>(dk)[piece] = reinterpret_cast<const u32x4*>(sk)[piece];
-    reinterpret_cast<u32x4*>(dv)[piece] = reinterpret_cast<const u32x4*>(sv)[piece];
+  // ---- gather the kept rows (positions written above by this workgroup) ----
+  __threadfence_block();
+  __syncthreads();
+  for (int i = tid; i < kept_before * pieces; i += kSelThreads) {
+    const int r = i / pieces, pc = i - r * pieces;
+    const int p = a.ret_pos[head * a.budget + r];
+    copy_piece(a, (lo + p) * a.tok_bytes + h * a.head_bytes, a.k_ret + (head * a.budget + r) * a.row_bytes,
+               a.v_ret + (head * a.budget + r) * a.row_bytes, pc);
   }
 }
 
@@ -216,28 +254,24 @@ cache_fill_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stri
 hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k, const void* v, int64_t stride_tok,
                          int64_t stride_head, const SeqView& sv, int rho, const ltea_cache& c, hipStream_t stream) {
   if (sv.n_seqs == 0) return hipSuccess;
+  const int64_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
+  RetainArgs a;
+  a.logits = logits; a.total = sv.total_tokens; a.cu = sv.cu_seqlens; a.Hkv = cfg.Hkv; a.window = cfg.window;
+  a.budget = cfg.budget; a.sink = cfg.sink; a.tau = cfg.tau_logit; a.rho = rho;
+  a.k = static_cast<const char*>(k); a.v = static_cast<const char*>(v);
+  a.tok_bytes = stride_tok * esz; a.head_bytes = stride_head * esz; a.row_bytes = (int)(cfg.D * esz);
+  a.k_win = static_cast<char*>(c.k_win); a.v_win = static_cast<char*>(c.v_win); a.win_score = c.win_score;
+  a.k_ret = static_cast<char*>(c.k_ret); a.v_ret = static_cast<char*>(c.v_ret);
+  a.ret_score = c.ret_score; a.ret_pos = c.ret_pos; a.ret_count = c.ret_count; a.n_seen = c.n_seen;
+  a.n_scored = c.n_scored;
   const unsigned heads = (unsigned)sv.n_seqs * (unsigned)cfg.Hkv;
-  hipLaunchKernelGGL(retain_select_kernel, dim3(heads), dim3(kSelThreads), 0, stream, logits, sv.total_tokens,
-                     sv.cu_seqlens, cfg.Hkv, cfg.window, cfg.budget, cfg.sink, cfg.tau_logit, rho, c.ret_score,
-                     c.ret_pos, c.ret_count, c.n_seen, c.n_scored);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int rows = cfg.budget + cfg.window;
-  const int rows_per_block = 128;
-  dim3 grid(heads, (unsigned)((rows + rows_per_block - 1) / rows_per_block));
-  if (cfg.dtype == LTEA_F32) {
-    hipLaunchKernelGGL(cache_fill_kernel<float>, grid, dim3(256), 0, stream, static_cast<const float*>(k),
-                       static_cast<const float*>(v), stride_tok, stride_head, cfg.D, logits, sv.total_tokens,
-                       sv.cu_seqlens, cfg.Hkv, cfg.window, cfg.budget, static_cast<float*>(c.k_win),
-                       static_cast<float*>(c.v_win), c.win_score, static_cast<float*>(c.k_ret),
-                       static_cast<float*>(c.v_ret), c.ret_pos, c.ret_count, rows_per_block);
-  } else {
-    hipLaunchKernelGGL(cache_fill_kernel<bf16_t>, grid, dim3(256), 0, stream, static_cast<const bf16_t*>(k),
-                       static_cast<const bf16_t*>(v), stride_tok, stride_head, cfg.D, logits, sv.total_tokens,
-                       sv.cu_seqlens, cfg.Hkv, cfg.window, cfg.budget, static_cast<bf16_t*>(c.k_win),
-                       static_cast<bf16_t*>(c.v_win), c.win_score, static_cast<bf16_t*>(c.k_ret),
-                       static_cast<bf16_t*>(c.v_ret), c.ret_pos, c.ret_count, rows_per_block);
-  }
+  const dim3 grid(heads, 1u + (unsigned)((cfg.window + kRingRows - 1) / kRingRows));
+  const int64_t n_out_max = sv.max_seqlen > cfg.window ? sv.max_seqlen - cfg.window : 0;
+  if (n_out_max <= 1 * kChunk) hipLaunchKernelGGL(retain_kernel<1>, grid, dim3(kSelThreads), 0, stream, a);
+  else if (n_out_max <= 2 * kChunk) hipLaunchKernelGGL(retain_kernel<2>, grid, dim3(kSelThreads), 0, stream, a);
+  else if (n_out_max <= 4 * kChunk) hipLaunchKernelGGL(retain_kernel<4>, grid, dim3(kSelThreads), 0, stream, a);
+  else if (n_out_max <= 8 * kChunk) hipLaunchKernelGGL(retain_kernel<8>, grid, dim3(kSelThreads), 0, stream, a);
+  else hipLaunchKernelGGL(retain_kernel<0>, grid, dim3(kSelThreads), 0, stream, a);
   return hipGetLastError();
 }
 
