@@ -177,6 +177,22 @@ int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, co
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* ---- measurement aids (not part of the method; the hot-path entry points above never call them) ----------
+ * What the chip sustains on the two resources the roofline figures are quoted against, so that a report can
+ * give a fraction of the measured ceiling next to the fraction of the datasheet peak.  Both launch
+ * LTEA_DIAG_BLOCKS workgroups of 256 threads on `stream` and return at once; `sink` is device memory of at
+ * least ltea_diag_sink_bytes() bytes that receives per-thread checksums (so the work cannot be elided). */
+#define LTEA_DIAG_BLOCKS 4096
+size_t ltea_diag_sink_bytes(void);
+
+/* Register-resident loop of bf16 32x32x16 MFMAs, 8 per iteration per wave, no memory traffic.  *flops_out
+ * (host, optional) receives the floating-point operations one launch performs. */
+int ltea_diag_mfma_loop(int32_t iters, void *sink, double *flops_out, void *stream);
+
+/* Reads every byte of [src, src+bytes) once with 16-byte loads, one contiguous share per workgroup
+ * (bytes % 16 == 0, src 16-byte aligned). */
+int ltea_diag_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,7 +50,8 @@ class ltea_cache(C.Structure):
 
 
 EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
-           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step"]
+           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_diag_sink_bytes",
+           "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
 
 _lib = None
 
@@ -84,6 +85,12 @@ def lib() -> C.CDLL:
                                P(ltea_cache), vp, vp, sz, vp]
     L.ltea_decode_step.restype = C.c_int
     L.ltea_decode_step.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp, sz, vp]
+    L.ltea_diag_sink_bytes.restype = sz
+    L.ltea_diag_sink_bytes.argtypes = []
+    L.ltea_diag_mfma_loop.restype = C.c_int
+    L.ltea_diag_mfma_loop.argtypes = [i32, vp, P(C.c_double), vp]
+    L.ltea_diag_stream_read.restype = C.c_int
+    L.ltea_diag_stream_read.argtypes = [vp, sz, vp, vp]
     _lib = L
     return L
 
@@ -275,3 +282,22 @@ def ltea_decode_step(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, 
                                   C.byref(cache.struct), B, _ptr(workspace), workspace.numel(), _stream()),
            "ltea_decode_step")
     return out
+
+
+def ltea_diag_sink(device="cuda") -> torch.Tensor:
+    """Device buffer the two measurement aids write their checksums to."""
+    return torch.empty(int(lib().ltea_diag_sink_bytes()), dtype=torch.uint8, device=device)
+
+
+def ltea_diag_mfma_loop(iters: int, sink: torch.Tensor) -> float:
+    """Enqueue the register-resident MFMA loop; returns the flops of the launch."""
+    flops = C.c_double(0.0)
+    _check(lib().ltea_diag_mfma_loop(int(iters), _ptr(sink), C.byref(flops), _stream()), "ltea_diag_mfma_loop")
+    return float(flops.value)
+
+
+def ltea_diag_stream_read(src: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueue one streaming read of `src`; returns the bytes read."""
+    nbytes = src.numel() * src.element_size()
+    _check(lib().ltea_diag_stream_read(_ptr(src), nbytes, _ptr(sink), _stream()), "ltea_diag_stream_read")
+    return nbytes

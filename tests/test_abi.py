@@ -130,3 +130,13 @@ def test_decode_and_prefill_argument_errors():
     assert 0 < a < b
     assert L.ltea_workspace_bytes(C.byref(good_cfg(D=96)), C.byref(cnn), 1, 1000, 1000) == 0
     assert L.ltea_decode_workspace_bytes(C.byref(cfg), C.byref(cnn), 4) > 0
+
+
+def test_diag_argument_errors():
+    L = B.lib()
+    assert L.ltea_diag_sink_bytes() >= 4 * 256
+    assert L.ltea_diag_mfma_loop(0, 0x1000, None, None) == B.LTEA_EINVAL
+    assert L.ltea_diag_mfma_loop(4, None, None, None) == B.LTEA_EINVAL
+    assert L.ltea_diag_stream_read(None, 1024, 0x1000, None) == B.LTEA_EINVAL
+    assert L.ltea_diag_stream_read(0x1000, 1000, 0x1000, None) == B.LTEA_EINVAL   # not a multiple of 16
+    assert L.ltea_diag_stream_read(0x1008, 1024, 0x1000, None) == B.LTEA_EINVAL   # misaligned
