@@ -162,6 +162,15 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
             const bf16x8 b = *reinterpret_cast<const bf16x8*>(b_row + 16 * mc);
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
           }
+          // Issue order inside one tap: operand reads run three MFMAs ahead of their use, so that LDS latency is
+          // covered by matrix work instead of being waited for before every MFMA.
+          __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+          for (int i = 0; i < CH / 16 - 3; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
         }
       }
     }
