@@ -45,6 +45,8 @@ WORKLOAD_TEXT = {
             "+ 1 decode step",
     "varlen": "varlen_prefill_bf16: 16 sequences of 1024..16384 tokens packed, H=16, D=128, window=1024, budget=512, "
               "CNN k=5 C=32, 1% planted near-duplicate keys; + 1 decode step per sequence",
+    "paper": "paper_stack_bf16: B=4 x n=4096, Hq=32 on Hkv=8, D=64, window=768, budget=512, sink=4, CNN 3 x (k=3, "
+             "dilation 2) with 64/32/16 channels, Q,K,V~N(0,1); + 1 decode step per sequence",
 }
 
 
@@ -90,7 +92,7 @@ def bench_prefill(args):
     from paper_2510_20787_amd import workloads as wl
 
     w = {"prefill": wl.config_prefill_bf16, "long": wl.config_long_prefill_bf16,
-         "varlen": wl.config_varlen_prefill_bf16}[args.workload]()
+         "varlen": wl.config_varlen_prefill_bf16, "paper": wl.config_paper_stack_bf16}[args.workload]()
     cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
     c = w.cnn
     cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
@@ -289,8 +291,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--workload", choices=["prefill", "long", "varlen"], default="prefill",
-                    help="prefill = the benchmark configuration (default); long / varlen = the other prefill "
+    ap.add_argument("--workload", choices=["prefill", "long", "varlen", "paper"], default="prefill",
+                    help="prefill = the benchmark configuration (default); long / varlen / paper = the other prefill "
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
     args = ap.parse_args()
     if args.workload != "prefill":

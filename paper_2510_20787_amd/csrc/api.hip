@@ -68,7 +68,9 @@ int check_cache(const ltea_cfg* cfg, const ltea_cache* c, bool need_window) {
 bool use_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn) { return score_mfma_supported(cfg, cnn); }
 
 size_t score_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total) {
-  return align_up(use_score_mfma(cfg, cnn) ? score_mfma_workspace(cfg, cnn) : score_generic_workspace(cfg, cnn, total), 256);
+  if (use_score_mfma(cfg, cnn)) return align_up(score_mfma_workspace(cfg, cnn), 256);
+  if (score_deep_supported(cfg, cnn)) return align_up(score_deep_workspace(cfg, cnn), 256);
+  return align_up(score_generic_workspace(cfg, cnn, total), 256);
 }
 
 int hip_status(hipError_t e) { return e == hipSuccess ? LTEA_OK : LTEA_EHIP; }
@@ -76,6 +78,7 @@ int hip_status(hipError_t e) { return e == hipSuccess ? LTEA_OK : LTEA_EHIP; }
 int do_score(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
              const SeqView& sv, float* logits, void* ws, hipStream_t stream) {
   if (use_score_mfma(cfg, cnn)) return hip_status(launch_score_mfma(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
+  if (score_deep_supported(cfg, cnn)) return hip_status(launch_score_deep(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
   return hip_status(launch_score_generic(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
 }
 

@@ -36,6 +36,14 @@ hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                              void* workspace, hipStream_t stream);
 
+// Multi-layer bf16 path on MFMA (all layers fused, activations in LDS as hi + lo bf16 pairs); the workspace holds
+// every layer's weights re-laid as tap-major panels.
+bool score_deep_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                             int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
+                             void* workspace, hipStream_t stream);
+
 // ---- (b) retention + cache fill -------------------------------------------------------------------
 hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k, const void* v,
                          int64_t stride_tok, int64_t stride_head, const SeqView& sv, int rho,

@@ -296,3 +296,12 @@ def config_varlen_prefill_bf16(seqlens: Optional[Sequence[int]] = None, H: int =
         seqlens = varlen_lengths()
     return make_prefill("varlen_prefill_bf16", 4, "bf16", seqlens, H, H, 128, window=1024, budget=512,
                         cnn_kernel=(5,), cnn_channels=(32,), qkv_scale=1.0, w_std=0.05, plant_fraction=0.01)
+
+
+def config_paper_stack_bf16(n: int = 4096, B: int = 4) -> PrefillWorkload:
+    """The LTE module and mixer shape of the paper's own models (Section 3.1.1, Appendix A): three k=3,
+    dilation-2 convolutions (receptive field 13) halving the channels 2D -> D -> D/2 -> D/4, attention sink of 4,
+    32 query heads sharing 8 KV heads of dimension 64, window 768, budget 512."""
+    return make_prefill("paper_stack_bf16", 5, "bf16", [n] * B, 32, 8, 64, window=768, budget=512, sink=4,
+                        cnn_kernel=(3, 3, 3), cnn_channels=(64, 32, 16), cnn_dilation=(2, 2, 2),
+                        qkv_scale=1.0, w_std=0.05)

@@ -95,6 +95,11 @@ def test_full_long_prefill_bf16():
     run_full_prefill(wl.config_long_prefill_bf16())
 
 
+def test_full_paper_stack_bf16():
+    """The paper's own module shape: 3-layer dilated CNN, sink 4, 32 query heads on 8 KV heads, window 768."""
+    run_full_prefill(wl.config_paper_stack_bf16())
+
+
 def test_full_varlen_prefill_bf16():
     w = wl.config_varlen_prefill_bf16()
     cache, z64 = run_full_prefill(w)

@@ -24,6 +24,8 @@ CASES = {
     "f32_d128_deep": ("f32", [257, 130], 2, 2, 128, 40, 16, 4, 0.0, (3, 3, 3), (32, 16, 8), (2, 2, 2), 1.0, 0.08),
     "bf16_d64": ("bf16", [700, 129, 300], 4, 4, 64, 96, 40, 0, 0.0, (5,), (32,), None, 0.125, 0.05),
     "bf16_d128_gqa": ("bf16", [513, 64, 391], 8, 2, 128, 128, 48, 4, 0.0, (7,), (32,), None, 1.0, 0.05),
+    "bf16_d64_deep": ("bf16", [700, 129, 300, 5], 8, 2, 64, 96, 40, 4, 0.0, (3, 3, 3), (64, 32, 16), (2, 2, 2), 1.0, 0.05),
+    "bf16_d128_deep2": ("bf16", [260, 131], 2, 2, 128, 64, 24, 0, 0.0, (5, 3), (32, 16), (1, 2), 1.0, 0.05),
     "bf16_topb": ("bf16", [600], 2, 2, 64, 64, 33, 0, -np.inf, (5,), (32,), None, 1.0, 0.05),
     "bf16_budget0": ("bf16", [300, 90], 2, 2, 64, 64, 0, 3, 0.0, (5,), (16,), None, 1.0, 0.05),
     "bf16_window_ge_n": ("bf16", [100, 128], 2, 2, 128, 128, 16, 0, 0.0, (5,), (32,), None, 1.0, 0.05),
