@@ -118,16 +118,9 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (work >= n_work) return;
   const int hq = work / tiles_upper;
-  int tile = work - hq * tiles_upper;
-  int s = 0, n = 0;
-  for (; s < n_seqs; ++s) {
-    n = cu[s + 1] - cu[s];
-    const int nt = (n + BM - 1) / BM;
-    if (tile < nt) break;
-    tile -= nt;
-  }
-  if (s == n_seqs) return;
-  const int64_t lo = cu[s];
+  int tile, s, n, lo32;
+  if (!locate_tile(cu, n_seqs, BM, work - hq * tiles_upper, s, tile, lo32, n)) return;
+  const int64_t lo = lo32;
   const int h = hq / (Hq / Hkv);
   const int64_t head = (int64_t)s * Hkv + h;
   const int i0 = tile * BM;

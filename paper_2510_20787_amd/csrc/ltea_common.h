@@ -66,4 +66,41 @@ __device__ __forceinline__ int find_sequence(const int32_t* __restrict__ cu, int
   return lo;
 }
 
+// Which sequence owns flat tile `flat`, when sequence i owns ceil(len_i / tile_len) consecutive tiles?  Called by
+// every lane of a wave with the same arguments (full exec).  The lengths are read 64 sequences at a time with one
+// vector load each for cu[i] and cu[i+1] and resolved with a wave prefix sum, so the search costs one trip to
+// memory per 64 sequences instead of one per sequence.  Returns false if `flat` is past the last tile.
+__device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int n_seqs, int tile_len, int flat,
+                                            int& seq, int& tile, int& lo, int& len) {
+  const int lane = threadIdx.x & (kWave - 1);
+  int before = 0;   // tiles owned by the sequences of earlier rounds
+  for (int s0 = 0; s0 < n_seqs; s0 += kWave) {
+    const int i = s0 + lane;
+    const int ic = i < n_seqs ? i : n_seqs - 1;      // unconditional loads, inactive lanes count zero tiles
+    const int a = cu[ic], b = cu[ic + 1];
+    const int nt = i < n_seqs ? (b - a + tile_len - 1) / tile_len : 0;
+    int inc = nt;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int t = __shfl_up(inc, off, kWave);
+      if (lane >= off) inc += t;
+    }
+    const int total = __builtin_amdgcn_readfirstlane(__shfl(inc, kWave - 1, kWave));
+    if (flat < before + total) {
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(inc > flat - before);
+      const int l = __builtin_ctzll(m);
+      // the results are wave-uniform: hand them back in scalar registers so that everything derived from them
+      // (loop bounds, buffer descriptors) stays scalar
+      seq = s0 + l;
+      lo = __builtin_amdgcn_readfirstlane(__shfl(a, l, kWave));
+      len = __builtin_amdgcn_readfirstlane(__shfl(b, l, kWave)) - lo;
+      tile = flat - before -
+             __builtin_amdgcn_readfirstlane(__shfl(inc, l, kWave) - __shfl(nt, l, kWave));
+      return true;
+    }
+    before += total;
+  }
+  return false;
+}
+
 }  // namespace ltea

@@ -66,15 +66,9 @@ score_deep_kernel(const DeepArgs a) {
   bf16_t* lds = reinterpret_cast<bf16_t*>(smem);
 
   const int h = blockIdx.y;
-  int tile = blockIdx.x, s = 0, n = 0;
-  for (; s < a.n_seqs; ++s) {
-    n = a.cu[s + 1] - a.cu[s];
-    const int nt = (n + a.TM - 1) / a.TM;
-    if (tile < nt) break;
-    tile -= nt;
-  }
-  if (s == a.n_seqs) return;
-  const int64_t lo = a.cu[s];
+  int tile, s, n, lo32;
+  if (!locate_tile(a.cu, a.n_seqs, a.TM, blockIdx.x, s, tile, lo32, n)) return;
+  const int64_t lo = lo32;
   const int j0 = tile * a.TM;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
   const int row = 32 * wv + ql;             // this lane's position index inside every layer's 128

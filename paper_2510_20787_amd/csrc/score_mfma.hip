@@ -66,15 +66,9 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   bf16_t* w_lds = x_lds + (size_t)kTileRows * XS;  // ks panels of CP x XS (all taps of the current chunk)
 
   const int h = blockIdx.y;
-  int grp = blockIdx.x, s = 0, n = 0;
-  for (; s < n_seqs; ++s) {
-    n = cu[s + 1] - cu[s];
-    const int ng = (n + NT * TM - 1) / (NT * TM);
-    if (grp < ng) break;
-    grp -= ng;
-  }
-  if (s == n_seqs) return;
-  const int64_t lo = cu[s];
+  int grp, s, n, lo32;
+  if (!locate_tile(cu, n_seqs, NT * TM, blockIdx.x, s, grp, lo32, n)) return;
+  const int64_t lo = lo32;
   const int g0 = grp * NT * TM;                      // first token of this workgroup's NT tiles
   int n_tiles = (n - g0 + TM - 1) / TM;
   n_tiles = n_tiles < NT ? n_tiles : NT;
