@@ -544,12 +544,21 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
   // h == 0 workgroup while other workgroups of the same sequence may still be starting.
   const int t = ws_t[b];
   const int slot = t % window;
+  // Everything that does not depend on the eviction decision is requested first, so that the loads of the
+  // decision, of the split partials and of the two rows that move are all in flight together.
+  T* kw = static_cast<T*>(C.k_win) + (head * window + slot) * D;
+  T* vw = static_cast<T*>(C.v_win) + (head * window + slot) * D;
+  constexpr int pieces = D * (int)sizeof(T) / 16;
+  const bool moves_k = tid < pieces, moves_v = tid >= pieces && tid < 2 * pieces;
+  const int pc = moves_k ? tid : (moves_v ? tid - pieces : 0);
+  u32x4 old_piece = {0u, 0u, 0u, 0u}, new_piece = {0u, 0u, 0u, 0u};
+  if (moves_k || moves_v) {
+    old_piece = reinterpret_cast<const u32x4*>(moves_k ? kw : vw)[pc];
+    new_piece = reinterpret_cast<const u32x4*>((moves_k ? k_new : v_new) + head * D)[pc];
+  }
   const int cnt_old = budget > 0 ? C.ret_count[head] : 0;
   const float z_e = t >= window ? C.win_score[head * window + slot] : 0.f;
   const float z_new = t - rho >= 0 ? ws_logit[head] : 0.f;
-  __syncthreads();  // every thread holds z_e before the slot's logit can be overwritten (rho == 0)
-  const int dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
-                                  C.ret_pos + head * budget, red64, &slot_lds);
 
   // ---- merge split partials of the group's query heads ------------------------------------------------------
   const int G = P.Hq / Hkv, nsplit = P.nsplit;
@@ -570,15 +579,15 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
     out[bh * D + d] = from_f32<T>(A / L);
   }
 
+  __syncthreads();  // every thread holds z_e and the old ring row before anything of this head is overwritten
+  const int dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
+                                  C.ret_pos + head * budget, red64, &slot_lds);
+
   // ---- cache update: evicted row -> compact slot dst, then token t -> ring slot ------------------------------
-  T* kw = static_cast<T*>(C.k_win) + (head * window + slot) * D;
-  T* vw = static_cast<T*>(C.v_win) + (head * window + slot) * D;
-  constexpr int pieces = D * (int)sizeof(T) / 16;
   if (dst >= 0) {
     T* kr = static_cast<T*>(C.k_ret) + (head * budget + dst) * D;
     T* vr = static_cast<T*>(C.v_ret) + (head * budget + dst) * D;
-    if (tid < pieces) reinterpret_cast<u32x4*>(kr)[tid] = reinterpret_cast<const u32x4*>(kw)[tid];
-    else if (tid < 2 * pieces) reinterpret_cast<u32x4*>(vr)[tid - pieces] = reinterpret_cast<const u32x4*>(vw)[tid - pieces];
+    if (moves_k || moves_v) reinterpret_cast<u32x4*>(moves_k ? kr : vr)[pc] = old_piece;
     if (tid == 0) {
       const int e_pos = t - window;
       C.ret_score[head * budget + dst] = select_key(z_e, e_pos, P.sink);
@@ -586,9 +595,7 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
       if (dst == cnt_old) C.ret_count[head] = cnt_old + 1;
     }
   }
-  __syncthreads();  // the old ring row has been read
-  if (tid < pieces) reinterpret_cast<u32x4*>(kw)[tid] = reinterpret_cast<const u32x4*>(k_new + head * D)[tid];
-  else if (tid < 2 * pieces) reinterpret_cast<u32x4*>(vw)[tid - pieces] = reinterpret_cast<const u32x4*>(v_new + head * D)[tid - pieces];
+  if (moves_k || moves_v) reinterpret_cast<u32x4*>(moves_k ? kw : vw)[pc] = new_piece;
   if (tid == 0) {
     if (t - rho >= 0) C.win_score[head * window + ((t - rho) % window)] = z_new;
     if (h == 0) {
