@@ -19,8 +19,8 @@
 // and its A operand (eight consecutive keys of one column per lane) comes out of the transposing LDS load
 // ds_read_b64_tr_b16, two per MFMA; the tile's 64-byte chunks are XOR-swizzled so that those loads and the
 // staging stores spread over the 64 banks without padding.
-// K/V tiles are double-buffered in LDS and prefetched through registers (two tiles ahead for D = 64, one for
-// D = 128 where registers are short), one barrier per tile.  The running maximum is only raised when a block of
+// K/V tiles are double-buffered in LDS and prefetched one tile ahead through registers, one barrier per tile
+// (D = 64 is held to 128 VGPRs so that four workgroups share a CU; D = 128 runs two).  The running maximum is only raised when a block of
 // scores exceeds it by more than 2^8 (the result does not depend on the stabiliser), which keeps the accumulator
 // rescale off the common path.  Inside a tile the matrix work of one 32-key block is placed next to the
 // exponentials of the other, so that they overlap within the wave's in-order instruction stream.
@@ -96,7 +96,7 @@ template <int D> struct TileRegs {
 };
 
 template <int D, int QB>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kThreads, D == 64 ? 4 : 2)
 attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, const bf16_t* __restrict__ k,
                       const bf16_t* __restrict__ v, int64_t kv_st, int64_t kv_sh, const int32_t* __restrict__ cu,
                       int n_seqs, int tiles_upper, int n_work, int Hq, int Hkv, int window, int budget,
@@ -312,12 +312,23 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const float m_use = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
-        float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float p = __builtin_amdgcn_exp2f(fmaf(scs[qb][r], scale_log2e, -m_use));
-          if (r & 1) psum1 += p; else psum0 += p;
           pb[qb][r / 8][r % 8] = static_cast<bf16_t>(p);
+        }
+        // Row sum from the rounded probabilities, two per instruction (v_dot2c_f32_bf16 with a vector of ones):
+        // the denominator then matches the bf16 P that the second MFMA consumes.
+        bf16x2 ones;
+        ones[0] = static_cast<bf16_t>(1.0f); ones[1] = static_cast<bf16_t>(1.0f);
+        float psum0 = 0.f, psum1 = 0.f;
+#pragma unroll
+        for (int r2 = 0; r2 < 8; r2 += 2) {
+          bf16x2 e0, e1;
+          e0[0] = pb[qb][r2 / 4][(2 * r2) % 8]; e0[1] = pb[qb][r2 / 4][(2 * r2) % 8 + 1];
+          e1[0] = pb[qb][r2 / 4][(2 * r2) % 8 + 2]; e1[1] = pb[qb][r2 / 4][(2 * r2) % 8 + 3];
+          psum0 = __builtin_amdgcn_fdot2_f32_bf16(e0, ones, psum0, false);
+          psum1 = __builtin_amdgcn_fdot2_f32_bf16(e1, ones, psum1, false);
         }
         l_part[qb] += psum0 + psum1;
         // Pin the packed probabilities here: without a use in this block the compiler sinks the exponentials
@@ -357,11 +368,10 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 
   // ---- software pipeline: tile t is computed from LDS buffer t&1 while tile t+1 is being stored into the other
   // buffer and tile t+2 is in flight from global memory --------------------------------------------------------
-  constexpr int kAhead = D == 64 ? 2 : 1;   // tiles in flight from global memory
-  auto step = [&](int t, TR& R) {   // R holds tile t+1 on entry and tile t+1+kAhead on exit
+  auto step = [&](int t, TR& R) {   // R holds tile t+1 on entry and tile t+2 on exit
     __syncthreads();   // tile t is in LDS; everyone is done with tile t-1 (whose buffer is overwritten next)
     if (t + 1 < n_tiles) store_tile(t + 1, R);
-    if (t + 1 + kAhead < n_tiles) load_tile(t + 1 + kAhead, R);
+    if (t + 2 < n_tiles) load_tile(t + 2, R);
     const bf16_t* buf = lds + (t & 1) * kBuf;
     // classify the tile for this wave: -1 skip, 0 every (query, key) pair valid, 1 window-edge mask, 2 retained mask
     int mode = -1, jt = 0;
@@ -382,19 +392,11 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     mode = __builtin_amdgcn_readfirstlane(mode);
     if (mode >= 0) compute(mode, buf, pos_lds[t & 1], jt);
   };
-  TR regs_a, regs_b;
-  load_tile(0, regs_a);
-  store_tile(0, regs_a);
-  if (n_tiles > 1) load_tile(1, regs_a);
-  if constexpr (kAhead == 2) {
-    if (n_tiles > 2) load_tile(2, regs_b);
-    for (int t = 0; t < n_tiles; t += 2) {
-      step(t, regs_a);
-      if (t + 1 < n_tiles) step(t + 1, regs_b);
-    }
-  } else {
-    for (int t = 0; t < n_tiles; ++t) step(t, regs_a);
-  }
+  TR regs;
+  load_tile(0, regs);
+  store_tile(0, regs);
+  if (n_tiles > 1) load_tile(1, regs);
+  for (int t = 0; t < n_tiles; ++t) step(t, regs);
 
   // ---- epilogue: normalise, stage through LDS, store rows coalesced -------------------------------------------
   __syncthreads();  // tile buffers are free
