@@ -51,10 +51,11 @@ diag_read_kernel(const u32x4* __restrict__ src, size_t pieces, uint32_t* __restr
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const size_t j = i + (size_t)u * kDiagThreads;
-      x[u] = src[j < end ? j : i];     // the tail re-reads a piece it already has instead of branching
+      x[u] = src[j < end ? j : i];     // past the share: re-read a piece it already has (not counted) instead of branching
     }
 #pragma unroll
-    for (int u = 0; u < U; ++u) s += x[u][0] ^ x[u][1] ^ x[u][2] ^ x[u][3];
+    for (int u = 0; u < U; ++u)
+      s += (i + (size_t)u * kDiagThreads < end) ? (x[u][0] ^ x[u][1] ^ x[u][2] ^ x[u][3]) : 0u;
   }
   sink[(size_t)blockIdx.x * kDiagThreads + threadIdx.x] = s;
 }

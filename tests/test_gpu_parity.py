@@ -282,3 +282,27 @@ def test_decode_from_empty_cache(dtype, D):
         ref = np.stack([orc.decode_step(states[s], q3[s, t], k3[s, t], v3[s, t], cfg, cnn) for s in range(B_)])
         check_output(out, ref, dtype, f"step {t}")
         compare_state(cache, states, w, t)
+
+
+# ------------------------------------------------------------------------------------------------
+# measurement aids: they must run, report the work they did and leave a checksum for every thread
+def test_diag_probes():
+    sink = B.ltea_diag_sink()
+    sink.zero_()
+    flops = B.ltea_diag_mfma_loop(50, sink)
+    torch.cuda.synchronize()
+    blocks = sink.numel() // (256 * 4)
+    assert flops == blocks * 4 * 50 * 8 * 2.0 * 32 * 32 * 16
+    got = sink.view(torch.float32)
+    # every lane accumulates 16 identical products per MFMA row: the per-thread sums are positive and finite
+    assert bool(torch.isfinite(got).all()) and float(got.min()) > 0.0
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    sink.zero_()
+    nbytes = B.ltea_diag_stream_read(src, sink)
+    torch.cuda.synchronize()
+    assert nbytes == 4 << 20
+    # every 16-byte piece is read exactly once: the per-thread checksums add up to the sum over all pieces
+    pieces = src.view(-1, 4).to(torch.int64)
+    expect = int((pieces[:, 0] ^ pieces[:, 1] ^ pieces[:, 2] ^ pieces[:, 3]).sum().item()) & 0xFFFFFFFF
+    total = int(sink.view(torch.int32).to(torch.int64).bitwise_and(0xFFFFFFFF).sum().item()) & 0xFFFFFFFF
+    assert total == expect
