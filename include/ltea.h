@@ -177,6 +177,22 @@ int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, co
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* Continues a prefill on an existing cache state (the chunked / multi-token form of (a)+(b)+(c)): sequence s of
+ * `cache` holds n_seen[s] tokens (from ltea_prefill, ltea_decode_step or an earlier call of this function) and
+ * receives cu_new[s+1] - cu_new[s] >= 0 new tokens (q, k, v: packed views as in ltea_prefill; out: contiguous
+ * [total_new][Hq][D]).  Outputs and the final state equal those rows and that state of one ltea_prefill over the
+ * whole history: new queries see their window plus the final capped retained set restricted to positions that have
+ * left their window; the retained set is re-selected among the old retained entries and the tokens that leave the
+ * window now (tokens dropped earlier stay dropped, which is what a one-shot prefill would also have decided).
+ * Implemented for cfg->dtype == LTEA_BF16 (LTEA_EUNSUPPORTED otherwise).  Workspace: ltea_append_workspace_bytes. */
+size_t ltea_append_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_new,
+                                   int32_t max_new);
+int ltea_prefill_append(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
+                        int64_t q_stride_head, const void *k, const void *v, int64_t kv_stride_tok,
+                        int64_t kv_stride_head, const int32_t *cu_new, int32_t n_seqs, int64_t total_new,
+                        int32_t max_new, void *out, const ltea_cache *cache, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
 /* ---- measurement aids (not part of the method; the hot-path entry points above never call them) ----------
  * What the chip sustains on the two resources the roofline figures are quoted against, so that a report can
  * give a fraction of the measured ceiling next to the fraction of the datasheet peak.  Both launch

@@ -50,7 +50,8 @@ class ltea_cache(C.Structure):
 
 
 EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
-           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_diag_sink_bytes",
+           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_append_workspace_bytes",
+           "ltea_prefill_append", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
 
 _lib = None
@@ -85,6 +86,11 @@ def lib() -> C.CDLL:
                                P(ltea_cache), vp, vp, sz, vp]
     L.ltea_decode_step.restype = C.c_int
     L.ltea_decode_step.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp, sz, vp]
+    L.ltea_append_workspace_bytes.restype = sz
+    L.ltea_append_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
+    L.ltea_prefill_append.restype = C.c_int
+    L.ltea_prefill_append.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp,
+                                      P(ltea_cache), vp, sz, vp]
     L.ltea_diag_sink_bytes.restype = sz
     L.ltea_diag_sink_bytes.argtypes = []
     L.ltea_diag_mfma_loop.restype = C.c_int
@@ -267,6 +273,29 @@ def ltea_prefill(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: t
     _check(lib().ltea_prefill(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
                               _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), C.byref(cache.struct), _ptr(logits),
                               _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill")
+    return out
+
+
+def ltea_append_workspace_bytes(cfg: ltea_cfg, cnn: Cnn, n_seqs: int, total_new: int, max_new: int) -> int:
+    return int(lib().ltea_append_workspace_bytes(C.byref(cfg), C.byref(cnn.struct), n_seqs, total_new, max_new))
+
+
+def ltea_prefill_append(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                        cu_new: torch.Tensor, max_new: int, cache: Cache, out: Optional[torch.Tensor] = None,
+                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Continue a prefill: q, k, v hold the new tokens of every sequence, packed by cu_new."""
+    T = q.shape[0]
+    n_seqs = cu_new.numel() - 1
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    if out is None:
+        out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = _workspace(max(ltea_append_workspace_bytes(cfg, cnn, n_seqs, T, max_new), 16), q.device)
+    _check(lib().ltea_prefill_append(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
+                                     _ptr(cu_new), n_seqs, T, max_new, _ptr(out), C.byref(cache.struct),
+                                     _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill_append")
     return out
 
 

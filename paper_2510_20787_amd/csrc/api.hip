@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <limits.h>
+
 #include "ltea_kernels.h"
 
 using namespace ltea;
@@ -218,6 +220,67 @@ int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_
   if (st != LTEA_OK) return st;
   if (total_tokens == 0) return LTEA_OK;
   return do_attention(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, *cache, out, s);
+}
+
+size_t ltea_append_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs, int64_t total_new,
+                                   int32_t max_new) {
+  (void)max_new;
+  if (check_cfg(cfg) != LTEA_OK || !cnn || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0 || total_new < 0) return 0;
+  const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
+  return align_up(append_workspace(*cfg, n_seqs, total_new), 256) + score_workspace(*cfg, *cnn, ext);
+}
+
+int ltea_prefill_append(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok,
+                        int64_t q_stride_head, const void* k, const void* v, int64_t kv_stride_tok,
+                        int64_t kv_stride_head, const int32_t* cu_new, int32_t n_seqs, int64_t total_new,
+                        int32_t max_new, void* out, const ltea_cache* cache, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_seqs(cu_new, n_seqs, total_new, max_new);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (n_seqs == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if (total_new > 0) {
+    if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (!out || !aligned16(out)) return LTEA_EINVAL;
+  }
+  const int64_t ext_stride_tok = (int64_t)cfg->Hkv * cfg->D;
+  const int64_t ext_len_max = (int64_t)cfg->budget + 2 * (int64_t)cfg->window + max_new;
+  if (ext_len_max > INT32_MAX / 2) return LTEA_EUNSUPPORTED;
+  // the continuation's attention stage exists on the bf16 MFMA path only
+  if (!attention_mfma_supported(*cfg, ext_stride_tok, (int32_t)ext_len_max)) return LTEA_EUNSUPPORTED;
+  const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
+  const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new), 256);
+  const size_t need = build_ws + score_workspace(*cfg, *cnn, ext);
+  if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int rho = cnn_rho(cnn);
+  AppendBuffers buf;
+  st = hip_status(launch_append_build(*cfg, k, v, kv_stride_tok, kv_stride_head, cu_new, n_seqs, total_new, max_new,
+                                      *cache, workspace, &buf, s));
+  if (st != LTEA_OK) return st;
+  SeqView sv_ext{buf.cu_ext, n_seqs, buf.total_ext, buf.max_ext_len};
+  st = do_score(*cfg, *cnn, buf.ext_k, buf.ext_v, ext_stride_tok, cfg->D, sv_ext, buf.ext_logits,
+                static_cast<char*>(workspace) + build_ws, s);
+  if (st != LTEA_OK) return st;
+  st = hip_status(launch_append_keys(*cfg, n_seqs, total_new, *cache, rho, workspace, buf, s));
+  if (st != LTEA_OK) return st;
+  ltea_cfg sel = *cfg;
+  sel.sink = 0;     // sinks already carry the key +inf in the extended sequence
+  st = hip_status(launch_retain(sel, buf.ext_logits, buf.ext_k, buf.ext_v, ext_stride_tok, cfg->D, sv_ext, rho, *cache, s));
+  if (st != LTEA_OK) return st;
+  st = hip_status(launch_append_fixup(*cfg, cu_new, n_seqs, total_new, *cache, rho, workspace, s));
+  if (st != LTEA_OK) return st;
+  if (total_new == 0) return LTEA_OK;
+  ltea_cache local = *cache;
+  local.ret_pos = buf.local_pos;
+  SeqView sv_q{cu_new, n_seqs, total_new, max_new};
+  return hip_status(launch_attention_mfma(*cfg, q, q_stride_tok, q_stride_head, buf.ext_k, buf.ext_v, ext_stride_tok,
+                                          cfg->D, sv_q, local, out, s, buf.kv_start, buf.kv_len));
 }
 
 int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, const void* k, const void* v, void* out,

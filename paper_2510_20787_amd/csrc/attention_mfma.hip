@@ -102,7 +102,8 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
                       int n_seqs, int tiles_upper, int n_work, int Hq, int Hkv, int window, int budget,
                       float scale_log2e, const bf16_t* __restrict__ k_ret, const bf16_t* __restrict__ v_ret,
                       const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count,
-                      bf16_t* __restrict__ out) {
+                      bf16_t* __restrict__ out, const int32_t* __restrict__ kv_start,
+                      const int32_t* __restrict__ kv_len) {
   using G = Geo<D, QB>;
   using TR = TileRegs<D>;
   constexpr int BM = G::BM, KS = G::KS, VS = G::VS, kBuf = G::kBuf;
@@ -118,12 +119,22 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (work >= n_work) return;
   const int hq = work / tiles_upper;
-  int tile, s, n, lo32;
-  if (!locate_tile(cu, n_seqs, BM, work - hq * tiles_upper, s, tile, lo32, n)) return;
-  const int64_t lo = lo32;
+  // cu packs the query / output rows.  Normally it packs the keys as well; with kv_start / kv_len given, the keys
+  // of sequence s are rows kv_start[s] .. kv_start[s] + kv_len[s] - 1 of k / v and the queries are the last
+  // cu[s+1] - cu[s] positions of that key sequence (continuation of a prefill).
+  int tile, s, n, lo_q;
+  if (!locate_tile(cu, n_seqs, BM, work - hq * tiles_upper, s, tile, lo_q, n)) return;
+  int64_t lo = lo_q;
+  int q_begin = 0;
+  if (kv_start != nullptr) {
+    const int nq = n;
+    lo = kv_start[s];
+    n = kv_len[s];
+    q_begin = n - nq;
+  }
   const int h = hq / (Hq / Hkv);
   const int64_t head = (int64_t)s * Hkv + h;
-  const int i0 = tile * BM;
+  const int i0 = q_begin + tile * BM;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -137,7 +148,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   for (int qb = 0; qb < QB; ++qb) {
     const int qi = r0 + 32 * qb + ql;
     const int qc = qi < n ? qi : n - 1;
-    const bf16_t* qrow = q + (lo + qc) * q_st + (int64_t)hq * q_sh;
+    const bf16_t* qrow = q + (int64_t)(lo_q + qc - q_begin) * q_st + (int64_t)hq * q_sh;
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) qreg[qb][ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * hb);
   }
@@ -416,7 +427,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   }
   __syncthreads();
   {
-    bf16_t* obase = out + ((lo + i0) * Hq + hq) * D;
+    bf16_t* obase = out + ((int64_t)(lo_q + i0 - q_begin) * Hq + hq) * D;
     const int64_t orow_stride = (int64_t)Hq * D;
 #pragma unroll
     for (int p = 0; p < BM / G::RPP; ++p) {
@@ -430,7 +441,8 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 
 template <int D, int QB>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
-               int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream) {
+               int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out,
+               const int32_t* kv_start, const int32_t* kv_len, hipStream_t stream) {
   constexpr int BM = Geo<D, QB>::BM;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   const int64_t tiles_upper = (sv.total_tokens + BM - 1) / BM + sv.n_seqs;
@@ -441,7 +453,7 @@ hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, c
                      static_cast<const bf16_t*>(v), kv_st, kv_sh, sv.cu_seqlens, sv.n_seqs, (int)tiles_upper,
                      (int)n_work, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale * 1.4426950408889634f,
                      static_cast<const bf16_t*>(c.k_ret), static_cast<const bf16_t*>(c.v_ret), c.ret_pos, c.ret_count,
-                     static_cast<bf16_t*>(out));
+                     static_cast<bf16_t*>(out), kv_start, kv_len);
   return hipGetLastError();
 }
 
@@ -455,10 +467,10 @@ bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_
 
 hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c,
-                                 void* out, hipStream_t stream) {
+                                 void* out, hipStream_t stream, const int32_t* kv_start, const int32_t* kv_len) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream)
-                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, stream);
+  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, stream)
+                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, stream);
 }
 
 }  // namespace ltea

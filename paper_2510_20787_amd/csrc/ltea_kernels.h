@@ -54,9 +54,37 @@ hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t 
                                     const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
                                     const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
 bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_t max_seqlen);
+// sv packs the query / output rows.  With kv_start / kv_len (device, per sequence) the keys of sequence s are rows
+// kv_start[s] .. +kv_len[s]-1 of k / v and its queries are the last positions of that key sequence; without
+// them sv packs the keys too.
 hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                  const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
-                                 const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
+                                 const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream,
+                                 const int32_t* kv_start = nullptr, const int32_t* kv_len = nullptr);
+
+// ---- continuation of a prefill onto an existing cache ---------------------------------------------------
+// Device buffers of the "extended sequences" (pad | old kept entries by position | ring tokens | new tokens) that
+// the scoring, retention and attention launchers are then pointed at.
+struct AppendBuffers {
+  void* ext_k; void* ext_v;      // [total_ext][Hkv][D]
+  float* ext_logits;             // [Hkv][total_ext]
+  const int32_t* cu_ext;         // [n_seqs + 1]
+  const int32_t* kv_start;       // first ring row of each sequence in the extended buffers
+  const int32_t* kv_len;         // ring + new tokens of each sequence
+  int32_t* local_pos;            // kept positions in the ring + new frame, [n_seqs][Hkv][budget]
+  int64_t total_ext;             // row count the buffers are sized for (an upper bound of cu_ext[n_seqs])
+  int32_t max_ext_len;           // upper bound of one extended sequence
+};
+int64_t append_ext_tokens(const ltea_cfg& cfg, int n_seqs, int64_t total_new);
+size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new);
+hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const void* v_new, int64_t stride_tok,
+                               int64_t stride_head, const int32_t* cu_new, int n_seqs, int64_t total_new,
+                               int32_t max_new, const ltea_cache& cache, void* workspace, AppendBuffers* out,
+                               hipStream_t stream);
+hipError_t launch_append_keys(const ltea_cfg& cfg, int n_seqs, int64_t total_new, const ltea_cache& cache, int rho,
+                              void* workspace, const AppendBuffers& buf, hipStream_t stream);
+hipError_t launch_append_fixup(const ltea_cfg& cfg, const int32_t* cu_new, int n_seqs, int64_t total_new,
+                               const ltea_cache& cache, int rho, void* workspace, hipStream_t stream);
 
 // ---- (d) decode step -------------------------------------------------------------------------------
 int decode_num_splits(const ltea_cfg& cfg, int n_seqs);

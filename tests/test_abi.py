@@ -140,3 +140,30 @@ def test_diag_argument_errors():
     assert L.ltea_diag_stream_read(None, 1024, 0x1000, None) == B.LTEA_EINVAL
     assert L.ltea_diag_stream_read(0x1000, 1000, 0x1000, None) == B.LTEA_EINVAL   # not a multiple of 16
     assert L.ltea_diag_stream_read(0x1008, 1024, 0x1000, None) == B.LTEA_EINVAL   # misaligned
+
+
+def test_append_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    cache = B.ltea_cache()
+    for name, _ in cache._fields_:
+        setattr(cache, name, 0x1000)
+    args = lambda **kw: dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), q=0x1000, qst=256, qsh=64, k=0x1000, v=0x1000,
+                                  st=128, sh=64, cu=0x1000, n_seqs=1, total=32, max_new=32, out=0x1000,
+                                  cache=C.byref(cache), ws=0x1000, ws_bytes=1 << 40, stream=None), **kw)
+    call = lambda a: L.ltea_prefill_append(a["cfg"], a["cnn"], a["q"], a["qst"], a["qsh"], a["k"], a["v"], a["st"],
+                                           a["sh"], a["cu"], a["n_seqs"], a["total"], a["max_new"], a["out"],
+                                           a["cache"], a["ws"], a["ws_bytes"], a["stream"])
+    assert call(args(cfg=None)) == B.LTEA_EINVAL
+    assert call(args(cnn=None)) == B.LTEA_EINVAL
+    assert call(args(cu=None)) == B.LTEA_EINVAL
+    assert call(args(q=None)) == B.LTEA_EINVAL
+    assert call(args(out=None)) == B.LTEA_EINVAL
+    assert call(args(cache=None)) == B.LTEA_EINVAL
+    assert call(args(ws=None)) == B.LTEA_EWORKSPACE
+    assert call(args(ws_bytes=16)) == B.LTEA_EWORKSPACE
+    assert call(args(n_seqs=0, total=0, max_new=0)) == B.LTEA_OK          # nothing to do
+    f32 = good_cfg(dtype="f32")
+    assert call(args(cfg=C.byref(f32))) == B.LTEA_EUNSUPPORTED            # continuation exists on the bf16 path only
+    assert L.ltea_append_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 32, 32) > 0
+    assert L.ltea_append_workspace_bytes(None, C.byref(cnn), 1, 32, 32) == 0

@@ -1,0 +1,166 @@
+"""GPU parity of ltea_prefill_append: continuing a prefill on an existing cache state must give the rows and
+the final state of one oracle prefill over the whole history (the kept set is nested in the prefix length, so
+re-selecting among the old kept entries and the tokens that leave the window now is the same as selecting among
+everything).  The history is cut at several points: inside the window, exactly at it, far beyond it, in more than
+one chunk, after decode steps (compact segment no longer ordered), with empty chunks for some sequences."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import LOGIT_TOL, OUT_TOL, check_sets, dev, to_np
+from tests.helpers import oracle_cfg, oracle_cnn
+
+pytestmark = pytest.mark.gpu
+
+
+def pack(x, cu, cuts_lo, cuts_hi):
+    """Rows [cuts_lo[s], cuts_hi[s]) of every sequence, packed."""
+    parts = [x[int(cu[s]) + cuts_lo[s]: int(cu[s]) + cuts_hi[s]] for s in range(len(cu) - 1)]
+    return np.ascontiguousarray(np.concatenate(parts, axis=0)) if parts else x[:0]
+
+
+def cu_of(lens):
+    cu = np.zeros(len(lens) + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    return cu
+
+
+CASES = {
+    # name: (seqlens, Hq, Hkv, D, window, budget, sink, tau, kernel, channels, dilation, list of cut fractions)
+    "d64": ([700, 129, 300, 40], 4, 2, 64, 96, 40, 0, 0.0, (5,), (32,), None, [0.5]),
+    "d64_chunks": ([900, 257], 4, 4, 64, 64, 24, 2, 0.0, (5,), (32,), None, [0.2, 0.55, 0.8]),
+    "d128_gqa_sink": ([513, 391, 70], 8, 2, 128, 128, 48, 4, 0.0, (7,), (32,), None, [0.6]),
+    "d64_deep": ([600, 333], 8, 2, 64, 96, 40, 4, 0.0, (3, 3, 3), (64, 32, 16), (2, 2, 2), [0.1, 0.7]),
+    "d64_topb": ([640], 2, 2, 64, 64, 33, 0, -np.inf, (5,), (32,), None, [0.3, 0.31]),
+    "d64_budget0": ([300, 200], 2, 2, 64, 64, 0, 3, 0.0, (5,), (16,), None, [0.5]),
+}
+
+
+def make(name):
+    lens, Hq, Hkv, D, w, b, s, tau, ker, ch, dil, cuts = CASES[name]
+    work = wl.make_prefill(name, 7000 + sum(map(ord, name)), "bf16", lens, Hq, Hkv, D, w, b, s, tau,
+                           cnn_kernel=ker, cnn_channels=ch, cnn_dilation=dil, qkv_scale=1.0, w_std=0.05)
+    return work, cuts
+
+
+def device_setup(w):
+    cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
+    c = w.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
+    return cfg, cnn
+
+
+def check_final_state(w, cache, ref_states, z64, eps):
+    near = check_sets(cache, z64, w, eps)
+    assert len(near) <= 1, f"heads inside the decision margin: {near}"
+    rho = w.cnn.rho
+    kw, vw, zw = to_np(cache.k_win), to_np(cache.v_win), to_np(cache.win_score)
+    kr, vr = to_np(cache.k_ret), to_np(cache.v_ret)
+    cnts, poss = cache.ret_count.cpu().numpy(), cache.ret_pos.cpu().numpy()
+    n_seen, n_scored = cache.n_seen.cpu().numpy(), cache.n_scored.cpu().numpy()
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        n = hi - lo
+        assert int(n_seen[s]) == n and int(n_scored[s]) == max(0, n - rho)
+        for h in range(w.Hkv):
+            # ring rows of every valid position, their final logits, and the kept rows
+            for p in range(max(0, n - w.window), n):
+                slot = p % w.window
+                np.testing.assert_array_equal(kw[s, h, slot], w.k[lo + p, h])
+                np.testing.assert_array_equal(vw[s, h, slot], w.v[lo + p, h])
+            for p in range(max(0, n - w.window), max(0, n - rho)):
+                ref = z64[h, lo + p]
+                assert abs(float(zw[s, h, p % w.window]) - ref) <= LOGIT_TOL["bf16"] * max(1.0, abs(ref))
+            for r in range(int(cnts[s, h])):
+                np.testing.assert_array_equal(kr[s, h, r], w.k[lo + poss[s, h, r], h])
+                np.testing.assert_array_equal(vr[s, h, r], w.v[lo + poss[s, h, r], h])
+    return set(near)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_append_equals_one_shot_prefill(name):
+    w, fracs = make(name)
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, ocfg, ocnn, w.cu_seqlens)
+    cfg, cnn = device_setup(w)
+    cu = w.cu_seqlens
+    lens = [int(cu[s + 1] - cu[s]) for s in range(w.n_seqs)]
+    # cut points per sequence; the second sequence gets an empty chunk somewhere to exercise M = 0
+    cuts = [[0] * w.n_seqs]
+    for f in fracs:
+        cuts.append([min(lens[s], int(round(f * lens[s]))) for s in range(w.n_seqs)])
+    cuts.append(lens)
+    if w.n_seqs > 1 and len(cuts) > 2:
+        cuts[-2][1] = cuts[-1][1]          # sequence 1 is complete one chunk early: its last chunk is empty
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    got = np.zeros_like(ref_out, dtype=np.float32)
+    for c in range(len(cuts) - 1):
+        a, b = cuts[c], cuts[c + 1]
+        m = [b[s] - a[s] for s in range(w.n_seqs)]
+        q, k, v = (dev(pack(x, cu, a, b), w.dtype) for x in (w.q, w.k, w.v))
+        cu_c = torch.from_numpy(cu_of(m)).cuda()
+        if c == 0:
+            out = B.ltea_prefill(cfg, cnn, q, k, v, cu_c, max(max(m), 1), cache)
+        else:
+            out = B.ltea_prefill_append(cfg, cnn, q, k, v, cu_c, max(max(m), 1), cache)
+        o = to_np(out)
+        off = 0
+        for s in range(w.n_seqs):
+            if c > 0:     # rows of the first chunk saw the first chunk's kept set, not the final one
+                got[int(cu[s]) + a[s]: int(cu[s]) + b[s]] = o[off: off + m[s]]
+            off += m[s]
+    torch.cuda.synchronize()
+    skip = check_final_state(w, cache, ref_states, z64, 1e-5)
+    # appended rows of the LAST chunk saw the final kept set: they must equal the one-shot rows
+    G = w.Hq // w.Hkv
+    a = cuts[-2]
+    worst, scale = 0.0, 0.0
+    for s in range(w.n_seqs):
+        lo = int(cu[s])
+        for hq in range(w.Hq):
+            if (s, hq // G) in skip:
+                continue
+            rows = slice(lo + a[s], lo + lens[s])
+            if a[s] == lens[s]:
+                continue
+            worst = max(worst, float(np.abs(got[rows, hq] - ref_out[rows, hq]).max()))
+            scale = max(scale, float(np.abs(ref_out[rows, hq]).max()))
+    assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale, (worst, scale)
+
+
+def test_append_after_decode_steps():
+    """Prefill, a run of decode steps (the compact segment is then no longer ordered by position: replacements
+    happen in place), then a continuation: state and appended rows must still equal the one-shot prefill."""
+    lens = [520, 410]
+    w = wl.make_prefill("append_after_decode", 7777, "bf16", lens, 4, 2, 64, 64, 20, 1, 0.0,
+                        cnn_kernel=(5,), cnn_channels=(32,), qkv_scale=1.0, w_std=0.05)
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, ocfg, ocnn, w.cu_seqlens)
+    cfg, cnn = device_setup(w)
+    cu = w.cu_seqlens
+    n_pre, n_dec = [300, 200], 90
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    zero = [0, 0]
+    q, k, v = (dev(pack(x, cu, zero, n_pre), w.dtype) for x in (w.q, w.k, w.v))
+    B.ltea_prefill(cfg, cnn, q, k, v, torch.from_numpy(cu_of(n_pre)).cuda(), max(n_pre), cache)
+    for t in range(n_dec):
+        idx = [int(cu[s]) + n_pre[s] + t for s in range(w.n_seqs)]
+        B.ltea_decode_step(cfg, cnn, dev(w.q[idx], w.dtype), dev(w.k[idx], w.dtype), dev(w.v[idx], w.dtype), cache)
+    a = [n_pre[s] + n_dec for s in range(w.n_seqs)]
+    m = [lens[s] - a[s] for s in range(w.n_seqs)]
+    q, k, v = (dev(pack(x, cu, a, lens), w.dtype) for x in (w.q, w.k, w.v))
+    out = to_np(B.ltea_prefill_append(cfg, cnn, q, k, v, torch.from_numpy(cu_of(m)).cuda(), max(m), cache))
+    torch.cuda.synchronize()
+    skip = check_final_state(w, cache, ref_states, z64, 1e-5)
+    G = w.Hq // w.Hkv
+    off, worst = 0, 0.0
+    for s in range(w.n_seqs):
+        rows = slice(int(cu[s]) + a[s], int(cu[s]) + lens[s])
+        for hq in range(w.Hq):
+            if (s, hq // G) not in skip:
+                worst = max(worst, float(np.abs(out[off: off + m[s], hq] - ref_out[rows, hq]).max()))
+        off += m[s]
+    assert worst <= OUT_TOL["bf16"], worst

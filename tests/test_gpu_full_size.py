@@ -100,6 +100,48 @@ def test_full_paper_stack_bf16():
     run_full_prefill(wl.config_paper_stack_bf16())
 
 
+def test_full_append_prefill_bf16():
+    """prefill_bf16 at full size, fed in two calls (3072 tokens by ltea_prefill, the last 1024 by
+    ltea_prefill_append): kept sets on all heads and sampled appended rows against the one-shot oracle."""
+    w = wl.config_prefill_bf16()
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    n, cut = 4096, 3072
+    cu = w.cu_seqlens
+    first = np.concatenate([np.arange(int(cu[s]), int(cu[s]) + cut) for s in range(w.n_seqs)])
+    rest = np.concatenate([np.arange(int(cu[s]) + cut, int(cu[s + 1])) for s in range(w.n_seqs)])
+    f_idx, r_idx = torch.from_numpy(first).cuda(), torch.from_numpy(rest).cuda()
+    cu1 = torch.arange(0, w.n_seqs + 1, dtype=torch.int32, device="cuda") * cut
+    cu2 = torch.arange(0, w.n_seqs + 1, dtype=torch.int32, device="cuda") * (n - cut)
+    B.ltea_prefill(d.cfg, d.cnn, d.q[f_idx].contiguous(), d.k[f_idx].contiguous(), d.v[f_idx].contiguous(), cu1, cut, cache)
+    out = B.ltea_prefill_append(d.cfg, d.cnn, d.q[r_idx].contiguous(), d.k[r_idx].contiguous(), d.v[r_idx].contiguous(),
+                                cu2, n - cut, cache)
+    torch.cuda.synchronize()
+    print("[append] gpu done; scoring oracle", flush=True)
+    z64 = orc.score(w.k, w.v, ocnn, w.cu_seqlens)
+    near = check_sets(cache, z64, w, 1e-5)
+    assert len(near) <= 2, near
+    skip = set(near)
+    rng = np.random.default_rng(99)
+    worst, scale = 0.0, 0.0
+    for s in range(w.n_seqs):
+        lo = int(cu[s])
+        assert int(cache.n_seen[s]) == n and int(cache.n_scored[s]) == n - w.cnn.rho
+        kept = {}
+        for hq in sorted({int(x) for x in rng.integers(0, w.Hq, size=3)}):
+            if (s, hq) in skip:
+                continue
+            kept[hq] = orc.retain(z64[hq, lo:lo + n], n, w.window, w.budget, w.sink, w.tau)
+            for i in sorted({cut, cut + 1, cut + 63, cut + 64, cut + 511, cut + 512, n - 1} | {int(x) for x in rng.integers(cut, n, size=4)}):
+                ref = orc.attention_row(w.q[lo:lo + n], w.k[lo:lo + n], w.v[lo:lo + n], ocfg, kept[hq], i, hq)
+                got = out[s * (n - cut) + (i - cut), hq].float().cpu().numpy()
+                worst = max(worst, float(np.abs(got - ref).max()))
+                scale = max(scale, float(np.abs(ref).max()))
+    print(f"[append] sampled appended rows: max-abs err {worst:.3e}, largest reference magnitude {scale:.3e}", flush=True)
+    assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale
+
+
 def test_full_varlen_prefill_bf16():
     w = wl.config_varlen_prefill_bf16()
     cache, z64 = run_full_prefill(w)
