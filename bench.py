@@ -226,6 +226,49 @@ def bench_decode(args):
                               traffic=measured_traffic("decode_bf16", "decode_main_kernel")))
 
 
+def bench_chunked(args):
+    """The prefill workload fed in `--chunks` equal pieces per sequence: ltea_prefill for the first piece,
+    ltea_prefill_append for the others (same final state and last-piece rows as the one-shot call)."""
+    import torch
+    from paper_2510_20787_amd import binding as B
+    from paper_2510_20787_amd import workloads as wl
+
+    w = wl.config_prefill_bf16()
+    K = args.chunks
+    n = int(w.cu_seqlens[1] - w.cu_seqlens[0])
+    assert n % K == 0, "--chunks must divide the sequence length"
+    m = n // K
+    cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
+    c = w.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
+    q, k, v = up(w.q, w.dtype), up(w.k, w.dtype), up(w.v, w.dtype)
+    pieces = []
+    for j in range(K):
+        idx = torch.cat([torch.arange(int(w.cu_seqlens[s]) + j * m, int(w.cu_seqlens[s]) + (j + 1) * m) for s in range(w.n_seqs)]).cuda()
+        pieces.append((q[idx].contiguous(), k[idx].contiguous(), v[idx].contiguous()))
+    cu = (torch.arange(0, w.n_seqs + 1, dtype=torch.int32) * m).cuda()
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    out = torch.empty((w.n_seqs * m, w.Hq, w.D), dtype=torch.bfloat16, device="cuda")
+    ws1 = torch.empty(max(B.ltea_workspace_bytes(cfg, cnn, w.n_seqs, w.n_seqs * m, m), 16), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(max(B.ltea_append_workspace_bytes(cfg, cnn, w.n_seqs, w.n_seqs * m, m), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.ltea_prefill(cfg, cnn, *pieces[0], cu, m, cache, out=out, workspace=ws1)
+        for j in range(1, K):
+            B.ltea_prefill_append(cfg, cnn, *pieces[j], cu, m, cache, out=out, workspace=ws2)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    return {"workload": f"prefill_bf16 in {K} pieces of {m} tokens per sequence (1 ltea_prefill + {K - 1} ltea_prefill_append)",
+            "ms_per_pass": ms, "tokens_per_s": w.total_tokens / (ms * 1e-3)}
+
+
 def cpu_baseline(w):
     """The oracle as it stands on a bounded sample of the same workload: whole sequences (all heads: scoring +
     retention + attention), as many as fit in about 12 s of wall time."""
@@ -298,6 +341,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--chunks", type=int, default=1,
+                    help="also time the prefill workload fed in this many pieces per sequence (continued prefill)")
     ap.add_argument("--workload", choices=["prefill", "long", "varlen", "paper"], default="prefill",
                     help="prefill = the benchmark configuration (default); long / varlen / paper = the other prefill "
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
@@ -344,6 +389,9 @@ def main():
         log(f"[bench] decode {dec['us_per_step']:.1f} us/step")
         add_measured_fraction(dec.get("roofline"), ceilings)
         line["decode"] = dec
+    if args.chunks > 1:
+        line["chunked_prefill"] = bench_chunked(args)
+        log(f"[bench] chunked prefill: {line['chunked_prefill']['ms_per_pass']:.3f} ms per pass")
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)

@@ -20,7 +20,8 @@
 // ds_read_b64_tr_b16, two per MFMA; the tile's 64-byte chunks are XOR-swizzled so that those loads and the
 // staging stores spread over the 64 banks without padding.
 // K/V tiles are double-buffered in LDS and prefetched one tile ahead through registers, one barrier per tile
-// (D = 64 is held to 128 VGPRs so that four workgroups share a CU; D = 128 runs two).  The running maximum is only raised when a block of
+// (three workgroups share a CU at D = 64, two at D = 128; a 128-VGPR build of the D = 64 kernel reaches four but
+// spills, which costs HBM traffic and gains no time).  The running maximum is only raised when a block of
 // scores exceeds it by more than 2^8 (the result does not depend on the stabiliser), which keeps the accumulator
 // rescale off the common path.  Inside a tile the matrix work of one 32-key block is placed next to the
 // exponentials of the other, so that they overlap within the wave's in-order instruction stream.
@@ -96,7 +97,7 @@ template <int D> struct TileRegs {
 };
 
 template <int D, int QB>
-__global__ void __launch_bounds__(kThreads, D == 64 ? 4 : 2)
+__global__ void __launch_bounds__(kThreads, D == 64 ? 3 : 2)
 attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, const bf16_t* __restrict__ k,
                       const bf16_t* __restrict__ v, int64_t kv_st, int64_t kv_sh, const int32_t* __restrict__ cu,
                       int n_seqs, int tiles_upper, int n_work, int Hq, int Hkv, int window, int budget,
