@@ -350,8 +350,8 @@ def main():
     if args.workload != "prefill":
         args.no_decode = args.no_cpu_baseline = True
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (every (sequence, head) is independent; "
-                 "see DESIGN.md for how the path would shard). Run with --gpus 1.")
+        sys.exit("bench.py: this build runs on one GPU only (every (sequence, KV head) is independent, so the path "
+                 "shards over batch x heads without any exchange; no multi-GPU run is implemented). Run with --gpus 1.")
     import torch
     from paper_2510_20787_amd import binding as B
     assert torch.cuda.is_available(), "bench.py needs a GPU"
