@@ -108,7 +108,9 @@ size_t ltea_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_
                             int32_t max_seqlen);
 
 /* Bytes of device workspace ltea_decode_step needs for n_seqs sequences (contents need no initialisation
- * and need not be preserved between steps). */
+ * and need not be preserved between steps).  With `cnn` given the size also covers the faster scoring path of
+ * multi-layer bf16 CNNs (receptive-field windows of the whole batch packed and scored by the fused prefill kernel);
+ * with cnn == NULL, or a smaller workspace passed to ltea_decode_step, that CNN is scored per (sequence, head). */
 size_t ltea_decode_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs);
 
 /* (a) Scoring (Section 3.1.1): logits[h][t] for every packed token t and KV

@@ -122,6 +122,7 @@ size_t ltea_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_
 size_t ltea_decode_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
   if (check_cfg(cfg) != LTEA_OK || n_seqs < 0) return 0;
   if (cnn && check_cnn(cfg, cnn) != LTEA_OK) return 0;
+  if (cnn) return align_up(decode_workspace_full(*cfg, *cnn, n_seqs), 256);
   return align_up(decode_workspace(*cfg, n_seqs), 256);
 }
 
@@ -299,7 +300,7 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
   if (lds > 48 * 1024) return LTEA_EUNSUPPORTED;  // activation pyramid of the per-step scoring must fit LDS
   const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
-  return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace,
+  return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace, workspace_bytes,
                                        static_cast<hipStream_t>(stream)));
 }
 

@@ -23,6 +23,8 @@
 //                         row into the compact segment, writes k_t, v_t and the new logit into the ring, merges
 //                         the split partials of the group's query heads into the output row and advances
 //                         n_seen / n_scored.
+#include <type_traits>
+
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 
@@ -54,6 +56,10 @@ struct CacheDev {
 struct StepParams {
   int B, Hq, Hkv, D, window, budget, sink, rho, nsplit, lds_row_floats, n_score_blocks, score_mfma;
   float tau, scale;
+  // Scores computed before this launch over packed receptive-field windows (multi-layer bf16 CNN): the window of
+  // sequence b occupies rows b*(2*rho+1) .. of pre_logits[h][.], its first row is position max(0, t - 2*rho).
+  const float* pre_logits;
+  int64_t pre_total;
 };
 
 // exp used by the softmax: library expf for fp32 storage (1e-5 tolerance), hardware exp2 path for bf16.
@@ -370,7 +376,9 @@ __device__ __forceinline__ void score_new_tokens_mfma(const CnnDev& cnn, const S
 }
 
 // Partial record per (sequence, query head, split): [max, sum, acc[D]] floats.
-template <typename T, int D>
+// GT = query heads of a KV group handled per pass over the rows (1, 2 or 4): every K/V row is loaded once per pass
+// and used for GT queries, so grouped-query configurations do not re-stream the cache once per query head.
+template <typename T, int D, int GT>
 __global__ void __launch_bounds__(kThreads, 4)
 decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q, const T* __restrict__ k_new,
                    const T* __restrict__ v_new, float* __restrict__ partial, float* __restrict__ ws_logit,
@@ -387,6 +395,19 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
 
   const int Hkv = P.Hkv, window = P.window, budget = P.budget;
   if ((int)blockIdx.x < P.n_score_blocks) {
+    if (P.pre_logits != nullptr) {
+      // one thread per (sequence, head): pick the logit of position t - rho out of the sequence's window
+      const int head = blockIdx.x * kThreads + threadIdx.x;
+      if (head < P.B * Hkv) {
+        const int b = head / Hkv, h = head - b * Hkv;
+        const int t = C.n_seen[b];
+        if (h == 0) ws_t[b] = t;
+        const int first = t - 2 * P.rho > 0 ? t - 2 * P.rho : 0;
+        if (t - P.rho >= 0)
+          ws_logit[head] = P.pre_logits[(int64_t)h * P.pre_total + (int64_t)b * (2 * P.rho + 1) + (t - P.rho - first)];
+      }
+      return;
+    }
     if constexpr (sizeof(T) == 2) {
       if (P.score_mfma) {
         const int h = blockIdx.x % Hkv, sg = blockIdx.x / Hkv;
@@ -440,22 +461,24 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
   const T* k_evicted = kw + (int64_t)slot * D;  // old ring row that moves to compact slot dst
   const T* v_evicted = vw + (int64_t)slot * D;
 
-  for (int g = 0; g < G; ++g) {
-    const int hq = h * G + g;
-    float qf[EPL];
-    Piece<T>::load(q + ((int64_t)b * P.Hq + hq) * D + sub * EPL, qf);
+  constexpr int RIF = GT >= 4 ? 2 : kRowsInFlight;   // rows in flight per lane group (registers: GT states per lane)
+  for (int g0 = 0; g0 < G; g0 += GT) {
+    float qf[GT][EPL];
+    float m_run[GT], l_run[GT], acc[GT][EPL];
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) qf[i] *= P.scale;
-    float m_run = -INFINITY, l_run = 0.f, acc[EPL];
+    for (int g = 0; g < GT; ++g) {
+      Piece<T>::load(q + ((int64_t)b * P.Hq + h * G + g0 + g) * D + sub * EPL, qf[g]);
+      m_run[g] = -INFINITY;
+      l_run[g] = 0.f;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+      for (int i = 0; i < EPL; ++i) { qf[g][i] *= P.scale; acc[g][i] = 0.f; }
+    }
 
-    for (int r0 = r_begin + wave * GPW + grp; r0 < r_end; r0 += GPB * kRowsInFlight) {
-      u32x4 kraw[kRowsInFlight], vraw[kRowsInFlight];
-      float s[kRowsInFlight];
-      bool live[kRowsInFlight];
+    for (int r0 = r_begin + wave * GPW + grp; r0 < r_end; r0 += GPB * RIF) {
+      u32x4 kraw[RIF], vraw[RIF];
+      bool live[RIF];
 #pragma unroll
-      for (int u = 0; u < kRowsInFlight; ++u) {
+      for (int u = 0; u < RIF; ++u) {
         // Branch-free row selection so that all loads of the iteration are issued back to back; rows that do
         // not exist re-read the incoming token's row and are masked out of the softmax below.
         const int r = r0 + u * GPB;
@@ -473,59 +496,77 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
         kraw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + sub * EPL));
         vraw[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + sub * EPL));
       }
-      float m_new = m_run;
+      float s[GT][RIF], m_new[GT];
 #pragma unroll
-      for (int u = 0; u < kRowsInFlight; ++u) {
+      for (int g = 0; g < GT; ++g) m_new[g] = m_run[g];
+#pragma unroll
+      for (int u = 0; u < RIF; ++u) {
         float kf[EPL];
         Piece<T>::unpack(kraw[u], kf);
-        float d = 0.f;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) d = fmaf(qf[i], kf[i], d);
+        for (int g = 0; g < GT; ++g) {
+          float d = 0.f;
 #pragma unroll
-        for (int off = LPR / 2; off > 0; off >>= 1) d += __shfl_xor(d, off, kWave);
-        s[u] = live[u] ? d : -INFINITY;
-        m_new = fmaxf(m_new, s[u]);
+          for (int i = 0; i < EPL; ++i) d = fmaf(qf[g][i], kf[i], d);
+#pragma unroll
+          for (int off = LPR / 2; off > 0; off >>= 1) d += __shfl_xor(d, off, kWave);
+          s[g][u] = live[u] ? d : -INFINITY;
+          m_new[g] = fmaxf(m_new[g], s[g][u]);
+        }
       }
-      if (m_new == -INFINITY) continue;  // nothing live for this lane group yet
-      const float alpha = soft_exp<T>(m_run - m_new);
-      l_run *= alpha;
+      if (m_new[0] == -INFINITY) continue;  // nothing live for this lane group yet (liveness is the same for every g)
+      float pr[GT][RIF];
 #pragma unroll
-      for (int i = 0; i < EPL; ++i) acc[i] *= alpha;
+      for (int g = 0; g < GT; ++g) {
+        const float alpha = soft_exp<T>(m_run[g] - m_new[g]);
+        l_run[g] *= alpha;
 #pragma unroll
-      for (int u = 0; u < kRowsInFlight; ++u) {
-        const float p = soft_exp<T>(s[u] - m_new);
-        l_run += p;
+        for (int i = 0; i < EPL; ++i) acc[g][i] *= alpha;
+#pragma unroll
+        for (int u = 0; u < RIF; ++u) {
+          pr[g][u] = soft_exp<T>(s[g][u] - m_new[g]);
+          l_run[g] += pr[g][u];
+        }
+        m_run[g] = m_new[g];
+      }
+#pragma unroll
+      for (int u = 0; u < RIF; ++u) {
         float vf[EPL];
         Piece<T>::unpack(vraw[u], vf);
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] = fmaf(p, vf[i], acc[i]);
+        for (int g = 0; g < GT; ++g)
+#pragma unroll
+          for (int i = 0; i < EPL; ++i) acc[g][i] = fmaf(pr[g][u], vf[i], acc[g][i]);
       }
-      m_run = m_new;
     }
 
-    // merge the row groups of the block (fixed order -> deterministic)
-    if (sub == 0) { red_m[wave][grp] = m_run; red_l[wave][grp] = l_run; }
+    // merge the row groups of the block (fixed order -> deterministic), one query head after the other
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) red_acc[wave][grp][sub * EPL + i] = acc[i];
-    __syncthreads();
-    if (threadIdx.x < D) {
-      float M = -INFINITY;
-      for (int w = 0; w < kWaves; ++w)
-        for (int gg = 0; gg < GPW; ++gg) M = fmaxf(M, red_m[w][gg]);
-      float L = 0.f, A = 0.f;
-      if (M != -INFINITY) {
+    for (int g = 0; g < GT; ++g) {
+      const int hq = h * G + g0 + g;
+      if (sub == 0) { red_m[wave][grp] = m_run[g]; red_l[wave][grp] = l_run[g]; }
+#pragma unroll
+      for (int i = 0; i < EPL; ++i) red_acc[wave][grp][sub * EPL + i] = acc[g][i];
+      __syncthreads();
+      if (threadIdx.x < D) {
+        float M = -INFINITY;
         for (int w = 0; w < kWaves; ++w)
-          for (int gg = 0; gg < GPW; ++gg) {
-            const float f = soft_exp<T>(red_m[w][gg] - M);
-            L = fmaf(red_l[w][gg], f, L);
-            A = fmaf(red_acc[w][gg][threadIdx.x], f, A);
-          }
+          for (int gg = 0; gg < GPW; ++gg) M = fmaxf(M, red_m[w][gg]);
+        float L = 0.f, A = 0.f;
+        if (M != -INFINITY) {
+          for (int w = 0; w < kWaves; ++w)
+            for (int gg = 0; gg < GPW; ++gg) {
+              const float f = soft_exp<T>(red_m[w][gg] - M);
+              L = fmaf(red_l[w][gg], f, L);
+              A = fmaf(red_acc[w][gg][threadIdx.x], f, A);
+            }
+        }
+        float* rec = partial + (((int64_t)b * P.Hq + hq) * nsplit + split) * (D + 2);
+        if (threadIdx.x == 0) { rec[0] = M; rec[1] = L; }
+        rec[2 + threadIdx.x] = A;
       }
-      float* rec = partial + (((int64_t)b * P.Hq + hq) * nsplit + split) * (D + 2);
-      if (threadIdx.x == 0) { rec[0] = M; rec[1] = L; }
-      rec[2 + threadIdx.x] = A;
+      __syncthreads();
     }
-    __syncthreads();
   }
 }
 
@@ -615,9 +656,70 @@ int lds_row_floats(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   return row_floats;
 }
 
+// Receptive-field windows of the token being finalised, packed for the prefill scoring kernels: sequence b gets
+// rows b*R .. b*R + len - 1 (R = 2*rho + 1) holding positions max(0, t - 2*rho) .. t (the ring rows and, last, the
+// incoming token); a second, possibly empty pseudo-sequence covers the unused rest of the R rows so that the packing
+// stays contiguous without a prefix sum over the batch: cu2[2b] = b*R, cu2[2b+1] = b*R + len, cu2[2B] = B*R.
+template <typename T>
+__global__ void __launch_bounds__(256)
+decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, T* __restrict__ win_k,
+                      T* __restrict__ win_v, int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho) {
+  const int b = blockIdx.x;
+  const int R = 2 * rho + 1;
+  const int t = C.n_seen[b];
+  const int first = t - 2 * rho > 0 ? t - 2 * rho : 0;
+  const int len = t - first + 1;
+  if (threadIdx.x == 0) {
+    cu2[2 * b] = b * R;
+    cu2[2 * b + 1] = b * R + len;
+    if (b == B - 1) cu2[2 * B] = B * R;
+  }
+  const int pieces = D * (int)sizeof(T) / 16;                 // 16-byte pieces per row
+  const int items = len * Hkv * pieces;
+  for (int i = threadIdx.x; i < items; i += 256) {
+    const int pc = i % pieces, h = (i / pieces) % Hkv, r = i / (pieces * Hkv);
+    const int p = first + r;
+    const int64_t head = (int64_t)b * Hkv + h;
+    const T* sk = p == t ? k_new + head * D : static_cast<const T*>(C.k_win) + (head * window + p % window) * D;
+    const T* sv = p == t ? v_new + head * D : static_cast<const T*>(C.v_win) + (head * window + p % window) * D;
+    const int64_t dst = ((int64_t)(b * R + r) * Hkv + h) * D;
+    reinterpret_cast<u32x4*>(win_k + dst)[pc] = reinterpret_cast<const u32x4*>(sk)[pc];
+    reinterpret_cast<u32x4*>(win_v + dst)[pc] = reinterpret_cast<const u32x4*>(sv)[pc];
+  }
+}
+
+struct PreScore {            // buffers of the window-scoring path, carved from the tail of the workspace
+  void* win_k; void* win_v; int32_t* cu2; float* logits; void* score_ws; int64_t total;
+};
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+size_t base_workspace(const ltea_cfg& cfg, int n_seqs) {
+  return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
+         (size_t)n_seqs * sizeof(int32_t);
+}
+
+bool window_scoring(const ltea_cfg& cfg, const ltea_cnn& cnn) {
+  return cfg.dtype == LTEA_BF16 && cnn.n_layers >= 2 && score_deep_supported(cfg, cnn);
+}
+
+size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char* base, PreScore* out) {
+  const int R = 2 * cnn_rho(&cnn) + 1;
+  const size_t rows = (size_t)n_seqs * R;
+  char* p = base;
+  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  void* wk = take(rows * cfg.Hkv * cfg.D * 2);
+  void* wv = take(rows * cfg.Hkv * cfg.D * 2);
+  int32_t* cu2 = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * (size_t)n_seqs + 1)));
+  float* lg = reinterpret_cast<float*>(take(sizeof(float) * rows * cfg.Hkv));
+  void* sws = take(score_deep_workspace(cfg, cnn));
+  if (out) { out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->score_ws = sws; out->total = (int64_t)rows; }
+  return (size_t)(p - base);
+}
+
 template <typename T, int D>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v, void* out,
-               const ltea_cache& c, int n_seqs, void* workspace, hipStream_t stream) {
+               const ltea_cache& c, int n_seqs, void* workspace, bool prescore, hipStream_t stream) {
   CnnDev cd;
   cd.n_layers = cnn.n_layers;
   for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) {
@@ -643,14 +745,42 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const vo
   const int ks0 = cnn.kernel[0];
   P.score_mfma = (cfg.dtype == LTEA_BF16 && cnn.n_layers == 1 && cnn.c_out[0] <= 32 && (ks0 == 3 || ks0 == 5 || ks0 == 7)) ? ks0 : 0;
   P.n_score_blocks = P.score_mfma ? cfg.Hkv * ((n_seqs + 63) / 64) : (int)heads;
-  const size_t lds_bytes = P.score_mfma ? 0 : (size_t)2 * (2 * P.rho + 1) * P.lds_row_floats * sizeof(float);
+  size_t lds_bytes = P.score_mfma ? 0 : (size_t)2 * (2 * P.rho + 1) * P.lds_row_floats * sizeof(float);
+  P.pre_logits = nullptr;
+  P.pre_total = 0;
+  if constexpr (sizeof(T) == 2) {
+    if (prescore) {
+      // multi-layer bf16 CNN: pack the receptive-field windows and run the fused prefill scoring kernel over them
+      // (weights staged once per workgroup instead of once per (sequence, head)), then only pick the logits here
+      PreScore ps;
+      prescore_bytes(cfg, cnn, n_seqs, static_cast<char*>(workspace) + up256(base_workspace(cfg, n_seqs)), &ps);
+      hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
+                         static_cast<const T*>(k), static_cast<const T*>(v), static_cast<T*>(ps.win_k),
+                         static_cast<T*>(ps.win_v), ps.cu2, n_seqs, cfg.Hkv, cfg.D, cfg.window, P.rho);
+      hipError_t e0 = hipGetLastError();
+      if (e0 != hipSuccess) return e0;
+      SeqView sv{ps.cu2, 2 * n_seqs, ps.total, 2 * P.rho + 1};
+      e0 = launch_score_deep(cfg, cnn, ps.win_k, ps.win_v, (int64_t)cfg.Hkv * cfg.D, cfg.D, sv, ps.logits, ps.score_ws, stream);
+      if (e0 != hipSuccess) return e0;
+      P.pre_logits = ps.logits;
+      P.pre_total = ps.total;
+      P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
+      lds_bytes = 0;
+    }
+  }
   float* partial = static_cast<float*>(workspace);
   float* ws_logit = partial + partial_floats(cfg, n_seqs, P.nsplit);
   int32_t* ws_t = reinterpret_cast<int32_t*>(ws_logit + heads);
   const unsigned grid = (unsigned)P.n_score_blocks + heads * (unsigned)P.nsplit;
-  hipLaunchKernelGGL((decode_main_kernel<T, D>), dim3(grid), dim3(kThreads), lds_bytes, stream, cd, C, P,
-                     static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit,
-                     ws_t);
+  const int G = cfg.Hq / cfg.Hkv;
+  auto launch_main = [&](auto gt) {
+    hipLaunchKernelGGL((decode_main_kernel<T, D, decltype(gt)::value>), dim3(grid), dim3(kThreads), lds_bytes, stream,
+                       cd, C, P, static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), partial,
+                       ws_logit, ws_t);
+  };
+  if (G % 4 == 0) launch_main(std::integral_constant<int, 4>{});
+  else if (G % 2 == 0) launch_main(std::integral_constant<int, 2>{});
+  else launch_main(std::integral_constant<int, 1>{});
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(heads), dim3(kThreads), 0, stream, C, P,
@@ -671,20 +801,27 @@ int decode_num_splits(const ltea_cfg& cfg, int n_seqs) {
   return n;
 }
 
-size_t decode_workspace(const ltea_cfg& cfg, int n_seqs) {
-  return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
-         (size_t)n_seqs * sizeof(int32_t);
+size_t decode_workspace(const ltea_cfg& cfg, int n_seqs) { return base_workspace(cfg, n_seqs); }
+
+// Workspace that also enables the window-scoring path of multi-layer bf16 CNNs (equal to decode_workspace otherwise).
+size_t decode_workspace_full(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs) {
+  size_t b = up256(base_workspace(cfg, n_seqs));
+  if (window_scoring(cfg, cnn)) b += prescore_bytes(cfg, cnn, n_seqs, nullptr, nullptr);
+  return b;
 }
 
 hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v,
-                              void* out, const ltea_cache& c, int n_seqs, void* workspace, hipStream_t stream) {
+                              void* out, const ltea_cache& c, int n_seqs, void* workspace, size_t workspace_bytes,
+                              hipStream_t stream) {
   if (n_seqs == 0) return hipSuccess;
   if (cfg.dtype == LTEA_F32) {
-    return cfg.D == 64 ? run<float, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, stream)
-                       : run<float, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, stream);
+    return cfg.D == 64 ? run<float, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, false, stream)
+                       : run<float, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, false, stream);
   }
-  return cfg.D == 64 ? run<bf16_t, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, stream)
-                     : run<bf16_t, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, stream);
+  // the window-scoring path needs the larger workspace; with the basic one the per-head path runs
+  const bool prescore = window_scoring(cfg, cnn) && workspace_bytes >= decode_workspace_full(cfg, cnn, n_seqs);
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, prescore, stream)
+                     : run<bf16_t, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, prescore, stream);
 }
 
 }  // namespace ltea

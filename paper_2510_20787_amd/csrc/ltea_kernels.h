@@ -88,8 +88,10 @@ hipError_t launch_append_fixup(const ltea_cfg& cfg, const int32_t* cu_new, int n
 
 // ---- (d) decode step -------------------------------------------------------------------------------
 int decode_num_splits(const ltea_cfg& cfg, int n_seqs);
-size_t decode_workspace(const ltea_cfg& cfg, int n_seqs);
+size_t decode_workspace(const ltea_cfg& cfg, int n_seqs);                               // minimum
+size_t decode_workspace_full(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs);     // enables every path
 hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v,
-                              void* out, const ltea_cache& cache, int n_seqs, void* workspace, hipStream_t stream);
+                              void* out, const ltea_cache& cache, int n_seqs, void* workspace, size_t workspace_bytes,
+                              hipStream_t stream);
 
 }  // namespace ltea

@@ -46,18 +46,23 @@ struct DeepArgs {
   const int32_t* cu; int n_seqs; int64_t total; float* logits;
 };
 
-// panels[l][h][tap][c][m] = W_l[h][c][m][tap] for c < cout, 0 for cout <= c < cp
+struct PanelArgs {
+  const uint16_t* w[kMaxL]; int64_t off[kMaxL], total[kMaxL]; int cout[kMaxL], cp[kMaxL], cin[kMaxL], ks[kMaxL];
+};
+
+// panels[l][h][tap][c][m] = W_l[h][c][m][tap] for c < cout, 0 for cout <= c < cp; blockIdx.y = layer
 __global__ void __launch_bounds__(256)
-deep_panels_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ panels, int cout, int cp, int cin, int ks,
-                   int64_t total) {
-  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [Hkv][ks][cp][cin]
-  if (idx >= total) return;
+deep_panels_kernel(PanelArgs a, uint16_t* __restrict__ panels) {
+  const int l = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;   // over [Hkv][ks][cp][cin] of layer l
+  if (idx >= a.total[l]) return;
+  const int cin = a.cin[l], cp = a.cp[l], ks = a.ks[l], cout = a.cout[l];
   const int m = (int)(idx % cin);
   int64_t r = idx / cin;
   const int c = (int)(r % cp); r /= cp;
   const int tap = (int)(r % ks);
   const int64_t h = r / ks;
-  panels[idx] = c < cout ? W[((h * cout + c) * cin + m) * ks + tap] : (uint16_t)0;
+  panels[a.off[l] + idx] = c < cout ? a.w[l][((h * cout + c) * cin + m) * ks + tap] : (uint16_t)0;
 }
 
 __global__ void __launch_bounds__(kThreads, 2)
@@ -340,21 +345,25 @@ hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
   a.w_out = static_cast<const bf16_t*>(cnn.w_out); a.b_out = cnn.b_out;
   a.L = cnn.n_layers;
   int cin = 2 * cfg.D;
+  PanelArgs pa;
+  int64_t most = 0;
   for (int l = 0; l < kMaxL; ++l) {
     const bool on = l < cnn.n_layers;
     a.panel_off[l] = p.panel_off[l]; a.panel_head[l] = p.panel_head[l];
     a.bias[l] = on ? cnn.bias[l] : nullptr;
     a.ks[l] = on ? cnn.kernel[l] : 1; a.dil[l] = on ? cnn.dilation[l] : 1;
     a.cin[l] = cin; a.cout[l] = on ? cnn.c_out[l] : 16; a.cp[l] = on ? p.cp[l] : 32;
-    if (on) {
-      const int64_t elems = p.panel_head[l] * cfg.Hkv;
-      hipLaunchKernelGGL(deep_panels_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, stream,
-                         static_cast<const uint16_t*>(cnn.w[l]), static_cast<uint16_t*>(workspace) + p.panel_off[l],
-                         cnn.c_out[l], p.cp[l], cin, cnn.kernel[l], elems);
-      hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return e;
-      cin = cnn.c_out[l];
-    }
+    pa.w[l] = on ? static_cast<const uint16_t*>(cnn.w[l]) : nullptr;
+    pa.off[l] = p.panel_off[l]; pa.total[l] = on ? p.panel_head[l] * cfg.Hkv : 0;
+    pa.cout[l] = a.cout[l]; pa.cp[l] = a.cp[l]; pa.cin[l] = cin; pa.ks[l] = a.ks[l];
+    most = pa.total[l] > most ? pa.total[l] : most;
+    if (on) cin = cnn.c_out[l];
+  }
+  hipLaunchKernelGGL(deep_panels_kernel, dim3((unsigned)((most + 255) / 256), (unsigned)cnn.n_layers), dim3(256), 0,
+                     stream, pa, static_cast<uint16_t*>(workspace));
+  {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
   }
   a.TM = p.TM; a.x_rows = p.x_rows; a.h0 = p.h0;
   a.lds_ra = p.lds_ra; a.lds_r1 = p.lds_r1; a.lds_rw = p.lds_rw;
