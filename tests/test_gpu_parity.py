@@ -145,6 +145,16 @@ def test_retain_large_budget_and_radix_paths():
     run_retain_case(w, z)
 
 
+def test_retain_longer_than_the_register_path():
+    """More than 32768 out-of-window positions: the selection re-reads its keys from memory in every pass
+    instead of holding them in registers; a second, short sequence shares the launch."""
+    w = wl.make_prefill("long_select", 11, "bf16", [70000, 4000], 1, 1, 64, 64, 700, 2, 0.0, cnn_kernel=(3,), cnn_channels=(16,))
+    rng = np.random.default_rng(6)
+    z = rng.standard_normal((1, w.total_tokens)).astype(np.float32)
+    z[0, rng.integers(0, w.total_tokens, size=500)] = np.float32(0.5)     # ties at a value that will be kept
+    run_retain_case(w, z)
+
+
 # ------------------------------------------------------------------------------------------------
 # (c) attention over window + an explicit keep set (uniform stride; no CNN involved)
 # ------------------------------------------------------------------------------------------------
@@ -306,3 +316,30 @@ def test_diag_probes():
     expect = int((pieces[:, 0] ^ pieces[:, 1] ^ pieces[:, 2] ^ pieces[:, 3]).sum().item()) & 0xFFFFFFFF
     total = int(sink.view(torch.int32).to(torch.int64).bitwise_and(0xFFFFFFFF).sum().item()) & 0xFFFFFFFF
     assert total == expect
+
+
+# ------------------------------------------------------------------------------------------------
+# many short sequences: the per-workgroup sequence lookup walks more than one group of 64 sequences, most tiles
+# are ragged, some sequences are empty or shorter than the receptive field
+def test_prefill_many_short_sequences():
+    rng = np.random.default_rng(4242)
+    lens = [int(x) for x in rng.integers(0, 180, size=300)]
+    lens[5], lens[17], lens[299] = 0, 1, 3
+    w = wl.make_prefill("many_short", 4242, "bf16", lens, 4, 2, 64, 48, 12, 1, 0.0, cnn_kernel=(5,), cnn_channels=(32,),
+                        qkv_scale=1.0, w_std=0.05)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, states, z64, kept = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    out = to_np(B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits))
+    eps = logit_eps(to_np(logits), z64, "bf16")
+    near = check_sets(cache, z64, w, eps)
+    assert len(near) <= 3, near
+    G = w.Hq // w.Hkv
+    bad = np.zeros(w.total_tokens, dtype=bool)
+    for (s, h) in near:
+        bad[int(w.cu_seqlens[s]):int(w.cu_seqlens[s + 1])] = True
+    check_output(out[~bad], ref_out[~bad], "bf16", "many short sequences")
+    n_seen = cache.n_seen.cpu().numpy()
+    assert np.array_equal(n_seen, np.asarray(lens, dtype=np.int32))
