@@ -77,6 +77,30 @@ def test_p4_budget_invariants():
             assert list(R) == brute_force_keep(orc.selection_key(z[h], 2), 80, 10, b, 2, 0.0)
 
 
+def test_p4_kept_set_is_nested_in_the_prefix_length():
+    """What a continued prefill relies on: a token outside the kept set of a prefix is outside the kept set of every
+    longer prefix, so re-selecting among (kept set of the prefix) + (tokens that leave the window afterwards) gives
+    the kept set of the longer prefix.  Heavy ties included (quantised logits)."""
+    rng = np.random.default_rng(21)
+    n, window, sink, tau = 140, 11, 2, 0.0
+    for budget in (0, 1, 5, 17):
+        for quant in (None, 0.5):
+            z = rng.standard_normal(n)
+            if quant:
+                z = np.round(z / quant) * quant
+            key = orc.selection_key(z, sink)
+            for n1 in (0, 5, window, window + 1, 60, 139):
+                R1 = orc.retain(z[:n1], n1, window, budget, sink, tau)
+                for n2 in (n1, n1 + 1, n1 + window, n):
+                    if n2 > n:
+                        continue
+                    R2 = orc.retain(z[:n2], n2, window, budget, sink, tau)
+                    leaving = [j for j in range(max(0, n1 - window), max(0, n2 - window))]
+                    pool = sorted(set(int(j) for j in R1) | {j for j in leaving if j < sink or np.float32(z[j]) > np.float32(tau)})
+                    pool.sort(key=lambda j: (-float(key[j]) if np.isfinite(key[j]) else -np.inf, j))
+                    assert sorted(pool[:budget]) == [int(j) for j in R2], (budget, quant, n1, n2)
+
+
 def test_p4_ties_and_nan():
     z = np.array([0.5, 0.5, np.nan, 0.5, 0.7, 0.5, -1.0, 0.5] + [0.0] * 4, dtype=np.float64)
     # n=12, window=4 -> evictable 0..7; candidates: 0,1,3,4,5,7 (NaN and -1 never)
