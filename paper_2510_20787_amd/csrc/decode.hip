@@ -9,7 +9,10 @@
 //                         one workgroup per (KV head, 64 sequences); the conv over the batch is a small GEMM
 //                         [sequences x taps*2D] . [taps*2D x C] on v_mfma_f32_16x16x32_bf16 with both operands
 //                         read straight from global memory (weights are shared by all sequences of a head).
-//                         Otherwise (fp32, deeper stacks): one workgroup per (sequence, head), activation pyramid
+//                         Multi-layer bf16 (given the larger workspace): two launches before this one pack the
+//                         receptive-field windows of all sequences as tiny sequences and run the fused prefill
+//                         scoring kernel over them; the role here only picks each window's centre logit.
+//                         Otherwise (fp32, unusual stacks): one workgroup per (sequence, head), activation pyramid
 //                         in LDS.  These few workgroups are dispatched first and hide under the streaming.
 //     attention role      the memory-bound part: grid (sequence x KV head) x splits; each workgroup streams its
 //                         share of the rows the query must see AFTER this step's cache update, without waiting
@@ -18,7 +21,7 @@
 //                         one pass over `budget` keys, only by workgroups whose share touches the compact
 //                         segment) is taken from the old ring row.  16-byte loads, one row per D*sizeof(T)/16
 //                         lanes, several rows in flight per lane group, online softmax per group, fixed-order
-//                         merges.
+//                         merges.  Up to four query heads of a KV group share one pass over the rows.
 //   decode_finish_kernel  one workgroup per (sequence, KV head): repeats the eviction decision, moves the evicted
 //                         row into the compact segment, writes k_t, v_t and the new logit into the ring, merges
 //                         the split partials of the group's query heads into the output row and advances
