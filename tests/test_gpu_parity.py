@@ -294,6 +294,31 @@ def test_decode_from_empty_cache(dtype, D):
         compare_state(cache, states, w, t)
 
 
+@pytest.mark.parametrize("small_ws", [False, True])
+def test_decode_deep_cnn_both_scoring_paths(small_ws):
+    """Multi-layer bf16 CNN from an empty cache (so the first 2*rho steps have receptive fields cut by the sequence
+    start): with the full workspace the packed-window path scores, with the minimal one the per-head path does;
+    both must agree with the oracle."""
+    n, B_ = 60, 3
+    w = wl.make_prefill("deep_from_empty", 78, "bf16", [n] * B_, 4, 2, 64, 32, 10, 2, 0.0, cnn_kernel=(3, 3, 3),
+                        cnn_channels=(64, 32, 16), cnn_dilation=(2, 2, 2), w_std=0.1)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    full = B.ltea_decode_workspace_bytes(d.cfg, d.cnn, B_)
+    minimal = int(B.lib().ltea_decode_workspace_bytes(B.C.byref(d.cfg), None, B_))
+    assert minimal < full
+    ws = torch.empty(minimal if small_ws else full, dtype=torch.uint8, device="cuda")
+    states = [orc.empty_state(cfg) for _ in range(B_)]
+    q3 = w.q.reshape(B_, n, w.Hq, 64); k3 = w.k.reshape(B_, n, w.Hkv, 64); v3 = w.v.reshape(B_, n, w.Hkv, 64)
+    for t in range(n):
+        out = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q3[:, t], "bf16"), dev(k3[:, t], "bf16"), dev(v3[:, t], "bf16"),
+                                       cache, workspace=ws))
+        ref = np.stack([orc.decode_step(states[s], q3[s, t], k3[s, t], v3[s, t], cfg, cnn) for s in range(B_)])
+        check_output(out, ref, "bf16", f"step {t}")
+        compare_state(cache, states, w, t)
+
+
 # ------------------------------------------------------------------------------------------------
 # measurement aids: they must run, report the work they did and leave a checksum for every thread
 def test_diag_probes():
