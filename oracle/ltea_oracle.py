@@ -24,7 +24,10 @@ Pins (tests/test_oracle_pins.py): dense masked softmax built from eq. 5,
 special cases b=0 / w>=n, budget invariants, streaming-vs-batch retention,
 prefill-vs-decode agreement when the cap does not bind, a library grouped
 convolution, closed forms for the CNN and the softmax, packing and GQA
-invariants.  No value printed by the paper exists for this mechanism.
+invariants; for the lazy path: complex multiplication and the relative-position
+identity for the rotation, deferred == per-step scoring, and un-rotated cached
+keys reproducing the scores of the unrotated ones.  No value printed by the
+paper exists for this mechanism.
 """
 from __future__ import annotations
 
@@ -356,3 +359,118 @@ def retained_positions(st: SeqState) -> List[np.ndarray]:
 
 def window_positions(st: SeqState) -> List[np.ndarray]:
     return [np.array(sorted(hs.win_pos), dtype=np.int64) for hs in st.heads]
+
+
+# --------------------------------------------------------------------------
+# O6: rotary encoding from cached sinusoids and its inverse (Section 3.1.3 "Lazy scoring")
+# --------------------------------------------------------------------------
+@dataclass
+class OracleRope:
+    """cos, sin: [n_pos, rot_dim/2] tables the model rotates its keys with (row = position).  Pair i of a
+    vector x is (x[i], x[i + rot_dim/2]), or (x[2i], x[2i+1]) when interleaved; features from rot_dim on are
+    not rotated."""
+    cos: np.ndarray
+    sin: np.ndarray
+    interleaved: bool = False
+
+    @property
+    def rot_dim(self) -> int:
+        return 2 * self.cos.shape[1]
+
+
+def rope_rotate(x: np.ndarray, pos: int, rope: OracleRope, inverse: bool = False) -> np.ndarray:
+    """Rotate every pair (a, b) of x [..., D] by the angle of table row `pos`:
+    (a, b) -> (a cos - b sin, a sin + b cos).  The inverse is the same rotation with the sines negated,
+    which is how the cached post-rotation keys are turned back into scoring features."""
+    x = np.asarray(x, dtype=np.float64)
+    c = np.asarray(rope.cos[pos], dtype=np.float64)
+    s = np.asarray(rope.sin[pos], dtype=np.float64)
+    if inverse:
+        s = -s
+    r = rope.rot_dim
+    out = x.copy()
+    if rope.interleaved:
+        a, b = x[..., 0:r:2], x[..., 1:r:2]
+        out[..., 0:r:2] = a * c - b * s
+        out[..., 1:r:2] = a * s + b * c
+    else:
+        a, b = x[..., :r // 2], x[..., r // 2:r]
+        out[..., :r // 2] = a * c - b * s
+        out[..., r // 2:r] = a * s + b * c
+    return out
+
+
+# --------------------------------------------------------------------------
+# O7: deferred, batched scoring during decode (Section 3.1.3 "Lazy scoring")
+# --------------------------------------------------------------------------
+def lazy_period(cfg: OracleCfg, cnn: OracleCnn) -> int:
+    """Decode steps that may pass between two batched scorings: window minus the receptive field's reach on
+    both sides."""
+    return cfg.window - 2 * cnn.rho
+
+
+def rescore_due(st: SeqState, cfg: OracleCfg, cnn: OracleCnn) -> bool:
+    """True when the next token would push out of the window a position that the oldest unscored token's
+    receptive field still needs (N - w = j - rho in the paper's notation, or already past it)."""
+    leaving = st.n_seen - cfg.window
+    return leaving >= 0 and st.n_scored - cnn.rho <= leaving
+
+
+def rescore(st: SeqState, cfg: OracleCfg, cnn: OracleCnn, rope: Optional[OracleRope] = None, round_features=None) -> None:
+    """Give final logits to all positions n_scored .. n_seen-rho-1 at once from the window's records.  With
+    `rope` the cached keys are post-rotation and are rotated back (negated sines, each at its own position)
+    before the CNN sees them; `round_features` (a function on arrays) models the storage precision the
+    un-rotated keys are held in."""
+    rho, n = cnn.rho, st.n_seen
+    first_new, end_new = st.n_scored, n - rho
+    if end_new <= first_new:
+        return
+    lo = max(0, first_new - rho)
+    for h, hs in enumerate(st.heads):
+        first = hs.win_pos[0]
+        assert lo >= first, "the receptive field of the oldest unscored token has left the window"
+        feats = []
+        for p in range(lo, n):
+            kp = hs.win_k[p - first]
+            if rope is not None:
+                kp = rope_rotate(kp, p, rope, inverse=True)
+                if round_features is not None:
+                    kp = round_features(kp)
+            feats.append(kp)
+        kk = np.stack(feats)[:, None, :]
+        vv = np.stack([hs.win_v[p - first] for p in range(lo, n)])[:, None, :]
+        sub = OracleCnn(cnn.kernel, cnn.dilation, [w[h:h + 1] for w in cnn.w], [b[h:h + 1] for b in cnn.bias],
+                        cnn.w_out[h:h + 1], cnn.b_out[h:h + 1])
+        zz = score_sequence(kk, vv, sub)[0]
+        # the slice's left edge is either the sequence start (lo == 0: real zero padding) or rho rows before
+        # the first position that is read out; its right edge is the newest token, rho rows past the last one
+        for j in range(first_new, end_new):
+            hs.win_z[j] = float(zz[j - lo])
+    st.n_scored = end_new
+
+
+def decode_step_lazy(st: SeqState, q_t, k_t, v_t, cfg: OracleCfg) -> np.ndarray:
+    """decode_step without the scoring: the token that leaves the window must already hold a final logit
+    (rescore() was called in time)."""
+    q_t = np.asarray(q_t, dtype=np.float64)
+    k_t = np.asarray(k_t, dtype=np.float64)
+    v_t = np.asarray(v_t, dtype=np.float64)
+    t = st.n_seen
+    out = np.zeros((cfg.Hq, cfg.D), dtype=np.float64)
+    for h in range(cfg.Hkv):
+        hs = st.heads[h]
+        hs.win_pos.append(t)
+        hs.win_k.append(k_t[h].copy())
+        hs.win_v.append(v_t[h].copy())
+        if len(hs.win_pos) > cfg.window:
+            e = hs.win_pos.pop(0)
+            ek, ev = hs.win_k.pop(0), hs.win_v.pop(0)
+            assert e < st.n_scored, "token leaves the window before it was scored"
+            evict_into_retained(hs, e, hs.win_z.pop(e), ek, ev, cfg)
+        K = np.stack(hs.ret_k + hs.win_k)
+        V = np.stack(hs.ret_v + hs.win_v)
+        for g in range(cfg.G):
+            hq = h * cfg.G + g
+            out[hq] = attend(q_t[hq], K, V, cfg.sigma)
+    st.n_seen = t + 1
+    return out

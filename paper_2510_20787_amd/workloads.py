@@ -266,6 +266,15 @@ def decode_inputs(seed: int, step: int, dtype: str, B: int, Hq: int, Hkv: int, D
 CONFIG_NAMES = ["tiny_f32", "prefill_bf16", "decode_bf16", "long_prefill_bf16", "varlen_prefill_bf16"]
 
 
+def rope_tables(n_pos: int, rot_dim: int, base: float = 10000.0):
+    """Cached sinusoids of a rotary position encoding, as a model would hold them: cos, sin [n_pos, rot_dim/2]
+    fp32 with angle(p, i) = p * base**(-2i/rot_dim).  Input data for the lazy-scoring path; applying them is the
+    library's (and, separately, the oracle's) business."""
+    inv_freq = base ** (-np.arange(0, rot_dim, 2, dtype=np.float64) / rot_dim)
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * inv_freq[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
 def config_tiny_f32() -> PrefillWorkload:
     return make_prefill("tiny_f32", 0, "f32", [512], 2, 2, 64, window=64, budget=32,
                         cnn_kernel=(5,), cnn_channels=(16,), qkv_scale=1.0, w_std=0.1)

@@ -329,6 +329,140 @@ def test_p13_gqa_shares_kept_set():
     np.testing.assert_allclose(out, dense_masked_attention(w.q, w.k, w.v, keepb, 9, cfg.sigma, 3), atol=1e-12)
 
 
+# ---- P14: the rotation used to undo RoPE on cached keys ---------------------------------------
+def _rope(n_pos=64, rot=8, interleaved=False, base=100.0):
+    ang = np.arange(n_pos, dtype=np.float64)[:, None] * base ** (-np.arange(0, rot, 2, dtype=np.float64) / rot)[None, :]
+    return orc.OracleRope(np.cos(ang), np.sin(ang), interleaved)
+
+
+def test_p14_rotation_is_complex_multiplication_and_has_an_inverse():
+    rng = np.random.default_rng(0)
+    D, rot = 12, 8
+    x = rng.normal(size=(5, D))
+    for inter in (False, True):
+        rope = _rope(rot=rot, interleaved=inter)
+        for pos in (0, 1, 17, 63):
+            y = orc.rope_rotate(x, pos, rope)
+            a = x[:, 0:rot:2] if inter else x[:, :rot // 2]
+            b = x[:, 1:rot:2] if inter else x[:, rot // 2:rot]
+            zc = (a + 1j * b) * (rope.cos[pos] + 1j * rope.sin[pos])       # library complex product
+            ya = y[:, 0:rot:2] if inter else y[:, :rot // 2]
+            yb = y[:, 1:rot:2] if inter else y[:, rot // 2:rot]
+            np.testing.assert_allclose(ya, zc.real, atol=1e-14)
+            np.testing.assert_allclose(yb, zc.imag, atol=1e-14)
+            np.testing.assert_array_equal(y[:, rot:], x[:, rot:])           # features past rot_dim untouched
+            np.testing.assert_allclose(np.linalg.norm(y, axis=1), np.linalg.norm(x, axis=1), rtol=1e-14)
+            np.testing.assert_allclose(orc.rope_rotate(y, pos, rope, inverse=True), x, atol=1e-14)
+    # quarter turn: (a, b) -> (-b, a)
+    quarter = orc.OracleRope(np.zeros((1, 2)), np.ones((1, 2)), False)
+    np.testing.assert_allclose(orc.rope_rotate(np.array([1.0, 2.0, 3.0, 4.0]), 0, quarter), [-3.0, -4.0, 1.0, 2.0])
+    quarter_i = orc.OracleRope(np.zeros((1, 2)), np.ones((1, 2)), True)
+    np.testing.assert_allclose(orc.rope_rotate(np.array([1.0, 2.0, 3.0, 4.0]), 0, quarter_i), [-2.0, 1.0, -4.0, 3.0])
+
+
+def test_p14_rotated_dot_products_depend_on_the_offset_only():
+    rng = np.random.default_rng(1)
+    rope = _rope(n_pos=80, rot=8)
+    q, k = rng.normal(size=8), rng.normal(size=8)
+    ref = float(orc.rope_rotate(q, 30, rope) @ orc.rope_rotate(k, 19, rope))
+    for shift in (1, 7, 40):
+        assert abs(float(orc.rope_rotate(q, 30 + shift, rope) @ orc.rope_rotate(k, 19 + shift, rope)) - ref) < 1e-12
+    assert abs(float(orc.rope_rotate(q, 11, rope) @ k) - ref) < 1e-12
+
+
+# ---- P15: deferred batched scoring gives what per-step scoring gives ----------------------------
+def _lazy_run(w, cfg, cnn, st, q, k, v, rope=None, rounder=None):
+    """Drive lazy decode with the paper's trigger; returns the number of batched scorings."""
+    calls = 0
+    outs = []
+    for t in range(len(q)):
+        if orc.rescore_due(st, cfg, cnn):
+            orc.rescore(st, cfg, cnn, rope, rounder)
+            calls += 1
+        outs.append(orc.decode_step_lazy(st, q[t], k[t], v[t], cfg))
+    return calls, outs
+
+
+@pytest.mark.parametrize("seed,n0,steps,window,budget,sink,kernel,dil", [(30, 0, 70, 13, 5, 1, (3,), None),
+                                                                         (31, 25, 60, 11, 4, 0, (5,), None),
+                                                                         (32, 40, 90, 21, 6, 2, (3, 3), (2, 1)),
+                                                                         (33, 3, 50, 9, 3, 0, (3, 3), (1, 1))])
+def test_p15_lazy_scoring_equals_per_step_scoring(seed, n0, steps, window, budget, sink, kernel, dil):
+    ch = (4,) * len(kernel)
+    w = small_prefill(seed=seed, seqlens=(n0 + steps,), window=window, budget=budget, sink=sink, kernel=kernel,
+                      channels=ch, dilation=dil)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    def start():
+        if n0 == 0:
+            return orc.empty_state(cfg)
+        return orc.prefill(w.q[:n0], w.k[:n0], w.v[:n0], cfg, cnn, [0, n0])[1][0]
+    eager, lazy = start(), start()
+    calls = 0
+    for t in range(n0, n0 + steps):
+        o_e = orc.decode_step(eager, w.q[t], w.k[t], w.v[t], cfg, cnn)
+        if orc.rescore_due(lazy, cfg, cnn):
+            orc.rescore(lazy, cfg, cnn)
+            calls += 1
+        o_l = orc.decode_step_lazy(lazy, w.q[t], w.k[t], w.v[t], cfg)
+        np.testing.assert_allclose(o_l, o_e, atol=1e-13)
+        for h in range(cfg.Hkv):
+            assert sorted(lazy.heads[h].ret_pos) == sorted(eager.heads[h].ret_pos), (t, h)
+    # the trigger fires once per (window - 2 rho) steps once the window is full
+    period = orc.lazy_period(cfg, cnn)
+    assert period == window - 2 * cnn.rho
+    full_from = max(n0, window)
+    expect = (n0 + steps - full_from) / period
+    assert abs(calls - expect) <= 1.5, (calls, expect)
+    orc.rescore(lazy, cfg, cnn)
+    assert lazy.n_scored == eager.n_scored
+    for h in range(cfg.Hkv):
+        for j, zj in eager.heads[h].win_z.items():
+            assert abs(lazy.heads[h].win_z[j] - zj) < 1e-12
+    # skipping the batched scoring is noticed
+    late = start()
+    with pytest.raises(AssertionError):
+        for t in range(n0, n0 + steps):
+            orc.decode_step_lazy(late, w.q[t], w.k[t], w.v[t], cfg)
+
+
+# ---- P16: un-rotated cached keys give the scores of the keys before rotation ---------------------
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_p16_inverse_rope_on_cached_keys_restores_the_scoring_features(interleaved):
+    n = 75
+    w = small_prefill(seed=40, seqlens=(n,), window=15, budget=5, sink=1, kernel=(3, 3), channels=(4, 4), dilation=(2, 1))
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    rope = _rope(n_pos=n, rot=8, interleaved=interleaved)
+    k_pre = np.asarray(w.k, np.float64)
+    k_post = np.stack([orc.rope_rotate(k_pre[p], p, rope) for p in range(n)])
+    eager = orc.empty_state(cfg)      # scores the keys before rotation, step by step
+    lazy = orc.empty_state(cfg)       # holds rotated keys, scores them in batches after rotating back
+    for t in range(n):
+        orc.decode_step(eager, w.q[t], k_pre[t], w.v[t], cfg, cnn)
+        if orc.rescore_due(lazy, cfg, cnn):
+            orc.rescore(lazy, cfg, cnn, rope)
+        orc.decode_step_lazy(lazy, w.q[t], k_post[t], w.v[t], cfg)
+        for h in range(cfg.Hkv):
+            assert sorted(lazy.heads[h].ret_pos) == sorted(eager.heads[h].ret_pos), (t, h)
+    orc.rescore(lazy, cfg, cnn, rope)
+    for h in range(cfg.Hkv):
+        assert len(eager.heads[h].win_z) > 0
+        for j, zj in eager.heads[h].win_z.items():
+            assert abs(lazy.heads[h].win_z[j] - zj) < 1e-10
+    # without the inverse rotation, or with it taken at a shifted position, the logits come out different
+    for broken in ("none", "shifted"):
+        st = orc.empty_state(cfg)
+        bad_rope = None if broken == "none" else orc.OracleRope(np.roll(rope.cos, 1, axis=0), np.roll(rope.sin, 1, axis=0), interleaved)
+        for t in range(20):
+            if orc.rescore_due(st, cfg, cnn):
+                orc.rescore(st, cfg, cnn, bad_rope)
+            orc.decode_step_lazy(st, w.q[t], k_post[t], w.v[t], cfg)
+        orc.rescore(st, cfg, cnn, bad_rope)
+        ref = orc.score_sequence(k_pre[:20], np.asarray(w.v[:20], np.float64), cnn)
+        got = np.array([[st.heads[h].win_z[j] for j in sorted(st.heads[h].win_z)] for h in range(cfg.Hkv)])
+        js = sorted(st.heads[0].win_z)
+        assert np.abs(got - ref[:, js]).max() > 1e-4, broken
+
+
 # ---- planted mistakes: the pins above must notice them ---------------------------------------
 def test_pins_catch_planted_mistakes(monkeypatch):
     w = small_prefill(seed=20, seqlens=(40,), window=8, budget=4)
