@@ -195,6 +195,55 @@ int ltea_prefill_append(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q,
                         int32_t max_new, void *out, const ltea_cache *cache, void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* ---- lazy scoring during decode (Section 3.1.3, lazy scoring paragraph) ------------------------------------
+ * Instead of finalising one logit per step, the caller may run ltea_decode_step_lazy (no scoring at all) and call
+ * ltea_rescore every so often, which finalises the logits of all positions n_scored .. n_seen - rho - 1 of every
+ * sequence in one batched pass over the ring and restores n_scored = max(0, n_seen - rho).  A token's logit is
+ * needed when it leaves the window, and its receptive field must still be in the ring when it is scored, so at
+ * most ltea_lazy_period() = window - 2*rho lazy steps may follow ltea_prefill / ltea_retain / ltea_prefill_append /
+ * ltea_rescore / an eager step before the next ltea_rescore.  The resulting cache state and outputs equal those
+ * of eager steps.  ltea_decode_step and ltea_prefill_append expect the invariant n_scored = max(0, n_seen - rho):
+ * call ltea_rescore before going back to them.
+ *
+ * Violations of the period cannot be seen from the host; they are reported through `status`, an optional device
+ * int32 the kernels OR bits into (the caller zeroes it and reads it when convenient): */
+#define LTEA_LATE_SCORING 1 /* set by ltea_rescore when the left context of an unscored token has already left the
+                               window (the period was exceeded: the logits it writes for that sequence are
+                               unspecified), and by ltea_decode_step_lazy when the token that leaves the window has
+                               no final logit (that step's output rows of the sequence are NaN and its kept set is
+                               unspecified from then on)                                                           */
+#define LTEA_ROPE_RANGE 2   /* a cached position lies beyond the rotary tables: that key was left as it is          */
+
+/* Rotary position encoding as the model holds it ("cached sinusoids"): row p of the tables rotates pair i of a
+ * key at position p, (a, b) -> (a cos - b sin, a sin + b cos), with pair i = (x[i], x[i + rot_dim/2]), or
+ * (x[2i], x[2i+1]) when `interleaved`; features from rot_dim on are not rotated.  Given to ltea_rescore, the cache
+ * is taken to hold rotated keys and the scoring CNN sees them rotated back (same tables, negated sines, each row at
+ * its own position), rounded to cfg->dtype. */
+typedef struct ltea_rope {
+  const float *cos, *sin; /* [n_pos][rot_dim/2] fp32, device                                    */
+  int32_t n_pos;          /* table rows; every cached position must be below it                  */
+  int32_t rot_dim;        /* multiple of 16, <= D                                                */
+  int32_t interleaved;    /* 0 or 1                                                              */
+} ltea_rope;
+
+/* window - 2*rho (>= 1), or 0 on invalid arguments. */
+int32_t ltea_lazy_period(const ltea_cfg *cfg, const ltea_cnn *cnn);
+
+/* Workspace of ltea_rescore: the packed ring rows of all sequences, their logits and the scoring kernels' own
+ * workspace (about 2 * n_seqs * window * Hkv * D elements). */
+size_t ltea_rescore_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs);
+
+/* Batched scoring of the unscored in-window positions (see above).  rope_or_null: NULL scores the cached keys as
+ * they are.  Only win_score and n_scored of `cache` are written. */
+int ltea_rescore(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope_or_null, const ltea_cache *cache,
+                 int32_t n_seqs, int32_t *status_or_null, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ltea_decode_step without step 1: position t - window is evicted on the logit win_score already holds for it,
+ * n_scored is left alone.  Arguments as ltea_decode_step; workspace: ltea_decode_workspace_bytes(cfg, NULL, n_seqs). */
+int ltea_decode_step_lazy(const ltea_cfg *cfg, const void *q, const void *k, const void *v, void *out,
+                          const ltea_cache *cache, int32_t n_seqs, int32_t *status_or_null, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* ---- measurement aids (not part of the method; the hot-path entry points above never call them) ----------
  * What the chip sustains on the two resources the roofline figures are quoted against, so that a report can
  * give a fraction of the measured ceiling next to the fraction of the datasheet peak.  Both launch

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libltea.so")
 
 LTEA_F32, LTEA_BF16 = 0, 1
 LTEA_OK, LTEA_EINVAL, LTEA_EUNSUPPORTED, LTEA_EWORKSPACE, LTEA_EHIP = 0, -1, -2, -3, -4
+LTEA_LATE_SCORING, LTEA_ROPE_RANGE = 1, 2
 MAX_LAYERS = 4
 
 
@@ -49,9 +50,15 @@ class ltea_cache(C.Structure):
                 ("n_scored", C.c_void_p)]
 
 
+class ltea_rope(C.Structure):
+    _fields_ = [("cos", C.c_void_p), ("sin", C.c_void_p), ("n_pos", C.c_int32), ("rot_dim", C.c_int32),
+                ("interleaved", C.c_int32)]
+
+
 EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_append_workspace_bytes",
-           "ltea_prefill_append", "ltea_diag_sink_bytes",
+           "ltea_prefill_append", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
+           "ltea_decode_step_lazy", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
 
 _lib = None
@@ -91,6 +98,14 @@ def lib() -> C.CDLL:
     L.ltea_prefill_append.restype = C.c_int
     L.ltea_prefill_append.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp,
                                       P(ltea_cache), vp, sz, vp]
+    L.ltea_lazy_period.restype = i32
+    L.ltea_lazy_period.argtypes = [P(ltea_cfg), P(ltea_cnn)]
+    L.ltea_rescore_workspace_bytes.restype = sz
+    L.ltea_rescore_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32]
+    L.ltea_rescore.restype = C.c_int
+    L.ltea_rescore.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), P(ltea_cache), i32, vp, vp, sz, vp]
+    L.ltea_decode_step_lazy.restype = C.c_int
+    L.ltea_decode_step_lazy.argtypes = [P(ltea_cfg), vp, vp, vp, vp, P(ltea_cache), i32, vp, vp, sz, vp]
     L.ltea_diag_sink_bytes.restype = sz
     L.ltea_diag_sink_bytes.argtypes = []
     L.ltea_diag_mfma_loop.restype = C.c_int
@@ -310,6 +325,55 @@ def ltea_decode_step(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, 
     _check(lib().ltea_decode_step(C.byref(cfg), C.byref(cnn.struct), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                   C.byref(cache.struct), B, _ptr(workspace), workspace.numel(), _stream()),
            "ltea_decode_step")
+    return out
+
+
+@dataclass
+class Rope:
+    """Device copies of the rotary tables plus the C struct pointing at them."""
+    struct: ltea_rope
+    tensors: List[torch.Tensor]
+
+
+def upload_rope(cos, sin, interleaved: bool = False, device="cuda") -> Rope:
+    """cos, sin: [n_pos, rot_dim/2] host arrays (fp32)."""
+    ct = torch.as_tensor(cos).to(device=device, dtype=torch.float32).contiguous()
+    st = torch.as_tensor(sin).to(device=device, dtype=torch.float32).contiguous()
+    assert ct.shape == st.shape and ct.dim() == 2
+    return Rope(ltea_rope(ct.data_ptr(), st.data_ptr(), ct.shape[0], 2 * ct.shape[1], 1 if interleaved else 0), [ct, st])
+
+
+def ltea_lazy_period(cfg: ltea_cfg, cnn: Cnn) -> int:
+    return int(lib().ltea_lazy_period(C.byref(cfg), C.byref(cnn.struct)))
+
+
+def ltea_rescore_workspace_bytes(cfg: ltea_cfg, cnn: Cnn, n_seqs: int) -> int:
+    return int(lib().ltea_rescore_workspace_bytes(C.byref(cfg), C.byref(cnn.struct), n_seqs))
+
+
+def ltea_rescore(cfg: ltea_cfg, cnn: Cnn, cache: Cache, rope: Optional[Rope] = None,
+                 status: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> None:
+    """Batched scoring of the unscored in-window positions of every sequence of `cache`."""
+    B = cache.n_seen.numel()
+    if workspace is None:
+        workspace = _workspace(ltea_rescore_workspace_bytes(cfg, cnn, B), cache.n_seen.device)
+    _check(lib().ltea_rescore(C.byref(cfg), C.byref(cnn.struct), C.byref(rope.struct) if rope else None,
+                              C.byref(cache.struct), B, _ptr(status), _ptr(workspace), workspace.numel(), _stream()),
+           "ltea_rescore")
+
+
+def ltea_decode_step_lazy(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cache: Cache,
+                          out: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    B = q.shape[0]
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    if out is None:
+        out = torch.empty((B, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = _workspace(ltea_decode_workspace_bytes(cfg, None, B), q.device)
+    _check(lib().ltea_decode_step_lazy(C.byref(cfg), _ptr(q), _ptr(k), _ptr(v), _ptr(out), C.byref(cache.struct), B,
+                                       _ptr(status), _ptr(workspace), workspace.numel(), _stream()),
+           "ltea_decode_step_lazy")
     return out
 
 

@@ -304,4 +304,61 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
                                        static_cast<hipStream_t>(stream)));
 }
 
+int32_t ltea_lazy_period(const ltea_cfg* cfg, const ltea_cnn* cnn) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK) return 0;
+  return cfg->window - 2 * cnn_rho(cnn);
+}
+
+size_t ltea_rescore_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0) return 0;
+  return align_up(rescore_workspace(*cfg, n_seqs, nullptr, nullptr), 256) +
+         score_workspace(*cfg, *cnn, (int64_t)n_seqs * cfg->window);
+}
+
+int ltea_rescore(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope, const ltea_cache* cache,
+                 int32_t n_seqs, int32_t* status, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (n_seqs < 0) return LTEA_EINVAL;
+  if (rope) {
+    if (!rope->cos || !rope->sin || rope->n_pos < 1) return LTEA_EINVAL;
+    if (rope->rot_dim < 16 || rope->rot_dim > cfg->D || rope->rot_dim % 16 != 0) return LTEA_EINVAL;
+    if (rope->interleaved != 0 && rope->interleaved != 1) return LTEA_EINVAL;
+  }
+  if (n_seqs == 0) return LTEA_OK;
+  const int64_t total = (int64_t)n_seqs * cfg->window;
+  if (total >= (int64_t)1 << 31) return LTEA_EUNSUPPORTED;
+  const size_t pack_ws = align_up(rescore_workspace(*cfg, n_seqs, nullptr, nullptr), 256);
+  const size_t need = pack_ws + score_workspace(*cfg, *cnn, total);
+  if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  RescoreBuffers buf;
+  rescore_workspace(*cfg, n_seqs, &buf, workspace);
+  st = hip_status(launch_rescore_pack(*cfg, rope, *cache, n_seqs, cnn_rho(cnn), status, buf, s));
+  if (st != LTEA_OK) return st;
+  SeqView sv{buf.cu, n_seqs, total, cfg->window};
+  st = do_score(*cfg, *cnn, buf.pk, buf.pv, (int64_t)cfg->Hkv * cfg->D, cfg->D, sv, buf.logits,
+                static_cast<char*>(workspace) + pack_ws, s);
+  if (st != LTEA_OK) return st;
+  return hip_status(launch_rescore_scatter(*cfg, *cache, n_seqs, buf, s));
+}
+
+int ltea_decode_step_lazy(const ltea_cfg* cfg, const void* q, const void* k, const void* v, void* out,
+                          const ltea_cache* cache, int32_t n_seqs, int32_t* status, void* workspace,
+                          size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st != LTEA_OK) return st;
+  if (n_seqs < 0) return LTEA_EINVAL;
+  if (n_seqs == 0) return LTEA_OK;
+  if (!q || !k || !v || !out) return LTEA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return LTEA_EINVAL;
+  const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
+  if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  return hip_status(launch_decode_step_lazy(*cfg, q, k, v, out, *cache, n_seqs, status, workspace,
+                                            static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

@@ -26,6 +26,12 @@
 //                         row into the compact segment, writes k_t, v_t and the new logit into the ring, merges
 //                         the split partials of the group's query heads into the output row and advances
 //                         n_seen / n_scored.
+//
+// The lazy step (Section 3.1.3, lazy scoring) is the same pair of launches without a scoring role: logits are
+// produced between steps by the batched scoring of lazy.hip, the finishing launch leaves n_scored alone and flags a
+// token that leaves the window unscored.
+#include <string.h>
+
 #include <type_traits>
 
 #include "ltea_common.h"
@@ -63,6 +69,10 @@ struct StepParams {
   // sequence b occupies rows b*(2*rho+1) .. of pre_logits[h][.], its first row is position max(0, t - 2*rho).
   const float* pre_logits;
   int64_t pre_total;
+  // Lazy mode (scores come from separate batched launches between steps): nothing is scored here, n_scored is
+  // left alone, and a token that leaves the window without a final logit is reported through `status`.
+  int lazy;
+  int32_t* status;
 };
 
 // exp used by the softmax: library expf for fp32 storage (1e-5 tolerance), hardware exp2 path for bf16.
@@ -398,6 +408,12 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
 
   const int Hkv = P.Hkv, window = P.window, budget = P.budget;
   if ((int)blockIdx.x < P.n_score_blocks) {
+    if (P.lazy) {
+      // only the snapshot of the token counts that the finishing launch reads
+      const int b = blockIdx.x * kThreads + threadIdx.x;
+      if (b < P.B) ws_t[b] = C.n_seen[b];
+      return;
+    }
     if (P.pre_logits != nullptr) {
       // one thread per (sequence, head): pick the logit of position t - rho out of the sequence's window
       const int head = blockIdx.x * kThreads + threadIdx.x;
@@ -602,7 +618,9 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
   }
   const int cnt_old = budget > 0 ? C.ret_count[head] : 0;
   const float z_e = t >= window ? C.win_score[head * window + slot] : 0.f;
-  const float z_new = t - rho >= 0 ? ws_logit[head] : 0.f;
+  const float z_new = (!P.lazy && t - rho >= 0) ? ws_logit[head] : 0.f;
+  // lazy mode: the token leaving the window must have been scored by a batched scoring call
+  const bool late = P.lazy && t >= window && C.n_scored[b] <= t - window;
 
   // ---- merge split partials of the group's query heads ------------------------------------------------------
   const int G = P.Hq / Hkv, nsplit = P.nsplit;
@@ -620,7 +638,7 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
       L = fmaf(rec[s * (D + 2) + 1], f, L);
       A = fmaf(rec[s * (D + 2) + 2 + d], f, A);
     }
-    out[bh * D + d] = from_f32<T>(A / L);
+    out[bh * D + d] = from_f32<T>(late ? __builtin_nanf("") : A / L);
   }
 
   __syncthreads();  // every thread holds z_e and the old ring row before anything of this head is overwritten
@@ -641,10 +659,11 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
   }
   if (moves_k || moves_v) reinterpret_cast<u32x4*>(moves_k ? kw : vw)[pc] = new_piece;
   if (tid == 0) {
-    if (t - rho >= 0) C.win_score[head * window + ((t - rho) % window)] = z_new;
+    if (!P.lazy && t - rho >= 0) C.win_score[head * window + ((t - rho) % window)] = z_new;
     if (h == 0) {
       C.n_seen[b] = t + 1;
-      C.n_scored[b] = t + 1 > rho ? t + 1 - rho : 0;
+      if (!P.lazy) C.n_scored[b] = t + 1 > rho ? t + 1 - rho : 0;
+      if (late && P.status != nullptr) atomicOr(P.status, LTEA_LATE_SCORING);
     }
   }
 }
@@ -720,9 +739,14 @@ size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char
   return (size_t)(p - base);
 }
 
+// cnn_or_null == nullptr selects the lazy step (no scoring; `status` receives LTEA_LATE_SCORING).
 template <typename T, int D>
-hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v, void* out,
-               const ltea_cache& c, int n_seqs, void* workspace, bool prescore, hipStream_t stream) {
+hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, const void* k, const void* v, void* out,
+               const ltea_cache& c, int n_seqs, void* workspace, bool prescore, int32_t* status, hipStream_t stream) {
+  const bool lazy = cnn_or_null == nullptr;
+  ltea_cnn none;
+  memset(&none, 0, sizeof(none));
+  const ltea_cnn& cnn = lazy ? none : *cnn_or_null;
   CnnDev cd;
   cd.n_layers = cnn.n_layers;
   for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) {
@@ -746,11 +770,17 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const vo
   P.scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   const unsigned heads = (unsigned)n_seqs * (unsigned)cfg.Hkv;
   const int ks0 = cnn.kernel[0];
-  P.score_mfma = (cfg.dtype == LTEA_BF16 && cnn.n_layers == 1 && cnn.c_out[0] <= 32 && (ks0 == 3 || ks0 == 5 || ks0 == 7)) ? ks0 : 0;
+  P.score_mfma = (!lazy && cfg.dtype == LTEA_BF16 && cnn.n_layers == 1 && cnn.c_out[0] <= 32 && (ks0 == 3 || ks0 == 5 || ks0 == 7)) ? ks0 : 0;
   P.n_score_blocks = P.score_mfma ? cfg.Hkv * ((n_seqs + 63) / 64) : (int)heads;
   size_t lds_bytes = P.score_mfma ? 0 : (size_t)2 * (2 * P.rho + 1) * P.lds_row_floats * sizeof(float);
   P.pre_logits = nullptr;
   P.pre_total = 0;
+  P.lazy = lazy ? 1 : 0;
+  P.status = status;
+  if (lazy) {
+    P.n_score_blocks = (n_seqs + kThreads - 1) / kThreads;
+    lds_bytes = 0;
+  }
   if constexpr (sizeof(T) == 2) {
     if (prescore) {
       // multi-layer bf16 CNN: pack the receptive-field windows and run the fused prefill scoring kernel over them
@@ -818,13 +848,25 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
                               hipStream_t stream) {
   if (n_seqs == 0) return hipSuccess;
   if (cfg.dtype == LTEA_F32) {
-    return cfg.D == 64 ? run<float, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, false, stream)
-                       : run<float, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, false, stream);
+    return cfg.D == 64 ? run<float, 64>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream)
+                       : run<float, 128>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream);
   }
   // the window-scoring path needs the larger workspace; with the basic one the per-head path runs
   const bool prescore = window_scoring(cfg, cnn) && workspace_bytes >= decode_workspace_full(cfg, cnn, n_seqs);
-  return cfg.D == 64 ? run<bf16_t, 64>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, prescore, stream)
-                     : run<bf16_t, 128>(cfg, cnn, q, k, v, out, c, n_seqs, workspace, prescore, stream);
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, prescore, nullptr, stream)
+                     : run<bf16_t, 128>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, prescore, nullptr, stream);
+}
+
+hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const void* k, const void* v, void* out,
+                                   const ltea_cache& c, int n_seqs, int32_t* status, void* workspace,
+                                   hipStream_t stream) {
+  if (n_seqs == 0) return hipSuccess;
+  if (cfg.dtype == LTEA_F32) {
+    return cfg.D == 64 ? run<float, 64>(cfg, nullptr, q, k, v, out, c, n_seqs, workspace, false, status, stream)
+                       : run<float, 128>(cfg, nullptr, q, k, v, out, c, n_seqs, workspace, false, status, stream);
+  }
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, nullptr, q, k, v, out, c, n_seqs, workspace, false, status, stream)
+                     : run<bf16_t, 128>(cfg, nullptr, q, k, v, out, c, n_seqs, workspace, false, status, stream);
 }
 
 }  // namespace ltea

@@ -94,4 +94,23 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
                               void* out, const ltea_cache& cache, int n_seqs, void* workspace, size_t workspace_bytes,
                               hipStream_t stream);
 
+hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const void* k, const void* v, void* out,
+                                   const ltea_cache& cache, int n_seqs, int32_t* status, void* workspace,
+                                   hipStream_t stream);
+
+// ---- deferred batched scoring of the decode cache ---------------------------------------------------------
+struct RescoreBuffers {
+  void* pk; void* pv;     // [n_seqs * window][Hkv][D] ring rows in position order (keys rotated back if asked)
+  float* logits;          // [Hkv][n_seqs * window]
+  int32_t* cu;            // [n_seqs + 1] = b * window
+  int32_t* plan;          // [n_seqs][3] = first packed position, first newly final position, end of them
+  int64_t total;          // n_seqs * window
+};
+// Carves the buffers from `base` (may be null when only the size is wanted); returns the bytes used.
+size_t rescore_workspace(const ltea_cfg& cfg, int n_seqs, RescoreBuffers* out, void* base);
+hipError_t launch_rescore_pack(const ltea_cfg& cfg, const ltea_rope* rope_or_null, const ltea_cache& cache, int n_seqs,
+                               int rho, int32_t* status, const RescoreBuffers& buf, hipStream_t stream);
+hipError_t launch_rescore_scatter(const ltea_cfg& cfg, const ltea_cache& cache, int n_seqs, const RescoreBuffers& buf,
+                                  hipStream_t stream);
+
 }  // namespace ltea

@@ -1,0 +1,175 @@
+"""GPU parity of the lazy-scoring decode path (Section 3.1.3, lazy scoring paragraph): ltea_decode_step_lazy steps
+with a batched ltea_rescore every ltea_lazy_period() steps, against the oracle.
+
+Without rotary tables the reference is the oracle's per-step decode (the definition: deferring the scoring must not
+change anything).  With them the cache holds rotated keys and the reference is the oracle's own lazy procedure,
+which rotates the cached keys back in fp64 and rounds them to the storage type like the kernel does.
+Bars as in test_gpu_parity.py; logits of un-rotated keys get LOGIT_TOL_ROPE because a feature that lands next to a
+bf16 rounding boundary may round differently after fp32 and fp64 arithmetic."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import LOGIT_TOL, DeviceWorkload, check_output, check_sets, dev, gpu_retained_sets, to_np
+from tests.helpers import oracle_cfg, oracle_cnn
+from tests.test_gpu_parity import logit_eps, make
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL_ROPE = 2e-3
+
+
+def compare_sets(cache, states, w, step):
+    for s, st in enumerate(states):
+        assert int(cache.n_seen[s]) == st.n_seen, step
+        for h in range(w.Hkv):
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(st)[h],
+                                          err_msg=f"step {step} seq {s} head {h}")
+
+
+def compare_ring_logits(cache, states, w, tol):
+    for s, st in enumerate(states):
+        assert int(cache.n_scored[s]) == st.n_scored
+        for h in range(w.Hkv):
+            for p, zp in st.heads[h].win_z.items():
+                zg = float(cache.win_score[s, h, p % w.window])
+                assert abs(zg - zp) <= tol * max(1.0, abs(zp)), (s, h, p, zg, zp)
+
+
+@pytest.mark.parametrize("name,every", [("f32_ragged_gqa", None), ("bf16_d64", None), ("bf16_d128_gqa", None),
+                                        ("bf16_d64_deep", None), ("bf16_d64", 7), ("f32_d128_deep", 5)])
+def test_lazy_decode_after_prefill(name, every):
+    """Prefill on the GPU, then lazy steps; a batched scoring every ltea_lazy_period() steps (the latest moment
+    that is allowed) or every `every` steps.  Outputs and retained sets equal the oracle's per-step decode at
+    every step; after each batched scoring the ring's logits and n_scored do too."""
+    w = make(name)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits)
+    _, states, z64, _ = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    eps = logit_eps(to_np(logits), z64, w.dtype)
+    assert not check_sets(cache, z64, w, eps), "pick another seed: a head sits inside the decision margin"
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    assert period == w.window - 2 * w.cnn.rho == orc.lazy_period(cfg, cnn)
+    gap = period if every is None else every
+    n_steps = int(2.3 * period) if every is None else 60
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    since = 0
+    for step in range(n_steps):
+        if since == gap:
+            B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+            compare_ring_logits(cache, states, w, LOGIT_TOL[w.dtype])
+            since = 0
+        q, k, v = wl.decode_inputs(w.seed, step, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+        out = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q, w.dtype), dev(k, w.dtype), dev(v, w.dtype), cache, status=status))
+        since += 1
+        ref = np.stack([orc.decode_step(states[s], q[s], k[s], v[s], cfg, cnn) for s in range(w.n_seqs)])
+        check_output(out, ref, w.dtype, f"{name} step {step}")
+        compare_sets(cache, states, w, step)
+    B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+    compare_ring_logits(cache, states, w, LOGIT_TOL[w.dtype])
+    assert int(status.item()) == 0
+    # the invariant of the eager step holds again: continue with eager steps
+    for step in range(n_steps, n_steps + 5):
+        q, k, v = wl.decode_inputs(w.seed, step, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+        out = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q, w.dtype), dev(k, w.dtype), dev(v, w.dtype), cache))
+        ref = np.stack([orc.decode_step(states[s], q[s], k[s], v[s], cfg, cnn) for s in range(w.n_seqs)])
+        check_output(out, ref, w.dtype, f"{name} eager step {step}")
+        compare_sets(cache, states, w, step)
+
+
+ROPE_CASES = {
+    # name: (dtype, D, rot_dim, interleaved, kernel, channels, dilation, window, budget, sink, n, B)
+    "bf16_d64_half_rot32": ("bf16", 64, 32, False, (5,), (32,), None, 40, 12, 1, 130, 3),
+    "bf16_d128_interleaved_full": ("bf16", 128, 128, True, (3, 3, 3), (64, 32, 16), (2, 2, 2), 48, 10, 2, 120, 2),
+    "bf16_d128_half_full": ("bf16", 128, 128, False, (7,), (32,), None, 64, 16, 0, 150, 2),
+    "f32_d64_half_rot64": ("f32", 64, 64, False, (3, 3), (16, 8), (1, 2), 32, 8, 1, 100, 2),
+}
+
+
+@pytest.mark.parametrize("name", list(ROPE_CASES))
+def test_lazy_decode_rotated_cache_from_empty(name):
+    """The cache receives rotated keys token by token from a zeroed state; every batched scoring rotates the ring's
+    keys back with the tables and negated sines.  Reference: the oracle's lazy procedure with its own inverse
+    rotation (fp64, rounded to the storage type)."""
+    dt, D, rot, inter, ker, ch, dil, window, budget, sink, n, B_ = ROPE_CASES[name]
+    w = wl.make_prefill(name, sum(map(ord, name)), dt, [n] * B_, 4, 2, D, window, budget, sink, 0.0, cnn_kernel=ker,
+                        cnn_channels=ch, cnn_dilation=dil, w_std=0.1)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    cos, sin = wl.rope_tables(n + 8, rot, 100.0)
+    rope_o = orc.OracleRope(cos.astype(np.float64), sin.astype(np.float64), inter)
+    rope_g = B.upload_rope(cos, sin, inter)
+    rounder = (lambda x: wl.to_storage(x.astype(np.float32), dt).astype(np.float64))
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    states = [orc.empty_state(cfg) for _ in range(B_)]
+    q3 = w.q.reshape(B_, n, w.Hq, D); k3 = w.k.reshape(B_, n, w.Hkv, D); v3 = w.v.reshape(B_, n, w.Hkv, D)
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tol = LOGIT_TOL_ROPE if dt == "bf16" else 1e-4
+    n_rescore = 0
+    for t in range(n):
+        if t % period == 0 and t > 0:
+            B.ltea_rescore(d.cfg, d.cnn, cache, rope=rope_g, status=status)
+            for st in states:
+                orc.rescore(st, cfg, cnn, rope_o, rounder)
+            compare_ring_logits(cache, states, w, tol)
+            n_rescore += 1
+        out = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache,
+                                            status=status))
+        ref = np.stack([orc.decode_step_lazy(states[s], q3[s, t], k3[s, t], v3[s, t], cfg) for s in range(B_)])
+        check_output(out, ref, dt, f"{name} step {t}")
+        compare_sets(cache, states, w, t)
+    assert n_rescore >= 2
+    assert int(status.item()) == 0
+    # the un-rotation matters: scoring the same ring without the tables gives other logits
+    B.ltea_rescore(d.cfg, d.cnn, cache, rope=rope_g, status=status)
+    with_rope = cache.win_score.clone()
+    cache.n_scored.copy_(torch.clamp(cache.n_seen - window + w.cnn.rho, min=0))
+    B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+    assert float((cache.win_score - with_rope).abs().max()) > 1e-3
+
+
+def test_lazy_status_flags():
+    """Skipping the batched scoring for longer than the period, and rotary tables that are too short, are reported
+    through the status word; every kernel still completes."""
+    w = make("bf16_d64")
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache)
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    rho = w.cnn.rho
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    lens = np.diff(w.cu_seqlens)
+    assert np.all(lens >= rho)
+    out = None
+    # the step itself notices once the token that leaves is unscored: window - rho steps after the last scoring
+    for step in range(w.window - rho + 1):
+        q, k, v = wl.decode_inputs(w.seed, step, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+        out = B.ltea_decode_step_lazy(d.cfg, dev(q, w.dtype), dev(k, w.dtype), dev(v, w.dtype), cache, status=status)
+        if step == w.window - rho - 1:
+            assert int(status.item()) == 0 and not bool(torch.isnan(out.float()).any())
+    assert int(status.item()) & B.LTEA_LATE_SCORING
+    assert bool(torch.isnan(out.float()).all())
+    # a batched scoring that comes too late says so as well
+    status.zero_()
+    B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+    assert int(status.item()) & B.LTEA_LATE_SCORING
+    # tables shorter than the cached positions
+    cache2 = d.new_cache()
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache2)
+    q, k, v = wl.decode_inputs(w.seed, 0, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+    B.ltea_decode_step_lazy(d.cfg, dev(q, w.dtype), dev(k, w.dtype), dev(v, w.dtype), cache2)
+    cos, sin = wl.rope_tables(16, 64)
+    status.zero_()
+    B.ltea_rescore(d.cfg, d.cnn, cache2, rope=B.upload_rope(cos, sin), status=status)
+    assert int(status.item()) == B.LTEA_ROPE_RANGE
+    # without a status word the same calls still run
+    B.ltea_rescore(d.cfg, d.cnn, cache2, rope=B.upload_rope(cos, sin))
+    torch.cuda.synchronize()
