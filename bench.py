@@ -218,9 +218,41 @@ def bench_decode(args):
     cnt = cache.ret_count.cpu().numpy().astype(np.int64)
     bytes_per_step = int(((st.window + cnt) * 2 * st.D * 2).sum())
     gbs = bytes_per_step / (us_per_step * 1e-6) / 1e9
+    # lazy scoring: the same steps without per-step scoring + one batched scoring per ltea_lazy_period() steps
+    period = B.ltea_lazy_period(cfg, cnn)
+    rws = torch.empty(B.ltea_rescore_workspace_bytes(cfg, cnn, st.B), dtype=torch.uint8, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    lws = B.decode_workspace(cfg, None, st.B)
+    for i in range(8):
+        q, k, v = steps_in[i]
+        B.ltea_decode_step_lazy(cfg, q, k, v, cache, out=out, status=status, workspace=lws)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(n_steps):
+        q, k, v = steps_in[i]
+        B.ltea_decode_step_lazy(cfg, q, k, v, cache, out=out, status=status, workspace=lws)
+    e1.record()
+    torch.cuda.synchronize()
+    lazy_us = e0.elapsed_time(e1) * 1e3 / n_steps
+    oldest = torch.clamp(cache.n_seen - st.window + c.rho, min=0)   # a batched scoring at the last allowed moment
+    B.ltea_rescore(cfg, cnn, cache, status=status, workspace=rws)
+    reps = 5
+    rescore_ms = 0.0
+    for _ in range(reps):
+        cache.n_scored.copy_(oldest)
+        torch.cuda.synchronize()
+        e0.record()
+        B.ltea_rescore(cfg, cnn, cache, status=status, workspace=rws)
+        e1.record()
+        torch.cuda.synchronize()
+        rescore_ms += e0.elapsed_time(e1) / reps
+    assert int(status.item()) == 0, "lazy decode reported late scoring"
+    lazy = dict(us_per_step=lazy_us, rescore_us=rescore_ms * 1e3, period=period,
+                amortised_us_per_step=lazy_us + rescore_ms * 1e3 / period,
+                frac_of_hbm_peak=bytes_per_step / ((lazy_us + rescore_ms * 1e3 / period) * 1e-6) / 1e9 / PEAK_HBM_GBS)
     return dict(workload="decode_bf16: B=64 H=16 D=128 window=1024 retained=512 n_seen=8192, 256 steps, cnn k5 c32",
                 us_per_step=us_per_step, us_per_token=us_per_step / st.B, wall_us_per_step=wall_us,
-                algorithmic_bytes_per_step=bytes_per_step,
+                algorithmic_bytes_per_step=bytes_per_step, lazy=lazy,
                 roofline=dict(bound="hbm", kernel="decode step (all launches)", achieved=gbs, peak=PEAK_HBM_GBS,
                               unit="GB/s", frac=gbs / PEAK_HBM_GBS,
                               traffic=measured_traffic("decode_bf16", "decode_main_kernel")))
@@ -386,7 +418,8 @@ def main():
     add_measured_fraction(line["scoring_roofline"], ceilings)
     if not args.no_decode:
         dec = bench_decode(args)
-        log(f"[bench] decode {dec['us_per_step']:.1f} us/step")
+        log(f"[bench] decode {dec['us_per_step']:.1f} us/step; lazy {dec['lazy']['us_per_step']:.1f} us/step + "
+            f"{dec['lazy']['rescore_us']:.0f} us per {dec['lazy']['period']} steps")
         add_measured_fraction(dec.get("roofline"), ceilings)
         line["decode"] = dec
     if args.chunks > 1:

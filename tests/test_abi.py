@@ -167,3 +167,45 @@ def test_append_argument_errors():
     assert call(args(cfg=C.byref(f32))) == B.LTEA_EUNSUPPORTED            # continuation exists on the bf16 path only
     assert L.ltea_append_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 32, 32) > 0
     assert L.ltea_append_workspace_bytes(None, C.byref(cnn), 1, 32, 32) == 0
+
+
+def test_lazy_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    cache = B.ltea_cache()
+    for name, _ in cache._fields_:
+        setattr(cache, name, 0x1000)
+    rho = 2
+    assert L.ltea_lazy_period(C.byref(cfg), C.byref(cnn)) == cfg.window - 2 * rho
+    assert L.ltea_lazy_period(None, C.byref(cnn)) == 0
+    assert L.ltea_lazy_period(C.byref(cfg), None) == 0
+    need = L.ltea_rescore_workspace_bytes(C.byref(cfg), C.byref(cnn), 3)
+    assert need >= 2 * 3 * cfg.window * cfg.Hkv * cfg.D * 2
+    assert L.ltea_rescore_workspace_bytes(C.byref(cfg), None, 3) == 0
+    rs = lambda **kw: L.ltea_rescore(*[dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), rope=None, cache=C.byref(cache), n=3,
+                                                 status=None, ws=0x1000, ws_bytes=1 << 40, stream=None), **kw)[k]
+                                       for k in ("cfg", "cnn", "rope", "cache", "n", "status", "ws", "ws_bytes", "stream")])
+    assert rs(cfg=None) == B.LTEA_EINVAL
+    assert rs(cnn=None) == B.LTEA_EINVAL
+    assert rs(cache=None) == B.LTEA_EINVAL
+    assert rs(n=-1) == B.LTEA_EINVAL
+    assert rs(n=0) == B.LTEA_OK
+    assert rs(ws=None) == B.LTEA_EWORKSPACE
+    assert rs(ws_bytes=need - 1) == B.LTEA_EWORKSPACE
+    rope = lambda **kw: C.byref(B.ltea_rope(**dict(dict(cos=0x1000, sin=0x1000, n_pos=100, rot_dim=32, interleaved=0), **kw)))
+    assert rs(rope=rope(cos=None)) == B.LTEA_EINVAL
+    assert rs(rope=rope(n_pos=0)) == B.LTEA_EINVAL
+    assert rs(rope=rope(rot_dim=24)) == B.LTEA_EINVAL              # not a multiple of 16
+    assert rs(rope=rope(rot_dim=128)) == B.LTEA_EINVAL             # wider than the head (D = 64)
+    assert rs(rope=rope(interleaved=2)) == B.LTEA_EINVAL
+    st = lambda **kw: L.ltea_decode_step_lazy(*[dict(dict(cfg=C.byref(cfg), q=0x1000, k=0x1000, v=0x1000, out=0x1000,
+                                                          cache=C.byref(cache), n=2, status=None, ws=0x1000,
+                                                          ws_bytes=1 << 30, stream=None), **kw)[k]
+                                                for k in ("cfg", "q", "k", "v", "out", "cache", "n", "status", "ws", "ws_bytes", "stream")])
+    assert st(cfg=None) == B.LTEA_EINVAL
+    assert st(q=None) == B.LTEA_EINVAL
+    assert st(out=0x1004) == B.LTEA_EINVAL
+    assert st(cache=None) == B.LTEA_EINVAL
+    assert st(n=-1) == B.LTEA_EINVAL
+    assert st(n=0) == B.LTEA_OK
+    assert st(ws_bytes=16) == B.LTEA_EWORKSPACE

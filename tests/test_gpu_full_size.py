@@ -186,29 +186,56 @@ def oracle_state_of_sequence(st, b, win_z64, cfg):
     return s
 
 
-def test_full_decode_bf16():
+_decode_state_cache = {}
+
+
+def decode_bf16_with_oracle_logits():
+    if "st" not in _decode_state_cache:
+        st = wl.config_decode_bf16()
+        ocnn = oracle_cnn(st.cnn)
+        print("[decode_bf16] scoring 1024 rings with the oracle", flush=True)
+        win_z = np.zeros((st.B, st.Hkv, st.window), dtype=np.float64)
+        for b in range(st.B):
+            kb = np.transpose(st.k_win[b], (1, 0, 2))   # [window, Hkv, D]
+            vb = np.transpose(st.v_win[b], (1, 0, 2))
+            win_z[b] = orc.score_sequence(kb, vb, ocnn)
+        _decode_state_cache["st"] = (st, ocnn, win_z)
+    return _decode_state_cache["st"]
+
+
+@pytest.mark.parametrize("lazy", [False, True])
+def test_full_decode_bf16(lazy):
     """decode_bf16 at full size (B=64, H=16, D=128, window 1024, 512 retained): ring logits from the oracle on all
     1024 rings, 48 steps on the GPU; outputs against the oracle on two sampled sequences at every step; the
-    eviction rule replayed by the oracle on ALL (sequence, head) pairs."""
-    st = wl.config_decode_bf16()
+    eviction rule replayed by the oracle on ALL (sequence, head) pairs.
+    lazy: the cache starts with only the oldest rho logits of each ring final (the latest moment a batched scoring
+    may come); ltea_rescore must reproduce the oracle's logits of ALL rings, then the steps are lazy ones."""
+    st, ocnn, win_z = decode_bf16_with_oracle_logits()
     ocfg = orc.OracleCfg(st.Hq, st.Hkv, st.D, st.window, st.budget, st.sink, st.tau)
-    ocnn = oracle_cnn(st.cnn)
     rho = st.cnn.rho
-    print("[decode_bf16] scoring 1024 rings with the oracle", flush=True)
-    win_z = np.zeros((st.B, st.Hkv, st.window), dtype=np.float64)
-    for b in range(st.B):
-        kb = np.transpose(st.k_win[b], (1, 0, 2))   # [window, Hkv, D]
-        vb = np.transpose(st.v_win[b], (1, 0, 2))
-        win_z[b] = orc.score_sequence(kb, vb, ocnn)
     dt = st.dtype
     cfg = B.make_cfg(st.Hq, st.Hkv, st.D, st.window, st.budget, st.sink, st.tau, 0.0, dt)
     c = st.cnn
     cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, dt)
-    cache = B.wrap_cache(dev(st.k_win, dt), dev(st.v_win, dt), torch.from_numpy(win_z.astype(np.float32)).cuda(),
+    z0 = win_z.astype(np.float32)
+    scored0 = (st.n_seen - rho).astype(np.int32)
+    if lazy:
+        z0 = z0.copy()
+        z0[:, :, rho:] = np.nan                       # ring slot i holds position n - window + i (n % window == 0)
+        scored0 = (st.n_seen - st.window + rho).astype(np.int32)
+    cache = B.wrap_cache(dev(st.k_win, dt), dev(st.v_win, dt), torch.from_numpy(z0).cuda(),
                          dev(st.k_ret, dt), dev(st.v_ret, dt), torch.from_numpy(st.ret_score).cuda(),
                          torch.from_numpy(st.ret_pos).cuda(), torch.from_numpy(st.ret_count).cuda(),
-                         torch.from_numpy(st.n_seen).cuda(),
-                         torch.from_numpy((st.n_seen - rho).astype(np.int32)).cuda())
+                         torch.from_numpy(st.n_seen).cuda(), torch.from_numpy(scored0).cuda())
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    if lazy:
+        assert B.ltea_lazy_period(cfg, cnn) == st.window - 2 * rho
+        B.ltea_rescore(cfg, cnn, cache, status=status)
+        zg = cache.win_score.cpu().numpy().astype(np.float64)
+        ref = win_z[:, :, :st.window - rho]
+        assert np.all(np.abs(zg[:, :, :st.window - rho] - ref) <= LOGIT_TOL["bf16"] * np.maximum(1.0, np.abs(ref)))
+        assert np.all(np.isnan(zg[:, :, st.window - rho:]))        # provisional positions are not written
+        assert np.all(cache.n_scored.cpu().numpy() == st.n_seen - rho) and int(status.item()) == 0
     sampled = [0, 37]
     states = {b: oracle_state_of_sequence(st, b, win_z[b], ocfg) for b in sampled}
     # position-only oracle records for every (sequence, head): the eviction rule needs logits and keys only
@@ -221,7 +248,10 @@ def test_full_decode_bf16():
     worst, scale = 0.0, 0.0
     for step in range(n_steps):
         q, k, v = wl.decode_inputs(st.seed, step, dt, st.B, st.Hq, st.Hkv, st.D)
-        out = B.ltea_decode_step(cfg, cnn, dev(q, dt), dev(k, dt), dev(v, dt), cache)
+        if lazy:
+            out = B.ltea_decode_step_lazy(cfg, dev(q, dt), dev(k, dt), dev(v, dt), cache, status=status)
+        else:
+            out = B.ltea_decode_step(cfg, cnn, dev(q, dt), dev(k, dt), dev(v, dt), cache)
         og = out[sampled].float().cpu().numpy()
         for i, b in enumerate(sampled):
             ref = orc.decode_step(states[b], q[b], k[b], v[b], ocfg, ocnn)
@@ -237,6 +267,10 @@ def test_full_decode_bf16():
     assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale
     torch.cuda.synchronize()
     assert np.all(cache.n_seen.cpu().numpy() == n0 + n_steps)
+    if lazy:
+        assert np.all(cache.n_scored.cpu().numpy() == n0 - rho)
+        B.ltea_rescore(cfg, cnn, cache, status=status)
+        assert np.all(cache.n_scored.cpu().numpy() == n0 + n_steps - rho) and int(status.item()) == 0
     pos = cache.ret_pos.cpu().numpy()
     cnt = cache.ret_count.cpu().numpy()
     for b in range(st.B):
