@@ -474,3 +474,89 @@ def decode_step_lazy(st: SeqState, q_t, k_t, v_t, cfg: OracleCfg) -> np.ndarray:
             out[hq] = attend(q_t[hq], K, V, cfg.sigma)
     st.n_seen = t + 1
     return out
+
+
+# --------------------------------------------------------------------------
+# O8: training-side forward and backward (Section 3.1.2 "Adaptive training"; Algorithm 1)
+# --------------------------------------------------------------------------
+def train_keep_mask(z_head: np.ndarray, sink: int, tau: float) -> np.ndarray:
+    """Uncapped eq. 5: token j stays visible after it has left a query's window iff it is a sink or its fp32
+    logit exceeds tau (no budget during training)."""
+    z32 = np.asarray(z_head, dtype=np.float32)
+    keep = z32 > np.float32(tau)
+    keep[:sink] = True
+    return keep
+
+
+def train_forward_sequence(q_seq, k_seq, v_seq, z_seq, cfg: OracleCfg):
+    """Masked attention of one sequence as used in training: query i sees j <= i with j > i-w, or kept j.
+    Returns (out [n,Hq,D], lse [Hq,n] natural-log normaliser of the scaled scores, P [Hq,n,n])."""
+    q = np.asarray(q_seq, np.float64); k = np.asarray(k_seq, np.float64); v = np.asarray(v_seq, np.float64)
+    n = q.shape[0]
+    i = np.arange(n)[:, None]
+    j = np.arange(n)[None, :]
+    out = np.zeros((n, cfg.Hq, cfg.D)); lse = np.zeros((cfg.Hq, n)); P = np.zeros((cfg.Hq, n, n))
+    for hq in range(cfg.Hq):
+        h = hq // cfg.G
+        keep = train_keep_mask(z_seq[h], cfg.sink, cfg.tau)
+        allowed = (j <= i) & ((j > i - cfg.window) | keep[None, :])
+        s = np.where(allowed, cfg.sigma * (q[:, hq] @ k[:, h].T), NEG_INF)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        l = e.sum(axis=1, keepdims=True)
+        P[hq] = e / l
+        lse[hq] = (m + np.log(l))[:, 0]
+        out[:, hq] = P[hq] @ v[:, h]
+    return out, lse, P
+
+
+def sparsity_threshold(tau: float) -> float:
+    """Retention score at the logit threshold (0.5 for tau = 0)."""
+    return 0.0 if tau == NEG_INF else 1.0 / (1.0 + np.exp(-float(tau)))
+
+
+def train_backward_sequence(q_seq, k_seq, v_seq, z_seq, dout, cfg: OracleCfg, lam: np.ndarray):
+    """Gradients of a loss with d(loss)/d(out) = dout through train_forward_sequence, plus the surrogate gradient
+    of the retention scores: d(loss)/d r_j := <v_j, d(loss)/d v_j> (straight-through estimator on a conceptual
+    mask multiplying v_j), and the gradient of the sparsity penalty sum_h lam_h sum_j ReLU(r_j - r_tau).  Both
+    reach the logits through r = sigmoid(z).  Returns dq [n,Hq,D], dk, dv [n,Hkv,D], dz [Hkv,n] and the
+    retention counts c [Hkv] = #{j : r_j > r_tau}."""
+    q = np.asarray(q_seq, np.float64); k = np.asarray(k_seq, np.float64); v = np.asarray(v_seq, np.float64)
+    do = np.asarray(dout, np.float64)
+    n = q.shape[0]
+    out, lse, P = train_forward_sequence(q, k, v, z_seq, cfg)
+    dq = np.zeros_like(q); dk = np.zeros_like(k); dv = np.zeros_like(v)
+    for hq in range(cfg.Hq):
+        h = hq // cfg.G
+        dv[:, h] += P[hq].T @ do[:, hq]
+        dP = do[:, hq] @ v[:, h].T
+        delta = np.sum(do[:, hq] * out[:, hq], axis=1, keepdims=True)
+        dS = P[hq] * (dP - delta)
+        dq[:, hq] = cfg.sigma * (dS @ k[:, h])
+        dk[:, h] += cfg.sigma * (dS.T @ q[:, hq])
+    z = np.asarray(z_seq, np.float64)
+    r = retention_score(z)
+    active = np.asarray(z_seq, np.float32) > np.float32(cfg.tau)       # r > r_tau, decided on the fp32 logit
+    g_r = np.einsum("nhd,nhd->hn", v, dv) + np.asarray(lam, np.float64)[:, None] * active
+    dz = g_r * r * (1.0 - r)
+    return dq, dk, dv, dz, active.sum(axis=1).astype(np.int64)
+
+
+def ema_count(c_bar: np.ndarray, c: np.ndarray, u: int) -> np.ndarray:
+    """Moving average of the retention counts with coefficient 2 / (1 + u/2) (Appendix, training details)."""
+    a = 2.0 / (1.0 + u / 2.0)
+    return a * np.asarray(c_bar, np.float64) + (1.0 - a) * np.asarray(c, np.float64)
+
+
+def lambda_update(lam: np.ndarray, c_bar: np.ndarray, cap: float, alpha: float) -> np.ndarray:
+    """Feedback step on the penalty weights (Algorithm 1): grow by alpha where the averaged count exceeds the cap,
+    shrink where it is below 0.95 cap, clamp to <= 1, flush values below 1e-9 to zero, and restart from 1e-9
+    where the count is too high while the weight is zero."""
+    lam = np.asarray(lam, np.float64).copy()
+    c_bar = np.asarray(c_bar, np.float64)
+    s = (c_bar > cap).astype(np.float64) - (c_bar < 0.95 * cap).astype(np.float64)
+    lam = lam * alpha ** s
+    lam = np.minimum(lam, 1.0)
+    lam[lam < 1e-9] = 0.0
+    lam[(c_bar > cap) & (lam == 0.0)] = 1e-9
+    return lam

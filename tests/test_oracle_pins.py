@@ -489,3 +489,106 @@ def _unscaled(qv, K, V):
     s = K @ qv
     p = np.exp(s - s.max())
     return (p / p.sum()) @ V
+
+
+# ---- P17: training-side forward / backward ---------------------------------------------------
+def _train_case(seed=50, n=40, window=9, sink=1, G=2, Hkv=2, D=8):
+    w = small_prefill(seed=seed, seqlens=(n,), Hq=Hkv * G, Hkv=Hkv, D=D, window=window, budget=5, sink=sink, kernel=(3,))
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    z = orc.score(w.k, w.v, cnn, w.cu_seqlens) * 20.0          # spread the logits so that both signs occur
+    rng = np.random.default_rng(seed + 1)
+    dout = rng.normal(size=(n, cfg.Hq, D))
+    return w, cfg, z, dout
+
+
+def test_p17_training_forward_is_the_uncapped_mask_of_eq5():
+    w, cfg, z, _ = _train_case()
+    out, lse, P = orc.train_forward_sequence(w.q, w.k, w.v, z, cfg)
+    n = w.q.shape[0]
+    keep = [[j for j in range(n) if j < cfg.sink or np.float32(z[h, j]) > 0] for h in range(cfg.Hkv)]
+    assert 0 < len(keep[0]) < n
+    ref = dense_masked_attention(w.q, w.k, w.v, keep, cfg.window, cfg.sigma, cfg.G)
+    np.testing.assert_allclose(out, ref, atol=1e-12)
+    np.testing.assert_allclose(P.sum(axis=2), 1.0, atol=1e-12)
+    # equals the inference prefill whenever the cap does not bind (budget >= n)
+    big = orc.OracleCfg(cfg.Hq, cfg.Hkv, cfg.D, cfg.window, n, cfg.sink, cfg.tau)
+    kept = [orc.retain(z[h], n, cfg.window, n, cfg.sink, cfg.tau) for h in range(cfg.Hkv)]
+    np.testing.assert_allclose(out, orc.sparse_attention_sequence(w.q, w.k, w.v, big, kept), atol=1e-12)
+    # the normaliser: exp(s - lse) are the probabilities
+    s00 = cfg.sigma * (np.asarray(w.q[5, 0], np.float64) @ np.asarray(w.k[5, 0], np.float64))
+    assert abs(np.exp(s00 - lse[0, 5]) - P[0, 5, 5]) < 1e-12
+
+
+def test_p17_backward_matches_library_autograd_and_finite_differences():
+    torch = pytest.importorskip("torch")
+    w, cfg, z, dout = _train_case()
+    lam = np.array([0.3, 0.0])
+    dq, dk, dv, dz, c = orc.train_backward_sequence(w.q, w.k, w.v, z, dout, cfg, lam)
+    n = w.q.shape[0]
+    # library autograd through a dense masked softmax
+    tq = torch.tensor(np.asarray(w.q, np.float64), requires_grad=True)
+    tk = torch.tensor(np.asarray(w.k, np.float64), requires_grad=True)
+    tv = torch.tensor(np.asarray(w.v, np.float64), requires_grad=True)
+    i = torch.arange(n)[:, None]; j = torch.arange(n)[None, :]
+    loss = 0.0
+    for hq in range(cfg.Hq):
+        h = hq // cfg.G
+        keep = torch.tensor(orc.train_keep_mask(z[h], cfg.sink, cfg.tau))
+        allowed = (j <= i) & ((j > i - cfg.window) | keep[None, :])
+        s = (tq[:, hq] @ tk[:, h].T) * cfg.sigma
+        p = torch.softmax(s.masked_fill(~allowed, float("-inf")), dim=1)
+        loss = loss + ((p @ tv[:, h]) * torch.tensor(dout[:, hq])).sum()
+    loss.backward()
+    np.testing.assert_allclose(dq, tq.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(dk, tk.grad.numpy(), atol=1e-11)
+    np.testing.assert_allclose(dv, tv.grad.numpy(), atol=1e-11)
+    # finite differences on the oracle's own forward for a few entries
+    def L(q, k, v):
+        return float((orc.train_forward_sequence(q, k, v, z, cfg)[0] * dout).sum())
+    rng = np.random.default_rng(3)
+    base = [np.asarray(x, np.float64) for x in (w.q, w.k, w.v)]
+    for which, grad in ((0, dq), (1, dk), (2, dv)):
+        for _ in range(4):
+            idx = tuple(int(rng.integers(0, s)) for s in base[which].shape)
+            hi = [x.copy() for x in base]; lo = [x.copy() for x in base]
+            hi[which][idx] += 1e-6; lo[which][idx] -= 1e-6
+            assert abs((L(*hi) - L(*lo)) / 2e-6 - grad[idx]) < 1e-6
+
+
+def test_p17_surrogate_gradient_of_the_retention_score():
+    """d(loss)/d r_j is the derivative with respect to a multiplier on v_j (mask held fixed); the penalty adds
+    lam_h where the token is active; both pass through the sigmoid's slope."""
+    w, cfg, z, dout = _train_case(seed=51)
+    lam = np.array([0.25, 0.5])
+    dq, dk, dv, dz, c = orc.train_backward_sequence(w.q, w.k, w.v, z, dout, cfg, lam)
+    v = np.asarray(w.v, np.float64)
+    r = 1.0 / (1.0 + np.exp(-z))
+    for (h, j) in ((0, 3), (1, 17), (0, 30), (1, 0)):
+        def L(mult):
+            v2 = v.copy(); v2[j, h] *= mult
+            return float((orc.train_forward_sequence(w.q, w.k, v2, z, cfg)[0] * dout).sum())
+        ste = (L(1 + 1e-6) - L(1 - 1e-6)) / 2e-6
+        active = 1.0 if np.float32(z[h, j]) > 0 else 0.0
+        assert abs(dz[h, j] - (ste + lam[h] * active) * r[h, j] * (1 - r[h, j])) < 1e-7
+    np.testing.assert_array_equal(c, (z.astype(np.float32) > 0).sum(axis=1))
+    # penalty alone: zero upstream gradient leaves lam * 1[r > 0.5] * r (1 - r)
+    *_, dz0, _ = orc.train_backward_sequence(w.q, w.k, w.v, z, np.zeros_like(dout), cfg, lam)
+    np.testing.assert_allclose(dz0, lam[:, None] * (z.astype(np.float32) > 0) * r * (1 - r), atol=1e-15)
+    # and it is the derivative of sum_h lam_h sum_j ReLU(r_j - 0.5) with respect to z
+    pen = lambda zz: float((lam[:, None] * np.maximum(1.0 / (1.0 + np.exp(-zz)) - 0.5, 0.0)).sum())
+    zz = z.copy(); h, j = 0, int(np.argmax(z[0])); zz[h, j] += 1e-6
+    zl = z.copy(); zl[h, j] -= 1e-6
+    assert abs((pen(zz) - pen(zl)) / 2e-6 - dz0[h, j]) < 1e-8
+    assert orc.sparsity_threshold(0.0) == 0.5 and orc.sparsity_threshold(-np.inf) == 0.0
+
+
+def test_p17_penalty_weight_feedback_follows_algorithm_1():
+    lam = np.array([1e-9, 0.5, 0.9, 2e-9, 0.0, 0.0, 1e-3])
+    cbar = np.array([600.0, 600.0, 600.0, 100.0, 600.0, 100.0, 500.0])       # cap 512: 0.95 cap = 486.4
+    got = orc.lambda_update(lam, cbar, 512.0, 2.0)
+    # grow x2 (clamped at 1) above the cap, shrink /2 below 0.95 cap (flushed to 0 under 1e-9), restart from 1e-9
+    # where it is zero but the count is too high, untouched inside the dead band
+    np.testing.assert_allclose(got, [2e-9, 1.0, 1.0, 1e-9, 1e-9, 0.0, 1e-3], rtol=1e-12)
+    np.testing.assert_allclose(orc.lambda_update(np.array([1.5e-9]), np.array([10.0]), 512.0, 2.0), [0.0])
+    # moving average: coefficient 2 / (1 + u/2)
+    np.testing.assert_allclose(orc.ema_count(np.array([100.0]), np.array([200.0]), 32), [2 / 17 * 100 + 15 / 17 * 200])
