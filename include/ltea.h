@@ -244,6 +244,43 @@ int ltea_decode_step_lazy(const ltea_cfg *cfg, const void *q, const void *k, con
                           const ltea_cache *cache, int32_t n_seqs, int32_t *status_or_null, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/* ---- training side (Section 3.1.2 "Adaptive training"; Algorithm 1) -----------------------------------------
+ * During training no cap applies: query i sees its window plus every candidate (sink, or logit > tau_logit) that
+ * has left it; cfg->budget is ignored by these entry points.  The forward is ltea_prefill's pipeline with the cap
+ * lifted and also returns the softmax normalisers; the state it leaves in `workspace` (the compacted candidates)
+ * must reach ltea_train_backward unchanged.  The CNN's own backward (d logits -> d weights, d features) and its
+ * dropout are not part of this library. */
+size_t ltea_train_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
+                                  int32_t max_seqlen);
+
+/* out: contiguous [total_tokens][Hq][D]; lse: [Hq][total_tokens] fp32, natural log of sum_j exp(scale q_i.k_j) over
+ * the keys query i sees; logits: [Hkv][total_tokens] fp32 (written).  Other arguments as ltea_prefill. */
+int ltea_train_forward(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
+                       int64_t q_stride_head, const void *k, const void *v, int64_t kv_stride_tok,
+                       int64_t kv_stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                       int32_t max_seqlen, void *out, float *lse, float *logits, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/* Gradients for d(loss)/d(out) = dout (contiguous [total_tokens][Hq][D], cfg->dtype):
+ *   dq [total_tokens][Hq][D], dk, dv [total_tokens][Hkv][D] (contiguous, cfg->dtype, fp32 accumulation; dk and dv
+ *   are the attention's gradients only: what flows into k, v through the scoring CNN is the caller's);
+ *   dz [Hkv][total_tokens] fp32 = (<v_j, dv_j> + lambda[h] * 1[logit_j > tau_logit]) * r_j (1 - r_j), r = sigmoid(logit):
+ *   the straight-through surrogate d(loss)/d r_j := <v_j, d(loss)/d v_j> plus the gradient of the sparsity penalty
+ *   sum_h lambda_h sum_j ReLU(r_j - sigmoid(tau_logit));
+ *   counts [n_seqs][Hkv] int32 = #{j : logit_j > tau_logit} (the c of the penalty-weight feedback).
+ * q, k, v, cu_seqlens, out, lse, logits: what ltea_train_forward was given / returned; lambda: [Hkv] fp32, device. */
+int ltea_train_backward(const ltea_cfg *cfg, const void *q, int64_t q_stride_tok, int64_t q_stride_head,
+                        const void *k, const void *v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                        const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen,
+                        const void *out, const void *dout, const float *lse, const float *logits, const float *lambda,
+                        void *dq, void *dk, void *dv, float *dz, int32_t *counts, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/* One feedback step on n penalty weights (Algorithm 1), on HOST arrays: lambda_i is multiplied by alpha where the
+ * averaged count c_bar_i exceeds cap, divided by alpha where it is below 0.95 cap, clamped to <= 1, flushed to 0
+ * below 1e-9, and restarted from 1e-9 where it is 0 while c_bar_i > cap. */
+int ltea_lambda_update(float *lambda, const float *c_bar, int32_t n, float cap, float alpha);
+
 /* ---- measurement aids (not part of the method; the hot-path entry points above never call them) ----------
  * What the chip sustains on the two resources the roofline figures are quoted against, so that a report can
  * give a fraction of the measured ceiling next to the fraction of the datasheet peak.  Both launch

@@ -58,7 +58,8 @@ class ltea_rope(C.Structure):
 EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_append_workspace_bytes",
            "ltea_prefill_append", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
-           "ltea_decode_step_lazy", "ltea_diag_sink_bytes",
+           "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
+           "ltea_lambda_update", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
 
 _lib = None
@@ -106,6 +107,16 @@ def lib() -> C.CDLL:
     L.ltea_rescore.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), P(ltea_cache), i32, vp, vp, sz, vp]
     L.ltea_decode_step_lazy.restype = C.c_int
     L.ltea_decode_step_lazy.argtypes = [P(ltea_cfg), vp, vp, vp, vp, P(ltea_cache), i32, vp, vp, sz, vp]
+    L.ltea_train_workspace_bytes.restype = sz
+    L.ltea_train_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
+    L.ltea_train_forward.restype = C.c_int
+    L.ltea_train_forward.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp, vp,
+                                     vp, vp, sz, vp]
+    L.ltea_train_backward.restype = C.c_int
+    L.ltea_train_backward.argtypes = [P(ltea_cfg), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp, vp, vp, vp, vp,
+                                      vp, vp, vp, vp, vp, vp, sz, vp]
+    L.ltea_lambda_update.restype = C.c_int
+    L.ltea_lambda_update.argtypes = [P(C.c_float), P(C.c_float), i32, C.c_float, C.c_float]
     L.ltea_diag_sink_bytes.restype = sz
     L.ltea_diag_sink_bytes.argtypes = []
     L.ltea_diag_mfma_loop.restype = C.c_int
@@ -375,6 +386,61 @@ def ltea_decode_step_lazy(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: to
                                        _ptr(status), _ptr(workspace), workspace.numel(), _stream()),
            "ltea_decode_step_lazy")
     return out
+
+
+def ltea_train_workspace_bytes(cfg: ltea_cfg, cnn: Cnn, n_seqs: int, total_tokens: int, max_seqlen: int) -> int:
+    return int(lib().ltea_train_workspace_bytes(C.byref(cfg), C.byref(cnn.struct), n_seqs, total_tokens, max_seqlen))
+
+
+def ltea_train_forward(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                       cu_seqlens: torch.Tensor, max_seqlen: int, workspace: Optional[torch.Tensor] = None):
+    """Training forward (no cap).  Returns (out, lse, logits, workspace); the workspace holds the state the
+    backward needs and must be passed to ltea_train_backward unchanged."""
+    T = q.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh)
+    out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    lse = torch.empty((cfg.Hq, T), dtype=torch.float32, device=q.device)
+    logits = torch.empty((cfg.Hkv, T), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = _workspace(ltea_train_workspace_bytes(cfg, cnn, n_seqs, T, max_seqlen), q.device)
+    _check(lib().ltea_train_forward(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
+                                    _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), _ptr(lse), _ptr(logits),
+                                    _ptr(workspace), workspace.numel(), _stream()), "ltea_train_forward")
+    return out, lse, logits, workspace
+
+
+def ltea_train_backward(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+                        max_seqlen: int, out: torch.Tensor, dout: torch.Tensor, lse: torch.Tensor,
+                        logits: torch.Tensor, lam: torch.Tensor, workspace: torch.Tensor):
+    """Returns (dq, dk, dv, dz, counts)."""
+    T = q.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    qst, qsh = _tok_head_strides(q)
+    st, sh = _tok_head_strides(k)
+    assert _tok_head_strides(v) == (st, sh) and out.is_contiguous() and dout.is_contiguous()
+    dq = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    dk = torch.empty((T, cfg.Hkv, cfg.D), dtype=q.dtype, device=q.device)
+    dv = torch.empty((T, cfg.Hkv, cfg.D), dtype=q.dtype, device=q.device)
+    dz = torch.empty((cfg.Hkv, T), dtype=torch.float32, device=q.device)
+    counts = torch.empty((n_seqs, cfg.Hkv), dtype=torch.int32, device=q.device)
+    _check(lib().ltea_train_backward(C.byref(cfg), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh, _ptr(cu_seqlens), n_seqs,
+                                     T, max_seqlen, _ptr(out), _ptr(dout), _ptr(lse), _ptr(logits), _ptr(lam), _ptr(dq),
+                                     _ptr(dk), _ptr(dv), _ptr(dz), _ptr(counts), _ptr(workspace), workspace.numel(),
+                                     _stream()), "ltea_train_backward")
+    return dq, dk, dv, dz, counts
+
+
+def ltea_lambda_update(lam, c_bar, cap: float, alpha: float):
+    """Host-side feedback step on the penalty weights; lam and c_bar are float32 numpy arrays (lam is updated)."""
+    import numpy as np
+    assert lam.dtype == np.float32 and c_bar.dtype == np.float32 and lam.size == c_bar.size
+    assert lam.flags["C_CONTIGUOUS"] and c_bar.flags["C_CONTIGUOUS"]
+    _check(lib().ltea_lambda_update(lam.ctypes.data_as(C.POINTER(C.c_float)), c_bar.ctypes.data_as(C.POINTER(C.c_float)),
+                                    lam.size, float(cap), float(alpha)), "ltea_lambda_update")
+    return lam
 
 
 def ltea_diag_sink(device="cuda") -> torch.Tensor:

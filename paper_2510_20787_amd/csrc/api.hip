@@ -85,10 +85,36 @@ int do_score(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void
 }
 
 int do_attention(const ltea_cfg& cfg, const void* q, int64_t qst, int64_t qsh, const void* k, const void* v,
-                 int64_t st, int64_t sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream) {
+                 int64_t st, int64_t sh, const SeqView& sv, const ltea_cache& c, void* out, hipStream_t stream,
+                 float* lse = nullptr) {
   if (attention_mfma_supported(cfg, st, sv.max_seqlen))
-    return hip_status(launch_attention_mfma(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
-  return hip_status(launch_attention_generic(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream));
+    return hip_status(launch_attention_mfma(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream, nullptr, nullptr, lse));
+  return hip_status(launch_attention_generic(cfg, q, qst, qsh, k, v, st, sh, sv, c, out, stream, lse));
+}
+
+// Saved state of a training forward, carved from the caller's workspace: an uncapped cache (compact arrays with
+// max_seqlen rows per head), the delta scratch of the backward, then the scoring kernels' own workspace.
+size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqlen, void* base, ltea_cache* c,
+                   float** delta) {
+  const size_t esz = (size_t)elem_size(cfg.dtype);
+  const size_t heads = (size_t)n_seqs * cfg.Hkv;
+  const size_t cap = (size_t)(max_seqlen > 1 ? max_seqlen : 1);
+  char* p = static_cast<char*>(base);
+  auto take = [&](size_t bytes) { char* r = p; p += align_up(bytes > 0 ? bytes : 1, 256); return r; };
+  void* k_ret = take(heads * cap * cfg.D * esz);
+  void* v_ret = take(heads * cap * cfg.D * esz);
+  float* ret_score = reinterpret_cast<float*>(take(heads * cap * 4));
+  int32_t* ret_pos = reinterpret_cast<int32_t*>(take(heads * cap * 4));
+  int32_t* ret_count = reinterpret_cast<int32_t*>(take(heads * 4));
+  void* k_win = take(heads * cfg.window * cfg.D * esz);
+  void* v_win = take(heads * cfg.window * cfg.D * esz);
+  float* win_score = reinterpret_cast<float*>(take(heads * cfg.window * 4));
+  int32_t* n_seen = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
+  int32_t* n_scored = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
+  float* d = reinterpret_cast<float*>(take((size_t)cfg.Hq * (size_t)total * 4));
+  if (c) *c = ltea_cache{k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored};
+  if (delta) *delta = d;
+  return (size_t)(p - static_cast<char*>(base));
 }
 
 }  // namespace
@@ -359,6 +385,94 @@ int ltea_decode_step_lazy(const ltea_cfg* cfg, const void* q, const void* k, con
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
   return hip_status(launch_decode_step_lazy(*cfg, q, k, v, out, *cache, n_seqs, status, workspace,
                                             static_cast<hipStream_t>(stream)));
+}
+
+size_t ltea_train_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs, int64_t total_tokens,
+                                  int32_t max_seqlen) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0 || total_tokens < 0 || max_seqlen < 0)
+    return 0;
+  return carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr) +
+         score_workspace(*cfg, *cnn, total_tokens);
+}
+
+int ltea_train_forward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok,
+                       int64_t q_stride_head, const void* k, const void* v, int64_t kv_stride_tok,
+                       int64_t kv_stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                       int32_t max_seqlen, void* out, float* lse, float* logits, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st != LTEA_OK) return st;
+  if (n_seqs == 0) return LTEA_OK;
+  const int esz = elem_size(cfg->dtype);
+  if (total_tokens > 0) {
+    if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (!out || !aligned16(out) || !lse || !logits) return LTEA_EINVAL;
+  }
+  const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
+  const size_t need = saved + score_workspace(*cfg, *cnn, total_tokens);
+  if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  ltea_cache cache;
+  carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, nullptr);
+  ltea_cfg open = *cfg;
+  open.budget = max_seqlen;           // every candidate is kept: no cap during training
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  if (total_tokens > 0) {
+    st = do_score(*cfg, *cnn, k, v, kv_stride_tok, kv_stride_head, sv, logits, static_cast<char*>(workspace) + saved, s);
+    if (st != LTEA_OK) return st;
+  }
+  st = hip_status(launch_retain(open, logits, k, v, kv_stride_tok, kv_stride_head, sv, cnn_rho(cnn), cache, s));
+  if (st != LTEA_OK || total_tokens == 0) return st;
+  return do_attention(open, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, cache, out, s, lse);
+}
+
+int ltea_train_backward(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head, const void* k,
+                        const void* v, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t* cu_seqlens,
+                        int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen, const void* out, const void* dout,
+                        const float* lse, const float* logits, const float* lambda, void* dq, void* dk, void* dv,
+                        float* dz, int32_t* counts, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st != LTEA_OK) return st;
+  if (n_seqs == 0) return LTEA_OK;
+  if (!lambda || !counts) return LTEA_EINVAL;
+  const int esz = elem_size(cfg->dtype);
+  if (total_tokens > 0) {
+    if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (!out || !dout || !lse || !logits || !dq || !dk || !dv || !dz) return LTEA_EINVAL;
+  }
+  const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
+  if (!workspace || workspace_bytes < saved) return LTEA_EWORKSPACE;
+  ltea_cache cache;
+  float* delta = nullptr;
+  carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, &delta);
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  return hip_status(launch_train_backward(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv,
+                                          out, dout, lse, logits, lambda, cache.ret_pos, cache.ret_count,
+                                          max_seqlen > 1 ? max_seqlen : 1, delta, dq, dk, dv, dz, counts,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int ltea_lambda_update(float* lambda, const float* c_bar, int32_t n, float cap, float alpha) {
+  if (!lambda || !c_bar || n < 0 || !(alpha > 0.f) || !(cap >= 0.f)) return LTEA_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    // in double so that the 1e-9 and 0.95 cap thresholds are the decimal ones
+    double l = lambda[i];
+    const double c = c_bar[i];
+    if (c > (double)cap) l *= (double)alpha;
+    else if (c < 0.95 * (double)cap) l /= (double)alpha;
+    if (l > 1.0) l = 1.0;
+    if (l < 1e-9) l = 0.0;
+    if (c > (double)cap && l == 0.0) l = 1e-9;
+    lambda[i] = (float)l;
+  }
+  return LTEA_OK;
 }
 
 }  // extern "C"

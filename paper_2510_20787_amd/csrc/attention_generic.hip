@@ -20,7 +20,7 @@ attention_generic_kernel(const T* __restrict__ q, int64_t q_st, int64_t q_sh, co
                          int n_seqs, int64_t total, int Hq, int Hkv, int window, int budget, float scale,
                          const T* __restrict__ k_ret, const T* __restrict__ v_ret,
                          const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count,
-                         T* __restrict__ out) {
+                         T* __restrict__ out, float* __restrict__ lse) {
   __shared__ float q_lds[kWavesPerBlock][D];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
@@ -90,19 +90,20 @@ attention_generic_kernel(const T* __restrict__ q, int64_t q_st, int64_t q_sh, co
   const float inv = 1.0f / l_run;
 #pragma unroll
   for (int e = 0; e < D / kWave; ++e) orow[lane + e * kWave] = from_f32<T>(acc[e] * inv);
+  if (lse != nullptr && lane == 0) lse[(int64_t)hq * total + tok] = m_run + logf(l_run);  // wanted by a backward pass
 }
 
 template <typename T, int D>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
                int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out, float scale,
-               hipStream_t stream) {
+               float* lse, hipStream_t stream) {
   const int64_t items = sv.total_tokens * cfg.Hq;
   dim3 grid((unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock));
   hipLaunchKernelGGL((attention_generic_kernel<T, D>), grid, dim3(kWavesPerBlock * kWave), 0, stream,
                      static_cast<const T*>(q), q_st, q_sh, static_cast<const T*>(k), static_cast<const T*>(v), kv_st,
                      kv_sh, sv.cu_seqlens, sv.n_seqs, sv.total_tokens, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale,
                      static_cast<const T*>(c.k_ret), static_cast<const T*>(c.v_ret), c.ret_pos, c.ret_count,
-                     static_cast<T*>(out));
+                     static_cast<T*>(out), lse);
   return hipGetLastError();
 }
 
@@ -110,15 +111,15 @@ hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, c
 
 hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                     const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv,
-                                    const ltea_cache& c, void* out, hipStream_t stream) {
+                                    const ltea_cache& c, void* out, hipStream_t stream, float* lse) {
   if (sv.total_tokens == 0) return hipSuccess;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   if (cfg.dtype == LTEA_F32) {
-    return cfg.D == 64 ? run<float, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, stream)
-                       : run<float, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, stream);
+    return cfg.D == 64 ? run<float, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream)
+                       : run<float, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream);
   }
-  return cfg.D == 64 ? run<bf16_t, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, stream)
-                     : run<bf16_t, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, stream);
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream)
+                     : run<bf16_t, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream);
 }
 
 }  // namespace ltea

@@ -104,7 +104,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
                       float scale_log2e, const bf16_t* __restrict__ k_ret, const bf16_t* __restrict__ v_ret,
                       const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count,
                       bf16_t* __restrict__ out, const int32_t* __restrict__ kv_start,
-                      const int32_t* __restrict__ kv_len) {
+                      const int32_t* __restrict__ kv_len, float* __restrict__ lse, int64_t lse_stride) {
   using G = Geo<D, QB>;
   using TR = TileRegs<D>;
   constexpr int BM = G::BM, KS = G::KS, VS = G::VS, kBuf = G::kBuf;
@@ -414,7 +414,13 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   __syncthreads();  // tile buffers are free
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
-    const float inv = 1.0f / pair_sum(l_part[qb]);
+    const float l_row = pair_sum(l_part[qb]);
+    const float inv = 1.0f / l_row;
+    if (lse != nullptr && hb == 0) {
+      // natural-log normaliser of the scaled scores (m_run is kept in the base-2 domain); wanted by a backward pass
+      const int row = 32 * QB * wv + 32 * qb + ql;
+      if (i0 + row < n) lse[(int64_t)hq * lse_stride + lo_q + i0 + row - q_begin] = (m_run[qb] + __log2f(l_row)) * 0.6931471805599453f;
+    }
     bf16_t* orow = lds + (32 * QB * wv + 32 * qb + ql) * G::OS + 4 * hb;
 #pragma unroll
     for (int db = 0; db < D / 32; ++db)
@@ -443,7 +449,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 template <int D, int QB>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
                int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out,
-               const int32_t* kv_start, const int32_t* kv_len, hipStream_t stream) {
+               const int32_t* kv_start, const int32_t* kv_len, float* lse, hipStream_t stream) {
   constexpr int BM = Geo<D, QB>::BM;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   const int64_t tiles_upper = (sv.total_tokens + BM - 1) / BM + sv.n_seqs;
@@ -454,7 +460,7 @@ hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, c
                      static_cast<const bf16_t*>(v), kv_st, kv_sh, sv.cu_seqlens, sv.n_seqs, (int)tiles_upper,
                      (int)n_work, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale * 1.4426950408889634f,
                      static_cast<const bf16_t*>(c.k_ret), static_cast<const bf16_t*>(c.v_ret), c.ret_pos, c.ret_count,
-                     static_cast<bf16_t*>(out), kv_start, kv_len);
+                     static_cast<bf16_t*>(out), kv_start, kv_len, lse, sv.total_tokens);
   return hipGetLastError();
 }
 
@@ -468,10 +474,11 @@ bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_
 
 hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c,
-                                 void* out, hipStream_t stream, const int32_t* kv_start, const int32_t* kv_len) {
+                                 void* out, hipStream_t stream, const int32_t* kv_start, const int32_t* kv_len,
+                                 float* lse) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, stream)
-                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, stream);
+  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream)
+                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream);
 }
 
 }  // namespace ltea

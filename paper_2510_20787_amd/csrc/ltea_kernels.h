@@ -52,7 +52,8 @@ hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k
 // ---- (c) prefill attention -------------------------------------------------------------------------
 hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                     const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
-                                    const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream);
+                                    const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream,
+                                    float* lse = nullptr);
 bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_t max_seqlen);
 // sv packs the query / output rows.  With kv_start / kv_len (device, per sequence) the keys of sequence s are rows
 // kv_start[s] .. +kv_len[s]-1 of k / v and its queries are the last positions of that key sequence; without
@@ -60,7 +61,9 @@ bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_
 hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                  const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
                                  const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream,
-                                 const int32_t* kv_start = nullptr, const int32_t* kv_len = nullptr);
+                                 const int32_t* kv_start = nullptr, const int32_t* kv_len = nullptr,
+                                 float* lse = nullptr);
+// lse (optional, both launchers): [Hq][total_tokens] fp32, natural log of each query's softmax normaliser.
 
 // ---- continuation of a prefill onto an existing cache ---------------------------------------------------
 // Device buffers of the "extended sequences" (pad | old kept entries by position | ring tokens | new tokens) that
@@ -97,6 +100,16 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
 hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const void* k, const void* v, void* out,
                                    const ltea_cache& cache, int n_seqs, int32_t* status, void* workspace,
                                    hipStream_t stream);
+
+// ---- training-side backward --------------------------------------------------------------------------------
+// ret_pos / ret_count: ascending kept out-of-window positions per (sequence, KV head) with row pitch kept_capacity
+// (what the retention launcher leaves when run with budget = kept_capacity and a cap that never binds).
+// delta: [Hq][total] fp32 scratch; dq/dk/dv contiguous [total][H][D] of cfg.dtype; dz [Hkv][total]; counts [n_seqs][Hkv].
+hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
+                                 const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const void* out,
+                                 const void* dout, const float* lse, const float* logits, const float* lambda,
+                                 const int32_t* ret_pos, const int32_t* ret_count, int kept_capacity, float* delta,
+                                 void* dq, void* dk, void* dv, float* dz, int32_t* counts, hipStream_t stream);
 
 // ---- deferred batched scoring of the decode cache ---------------------------------------------------------
 struct RescoreBuffers {

@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_2510_20787_amd import binding as B
@@ -209,3 +211,60 @@ def test_lazy_argument_errors():
     assert st(n=-1) == B.LTEA_EINVAL
     assert st(n=0) == B.LTEA_OK
     assert st(ws_bytes=16) == B.LTEA_EWORKSPACE
+
+
+def test_lambda_update_matches_the_oracle():
+    """Host-side entry point: runs without a GPU."""
+    from oracle import ltea_oracle as orc
+    rng = np.random.default_rng(5)
+    lam = np.concatenate([np.array([1e-9, 0.5, 0.9, 2e-9, 0.0, 0.0, 1e-3, 1.5e-9], np.float32),
+                          (10.0 ** rng.uniform(-10, 0.3, size=200)).astype(np.float32)])
+    cbar = np.concatenate([np.array([600, 600, 600, 100, 600, 100, 500, 10], np.float32),
+                           rng.uniform(300, 700, size=200).astype(np.float32)])
+    ref = orc.lambda_update(lam.astype(np.float64), cbar.astype(np.float64), 512.0, 2.0)
+    got = B.ltea_lambda_update(lam.copy(), cbar, 512.0, 2.0)
+    np.testing.assert_allclose(got, ref, rtol=1e-6, atol=0)
+    assert np.array_equal(got == 0, ref == 0)
+    assert (ref == 0).sum() > 3 and (ref == 1.0).sum() > 3 and (ref == 1e-9).sum() >= 1
+
+
+def test_train_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    need = L.ltea_train_workspace_bytes(C.byref(cfg), C.byref(cnn), 2, 64, 32)
+    assert need > 2 * 2 * cfg.Hkv * 32 * cfg.D * 2
+    assert L.ltea_train_workspace_bytes(None, C.byref(cnn), 2, 64, 32) == 0
+    fw = lambda **kw: L.ltea_train_forward(*[dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), q=0x1000, qst=256, qsh=64, k=0x1000,
+                                                       v=0x1000, st=128, sh=64, cu=0x1000, n=2, total=64, max_len=32,
+                                                       out=0x1000, lse=0x1000, logits=0x1000, ws=0x1000, ws_bytes=1 << 40,
+                                                       stream=None), **kw)[k]
+                                             for k in ("cfg", "cnn", "q", "qst", "qsh", "k", "v", "st", "sh", "cu", "n", "total",
+                                                       "max_len", "out", "lse", "logits", "ws", "ws_bytes", "stream")])
+    assert fw(cfg=None) == B.LTEA_EINVAL
+    assert fw(cnn=None) == B.LTEA_EINVAL
+    assert fw(cu=None) == B.LTEA_EINVAL
+    assert fw(lse=None) == B.LTEA_EINVAL
+    assert fw(logits=None) == B.LTEA_EINVAL
+    assert fw(ws=None) == B.LTEA_EWORKSPACE
+    assert fw(ws_bytes=need - 1) == B.LTEA_EWORKSPACE
+    assert fw(n=0, total=0, max_len=0) == B.LTEA_OK
+    bw = lambda **kw: L.ltea_train_backward(*[dict(dict(cfg=C.byref(cfg), q=0x1000, qst=256, qsh=64, k=0x1000, v=0x1000,
+                                                        st=128, sh=64, cu=0x1000, n=2, total=64, max_len=32, out=0x1000,
+                                                        dout=0x1000, lse=0x1000, logits=0x1000, lam=0x1000, dq=0x1000,
+                                                        dk=0x1000, dv=0x1000, dz=0x1000, counts=0x1000, ws=0x1000,
+                                                        ws_bytes=1 << 40, stream=None), **kw)[k]
+                                              for k in ("cfg", "q", "qst", "qsh", "k", "v", "st", "sh", "cu", "n", "total",
+                                                        "max_len", "out", "dout", "lse", "logits", "lam", "dq", "dk", "dv",
+                                                        "dz", "counts", "ws", "ws_bytes", "stream")])
+    assert bw(cfg=None) == B.LTEA_EINVAL
+    assert bw(dout=None) == B.LTEA_EINVAL
+    assert bw(lam=None) == B.LTEA_EINVAL
+    assert bw(counts=None) == B.LTEA_EINVAL
+    assert bw(dz=None) == B.LTEA_EINVAL
+    assert bw(ws_bytes=16) == B.LTEA_EWORKSPACE
+    assert bw(n=0, total=0, max_len=0) == B.LTEA_OK
+    lam = (C.c_float * 2)(0.5, 0.0)
+    cb = (C.c_float * 2)(600.0, 600.0)
+    assert L.ltea_lambda_update(lam, cb, 2, 512.0, 2.0) == B.LTEA_OK and lam[0] == 1.0 and abs(lam[1] - 1e-9) < 1e-15
+    assert L.ltea_lambda_update(None, cb, 2, 512.0, 2.0) == B.LTEA_EINVAL
+    assert L.ltea_lambda_update(lam, cb, 2, 512.0, 0.0) == B.LTEA_EINVAL

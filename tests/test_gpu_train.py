@@ -1,0 +1,96 @@
+"""GPU parity of the training-side forward / backward (Section 3.1.2; Algorithm 1) against the oracle: outputs and
+softmax normalisers of the uncapped masked attention, dQ / dK / dV, the straight-through gradient of the retention
+scores plus the sparsity penalty (as d logits), and the retention counts.
+
+Bars: counts bit-exact; fp32 gradients within 2e-5 and bf16 gradients within 2e-2 of the fp64 oracle, both relative
+to the largest reference magnitude of the tensor (bf16: O, dQ, dK, dV are rounded to bf16 and the backward reads the
+rounded O).  A logit within the scoring tolerance of the threshold may flip a token's visibility: seeds are chosen
+so that no logit sits there (checked)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import LOGIT_TOL, DeviceWorkload, dev, to_np
+from tests.helpers import oracle_cfg, oracle_cnn
+
+pytestmark = pytest.mark.gpu
+
+GRAD_TOL = {"f32": 2e-5, "bf16": 2e-2}
+
+CASES = {
+    # name: (dtype, seqlens, Hq, Hkv, D, window, sink, kernel, channels, dilation, w_std)
+    "f32_d64": ("f32", [150, 0, 67, 1], 4, 2, 64, 24, 1, (5,), (16,), None, 0.3),
+    "f32_d128_deep": ("f32", [130, 90], 2, 2, 128, 32, 2, (3, 3, 3), (32, 16, 8), (2, 2, 2), 0.12),
+    "bf16_d64_gqa": ("bf16", [300, 129, 40], 8, 2, 64, 48, 2, (5,), (32,), None, 0.2),
+    "bf16_d128": ("bf16", [260, 77], 2, 2, 128, 64, 0, (7,), (32,), None, 0.2),
+    "bf16_d64_deep": ("bf16", [280, 150], 4, 2, 64, 64, 4, (3, 3, 3), (64, 32, 16), (2, 2, 2), 0.12),
+}
+
+
+def max_err(got, ref):
+    return float(np.max(np.abs(got.astype(np.float64) - ref)))
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_train_forward_backward(name):
+    dt, lens, Hq, Hkv, D, window, sink, ker, ch, dil, w_std = CASES[name]
+    w = wl.make_prefill(name, sum(map(ord, name)), dt, lens, Hq, Hkv, D, window, 1, sink, 0.0, cnn_kernel=ker,
+                        cnn_channels=ch, cnn_dilation=dil, qkv_scale=1.0, w_std=w_std)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    rng = np.random.default_rng(w.seed + 99)
+    dout = wl.to_storage(rng.standard_normal((w.total_tokens, Hq, D), dtype=np.float32), dt)
+    lam = np.abs(rng.standard_normal(Hkv)).astype(np.float32) * np.float32(0.1)
+    z64 = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    frac = float((z64 > 0).mean())
+    assert 0.05 < frac < 0.95, f"both kept and dropped tokens are needed, kept fraction {frac}"
+    d = DeviceWorkload(w)
+    out, lse, logits, ws = B.ltea_train_forward(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen)
+    d_dout = dev(dout, dt)
+    dq, dk, dv, dz, counts = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, out, d_dout, lse, logits,
+                                                   torch.from_numpy(lam).cuda(), ws)
+    torch.cuda.synchronize()
+    zg = to_np(logits)
+    # the multi-layer bf16 kernel carries activations as bf16 hi + lo pairs: allow it a few 1e-5 at these weights
+    eps = float(np.max(np.abs(zg - z64)))
+    assert np.all(np.abs(zg - z64) <= 5 * LOGIT_TOL[dt] * np.maximum(1.0, np.abs(z64)))
+    assert np.min(np.abs(z64)) > 2 * eps, "a logit sits inside the scoring error of the threshold: pick another seed"
+    tol = GRAD_TOL[dt]
+    out_g, lse_g, dq_g, dk_g, dv_g, dz_g = (to_np(x) for x in (out, lse, dq, dk, dv, dz))
+    cnt_g = counts.cpu().numpy()
+    refs = {key: np.zeros(shape) for key, shape in (("out", out_g.shape), ("lse", lse_g.shape), ("dq", dq_g.shape),
+                                                     ("dk", dk_g.shape), ("dv", dv_g.shape), ("dz", dz_g.shape))}
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        if hi == lo:
+            assert np.all(cnt_g[s] == 0)
+            continue
+        refs["out"][lo:hi], refs["lse"][:, lo:hi], _ = orc.train_forward_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi],
+                                                                                 z64[:, lo:hi], cfg)
+        refs["dq"][lo:hi], refs["dk"][lo:hi], refs["dv"][lo:hi], refs["dz"][:, lo:hi], c_ref = orc.train_backward_sequence(
+            w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi], dout[lo:hi], cfg, lam.astype(np.float64))
+        np.testing.assert_array_equal(cnt_g[s], c_ref)
+    assert max_err(lse_g, refs["lse"]) <= (1e-4 if dt == "f32" else 2e-3)
+    for key, got in (("out", out_g), ("dq", dq_g), ("dk", dk_g), ("dv", dv_g), ("dz", dz_g)):
+        scale = float(np.max(np.abs(refs[key])))
+        err = max_err(got, refs[key])
+        assert scale > 0 and err <= tol * scale, (name, key, err, scale)
+    # same inputs, same bits
+    dq2, dk2, dv2, dz2, counts2 = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, out, d_dout, lse, logits,
+                                                        torch.from_numpy(lam).cuda(), ws)
+    for a, b in ((dq, dq2), (dk, dk2), (dv, dv2), (dz, dz2), (counts, counts2)):
+        assert torch.equal(a, b)
+
+
+def test_train_forward_equals_prefill_when_the_cap_does_not_bind():
+    """With budget >= n the inference prefill and the training forward are the same computation."""
+    dt, lens, Hq, Hkv, D, window, sink, ker, ch, dil, w_std = CASES["bf16_d64_gqa"]
+    w = wl.make_prefill("cap_free", 7, dt, lens, Hq, Hkv, D, window, max(lens), sink, 0.0, cnn_kernel=ker,
+                        cnn_channels=ch, cnn_dilation=dil, qkv_scale=1.0, w_std=w_std)
+    d = DeviceWorkload(w)
+    out_t, lse, logits, ws = B.ltea_train_forward(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen)
+    cache = d.new_cache()
+    out_p = B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache)
+    assert torch.equal(out_t, out_p)
