@@ -258,6 +258,62 @@ def bench_decode(args):
                               traffic=measured_traffic("decode_bf16", "decode_main_kernel")))
 
 
+def bench_train(args):
+    """Training-side forward + backward on the paper's module shape (no cap): ltea_train_forward, then
+    ltea_train_backward for a random d(out).  Pairs = (query, visible key) pairs counted from the logits."""
+    import torch
+    from paper_2510_20787_amd import binding as B
+    from paper_2510_20787_amd import workloads as wl
+
+    w = wl.config_paper_stack_bf16()
+    cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
+    c = w.cnn
+    cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
+    cu = torch.from_numpy(w.cu_seqlens).cuda()
+    q, k, v = up(w.q, w.dtype), up(w.k, w.dtype), up(w.v, w.dtype)
+    rng = np.random.default_rng(w.seed + 99)
+    dout = up(wl.to_storage(rng.standard_normal(w.q.shape, dtype=np.float32), w.dtype), w.dtype)
+    lam = torch.full((w.Hkv,), 1e-3, dtype=torch.float32, device="cuda")
+    ws = torch.empty(B.ltea_train_workspace_bytes(cfg, cnn, w.n_seqs, w.total_tokens, w.max_seqlen), dtype=torch.uint8,
+                     device="cuda")
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    fwd_ms = bwd_ms = 0.0
+    reps = 3
+    for it in range(reps + 1):
+        ev[0].record()
+        out, lse, logits, _ = B.ltea_train_forward(cfg, cnn, q, k, v, cu, w.max_seqlen, workspace=ws)
+        ev[1].record()
+        grads = B.ltea_train_backward(cfg, q, k, v, cu, w.max_seqlen, out, dout, lse, logits, lam, ws)
+        ev[2].record()
+        torch.cuda.synchronize()
+        if it > 0:
+            fwd_ms += ev[0].elapsed_time(ev[1]) / reps
+            bwd_ms += ev[1].elapsed_time(ev[2]) / reps
+    z = logits.cpu().numpy()
+    G = w.Hq // w.Hkv
+    pairs = 0
+    for s_ in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s_]), int(w.cu_seqlens[s_ + 1])
+        n = hi - lo
+        i = np.arange(n)
+        n_win = np.minimum(i + 1, w.window)
+        for h in range(w.Hkv):
+            keep = z[h, lo:hi] > w.tau
+            keep[:w.sink] = True
+            left = np.concatenate([[0], np.cumsum(keep)])          # kept positions below an index
+            n_far = left[np.maximum(i - w.window + 1, 0)]
+            pairs += int((n_win + n_far).sum()) * G
+    kept_frac = float(grads[4].sum().item()) / (w.total_tokens * w.Hkv)
+    flops_bwd = 10.0 * w.D * pairs                                # S, dP, dV, dK, dQ: 2 D flop each per pair
+    tf = flops_bwd / (bwd_ms * 1e-3) / 1e12
+    return dict(workload="paper_stack_bf16 without the cap (training): B=4 x n=4096, Hq=32 on Hkv=8, D=64, window=768, "
+                         f"kept fraction {kept_frac:.2f}", forward_ms=fwd_ms, backward_ms=bwd_ms,
+                tokens_per_s=w.total_tokens / ((fwd_ms + bwd_ms) * 1e-3), pairs=pairs,
+                roofline=dict(bound="alu", kernel="train_dq_kernel + train_dkv_kernel", achieved=tf, peak=157.3,
+                              unit="TFLOP/s", frac=tf / 157.3, traffic=None,
+                              note="algorithmic flops = 10 D per (query, key) pair; fp32 vector peak"))
+
+
 def bench_chunked(args):
     """The prefill workload fed in `--chunks` equal pieces per sequence: ltea_prefill for the first piece,
     ltea_prefill_append for the others (same final state and last-piece rows as the one-shot call)."""
@@ -370,6 +426,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--train", action="store_true", help="also time the training-side forward + backward")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -422,6 +479,9 @@ def main():
             f"{dec['lazy']['rescore_us']:.0f} us per {dec['lazy']['period']} steps")
         add_measured_fraction(dec.get("roofline"), ceilings)
         line["decode"] = dec
+    if args.train:
+        line["train"] = bench_train(args)
+        log(f"[bench] train forward {line['train']['forward_ms']:.3f} ms, backward {line['train']['backward_ms']:.3f} ms")
     if args.chunks > 1:
         line["chunked_prefill"] = bench_chunked(args)
         log(f"[bench] chunked prefill: {line['chunked_prefill']['ms_per_pass']:.3f} ms per pass")

@@ -454,8 +454,7 @@ int ltea_train_backward(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok
   carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, &delta);
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
   return hip_status(launch_train_backward(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv,
-                                          out, dout, lse, logits, lambda, cache.ret_pos, cache.ret_count,
-                                          max_seqlen > 1 ? max_seqlen : 1, delta, dq, dk, dv, dz, counts,
+                                          out, dout, lse, logits, lambda, cache, max_seqlen > 1 ? max_seqlen : 1, delta, dq, dk, dv, dz, counts,
                                           static_cast<hipStream_t>(stream)));
 }
 

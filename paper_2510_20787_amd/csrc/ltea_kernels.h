@@ -102,14 +102,14 @@ hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const voi
                                    hipStream_t stream);
 
 // ---- training-side backward --------------------------------------------------------------------------------
-// ret_pos / ret_count: ascending kept out-of-window positions per (sequence, KV head) with row pitch kept_capacity
-// (what the retention launcher leaves when run with budget = kept_capacity and a cap that never binds).
+// kept: the compact arrays the retention launcher leaves when run with budget = kept_capacity and a cap that never
+// binds (ascending kept out-of-window positions per (sequence, KV head) and their K / V rows).
 // delta: [Hq][total] fp32 scratch; dq/dk/dv contiguous [total][H][D] of cfg.dtype; dz [Hkv][total]; counts [n_seqs][Hkv].
 hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const void* out,
                                  const void* dout, const float* lse, const float* logits, const float* lambda,
-                                 const int32_t* ret_pos, const int32_t* ret_count, int kept_capacity, float* delta,
-                                 void* dq, void* dk, void* dv, float* dz, int32_t* counts, hipStream_t stream);
+                                 const ltea_cache& kept, int kept_capacity, float* delta, void* dq, void* dk, void* dv,
+                                 float* dz, int32_t* counts, hipStream_t stream);
 
 // ---- deferred batched scoring of the decode cache ---------------------------------------------------------
 struct RescoreBuffers {

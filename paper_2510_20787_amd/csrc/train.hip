@@ -16,29 +16,17 @@
 // Both kernels give one lane one key (or one query) for the two dot products, then broadcast the lane results
 // and let the lanes own the feature dimension for the rank-1 updates: fp32 VALU arithmetic, every row read as
 // whole 128/256-byte rows.  Results do not depend on launch order (no floating-point atomics).
+#include <type_traits>
+
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "train_common.h"
 
 namespace ltea {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
 
-struct TrainArgs {
-  const void *q, *k, *v, *out, *dout;
-  int64_t q_st, q_sh, kv_st, kv_sh;
-  const int32_t* cu;
-  int n_seqs;
-  int64_t total;
-  int Hq, Hkv, window, budget, sink;
-  float scale, tau;
-  const int32_t *ret_pos, *ret_count;
-  const float *lse, *logits, *lambda;
-  float* delta;
-  void *dq, *dk, *dv;
-  float* dz;
-  int32_t* counts;
-};
 
 template <typename T, int D>
 __global__ void __launch_bounds__(kWavesPerBlock * kWave)
@@ -211,6 +199,25 @@ __global__ void __launch_bounds__(256) train_zero_counts_kernel(int32_t* counts,
   if (i < n) counts[i] = 0;
 }
 
+// delta = <dO, O> per (query, query head): one wave per row (the matrix-core path reads it from memory; the
+// generic dQ kernel computes it on its own).
+template <typename T, int D>
+__global__ void __launch_bounds__(kWavesPerBlock * kWave)
+train_delta_kernel(TrainArgs A) {
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+  if (item >= A.total * A.Hq) return;
+  const int64_t tok = item / A.Hq;
+  const int hq = (int)(item - tok * A.Hq);
+  const T* orow = static_cast<const T*>(A.out) + item * D;
+  const T* dorow = static_cast<const T*>(A.dout) + item * D;
+  float dsum = 0.f;
+#pragma unroll
+  for (int e = 0; e < D / kWave; ++e) dsum = fmaf(to_f32(dorow[lane + e * kWave]), to_f32(orow[lane + e * kWave]), dsum);
+  dsum = wave_sum(dsum);
+  if (lane == 0) A.delta[(int64_t)hq * A.total + tok] = dsum;
+}
+
 template <typename T, int D>
 hipError_t run(const TrainArgs& A, hipStream_t stream) {
   const int n_counts = A.n_seqs * A.Hkv;
@@ -220,12 +227,25 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
   if (e != hipSuccess) return e;
   if (A.total == 0) return hipSuccess;
   const int64_t qi = A.total * A.Hq, ki = A.total * A.Hkv;
-  hipLaunchKernelGGL((train_dq_kernel<T, D>), dim3((unsigned)((qi + kWavesPerBlock - 1) / kWavesPerBlock)),
-                     dim3(kWavesPerBlock * kWave), 0, stream, A);
+  const dim3 qgrid((unsigned)((qi + kWavesPerBlock - 1) / kWavesPerBlock)), block(kWavesPerBlock * kWave);
+  if constexpr (std::is_same<T, bf16_t>::value && D == 64) {
+    if (train_mfma_supported(A)) {
+      // matrix-core path: delta first, then dQ per query tile and dK / dV per key tile
+      hipLaunchKernelGGL((train_delta_kernel<T, D>), qgrid, block, 0, stream, A);
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      e = launch_train_dq_mfma(A, stream);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL((train_dkv_kernel<T, D>), dim3((unsigned)((ki + kWavesPerBlock - 1) / kWavesPerBlock)), block, 0,
+                         stream, A);
+      return hipGetLastError();
+    }
+  }
+  hipLaunchKernelGGL((train_dq_kernel<T, D>), qgrid, block, 0, stream, A);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((train_dkv_kernel<T, D>), dim3((unsigned)((ki + kWavesPerBlock - 1) / kWavesPerBlock)),
-                     dim3(kWavesPerBlock * kWave), 0, stream, A);
+  hipLaunchKernelGGL((train_dkv_kernel<T, D>), dim3((unsigned)((ki + kWavesPerBlock - 1) / kWavesPerBlock)), block, 0,
+                     stream, A);
   return hipGetLastError();
 }
 
@@ -234,8 +254,8 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
 hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const void* out,
                                  const void* dout, const float* lse, const float* logits, const float* lambda,
-                                 const int32_t* ret_pos, const int32_t* ret_count, int kept_capacity, float* delta,
-                                 void* dq, void* dk, void* dv, float* dz, int32_t* counts, hipStream_t stream) {
+                                 const ltea_cache& kept, int kept_capacity, float* delta, void* dq, void* dk, void* dv,
+                                 float* dz, int32_t* counts, hipStream_t stream) {
   if (sv.n_seqs == 0) return hipSuccess;
   TrainArgs A;
   A.q = q; A.k = k; A.v = v; A.out = out; A.dout = dout;
@@ -244,7 +264,8 @@ hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_s
   A.Hq = cfg.Hq; A.Hkv = cfg.Hkv; A.window = cfg.window; A.budget = kept_capacity; A.sink = cfg.sink;
   A.scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   A.tau = cfg.tau_logit;
-  A.ret_pos = ret_pos; A.ret_count = ret_count;
+  A.ret_pos = kept.ret_pos; A.ret_count = kept.ret_count; A.k_ret = kept.k_ret; A.v_ret = kept.v_ret;
+  A.max_seqlen = sv.max_seqlen;
   A.lse = lse; A.logits = logits; A.lambda = lambda; A.delta = delta;
   A.dq = dq; A.dk = dk; A.dv = dv; A.dz = dz; A.counts = counts;
   if (cfg.dtype == LTEA_F32) return cfg.D == 64 ? run<float, 64>(A, stream) : run<float, 128>(A, stream);

@@ -1,0 +1,30 @@
+// Arguments shared by the training-side backward kernels (generic and matrix-core paths).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ltea {
+
+struct TrainArgs {
+  const void *q, *k, *v, *out, *dout;
+  int64_t q_st, q_sh, kv_st, kv_sh;
+  const int32_t* cu;
+  int n_seqs;
+  int64_t total;
+  int Hq, Hkv, window, budget, sink;
+  float scale, tau;
+  const int32_t *ret_pos, *ret_count;   // compacted candidates of the forward: ascending positions, row pitch `budget`
+  const void *k_ret, *v_ret;            // their K / V rows, [n_seqs][Hkv][budget][D]
+  int max_seqlen;
+  const float *lse, *logits, *lambda;
+  float* delta;
+  void *dq, *dk, *dv;
+  float* dz;
+  int32_t* counts;
+};
+
+// bf16, D = 64 path on MFMA (train_mfma.hip).
+bool train_mfma_supported(const TrainArgs& A);
+hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream);
+
+}  // namespace ltea

@@ -1,0 +1,310 @@
+// Training-side backward of the SWA+LTE attention on bf16 MFMA for gfx950, head dimension 64 (paper Section 3.1.2:
+// the gradients that reach Q, K, V and, through the straight-through estimator, the retention scores).
+//
+// train_dq_mfma_kernel: one workgroup = 128 consecutive queries of one (sequence, query head), 4 waves x 32 queries,
+// walking the same key tiles as the forward kernel (64-key tiles of K/V inside the window range, then 64-slot tiles
+// of the compacted candidates with the per-row mask "position <= i - window").  Per 32-key block and wave
+// (v_mfma_f32_32x32x16_bf16, a lane owns one query column):
+//   S^T[key, query]  = K . Q^T        A = K tile rows from LDS, B = Q fragment in registers
+//   dP^T[key, query] = V . dO^T       A = V tile rows from LDS, B = dO fragment in registers
+//   P^T = exp2(S^T c - lse), dS^T = P^T (dP^T - delta)      per-lane scalars lse, delta (no running maximum)
+//   dQ^T[d, query]  += K^T . dS^T     A = K^T through the transposing LDS load, B = dS^T straight from registers
+// K is therefore staged twice per tile (padded rows for the row reads, swizzled unpadded rows for the transposing
+// reads), V once.  One tile buffer, next tile prefetched through registers, two barriers per tile.
+#include "ltea_common.h"
+#include "ltea_kernels.h"
+#include "train_common.h"
+
+namespace ltea {
+namespace {
+
+constexpr int D = 64;
+constexpr int BN = 64;          // keys per tile
+constexpr int BM = 128;         // queries per workgroup
+constexpr int kThreads = 256;
+constexpr int KS = D + 8;       // padded row stride (elements) of tiles read row-wise
+constexpr int VS = D;           // unpadded, chunk-swizzled row stride of tiles read through the transposing load
+constexpr int PPR = D / 8;      // 16-byte pieces per row
+constexpr int RPP = kThreads / PPR;
+constexpr int KPASS = BN / RPP;
+constexpr int OS = D + 8;       // epilogue staging stride
+
+// Row of a tile (within a block of 32) that MFMA row m must carry so that accumulator register r of lane half hb
+// holds row 16*(r/8) + 8*hb + r%8: swap bits 2 and 3 of m.
+__device__ __forceinline__ int tile_row_of_mfma_row(int m) { return (m & 0x13) | ((m & 0x08) >> 1) | ((m & 0x04) << 1); }
+// 64-byte chunk swizzle of the unpadded tiles (rows are 128 bytes: two chunks, alternating every second row).
+__device__ __forceinline__ int chunk_swizzle(int row) { return (row >> 1) & 1; }
+
+// A operand "transposed tile": eight consecutive tile rows of one column per lane, two transposing 64-bit LDS loads.
+__device__ __forceinline__ bf16x8 load_transposed(const bf16_t* p, int row_stride) {
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x8 __attribute__((ext_vector_type(8)));
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
+  s16x8 r;
+  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+__device__ __forceinline__ int wave_min_i(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y < x ? y : x; }
+  return x;
+}
+__device__ __forceinline__ int wave_max_i(int x) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y > x ? y : x; }
+  return x;
+}
+
+struct TileRegs {
+  u32x4 a[KPASS], b[KPASS];
+  int pos;
+};
+
+__global__ void __launch_bounds__(kThreads, 2)
+train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e) {
+  constexpr int kK = 0, kKt = BN * KS, kV = BN * KS + BN * VS, kBuf = 2 * BN * KS + BN * VS;
+  static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
+  __shared__ __align__(16) bf16_t lds[kBuf];
+  __shared__ int pos_lds[BN];
+  __shared__ int pos_rng[2];
+
+  const int per_xcd = (n_work + 7) / 8;
+  const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  if (work >= n_work) return;
+  const int hq = work / tiles_upper;
+  int tile, s, n, lo;
+  if (!locate_tile(A.cu, A.n_seqs, BM, work - hq * tiles_upper, s, tile, lo, n)) return;
+  const int Hq = A.Hq, Hkv = A.Hkv, window = A.window, budget = A.budget;
+  const int h = hq / (Hq / Hkv);
+  const int64_t head = (int64_t)s * Hkv + h;
+  const int i0 = tile * BM;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ql = lane & 31, hb = lane >> 5;
+  const int r0 = i0 + 32 * wv;
+  const int r_hi = r0 + 31;
+
+  const bf16_t* q = static_cast<const bf16_t*>(A.q);
+  const bf16_t* k = static_cast<const bf16_t*>(A.k);
+  const bf16_t* v = static_cast<const bf16_t*>(A.v);
+  const bf16_t* dout = static_cast<const bf16_t*>(A.dout);
+
+  // ---- per-lane query state: Q and dO fragments (B operands), lse (base-2 domain), delta ---------------------
+  const int qi = r0 + ql;
+  const int qc = qi < n ? qi : n - 1;
+  bf16x8 qreg[D / 16], doreg[D / 16];
+  {
+    const bf16_t* qrow = q + (int64_t)(lo + qc) * A.q_st + (int64_t)hq * A.q_sh;
+    const bf16_t* dorow = dout + ((int64_t)(lo + qc) * Hq + hq) * D;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      qreg[ks] = *reinterpret_cast<const bf16x8*>(qrow + 16 * ks + 8 * hb);
+      doreg[ks] = *reinterpret_cast<const bf16x8*>(dorow + 16 * ks + 8 * hb);
+    }
+  }
+  const float lse2 = A.lse[(int64_t)hq * A.total + lo + qc] * 1.4426950408889634f;
+  const float dlt = A.delta[(int64_t)hq * A.total + lo + qc];
+
+  // ---- tile schedule (as in the forward) ------------------------------------------------------------------
+  const int i_last = (i0 + BM < n ? i0 + BM : n) - 1;
+  const int jlo = i0 - window + 1 > 0 ? i0 - window + 1 : 0;
+  const int jt0 = (jlo / BN) * BN;
+  const int n_win_tiles = (i_last - jt0) / BN + 1;
+  const int cnt = (budget > 0 && i_last - window >= 0) ? A.ret_count[head] : 0;
+  const int n_ret_tiles = (cnt + BN - 1) / BN;
+  const int n_tiles = n_win_tiles + n_ret_tiles;
+
+  const uint32_t row_bytes = (uint32_t)A.kv_st * 2u;
+  const uint32_t win_bytes = (uint32_t)(n - 1) * row_bytes + (uint32_t)(D * 2);
+  const uint32_t ret_bytes = (uint32_t)cnt * (uint32_t)(D * 2);
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k + (int64_t)lo * A.kv_st + (int64_t)h * A.kv_sh), 0, win_bytes, 0x00020000);
+  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v + (int64_t)lo * A.kv_st + (int64_t)h * A.kv_sh), 0, win_bytes, 0x00020000);
+  const auto rs_kr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(static_cast<const bf16_t*>(A.k_ret) + head * budget * D), 0, ret_bytes, 0x00020000);
+  const auto rs_vr = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(static_cast<const bf16_t*>(A.v_ret) + head * budget * D), 0, ret_bytes, 0x00020000);
+  const int32_t* prbase = A.ret_pos + head * budget;
+  const int k_piece = tid % PPR, k_row = tid / PPR;
+  const uint32_t k_col = (uint32_t)k_piece * 16u;
+  const uint32_t k_loc = (uint32_t)k_row * row_bytes + k_col;
+  const uint32_t kr_loc = (uint32_t)k_row * (uint32_t)(D * 2) + k_col;
+
+  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t b0, uint32_t rb, TileRegs& R) {
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+      R.a[p] = __builtin_amdgcn_raw_buffer_load_b128(rk, b0 + (uint32_t)(p * RPP) * rb, 0, 0);
+      R.b[p] = __builtin_amdgcn_raw_buffer_load_b128(rv, b0 + (uint32_t)(p * RPP) * rb, 0, 0);
+    }
+  };
+  auto load_tile = [&](int t, TileRegs& R) {
+    if (t < n_win_tiles) {
+      load_rows(rs_k, rs_v, (uint32_t)(jt0 + t * BN) * row_bytes + k_loc, row_bytes, R);
+    } else {
+      const int base = (t - n_win_tiles) * BN;
+      load_rows(rs_kr, rs_vr, (uint32_t)base * (uint32_t)(D * 2) + kr_loc, (uint32_t)(D * 2), R);
+      R.pos = 0x7FFFFFFF;
+      if (tid < BN && base + tid < cnt) R.pos = prbase[base + tid];
+    }
+  };
+  static_assert(RPP % 4 == 0, "row passes must preserve the swizzle phase");
+  const int p_st_off = k_row * KS + k_piece * 8;
+  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle(k_row)) << 5) + (k_piece & 3) * 8;
+  auto store_tile = [&](int t, const TileRegs& R) {
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+      *reinterpret_cast<u32x4*>(lds + kK + p_st_off + p * RPP * KS) = R.a[p];
+      *reinterpret_cast<u32x4*>(lds + kKt + t_st_off + p * RPP * VS) = R.a[p];
+      *reinterpret_cast<u32x4*>(lds + kV + p_st_off + p * RPP * KS) = R.b[p];
+    }
+    if (t >= n_win_tiles && wv == 0) {
+      pos_lds[lane] = R.pos;
+      const int mn = wave_min_i(R.pos);
+      const int mx = wave_max_i(R.pos == 0x7FFFFFFF ? (int)0x80000000 : R.pos);
+      if (lane == 0) { pos_rng[0] = mn; pos_rng[1] = mx; }
+    }
+  };
+
+  const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*kb*KS + 16*ks
+  const int tr_key = 8 * hb + ((lane & 15) >> 2);
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int tr_swz = chunk_swizzle(tr_key);
+  const int a_tr_off = kKt + tr_key * VS + tr_col;
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[db][r] = 0.f;
+
+  // mode: 0 = every pair valid, 1 = window-edge mask, 2 = mask by the candidates' positions
+  auto compute = [&](const int mode, int jt) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(lds + kK + a_row_off + 32 * kb * KS + 16 * ks);
+        const bf16x8 av = *reinterpret_cast<const bf16x8*>(lds + kV + a_row_off + 32 * kb * KS + 16 * ks);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[ks], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, doreg[ks], dp, 0, 0, 0);
+      }
+      // register r is local key 32*kb + 16*(r/8) + 8*hb + r%8
+      if (mode == 1) {
+        const int shift = jt + 8 * hb;
+        int c_hi = qi - shift;
+        const int c_end = n - 1 - shift;
+        c_hi = c_hi < c_end ? c_hi : c_end;
+        int c_lo = qi - window + 1 - shift;
+        const unsigned span = c_hi >= c_lo ? (unsigned)(c_hi - c_lo) : 0u;
+        if (c_hi < c_lo) c_lo = 0x40000000;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int c = 32 * kb + 16 * (r / 8) + (r % 8);
+          sc[r] = ((unsigned)(c - c_lo) <= span) ? sc[r] : -INFINITY;
+        }
+      } else if (mode == 2) {
+        const int lim = qi - window;
+#pragma unroll
+        for (int r8 = 0; r8 < 2; ++r8) {
+          const int* pp = pos_lds + 32 * kb + 16 * r8 + 8 * hb;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) sc[8 * r8 + e] = (pp[e] <= lim) ? sc[8 * r8 + e] : -INFINITY;
+        }
+      }
+      bf16x8 pb[2];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(sc[r], scale_log2e, -lse2));   // exp2(-inf) = 0 for masked pairs
+        pb[r / 8][r % 8] = static_cast<bf16_t>(p * (dp[r] - dlt));
+      }
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const bf16_t* ap = lds + a_tr_off + 32 * kb * VS + ((db ^ tr_swz) << 5);
+        const bf16x8 a0 = load_transposed(ap, VS);
+        const bf16x8 a1 = load_transposed(ap + 16 * VS, VS);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[0], acc[db], 0, 0, 0);
+        acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pb[1], acc[db], 0, 0, 0);
+      }
+    }
+  };
+
+  TileRegs regs;
+  load_tile(0, regs);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();                 // everyone is done reading the previous tile
+    store_tile(t, regs);
+    __syncthreads();                 // tile t is in LDS
+    if (t + 1 < n_tiles) load_tile(t + 1, regs);
+    int mode = -1, jt = 0;
+    if (r0 < n) {
+      if (t < n_win_tiles) {
+        jt = jt0 + t * BN;
+        if (!(jt > r_hi || jt + BN - 1 < r0 - window + 1))
+          mode = ((jt + BN - 1 <= r0) && (jt >= r_hi - window + 1)) ? 0 : 1;
+      } else {
+        const int pmin = pos_rng[0], pmax = pos_rng[1];
+        if (pmin <= r_hi - window) {
+          const bool full = (t - n_win_tiles + 1) * BN <= cnt;
+          mode = (full && pmax <= r0 - window) ? 0 : 2;
+        }
+      }
+    }
+    mode = __builtin_amdgcn_readfirstlane(mode);
+    if (mode == 0) compute(0, jt);
+    else if (mode == 1) compute(1, jt);
+    else if (mode == 2) compute(2, jt);
+  }
+
+  // ---- epilogue: dQ = scale * acc, staged through LDS, rows stored coalesced ---------------------------------
+  __syncthreads();
+  {
+    bf16_t* orow = lds + (32 * wv + ql) * OS + 4 * hb;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 w4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w4[e] = static_cast<bf16_t>(acc[db][4 * g4 + e] * A.scale);
+        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g4) = w4;
+      }
+  }
+  __syncthreads();
+  {
+    bf16_t* obase = static_cast<bf16_t*>(A.dq) + ((int64_t)(lo + i0) * Hq + hq) * D;
+    const int64_t orow_stride = (int64_t)Hq * D;
+#pragma unroll
+    for (int p = 0; p < BM / RPP; ++p) {
+      const int row = p * RPP + k_row;
+      if (i0 + row < n)
+        *reinterpret_cast<u32x4*>(obase + row * orow_stride + k_piece * 8) =
+            *reinterpret_cast<const u32x4*>(lds + row * OS + k_piece * 8);
+    }
+  }
+}
+
+}  // namespace
+
+// Rows are addressed with 32-bit byte offsets inside one sequence, and loaded in 16-byte pieces.
+bool train_mfma_supported(const TrainArgs& A) {
+  if ((int64_t)A.max_seqlen * A.kv_st * 2 >= ((int64_t)1 << 31)) return false;
+  if ((int64_t)A.budget * D * 2 >= ((int64_t)1 << 31)) return false;
+  auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
+  return al16(A.dout) && al16(A.dq) && al16(A.dk) && al16(A.dv) && al16(A.out);
+}
+
+hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream) {
+  const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
+  const int64_t n_work = tiles_upper * A.Hq;
+  const int64_t grid = (n_work + 7) / 8 * 8;
+  hipLaunchKernelGGL(train_dq_mfma_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, A, (int)tiles_upper,
+                     (int)n_work, A.scale * 1.4426950408889634f);
+  return hipGetLastError();
+}
+
+}  // namespace ltea
