@@ -95,7 +95,7 @@ int do_attention(const ltea_cfg& cfg, const void* q, int64_t qst, int64_t qsh, c
 // Saved state of a training forward, carved from the caller's workspace: an uncapped cache (compact arrays with
 // max_seqlen rows per head), the delta scratch of the backward, then the scoring kernels' own workspace.
 size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqlen, void* base, ltea_cache* c,
-                   float** delta) {
+                   float** delta, float** far_dk = nullptr, float** far_dv = nullptr) {
   const size_t esz = (size_t)elem_size(cfg.dtype);
   const size_t heads = (size_t)n_seqs * cfg.Hkv;
   const size_t cap = (size_t)(max_seqlen > 1 ? max_seqlen : 1);
@@ -112,6 +112,10 @@ size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqle
   int32_t* n_seen = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
   int32_t* n_scored = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
   float* d = reinterpret_cast<float*>(take((size_t)cfg.Hq * (size_t)total * 4));
+  float* fk = reinterpret_cast<float*>(take(heads * cap * cfg.D * 4));
+  float* fv = reinterpret_cast<float*>(take(heads * cap * cfg.D * 4));
+  if (far_dk) *far_dk = fk;
+  if (far_dv) *far_dv = fv;
   if (c) *c = ltea_cache{k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored};
   if (delta) *delta = d;
   return (size_t)(p - static_cast<char*>(base));
@@ -450,11 +454,12 @@ int ltea_train_backward(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok
   const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
   if (!workspace || workspace_bytes < saved) return LTEA_EWORKSPACE;
   ltea_cache cache;
-  float* delta = nullptr;
-  carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, &delta);
+  float *delta = nullptr, *far_dk = nullptr, *far_dv = nullptr;
+  carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, &delta, &far_dk, &far_dv);
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
   return hip_status(launch_train_backward(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv,
-                                          out, dout, lse, logits, lambda, cache, max_seqlen > 1 ? max_seqlen : 1, delta, dq, dk, dv, dz, counts,
+                                          out, dout, lse, logits, lambda, cache, max_seqlen > 1 ? max_seqlen : 1, delta, far_dk, far_dv, dq, dk, dv, dz,
+                                          counts,
                                           static_cast<hipStream_t>(stream)));
 }
 

@@ -236,9 +236,7 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
       if (e != hipSuccess) return e;
       e = launch_train_dq_mfma(A, stream);
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL((train_dkv_kernel<T, D>), dim3((unsigned)((ki + kWavesPerBlock - 1) / kWavesPerBlock)), block, 0,
-                         stream, A);
-      return hipGetLastError();
+      return launch_train_dkv_mfma(A, A.far_dk, A.far_dv, stream);
     }
   }
   hipLaunchKernelGGL((train_dq_kernel<T, D>), qgrid, block, 0, stream, A);
@@ -254,8 +252,8 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
 hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                  const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv, const void* out,
                                  const void* dout, const float* lse, const float* logits, const float* lambda,
-                                 const ltea_cache& kept, int kept_capacity, float* delta, void* dq, void* dk, void* dv,
-                                 float* dz, int32_t* counts, hipStream_t stream) {
+                                 const ltea_cache& kept, int kept_capacity, float* delta, float* far_dk, float* far_dv,
+                                 void* dq, void* dk, void* dv, float* dz, int32_t* counts, hipStream_t stream) {
   if (sv.n_seqs == 0) return hipSuccess;
   TrainArgs A;
   A.q = q; A.k = k; A.v = v; A.out = out; A.dout = dout;
@@ -266,7 +264,7 @@ hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_s
   A.tau = cfg.tau_logit;
   A.ret_pos = kept.ret_pos; A.ret_count = kept.ret_count; A.k_ret = kept.k_ret; A.v_ret = kept.v_ret;
   A.max_seqlen = sv.max_seqlen;
-  A.lse = lse; A.logits = logits; A.lambda = lambda; A.delta = delta;
+  A.lse = lse; A.logits = logits; A.lambda = lambda; A.delta = delta; A.far_dk = far_dk; A.far_dv = far_dv;
   A.dq = dq; A.dk = dk; A.dv = dv; A.dz = dz; A.counts = counts;
   if (cfg.dtype == LTEA_F32) return cfg.D == 64 ? run<float, 64>(A, stream) : run<float, 128>(A, stream);
   return cfg.D == 64 ? run<bf16_t, 64>(A, stream) : run<bf16_t, 128>(A, stream);

@@ -18,6 +18,7 @@ struct TrainArgs {
   int max_seqlen;
   const float *lse, *logits, *lambda;
   float* delta;
+  float *far_dk, *far_dv;               // fp32 scratch of the matrix-core dK / dV path, laid out like k_ret / v_ret
   void *dq, *dk, *dv;
   float* dz;
   int32_t* counts;
@@ -26,5 +27,6 @@ struct TrainArgs {
 // bf16, D = 64 path on MFMA (train_mfma.hip).
 bool train_mfma_supported(const TrainArgs& A);
 hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream);
+hipError_t launch_train_dkv_mfma(const TrainArgs& A, float* far_dk, float* far_dv, hipStream_t stream);
 
 }  // namespace ltea

@@ -288,6 +288,304 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
   }
 }
 
+
+// Both lane halves (l, l^32) receive the sum of the pair.
+__device__ __forceinline__ float pair_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+struct QTileRegs {
+  u32x4 a[KPASS], b[KPASS];
+  float stat;     // threads 0..63: lse (base-2 domain) of a query of the tile, threads 64..127: its delta
+};
+
+// train_dkv_mfma_kernel<FAR>: one workgroup = 128 keys of one (sequence, KV head), 4 waves x 32 keys; a lane owns one
+// key column.  It walks 64-query tiles of every query head of the group that can see its keys:
+//   S[query, key]  = Q . K^T          A = Q tile rows from LDS, B = K fragment in registers
+//   dP[query, key] = dO . V^T         A = dO tile rows from LDS, B = V fragment in registers
+//   P = exp2(S c - lse[query]), dS = P (dP - delta[query])      lse, delta per row, read from LDS
+//   dV^T[d, key] += dO^T . P          A = dO^T through the transposing LDS load, B = P from registers
+//   dK^T[d, key] += Q^T . dS          A = Q^T through the transposing LDS load, B = dS from registers
+// FAR = false ("band"): the keys are 128 consecutive positions, seen by the queries j .. j+window-1; the epilogue adds
+// what the FAR pass left for keys that are candidates, rounds and stores dK, dV, and forms d logit and the counts.
+// FAR = true: the keys are 128 consecutive entries of the compacted candidates (positions ascending), seen by the
+// queries from position + window on; the fp32 sums go to a scratch array indexed like the compact segment.
+template <bool FAR>
+__global__ void __launch_bounds__(kThreads, 2)
+train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* far_dk, float* far_dv) {
+  constexpr int kQ = 0, kQt = BN * KS, kO = BN * KS + BN * VS, kOt = 2 * BN * KS + BN * VS, kBuf = 2 * BN * KS + 2 * BN * VS;
+  static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
+  __shared__ __align__(16) bf16_t lds[kBuf];
+  __shared__ __align__(16) float lse_lds[BN], dlt_lds[BN];
+
+  const int Hq = A.Hq, Hkv = A.Hkv, window = A.window, cap = A.budget;
+  const int G = Hq / Hkv;
+  int s, n, lo, h, j0 = 0, r_base = 0, cnt = 0;
+  if (FAR) {
+    const int per_head = (A.max_seqlen + BM - 1) / BM;
+    const int hd = blockIdx.x / per_head;
+    r_base = (blockIdx.x - hd * per_head) * BM;
+    s = hd / Hkv;
+    h = hd - s * Hkv;
+    cnt = A.ret_count[hd];
+    if (r_base >= cnt) return;
+    lo = A.cu[s];
+    n = A.cu[s + 1] - lo;
+  } else {
+    h = blockIdx.x / tiles_upper;
+    int tile;
+    if (!locate_tile(A.cu, A.n_seqs, BM, blockIdx.x - h * tiles_upper, s, tile, lo, n)) return;
+    j0 = tile * BM;
+  }
+  const int64_t head = (int64_t)s * Hkv + h;
+  const int32_t* rp = A.ret_pos + head * cap;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ql = lane & 31, hb = lane >> 5;
+  const bf16_t* q = static_cast<const bf16_t*>(A.q);
+  const bf16_t* dout = static_cast<const bf16_t*>(A.dout);
+
+  // ---- this lane's key: its K / V fragments and the range of queries [q_lo, q_hi) that saw it -----------------
+  const int kloc = 32 * wv + ql;          // key index inside the workgroup
+  int q_lo = 0, q_hi = 0, jpos = 0;
+  const bf16_t *krow, *vrow;
+  bool key_ok;
+  if (FAR) {
+    const int r = r_base + kloc;
+    key_ok = r < cnt;
+    const int rc = key_ok ? r : cnt - 1;
+    jpos = rp[rc];
+    krow = static_cast<const bf16_t*>(A.k_ret) + (head * cap + rc) * D;
+    vrow = static_cast<const bf16_t*>(A.v_ret) + (head * cap + rc) * D;
+    if (key_ok) { q_lo = jpos + window; q_hi = n; }
+  } else {
+    const int j = j0 + kloc;
+    key_ok = j < n;
+    jpos = key_ok ? j : n - 1;
+    krow = static_cast<const bf16_t*>(A.k) + (int64_t)(lo + jpos) * A.kv_st + (int64_t)h * A.kv_sh;
+    vrow = static_cast<const bf16_t*>(A.v) + (int64_t)(lo + jpos) * A.kv_st + (int64_t)h * A.kv_sh;
+    if (key_ok) { q_lo = j; q_hi = j + window < n ? j + window : n; }
+  }
+  const unsigned q_span = (unsigned)(q_hi - q_lo);     // 0 for lanes without a key
+  bf16x8 kreg[D / 16], vreg[D / 16];
+#pragma unroll
+  for (int ks = 0; ks < D / 16; ++ks) {
+    kreg[ks] = *reinterpret_cast<const bf16x8*>(krow + 16 * ks + 8 * hb);
+    vreg[ks] = *reinterpret_cast<const bf16x8*>(vrow + 16 * ks + 8 * hb);
+  }
+
+  // ---- query tiles the workgroup has to visit (the same for every query head of the group) --------------------
+  int qt_first, qt_last;
+  if (FAR) {
+    qt_first = (rp[r_base] + window) / BN;            // positions ascend: the first entry is seen first
+    qt_last = (n - 1) / BN;
+  } else {
+    qt_first = j0 / BN;
+    const int last_key = (j0 + BM < n ? j0 + BM : n) - 1;
+    const int last_q = last_key + window - 1 < n - 1 ? last_key + window - 1 : n - 1;
+    qt_last = last_q / BN;
+  }
+  const int n_qt = qt_last - qt_first + 1;
+  const int n_iter = n_qt * G;
+
+  const uint32_t q_row_bytes = (uint32_t)A.q_st * 2u, o_row_bytes = (uint32_t)(Hq * D) * 2u;
+  const uint32_t q_bytes = (uint32_t)(n - 1) * q_row_bytes + (uint32_t)(D * 2);
+  const uint32_t o_bytes = (uint32_t)(n - 1) * o_row_bytes + (uint32_t)(D * 2);
+  const int k_piece = tid % PPR, k_row = tid / PPR;
+  auto load_tile = [&](int it, QTileRegs& R) {
+    const int g = it / n_qt, t = it - g * n_qt;
+    const int hq = h * G + g;
+    const int qt = (qt_first + t) * BN;
+    const auto rs_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(q + (int64_t)lo * A.q_st + (int64_t)hq * A.q_sh), 0, q_bytes, 0x00020000);
+    const auto rs_o = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(dout + ((int64_t)lo * Hq + hq) * D), 0, o_bytes, 0x00020000);
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+      const uint32_t row = (uint32_t)(qt + k_row + p * RPP);
+      R.a[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_q, row * q_row_bytes + (uint32_t)k_piece * 16u, 0, 0);
+      R.b[p] = __builtin_amdgcn_raw_buffer_load_b128(rs_o, row * o_row_bytes + (uint32_t)k_piece * 16u, 0, 0);
+    }
+    if (tid < 2 * BN) {
+      const int qrow = qt + (tid & (BN - 1));
+      const int qc = qrow < n ? qrow : n - 1;
+      const int64_t idx = (int64_t)hq * A.total + lo + qc;
+      R.stat = tid < BN ? A.lse[idx] * 1.4426950408889634f : A.delta[idx];
+    }
+  };
+  static_assert(RPP % 4 == 0, "row passes must preserve the swizzle phase");
+  const int p_st_off = k_row * KS + k_piece * 8;
+  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle(k_row)) << 5) + (k_piece & 3) * 8;
+  auto store_tile = [&](const QTileRegs& R) {
+#pragma unroll
+    for (int p = 0; p < KPASS; ++p) {
+      *reinterpret_cast<u32x4*>(lds + kQ + p_st_off + p * RPP * KS) = R.a[p];
+      *reinterpret_cast<u32x4*>(lds + kQt + t_st_off + p * RPP * VS) = R.a[p];
+      *reinterpret_cast<u32x4*>(lds + kO + p_st_off + p * RPP * KS) = R.b[p];
+      *reinterpret_cast<u32x4*>(lds + kOt + t_st_off + p * RPP * VS) = R.b[p];
+    }
+    if (tid < BN) lse_lds[tid] = R.stat;
+    else if (tid < 2 * BN) dlt_lds[tid - BN] = R.stat;
+  };
+
+  const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*qb*KS + 16*ks
+  const int tr_row = 8 * hb + ((lane & 15) >> 2);
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  const int tr_swz = chunk_swizzle(tr_row);
+  const int a_tr_off = tr_row * VS + tr_col;
+
+  f32x16 dva[D / 32], dka[D / 32];
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dva[db][r] = 0.f; dka[db][r] = 0.f; }
+
+  auto compute = [&](const bool masked, int qt) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 sc, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) {
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(lds + kQ + a_row_off + 32 * qb * KS + 16 * ks);
+        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(lds + kO + a_row_off + 32 * qb * KS + 16 * ks);
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kreg[ks], sc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, vreg[ks], dp, 0, 0, 0);
+      }
+      // register r is the tile's query 32*qb + 16*(r/8) + 8*hb + r%8
+      bf16x8 pp[2], ps[2];
+#pragma unroll
+      for (int r8 = 0; r8 < 2; ++r8) {
+        const int row0 = 32 * qb + 16 * r8 + 8 * hb;
+        const f32x4 l0 = *reinterpret_cast<const f32x4*>(lse_lds + row0), l1 = *reinterpret_cast<const f32x4*>(lse_lds + row0 + 4);
+        const f32x4 d0 = *reinterpret_cast<const f32x4*>(dlt_lds + row0), d1 = *reinterpret_cast<const f32x4*>(dlt_lds + row0 + 4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float l = e < 4 ? l0[e] : l1[e - 4];
+          const float dl = e < 4 ? d0[e] : d1[e - 4];
+          float p = __builtin_amdgcn_exp2f(fmaf(sc[8 * r8 + e], scale_log2e, -l));
+          if (masked) p = ((unsigned)(qt + row0 + e - q_lo) < q_span) ? p : 0.f;
+          pp[r8][e] = static_cast<bf16_t>(p);
+          ps[r8][e] = static_cast<bf16_t>(p * (dp[8 * r8 + e] - dl));
+        }
+      }
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db) {
+        const bf16_t* ao = lds + kOt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
+        const bf16_t* aq = lds + kQt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
+        const bf16x8 o0 = load_transposed(ao, VS), o1 = load_transposed(ao + 16 * VS, VS);
+        const bf16x8 q0 = load_transposed(aq, VS), q1 = load_transposed(aq + 16 * VS, VS);
+        dva[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o0, pp[0], dva[db], 0, 0, 0);
+        dva[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o1, pp[1], dva[db], 0, 0, 0);
+        dka[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q0, ps[0], dka[db], 0, 0, 0);
+        dka[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q1, ps[1], dka[db], 0, 0, 0);
+      }
+    }
+  };
+
+  QTileRegs regs;
+  load_tile(0, regs);
+  for (int it = 0; it < n_iter; ++it) {
+    __syncthreads();
+    store_tile(regs);
+    __syncthreads();
+    if (it + 1 < n_iter) load_tile(it + 1, regs);
+    const int t = it % n_qt;
+    const int qt = (qt_first + t) * BN;
+    // does any key of this wave see a query of the tile, and do all of them see all of it?
+    const bool touches = q_span != 0u && q_lo < qt + BN && q_hi > qt;
+    const bool covers = q_span != 0u && q_lo <= qt && q_hi >= qt + BN;
+    if (__builtin_amdgcn_ballot_w64(touches) == 0ull) continue;
+    if (__builtin_amdgcn_ballot_w64(!covers) == 0ull) compute(false, qt);
+    else compute(true, qt);
+  }
+
+  // ---- epilogue: accumulator register r of block db is feature d = 32*db + 8*(r/4) + 4*hb + r%4 of the lane's key ---
+  if (FAR) {
+    if (key_ok) {
+      float* fk = far_dk + (head * cap + r_base + kloc) * D + 4 * hb;
+      float* fv = far_dv + (head * cap + r_base + kloc) * D + 4 * hb;
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int g4 = 0; g4 < 4; ++g4) {
+          f32x4 a, b;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { a[e] = dka[db][4 * g4 + e] * A.scale; b[e] = dva[db][4 * g4 + e]; }
+          *reinterpret_cast<f32x4*>(fk + 32 * db + 8 * g4) = a;
+          *reinterpret_cast<f32x4*>(fv + 32 * db + 8 * g4) = b;
+        }
+    }
+    return;
+  }
+  // band: add the far part of candidate keys (their compact index by binary search over the ascending positions)
+  int ridx = -1;
+  if (key_ok && cap > 0) {
+    int a = 0, b = A.ret_count[head];
+    while (a < b) {
+      const int mid = (a + b) >> 1;
+      if (rp[mid] < jpos) a = mid + 1; else b = mid;
+    }
+    if (a < A.ret_count[head] && rp[a] == jpos) ridx = a;
+  }
+  float ste = 0.f;
+#pragma unroll
+  for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+    for (int g4 = 0; g4 < 4; ++g4) {
+      const int d0 = 32 * db + 8 * g4 + 4 * hb;
+      f32x4 fk = {0.f, 0.f, 0.f, 0.f}, fv = {0.f, 0.f, 0.f, 0.f};
+      if (ridx >= 0) {
+        fk = *reinterpret_cast<const f32x4*>(far_dk + (head * cap + ridx) * D + d0);
+        fv = *reinterpret_cast<const f32x4*>(far_dv + (head * cap + ridx) * D + d0);
+      }
+      const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(vrow + d0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        dka[db][4 * g4 + e] = fmaf(dka[db][4 * g4 + e], A.scale, fk[e]);
+        dva[db][4 * g4 + e] += fv[e];
+        ste = fmaf(dva[db][4 * g4 + e], static_cast<float>(v4[e]), ste);
+      }
+    }
+  ste = pair_sum(ste);
+  {
+    const float z = A.logits[(int64_t)h * A.total + lo + jpos];
+    const bool above = key_ok && z > A.tau;
+    if (key_ok && hb == 0) {
+      const float r = 1.0f / (1.0f + expf(-z));
+      A.dz[(int64_t)h * A.total + lo + jpos] = (ste + (above ? A.lambda[h] : 0.f)) * r * (1.0f - r);
+    }
+    const int c = __builtin_popcountll(__builtin_amdgcn_ballot_w64(above && hb == 0));
+    if (lane == 0 && c > 0) atomicAdd(&A.counts[s * Hkv + h], c);    // integer: order does not matter
+  }
+  bf16_t* outs[2] = {static_cast<bf16_t*>(A.dk), static_cast<bf16_t*>(A.dv)};
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+    bf16_t* orow = lds + kloc * OS + 4 * hb;
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 w4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w4[e] = static_cast<bf16_t>(which == 0 ? dka[db][4 * g4 + e] : dva[db][4 * g4 + e]);
+        *reinterpret_cast<bf16x4*>(orow + 32 * db + 8 * g4) = w4;
+      }
+    __syncthreads();
+    bf16_t* obase = outs[which] + ((int64_t)(lo + j0) * Hkv + h) * D;
+    const int64_t orow_stride = (int64_t)Hkv * D;
+#pragma unroll
+    for (int p = 0; p < BM / RPP; ++p) {
+      const int row = p * RPP + k_row;
+      if (j0 + row < n)
+        *reinterpret_cast<u32x4*>(obase + row * orow_stride + k_piece * 8) =
+            *reinterpret_cast<const u32x4*>(lds + row * OS + k_piece * 8);
+    }
+  }
+}
+
 }  // namespace
 
 // Rows are addressed with 32-bit byte offsets inside one sequence, and loaded in 16-byte pieces.
@@ -304,6 +602,23 @@ hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream) {
   const int64_t grid = (n_work + 7) / 8 * 8;
   hipLaunchKernelGGL(train_dq_mfma_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, A, (int)tiles_upper,
                      (int)n_work, A.scale * 1.4426950408889634f);
+  return hipGetLastError();
+}
+
+// far_dk / far_dv: fp32 scratch, [n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
+hipError_t launch_train_dkv_mfma(const TrainArgs& A, float* far_dk, float* far_dv, hipStream_t stream) {
+  const float sl2 = A.scale * 1.4426950408889634f;
+  const int per_head = (A.max_seqlen + BM - 1) / BM;
+  const int64_t far_grid = (int64_t)A.n_seqs * A.Hkv * per_head;
+  if (far_grid > 0 && A.budget > 0) {
+    hipLaunchKernelGGL(train_dkv_mfma_kernel<true>, dim3((unsigned)far_grid), dim3(kThreads), 0, stream, A, 0, sl2, far_dk,
+                       far_dv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
+  hipLaunchKernelGGL(train_dkv_mfma_kernel<false>, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
+                     (int)tiles_upper, sl2, far_dk, far_dv);
   return hipGetLastError();
 }
 
