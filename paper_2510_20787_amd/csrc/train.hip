@@ -199,25 +199,6 @@ __global__ void __launch_bounds__(256) train_zero_counts_kernel(int32_t* counts,
   if (i < n) counts[i] = 0;
 }
 
-// delta = <dO, O> per (query, query head): one wave per row (the matrix-core path reads it from memory; the
-// generic dQ kernel computes it on its own).
-template <typename T, int D>
-__global__ void __launch_bounds__(kWavesPerBlock * kWave)
-train_delta_kernel(TrainArgs A) {
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-  const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
-  if (item >= A.total * A.Hq) return;
-  const int64_t tok = item / A.Hq;
-  const int hq = (int)(item - tok * A.Hq);
-  const T* orow = static_cast<const T*>(A.out) + item * D;
-  const T* dorow = static_cast<const T*>(A.dout) + item * D;
-  float dsum = 0.f;
-#pragma unroll
-  for (int e = 0; e < D / kWave; ++e) dsum = fmaf(to_f32(dorow[lane + e * kWave]), to_f32(orow[lane + e * kWave]), dsum);
-  dsum = wave_sum(dsum);
-  if (lane == 0) A.delta[(int64_t)hq * A.total + tok] = dsum;
-}
-
 template <typename T, int D>
 hipError_t run(const TrainArgs& A, hipStream_t stream) {
   const int n_counts = A.n_seqs * A.Hkv;
@@ -230,10 +211,7 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
   const dim3 qgrid((unsigned)((qi + kWavesPerBlock - 1) / kWavesPerBlock)), block(kWavesPerBlock * kWave);
   if constexpr (std::is_same<T, bf16_t>::value && D == 64) {
     if (train_mfma_supported(A)) {
-      // matrix-core path: delta first, then dQ per query tile and dK / dV per key tile
-      hipLaunchKernelGGL((train_delta_kernel<T, D>), qgrid, block, 0, stream, A);
-      e = hipGetLastError();
-      if (e != hipSuccess) return e;
+      // matrix-core path: dQ (and delta) per query tile, then dK / dV per key tile
       e = launch_train_dq_mfma(A, stream);
       if (e != hipSuccess) return e;
       return launch_train_dkv_mfma(A, A.far_dk, A.far_dv, stream);

@@ -18,7 +18,7 @@ struct TrainArgs {
   int max_seqlen;
   const float *lse, *logits, *lambda;
   float* delta;
-  float *far_dk, *far_dv;               // fp32 scratch of the matrix-core dK / dV path, laid out like k_ret / v_ret
+  float *far_dk, *far_dv;               // fp32 scratch of the matrix-core dK / dV path, G slices laid out like k_ret / v_ret
   void *dq, *dk, *dv;
   float* dz;
   int32_t* counts;

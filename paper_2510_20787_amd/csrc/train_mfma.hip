@@ -59,6 +59,12 @@ __device__ __forceinline__ int wave_max_i(int x) {
   return x;
 }
 
+// Both lane halves (l, l^32) receive the sum of the pair.
+__device__ __forceinline__ float pair_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 struct TileRegs {
   u32x4 a[KPASS], b[KPASS];
   int pos;
@@ -108,7 +114,19 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
     }
   }
   const float lse2 = A.lse[(int64_t)hq * A.total + lo + qc] * 1.4426950408889634f;
-  const float dlt = A.delta[(int64_t)hq * A.total + lo + qc];
+  // delta = <dO, O> of the lane's query: each lane half holds half of the row; also left in memory for the dK / dV pass
+  float dlt = 0.f;
+  {
+    const bf16_t* orow = static_cast<const bf16_t*>(A.out) + ((int64_t)(lo + qc) * Hq + hq) * D;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      const bf16x8 o8 = *reinterpret_cast<const bf16x8*>(orow + 16 * ks + 8 * hb);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dlt = fmaf(static_cast<float>(doreg[ks][e]), static_cast<float>(o8[e]), dlt);
+    }
+    dlt = pair_sum(dlt);
+    if (hb == 0 && qi < n) A.delta[(int64_t)hq * A.total + lo + qi] = dlt;
+  }
 
   // ---- tile schedule (as in the forward) ------------------------------------------------------------------
   const int i_last = (i0 + BM < n ? i0 + BM : n) - 1;
@@ -289,11 +307,6 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
 }
 
 
-// Both lane halves (l, l^32) receive the sum of the pair.
-__device__ __forceinline__ float pair_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
 
 struct QTileRegs {
   u32x4 a[KPASS], b[KPASS];
@@ -322,10 +335,16 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   const int Hq = A.Hq, Hkv = A.Hkv, window = A.window, cap = A.budget;
   const int G = Hq / Hkv;
   int s, n, lo, h, j0 = 0, r_base = 0, cnt = 0;
+  int g_first = 0, g_count = G;          // query heads of the group this workgroup walks
   if (FAR) {
+    // one workgroup per (128 compact entries, query head of the group): the partial sums of the G query heads go to
+    // G scratch slices that the band pass adds up in a fixed order
     const int per_head = (A.max_seqlen + BM - 1) / BM;
-    const int hd = blockIdx.x / per_head;
-    r_base = (blockIdx.x - hd * per_head) * BM;
+    g_first = blockIdx.x % G;
+    g_count = 1;
+    const int rest = blockIdx.x / G;
+    const int hd = rest / per_head;
+    r_base = (rest - hd * per_head) * BM;
     s = hd / Hkv;
     h = hd - s * Hkv;
     cnt = A.ret_count[hd];
@@ -388,7 +407,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
     qt_last = last_q / BN;
   }
   const int n_qt = qt_last - qt_first + 1;
-  const int n_iter = n_qt * G;
+  const int n_iter = n_qt * g_count;
 
   const uint32_t q_row_bytes = (uint32_t)A.q_st * 2u, o_row_bytes = (uint32_t)(Hq * D) * 2u;
   const uint32_t q_bytes = (uint32_t)(n - 1) * q_row_bytes + (uint32_t)(D * 2);
@@ -396,7 +415,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   const int k_piece = tid % PPR, k_row = tid / PPR;
   auto load_tile = [&](int it, QTileRegs& R) {
     const int g = it / n_qt, t = it - g * n_qt;
-    const int hq = h * G + g;
+    const int hq = h * G + g_first + g;
     const int qt = (qt_first + t) * BN;
     const auto rs_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(q + (int64_t)lo * A.q_st + (int64_t)hq * A.q_sh), 0, q_bytes, 0x00020000);
     const auto rs_o = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(dout + ((int64_t)lo * Hq + hq) * D), 0, o_bytes, 0x00020000);
@@ -441,7 +460,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
     for (int r = 0; r < 16; ++r) { dva[db][r] = 0.f; dka[db][r] = 0.f; }
 
   auto compute = [&](const bool masked, int qt) {
-#pragma unroll
+#pragma unroll 1
     for (int qb = 0; qb < 2; ++qb) {
       f32x16 sc, dp;
 #pragma unroll
@@ -504,8 +523,9 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   // ---- epilogue: accumulator register r of block db is feature d = 32*db + 8*(r/4) + 4*hb + r%4 of the lane's key ---
   if (FAR) {
     if (key_ok) {
-      float* fk = far_dk + (head * cap + r_base + kloc) * D + 4 * hb;
-      float* fv = far_dv + (head * cap + r_base + kloc) * D + 4 * hb;
+      const int64_t slice = (int64_t)g_first * A.n_seqs * Hkv + head;
+      float* fk = far_dk + (slice * cap + r_base + kloc) * D + 4 * hb;
+      float* fv = far_dv + (slice * cap + r_base + kloc) * D + 4 * hb;
 #pragma unroll
       for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -537,8 +557,13 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
       const int d0 = 32 * db + 8 * g4 + 4 * hb;
       f32x4 fk = {0.f, 0.f, 0.f, 0.f}, fv = {0.f, 0.f, 0.f, 0.f};
       if (ridx >= 0) {
-        fk = *reinterpret_cast<const f32x4*>(far_dk + (head * cap + ridx) * D + d0);
-        fv = *reinterpret_cast<const f32x4*>(far_dv + (head * cap + ridx) * D + d0);
+        for (int g = 0; g < G; ++g) {
+          const int64_t slice = (int64_t)g * A.n_seqs * Hkv + head;
+          const f32x4 a = *reinterpret_cast<const f32x4*>(far_dk + (slice * cap + ridx) * D + d0);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(far_dv + (slice * cap + ridx) * D + d0);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { fk[e] += a[e]; fv[e] += b[e]; }
+        }
       }
       const bf16x4 v4 = *reinterpret_cast<const bf16x4*>(vrow + d0);
 #pragma unroll
@@ -605,11 +630,11 @@ hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream) {
   return hipGetLastError();
 }
 
-// far_dk / far_dv: fp32 scratch, [n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
+// far_dk / far_dv: fp32 scratch, [Hq / Hkv][n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
 hipError_t launch_train_dkv_mfma(const TrainArgs& A, float* far_dk, float* far_dv, hipStream_t stream) {
   const float sl2 = A.scale * 1.4426950408889634f;
   const int per_head = (A.max_seqlen + BM - 1) / BM;
-  const int64_t far_grid = (int64_t)A.n_seqs * A.Hkv * per_head;
+  const int64_t far_grid = (int64_t)A.n_seqs * A.Hkv * per_head * (A.Hq / A.Hkv);
   if (far_grid > 0 && A.budget > 0) {
     hipLaunchKernelGGL(train_dkv_mfma_kernel<true>, dim3((unsigned)far_grid), dim3(kThreads), 0, stream, A, 0, sl2, far_dk,
                        far_dv);

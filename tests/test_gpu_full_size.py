@@ -284,3 +284,55 @@ def test_full_decode_bf16(lazy):
                 if p >= n0 - rho:      # logits finalised by the decode steps themselves
                     zg = float(cache.win_score[b, h, p % st.window])
                     assert abs(zg - zp) <= LOGIT_TOL["bf16"] * max(1.0, abs(zp))
+
+
+def test_full_train_paper_stack_bf16():
+    """Training forward + backward at the paper's module shape (B=4 x n=4096, 32 query heads on 8 KV heads, D=64,
+    window 768, no cap): one (sequence, KV head) group per run through the fp64 oracle (dense n x n), all rows;
+    retention counts of every (sequence, head) against the oracle's logits."""
+    w = wl.config_paper_stack_bf16()
+    d = DeviceWorkload(w)
+    rng = np.random.default_rng(w.seed + 99)
+    dout = wl.to_storage(rng.standard_normal(w.q.shape, dtype=np.float32), "bf16")
+    lam = np.full(w.Hkv, 1e-3, dtype=np.float32)
+    out, lse, logits, ws = B.ltea_train_forward(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen)
+    dq, dk, dv, dz, counts = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, out, dev(dout, "bf16"), lse,
+                                                   logits, torch.from_numpy(lam).cuda(), ws)
+    torch.cuda.synchronize()
+    cnn = oracle_cnn(w.cnn)
+    z64 = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    zg = to_np(logits)
+    eps = float(np.max(np.abs(zg - z64)))
+    assert eps <= 5 * LOGIT_TOL["bf16"] * max(1.0, float(np.max(np.abs(z64))))
+    cnt_g = counts.cpu().numpy()
+    G = w.Hq // w.Hkv
+    n_checked = 0
+    for s, h in ((0, 2), (3, 4)):                       # heads with a mixed kept / dropped population
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        zh = z64[h:h + 1, lo:hi]
+        if np.min(np.abs(zh)) <= 2 * eps:
+            continue                                    # a logit inside the scoring error of the threshold
+        n_checked += 1
+        print(f"[train paper_stack] oracle backward for sequence {s}, KV head {h} (kept {float((zh > 0).mean()):.2f})", flush=True)
+        sub = orc.OracleCfg(G, 1, w.D, w.window, 1, w.sink, w.tau)
+        qs = w.q[lo:hi, h * G:(h + 1) * G]; ks = w.k[lo:hi, h:h + 1]; vs = w.v[lo:hi, h:h + 1]
+        o_ref, lse_ref, _ = orc.train_forward_sequence(qs, ks, vs, zh, sub)
+        dq_ref, dk_ref, dv_ref, dz_ref, c_ref = orc.train_backward_sequence(qs, ks, vs, zh, dout[lo:hi, h * G:(h + 1) * G], sub,
+                                                                             lam[h:h + 1].astype(np.float64))
+        pairs = ((to_np(out[lo:hi, h * G:(h + 1) * G]), o_ref, "out"), (to_np(dq[lo:hi, h * G:(h + 1) * G]), dq_ref, "dq"),
+                 (to_np(dk[lo:hi, h:h + 1]), dk_ref, "dk"), (to_np(dv[lo:hi, h:h + 1]), dv_ref, "dv"),
+                 (to_np(dz[h:h + 1, lo:hi]), dz_ref, "dz"))
+        for got, ref, what in pairs:
+            scale = float(np.max(np.abs(ref)))
+            err = float(np.max(np.abs(got.astype(np.float64) - ref)))
+            assert err <= OUT_TOL["bf16"] * scale, (s, h, what, err, scale)
+        assert float(np.max(np.abs(to_np(lse[h * G:(h + 1) * G, lo:hi]) - lse_ref))) <= 2e-3
+        assert int(cnt_g[s, h]) == int(c_ref[0])
+    assert n_checked >= 1
+    # counts of every (sequence, head): exact wherever no logit sits inside the scoring error of the threshold
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        for h in range(w.Hkv):
+            zh = z64[h, lo:hi]
+            unsure = int((np.abs(zh) <= 2 * eps).sum())
+            assert abs(int(cnt_g[s, h]) - int((zh.astype(np.float32) > 0).sum())) <= unsure
