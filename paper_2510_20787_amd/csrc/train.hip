@@ -211,10 +211,7 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
   const dim3 qgrid((unsigned)((qi + kWavesPerBlock - 1) / kWavesPerBlock)), block(kWavesPerBlock * kWave);
   if constexpr (std::is_same<T, bf16_t>::value && D == 64) {
     if (train_mfma_supported(A)) {
-      // matrix-core path: dQ (and delta) per query tile, then dK / dV per key tile
-      e = launch_train_dq_mfma(A, stream);
-      if (e != hipSuccess) return e;
-      return launch_train_dkv_mfma(A, A.far_dk, A.far_dv, stream);
+      return launch_train_backward_mfma(A, stream);   // matrix-core path
     }
   }
   hipLaunchKernelGGL((train_dq_kernel<T, D>), qgrid, block, 0, stream, A);

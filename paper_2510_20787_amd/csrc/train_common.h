@@ -5,6 +5,8 @@
 
 namespace ltea {
 
+constexpr int kTrainFarChunks = 8;   // shares of the query range in the far pass of dK / dV (= scratch slices)
+
 struct TrainArgs {
   const void *q, *k, *v, *out, *dout;
   int64_t q_st, q_sh, kv_st, kv_sh;
@@ -18,7 +20,7 @@ struct TrainArgs {
   int max_seqlen;
   const float *lse, *logits, *lambda;
   float* delta;
-  float *far_dk, *far_dv;               // fp32 scratch of the matrix-core dK / dV path, G slices laid out like k_ret / v_ret
+  float *far_dk, *far_dv;               // fp32 scratch of the matrix-core dK / dV path, kTrainFarChunks slices laid out like k_ret / v_ret
   void *dq, *dk, *dv;
   float* dz;
   int32_t* counts;
@@ -26,7 +28,6 @@ struct TrainArgs {
 
 // bf16, D = 64 path on MFMA (train_mfma.hip).
 bool train_mfma_supported(const TrainArgs& A);
-hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream);
-hipError_t launch_train_dkv_mfma(const TrainArgs& A, float* far_dk, float* far_dv, hipStream_t stream);
+hipError_t launch_train_backward_mfma(const TrainArgs& A, hipStream_t stream);
 
 }  // namespace ltea

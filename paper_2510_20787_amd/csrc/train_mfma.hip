@@ -70,8 +70,7 @@ struct TileRegs {
   int pos;
 };
 
-__global__ void __launch_bounds__(kThreads, 2)
-train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e) {
+__device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int n_work, float scale_log2e, int block) {
   constexpr int kK = 0, kKt = BN * KS, kV = BN * KS + BN * VS, kBuf = 2 * BN * KS + BN * VS;
   static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
   __shared__ __align__(16) bf16_t lds[kBuf];
@@ -79,7 +78,7 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
   __shared__ int pos_rng[2];
 
   const int per_xcd = (n_work + 7) / 8;
-  const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  const int work = (block % 8) * per_xcd + block / 8;
   if (work >= n_work) return;
   const int hq = work / tiles_upper;
   int tile, s, n, lo;
@@ -114,7 +113,7 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
     }
   }
   const float lse2 = A.lse[(int64_t)hq * A.total + lo + qc] * 1.4426950408889634f;
-  // delta = <dO, O> of the lane's query: each lane half holds half of the row; also left in memory for the dK / dV pass
+  // delta = <dO, O> of the lane's query: each lane half holds half of the row
   float dlt = 0.f;
   {
     const bf16_t* orow = static_cast<const bf16_t*>(A.out) + ((int64_t)(lo + qc) * Hq + hq) * D;
@@ -125,7 +124,6 @@ train_dq_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e
       for (int e = 0; e < 8; ++e) dlt = fmaf(static_cast<float>(doreg[ks][e]), static_cast<float>(o8[e]), dlt);
     }
     dlt = pair_sum(dlt);
-    if (hb == 0 && qi < n) A.delta[(int64_t)hq * A.total + lo + qi] = dlt;
   }
 
   // ---- tile schedule (as in the forward) ------------------------------------------------------------------
@@ -325,8 +323,8 @@ struct QTileRegs {
 // FAR = true: the keys are 128 consecutive entries of the compacted candidates (positions ascending), seen by the
 // queries from position + window on; the fp32 sums go to a scratch array indexed like the compact segment.
 template <bool FAR>
-__global__ void __launch_bounds__(kThreads, 2)
-train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* far_dk, float* far_dv) {
+__device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, float scale_log2e, float* far_dk,
+                                         float* far_dv, int block) {
   constexpr int kQ = 0, kQt = BN * KS, kO = BN * KS + BN * VS, kOt = 2 * BN * KS + BN * VS, kBuf = 2 * BN * KS + 2 * BN * VS;
   static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
   __shared__ __align__(16) bf16_t lds[kBuf];
@@ -335,15 +333,16 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   const int Hq = A.Hq, Hkv = A.Hkv, window = A.window, cap = A.budget;
   const int G = Hq / Hkv;
   int s, n, lo, h, j0 = 0, r_base = 0, cnt = 0;
-  int g_first = 0, g_count = G;          // query heads of the group this workgroup walks
+  int chunk = 0;                          // FAR: which share of the query tiles this workgroup walks
   if (FAR) {
-    // one workgroup per (128 compact entries, query head of the group): the partial sums of the G query heads go to
-    // G scratch slices that the band pass adds up in a fixed order
+    // one workgroup per (128 compact entries, share of the query range): kTrainFarChunks shares of equal length keep
+    // the workgroups short and alike; their partial sums go to one scratch slice each, which the band pass adds up
+    // in a fixed order
     const int per_head = (A.max_seqlen + BM - 1) / BM;
-    g_first = blockIdx.x % G;
-    g_count = 1;
-    const int rest = blockIdx.x / G;
+    chunk = block % kTrainFarChunks;
+    const int rest = block / kTrainFarChunks;
     const int hd = rest / per_head;
+    if (hd >= A.n_seqs * Hkv) return;     // padding workgroups of the combined launch
     r_base = (rest - hd * per_head) * BM;
     s = hd / Hkv;
     h = hd - s * Hkv;
@@ -352,9 +351,9 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
     lo = A.cu[s];
     n = A.cu[s + 1] - lo;
   } else {
-    h = blockIdx.x / tiles_upper;
+    h = block / tiles_upper;
     int tile;
-    if (!locate_tile(A.cu, A.n_seqs, BM, blockIdx.x - h * tiles_upper, s, tile, lo, n)) return;
+    if (!locate_tile(A.cu, A.n_seqs, BM, block - h * tiles_upper, s, tile, lo, n)) return;
     j0 = tile * BM;
   }
   const int64_t head = (int64_t)s * Hkv + h;
@@ -397,9 +396,13 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
 
   // ---- query tiles the workgroup has to visit (the same for every query head of the group) --------------------
   int qt_first, qt_last;
+  const int chunk_tiles = ((n + BN - 1) / BN + kTrainFarChunks - 1) / kTrainFarChunks;   // query tiles per share
   if (FAR) {
     qt_first = (rp[r_base] + window) / BN;            // positions ascend: the first entry is seen first
     qt_last = (n - 1) / BN;
+    qt_first = qt_first > chunk * chunk_tiles ? qt_first : chunk * chunk_tiles;
+    qt_last = qt_last < (chunk + 1) * chunk_tiles - 1 ? qt_last : (chunk + 1) * chunk_tiles - 1;
+    if (qt_first > qt_last) return;                   // this share lies before the entries' first query: nothing to add
   } else {
     qt_first = j0 / BN;
     const int last_key = (j0 + BM < n ? j0 + BM : n) - 1;
@@ -407,7 +410,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
     qt_last = last_q / BN;
   }
   const int n_qt = qt_last - qt_first + 1;
-  const int n_iter = n_qt * g_count;
+  const int n_iter = n_qt * G;
 
   const uint32_t q_row_bytes = (uint32_t)A.q_st * 2u, o_row_bytes = (uint32_t)(Hq * D) * 2u;
   const uint32_t q_bytes = (uint32_t)(n - 1) * q_row_bytes + (uint32_t)(D * 2);
@@ -415,7 +418,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   const int k_piece = tid % PPR, k_row = tid / PPR;
   auto load_tile = [&](int it, QTileRegs& R) {
     const int g = it / n_qt, t = it - g * n_qt;
-    const int hq = h * G + g_first + g;
+    const int hq = h * G + g;
     const int qt = (qt_first + t) * BN;
     const auto rs_q = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(q + (int64_t)lo * A.q_st + (int64_t)hq * A.q_sh), 0, q_bytes, 0x00020000);
     const auto rs_o = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(dout + ((int64_t)lo * Hq + hq) * D), 0, o_bytes, 0x00020000);
@@ -523,7 +526,7 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   // ---- epilogue: accumulator register r of block db is feature d = 32*db + 8*(r/4) + 4*hb + r%4 of the lane's key ---
   if (FAR) {
     if (key_ok) {
-      const int64_t slice = (int64_t)g_first * A.n_seqs * Hkv + head;
+      const int64_t slice = (int64_t)chunk * A.n_seqs * Hkv + head;
       float* fk = far_dk + (slice * cap + r_base + kloc) * D + 4 * hb;
       float* fv = far_dv + (slice * cap + r_base + kloc) * D + 4 * hb;
 #pragma unroll
@@ -549,6 +552,12 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
     }
     if (a < A.ret_count[head] && rp[a] == jpos) ridx = a;
   }
+  // the shares of the query range in which the far pass wrote something for this entry's group of 128
+  int c_first = 0, c_last = -1;
+  if (ridx >= 0) {
+    c_first = ((rp[ridx / BM * BM] + window) / BN) / chunk_tiles;
+    c_last = ((n - 1) / BN) / chunk_tiles;
+  }
   float ste = 0.f;
 #pragma unroll
   for (int db = 0; db < D / 32; ++db)
@@ -557,8 +566,8 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
       const int d0 = 32 * db + 8 * g4 + 4 * hb;
       f32x4 fk = {0.f, 0.f, 0.f, 0.f}, fv = {0.f, 0.f, 0.f, 0.f};
       if (ridx >= 0) {
-        for (int g = 0; g < G; ++g) {
-          const int64_t slice = (int64_t)g * A.n_seqs * Hkv + head;
+        for (int c = c_first; c <= c_last; ++c) {
+          const int64_t slice = (int64_t)c * A.n_seqs * Hkv + head;
           const f32x4 a = *reinterpret_cast<const f32x4*>(far_dk + (slice * cap + ridx) * D + d0);
           const f32x4 b = *reinterpret_cast<const f32x4*>(far_dv + (slice * cap + ridx) * D + d0);
 #pragma unroll
@@ -611,6 +620,41 @@ train_dkv_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* fa
   }
 }
 
+// delta = <dO, O> per (query, query head), read by the dK / dV passes: eight lanes per 128-byte row.
+__global__ void __launch_bounds__(kThreads)
+train_delta_mfma_kernel(TrainArgs A) {
+  const int64_t row = (int64_t)blockIdx.x * (kThreads / PPR) + threadIdx.x / PPR;
+  const int piece = threadIdx.x % PPR;
+  const int64_t rows = A.total * A.Hq;
+  const int64_t rc = row < rows ? row : rows - 1;
+  const bf16x8 o8 = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(A.out) + rc * D + piece * 8);
+  const bf16x8 d8 = *reinterpret_cast<const bf16x8*>(static_cast<const bf16_t*>(A.dout) + rc * D + piece * 8);
+  float acc = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc = fmaf(static_cast<float>(d8[e]), static_cast<float>(o8[e]), acc);
+#pragma unroll
+  for (int off = PPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+  if (piece == 0 && row < rows) {
+    const int64_t tok = row / A.Hq;
+    A.delta[(row - tok * A.Hq) * A.total + tok] = acc;
+  }
+}
+
+// One launch, two independent roles: the first far_blocks workgroups run the far pass of dK / dV (few, long-running:
+// the candidates of early positions face almost every later query), the others compute dQ and fill the compute
+// units that the far pass leaves idle.
+__global__ void __launch_bounds__(kThreads, 2)
+train_dq_far_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e, float* far_dk, float* far_dv,
+                         int far_blocks) {
+  if ((int)blockIdx.x < far_blocks) dkv_body<true>(A, 0, scale_log2e, far_dk, far_dv, (int)blockIdx.x);
+  else dq_body(A, tiles_upper, n_work, scale_log2e, (int)blockIdx.x - far_blocks);
+}
+
+__global__ void __launch_bounds__(kThreads, 2)
+train_dkv_band_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* far_dk, float* far_dv) {
+  dkv_body<false>(A, tiles_upper, scale_log2e, far_dk, far_dv, (int)blockIdx.x);
+}
+
 }  // namespace
 
 // Rows are addressed with 32-bit byte offsets inside one sequence, and loaded in 16-byte pieces.
@@ -621,29 +665,27 @@ bool train_mfma_supported(const TrainArgs& A) {
   return al16(A.dout) && al16(A.dq) && al16(A.dk) && al16(A.dv) && al16(A.out);
 }
 
-hipError_t launch_train_dq_mfma(const TrainArgs& A, hipStream_t stream) {
+// delta, then [far pass of dK / dV | dQ] in one launch, then the band pass of dK / dV (which adds the far pass in).
+// far_dk / far_dv: fp32 scratch, [kTrainFarChunks][n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
+hipError_t launch_train_backward_mfma(const TrainArgs& A, hipStream_t stream) {
+  const float sl2 = A.scale * 1.4426950408889634f;
+  const int64_t rows = A.total * A.Hq;
+  hipLaunchKernelGGL(train_delta_mfma_kernel, dim3((unsigned)((rows + kThreads / PPR - 1) / (kThreads / PPR))),
+                     dim3(kThreads), 0, stream, A);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int per_head = (A.max_seqlen + BM - 1) / BM;
+  int64_t far_blocks = A.budget > 0 ? (int64_t)A.n_seqs * A.Hkv * per_head * kTrainFarChunks : 0;
+  far_blocks = (far_blocks + 7) / 8 * 8;      // keeps the dQ role's workgroup-to-XCD pattern
   const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
   const int64_t n_work = tiles_upper * A.Hq;
-  const int64_t grid = (n_work + 7) / 8 * 8;
-  hipLaunchKernelGGL(train_dq_mfma_kernel, dim3((unsigned)grid), dim3(kThreads), 0, stream, A, (int)tiles_upper,
-                     (int)n_work, A.scale * 1.4426950408889634f);
-  return hipGetLastError();
-}
-
-// far_dk / far_dv: fp32 scratch, [Hq / Hkv][n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
-hipError_t launch_train_dkv_mfma(const TrainArgs& A, float* far_dk, float* far_dv, hipStream_t stream) {
-  const float sl2 = A.scale * 1.4426950408889634f;
-  const int per_head = (A.max_seqlen + BM - 1) / BM;
-  const int64_t far_grid = (int64_t)A.n_seqs * A.Hkv * per_head * (A.Hq / A.Hkv);
-  if (far_grid > 0 && A.budget > 0) {
-    hipLaunchKernelGGL(train_dkv_mfma_kernel<true>, dim3((unsigned)far_grid), dim3(kThreads), 0, stream, A, 0, sl2, far_dk,
-                       far_dv);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
-  hipLaunchKernelGGL(train_dkv_mfma_kernel<false>, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
-                     (int)tiles_upper, sl2, far_dk, far_dv);
+  const int64_t dq_blocks = (n_work + 7) / 8 * 8;
+  hipLaunchKernelGGL(train_dq_far_mfma_kernel, dim3((unsigned)(far_blocks + dq_blocks)), dim3(kThreads), 0, stream, A,
+                     (int)tiles_upper, (int)n_work, sl2, A.far_dk, A.far_dv, (int)far_blocks);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(train_dkv_band_mfma_kernel, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
+                     (int)tiles_upper, sl2, A.far_dk, A.far_dv);
   return hipGetLastError();
 }
 
