@@ -209,9 +209,9 @@ hipError_t run(const TrainArgs& A, hipStream_t stream) {
   if (A.total == 0) return hipSuccess;
   const int64_t qi = A.total * A.Hq, ki = A.total * A.Hkv;
   const dim3 qgrid((unsigned)((qi + kWavesPerBlock - 1) / kWavesPerBlock)), block(kWavesPerBlock * kWave);
-  if constexpr (std::is_same<T, bf16_t>::value && D == 64) {
-    if (train_mfma_supported(A)) {
-      return launch_train_backward_mfma(A, stream);   // matrix-core path
+  if constexpr (std::is_same<T, bf16_t>::value) {
+    if (train_mfma_supported(A, D)) {
+      return launch_train_backward_mfma(A, D, stream);   // matrix-core path
     }
   }
   hipLaunchKernelGGL((train_dq_kernel<T, D>), qgrid, block, 0, stream, A);

@@ -26,8 +26,8 @@ struct TrainArgs {
   int32_t* counts;
 };
 
-// bf16, D = 64 path on MFMA (train_mfma.hip).
-bool train_mfma_supported(const TrainArgs& A);
-hipError_t launch_train_backward_mfma(const TrainArgs& A, hipStream_t stream);
+// bf16 path on MFMA (train_mfma.hip).
+bool train_mfma_supported(const TrainArgs& A, int D);
+hipError_t launch_train_backward_mfma(const TrainArgs& A, int D, hipStream_t stream);
 
 }  // namespace ltea

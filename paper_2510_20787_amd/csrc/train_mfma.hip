@@ -1,4 +1,4 @@
-// Training-side backward of the SWA+LTE attention on bf16 MFMA for gfx950, head dimension 64 (paper Section 3.1.2:
+// Training-side backward of the SWA+LTE attention on bf16 MFMA for gfx950, head dimensions 64 and 128 (paper Section 3.1.2:
 // the gradients that reach Q, K, V and, through the straight-through estimator, the retention scores).
 //
 // train_dq_mfma_kernel: one workgroup = 128 consecutive queries of one (sequence, query head), 4 waves x 32 queries,
@@ -18,22 +18,32 @@
 namespace ltea {
 namespace {
 
-constexpr int D = 64;
-constexpr int BN = 64;          // keys per tile
-constexpr int BM = 128;         // queries per workgroup
+constexpr int BN = 64;          // keys (or queries) per tile
+constexpr int BM = 128;         // queries (or keys) per workgroup
 constexpr int kThreads = 256;
-constexpr int KS = D + 8;       // padded row stride (elements) of tiles read row-wise
-constexpr int VS = D;           // unpadded, chunk-swizzled row stride of tiles read through the transposing load
-constexpr int PPR = D / 8;      // 16-byte pieces per row
-constexpr int RPP = kThreads / PPR;
-constexpr int KPASS = BN / RPP;
-constexpr int OS = D + 8;       // epilogue staging stride
+
+template <int D> struct Geo {
+  static constexpr int KS = D + 8;       // padded row stride (elements) of tiles read row-wise
+  static constexpr int VS = D;           // unpadded, chunk-swizzled row stride of tiles read through the transposing load
+  static constexpr int PPR = D / 8;      // 16-byte pieces per row
+  static constexpr int RPP = kThreads / PPR;
+  static constexpr int KPASS = BN / RPP;
+  static constexpr int OS = D + 8;       // epilogue staging stride
+  static constexpr int kBufDq = 2 * BN * KS + BN * VS;        // K rows | K for transposed reads | V rows
+  static constexpr int kBufDkv = 2 * BN * KS + 2 * BN * VS;   // Q rows | Q transposed | dO rows | dO transposed
+  static constexpr int kBuf = kBufDkv;
+};
+#define LTEA_GEO(D) \
+  using G_ = Geo<D>; \
+  constexpr int KS = G_::KS, VS = G_::VS, PPR = G_::PPR, RPP = G_::RPP, KPASS = G_::KPASS, OS = G_::OS
 
 // Row of a tile (within a block of 32) that MFMA row m must carry so that accumulator register r of lane half hb
 // holds row 16*(r/8) + 8*hb + r%8: swap bits 2 and 3 of m.
 __device__ __forceinline__ int tile_row_of_mfma_row(int m) { return (m & 0x13) | ((m & 0x08) >> 1) | ((m & 0x04) << 1); }
-// 64-byte chunk swizzle of the unpadded tiles (rows are 128 bytes: two chunks, alternating every second row).
-__device__ __forceinline__ int chunk_swizzle(int row) { return (row >> 1) & 1; }
+// 64-byte chunk swizzle of the unpadded tiles: four consecutive rows must land in four different 64-byte bank
+// groups; rows are 128 bytes (D = 64: two chunks, alternating every second row) or 256 bytes (D = 128: four chunks,
+// rotating every row).
+template <int D> __device__ __forceinline__ int chunk_swizzle(int row) { return D == 64 ? ((row >> 1) & 1) : (row & 3); }
 
 // A operand "transposed tile": eight consecutive tile rows of one column per lane, two transposing 64-bit LDS loads.
 __device__ __forceinline__ bf16x8 load_transposed(const bf16_t* p, int row_stride) {
@@ -65,17 +75,17 @@ __device__ __forceinline__ float pair_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-struct TileRegs {
-  u32x4 a[KPASS], b[KPASS];
+template <int D> struct TileRegs {
+  u32x4 a[Geo<D>::KPASS], b[Geo<D>::KPASS];
   int pos;
 };
 
-__device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int n_work, float scale_log2e, int block) {
-  constexpr int kK = 0, kKt = BN * KS, kV = BN * KS + BN * VS, kBuf = 2 * BN * KS + BN * VS;
-  static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
-  __shared__ __align__(16) bf16_t lds[kBuf];
-  __shared__ int pos_lds[BN];
-  __shared__ int pos_rng[2];
+template <int D>
+__device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int n_work, float scale_log2e, int block,
+                                        bf16_t* lds, int* pos_lds, int* pos_rng) {
+  LTEA_GEO(D);
+  constexpr int kK = 0, kKt = BN * KS, kV = BN * KS + BN * VS;
+  static_assert(G_::kBufDq >= BM * OS, "epilogue staging must fit in the tile buffer");
 
   const int per_xcd = (n_work + 7) / 8;
   const int work = (block % 8) * per_xcd + block / 8;
@@ -148,14 +158,14 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
   const uint32_t k_loc = (uint32_t)k_row * row_bytes + k_col;
   const uint32_t kr_loc = (uint32_t)k_row * (uint32_t)(D * 2) + k_col;
 
-  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t b0, uint32_t rb, TileRegs& R) {
+  auto load_rows = [&](const auto& rk, const auto& rv, uint32_t b0, uint32_t rb, TileRegs<D>& R) {
 #pragma unroll
     for (int p = 0; p < KPASS; ++p) {
       R.a[p] = __builtin_amdgcn_raw_buffer_load_b128(rk, b0 + (uint32_t)(p * RPP) * rb, 0, 0);
       R.b[p] = __builtin_amdgcn_raw_buffer_load_b128(rv, b0 + (uint32_t)(p * RPP) * rb, 0, 0);
     }
   };
-  auto load_tile = [&](int t, TileRegs& R) {
+  auto load_tile = [&](int t, TileRegs<D>& R) {
     if (t < n_win_tiles) {
       load_rows(rs_k, rs_v, (uint32_t)(jt0 + t * BN) * row_bytes + k_loc, row_bytes, R);
     } else {
@@ -167,8 +177,8 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
   };
   static_assert(RPP % 4 == 0, "row passes must preserve the swizzle phase");
   const int p_st_off = k_row * KS + k_piece * 8;
-  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle(k_row)) << 5) + (k_piece & 3) * 8;
-  auto store_tile = [&](int t, const TileRegs& R) {
+  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
+  auto store_tile = [&](int t, const TileRegs<D>& R) {
 #pragma unroll
     for (int p = 0; p < KPASS; ++p) {
       *reinterpret_cast<u32x4*>(lds + kK + p_st_off + p * RPP * KS) = R.a[p];
@@ -186,7 +196,7 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
   const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*kb*KS + 16*ks
   const int tr_key = 8 * hb + ((lane & 15) >> 2);
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const int tr_swz = chunk_swizzle(tr_key);
+  const int tr_swz = chunk_swizzle<D>(tr_key);
   const int a_tr_off = kKt + tr_key * VS + tr_col;
 
   f32x16 acc[D / 32];
@@ -249,7 +259,7 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
     }
   };
 
-  TileRegs regs;
+  TileRegs<D> regs;
   load_tile(0, regs);
   for (int t = 0; t < n_tiles; ++t) {
     __syncthreads();                 // everyone is done reading the previous tile
@@ -306,8 +316,8 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
 
 
 
-struct QTileRegs {
-  u32x4 a[KPASS], b[KPASS];
+template <int D> struct QTileRegs {
+  u32x4 a[Geo<D>::KPASS], b[Geo<D>::KPASS];
   float stat;     // threads 0..63: lse (base-2 domain) of a query of the tile, threads 64..127: its delta
 };
 
@@ -322,13 +332,12 @@ struct QTileRegs {
 // what the FAR pass left for keys that are candidates, rounds and stores dK, dV, and forms d logit and the counts.
 // FAR = true: the keys are 128 consecutive entries of the compacted candidates (positions ascending), seen by the
 // queries from position + window on; the fp32 sums go to a scratch array indexed like the compact segment.
-template <bool FAR>
+template <int D, bool FAR>
 __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, float scale_log2e, float* far_dk,
-                                         float* far_dv, int block) {
-  constexpr int kQ = 0, kQt = BN * KS, kO = BN * KS + BN * VS, kOt = 2 * BN * KS + BN * VS, kBuf = 2 * BN * KS + 2 * BN * VS;
-  static_assert(kBuf >= BM * OS, "epilogue staging must fit in the tile buffer");
-  __shared__ __align__(16) bf16_t lds[kBuf];
-  __shared__ __align__(16) float lse_lds[BN], dlt_lds[BN];
+                                         float* far_dv, int block, bf16_t* lds, float* lse_lds, float* dlt_lds) {
+  LTEA_GEO(D);
+  constexpr int kQ = 0, kQt = BN * KS, kO = BN * KS + BN * VS, kOt = 2 * BN * KS + BN * VS;
+  static_assert(G_::kBufDkv >= BM * OS, "epilogue staging must fit in the tile buffer");
 
   const int Hq = A.Hq, Hkv = A.Hkv, window = A.window, cap = A.budget;
   const int G = Hq / Hkv;
@@ -416,7 +425,7 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
   const uint32_t q_bytes = (uint32_t)(n - 1) * q_row_bytes + (uint32_t)(D * 2);
   const uint32_t o_bytes = (uint32_t)(n - 1) * o_row_bytes + (uint32_t)(D * 2);
   const int k_piece = tid % PPR, k_row = tid / PPR;
-  auto load_tile = [&](int it, QTileRegs& R) {
+  auto load_tile = [&](int it, QTileRegs<D>& R) {
     const int g = it / n_qt, t = it - g * n_qt;
     const int hq = h * G + g;
     const int qt = (qt_first + t) * BN;
@@ -437,8 +446,8 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
   };
   static_assert(RPP % 4 == 0, "row passes must preserve the swizzle phase");
   const int p_st_off = k_row * KS + k_piece * 8;
-  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle(k_row)) << 5) + (k_piece & 3) * 8;
-  auto store_tile = [&](const QTileRegs& R) {
+  const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
+  auto store_tile = [&](const QTileRegs<D>& R) {
 #pragma unroll
     for (int p = 0; p < KPASS; ++p) {
       *reinterpret_cast<u32x4*>(lds + kQ + p_st_off + p * RPP * KS) = R.a[p];
@@ -453,7 +462,7 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
   const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*qb*KS + 16*ks
   const int tr_row = 8 * hb + ((lane & 15) >> 2);
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-  const int tr_swz = chunk_swizzle(tr_row);
+  const int tr_swz = chunk_swizzle<D>(tr_row);
   const int a_tr_off = tr_row * VS + tr_col;
 
   f32x16 dva[D / 32], dka[D / 32];
@@ -506,7 +515,7 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
     }
   };
 
-  QTileRegs regs;
+  QTileRegs<D> regs;
   load_tile(0, regs);
   for (int it = 0; it < n_iter; ++it) {
     __syncthreads();
@@ -621,8 +630,10 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
 }
 
 // delta = <dO, O> per (query, query head), read by the dK / dV passes: eight lanes per 128-byte row.
+template <int D>
 __global__ void __launch_bounds__(kThreads)
 train_delta_mfma_kernel(TrainArgs A) {
+  constexpr int PPR = Geo<D>::PPR;
   const int64_t row = (int64_t)blockIdx.x * (kThreads / PPR) + threadIdx.x / PPR;
   const int piece = threadIdx.x % PPR;
   const int64_t rows = A.total * A.Hq;
@@ -643,23 +654,36 @@ train_delta_mfma_kernel(TrainArgs A) {
 // One launch, two independent roles: the first far_blocks workgroups run the far pass of dK / dV (few, long-running:
 // the candidates of early positions face almost every later query), the others compute dQ and fill the compute
 // units that the far pass leaves idle.
-__global__ void __launch_bounds__(kThreads, 2)
+// (D = 128 needs more than 256 registers per lane for the dK / dV role: one wave per SIMD there.)
+template <int D>
+__global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1)
 train_dq_far_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e, float* far_dk, float* far_dv,
                          int far_blocks) {
-  if ((int)blockIdx.x < far_blocks) dkv_body<true>(A, 0, scale_log2e, far_dk, far_dv, (int)blockIdx.x);
-  else dq_body(A, tiles_upper, n_work, scale_log2e, (int)blockIdx.x - far_blocks);
+  __shared__ __align__(16) bf16_t lds[Geo<D>::kBuf];      // the two roles lay their tiles out in the same buffer
+  __shared__ __align__(16) float stat_lds[2 * BN];
+  __shared__ int pos_rng[2];
+  if ((int)blockIdx.x < far_blocks)
+    dkv_body<D, true>(A, 0, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds, stat_lds + BN);
+  else
+    dq_body<D>(A, tiles_upper, n_work, scale_log2e, (int)blockIdx.x - far_blocks, lds, reinterpret_cast<int*>(stat_lds), pos_rng);
 }
 
-__global__ void __launch_bounds__(kThreads, 2)
+template <int D>
+__global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1)
 train_dkv_band_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* far_dk, float* far_dv) {
-  dkv_body<false>(A, tiles_upper, scale_log2e, far_dk, far_dv, (int)blockIdx.x);
+  __shared__ __align__(16) bf16_t lds[Geo<D>::kBufDkv];
+  __shared__ __align__(16) float stat_lds[2 * BN];
+  dkv_body<D, false>(A, tiles_upper, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds, stat_lds + BN);
 }
 
 }  // namespace
 
 // Rows are addressed with 32-bit byte offsets inside one sequence, and loaded in 16-byte pieces.
-bool train_mfma_supported(const TrainArgs& A) {
+bool train_mfma_supported(const TrainArgs& A, int D) {
+  if (D != 64 && D != 128) return false;
   if ((int64_t)A.max_seqlen * A.kv_st * 2 >= ((int64_t)1 << 31)) return false;
+  if ((int64_t)A.max_seqlen * A.q_st * 2 >= ((int64_t)1 << 31)) return false;
+  if ((int64_t)A.max_seqlen * A.Hq * D * 2 >= ((int64_t)1 << 31)) return false;
   if ((int64_t)A.budget * D * 2 >= ((int64_t)1 << 31)) return false;
   auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; };
   return al16(A.dout) && al16(A.dq) && al16(A.dk) && al16(A.dv) && al16(A.out);
@@ -667,10 +691,13 @@ bool train_mfma_supported(const TrainArgs& A) {
 
 // delta, then [far pass of dK / dV | dQ] in one launch, then the band pass of dK / dV (which adds the far pass in).
 // far_dk / far_dv: fp32 scratch, [kTrainFarChunks][n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
-hipError_t launch_train_backward_mfma(const TrainArgs& A, hipStream_t stream) {
+namespace {
+template <int D>
+hipError_t run_mfma(const TrainArgs& A, hipStream_t stream) {
+  constexpr int PPR = Geo<D>::PPR;
   const float sl2 = A.scale * 1.4426950408889634f;
   const int64_t rows = A.total * A.Hq;
-  hipLaunchKernelGGL(train_delta_mfma_kernel, dim3((unsigned)((rows + kThreads / PPR - 1) / (kThreads / PPR))),
+  hipLaunchKernelGGL(train_delta_mfma_kernel<D>, dim3((unsigned)((rows + kThreads / PPR - 1) / (kThreads / PPR))),
                      dim3(kThreads), 0, stream, A);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
@@ -680,13 +707,18 @@ hipError_t launch_train_backward_mfma(const TrainArgs& A, hipStream_t stream) {
   const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
   const int64_t n_work = tiles_upper * A.Hq;
   const int64_t dq_blocks = (n_work + 7) / 8 * 8;
-  hipLaunchKernelGGL(train_dq_far_mfma_kernel, dim3((unsigned)(far_blocks + dq_blocks)), dim3(kThreads), 0, stream, A,
+  hipLaunchKernelGGL(train_dq_far_mfma_kernel<D>, dim3((unsigned)(far_blocks + dq_blocks)), dim3(kThreads), 0, stream, A,
                      (int)tiles_upper, (int)n_work, sl2, A.far_dk, A.far_dv, (int)far_blocks);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(train_dkv_band_mfma_kernel, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
+  hipLaunchKernelGGL(train_dkv_band_mfma_kernel<D>, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
                      (int)tiles_upper, sl2, A.far_dk, A.far_dv);
   return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_train_backward_mfma(const TrainArgs& A, int D, hipStream_t stream) {
+  return D == 64 ? run_mfma<64>(A, stream) : run_mfma<128>(A, stream);
 }
 
 }  // namespace ltea
