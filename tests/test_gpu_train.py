@@ -27,6 +27,7 @@ CASES = {
     "bf16_d64_gqa": ("bf16", [300, 129, 40], 8, 2, 64, 48, 2, (5,), (32,), None, 0.2),
     "bf16_d128": ("bf16", [260, 77], 2, 2, 128, 64, 0, (7,), (32,), None, 0.2),
     "bf16_d128_gqa": ("bf16", [333, 140, 9], 4, 2, 128, 40, 1, (5,), (32,), None, 0.2),
+    "bf16_d64_edges": ("bf16", [0, 1, 50, 200, 0, 129], 4, 4, 64, 64, 3, (5,), (32,), None, 0.2),
     "bf16_d64_deep": ("bf16", [280, 150], 4, 2, 64, 64, 4, (3, 3, 3), (64, 32, 16), (2, 2, 2), 0.12),
 }
 
