@@ -29,6 +29,7 @@
 
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "mfma_tiles.h"
 
 namespace ltea {
 namespace {
@@ -36,48 +37,6 @@ namespace {
 constexpr int BN = 64;   // keys per tile
 constexpr int kThreads = 256;
 constexpr float kLazyMax = 8.0f;  // log2 units
-
-// Row of the K tile (within a block of 32) that MFMA row m must carry so that accumulator register r of
-// lane half hb holds key 16*(r/8) + 8*hb + r%8: swap bits 2 and 3 of m.
-__device__ __forceinline__ int key_row_of_mfma_row(int m) { return (m & 0x13) | ((m & 0x08) >> 1) | ((m & 0x04) << 1); }
-
-// Swizzle term of the V tile: which 64-byte chunk of its row a key row's chunk c is stored in (c ^ term).
-// Four consecutive rows must land in four different 64-byte bank groups: rows are 128 bytes (D = 64, two
-// chunks, alternate every second row) or 256 bytes (D = 128, four chunks, rotate every row).
-template <int D> __device__ __forceinline__ int v_swizzle(int row) { return D == 64 ? ((row >> 1) & 1) : (row & 3); }
-
-// A operand of O^T += V^T P^T for 8 consecutive keys: two transposing 64-bit LDS loads (keys +0..3, +4..7).
-__device__ __forceinline__ bf16x8 load_v_operand(const bf16_t* p, int row_stride) {
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
-  s16x8 r;
-  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
-  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
-  return __builtin_bit_cast(bf16x8, r);
-}
-
-// Both lane halves (l, l^32) receive max / sum of the pair.
-__device__ __forceinline__ float pair_max(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float pair_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-__device__ __forceinline__ int wave_min_i(int x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y < x ? y : x; }
-  return x;
-}
-__device__ __forceinline__ int wave_max_i(int x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y > x ? y : x; }
-  return x;
-}
 
 template <int D, int QB> struct Geo {
   static constexpr int BM = 128 * QB;           // queries per workgroup
@@ -203,7 +162,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   // spread over all banks.  Rows of one pass differ by multiples of RPP, which leaves the swizzle term unchanged.
   static_assert(G::RPP % 4 == 0, "row passes must preserve the swizzle phase");
   const int k_st_off = k_row * KS + k_piece * 8;
-  const int v_st_off = BN * KS + k_row * VS + (((k_piece >> 2) ^ v_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
+  const int v_st_off = BN * KS + k_row * VS + (((k_piece >> 2) ^ chunk_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
   auto store_tile = [&](int t, const TR& R) {
     bf16_t* buf = lds + (t & 1) * kBuf;
 #pragma unroll
@@ -220,12 +179,12 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   };
 
   // operand load offsets inside a tile buffer
-  const int a_k_off = key_row_of_mfma_row(ql) * KS + 8 * hb;                 // + 32*kb*KS + 16*ks
+  const int a_k_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;                 // + 32*kb*KS + 16*ks
   // V operand through the transposing LDS load: in each group of 16 lanes, lane j points at the four columns
   // d0 + 4*(j%4).. of key row kbase + j/4, and receives column d0 + j of the four keys kbase..kbase+3.
   const int tr_key = 8 * hb + ((lane & 15) >> 2);           // + 32*kb + 16*kk (+ 4 for the upper half)
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db, inside one 64-byte chunk
-  const int tr_swz = v_swizzle<D>(tr_key);                  // unchanged by adding multiples of 4 to the key
+  const int tr_swz = chunk_swizzle<D>(tr_key);                  // unchanged by adding multiples of 4 to the key
   const int a_v_off = BN * KS + tr_key * VS + tr_col;
 
   // ---- online softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
@@ -355,8 +314,8 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
         const bf16_t* ap = a_v + 32 * kb * VS + ((db ^ tr_swz) << 5);
-        const bf16x8 a0 = load_v_operand(ap, VS);
-        const bf16x8 a1 = load_v_operand(ap + 16 * VS, VS);
+        const bf16x8 a0 = load_transposed(ap, VS);
+        const bf16x8 a1 = load_transposed(ap + 16 * VS, VS);
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
           o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[qb][0], o[qb][db], 0, 0, 0);

@@ -1,18 +1,28 @@
-// Training-side backward of the SWA+LTE attention on bf16 MFMA for gfx950, head dimensions 64 and 128 (paper Section 3.1.2:
-// the gradients that reach Q, K, V and, through the straight-through estimator, the retention scores).
+// Training-side backward of the SWA+LTE attention on bf16 MFMA for gfx950, head dimensions 64 and 128 (paper
+// Section 3.1.2: the gradients that reach Q, K, V and, through the straight-through estimator, the retention scores).
 //
-// train_dq_mfma_kernel: one workgroup = 128 consecutive queries of one (sequence, query head), 4 waves x 32 queries,
-// walking the same key tiles as the forward kernel (64-key tiles of K/V inside the window range, then 64-slot tiles
-// of the compacted candidates with the per-row mask "position <= i - window").  Per 32-key block and wave
+// Three launches on the caller's stream:
+//   train_delta_mfma_kernel      delta = <dO, O> per (query, query head).
+//   train_dq_far_mfma_kernel     two independent roles in one grid: the far pass of dK / dV (first, few and
+//                                long-running workgroups) and dQ (fills the compute units the far pass leaves idle).
+//   train_dkv_band_mfma_kernel   the band pass of dK / dV, which adds the far pass in, stores dK, dV and forms
+//                                d logit and the retention counts.
+//
+// dQ role: one workgroup = 128 consecutive queries of one (sequence, query head), 4 waves x 32 queries, walking the
+// same key tiles as the forward kernel (64-key tiles of K/V inside the window range, then 64-slot tiles of the
+// compacted candidates with the per-row mask "position <= i - window").  Per 32-key block and wave
 // (v_mfma_f32_32x32x16_bf16, a lane owns one query column):
 //   S^T[key, query]  = K . Q^T        A = K tile rows from LDS, B = Q fragment in registers
 //   dP^T[key, query] = V . dO^T       A = V tile rows from LDS, B = dO fragment in registers
 //   P^T = exp2(S^T c - lse), dS^T = P^T (dP^T - delta)      per-lane scalars lse, delta (no running maximum)
 //   dQ^T[d, query]  += K^T . dS^T     A = K^T through the transposing LDS load, B = dS^T straight from registers
 // K is therefore staged twice per tile (padded rows for the row reads, swizzled unpadded rows for the transposing
-// reads), V once.  One tile buffer, next tile prefetched through registers, two barriers per tile.
+// reads), V once.  The dK / dV roles are the mirror image with a lane owning a key column (see dkv_body).
+// One tile buffer, next tile prefetched through registers, two barriers per tile.  No floating-point atomics: the
+// partial sums of the far pass go to scratch slices that the band pass adds in a fixed order.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "mfma_tiles.h"
 #include "train_common.h"
 
 namespace ltea {
@@ -36,44 +46,6 @@ template <int D> struct Geo {
 #define LTEA_GEO(D) \
   using G_ = Geo<D>; \
   constexpr int KS = G_::KS, VS = G_::VS, PPR = G_::PPR, RPP = G_::RPP, KPASS = G_::KPASS, OS = G_::OS
-
-// Row of a tile (within a block of 32) that MFMA row m must carry so that accumulator register r of lane half hb
-// holds row 16*(r/8) + 8*hb + r%8: swap bits 2 and 3 of m.
-__device__ __forceinline__ int tile_row_of_mfma_row(int m) { return (m & 0x13) | ((m & 0x08) >> 1) | ((m & 0x04) << 1); }
-// 64-byte chunk swizzle of the unpadded tiles: four consecutive rows must land in four different 64-byte bank
-// groups; rows are 128 bytes (D = 64: two chunks, alternating every second row) or 256 bytes (D = 128: four chunks,
-// rotating every row).
-template <int D> __device__ __forceinline__ int chunk_swizzle(int row) { return D == 64 ? ((row >> 1) & 1) : (row & 3); }
-
-// A operand "transposed tile": eight consecutive tile rows of one column per lane, two transposing 64-bit LDS loads.
-__device__ __forceinline__ bf16x8 load_transposed(const bf16_t* p, int row_stride) {
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  typedef short s16x8 __attribute__((ext_vector_type(8)));
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
-  s16x8 r;
-  r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
-  r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
-  return __builtin_bit_cast(bf16x8, r);
-}
-
-__device__ __forceinline__ int wave_min_i(int x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y < x ? y : x; }
-  return x;
-}
-__device__ __forceinline__ int wave_max_i(int x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) { const int y = __shfl_xor(x, off, kWave); x = y > x ? y : x; }
-  return x;
-}
-
-// Both lane halves (l, l^32) receive the sum of the pair.
-__device__ __forceinline__ float pair_sum(float x) {
-  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
 
 template <int D> struct TileRegs {
   u32x4 a[Geo<D>::KPASS], b[Geo<D>::KPASS];
