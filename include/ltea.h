@@ -250,15 +250,19 @@ int ltea_decode_step_lazy(const ltea_cfg *cfg, const void *q, const void *k, con
  * lifted and also returns the softmax normalisers; the state it leaves in `workspace` (the compacted candidates)
  * must reach ltea_train_backward unchanged.  The CNN's own backward (d logits -> d weights, d features) and its
  * dropout are not part of this library. */
+/* cnn may be NULL (logits supplied by the caller). */
 size_t ltea_train_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
                                   int32_t max_seqlen);
 
 /* out: contiguous [total_tokens][Hq][D]; lse: [Hq][total_tokens] fp32, natural log of sum_j exp(scale q_i.k_j) over
- * the keys query i sees; logits: [Hkv][total_tokens] fp32 (written).  Other arguments as ltea_prefill. */
+ * the keys query i sees; logits: [Hkv][total_tokens] fp32.  With `cnn` given the logits are computed and written
+ * (rho is ignored).  With cnn == NULL the logits are an INPUT: a framework that runs the scoring CNN under its own
+ * autograd passes its logits here (and rho, the CNN's look-ahead, which must satisfy window >= 2*rho + 1) and feeds
+ * the d logits of ltea_train_backward back into its graph.  Other arguments as ltea_prefill. */
 int ltea_train_forward(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
                        int64_t q_stride_head, const void *k, const void *v, int64_t kv_stride_tok,
                        int64_t kv_stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
-                       int32_t max_seqlen, void *out, float *lse, float *logits, void *workspace,
+                       int32_t max_seqlen, int32_t rho, void *out, float *lse, float *logits, void *workspace,
                        size_t workspace_bytes, void *stream);
 
 /* Gradients for d(loss)/d(out) = dout (contiguous [total_tokens][Hq][D], cfg->dtype):

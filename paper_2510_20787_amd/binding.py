@@ -110,8 +110,8 @@ def lib() -> C.CDLL:
     L.ltea_train_workspace_bytes.restype = sz
     L.ltea_train_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
     L.ltea_train_forward.restype = C.c_int
-    L.ltea_train_forward.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp, vp,
-                                     vp, vp, sz, vp]
+    L.ltea_train_forward.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, i32, vp,
+                                     vp, vp, vp, sz, vp]
     L.ltea_train_backward.restype = C.c_int
     L.ltea_train_backward.argtypes = [P(ltea_cfg), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp, vp, vp, vp, vp,
                                       vp, vp, vp, vp, vp, vp, sz, vp]
@@ -388,14 +388,17 @@ def ltea_decode_step_lazy(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: to
     return out
 
 
-def ltea_train_workspace_bytes(cfg: ltea_cfg, cnn: Cnn, n_seqs: int, total_tokens: int, max_seqlen: int) -> int:
-    return int(lib().ltea_train_workspace_bytes(C.byref(cfg), C.byref(cnn.struct), n_seqs, total_tokens, max_seqlen))
+def ltea_train_workspace_bytes(cfg: ltea_cfg, cnn: Optional[Cnn], n_seqs: int, total_tokens: int, max_seqlen: int) -> int:
+    return int(lib().ltea_train_workspace_bytes(C.byref(cfg), C.byref(cnn.struct) if cnn else None, n_seqs, total_tokens,
+                                                max_seqlen))
 
 
-def ltea_train_forward(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
-                       cu_seqlens: torch.Tensor, max_seqlen: int, workspace: Optional[torch.Tensor] = None):
+def ltea_train_forward(cfg: ltea_cfg, cnn: Optional[Cnn], q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
+                       cu_seqlens: torch.Tensor, max_seqlen: int, workspace: Optional[torch.Tensor] = None,
+                       logits: Optional[torch.Tensor] = None, rho: int = 0):
     """Training forward (no cap).  Returns (out, lse, logits, workspace); the workspace holds the state the
-    backward needs and must be passed to ltea_train_backward unchanged."""
+    backward needs and must be passed to ltea_train_backward unchanged.  With cnn=None the caller supplies the
+    logits ([Hkv, T] fp32) and the CNN's look-ahead rho."""
     T = q.shape[0]
     n_seqs = cu_seqlens.numel() - 1
     qst, qsh = _tok_head_strides(q)
@@ -403,11 +406,16 @@ def ltea_train_forward(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor
     assert _tok_head_strides(v) == (st, sh)
     out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
     lse = torch.empty((cfg.Hq, T), dtype=torch.float32, device=q.device)
-    logits = torch.empty((cfg.Hkv, T), dtype=torch.float32, device=q.device)
+    if cnn is not None:
+        logits = torch.empty((cfg.Hkv, T), dtype=torch.float32, device=q.device)
+        rho = cnn.rho
+    else:
+        assert logits is not None and logits.dtype == torch.float32 and logits.is_contiguous()
     if workspace is None:
         workspace = _workspace(ltea_train_workspace_bytes(cfg, cnn, n_seqs, T, max_seqlen), q.device)
-    _check(lib().ltea_train_forward(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
-                                    _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), _ptr(lse), _ptr(logits),
+    _check(lib().ltea_train_forward(C.byref(cfg), C.byref(cnn.struct) if cnn else None, _ptr(q), qst, qsh, _ptr(k), _ptr(v),
+                                    st, sh, _ptr(cu_seqlens), n_seqs, T, max_seqlen, int(rho), _ptr(out), _ptr(lse),
+                                    _ptr(logits),
                                     _ptr(workspace), workspace.numel(), _stream()), "ltea_train_forward")
     return out, lse, logits, workspace
 

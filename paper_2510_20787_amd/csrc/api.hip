@@ -394,21 +394,24 @@ int ltea_decode_step_lazy(const ltea_cfg* cfg, const void* q, const void* k, con
 
 size_t ltea_train_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs, int64_t total_tokens,
                                   int32_t max_seqlen) {
-  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0 || total_tokens < 0 || max_seqlen < 0)
+  if (check_cfg(cfg) != LTEA_OK || (cnn && check_cnn(cfg, cnn) != LTEA_OK) || n_seqs < 0 || total_tokens < 0 ||
+      max_seqlen < 0)
     return 0;
   return carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr) +
-         score_workspace(*cfg, *cnn, total_tokens);
+         (cnn ? score_workspace(*cfg, *cnn, total_tokens) : 0);
 }
 
 int ltea_train_forward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok,
                        int64_t q_stride_head, const void* k, const void* v, int64_t kv_stride_tok,
                        int64_t kv_stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
-                       int32_t max_seqlen, void* out, float* lse, float* logits, void* workspace,
+                       int32_t max_seqlen, int32_t rho, void* out, float* lse, float* logits, void* workspace,
                        size_t workspace_bytes, void* stream) {
   int st = check_cfg(cfg);
-  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK && cnn) st = check_cnn(cfg, cnn);
   if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
   if (st != LTEA_OK) return st;
+  if (cnn) rho = cnn_rho(cnn);
+  if (rho < 0 || cfg->window < 2 * rho + 1) return LTEA_EINVAL;
   if (n_seqs == 0) return LTEA_OK;
   const int esz = elem_size(cfg->dtype);
   if (total_tokens > 0) {
@@ -418,7 +421,7 @@ int ltea_train_forward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, 
     if (!out || !aligned16(out) || !lse || !logits) return LTEA_EINVAL;
   }
   const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
-  const size_t need = saved + score_workspace(*cfg, *cnn, total_tokens);
+  const size_t need = saved + (cnn ? score_workspace(*cfg, *cnn, total_tokens) : 0);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
   ltea_cache cache;
   carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, nullptr);
@@ -426,11 +429,11 @@ int ltea_train_forward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, 
   open.budget = max_seqlen;           // every candidate is kept: no cap during training
   hipStream_t s = static_cast<hipStream_t>(stream);
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
-  if (total_tokens > 0) {
+  if (cnn && total_tokens > 0) {
     st = do_score(*cfg, *cnn, k, v, kv_stride_tok, kv_stride_head, sv, logits, static_cast<char*>(workspace) + saved, s);
     if (st != LTEA_OK) return st;
   }
-  st = hip_status(launch_retain(open, logits, k, v, kv_stride_tok, kv_stride_head, sv, cnn_rho(cnn), cache, s));
+  st = hip_status(launch_retain(open, logits, k, v, kv_stride_tok, kv_stride_head, sv, rho, cache, s));
   if (st != LTEA_OK || total_tokens == 0) return st;
   return do_attention(open, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, cache, out, s, lse);
 }

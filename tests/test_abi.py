@@ -235,13 +235,15 @@ def test_train_argument_errors():
     assert need > 2 * 2 * cfg.Hkv * 32 * cfg.D * 2
     assert L.ltea_train_workspace_bytes(None, C.byref(cnn), 2, 64, 32) == 0
     fw = lambda **kw: L.ltea_train_forward(*[dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), q=0x1000, qst=256, qsh=64, k=0x1000,
-                                                       v=0x1000, st=128, sh=64, cu=0x1000, n=2, total=64, max_len=32,
+                                                       v=0x1000, st=128, sh=64, cu=0x1000, n=2, total=64, max_len=32, rho=0,
                                                        out=0x1000, lse=0x1000, logits=0x1000, ws=0x1000, ws_bytes=1 << 40,
                                                        stream=None), **kw)[k]
                                              for k in ("cfg", "cnn", "q", "qst", "qsh", "k", "v", "st", "sh", "cu", "n", "total",
-                                                       "max_len", "out", "lse", "logits", "ws", "ws_bytes", "stream")])
+                                                       "max_len", "rho", "out", "lse", "logits", "ws", "ws_bytes", "stream")])
     assert fw(cfg=None) == B.LTEA_EINVAL
-    assert fw(cnn=None) == B.LTEA_EINVAL
+    assert fw(cnn=None, rho=9) == B.LTEA_EINVAL         # caller's logits: the look-ahead must fit the window
+    assert fw(cnn=None, rho=-1) == B.LTEA_EINVAL
+    assert L.ltea_train_workspace_bytes(C.byref(cfg), None, 2, 64, 32) > 0
     assert fw(cu=None) == B.LTEA_EINVAL
     assert fw(lse=None) == B.LTEA_EINVAL
     assert fw(logits=None) == B.LTEA_EINVAL

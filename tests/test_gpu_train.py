@@ -96,3 +96,33 @@ def test_train_forward_equals_prefill_when_the_cap_does_not_bind():
     cache = d.new_cache()
     out_p = B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache)
     assert torch.equal(out_t, out_p)
+
+
+def test_train_with_logits_supplied_by_the_caller():
+    """cnn = NULL: the logits come from outside (here: random ones, unrelated to any CNN), so both sides take the
+    visibility decisions on identical numbers."""
+    dt, lens, Hq, Hkv, D, window, sink, ker, ch, dil, w_std = CASES["bf16_d64_gqa"]
+    w = wl.make_prefill("supplied", 11, dt, lens, Hq, Hkv, D, window, 1, sink, 0.0, cnn_kernel=ker, cnn_channels=ch,
+                        cnn_dilation=dil, qkv_scale=1.0, w_std=w_std)
+    cfg = oracle_cfg(w)
+    rng = np.random.default_rng(12)
+    z32 = rng.standard_normal((Hkv, w.total_tokens)).astype(np.float32) - np.float32(0.8)     # about a fifth kept
+    dout = wl.to_storage(rng.standard_normal((w.total_tokens, Hq, D), dtype=np.float32), dt)
+    lam = np.array([0.05, 0.0], dtype=np.float32)
+    d = DeviceWorkload(w)
+    zt = torch.from_numpy(z32).cuda()
+    out, lse, logits, ws = B.ltea_train_forward(d.cfg, None, d.q, d.k, d.v, d.cu, d.max_seqlen, logits=zt, rho=2)
+    assert logits.data_ptr() == zt.data_ptr()
+    dq, dk, dv, dz, counts = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, out, dev(dout, dt), lse, zt,
+                                                   torch.from_numpy(lam).cuda(), ws)
+    z64 = z32.astype(np.float64)
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        o_ref, _, _ = orc.train_forward_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi], cfg)
+        dq_ref, dk_ref, dv_ref, dz_ref, c_ref = orc.train_backward_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi],
+                                                                             dout[lo:hi], cfg, lam.astype(np.float64))
+        for got, ref, what in ((out[lo:hi], o_ref, "out"), (dq[lo:hi], dq_ref, "dq"), (dk[lo:hi], dk_ref, "dk"),
+                               (dv[lo:hi], dv_ref, "dv"), (dz[:, lo:hi], dz_ref, "dz")):
+            scale = float(np.max(np.abs(ref)))
+            assert max_err(to_np(got), ref) <= GRAD_TOL[dt] * scale, (s, what)
+        np.testing.assert_array_equal(counts[s].cpu().numpy(), c_ref)
