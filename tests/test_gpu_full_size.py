@@ -336,3 +336,53 @@ def test_full_train_paper_stack_bf16():
             zh = z64[h, lo:hi]
             unsure = int((np.abs(zh) <= 2 * eps).sum())
             assert abs(int(cnt_g[s, h]) - int((zh.astype(np.float32) > 0).sum())) <= unsure
+
+
+@pytest.mark.parametrize("lazy", [False, True])
+def test_full_paper_stack_decode(lazy):
+    """Decode at the paper's module shape (B=4, 32 query heads on 8 KV heads, window 768, 512 retained, 3-layer dilated
+    CNN) after the full-size prefill: 40 steps, eager (packed-window scoring) or lazy with one batched scoring in the
+    middle; one whole sequence through the oracle at every step (outputs of all 32 heads, retained sets of all 8)."""
+    w = wl.config_paper_stack_bf16()
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits)
+    z64 = orc.score(w.k, w.v, ocnn, w.cu_seqlens)
+    eps = float(np.max(np.abs(to_np(logits) - z64)))
+    near = check_sets(cache, z64, w, eps)
+    s = next(x for x in range(w.n_seqs) if all(ss != x for ss, _ in near))
+    lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+    rho = w.cnn.rho
+    kept = [orc.retain(z64[h, lo:hi], hi - lo, w.window, w.budget, w.sink, w.tau) for h in range(w.Hkv)]
+    st = orc.state_after_prefill(w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi], ocfg, rho, kept)
+    ws = B.decode_workspace(d.cfg, d.cnn, w.n_seqs)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    worst, scale = 0.0, 0.0
+    for step in range(40):
+        q, k, v = wl.decode_inputs(w.seed, step, w.dtype, w.n_seqs, w.Hq, w.Hkv, w.D)
+        if lazy:
+            if step == 20:
+                B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+            out = B.ltea_decode_step_lazy(d.cfg, dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), cache, status=status)
+        else:
+            out = B.ltea_decode_step(d.cfg, d.cnn, dev(q, "bf16"), dev(k, "bf16"), dev(v, "bf16"), cache, workspace=ws)
+        ref = orc.decode_step(st, q[s], k[s], v[s], ocfg, ocnn)
+        got = out[s].float().cpu().numpy()
+        worst = max(worst, float(np.abs(got - ref).max()))
+        scale = max(scale, float(np.abs(ref).max()))
+        if step % 10 == 9:
+            for h in range(w.Hkv):
+                cnt, pos = gpu_retained_sets(cache, s, h)
+                np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(st)[h], err_msg=f"step {step} head {h}")
+    assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale, (worst, scale)
+    if lazy:
+        B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+        assert int(status.item()) == 0
+    assert int(cache.n_seen[s]) == st.n_seen and int(cache.n_scored[s]) == st.n_scored
+    for h in range(w.Hkv):
+        for p, zp in st.heads[h].win_z.items():
+            if p >= hi - lo - rho:        # logits finalised during decoding
+                zg = float(cache.win_score[s, h, p % w.window])
+                assert abs(zg - zp) <= 5 * LOGIT_TOL["bf16"] * max(1.0, abs(zp)), (h, p, zg, zp)
