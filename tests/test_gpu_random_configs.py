@@ -1,0 +1,157 @@
+"""Seeded sweep over odd configurations: every entry point on shapes nobody would pick by hand (odd windows and
+budgets, group sizes 1..4, sinks, thresholds, stacks of 1..3 conv layers, empty and one-token sequences), each
+against the oracle on the same inputs.  Sizes are small; the point is the corners of the index arithmetic.
+
+Bars as in the other GPU tests.  Retained sets must match on every head whose decision margin exceeds twice the
+measured logit error; heads inside the margin are skipped (and counted), and so is everything downstream of them."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltea_oracle as orc
+from paper_2510_20787_amd import binding as B
+from paper_2510_20787_amd import workloads as wl
+from tests.gpu_util import LOGIT_TOL, OUT_TOL, DeviceWorkload, boundary_margin, dev, gpu_retained_sets, to_np
+from tests.helpers import oracle_cfg, oracle_cnn
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_config(seed):
+    rng = np.random.default_rng(90000 + seed)
+    dtype = "bf16" if rng.random() < 0.75 else "f32"
+    D = int(rng.choice([64, 128]))
+    Hkv = int(rng.integers(1, 4))
+    G = int(rng.choice([1, 2, 3, 4]))
+    n_layers = int(rng.integers(1, 4))
+    kernel = tuple(int(rng.choice([1, 3, 5, 7] if n_layers == 1 else [1, 3, 5])) for _ in range(n_layers))
+    dilation = tuple(int(rng.integers(1, 3)) for _ in range(n_layers))
+    widths = [int(rng.choice([8, 16, 32, 48, 64] if n_layers > 1 else [4, 8, 16, 24, 32])) for _ in range(n_layers)]
+    rho = sum(d * (k - 1) // 2 for k, d in zip(kernel, dilation))
+    # the per-step scoring of the eager decode keeps (2 rho + 1) rows of the widest layer twice in 48 KB of LDS
+    while 2 * (2 * rho + 1) * max(2 * D, max(widths)) * 4 > 48 * 1024:
+        dilation = tuple(1 for _ in dilation)
+        kernel = tuple(min(k, 3) for k in kernel)
+        rho = sum(d * (k - 1) // 2 for k, d in zip(kernel, dilation))
+    window = int(rng.integers(2 * rho + 1, 2 * rho + 90))
+    budget = int(rng.choice([0, 1, 2, 7, 16, 31, 40]))
+    sink = int(rng.integers(0, 5))
+    tau = float(rng.choice([0.0, 0.0, -np.inf, 0.02]))
+    n_seqs = int(rng.integers(1, 6))
+    lens = [int(x) for x in rng.integers(0, 330, size=n_seqs)]
+    if rng.random() < 0.5:
+        lens[int(rng.integers(0, n_seqs))] = int(rng.choice([0, 1, 2]))
+    if sum(lens) == 0:
+        lens[0] = 77
+    return dict(dtype=dtype, D=D, Hkv=Hkv, Hq=Hkv * G, kernel=kernel, dilation=dilation, widths=tuple(widths),
+                window=window, budget=budget, sink=sink, tau=tau, lens=lens)
+
+
+def head_margins(z64, w):
+    """Decision margin of every (sequence, head) at the final length."""
+    m = {}
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        for h in range(w.Hkv):
+            m[(s, h)] = boundary_margin(orc.selection_key(z64[h, lo:hi], w.sink), hi - lo, w.window, w.budget, w.sink, w.tau)
+    return m
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration(seed):
+    c = draw_config(seed)
+    w = wl.make_prefill(f"random{seed}", 90000 + seed, c["dtype"], c["lens"], c["Hq"], c["Hkv"], c["D"], c["window"],
+                        c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
+                        cnn_dilation=c["dilation"], qkv_scale=1.0, w_std=0.08)
+    print(f"[random {seed}] {c}", flush=True)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    dt = w.dtype
+    tol = OUT_TOL[dt]
+    d = DeviceWorkload(w)
+    G = w.Hq // w.Hkv
+
+    # ---- prefill -------------------------------------------------------------------------------------------
+    ref_out, states, z64, kept = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    cache = d.new_cache()
+    logits = torch.empty((w.Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    out = to_np(B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits))
+    zg = to_np(logits)
+    assert np.all(np.abs(zg - z64) <= 5 * LOGIT_TOL[dt] * np.maximum(1.0, np.abs(z64)))
+    eps = float(np.max(np.abs(zg - z64))) if z64.size else 0.0
+    margins = head_margins(z64, w)
+    unsure = {key for key, m in margins.items() if m <= 2 * eps}
+    scale = max(float(np.max(np.abs(ref_out))), 1e-30)
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        assert int(cache.n_seen[s]) == hi - lo and int(cache.n_scored[s]) == max(0, hi - lo - w.cnn.rho)
+        for h in range(w.Hkv):
+            if (s, h) in unsure:
+                continue
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            np.testing.assert_array_equal(pos, kept[s][h], err_msg=f"prefill seq {s} head {h}")
+            if hi > lo:
+                err = float(np.max(np.abs(out[lo:hi, h * G:(h + 1) * G] - ref_out[lo:hi, h * G:(h + 1) * G])))
+                assert err <= tol * max(1.0, scale) and err <= tol * scale, (s, h, err, scale)
+    assert len(unsure) <= 1, f"too many heads inside the decision margin: {unsure}"
+
+    # ---- decode: three eager steps, then lazy steps with a batched scoring in between -----------------------
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    n_lazy = min(period, 6)
+    for step in range(3 + n_lazy):
+        q, k, v = wl.decode_inputs(w.seed, step, dt, w.n_seqs, w.Hq, w.Hkv, w.D)
+        if step < 3:
+            got = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q, dt), dev(k, dt), dev(v, dt), cache))
+        else:
+            if step == 3 + n_lazy // 2:
+                B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+            got = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q, dt), dev(k, dt), dev(v, dt), cache, status=status))
+        ref = np.stack([orc.decode_step(states[s], q[s], k[s], v[s], cfg, cnn) for s in range(w.n_seqs)])
+        # a logit finalised during decoding may land inside the error of the threshold: such heads drop out
+        for s in range(w.n_seqs):
+            for h in range(w.Hkv):
+                for p, zp in states[s].heads[h].win_z.items():
+                    if abs(zp - w.tau) <= 2 * max(eps, 5 * LOGIT_TOL[dt]):
+                        unsure.add((s, h))
+        for s in range(w.n_seqs):
+            for h in range(w.Hkv):
+                if (s, h) in unsure:
+                    continue
+                cnt, pos = gpu_retained_sets(cache, s, h)
+                np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(states[s])[h],
+                                              err_msg=f"decode step {step} seq {s} head {h}")
+                err = float(np.max(np.abs(got[s, h * G:(h + 1) * G] - ref[s, h * G:(h + 1) * G])))
+                sc = float(np.max(np.abs(ref[s, h * G:(h + 1) * G])))
+                assert err <= tol and err <= tol * max(sc, 1e-30), (step, s, h, err, sc)
+    B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+    assert int(status.item()) == 0
+    for s in range(w.n_seqs):
+        assert int(cache.n_seen[s]) == states[s].n_seen and int(cache.n_scored[s]) == states[s].n_scored
+    assert len(unsure) <= 2, f"too many heads inside the decision margin: {unsure}"
+
+    # ---- training forward / backward on the same sequences (no cap) -----------------------------------------
+    if np.isfinite(w.tau) and z64.size and np.min(np.abs(z64 - w.tau)) > 2 * eps:
+        rng = np.random.default_rng(w.seed + 5)
+        dout = wl.to_storage(rng.standard_normal((w.total_tokens, w.Hq, w.D), dtype=np.float32), dt)
+        lam = np.abs(rng.standard_normal(w.Hkv)).astype(np.float32) * np.float32(0.1)
+        o_g, lse, lg, ws = B.ltea_train_forward(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen)
+        grads = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, o_g, dev(dout, dt), lse, lg,
+                                      torch.from_numpy(lam).cuda(), ws)
+        names = ("dq", "dk", "dv", "dz")
+        got = {n: to_np(x) for n, x in zip(names, grads[:4])}
+        refs = {"dq": np.zeros(got["dq"].shape), "dk": np.zeros(got["dk"].shape), "dv": np.zeros(got["dv"].shape),
+                "dz": np.zeros(got["dz"].shape)}
+        for s in range(w.n_seqs):
+            lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+            if hi == lo:
+                continue
+            r = orc.train_backward_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi], dout[lo:hi], cfg,
+                                            lam.astype(np.float64))
+            refs["dq"][lo:hi], refs["dk"][lo:hi], refs["dv"][lo:hi], refs["dz"][:, lo:hi] = r[0], r[1], r[2], r[3]
+            np.testing.assert_array_equal(grads[4][s].cpu().numpy(), r[4])
+        gtol = 2e-5 if dt == "f32" else 2e-2
+        for n in names:
+            sc = float(np.max(np.abs(refs[n])))
+            err = float(np.max(np.abs(got[n].astype(np.float64) - refs[n])))
+            # a reference that is exactly zero (one-token sequences: p = 1, dP = delta) is met up to rounding only
+            assert err <= gtol * (sc if sc > 1e-3 else 1.0), (n, err, sc)
