@@ -229,7 +229,10 @@ def decode_workspace(cfg: ltea_cfg, cnn: Optional["Cnn"], n_seqs: int, device="c
 
 
 def _tok_head_strides(x: torch.Tensor):
-    assert x.dim() == 3 and x.stride(2) == 1, "expected a [T, H, D] view with contiguous last dimension"
+    assert x.dim() == 3, "expected a [T, H, D] view"
+    if x.numel() == 0:                      # an empty view has no meaningful strides: report the packed ones
+        return x.shape[1] * x.shape[2], x.shape[2]
+    assert x.stride(2) == 1, "expected a [T, H, D] view with contiguous last dimension"
     return x.stride(0), x.stride(1)
 
 

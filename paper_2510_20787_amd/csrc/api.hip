@@ -296,7 +296,8 @@ int ltea_prefill_append(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q,
                                       *cache, workspace, &buf, s));
   if (st != LTEA_OK) return st;
   SeqView sv_ext{buf.cu_ext, n_seqs, buf.total_ext, buf.max_ext_len};
-  st = do_score(*cfg, *cnn, buf.ext_k, buf.ext_v, ext_stride_tok, cfg->D, sv_ext, buf.ext_logits,
+  SeqView sv_score{buf.cu_score, n_seqs, buf.total_ext, 2 * buf.max_ext_len};
+  st = do_score(*cfg, *cnn, buf.ext_k, buf.ext_v, ext_stride_tok, cfg->D, sv_score, buf.ext_logits,
                 static_cast<char*>(workspace) + build_ws, s);
   if (st != LTEA_OK) return st;
   st = hip_status(launch_append_keys(*cfg, n_seqs, total_new, *cache, rho, workspace, buf, s));

@@ -13,8 +13,8 @@
 // window, can be computed from either).  Then
 //   1. the scoring kernel runs over the extended sequence; logits of ring tokens that were already final are taken
 //      from the cache instead (their left context may be outside the ring), prefix entries get their stored keys,
-//      pad entries NaN (never candidates; their K/V rows are zero, which is also the correct left padding when the
-//      sequence started inside the ring);
+//      pad entries NaN (never candidates; their K/V rows are zero, and the scoring is told that a sequence which
+//      started inside the ring begins after them: cu_score);
 //   2. the retention kernel runs over the extended sequence (candidates, top-b, gather, ring fill) unchanged;
 //   3. kept positions are translated back from extended indices to true positions, counters are set;
 //   4. the attention kernel runs with the ring + new part of the extended sequence as keys and the new tokens as
@@ -31,6 +31,7 @@ struct AppendPlan {        // device arrays in the workspace, one entry per sequ
   int32_t* w_old;          // min(n_old, window): ring tokens
   int32_t* prefix;         // F
   int32_t* cu_ext;         // [n_seqs + 1] packing of the extended sequences
+  int32_t* cu_score;       // [n_seqs + 1] the same packing as the scoring kernels must see it (see the plan kernel)
   int32_t* kv_start;       // first row of the ring + new part in the extended buffers
   int32_t* kv_len;         // w_old + new tokens
   int32_t* sorted_pos;     // [n_seqs][Hkv][budget] old kept positions ascending
@@ -73,9 +74,14 @@ append_plan_kernel(AppendPlan P, const int32_t* __restrict__ cu_new, const int32
       const int start = before + inc - ext;
       P.n_old[s] = N; P.w_old[s] = wo; P.prefix[s] = F;
       P.cu_ext[s] = start;
+      // A sequence whose ring still begins at position 0 has only pad rows in its prefix.  For the scoring they
+      // must not exist at all (a conv stack pads with zeros at every layer, and a zero input row does not give a
+      // zero activation), so the scoring sees this sequence begin after its pad; the pad then trails the previous
+      // sequence, where it can only reach logits that are provisional anyway.
+      P.cu_score[s] = start + (N <= window ? F : 0);
       P.kv_start[s] = start + F;
       P.kv_len[s] = wo + M;
-      if (s == n_seqs - 1) P.cu_ext[n_seqs] = start + ext;
+      if (s == n_seqs - 1) { P.cu_ext[n_seqs] = start + ext; P.cu_score[n_seqs] = start + ext; }
     }
     __syncthreads();
     if (threadIdx.x == 255) carry = before + inc;
@@ -212,7 +218,7 @@ size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new) {
   const int64_t ext = append_ext_tokens(cfg, n_seqs, total_new);
   const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   size_t b = 0;
-  b += 6 * up256(sizeof(int32_t) * (size_t)(n_seqs + 1));                                 // per-sequence plan arrays
+  b += 7 * up256(sizeof(int32_t) * (size_t)(n_seqs + 1));                                 // per-sequence plan arrays
   b += 4 * up256(sizeof(int32_t) * (size_t)n_seqs * cfg.Hkv * (size_t)(cfg.budget > 0 ? cfg.budget : 1));  // sorted_pos, sorted_slot, local_pos, old counts
   b += 2 * up256((size_t)ext * cfg.Hkv * cfg.D * esz);                                      // extended K, V
   b += up256((size_t)ext * cfg.Hkv * sizeof(float));                                        // extended logits / keys
@@ -231,6 +237,7 @@ static size_t carve(const ltea_cfg& cfg, int n_seqs, int64_t total_new, char* ws
   P.w_old = reinterpret_cast<int32_t*>(take(per_seq));
   P.prefix = reinterpret_cast<int32_t*>(take(per_seq));
   P.cu_ext = reinterpret_cast<int32_t*>(take(per_seq));
+  P.cu_score = reinterpret_cast<int32_t*>(take(per_seq));
   P.kv_start = reinterpret_cast<int32_t*>(take(per_seq));
   P.kv_len = reinterpret_cast<int32_t*>(take(per_seq));
   const size_t per_entry = sizeof(int32_t) * (size_t)n_seqs * cfg.Hkv * (size_t)(cfg.budget > 0 ? cfg.budget : 1);
@@ -275,7 +282,7 @@ hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const voi
   hipLaunchKernelGGL(append_build_kernel, dim3(heads, chunks), dim3(256), 0, stream, P, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  out->ext_k = ext_k; out->ext_v = ext_v; out->ext_logits = ext_logits; out->cu_ext = P.cu_ext;
+  out->ext_k = ext_k; out->ext_v = ext_v; out->ext_logits = ext_logits; out->cu_ext = P.cu_ext; out->cu_score = P.cu_score;
   out->kv_start = P.kv_start; out->kv_len = P.kv_len; out->local_pos = P.local_pos;
   out->total_ext = append_ext_tokens(cfg, n_seqs, total_new);
   return hipSuccess;

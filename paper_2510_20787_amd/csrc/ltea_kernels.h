@@ -72,6 +72,8 @@ struct AppendBuffers {
   void* ext_k; void* ext_v;      // [total_ext][Hkv][D]
   float* ext_logits;             // [Hkv][total_ext]
   const int32_t* cu_ext;         // [n_seqs + 1]
+  const int32_t* cu_score;       // [n_seqs + 1] packing handed to the scoring kernels (pad rows of sequences whose
+                                 // ring begins at position 0 are left out of them)
   const int32_t* kv_start;       // first ring row of each sequence in the extended buffers
   const int32_t* kv_len;         // ring + new tokens of each sequence
   int32_t* local_pos;            // kept positions in the ring + new frame, [n_seqs][Hkv][budget]

@@ -195,3 +195,38 @@ def test_append_many_sequences():
                 worst = max(worst, float(np.abs(out[off: off + m[s], hq] - ref_out[rows, hq]).max()))
         off += m[s]
     assert worst <= OUT_TOL["bf16"], worst
+
+
+@pytest.mark.parametrize("n_first", [0, 1, 5, 11])
+def test_append_to_a_history_shorter_than_the_receptive_field(n_first):
+    """Multi-layer CNN and a first chunk of at most 2 rho tokens (or none at all): the continuation must score the
+    positions next to the sequence start with real zero padding at every layer, not with the activations of zero
+    input rows standing in front of the ring."""
+    lens = [150, 90]
+    w = wl.make_prefill("append_short_history", 7100 + n_first, "bf16", lens, 4, 2, 64, 64, 12, 2, 0.0,
+                        cnn_kernel=(3, 3, 3), cnn_channels=(64, 32, 16), cnn_dilation=(2, 2, 2), qkv_scale=1.0, w_std=0.05)
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, ocfg, ocnn, w.cu_seqlens)
+    cfg, cnn = device_setup(w)
+    cu = w.cu_seqlens
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    a = [n_first, min(n_first, 3)]
+    zero = [0, 0]
+    if n_first > 0:
+        q, k, v = (dev(pack(x, cu, zero, a), w.dtype) for x in (w.q, w.k, w.v))
+        B.ltea_prefill(cfg, cnn, q, k, v, torch.from_numpy(cu_of(a)).cuda(), max(a), cache)
+    else:
+        a = zero
+    m = [lens[s] - a[s] for s in range(w.n_seqs)]
+    q, k, v = (dev(pack(x, cu, a, lens), w.dtype) for x in (w.q, w.k, w.v))
+    out = to_np(B.ltea_prefill_append(cfg, cnn, q, k, v, torch.from_numpy(cu_of(m)).cuda(), max(m), cache))
+    skip = check_final_state(w, cache, ref_states, z64, 1e-5)
+    G = w.Hq // w.Hkv
+    off = 0
+    for s in range(w.n_seqs):
+        rows = slice(int(cu[s]) + a[s], int(cu[s]) + lens[s])
+        for hq in range(w.Hq):
+            if (s, hq // G) not in skip:
+                err = float(np.abs(out[off: off + m[s], hq] - ref_out[rows, hq]).max())
+                assert err <= OUT_TOL["bf16"] * float(np.abs(ref_out[rows, hq]).max()), (s, hq, err)
+        off += m[s]

@@ -155,3 +155,57 @@ def test_random_configuration(seed):
             err = float(np.max(np.abs(got[n].astype(np.float64) - refs[n])))
             # a reference that is exactly zero (one-token sequences: p = 1, dP = delta) is met up to rounding only
             assert err <= gtol * (sc if sc > 1e-3 else 1.0), (n, err, sc)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_append(seed):
+    """The same kind of configurations through ltea_prefill + ltea_prefill_append with random cut points (bf16; the
+    continuation's scoring tolerance is the prefill's): final state and last-chunk rows equal the one-shot oracle."""
+    from tests.test_gpu_append import check_final_state, cu_of, pack
+    c = draw_config(1000 + seed)
+    lens = [x + 40 for x in c["lens"]]
+    w = wl.make_prefill(f"random_append{seed}", 91000 + seed, "bf16", lens, c["Hq"], c["Hkv"], c["D"], c["window"],
+                        c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
+                        cnn_dilation=c["dilation"], qkv_scale=1.0, w_std=0.05)
+    print(f"[random append {seed}] {c}", flush=True)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    d = DeviceWorkload(w)
+    rng = np.random.default_rng(92000 + seed)
+    cu = w.cu_seqlens
+    n_cuts = int(rng.integers(1, 4))
+    cuts = [[0] * w.n_seqs]
+    for _ in range(n_cuts):
+        cuts.append([int(rng.integers(cuts[-1][s], lens[s] + 1)) for s in range(w.n_seqs)])
+    cuts.append(lens)
+    cache = d.new_cache()
+    last = np.zeros_like(ref_out, dtype=np.float32)
+    for ci in range(len(cuts) - 1):
+        a, b = cuts[ci], cuts[ci + 1]
+        m = [b[s] - a[s] for s in range(w.n_seqs)]
+        q, k, v = (dev(pack(x, cu, a, b), "bf16") for x in (w.q, w.k, w.v))
+        cu_c = torch.from_numpy(cu_of(m)).cuda()
+        if ci == 0:
+            out = B.ltea_prefill(d.cfg, d.cnn, q, k, v, cu_c, max(max(m), 1), cache)
+        else:
+            out = B.ltea_prefill_append(d.cfg, d.cnn, q, k, v, cu_c, max(max(m), 1), cache)
+        o = to_np(out)
+        off = 0
+        for s in range(w.n_seqs):
+            last[int(cu[s]) + a[s]: int(cu[s]) + b[s]] = o[off: off + m[s]]
+            off += m[s]
+    torch.cuda.synchronize()
+    zmax = float(np.max(np.abs(z64))) if z64.size else 1.0
+    skip = check_final_state(w, cache, ref_states, z64, 5 * LOGIT_TOL["bf16"] * max(1.0, zmax))
+    G = w.Hq // w.Hkv
+    a = cuts[-2]
+    for s in range(w.n_seqs):
+        if a[s] == lens[s] or len(cuts) == 2:
+            continue
+        rows = slice(int(cu[s]) + a[s], int(cu[s]) + lens[s])
+        for hq in range(w.Hq):
+            if (s, hq // G) in skip:
+                continue
+            sc = float(np.max(np.abs(ref_out[rows, hq])))
+            err = float(np.max(np.abs(last[rows, hq] - ref_out[rows, hq])))
+            assert err <= OUT_TOL["bf16"] and err <= OUT_TOL["bf16"] * sc, (s, hq, err, sc)
