@@ -209,3 +209,92 @@ def test_random_append(seed):
             sc = float(np.max(np.abs(ref_out[rows, hq])))
             err = float(np.max(np.abs(last[rows, hq] - ref_out[rows, hq])))
             assert err <= OUT_TOL["bf16"] and err <= OUT_TOL["bf16"] * sc, (s, hq, err, sc)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_decode_mix(seed):
+    """Token-by-token decoding from an empty cache with small windows (rings wrap, compact segments overflow),
+    switching at random between eager steps and lazy steps (a batched scoring whenever one is due or at random),
+    then a continuation chunk (bf16) on top of the decoded state.  Reference: the oracle's per-step decode, and
+    the oracle's one-shot prefill for the state after the continuation."""
+    from tests.test_gpu_append import check_final_state, cu_of
+    c = draw_config(2000 + seed)
+    rng = np.random.default_rng(93000 + seed)
+    rho = sum(dd * (kk - 1) // 2 for kk, dd in zip(c["kernel"], c["dilation"]))
+    window = int(rng.integers(2 * rho + 1, 2 * rho + 30))
+    n_dec, n_app, B_ = 110, int(rng.integers(1, 60)), int(rng.integers(1, 4))
+    n = n_dec + n_app
+    w = wl.make_prefill(f"random_mix{seed}", 93000 + seed, c["dtype"], [n] * B_, c["Hq"], c["Hkv"], c["D"], window,
+                        c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
+                        cnn_dilation=c["dilation"], qkv_scale=1.0, w_std=0.08)
+    print(f"[random mix {seed}] window {window} {c}", flush=True)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    dt = w.dtype
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    states = [orc.empty_state(cfg) for _ in range(B_)]
+    q3 = w.q.reshape(B_, n, w.Hq, w.D); k3 = w.k.reshape(B_, n, w.Hkv, w.D); v3 = w.v.reshape(B_, n, w.Hkv, w.D)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    since, lazy_mode = 0, False
+    G = w.Hq // w.Hkv
+    unsure = set()
+    tol = OUT_TOL[dt]
+    # decision margins of every prefix from the oracle's final logits: a head drops out of the comparison once two
+    # keys competing for the last slot (or a logit and the threshold) are closer than the scoring error
+    z_all = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    z_eps = 1e-6                          # running maximum of the measured logit error (ring logits against the oracle's)
+    for t in range(n_dec):
+        want_lazy = rng.random() < 0.6
+        if lazy_mode and (not want_lazy or since >= period or rng.random() < 0.1):
+            B.ltea_rescore(d.cfg, d.cnn, cache, status=status)      # also restores the eager step's invariant
+            since = 0
+        lazy_mode = want_lazy
+        args = (dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache)
+        if lazy_mode:
+            got = to_np(B.ltea_decode_step_lazy(d.cfg, *args, status=status))
+            since += 1
+        else:
+            got = to_np(B.ltea_decode_step(d.cfg, d.cnn, *args))
+            since = 0
+        ref = np.stack([orc.decode_step(states[s], q3[s, t], k3[s, t], v3[s, t], cfg, cnn) for s in range(B_)])
+        if not lazy_mode:
+            zw = cache.win_score.cpu().numpy()
+            for s in range(B_):
+                for h in range(w.Hkv):
+                    for p, zp in states[s].heads[h].win_z.items():
+                        z_eps = max(z_eps, abs(float(zw[s, h, p % window]) - zp))
+            assert z_eps <= 5 * LOGIT_TOL[dt] * max(1.0, float(np.max(np.abs(z_all))))
+        for s in range(B_):
+            for h in range(w.Hkv):
+                if (s, h) not in unsure:
+                    key = orc.selection_key(z_all[h, s * n:s * n + t + 1], w.sink)
+                    if boundary_margin(key, t + 1, window, w.budget, w.sink, w.tau) <= 2 * z_eps:
+                        unsure.add((s, h))
+                if (s, h) in unsure:
+                    continue
+                cnt, pos = gpu_retained_sets(cache, s, h)
+                np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(states[s])[h], err_msg=f"t {t} seq {s} head {h}")
+                err = float(np.max(np.abs(got[s, h * G:(h + 1) * G] - ref[s, h * G:(h + 1) * G])))
+                sc = float(np.max(np.abs(ref[s, h * G:(h + 1) * G])))
+                assert err <= tol and err <= tol * max(sc, 1e-30), (t, s, h, err, sc)
+    if lazy_mode:
+        B.ltea_rescore(d.cfg, d.cnn, cache, status=status)
+    assert int(status.item()) == 0
+    assert len(unsure) <= max(2, B_ * w.Hkv // 2), unsure
+    if dt != "bf16" or unsure:
+        return
+    # ---- continuation on top of the decoded state --------------------------------------------------------
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    idx = np.concatenate([np.arange(s * n + n_dec, (s + 1) * n) for s in range(B_)])
+    out = to_np(B.ltea_prefill_append(d.cfg, d.cnn, dev(w.q[idx], dt), dev(w.k[idx], dt), dev(w.v[idx], dt),
+                                      torch.from_numpy(cu_of([n_app] * B_)).cuda(), n_app, cache))
+    zmax = float(np.max(np.abs(z64)))
+    skip = check_final_state(w, cache, ref_states, z64, 5 * LOGIT_TOL["bf16"] * max(1.0, zmax))
+    for s in range(B_):
+        for hq in range(w.Hq):
+            if (s, hq // G) in skip:
+                continue
+            ref = ref_out[s * n + n_dec:(s + 1) * n, hq]
+            err = float(np.max(np.abs(out[s * n_app:(s + 1) * n_app, hq] - ref)))
+            assert err <= tol * float(np.max(np.abs(ref))), (s, hq, err)
