@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the SWA+LTE hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-decode] [--no-train]
 
 One "step" = one pass of the whole hot path over the prefill_bf16 workload (B=4 sequences x 4096 tokens,
 H=16, D=64, window 512, budget 256, CNN width 5 / 32 channels): ltea_prefill (scoring CNN -> capped
@@ -17,7 +17,10 @@ Also reported on the same JSON line:
                 repeat of the same steps (entry points called one by one).
   decode        the decode_bf16 workload (B=64, H=16, D=128, window 1024 + 512 retained, n_seen 8192):
                 256 consecutive steps timed as a whole; us/step, us/token, and the streaming attention
-                kernel's achieved HBM bandwidth.
+                kernel's achieved HBM bandwidth; `lazy`: the same steps without per-step scoring plus one
+                batched scoring per ltea_lazy_period() steps.
+  train         training-side forward + backward (no cap) on the paper's module shape, every head keeping
+                budget/N of its tokens; ms per pass and the backward kernels against the bf16 MFMA peak.
   cpu_baseline  the fp64 NumPy oracle timed on this machine's host cores on a bounded sample.
 """
 from __future__ import annotations
@@ -434,7 +437,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
-    ap.add_argument("--train", action="store_true", help="also time the training-side forward + backward")
+    ap.add_argument("--train", action="store_true", help="(default) also time the training-side forward + backward")
+    ap.add_argument("--no-train", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -445,7 +449,7 @@ def main():
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
     args = ap.parse_args()
     if args.workload != "prefill":
-        args.no_decode = args.no_cpu_baseline = True
+        args.no_decode = args.no_cpu_baseline = args.no_train = True
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (every (sequence, KV head) is independent, so the path "
                  "shards over batch x heads without any exchange; no multi-GPU run is implemented). Run with --gpus 1.")
@@ -487,7 +491,7 @@ def main():
             f"{dec['lazy']['rescore_us']:.0f} us per {dec['lazy']['period']} steps")
         add_measured_fraction(dec.get("roofline"), ceilings)
         line["decode"] = dec
-    if args.train:
+    if not args.no_train:
         line["train"] = bench_train(args)
         log(f"[bench] train forward {line['train']['forward_ms']:.3f} ms, backward {line['train']['backward_ms']:.3f} ms")
     if args.chunks > 1:

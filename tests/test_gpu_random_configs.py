@@ -17,7 +17,8 @@ from tests.helpers import oracle_cfg, oracle_cnn
 pytestmark = pytest.mark.gpu
 
 
-def draw_config(seed):
+def draw_config(seed, scale=1):
+    """scale multiplies the window range, the budgets and the sequence lengths (1 in the committed tests)."""
     rng = np.random.default_rng(90000 + seed)
     dtype = "bf16" if rng.random() < 0.75 else "f32"
     D = int(rng.choice([64, 128]))
@@ -33,12 +34,12 @@ def draw_config(seed):
         dilation = tuple(1 for _ in dilation)
         kernel = tuple(min(k, 3) for k in kernel)
         rho = sum(d * (k - 1) // 2 for k, d in zip(kernel, dilation))
-    window = int(rng.integers(2 * rho + 1, 2 * rho + 90))
-    budget = int(rng.choice([0, 1, 2, 7, 16, 31, 40]))
+    window = int(rng.integers(2 * rho + 1, 2 * rho + 90 * scale))
+    budget = int(rng.choice([0, 1, 2, 7, 16, 31, 40])) * scale
     sink = int(rng.integers(0, 5))
     tau = float(rng.choice([0.0, 0.0, -np.inf, 0.02]))
     n_seqs = int(rng.integers(1, 6))
-    lens = [int(x) for x in rng.integers(0, 330, size=n_seqs)]
+    lens = [int(x) for x in rng.integers(0, 330 * scale, size=n_seqs)]
     if rng.random() < 0.5:
         lens[int(rng.integers(0, n_seqs))] = int(rng.choice([0, 1, 2]))
     if sum(lens) == 0:
@@ -58,8 +59,8 @@ def head_margins(z64, w):
 
 
 @pytest.mark.parametrize("seed", range(24))
-def test_random_configuration(seed):
-    c = draw_config(seed)
+def test_random_configuration(seed, scale=1):
+    c = draw_config(seed, scale)
     w = wl.make_prefill(f"random{seed}", 90000 + seed, c["dtype"], c["lens"], c["Hq"], c["Hkv"], c["D"], c["window"],
                         c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
                         cnn_dilation=c["dilation"], qkv_scale=1.0, w_std=0.08)
@@ -158,11 +159,11 @@ def test_random_configuration(seed):
 
 
 @pytest.mark.parametrize("seed", range(12))
-def test_random_append(seed):
+def test_random_append(seed, scale=1):
     """The same kind of configurations through ltea_prefill + ltea_prefill_append with random cut points (bf16; the
     continuation's scoring tolerance is the prefill's): final state and last-chunk rows equal the one-shot oracle."""
     from tests.test_gpu_append import check_final_state, cu_of, pack
-    c = draw_config(1000 + seed)
+    c = draw_config(1000 + seed, scale)
     lens = [x + 40 for x in c["lens"]]
     w = wl.make_prefill(f"random_append{seed}", 91000 + seed, "bf16", lens, c["Hq"], c["Hkv"], c["D"], c["window"],
                         c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
