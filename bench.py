@@ -221,6 +221,34 @@ def bench_decode(args):
     cnt = cache.ret_count.cpu().numpy().astype(np.int64)
     bytes_per_step = int(((st.window + cnt) * 2 * st.D * 2).sum())
     gbs = bytes_per_step / (us_per_step * 1e-6) / 1e9
+    # the same eager steps recorded once into a HIP graph (16 steps per graph) and replayed: what a caller that
+    # captures its decode loop sees (the entry points only enqueue kernels, so they can be captured as they are)
+    def graph_us(enqueue_step):
+        per_graph = 16
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            enqueue_step(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(per_graph):
+                enqueue_step(i)
+        g.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n_steps // per_graph):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n_steps
+
+    def eager_step(i):
+        q, k, v = steps_in[i]
+        B.ltea_decode_step(cfg, cnn, q, k, v, cache, out=out, workspace=ws)
+
+    graph_eager_us = graph_us(eager_step)
     # lazy scoring: the same steps without per-step scoring + one batched scoring per ltea_lazy_period() steps
     period = B.ltea_lazy_period(cfg, cnn)
     rws = torch.empty(B.ltea_rescore_workspace_bytes(cfg, cnn, st.B), dtype=torch.uint8, device="cuda")
@@ -250,11 +278,21 @@ def bench_decode(args):
         torch.cuda.synchronize()
         rescore_ms += e0.elapsed_time(e1) / reps
     assert int(status.item()) == 0, "lazy decode reported late scoring"
-    lazy = dict(us_per_step=lazy_us, rescore_us=rescore_ms * 1e3, period=period,
+    def lazy_step(i):
+        q, k, v = steps_in[i]
+        B.ltea_decode_step_lazy(cfg, q, k, v, cache, out=out, status=status, workspace=lws)
+
+    graph_lazy_us = graph_us(lazy_step)
+    B.ltea_rescore(cfg, cnn, cache, status=status, workspace=rws)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0, "lazy decode reported late scoring"
+    lazy = dict(us_per_step=lazy_us, graph_us_per_step=graph_lazy_us, rescore_us=rescore_ms * 1e3, period=period,
                 amortised_us_per_step=lazy_us + rescore_ms * 1e3 / period,
                 frac_of_hbm_peak=bytes_per_step / ((lazy_us + rescore_ms * 1e3 / period) * 1e-6) / 1e9 / PEAK_HBM_GBS)
     return dict(workload="decode_bf16: B=64 H=16 D=128 window=1024 retained=512 n_seen=8192, 256 steps, cnn k5 c32",
                 us_per_step=us_per_step, us_per_token=us_per_step / st.B, wall_us_per_step=wall_us,
+                graph_us_per_step=graph_eager_us,
+                graph_frac_of_hbm_peak=bytes_per_step / (graph_eager_us * 1e-6) / 1e9 / PEAK_HBM_GBS,
                 algorithmic_bytes_per_step=bytes_per_step, lazy=lazy,
                 roofline=dict(bound="hbm", kernel="decode step (all launches)", achieved=gbs, peak=PEAK_HBM_GBS,
                               unit="GB/s", frac=gbs / PEAK_HBM_GBS,
@@ -487,7 +525,7 @@ def main():
     add_measured_fraction(line["scoring_roofline"], ceilings)
     if not args.no_decode:
         dec = bench_decode(args)
-        log(f"[bench] decode {dec['us_per_step']:.1f} us/step; lazy {dec['lazy']['us_per_step']:.1f} us/step + "
+        log(f"[bench] decode {dec['us_per_step']:.1f} us/step ({dec['graph_us_per_step']:.1f} replayed from a graph); lazy {dec['lazy']['us_per_step']:.1f} us/step + "
             f"{dec['lazy']['rescore_us']:.0f} us per {dec['lazy']['period']} steps")
         add_measured_fraction(dec.get("roofline"), ceilings)
         line["decode"] = dec
