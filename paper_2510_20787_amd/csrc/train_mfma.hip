@@ -319,12 +319,17 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
     // one workgroup per (128 compact entries, share of the query range): kTrainFarChunks shares of equal length keep
     // the workgroups short and alike; their partial sums go to one scratch slice each, which the band pass adds up
     // in a fixed order
+    // The workgroups of one (head, share) read the same Q and dO tiles: order them so that they are neighbours, and
+    // give each XCD a contiguous range of that order (workgroups are dealt round-robin to the 8 XCDs).
     const int per_head = (A.max_seqlen + BM - 1) / BM;
-    chunk = block % kTrainFarChunks;
-    const int rest = block / kTrainFarChunks;
-    const int hd = rest / per_head;
-    if (hd >= A.n_seqs * Hkv) return;     // padding workgroups of the combined launch
-    r_base = (rest - hd * per_head) * BM;
+    const int n_far = A.n_seqs * Hkv * kTrainFarChunks * per_head;
+    const int per_xcd = (n_far + 7) / 8;
+    const int work = (block % 8) * per_xcd + block / 8;
+    if (work >= n_far) return;            // padding workgroups of the combined launch
+    const int rest = work / per_head;
+    chunk = rest % kTrainFarChunks;
+    const int hd = rest / kTrainFarChunks;
+    r_base = (work - rest * per_head) * BM;
     s = hd / Hkv;
     h = hd - s * Hkv;
     cnt = A.ret_count[hd];
@@ -332,9 +337,15 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
     lo = A.cu[s];
     n = A.cu[s + 1] - lo;
   } else {
-    h = block / tiles_upper;
+    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of key tiles so that
+    // neighbouring tiles of one head (which walk mostly the same Q and dO tiles) meet in the same L2.
+    const int n_work = tiles_upper * Hkv;
+    const int per_xcd = (n_work + 7) / 8;
+    const int work = (block % 8) * per_xcd + block / 8;
+    if (work >= n_work) return;
+    h = work / tiles_upper;
     int tile;
-    if (!locate_tile(A.cu, A.n_seqs, BM, block - h * tiles_upper, s, tile, lo, n)) return;
+    if (!locate_tile(A.cu, A.n_seqs, BM, work - h * tiles_upper, s, tile, lo, n)) return;
     j0 = tile * BM;
   }
   const int64_t head = (int64_t)s * Hkv + h;
@@ -683,7 +694,7 @@ hipError_t run_mfma(const TrainArgs& A, hipStream_t stream) {
                      (int)tiles_upper, (int)n_work, sl2, A.far_dk, A.far_dv, (int)far_blocks);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(train_dkv_band_mfma_kernel<D>, dim3((unsigned)(tiles_upper * A.Hkv)), dim3(kThreads), 0, stream, A,
+  hipLaunchKernelGGL(train_dkv_band_mfma_kernel<D>, dim3((unsigned)((tiles_upper * A.Hkv + 7) / 8 * 8)), dim3(kThreads), 0, stream, A,
                      (int)tiles_upper, sl2, A.far_dk, A.far_dv);
   return hipGetLastError();
 }
