@@ -18,7 +18,7 @@
 //   dQ^T[d, query]  += K^T . dS^T     A = K^T through the transposing LDS load, B = dS^T straight from registers
 // K is therefore staged twice per tile (padded rows for the row reads, swizzled unpadded rows for the transposing
 // reads), V once.  The dK / dV roles are the mirror image with a lane owning a key column (see dkv_body).
-// One tile buffer, next tile prefetched through registers, two barriers per tile.  No floating-point atomics: the
+// Two tile buffers and a register prefetch: one barrier per tile.  No floating-point atomics: the
 // partial sums of the far pass go to scratch slices that the band pass adds in a fixed order.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
@@ -54,7 +54,7 @@ template <int D> struct TileRegs {
 
 template <int D>
 __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int n_work, float scale_log2e, int block,
-                                        bf16_t* lds, int* pos_lds, int* pos_rng) {
+                                        bf16_t* lds, int* pos_lds_base, int* pos_rng_base) {
   LTEA_GEO(D);
   constexpr int kK = 0, kKt = BN * KS, kV = BN * KS + BN * VS;
   static_assert(G_::kBufDq >= BM * OS, "epilogue staging must fit in the tile buffer");
@@ -151,19 +151,22 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
   const int p_st_off = k_row * KS + k_piece * 8;
   const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
   auto store_tile = [&](int t, const TileRegs<D>& R) {
+    bf16_t* sb = lds + (t & 1) * G_::kBufDq;
 #pragma unroll
     for (int p = 0; p < KPASS; ++p) {
-      *reinterpret_cast<u32x4*>(lds + kK + p_st_off + p * RPP * KS) = R.a[p];
-      *reinterpret_cast<u32x4*>(lds + kKt + t_st_off + p * RPP * VS) = R.a[p];
-      *reinterpret_cast<u32x4*>(lds + kV + p_st_off + p * RPP * KS) = R.b[p];
+      *reinterpret_cast<u32x4*>(sb + kK + p_st_off + p * RPP * KS) = R.a[p];
+      *reinterpret_cast<u32x4*>(sb + kKt + t_st_off + p * RPP * VS) = R.a[p];
+      *reinterpret_cast<u32x4*>(sb + kV + p_st_off + p * RPP * KS) = R.b[p];
     }
     if (t >= n_win_tiles && wv == 0) {
-      pos_lds[lane] = R.pos;
+      pos_lds_base[(t & 1) * BN + lane] = R.pos;
       const int mn = wave_min_i(R.pos);
       const int mx = wave_max_i(R.pos == 0x7FFFFFFF ? (int)0x80000000 : R.pos);
-      if (lane == 0) { pos_rng[0] = mn; pos_rng[1] = mx; }
+      if (lane == 0) { pos_rng_base[(t & 1) * 2] = mn; pos_rng_base[(t & 1) * 2 + 1] = mx; }
     }
   };
+  const bf16_t* tb = lds;            // tile buffer and position list of the tile being computed
+  const int* pos_lds = pos_lds_base;
 
   const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*kb*KS + 16*ks
   const int tr_key = 8 * hb + ((lane & 15) >> 2);
@@ -186,8 +189,8 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(lds + kK + a_row_off + 32 * kb * KS + 16 * ks);
-        const bf16x8 av = *reinterpret_cast<const bf16x8*>(lds + kV + a_row_off + 32 * kb * KS + 16 * ks);
+        const bf16x8 ak = *reinterpret_cast<const bf16x8*>(tb + kK + a_row_off + 32 * kb * KS + 16 * ks);
+        const bf16x8 av = *reinterpret_cast<const bf16x8*>(tb + kV + a_row_off + 32 * kb * KS + 16 * ks);
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qreg[ks], sc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, doreg[ks], dp, 0, 0, 0);
       }
@@ -222,7 +225,7 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
       }
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
-        const bf16_t* ap = lds + a_tr_off + 32 * kb * VS + ((db ^ tr_swz) << 5);
+        const bf16_t* ap = tb + a_tr_off + 32 * kb * VS + ((db ^ tr_swz) << 5);
         const bf16x8 a0 = load_transposed(ap, VS);
         const bf16x8 a1 = load_transposed(ap + 16 * VS, VS);
         acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[0], acc[db], 0, 0, 0);
@@ -231,13 +234,17 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
     }
   };
 
+  // tile t is computed from buffer t & 1 while tile t+1 is stored into the other buffer and tile t+2 is in flight
   TileRegs<D> regs;
   load_tile(0, regs);
+  store_tile(0, regs);
+  if (n_tiles > 1) load_tile(1, regs);
   for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();                 // everyone is done reading the previous tile
-    store_tile(t, regs);
-    __syncthreads();                 // tile t is in LDS
-    if (t + 1 < n_tiles) load_tile(t + 1, regs);
+    __syncthreads();                 // tile t is in LDS; everyone is done with tile t-1 (its buffer is written next)
+    if (t + 1 < n_tiles) store_tile(t + 1, regs);
+    if (t + 2 < n_tiles) load_tile(t + 2, regs);
+    tb = lds + (t & 1) * G_::kBufDq;
+    pos_lds = pos_lds_base + (t & 1) * BN;
     int mode = -1, jt = 0;
     if (r0 < n) {
       if (t < n_win_tiles) {
@@ -245,7 +252,7 @@ __device__ __forceinline__ void dq_body(const TrainArgs& A, int tiles_upper, int
         if (!(jt > r_hi || jt + BN - 1 < r0 - window + 1))
           mode = ((jt + BN - 1 <= r0) && (jt >= r_hi - window + 1)) ? 0 : 1;
       } else {
-        const int pmin = pos_rng[0], pmax = pos_rng[1];
+        const int pmin = pos_rng_base[(t & 1) * 2], pmax = pos_rng_base[(t & 1) * 2 + 1];
         if (pmin <= r_hi - window) {
           const bool full = (t - n_win_tiles + 1) * BN <= cnt;
           mode = (full && pmax <= r0 - window) ? 0 : 2;
@@ -306,7 +313,7 @@ template <int D> struct QTileRegs {
 // queries from position + window on; the fp32 sums go to a scratch array indexed like the compact segment.
 template <int D, bool FAR>
 __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, float scale_log2e, float* far_dk,
-                                         float* far_dv, int block, bf16_t* lds, float* lse_lds, float* dlt_lds) {
+                                         float* far_dv, int block, bf16_t* lds, float* stat_base) {
   LTEA_GEO(D);
   constexpr int kQ = 0, kQt = BN * KS, kO = BN * KS + BN * VS, kOt = 2 * BN * KS + BN * VS;
   static_assert(G_::kBufDkv >= BM * OS, "epilogue staging must fit in the tile buffer");
@@ -430,17 +437,19 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
   static_assert(RPP % 4 == 0, "row passes must preserve the swizzle phase");
   const int p_st_off = k_row * KS + k_piece * 8;
   const int t_st_off = k_row * VS + (((k_piece >> 2) ^ chunk_swizzle<D>(k_row)) << 5) + (k_piece & 3) * 8;
-  auto store_tile = [&](const QTileRegs<D>& R) {
+  auto store_tile = [&](int it, const QTileRegs<D>& R) {
+    bf16_t* sb = lds + (it & 1) * G_::kBufDkv;
 #pragma unroll
     for (int p = 0; p < KPASS; ++p) {
-      *reinterpret_cast<u32x4*>(lds + kQ + p_st_off + p * RPP * KS) = R.a[p];
-      *reinterpret_cast<u32x4*>(lds + kQt + t_st_off + p * RPP * VS) = R.a[p];
-      *reinterpret_cast<u32x4*>(lds + kO + p_st_off + p * RPP * KS) = R.b[p];
-      *reinterpret_cast<u32x4*>(lds + kOt + t_st_off + p * RPP * VS) = R.b[p];
+      *reinterpret_cast<u32x4*>(sb + kQ + p_st_off + p * RPP * KS) = R.a[p];
+      *reinterpret_cast<u32x4*>(sb + kQt + t_st_off + p * RPP * VS) = R.a[p];
+      *reinterpret_cast<u32x4*>(sb + kO + p_st_off + p * RPP * KS) = R.b[p];
+      *reinterpret_cast<u32x4*>(sb + kOt + t_st_off + p * RPP * VS) = R.b[p];
     }
-    if (tid < BN) lse_lds[tid] = R.stat;
-    else if (tid < 2 * BN) dlt_lds[tid - BN] = R.stat;
+    if (tid < 2 * BN) stat_base[(it & 1) * 2 * BN + tid] = R.stat;     // [lse of the 64 queries | their delta]
   };
+  const bf16_t* tb = lds;            // tile buffer and row statistics of the tile being computed
+  const float *lse_lds = stat_base, *dlt_lds = stat_base + BN;
 
   const int a_row_off = tile_row_of_mfma_row(ql) * KS + 8 * hb;        // + 32*qb*KS + 16*ks
   const int tr_row = 8 * hb + ((lane & 15) >> 2);
@@ -462,8 +471,8 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
       for (int r = 0; r < 16; ++r) { sc[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(lds + kQ + a_row_off + 32 * qb * KS + 16 * ks);
-        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(lds + kO + a_row_off + 32 * qb * KS + 16 * ks);
+        const bf16x8 aq = *reinterpret_cast<const bf16x8*>(tb + kQ + a_row_off + 32 * qb * KS + 16 * ks);
+        const bf16x8 ao = *reinterpret_cast<const bf16x8*>(tb + kO + a_row_off + 32 * qb * KS + 16 * ks);
         sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kreg[ks], sc, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ao, vreg[ks], dp, 0, 0, 0);
       }
@@ -486,8 +495,8 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
       }
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
-        const bf16_t* ao = lds + kOt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
-        const bf16_t* aq = lds + kQt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
+        const bf16_t* ao = tb + kOt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
+        const bf16_t* aq = tb + kQt + a_tr_off + 32 * qb * VS + ((db ^ tr_swz) << 5);
         const bf16x8 o0 = load_transposed(ao, VS), o1 = load_transposed(ao + 16 * VS, VS);
         const bf16x8 q0 = load_transposed(aq, VS), q1 = load_transposed(aq + 16 * VS, VS);
         dva[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o0, pp[0], dva[db], 0, 0, 0);
@@ -498,13 +507,18 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
     }
   };
 
+  // tile `it` is computed from buffer it & 1 while the next one is stored into the other and the one after is in flight
   QTileRegs<D> regs;
   load_tile(0, regs);
+  store_tile(0, regs);
+  if (n_iter > 1) load_tile(1, regs);
   for (int it = 0; it < n_iter; ++it) {
     __syncthreads();
-    store_tile(regs);
-    __syncthreads();
-    if (it + 1 < n_iter) load_tile(it + 1, regs);
+    if (it + 1 < n_iter) store_tile(it + 1, regs);
+    if (it + 2 < n_iter) load_tile(it + 2, regs);
+    tb = lds + (it & 1) * G_::kBufDkv;
+    lse_lds = stat_base + (it & 1) * 2 * BN;
+    dlt_lds = lse_lds + BN;
     const int t = it % n_qt;
     const int qt = (qt_first + t) * BN;
     // does any key of this wave see a query of the tile, and do all of them see all of it?
@@ -642,11 +656,11 @@ template <int D>
 __global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1)
 train_dq_far_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_log2e, float* far_dk, float* far_dv,
                          int far_blocks) {
-  __shared__ __align__(16) bf16_t lds[Geo<D>::kBuf];      // the two roles lay their tiles out in the same buffer
-  __shared__ __align__(16) float stat_lds[2 * BN];
-  __shared__ int pos_rng[2];
+  __shared__ __align__(16) bf16_t lds[2 * Geo<D>::kBuf];  // two tile buffers; the two roles lay their tiles out in them
+  __shared__ __align__(16) float stat_lds[4 * BN];
+  __shared__ int pos_rng[4];
   if ((int)blockIdx.x < far_blocks)
-    dkv_body<D, true>(A, 0, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds, stat_lds + BN);
+    dkv_body<D, true>(A, 0, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds);
   else
     dq_body<D>(A, tiles_upper, n_work, scale_log2e, (int)blockIdx.x - far_blocks, lds, reinterpret_cast<int*>(stat_lds), pos_rng);
 }
@@ -654,9 +668,9 @@ train_dq_far_mfma_kernel(TrainArgs A, int tiles_upper, int n_work, float scale_l
 template <int D>
 __global__ void __launch_bounds__(kThreads, D == 64 ? 2 : 1)
 train_dkv_band_mfma_kernel(TrainArgs A, int tiles_upper, float scale_log2e, float* far_dk, float* far_dv) {
-  __shared__ __align__(16) bf16_t lds[Geo<D>::kBufDkv];
-  __shared__ __align__(16) float stat_lds[2 * BN];
-  dkv_body<D, false>(A, tiles_upper, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds, stat_lds + BN);
+  __shared__ __align__(16) bf16_t lds[2 * Geo<D>::kBufDkv];
+  __shared__ __align__(16) float stat_lds[4 * BN];
+  dkv_body<D, false>(A, tiles_upper, scale_log2e, far_dk, far_dv, (int)blockIdx.x, lds, stat_lds);
 }
 
 }  // namespace
