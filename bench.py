@@ -131,6 +131,24 @@ def bench_prefill(args):
     tokens_per_step = T + nB
     value = tokens_per_step / (ms_per_step * 1e-3)
 
+    # the same steps with the conv weights re-laid once beforehand (ltea_cnn_prepare) instead of on every call:
+    # what a server that loads its weights once sees.  Reported beside the headline, which keeps the per-call re-layout.
+    cnn_once = B.prepare_cnn(cfg, B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype))
+
+    def step_prepared(i):
+        s = sets[i % n_copies]
+        B.ltea_prefill(cfg, cnn_once, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"], workspace=ws)
+        B.ltea_decode_step(cfg, cnn_once, dq, dk, dv, s["cache"], out=dout, workspace=dws)
+
+    for i in range(args.warmup):
+        step_prepared(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step_prepared(i)
+    torch.cuda.synchronize()
+    prepared_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # instrumented repeat: same work, entry points one by one, HIP events on the launch stream
     names = ["score", "retain", "attention", "decode_step"]
     acc = {n: 0.0 for n in names}
@@ -162,6 +180,7 @@ def bench_prefill(args):
     achieved = flops / (kern_ms["attention"] * 1e-3) / 1e12
     score_bytes = 2 * T * w.Hkv * w.D * 2 + 4 * T * w.Hkv
     res = dict(value=value, ms_per_step=ms_per_step, tokens_per_step=tokens_per_step, kern_ms=kern_ms,
+               prepared_ms=prepared_ms,
                roofline=dict(bound="mfma", kernel="prefill attention (window + retained)", achieved=achieved,
                              peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS,
                              traffic=measured_traffic("prefill_bf16", "attention_mfma_kernel") if args.workload == "prefill" else None,
@@ -516,6 +535,8 @@ def main():
                    "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": 4 if args.workload == "prefill" else 1},
         "roofline": pre["roofline"],
         "kernel_ms": pre["kern_ms"],
+        "prepared_cnn": {"ms_per_step": pre["prepared_ms"], "tokens_per_s": pre["tokens_per_step"] / (pre["prepared_ms"] * 1e-3),
+                         "note": "same steps with the conv weights re-laid once by ltea_cnn_prepare instead of on every call"},
         "scoring_roofline": pre["scoring"],
     }
     ceilings = measure_ceilings()

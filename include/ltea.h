@@ -69,6 +69,8 @@ typedef struct ltea_cnn {
   const float *bias[LTEA_MAX_CNN_LAYERS]; /* [Hkv][c_out] fp32, device                       */
   const void *w_out;                      /* [Hkv][c_out of last layer], cfg->dtype, device  */
   const float *b_out;                     /* [Hkv] fp32, device                              */
+  const void *panels;                     /* optional, device: what ltea_cnn_prepare wrote for exactly these weights
+                                             and this cfg; NULL: the weights are re-laid on every call (workspace)  */
 } ltea_cnn;
 
 typedef struct ltea_cfg {
@@ -97,6 +99,15 @@ typedef struct ltea_cache {
   int32_t *n_seen;       /* [B]                  tokens consumed so far                       */
   int32_t *n_scored;     /* [B]                  = max(0, n_seen - rho) after every call      */
 } ltea_cache;
+
+/* The matrix-core scoring kernels read the conv weights re-laid as tap-major panels.  By default every call that
+ * scores re-lays them into its workspace (a few microseconds); weights that do not change between calls can be
+ * prepared once instead: ltea_cnn_prepare fills `panels` (device, ltea_cnn_panels_bytes bytes, 0 if this
+ * configuration runs on kernels that need none), and a ltea_cnn whose `panels` member points there makes every
+ * entry point skip the re-layout.  The caller keeps `panels` alive and redoes the preparation when the weights
+ * change; cnn->panels is ignored by ltea_cnn_prepare itself. */
+size_t ltea_cnn_panels_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn);
+int ltea_cnn_prepare(const ltea_cfg *cfg, const ltea_cnn *cnn, void *panels, size_t panels_bytes, void *stream);
 
 /* Human-readable text for a status code (static storage). */
 const char *ltea_strerror(int status);

@@ -34,7 +34,7 @@ class ltea_cnn(C.Structure):
                 ("kernel", C.c_int32 * MAX_LAYERS), ("dilation", C.c_int32 * MAX_LAYERS),
                 ("c_out", C.c_int32 * MAX_LAYERS),
                 ("w", C.c_void_p * MAX_LAYERS), ("bias", C.c_void_p * MAX_LAYERS),
-                ("w_out", C.c_void_p), ("b_out", C.c_void_p)]
+                ("w_out", C.c_void_p), ("b_out", C.c_void_p), ("panels", C.c_void_p)]
 
 
 class ltea_cfg(C.Structure):
@@ -55,7 +55,7 @@ class ltea_rope(C.Structure):
                 ("interleaved", C.c_int32)]
 
 
-EXPORTS = ["ltea_strerror", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
+EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_append_workspace_bytes",
            "ltea_prefill_append", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
@@ -78,6 +78,10 @@ def lib() -> C.CDLL:
     P = C.POINTER
     L.ltea_strerror.restype = C.c_char_p
     L.ltea_strerror.argtypes = [C.c_int]
+    L.ltea_cnn_panels_bytes.restype = sz
+    L.ltea_cnn_panels_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn)]
+    L.ltea_cnn_prepare.restype = C.c_int
+    L.ltea_cnn_prepare.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, sz, vp]
     L.ltea_workspace_bytes.restype = sz
     L.ltea_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
     L.ltea_decode_workspace_bytes.restype = sz
@@ -181,6 +185,20 @@ def upload_cnn(kernel: Sequence[int], dilation: Sequence[int], w: Sequence, bias
     s.w_out, s.b_out = wo.data_ptr(), bo.data_ptr()
     rho = sum(int(d) * (int(k) - 1) // 2 for k, d in zip(kernel, dilation))
     return Cnn(s, keep, rho)
+
+
+def prepare_cnn(cfg: ltea_cfg, cnn: Cnn) -> Cnn:
+    """Re-lay the conv weights once for the matrix-core scoring kernels (ltea_cnn_prepare) and point cnn.struct.panels
+    at the result; every later call with this Cnn then skips the per-call re-layout.  No-op for configurations whose
+    kernels read the weights as they are."""
+    nbytes = int(lib().ltea_cnn_panels_bytes(C.byref(cfg), C.byref(cnn.struct)))
+    if nbytes == 0:
+        return cnn
+    panels = torch.empty(nbytes, dtype=torch.uint8, device=cnn.tensors[0].device)
+    _check(lib().ltea_cnn_prepare(C.byref(cfg), C.byref(cnn.struct), _ptr(panels), nbytes, _stream()), "ltea_cnn_prepare")
+    cnn.tensors.append(panels)
+    cnn.struct.panels = panels.data_ptr()
+    return cnn
 
 
 @dataclass

@@ -126,6 +126,25 @@ size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqle
 
 extern "C" {
 
+size_t ltea_cnn_panels_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK) return 0;
+  if (use_score_mfma(*cfg, *cnn)) return align_up(score_mfma_workspace(*cfg, *cnn), 256);
+  if (score_deep_supported(*cfg, *cnn)) return align_up(score_deep_workspace(*cfg, *cnn), 256);
+  return 0;
+}
+
+int ltea_cnn_prepare(const ltea_cfg* cfg, const ltea_cnn* cnn, void* panels, size_t panels_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st != LTEA_OK) return st;
+  const size_t need = ltea_cnn_panels_bytes(cfg, cnn);
+  if (need == 0) return LTEA_OK;                      // this configuration's kernels read the weights as they are
+  if (!panels || !aligned16(panels) || panels_bytes < need) return LTEA_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (use_score_mfma(*cfg, *cnn)) return hip_status(launch_score_mfma_panels(*cfg, *cnn, panels, s));
+  return hip_status(launch_score_deep_panels(*cfg, *cnn, panels, s));
+}
+
 const char* ltea_strerror(int status) {
   switch (status) {
     case LTEA_OK: return "ok";

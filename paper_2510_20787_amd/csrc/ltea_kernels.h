@@ -29,9 +29,10 @@ hipError_t launch_score_generic(const ltea_cfg& cfg, const ltea_cnn& cnn, const 
                                 int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                                 void* workspace, hipStream_t stream);
 // Single-layer bf16 path on MFMA (fused conv + Swish + output projection); the workspace holds the weights
-// re-laid as tap-major panels.
+// re-laid as tap-major panels unless cnn.panels supplies them (launch_*_panels writes either).
 bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
 size_t score_mfma_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_mfma_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
 hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                              void* workspace, hipStream_t stream);
@@ -40,6 +41,7 @@ hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
 // every layer's weights re-laid as tap-major panels.
 bool score_deep_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
 size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
 hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                              void* workspace, hipStream_t stream);

@@ -334,36 +334,50 @@ size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   return (size_t)plan(cfg, cnn).panel_elems * sizeof(uint16_t);
 }
 
+// Fills `panels` with every layer's weights re-laid for score_deep_kernel.
+hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream) {
+  const DeepPlan p = plan(cfg, cnn);
+  if (!p.ok) return hipErrorInvalidValue;
+  int cin = 2 * cfg.D;
+  PanelArgs pa;
+  int64_t most = 0;
+  for (int l = 0; l < kMaxL; ++l) {
+    const bool on = l < cnn.n_layers;
+    pa.w[l] = on ? static_cast<const uint16_t*>(cnn.w[l]) : nullptr;
+    pa.off[l] = p.panel_off[l]; pa.total[l] = on ? p.panel_head[l] * cfg.Hkv : 0;
+    pa.cout[l] = on ? cnn.c_out[l] : 16; pa.cp[l] = on ? p.cp[l] : 32; pa.cin[l] = cin; pa.ks[l] = on ? cnn.kernel[l] : 1;
+    most = pa.total[l] > most ? pa.total[l] : most;
+    if (on) cin = cnn.c_out[l];
+  }
+  hipLaunchKernelGGL(deep_panels_kernel, dim3((unsigned)((most + 255) / 256), (unsigned)cnn.n_layers), dim3(256), 0,
+                     stream, pa, static_cast<uint16_t*>(panels));
+  return hipGetLastError();
+}
+
 hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
                              int64_t sh, const SeqView& sv, float* logits, void* workspace, hipStream_t stream) {
   if (sv.total_tokens == 0) return hipSuccess;
   const DeepPlan p = plan(cfg, cnn);
   if (!p.ok) return hipErrorInvalidValue;
+  const void* panels = cnn.panels;
+  if (panels == nullptr) {            // not prepared by the caller: re-lay the weights into the workspace now
+    hipError_t e = launch_score_deep_panels(cfg, cnn, workspace, stream);
+    if (e != hipSuccess) return e;
+    panels = workspace;
+  }
   DeepArgs a;
   a.k = static_cast<const bf16_t*>(k); a.v = static_cast<const bf16_t*>(v); a.st = st; a.sh = sh;
-  a.panels = static_cast<const bf16_t*>(workspace);
+  a.panels = static_cast<const bf16_t*>(panels);
   a.w_out = static_cast<const bf16_t*>(cnn.w_out); a.b_out = cnn.b_out;
   a.L = cnn.n_layers;
   int cin = 2 * cfg.D;
-  PanelArgs pa;
-  int64_t most = 0;
   for (int l = 0; l < kMaxL; ++l) {
     const bool on = l < cnn.n_layers;
     a.panel_off[l] = p.panel_off[l]; a.panel_head[l] = p.panel_head[l];
     a.bias[l] = on ? cnn.bias[l] : nullptr;
     a.ks[l] = on ? cnn.kernel[l] : 1; a.dil[l] = on ? cnn.dilation[l] : 1;
     a.cin[l] = cin; a.cout[l] = on ? cnn.c_out[l] : 16; a.cp[l] = on ? p.cp[l] : 32;
-    pa.w[l] = on ? static_cast<const uint16_t*>(cnn.w[l]) : nullptr;
-    pa.off[l] = p.panel_off[l]; pa.total[l] = on ? p.panel_head[l] * cfg.Hkv : 0;
-    pa.cout[l] = a.cout[l]; pa.cp[l] = a.cp[l]; pa.cin[l] = cin; pa.ks[l] = a.ks[l];
-    most = pa.total[l] > most ? pa.total[l] : most;
     if (on) cin = cnn.c_out[l];
-  }
-  hipLaunchKernelGGL(deep_panels_kernel, dim3((unsigned)((most + 255) / 256), (unsigned)cnn.n_layers), dim3(256), 0,
-                     stream, pa, static_cast<uint16_t*>(workspace));
-  {
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
   }
   a.TM = p.TM; a.x_rows = p.x_rows; a.h0 = p.h0;
   a.lds_ra = p.lds_ra; a.lds_r1 = p.lds_r1; a.lds_rw = p.lds_rw;

@@ -207,13 +207,14 @@ size_t lds_bytes(int ks, int dil) {
 template <int D>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
                const SeqView& sv, float* logits, void* workspace, hipStream_t stream) {
-  const int ks = cnn.kernel[0], C2 = 2 * D;
-  const int64_t panel_elems = (int64_t)cfg.Hkv * ks * CP * C2;
-  hipLaunchKernelGGL(score_weight_panels_kernel, dim3((unsigned)((panel_elems + 255) / 256)), dim3(256), 0, stream,
-                     static_cast<const uint16_t*>(cnn.w[0]), static_cast<uint16_t*>(workspace), cnn.c_out[0], C2, ks,
-                     panel_elems);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  const int ks = cnn.kernel[0];
+  const void* panels = cnn.panels;
+  hipError_t e = hipSuccess;
+  if (panels == nullptr) {            // not prepared by the caller: re-lay the weights into the workspace now
+    e = launch_score_mfma_panels(cfg, cnn, workspace, stream);
+    if (e != hipSuccess) return e;
+    panels = workspace;
+  }
   const size_t lds = lds_bytes(ks, cnn.dilation[0]);
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -221,7 +222,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   const int64_t groups_upper = (sv.total_tokens + NT * TM - 1) / (NT * TM) + sv.n_seqs;
   hipLaunchKernelGGL(score_mfma_kernel<D>, dim3((unsigned)groups_upper, (unsigned)cfg.Hkv), dim3(kThreads), lds, stream,
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), st, sh,
-                     static_cast<const bf16_t*>(workspace), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out),
+                     static_cast<const bf16_t*>(panels), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out),
                      cnn.b_out, cnn.c_out[0], ks, cnn.dilation[0], sv.cu_seqlens, sv.n_seqs, (int)groups_upper,
                      sv.total_tokens, logits);
   return hipGetLastError();
@@ -234,6 +235,15 @@ bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   if (cfg.D != 64 && cfg.D != 128) return false;
   if ((cnn.kernel[0] - 1) / 2 * cnn.dilation[0] > kMaxRho) return false;
   return lds_bytes(cnn.kernel[0], cnn.dilation[0]) <= 150 * 1024;
+}
+
+hipError_t launch_score_mfma_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream) {
+  const int ks = cnn.kernel[0], C2 = 2 * cfg.D;
+  const int64_t panel_elems = (int64_t)cfg.Hkv * ks * CP * C2;
+  hipLaunchKernelGGL(score_weight_panels_kernel, dim3((unsigned)((panel_elems + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const uint16_t*>(cnn.w[0]), static_cast<uint16_t*>(panels), cnn.c_out[0], C2, ks,
+                     panel_elems);
+  return hipGetLastError();
 }
 
 size_t score_mfma_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn) {

@@ -270,3 +270,17 @@ def test_train_argument_errors():
     assert L.ltea_lambda_update(lam, cb, 2, 512.0, 2.0) == B.LTEA_OK and lam[0] == 1.0 and abs(lam[1] - 1e-9) < 1e-15
     assert L.ltea_lambda_update(None, cb, 2, 512.0, 2.0) == B.LTEA_EINVAL
     assert L.ltea_lambda_update(lam, cb, 2, 512.0, 0.0) == B.LTEA_EINVAL
+
+
+def test_cnn_prepare_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    need = L.ltea_cnn_panels_bytes(C.byref(cfg), C.byref(cnn))
+    assert need >= cfg.Hkv * 5 * 32 * 2 * cfg.D * 2                     # single layer, kernel 5, 32-channel panels
+    assert L.ltea_cnn_panels_bytes(None, C.byref(cnn)) == 0
+    assert L.ltea_cnn_panels_bytes(C.byref(good_cfg(dtype="f32")), C.byref(cnn)) == 0
+    assert L.ltea_cnn_prepare(None, C.byref(cnn), 0x1000, need, None) == B.LTEA_EINVAL
+    assert L.ltea_cnn_prepare(C.byref(cfg), None, 0x1000, need, None) == B.LTEA_EINVAL
+    assert L.ltea_cnn_prepare(C.byref(cfg), C.byref(cnn), None, need, None) == B.LTEA_EWORKSPACE
+    assert L.ltea_cnn_prepare(C.byref(cfg), C.byref(cnn), 0x1000, need - 1, None) == B.LTEA_EWORKSPACE
+    assert L.ltea_cnn_prepare(C.byref(good_cfg(dtype="f32")), C.byref(cnn), None, 0, None) == B.LTEA_OK   # nothing to prepare
