@@ -299,3 +299,74 @@ def test_random_decode_mix(seed):
             ref = ref_out[s * n + n_dec:(s + 1) * n, hq]
             err = float(np.max(np.abs(out[s * n_app:(s + 1) * n_app, hq] - ref)))
             assert err <= tol * float(np.max(np.abs(ref))), (s, hq, err)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_rotated_cache(seed):
+    """Lazy decoding of a cache that holds rotated keys, from empty, on random configurations: random rotary width
+    (a multiple of 16 up to D), either pairing, random cadence of the batched scoring (never later than allowed).
+    Reference: the oracle's lazy procedure with its own inverse rotation, rounded to the storage type."""
+    c = draw_config(3000 + seed)
+    rng = np.random.default_rng(94000 + seed)
+    rho = sum(dd * (kk - 1) // 2 for kk, dd in zip(c["kernel"], c["dilation"]))
+    window = int(rng.integers(2 * rho + 1, 2 * rho + 40))
+    n, B_ = 100, int(rng.integers(1, 4))
+    rot = int(rng.choice([r for r in (16, 32, 48, 64, 96, 128) if r <= c["D"]]))
+    inter = bool(rng.integers(0, 2))
+    dt = c["dtype"]
+    w = wl.make_prefill(f"random_rope{seed}", 94000 + seed, dt, [n] * B_, c["Hq"], c["Hkv"], c["D"], window, c["budget"],
+                        c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"], cnn_dilation=c["dilation"],
+                        qkv_scale=1.0, w_std=0.1)
+    print(f"[random rope {seed}] window {window} rot {rot} interleaved {inter} {c}", flush=True)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    cos, sin = wl.rope_tables(n + 4, rot, 50.0)
+    rope_o = orc.OracleRope(cos.astype(np.float64), sin.astype(np.float64), inter)
+    rope_g = B.upload_rope(cos, sin, inter)
+    rounder = (lambda x: wl.to_storage(x.astype(np.float32), dt).astype(np.float64))
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    states = [orc.empty_state(cfg) for _ in range(B_)]
+    q3 = w.q.reshape(B_, n, w.Hq, w.D); k3 = w.k.reshape(B_, n, w.Hkv, w.D); v3 = w.v.reshape(B_, n, w.Hkv, w.D)
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    G = w.Hq // w.Hkv
+    since, z_eps, unsure = 0, 1e-6, set()
+    tol = OUT_TOL[dt]
+    for t in range(n):
+        if since >= period or (since > 0 and rng.random() < 0.15):
+            B.ltea_rescore(d.cfg, d.cnn, cache, rope=rope_g, status=status)
+            zw = cache.win_score.cpu().numpy()
+            for s in range(B_):
+                orc.rescore(states[s], cfg, cnn, rope_o, rounder)
+                assert int(cache.n_scored[s]) == states[s].n_scored
+                for h in range(w.Hkv):
+                    for p, zp in states[s].heads[h].win_z.items():
+                        z_eps = max(z_eps, abs(float(zw[s, h, p % window]) - zp))
+            since = 0
+        got = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache, status=status))
+        since += 1
+        # the oracle's keep decisions of this step, with their margins, before it takes the step
+        for s in range(B_):
+            for h in range(w.Hkv):
+                hs = states[s].heads[h]
+                if len(hs.win_pos) == window and (s, h) not in unsure:
+                    e = hs.win_pos[0]
+                    ze = hs.win_z[e]
+                    close = [abs(ze - w.tau)] if e >= w.sink else []
+                    if len(hs.ret_pos) >= w.budget > 0 and e >= w.sink:
+                        close.append(abs(float(min(hs.ret_key)) - ze))
+                    if close and min(close) <= 2 * z_eps + 1e-6:
+                        unsure.add((s, h))
+        ref = np.stack([orc.decode_step_lazy(states[s], q3[s, t], k3[s, t], v3[s, t], cfg) for s in range(B_)])
+        for s in range(B_):
+            for h in range(w.Hkv):
+                if (s, h) in unsure:
+                    continue
+                cnt, pos = gpu_retained_sets(cache, s, h)
+                np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(states[s])[h], err_msg=f"t {t} seq {s} head {h}")
+                err = float(np.max(np.abs(got[s, h * G:(h + 1) * G] - ref[s, h * G:(h + 1) * G])))
+                sc = float(np.max(np.abs(ref[s, h * G:(h + 1) * G])))
+                assert err <= tol and err <= tol * max(sc, 1e-30), (t, s, h, err, sc)
+    assert int(status.item()) == 0
+    assert z_eps <= (2e-3 if dt == "bf16" else 1e-4) * 4, z_eps
+    assert len(unsure) <= max(2, B_ * w.Hkv // 2), unsure
