@@ -171,6 +171,16 @@ int ltea_prefill(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_
                  const ltea_cache *cache, float *logits_or_null, void *workspace, size_t workspace_bytes,
                  void *stream);
 
+/* ltea_prefill for models whose cached keys differ from the keys the scoring CNN is trained on (rotary position
+ * encoding: Section 3.1.1 scores keys as they are before the rotation, the cache holds them after it): k_feat, a view
+ * with the strides of k, is what the CNN scores; k is what is cached and attended.  ltea_prefill is this call with
+ * k_feat = k.  (For decoding such a cache see ltea_rescore.) */
+int ltea_prefill_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
+                      int64_t q_stride_head, const void *k, const void *v, const void *k_feat, int64_t kv_stride_tok,
+                      int64_t kv_stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                      int32_t max_seqlen, void *out, const ltea_cache *cache, float *logits_or_null, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
 /* (d) One decode step for n_seqs sequences (Section 3.1.3, cache replacement
  * and lazy scoring paragraphs): for sequence b with t = n_seen[b],
  *   1. the logit of position t - rho becomes final (its receptive field

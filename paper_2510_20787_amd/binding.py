@@ -56,7 +56,7 @@ class ltea_rope(C.Structure):
 
 
 EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
-           "ltea_sparse_attention", "ltea_prefill", "ltea_decode_step", "ltea_append_workspace_bytes",
+           "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_append_workspace_bytes",
            "ltea_prefill_append", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
            "ltea_lambda_update", "ltea_diag_sink_bytes",
@@ -96,6 +96,9 @@ def lib() -> C.CDLL:
     L.ltea_prefill.restype = C.c_int
     L.ltea_prefill.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp,
                                P(ltea_cache), vp, vp, sz, vp]
+    L.ltea_prefill_feat.restype = C.c_int
+    L.ltea_prefill_feat.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, vp, i64, i64, vp, i32, i64, i32, vp,
+                                    P(ltea_cache), vp, vp, sz, vp]
     L.ltea_decode_step.restype = C.c_int
     L.ltea_decode_step.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp, sz, vp]
     L.ltea_append_workspace_bytes.restype = sz
@@ -307,7 +310,9 @@ def ltea_sparse_attention(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: to
 
 def ltea_prefill(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                  cu_seqlens: torch.Tensor, max_seqlen: int, cache: Cache, out: Optional[torch.Tensor] = None,
-                 logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 k_feat: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """k_feat (optional, same strides as k): the keys the CNN scores when they differ from the cached ones."""
     T = q.shape[0]
     n_seqs = cu_seqlens.numel() - 1
     qst, qsh = _tok_head_strides(q)
@@ -317,6 +322,12 @@ def ltea_prefill(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: t
         out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
     if workspace is None:
         workspace = _workspace(ltea_workspace_bytes(cfg, cnn, n_seqs, T, max_seqlen), q.device)
+    if k_feat is not None:
+        assert _tok_head_strides(k_feat) == (st, sh)
+        _check(lib().ltea_prefill_feat(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), _ptr(k_feat),
+                                       st, sh, _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), C.byref(cache.struct),
+                                       _ptr(logits), _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill_feat")
+        return out
     _check(lib().ltea_prefill(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
                               _ptr(cu_seqlens), n_seqs, T, max_seqlen, _ptr(out), C.byref(cache.struct), _ptr(logits),
                               _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill")

@@ -236,11 +236,11 @@ int ltea_sparse_attention(const ltea_cfg* cfg, const void* q, int64_t q_stride_t
                       static_cast<hipStream_t>(stream));
 }
 
-int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
-                 const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
-                 const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen, void* out,
-                 const ltea_cache* cache, float* logits_or_null, void* workspace, size_t workspace_bytes,
-                 void* stream) {
+int ltea_prefill_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok,
+                      int64_t q_stride_head, const void* k, const void* v, const void* k_feat, int64_t kv_stride_tok,
+                      int64_t kv_stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                      int32_t max_seqlen, void* out, const ltea_cache* cache, float* logits_or_null, void* workspace,
+                      size_t workspace_bytes, void* stream) {
   int st = check_cfg(cfg);
   if (st == LTEA_OK) st = check_cnn(cfg, cnn);
   if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
@@ -252,6 +252,7 @@ int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_
     if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if ((st = check_view(k_feat, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if (!out || !aligned16(out)) return LTEA_EINVAL;
   }
   const size_t logits_bytes = align_up((size_t)cfg->Hkv * (size_t)total_tokens * sizeof(float), 256);
@@ -264,13 +265,23 @@ int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_
   hipStream_t s = static_cast<hipStream_t>(stream);
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
   if (total_tokens > 0) {
-    st = do_score(*cfg, *cnn, k, v, kv_stride_tok, kv_stride_head, sv, logits, ws, s);
+    st = do_score(*cfg, *cnn, k_feat, v, kv_stride_tok, kv_stride_head, sv, logits, ws, s);
     if (st != LTEA_OK) return st;
   }
   st = hip_status(launch_retain(*cfg, logits, k, v, kv_stride_tok, kv_stride_head, sv, cnn_rho(cnn), *cache, s));
   if (st != LTEA_OK) return st;
   if (total_tokens == 0) return LTEA_OK;
   return do_attention(*cfg, q, q_stride_tok, q_stride_head, k, v, kv_stride_tok, kv_stride_head, sv, *cache, out, s);
+}
+
+int ltea_prefill(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
+                 const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
+                 const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens, int32_t max_seqlen, void* out,
+                 const ltea_cache* cache, float* logits_or_null, void* workspace, size_t workspace_bytes,
+                 void* stream) {
+  return ltea_prefill_feat(cfg, cnn, q, q_stride_tok, q_stride_head, k, v, k, kv_stride_tok, kv_stride_head, cu_seqlens,
+                           n_seqs, total_tokens, max_seqlen, out, cache, logits_or_null, workspace, workspace_bytes,
+                           stream);
 }
 
 size_t ltea_append_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs, int64_t total_new,

@@ -173,3 +173,75 @@ def test_lazy_status_flags():
     # without a status word the same calls still run
     B.ltea_rescore(d.cfg, d.cnn, cache2, rope=B.upload_rope(cos, sin))
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("interleaved", [False, True])
+def test_rotary_model_flow_prefill_then_lazy_decode(interleaved):
+    """What a rotary model does end to end: the prefill scores the keys as they are before the rotation
+    (ltea_prefill with k_feat) while caching and attending the rotated ones; decoding then appends rotated keys and
+    every batched scoring rotates the ring back.  Oracle: the same composition (scores from the unrotated keys,
+    everything else from the rotated ones; lazy procedure with the inverse rotation afterwards)."""
+    lens, Hq, Hkv, D, window, budget, sink = [150, 61], 4, 2, 64, 40, 12, 2
+    w = wl.make_prefill("rotary_flow", 4711 + int(interleaved), "bf16", lens, Hq, Hkv, D, window, budget, sink, 0.0,
+                        cnn_kernel=(3, 3), cnn_channels=(32, 16), cnn_dilation=(2, 1), w_std=0.1)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    n_dec = 70
+    cos, sin = wl.rope_tables(max(lens) + n_dec + 1, 64, 100.0)
+    rope_o = orc.OracleRope(cos.astype(np.float64), sin.astype(np.float64), interleaved)
+    rope_g = B.upload_rope(cos, sin, interleaved)
+    to_bf16 = lambda x: wl.to_storage(np.asarray(x, np.float32), "bf16")
+    rounder = lambda x: to_bf16(x).astype(np.float64)
+    # the model's rotated keys (its own arithmetic; here through the oracle's rotation, rounded to bf16)
+    k_pre = w.k
+    k_post = np.zeros_like(k_pre)
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        for p in range(hi - lo):
+            k_post[lo + p] = to_bf16(orc.rope_rotate(k_pre[lo + p], p, rope_o))
+    # oracle prefill: logits from k_pre, the rest from k_post
+    z64 = orc.score(k_pre, w.v, cnn, w.cu_seqlens)
+    states, ref_out = [], np.zeros((w.total_tokens, Hq, D))
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        kept = [orc.retain(z64[h, lo:hi], hi - lo, window, budget, sink, 0.0) for h in range(Hkv)]
+        ref_out[lo:hi] = orc.sparse_attention_sequence(w.q[lo:hi], k_post[lo:hi], w.v[lo:hi], cfg, kept)
+        states.append(orc.state_after_prefill(k_post[lo:hi], w.v[lo:hi], z64[:, lo:hi], cfg, w.cnn.rho, kept))
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    out = to_np(B.ltea_prefill(d.cfg, d.cnn, d.q, dev(k_post, "bf16"), d.v, d.cu, d.max_seqlen, cache, logits=logits,
+                               k_feat=d.k))
+    eps = logit_eps(to_np(logits), z64, "bf16")
+    assert not check_sets(cache, z64, w, eps), "pick another seed: a head sits inside the decision margin"
+    check_output(out, ref_out, "bf16", "rotary prefill")
+    period = B.ltea_lazy_period(d.cfg, d.cnn)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    since = 0
+    for t in range(n_dec):
+        if since == period:
+            B.ltea_rescore(d.cfg, d.cnn, cache, rope=rope_g, status=status)
+            for st in states:
+                orc.rescore(st, cfg, cnn, rope_o, rounder)
+            compare_ring_logits_new(cache, states, w, LOGIT_TOL_ROPE, z64)
+            since = 0
+        q, k, v = wl.decode_inputs(w.seed, t, "bf16", w.n_seqs, Hq, Hkv, D)
+        kp = np.stack([to_bf16(orc.rope_rotate(k[s], states[s].n_seen, rope_o)) for s in range(w.n_seqs)])
+        got = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q, "bf16"), dev(kp, "bf16"), dev(v, "bf16"), cache, status=status))
+        since += 1
+        ref = np.stack([orc.decode_step_lazy(states[s], q[s], kp[s], v[s], cfg) for s in range(w.n_seqs)])
+        check_output(got, ref, "bf16", f"rotary decode step {t}")
+        compare_sets(cache, states, w, t)
+    assert int(status.item()) == 0
+
+
+def compare_ring_logits_new(cache, states, w, tol, z_prefill):
+    """Ring logits against the oracle's; the ones that date from the prefill were computed from exact unrotated keys
+    (tight tolerance), the ones from batched scorings from un-rotated rounded keys (tolerance `tol`)."""
+    for s, st in enumerate(states):
+        assert int(cache.n_scored[s]) == st.n_scored
+        n0 = int(w.cu_seqlens[s + 1] - w.cu_seqlens[s])
+        for h in range(w.Hkv):
+            for p, zp in st.heads[h].win_z.items():
+                zg = float(cache.win_score[s, h, p % w.window])
+                t = LOGIT_TOL["bf16"] if p < n0 - w.cnn.rho else tol
+                assert abs(zg - zp) <= t * max(1.0, abs(zp)), (s, h, p, zg, zp)
