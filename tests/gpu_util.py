@@ -53,6 +53,8 @@ def boundary_margin(key32: np.ndarray, n: int, window: int, budget: int, sink: i
     if len(cand) > budget:
         if budget == 0:
             return np.inf
+        if cand[budget - 1] == cand[budget] == np.inf:      # more sinks than budget: the order among them is by position
+            return np.inf
         return float(cand[budget - 1] - cand[budget])
     nonsink = kk[sink:] if n_out > sink else np.array([])
     nonsink = nonsink[np.isfinite(nonsink)]
