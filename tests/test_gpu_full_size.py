@@ -386,3 +386,11 @@ def test_full_paper_stack_decode(lazy):
             if p >= hi - lo - rho:        # logits finalised during decoding
                 zg = float(cache.win_score[s, h, p % w.window])
                 assert abs(zg - zp) <= 5 * LOGIT_TOL["bf16"] * max(1.0, abs(zp)), (h, p, zg, zp)
+
+
+def test_full_very_long_sequence():
+    """One sequence of 400 000 tokens next to a short one (the streaming path of the selection, thousands of query
+    tiles, 32-bit byte offsets inside a sequence far from their limit but far from small)."""
+    w = wl.make_prefill("very_long", 321, "bf16", [400000, 5000], 4, 2, 64, 1024, 512, 4, 0.0, cnn_kernel=(5,),
+                        cnn_channels=(32,), qkv_scale=1.0, w_std=0.05)
+    run_full_prefill(w)
