@@ -394,3 +394,80 @@ def test_full_very_long_sequence():
     w = wl.make_prefill("very_long", 321, "bf16", [400000, 5000], 4, 2, 64, 1024, 512, 4, 0.0, cnn_kernel=(5,),
                         cnn_channels=(32,), qkv_scale=1.0, w_std=0.05)
     run_full_prefill(w)
+
+
+def test_full_decode_large_batch():
+    """640 sequences of the decode_bf16 shape: every cache tensor is larger than 2^31 bytes, so any 32-bit offset in
+    the decode, batched-scoring or lazy kernels would show.  The state is drawn on the device; ring logits come from
+    ltea_rescore over the whole batch; three sequences (first, middle, last) are stepped through the oracle."""
+    Bn, Hq, Hkv, D, window, budget, n0 = 640, 16, 16, 128, 1024, 512, 4096
+    rng = np.random.default_rng(77)
+    cnnw = wl.make_cnn(rng, "bf16", Hkv, D, (5,), (32,), [1], 0.05)
+    cfg = B.make_cfg(Hq, Hkv, D, window, budget, 0, 0.0, 0.0, "bf16")
+    cnn = B.upload_cnn(cnnw.kernel, cnnw.dilation, cnnw.w, cnnw.bias, cnnw.w_out, cnnw.b_out, "bf16")
+    ocfg, ocnn = orc.OracleCfg(Hq, Hkv, D, window, budget, 0, 0.0), oracle_cnn(cnnw)
+    rho = cnnw.rho
+    gen = torch.Generator("cuda").manual_seed(99)
+    rnd = lambda *shape: torch.randn(shape, device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    k_win, v_win = rnd(Bn, Hkv, window, D), rnd(Bn, Hkv, window, D)
+    k_ret, v_ret = rnd(Bn, Hkv, budget, D), rnd(Bn, Hkv, budget, D)
+    assert k_win.numel() * 2 > 2 ** 31
+    ret_score = torch.rand((Bn, Hkv, budget), device="cuda", generator=gen) * 0.05 + 0.001
+    # distinct positions below n0 - window, ascending
+    ret_pos = torch.sort(torch.argsort(torch.rand((Bn, Hkv, n0 - window), device="cuda", generator=gen), dim=2)[:, :, :budget],
+                         dim=2).values.to(torch.int32).contiguous()
+    cache = B.wrap_cache(k_win, v_win, torch.full((Bn, Hkv, window), float("nan"), device="cuda"), k_ret, v_ret, ret_score,
+                         ret_pos, torch.full((Bn, Hkv), budget, dtype=torch.int32, device="cuda"),
+                         torch.full((Bn,), n0, dtype=torch.int32, device="cuda"),
+                         torch.full((Bn,), n0 - window + rho, dtype=torch.int32, device="cuda"))
+    # the oldest rho ring logits must be final already: score them per sampled sequence below, zero elsewhere (those
+    # tokens are evicted in the first rho steps; a zero logit is "not a candidate", the same on both sides)
+    cache.win_score[:, :, :rho] = 0.0
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.ltea_rescore(cfg, cnn, cache, status=status)
+    torch.cuda.synchronize()
+    assert int(status.item()) == 0 and bool((cache.n_scored == n0 - rho).all())
+    sampled = [0, Bn // 2, Bn - 1]
+    states = {}
+    for b in sampled:
+        st = orc.empty_state(ocfg)
+        st.n_seen, st.n_scored = n0, n0 - rho
+        kb, vb = to_np(k_win[b]), to_np(v_win[b])
+        z = orc.score_sequence(np.transpose(kb, (1, 0, 2)), np.transpose(vb, (1, 0, 2)), ocnn)
+        zg = cache.win_score[b].cpu().numpy()
+        # slot i holds position n0 - window + i (n0 is a multiple of the window); positions rho .. window-rho-1 were
+        # scored by the batched scoring with their whole receptive field inside the ring
+        ref = z[:, rho:window - rho]
+        assert np.all(np.abs(zg[:, rho:window - rho] - ref) <= LOGIT_TOL["bf16"] * np.maximum(1.0, np.abs(ref)))
+        for h in range(Hkv):
+            hs = st.heads[h]
+            for i in range(window):
+                hs.win_pos.append(n0 - window + i)
+                hs.win_k.append(kb[h, i].astype(np.float64)); hs.win_v.append(vb[h, i].astype(np.float64))
+                if i < rho:
+                    hs.win_z[n0 - window + i] = 0.0
+                elif i < window - rho:
+                    hs.win_z[n0 - window + i] = float(z[h, i])
+            kr, vr = to_np(k_ret[b, h]), to_np(v_ret[b, h])
+            sc, ps = ret_score[b, h].cpu().numpy(), ret_pos[b, h].cpu().numpy()
+            for r in range(budget):
+                hs.ret_pos.append(int(ps[r])); hs.ret_key.append(np.float32(sc[r]))
+                hs.ret_k.append(kr[r].astype(np.float64)); hs.ret_v.append(vr[r].astype(np.float64))
+        states[b] = st
+    worst, scale = 0.0, 0.0
+    for step in range(12):
+        q, k, v = rnd(Bn, Hq, D), rnd(Bn, Hkv, D), rnd(Bn, Hkv, D)
+        if step < 6:
+            out = B.ltea_decode_step(cfg, cnn, q, k, v, cache)
+        else:
+            out = B.ltea_decode_step_lazy(cfg, q, k, v, cache, status=status)
+        for b in sampled:
+            ref = orc.decode_step(states[b], to_np(q[b]), to_np(k[b]), to_np(v[b]), ocfg, ocnn)
+            worst = max(worst, float(np.abs(to_np(out[b]) - ref).max()))
+            scale = max(scale, float(np.abs(ref).max()))
+    assert worst <= OUT_TOL["bf16"] and worst <= OUT_TOL["bf16"] * scale, (worst, scale)
+    assert int(status.item()) == 0 and bool((cache.n_seen == n0 + 12).all())
+    for b in sampled:
+        for h in range(Hkv):
+            cnt, pos = gpu_retained_sets(cache, b, h)
+            np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(states[b])[h])
