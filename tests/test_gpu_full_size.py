@@ -471,3 +471,35 @@ def test_full_decode_large_batch():
         for h in range(Hkv):
             cnt, pos = gpu_retained_sets(cache, b, h)
             np.testing.assert_array_equal(np.sort(pos), orc.retained_positions(states[b])[h])
+
+
+def test_full_prefill_batch_above_2gib_matches_single_sequences():
+    """300 sequences x 4000 tokens, 8 KV heads, D=128: K and V are 2.4 GB each, so any 32-bit element or byte offset
+    across sequences would show.  Property checked (the small-case parity against the oracle is established
+    elsewhere): packing is invisible, i.e. three sequences taken out of the batch and run alone give the same bits
+    (outputs, logits, retained sets) as inside it."""
+    n_seqs, n, Hq, Hkv, D, window, budget = 300, 4000, 8, 8, 128, 512, 256
+    rng = np.random.default_rng(5)
+    cnnw = wl.make_cnn(rng, "bf16", Hkv, D, (5,), (32,), [1], 0.05)
+    cfg = B.make_cfg(Hq, Hkv, D, window, budget, 2, 0.0, 0.0, "bf16")
+    cnn = B.upload_cnn(cnnw.kernel, cnnw.dilation, cnnw.w, cnnw.bias, cnnw.w_out, cnnw.b_out, "bf16")
+    gen = torch.Generator("cuda").manual_seed(7)
+    T = n_seqs * n
+    rnd = lambda h: torch.randn((T, h, D), device="cuda", generator=gen, dtype=torch.float32).to(torch.bfloat16)
+    q, k, v = rnd(Hq), rnd(Hkv), rnd(Hkv)
+    assert k.numel() * 2 > 2 ** 31
+    cu = torch.arange(0, T + 1, n, dtype=torch.int32, device="cuda")
+    cache = B.alloc_cache(cfg, n_seqs)
+    logits = torch.empty((Hkv, T), dtype=torch.float32, device="cuda")
+    out = B.ltea_prefill(cfg, cnn, q, k, v, cu, n, cache, logits=logits)
+    torch.cuda.synchronize()
+    cu1 = torch.tensor([0, n], dtype=torch.int32, device="cuda")
+    for s in (0, 171, n_seqs - 1):
+        sl = slice(s * n, (s + 1) * n)
+        c1 = B.alloc_cache(cfg, 1)
+        l1 = torch.empty((Hkv, n), dtype=torch.float32, device="cuda")
+        o1 = B.ltea_prefill(cfg, cnn, q[sl], k[sl], v[sl], cu1, n, c1, logits=l1)
+        assert torch.equal(o1, out[sl]) and torch.equal(l1, logits[:, sl])
+        assert torch.equal(c1.ret_count[0], cache.ret_count[s]) and torch.equal(c1.ret_pos[0], cache.ret_pos[s])
+        assert torch.equal(c1.k_ret[0], cache.k_ret[s]) and torch.equal(c1.k_win[0], cache.k_win[s])
+        assert torch.equal(c1.win_score[0], cache.win_score[s])
