@@ -113,8 +113,8 @@ size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqle
   int32_t* n_seen = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
   int32_t* n_scored = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 4));
   float* d = reinterpret_cast<float*>(take((size_t)cfg.Hq * (size_t)total * 4));
-  float* fk = reinterpret_cast<float*>(take((size_t)kTrainFarChunks * heads * cap * cfg.D * 4));
-  float* fv = reinterpret_cast<float*>(take((size_t)kTrainFarChunks * heads * cap * cfg.D * 4));
+  float* fk = reinterpret_cast<float*>(take((size_t)train_far_chunks(n_seqs, cfg.Hkv) * heads * cap * cfg.D * 4));
+  float* fv = reinterpret_cast<float*>(take((size_t)train_far_chunks(n_seqs, cfg.Hkv) * heads * cap * cfg.D * 4));
   if (far_dk) *far_dk = fk;
   if (far_dv) *far_dv = fv;
   if (c) *c = ltea_cache{k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored};

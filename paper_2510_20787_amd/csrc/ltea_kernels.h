@@ -114,7 +114,7 @@ hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_s
                                  const void* dout, const float* lse, const float* logits, const float* lambda,
                                  const ltea_cache& kept, int kept_capacity, float* delta, float* far_dk, float* far_dv,
                                  void* dq, void* dk, void* dv, float* dz, int32_t* counts, hipStream_t stream);
-// far_dk / far_dv: fp32 scratch [kTrainFarChunks][n_seqs * Hkv][kept_capacity][D] each (used by the bf16 D = 64 path).
+// far_dk / far_dv: fp32 scratch [train_far_chunks(n_seqs, Hkv)][n_seqs * Hkv][kept_capacity][D] each (used by the bf16 path).
 
 // ---- deferred batched scoring of the decode cache ---------------------------------------------------------
 struct RescoreBuffers {

@@ -239,6 +239,7 @@ hipError_t launch_train_backward(const ltea_cfg& cfg, const void* q, int64_t q_s
   A.tau = cfg.tau_logit;
   A.ret_pos = kept.ret_pos; A.ret_count = kept.ret_count; A.k_ret = kept.k_ret; A.v_ret = kept.v_ret;
   A.max_seqlen = sv.max_seqlen;
+  A.far_chunks = train_far_chunks(sv.n_seqs, cfg.Hkv);
   A.lse = lse; A.logits = logits; A.lambda = lambda; A.delta = delta; A.far_dk = far_dk; A.far_dv = far_dv;
   A.dq = dq; A.dk = dk; A.dv = dv; A.dz = dz; A.counts = counts;
   if (cfg.dtype == LTEA_F32) return cfg.D == 64 ? run<float, 64>(A, stream) : run<float, 128>(A, stream);

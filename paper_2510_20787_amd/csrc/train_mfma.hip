@@ -323,19 +323,19 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
   int s, n, lo, h, j0 = 0, r_base = 0, cnt = 0;
   int chunk = 0;                          // FAR: which share of the query tiles this workgroup walks
   if (FAR) {
-    // one workgroup per (128 compact entries, share of the query range): kTrainFarChunks shares of equal length keep
+    // one workgroup per (128 compact entries, share of the query range): A.far_chunks shares of equal length keep
     // the workgroups short and alike; their partial sums go to one scratch slice each, which the band pass adds up
     // in a fixed order
     // The workgroups of one (head, share) read the same Q and dO tiles: order them so that they are neighbours, and
     // give each XCD a contiguous range of that order (workgroups are dealt round-robin to the 8 XCDs).
     const int per_head = (A.max_seqlen + BM - 1) / BM;
-    const int n_far = A.n_seqs * Hkv * kTrainFarChunks * per_head;
+    const int n_far = A.n_seqs * Hkv * A.far_chunks * per_head;
     const int per_xcd = (n_far + 7) / 8;
     const int work = (block % 8) * per_xcd + block / 8;
     if (work >= n_far) return;            // padding workgroups of the combined launch
     const int rest = work / per_head;
-    chunk = rest % kTrainFarChunks;
-    const int hd = rest / kTrainFarChunks;
+    chunk = rest % A.far_chunks;
+    const int hd = rest / A.far_chunks;
     r_base = (work - rest * per_head) * BM;
     s = hd / Hkv;
     h = hd - s * Hkv;
@@ -395,7 +395,7 @@ __device__ __forceinline__ void dkv_body(const TrainArgs& A, int tiles_upper, fl
 
   // ---- query tiles the workgroup has to visit (the same for every query head of the group) --------------------
   int qt_first, qt_last;
-  const int chunk_tiles = ((n + BN - 1) / BN + kTrainFarChunks - 1) / kTrainFarChunks;   // query tiles per share
+  const int chunk_tiles = ((n + BN - 1) / BN + A.far_chunks - 1) / A.far_chunks;   // query tiles per share
   if (FAR) {
     qt_first = (rp[r_base] + window) / BN;            // positions ascend: the first entry is seen first
     qt_last = (n - 1) / BN;
@@ -687,7 +687,7 @@ bool train_mfma_supported(const TrainArgs& A, int D) {
 }
 
 // delta, then [far pass of dK / dV | dQ] in one launch, then the band pass of dK / dV (which adds the far pass in).
-// far_dk / far_dv: fp32 scratch, [kTrainFarChunks][n_seqs * Hkv][budget][64] each (only rows below ret_count are touched).
+// far_dk / far_dv: fp32 scratch, [far_chunks][n_seqs * Hkv][budget][D] each (only rows below ret_count are touched).
 namespace {
 template <int D>
 hipError_t run_mfma(const TrainArgs& A, hipStream_t stream) {
@@ -699,7 +699,7 @@ hipError_t run_mfma(const TrainArgs& A, hipStream_t stream) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int per_head = (A.max_seqlen + BM - 1) / BM;
-  int64_t far_blocks = A.budget > 0 ? (int64_t)A.n_seqs * A.Hkv * per_head * kTrainFarChunks : 0;
+  int64_t far_blocks = A.budget > 0 ? (int64_t)A.n_seqs * A.Hkv * per_head * A.far_chunks : 0;
   far_blocks = (far_blocks + 7) / 8 * 8;      // keeps the dQ role's workgroup-to-XCD pattern
   const int64_t tiles_upper = (A.total + BM - 1) / BM + A.n_seqs;
   const int64_t n_work = tiles_upper * A.Hq;
