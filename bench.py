@@ -425,6 +425,58 @@ def bench_chunked(args):
             "ms_per_pass": ms, "tokens_per_s": w.total_tokens / (ms * 1e-3)}
 
 
+def bench_seqlen_sweep(args):
+    """Attention kernel alone against the sequence length, on the shape of the paper's kernel comparison (Section 4.3,
+    Figure 4a): the 1.4B model's heads (Hq=32 on Hkv=8, D=64), batch 32, window 1024 and an artificial half-full
+    out-of-window cache (256 of budget 512 entries per head, positions drawn uniformly, the same for every length so
+    that only the sequence length changes).  Three index sets through the same kernel: window + kept entries, window
+    only (budget 0), full causal attention (window = n).  Inputs are drawn on the device (timing only)."""
+    import torch
+    from paper_2510_20787_amd import binding as B
+    Hq, Hkv, D, window, budget, kept, batch = 32, 8, 64, 1024, 512, 256, 32
+    gen = torch.Generator(device="cuda").manual_seed(4)
+    rows = []
+    for n in (2048, 4096, 8192, 16384, 32768):
+        T = batch * n
+        q = torch.randn((T, Hq, D), generator=gen, device="cuda", dtype=torch.bfloat16)
+        k = torch.randn((T, Hkv, D), generator=gen, device="cuda", dtype=torch.bfloat16)
+        v = torch.randn((T, Hkv, D), generator=gen, device="cuda", dtype=torch.bfloat16)
+        out = torch.empty_like(q)
+        cu = torch.arange(batch + 1, dtype=torch.int32, device="cuda") * n
+        row = {"n": n, "tokens": T}
+        for name, w_, b_, c_ in (("lte", window, budget, kept), ("swa", window, 0, 0), ("full", n, 0, 0)):
+            cfg = B.make_cfg(Hq, Hkv, D, w_, b_, 0, 0.0, 0.0, "bf16")
+            cache = B.alloc_cache(cfg, batch)
+            pairs = Hq * batch * (w_ * (w_ + 1) // 2 + (n - w_) * w_)
+            if c_:
+                pos = torch.rand((batch, Hkv, n - w_), generator=gen, device="cuda").argsort(dim=-1)[..., :c_]
+                pos = pos.sort(dim=-1).values
+                cache.ret_pos[..., :c_] = pos.to(torch.int32)
+                cache.ret_count.fill_(c_)
+                tok = (pos + (torch.arange(batch, device="cuda") * n)[:, None, None]).reshape(-1)
+                hd = torch.arange(Hkv, device="cuda")[None, :, None].expand(batch, Hkv, c_).reshape(-1)
+                cache.k_ret[:, :, :c_] = k[tok, hd].reshape(batch, Hkv, c_, D)
+                cache.v_ret[:, :, :c_] = v[tok, hd].reshape(batch, Hkv, c_, D)
+                pairs += (Hq // Hkv) * int((n - w_ - pos.to(torch.int64)).clamp_(min=0).sum().item())
+            reps = 1 if name == "full" and n >= 16384 else 3
+            B.ltea_sparse_attention(cfg, q, k, v, cu, n, cache, out=out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                B.ltea_sparse_attention(cfg, q, k, v, cu, n, cache, out=out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            row[name] = {"ms": ms, "tflops": 4.0 * D * pairs / (ms * 1e-3) / 1e12}
+            log(f"[bench] seqlen sweep n={n} {name}: {ms:.3f} ms, {row[name]['tflops']:.0f} TFLOP/s")
+            del cache
+        rows.append(row)
+        del q, k, v, out
+    return {"workload": f"attention kernel alone, B={batch}, Hq={Hq} on Hkv={Hkv}, D={D}, window={window}, {kept} kept "
+                        f"entries per head (artificial, budget {budget}); lte = window + kept, swa = window only, "
+                        "full = causal", "rows": rows}
+
+
 def cpu_baseline(w):
     """The oracle as it stands on a bounded sample of the same workload: whole sequences (all heads: scoring +
     retention + attention), as many as fit in about 12 s of wall time."""
@@ -501,6 +553,9 @@ def main():
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--chunks", type=int, default=1,
                     help="also time the prefill workload fed in this many pieces per sequence (continued prefill)")
+    ap.add_argument("--seqlen-sweep", action="store_true",
+                    help="also time the attention kernel alone against the sequence length (batch 32, 1.4B head "
+                         "shape, half-full artificial cache) for three index sets: window + kept, window, full causal")
     ap.add_argument("--workload", choices=["prefill", "long", "varlen", "paper"], default="prefill",
                     help="prefill = the benchmark configuration (default); long / varlen / paper = the other prefill "
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
@@ -556,6 +611,8 @@ def main():
     if args.chunks > 1:
         line["chunked_prefill"] = bench_chunked(args)
         log(f"[bench] chunked prefill: {line['chunked_prefill']['ms_per_pass']:.3f} ms per pass")
+    if args.seqlen_sweep:
+        line["seqlen_sweep"] = bench_seqlen_sweep(args)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)
