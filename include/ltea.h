@@ -259,6 +259,21 @@ size_t ltea_rescore_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, in
 int ltea_rescore(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope_or_null, const ltea_cache *cache,
                  int32_t n_seqs, int32_t *status_or_null, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ltea_prefill_append for models that cache rotated keys.  rope (required here): the ring's keys are rotated back at
+ * their positions for the scoring CNN, exactly as ltea_rescore does it.  k_feat_or_null: the new tokens' keys as they
+ * were before the rotation (same strides as k); NULL rotates the new keys back too (positions n_seen[s] + i), so the
+ * caller need not keep them.  k, the rotated keys, are what is cached and attended.  Results equal ltea_prefill_feat
+ * over the whole history up to the rounding of the keys that are rotated back.  status_or_null receives
+ * LTEA_ROPE_RANGE when a position lies beyond the tables (that key is scored as cached).  rope == NULL with
+ * k_feat == NULL is ltea_prefill_append; k_feat without rope is LTEA_EINVAL.  Requires n_scored = max(0, n_seen - rho)
+ * on entry like ltea_prefill_append.  Workspace: ltea_append_workspace_bytes. */
+int ltea_prefill_append_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope, const void *q,
+                             int64_t q_stride_tok, int64_t q_stride_head, const void *k, const void *v,
+                             const void *k_feat_or_null, int64_t kv_stride_tok, int64_t kv_stride_head,
+                             const int32_t *cu_new, int32_t n_seqs, int64_t total_new, int32_t max_new, void *out,
+                             const ltea_cache *cache, int32_t *status_or_null, void *workspace, size_t workspace_bytes,
+                             void *stream);
+
 /* ltea_decode_step without step 1: position t - window is evicted on the logit win_score already holds for it,
  * n_scored is left alone.  Arguments as ltea_decode_step; workspace: ltea_decode_workspace_bytes(cfg, NULL, n_seqs). */
 int ltea_decode_step_lazy(const ltea_cfg *cfg, const void *q, const void *k, const void *v, void *out,

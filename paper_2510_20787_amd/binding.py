@@ -57,7 +57,7 @@ class ltea_rope(C.Structure):
 
 EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_append_workspace_bytes",
-           "ltea_prefill_append", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
+           "ltea_prefill_append", "ltea_prefill_append_feat", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
            "ltea_lambda_update", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
@@ -106,6 +106,9 @@ def lib() -> C.CDLL:
     L.ltea_prefill_append.restype = C.c_int
     L.ltea_prefill_append.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, i64, i64, vp, vp, i64, i64, vp, i32, i64, i32, vp,
                                       P(ltea_cache), vp, sz, vp]
+    L.ltea_prefill_append_feat.restype = C.c_int
+    L.ltea_prefill_append_feat.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), vp, i64, i64, vp, vp, vp, i64, i64,
+                                           vp, i32, i64, i32, vp, P(ltea_cache), vp, vp, sz, vp]
     L.ltea_lazy_period.restype = i32
     L.ltea_lazy_period.argtypes = [P(ltea_cfg), P(ltea_cnn)]
     L.ltea_rescore_workspace_bytes.restype = sz
@@ -340,20 +343,31 @@ def ltea_append_workspace_bytes(cfg: ltea_cfg, cnn: Cnn, n_seqs: int, total_new:
 
 def ltea_prefill_append(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
                         cu_new: torch.Tensor, max_new: int, cache: Cache, out: Optional[torch.Tensor] = None,
-                        workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Continue a prefill: q, k, v hold the new tokens of every sequence, packed by cu_new."""
+                        workspace: Optional[torch.Tensor] = None, rope: Optional[Rope] = None,
+                        k_feat: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Continue a prefill: q, k, v hold the new tokens of every sequence, packed by cu_new.  rope (rotary models): the
+    cached keys are rotated, the ring is rotated back for the scoring; k_feat: the new keys before the rotation
+    (optional with rope: without it the new keys are rotated back too)."""
     T = q.shape[0]
     n_seqs = cu_new.numel() - 1
     qst, qsh = _tok_head_strides(q)
     st, sh = _tok_head_strides(k)
     assert _tok_head_strides(v) == (st, sh)
+    assert k_feat is None or _tok_head_strides(k_feat) == (st, sh)
     if out is None:
         out = torch.empty((T, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
     if workspace is None:
         workspace = _workspace(max(ltea_append_workspace_bytes(cfg, cnn, n_seqs, T, max_new), 16), q.device)
-    _check(lib().ltea_prefill_append(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
-                                     _ptr(cu_new), n_seqs, T, max_new, _ptr(out), C.byref(cache.struct),
-                                     _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill_append")
+    if rope is None and k_feat is None and status is None:
+        _check(lib().ltea_prefill_append(C.byref(cfg), C.byref(cnn.struct), _ptr(q), qst, qsh, _ptr(k), _ptr(v), st, sh,
+                                         _ptr(cu_new), n_seqs, T, max_new, _ptr(out), C.byref(cache.struct),
+                                         _ptr(workspace), workspace.numel(), _stream()), "ltea_prefill_append")
+    else:
+        _check(lib().ltea_prefill_append_feat(C.byref(cfg), C.byref(cnn.struct), C.byref(rope.struct) if rope else None,
+                                              _ptr(q), qst, qsh, _ptr(k), _ptr(v), _ptr(k_feat), st, sh, _ptr(cu_new),
+                                              n_seqs, T, max_new, _ptr(out), C.byref(cache.struct), _ptr(status),
+                                              _ptr(workspace), workspace.numel(), _stream()),
+               "ltea_prefill_append_feat")
     return out
 
 

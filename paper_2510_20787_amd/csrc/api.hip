@@ -59,6 +59,13 @@ int check_view(const void* p, int64_t st, int64_t sh, int D, int esz) {
   return LTEA_OK;
 }
 
+int check_rope(const ltea_cfg* cfg, const ltea_rope* rope) {
+  if (!rope->cos || !rope->sin || rope->n_pos < 1) return LTEA_EINVAL;
+  if (rope->rot_dim < 16 || rope->rot_dim > cfg->D || rope->rot_dim % 16 != 0) return LTEA_EINVAL;
+  if (rope->interleaved != 0 && rope->interleaved != 1) return LTEA_EINVAL;
+  return LTEA_OK;
+}
+
 int check_cache(const ltea_cfg* cfg, const ltea_cache* c, bool need_window) {
   if (!c) return LTEA_EINVAL;
   if (!c->ret_count || !c->n_seen || !c->n_scored) return LTEA_EINVAL;
@@ -289,7 +296,7 @@ size_t ltea_append_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int
   (void)max_new;
   if (check_cfg(cfg) != LTEA_OK || !cnn || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0 || total_new < 0) return 0;
   const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
-  return align_up(append_workspace(*cfg, n_seqs, total_new), 256) + score_workspace(*cfg, *cnn, ext);
+  return align_up(append_workspace(*cfg, n_seqs, total_new, true), 256) + score_workspace(*cfg, *cnn, ext);
 }
 
 int ltea_prefill_append(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, int64_t q_stride_tok,
@@ -297,17 +304,31 @@ int ltea_prefill_append(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q,
                         int64_t kv_stride_head, const int32_t* cu_new, int32_t n_seqs, int64_t total_new,
                         int32_t max_new, void* out, const ltea_cache* cache, void* workspace, size_t workspace_bytes,
                         void* stream) {
+  return ltea_prefill_append_feat(cfg, cnn, nullptr, q, q_stride_tok, q_stride_head, k, v, nullptr, kv_stride_tok,
+                                  kv_stride_head, cu_new, n_seqs, total_new, max_new, out, cache, nullptr, workspace,
+                                  workspace_bytes, stream);
+}
+
+int ltea_prefill_append_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope, const void* q,
+                             int64_t q_stride_tok, int64_t q_stride_head, const void* k, const void* v,
+                             const void* k_feat, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t* cu_new,
+                             int32_t n_seqs, int64_t total_new, int32_t max_new, void* out, const ltea_cache* cache,
+                             int32_t* status, void* workspace, size_t workspace_bytes, void* stream) {
   int st = check_cfg(cfg);
   if (st == LTEA_OK) st = check_cnn(cfg, cnn);
   if (st == LTEA_OK) st = check_seqs(cu_new, n_seqs, total_new, max_new);
   if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st == LTEA_OK && rope) st = check_rope(cfg, rope);
   if (st != LTEA_OK) return st;
+  // without the sinusoids there is no way back from the cached keys to the ones the CNN scored
+  if (k_feat && !rope) return LTEA_EINVAL;
   if (n_seqs == 0) return LTEA_OK;
   const int esz = elem_size(cfg->dtype);
   if (total_new > 0) {
     if ((st = check_view(q, q_stride_tok, q_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if ((st = check_view(k, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if ((st = check_view(v, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
+    if (k_feat && (st = check_view(k_feat, kv_stride_tok, kv_stride_head, cfg->D, esz)) != LTEA_OK) return st;
     if (!out || !aligned16(out)) return LTEA_EINVAL;
   }
   const int64_t ext_stride_tok = (int64_t)cfg->Hkv * cfg->D;
@@ -316,18 +337,18 @@ int ltea_prefill_append(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q,
   // the continuation's attention stage exists on the bf16 MFMA path only
   if (!attention_mfma_supported(*cfg, ext_stride_tok, (int32_t)ext_len_max)) return LTEA_EUNSUPPORTED;
   const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
-  const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new), 256);
+  const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new, rope != nullptr), 256);
   const size_t need = build_ws + score_workspace(*cfg, *cnn, ext);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int rho = cnn_rho(cnn);
   AppendBuffers buf;
-  st = hip_status(launch_append_build(*cfg, k, v, kv_stride_tok, kv_stride_head, cu_new, n_seqs, total_new, max_new,
-                                      *cache, workspace, &buf, s));
+  st = hip_status(launch_append_build(*cfg, k, v, k_feat, kv_stride_tok, kv_stride_head, cu_new, n_seqs, total_new,
+                                      max_new, rope, status, *cache, workspace, &buf, s));
   if (st != LTEA_OK) return st;
   SeqView sv_ext{buf.cu_ext, n_seqs, buf.total_ext, buf.max_ext_len};
   SeqView sv_score{buf.cu_score, n_seqs, buf.total_ext, 2 * buf.max_ext_len};
-  st = do_score(*cfg, *cnn, buf.ext_k, buf.ext_v, ext_stride_tok, cfg->D, sv_score, buf.ext_logits,
+  st = do_score(*cfg, *cnn, buf.ext_kf, buf.ext_v, ext_stride_tok, cfg->D, sv_score, buf.ext_logits,
                 static_cast<char*>(workspace) + build_ws, s);
   if (st != LTEA_OK) return st;
   st = hip_status(launch_append_keys(*cfg, n_seqs, total_new, *cache, rho, workspace, buf, s));
@@ -384,11 +405,7 @@ int ltea_rescore(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope
   if (st == LTEA_OK) st = check_cache(cfg, cache, true);
   if (st != LTEA_OK) return st;
   if (n_seqs < 0) return LTEA_EINVAL;
-  if (rope) {
-    if (!rope->cos || !rope->sin || rope->n_pos < 1) return LTEA_EINVAL;
-    if (rope->rot_dim < 16 || rope->rot_dim > cfg->D || rope->rot_dim % 16 != 0) return LTEA_EINVAL;
-    if (rope->interleaved != 0 && rope->interleaved != 1) return LTEA_EINVAL;
-  }
+  if (rope && (st = check_rope(cfg, rope)) != LTEA_OK) return st;
   if (n_seqs == 0) return LTEA_OK;
   const int64_t total = (int64_t)n_seqs * cfg->window;
   if (total >= (int64_t)1 << 31) return LTEA_EUNSUPPORTED;

@@ -20,8 +20,13 @@
 //   4. the attention kernel runs with the ring + new part of the extended sequence as keys and the new tokens as
 //      queries (kept positions expressed in that local frame; old kept entries get negative positions and are visible
 //      to every new query, as they should be).
+// Rotary models cache the keys after the rotation while the CNN scores them as they were before it.  For them the
+// extended sequence gets a second key buffer that only the scoring kernel reads: ring rows rotated back with the
+// model's sinusoids (as in the batched scoring of the decode ring), new rows taken from the caller's unrotated keys or
+// rotated back as well.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "rope_dev.h"
 
 namespace ltea {
 namespace {
@@ -108,15 +113,21 @@ append_rank_kernel(AppendPlan P, const int32_t* __restrict__ ret_pos, const int3
 
 struct BuildArgs {
   const char* k_new; const char* v_new; int64_t tok_bytes, head_bytes;   // new tokens [T][Hkv][D] view, in bytes
+  const char* kf_new;                // the new tokens' keys as the CNN wants them (same view), or null
   const int32_t* cu_new;
   const char* k_win; const char* v_win; const char* k_ret; const char* v_ret; const int32_t* ret_count;
   char* k_ext; char* v_ext;          // [total_ext][Hkv][D] contiguous
+  char* kf_ext;                      // scoring keys of the extended rows, or null when they are the cached keys
+  RopeDev rope;                      // cos == null: no rotation to undo
+  int32_t* status;
   int Hkv, window, budget, row_bytes;
 };
 
 // Extended K/V rows of one (sequence, head): blockIdx.y walks chunks of 128 extended rows.
+template <typename T>
 __global__ void __launch_bounds__(256)
 append_build_kernel(AppendPlan P, BuildArgs a) {
+  constexpr int EPP = Elems<T>::N;
   const int b = blockIdx.x / a.Hkv, h = blockIdx.x - b * a.Hkv;
   const int64_t head = (int64_t)b * a.Hkv + h;
   const int N = P.n_old[b], wo = P.w_old[b], F = P.prefix[b];
@@ -126,12 +137,16 @@ append_build_kernel(AppendPlan P, BuildArgs a) {
   const int sub = threadIdx.x / pieces, pc = threadIdx.x - sub * pieces;
   const int row_end = min((int)(blockIdx.y + 1) * 128, len);
   const int64_t new0 = a.cu_new[b];
+  bool out_of_tables = false;
   for (int e = blockIdx.y * 128 + sub; e < row_end; e += rows_per_pass) {
     const char* sk = nullptr;
     const char* sv = nullptr;
+    const char* sf = nullptr;   // a row of ready-made scoring keys
+    int p_rot = -1;             // position whose rotation has to be undone for the scoring keys
     if (e < pad) {
       // zero rows
     } else if (e < F) {
+      // an old kept entry: only its stored key takes part in the selection, its rows never reach a logit that is used
       const int slot = P.sorted_slot[head * a.budget + (e - pad)];
       sk = a.k_ret + (head * a.budget + slot) * a.row_bytes;
       sv = a.v_ret + (head * a.budget + slot) * a.row_bytes;
@@ -140,10 +155,13 @@ append_build_kernel(AppendPlan P, BuildArgs a) {
       const int slot = p % a.window;
       sk = a.k_win + (head * a.window + slot) * a.row_bytes;
       sv = a.v_win + (head * a.window + slot) * a.row_bytes;
+      p_rot = p;
     } else {
       const int64_t t = new0 + (e - F - wo);
       sk = a.k_new + t * a.tok_bytes + h * a.head_bytes;
       sv = a.v_new + t * a.tok_bytes + h * a.head_bytes;
+      if (a.kf_new != nullptr) sf = a.kf_new + t * a.tok_bytes + h * a.head_bytes;
+      else p_rot = N + (e - F - wo);
     }
     u32x4 xk = {0u, 0u, 0u, 0u}, xv = {0u, 0u, 0u, 0u};
     if (sk != nullptr) {
@@ -153,7 +171,18 @@ append_build_kernel(AppendPlan P, BuildArgs a) {
     const int64_t dst = ((int64_t)(e0 + e) * a.Hkv + h) * a.row_bytes;
     reinterpret_cast<u32x4*>(a.k_ext + dst)[pc] = xk;
     reinterpret_cast<u32x4*>(a.v_ext + dst)[pc] = xv;
+    if (a.kf_ext != nullptr) {
+      u32x4 xf = xk;
+      if (sf != nullptr) {
+        xf = reinterpret_cast<const u32x4*>(sf)[pc];
+      } else if (p_rot >= 0 && a.rope.cos != nullptr && pc * EPP < a.rope.rot_dim) {
+        if (p_rot >= a.rope.n_pos) out_of_tables = true;
+        else xf = unrotate_piece<T>(a.rope, p_rot, pc * EPP, xk, reinterpret_cast<const T*>(sk));
+      }
+      reinterpret_cast<u32x4*>(a.kf_ext + dst)[pc] = xf;
+    }
   }
+  if (out_of_tables && a.status != nullptr) atomicOr(a.status, LTEA_ROPE_RANGE);
 }
 
 // Selection keys over the extended sequence, written over the logits the scoring kernel produced.
@@ -214,13 +243,13 @@ int64_t append_ext_tokens(const ltea_cfg& cfg, int n_seqs, int64_t total_new) {
   return (int64_t)n_seqs * ((int64_t)cfg.budget + 2 * (int64_t)cfg.window) + total_new;
 }
 
-size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new) {
+size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new, bool feature_keys) {
   const int64_t ext = append_ext_tokens(cfg, n_seqs, total_new);
   const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   size_t b = 0;
   b += 7 * up256(sizeof(int32_t) * (size_t)(n_seqs + 1));                                 // per-sequence plan arrays
   b += 4 * up256(sizeof(int32_t) * (size_t)n_seqs * cfg.Hkv * (size_t)(cfg.budget > 0 ? cfg.budget : 1));  // sorted_pos, sorted_slot, local_pos, old counts
-  b += 2 * up256((size_t)ext * cfg.Hkv * cfg.D * esz);                                      // extended K, V
+  b += (feature_keys ? 3 : 2) * up256((size_t)ext * cfg.Hkv * cfg.D * esz);                 // extended K, V (, scoring keys)
   b += up256((size_t)ext * cfg.Hkv * sizeof(float));                                        // extended logits / keys
   return b;
 }
@@ -248,19 +277,23 @@ static size_t carve(const ltea_cfg& cfg, int n_seqs, int64_t total_new, char* ws
   ext_k = take((size_t)ext * cfg.Hkv * cfg.D * esz);
   ext_v = take((size_t)ext * cfg.Hkv * cfg.D * esz);
   ext_logits = reinterpret_cast<float*>(take((size_t)ext * cfg.Hkv * sizeof(float)));
+  // an optional third key buffer (scoring keys) follows; launch_append_build takes it from here
   return (size_t)(p - ws);
 }
 
 // Stage 1 of the continuation: plan, ranks, extended K/V.  Returns the device arrays later stages need.
-hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const void* v_new, int64_t stride_tok,
-                               int64_t stride_head, const int32_t* cu_new, int n_seqs, int64_t total_new,
-                               int32_t max_new, const ltea_cache& c, void* workspace, AppendBuffers* out,
-                               hipStream_t stream) {
+// With `rope` or `kf_new` given, out->ext_kf is a third buffer with the keys as the scoring CNN wants them.
+hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const void* v_new, const void* kf_new,
+                               int64_t stride_tok, int64_t stride_head, const int32_t* cu_new, int n_seqs,
+                               int64_t total_new, int32_t max_new, const ltea_rope* rope, int32_t* status,
+                               const ltea_cache& c, void* workspace, AppendBuffers* out, hipStream_t stream) {
   AppendPlan P;
   char *ext_k, *ext_v;
   float* ext_logits;
   int32_t* old_count;
-  carve(cfg, n_seqs, total_new, static_cast<char*>(workspace), P, ext_k, ext_v, ext_logits, old_count);
+  const size_t used = carve(cfg, n_seqs, total_new, static_cast<char*>(workspace), P, ext_k, ext_v, ext_logits, old_count);
+  const bool feature_keys = rope != nullptr || kf_new != nullptr;
+  char* ext_kf = feature_keys ? static_cast<char*>(workspace) + used : nullptr;
   const int64_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   const unsigned heads = (unsigned)n_seqs * (unsigned)cfg.Hkv;
   hipLaunchKernelGGL(append_plan_kernel, dim3(1), dim3(256), 0, stream, P, cu_new, c.n_seen, n_seqs, cfg.window, cfg.budget);
@@ -272,17 +305,21 @@ hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const voi
   if (e != hipSuccess) return e;
   BuildArgs a;
   a.k_new = static_cast<const char*>(k_new); a.v_new = static_cast<const char*>(v_new);
+  a.kf_new = static_cast<const char*>(kf_new);
   a.tok_bytes = stride_tok * esz; a.head_bytes = stride_head * esz; a.cu_new = cu_new;
   a.k_win = static_cast<const char*>(c.k_win); a.v_win = static_cast<const char*>(c.v_win);
   a.k_ret = static_cast<const char*>(c.k_ret); a.v_ret = static_cast<const char*>(c.v_ret);
-  a.ret_count = c.ret_count; a.k_ext = ext_k; a.v_ext = ext_v;
+  a.ret_count = c.ret_count; a.k_ext = ext_k; a.v_ext = ext_v; a.kf_ext = ext_kf;
+  a.rope = rope_dev(rope); a.status = status;
   a.Hkv = cfg.Hkv; a.window = cfg.window; a.budget = cfg.budget; a.row_bytes = (int)(cfg.D * esz);
   out->max_ext_len = cfg.budget + 2 * cfg.window + max_new;
   const unsigned chunks = (unsigned)((out->max_ext_len + 127) / 128);
-  hipLaunchKernelGGL(append_build_kernel, dim3(heads, chunks), dim3(256), 0, stream, P, a);
+  if (cfg.dtype == LTEA_F32) hipLaunchKernelGGL(append_build_kernel<float>, dim3(heads, chunks), dim3(256), 0, stream, P, a);
+  else hipLaunchKernelGGL(append_build_kernel<bf16_t>, dim3(heads, chunks), dim3(256), 0, stream, P, a);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  out->ext_k = ext_k; out->ext_v = ext_v; out->ext_logits = ext_logits; out->cu_ext = P.cu_ext; out->cu_score = P.cu_score;
+  out->ext_k = ext_k; out->ext_v = ext_v; out->ext_kf = ext_kf != nullptr ? ext_kf : ext_k;
+  out->ext_logits = ext_logits; out->cu_ext = P.cu_ext; out->cu_score = P.cu_score;
   out->kv_start = P.kv_start; out->kv_len = P.kv_len; out->local_pos = P.local_pos;
   out->total_ext = append_ext_tokens(cfg, n_seqs, total_new);
   return hipSuccess;

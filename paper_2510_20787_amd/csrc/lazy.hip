@@ -19,14 +19,10 @@
 // there); those rows are the left context of the first unscored position and are not read back.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "rope_dev.h"
 
 namespace ltea {
 namespace {
-
-struct RopeDev {
-  const float *cos, *sin;
-  int n_pos, rot_dim, interleaved;
-};
 
 struct PackArgs {
   const void *k_win, *v_win;
@@ -35,36 +31,6 @@ struct PackArgs {
   int32_t *cu, *plan, *status;
   int B, Hkv, D, window, rho, rows_per_block;
   RopeDev rope;
-};
-
-template <typename T> struct Elems;   // 16 bytes <-> fp32 values
-template <> struct Elems<float> {
-  static constexpr int N = 4;
-  static __device__ __forceinline__ void unpack(const u32x4& r, float (&x)[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) x[i] = __uint_as_float(r[i]);
-  }
-  static __device__ __forceinline__ u32x4 pack(const float (&x)[4]) {
-    return u32x4{__float_as_uint(x[0]), __float_as_uint(x[1]), __float_as_uint(x[2]), __float_as_uint(x[3])};
-  }
-};
-template <> struct Elems<bf16_t> {
-  static constexpr int N = 8;
-  static __device__ __forceinline__ void unpack(const u32x4& r, float (&x)[8]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      x[2 * i] = __uint_as_float(r[i] << 16);
-      x[2 * i + 1] = __uint_as_float(r[i] & 0xFFFF0000u);
-    }
-  }
-  static __device__ __forceinline__ u32x4 pack(const float (&x)[8]) {
-    u32x4 r;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      r[i] = (uint32_t)__builtin_bit_cast(uint16_t, from_f32<bf16_t>(x[2 * i])) |
-             ((uint32_t)__builtin_bit_cast(uint16_t, from_f32<bf16_t>(x[2 * i + 1])) << 16);
-    return r;
-  }
 };
 
 template <typename T>
@@ -101,7 +67,6 @@ rescore_pack_kernel(PackArgs A) {
   T* pk = static_cast<T*>(A.pk);
   T* pv = static_cast<T*>(A.pv);
   const int rot = A.rope.cos != nullptr ? A.rope.rot_dim : 0;
-  const int half = rot / 2;
   bool out_of_tables = false;
   for (int i = threadIdx.x; i < items; i += 256) {
     const int pc = i % pieces, h = (i / pieces) % Hkv, r = r_begin + i / (pieces * Hkv);
@@ -112,37 +77,9 @@ rescore_pack_kernel(PackArgs A) {
       const int64_t src = (((int64_t)b * Hkv + h) * window + p % window) * D;
       kraw = *reinterpret_cast<const u32x4*>(kw + src + pc * EPP);
       vraw = *reinterpret_cast<const u32x4*>(vw + src + pc * EPP);
-      const int e0 = pc * EPP;
-      if (e0 < rot) {
-        if (p >= A.rope.n_pos) {
-          out_of_tables = true;
-        } else {
-          // inverse rotation of pair (a, b): (a cos + b sin, -a sin + b cos)
-          const float* ct = A.rope.cos + (int64_t)p * half;
-          const float* st = A.rope.sin + (int64_t)p * half;
-          float x[EPP], y[EPP];
-          Elems<T>::unpack(kraw, x);
-          if (A.rope.interleaved) {
-#pragma unroll
-            for (int j = 0; j < EPP; j += 2) {
-              const float c = ct[(e0 + j) / 2], s = st[(e0 + j) / 2];
-              y[j] = fmaf(x[j + 1], s, x[j] * c);
-              y[j + 1] = fmaf(x[j + 1], c, -(x[j] * s));
-            }
-          } else {
-            const bool is_b = e0 >= half;                       // this piece holds the second members of its pairs
-            const int partner = is_b ? e0 - half : e0 + half;
-            float o[EPP];
-            Elems<T>::unpack(*reinterpret_cast<const u32x4*>(kw + src + partner), o);
-            const int i0 = is_b ? e0 - half : e0;
-#pragma unroll
-            for (int j = 0; j < EPP; ++j) {
-              const float c = ct[i0 + j], s = st[i0 + j];
-              y[j] = is_b ? fmaf(x[j], c, -(o[j] * s)) : fmaf(o[j], s, x[j] * c);
-            }
-          }
-          kraw = Elems<T>::pack(y);
-        }
+      if (pc * EPP < rot) {
+        if (p >= A.rope.n_pos) out_of_tables = true;
+        else kraw = unrotate_piece<T>(A.rope, p, pc * EPP, kraw, kw + src);
       }
     }
     *reinterpret_cast<u32x4*>(pk + dst) = kraw;
@@ -190,8 +127,7 @@ hipError_t launch_rescore_pack(const ltea_cfg& cfg, const ltea_rope* rope, const
   A.pk = buf.pk; A.pv = buf.pv; A.cu = buf.cu; A.plan = buf.plan; A.status = status;
   A.B = n_seqs; A.Hkv = cfg.Hkv; A.D = cfg.D; A.window = cfg.window; A.rho = rho;
   A.rows_per_block = 32;
-  A.rope = RopeDev{rope ? rope->cos : nullptr, rope ? rope->sin : nullptr, rope ? rope->n_pos : 0,
-                   rope ? rope->rot_dim : 0, rope ? rope->interleaved : 0};
+  A.rope = rope_dev(rope);
   const dim3 grid((unsigned)n_seqs, (unsigned)((cfg.window + A.rows_per_block - 1) / A.rows_per_block));
   if (cfg.dtype == LTEA_F32) hipLaunchKernelGGL(rescore_pack_kernel<float>, grid, dim3(256), 0, stream, A);
   else hipLaunchKernelGGL(rescore_pack_kernel<bf16_t>, grid, dim3(256), 0, stream, A);

@@ -72,6 +72,7 @@ hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_s
 // the scoring, retention and attention launchers are then pointed at.
 struct AppendBuffers {
   void* ext_k; void* ext_v;      // [total_ext][Hkv][D]
+  void* ext_kf;                  // the keys the scoring kernels read: ext_k, or a buffer of its own (rotary models)
   float* ext_logits;             // [Hkv][total_ext]
   const int32_t* cu_ext;         // [n_seqs + 1]
   const int32_t* cu_score;       // [n_seqs + 1] packing handed to the scoring kernels (pad rows of sequences whose
@@ -83,11 +84,11 @@ struct AppendBuffers {
   int32_t max_ext_len;           // upper bound of one extended sequence
 };
 int64_t append_ext_tokens(const ltea_cfg& cfg, int n_seqs, int64_t total_new);
-size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new);
-hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const void* v_new, int64_t stride_tok,
-                               int64_t stride_head, const int32_t* cu_new, int n_seqs, int64_t total_new,
-                               int32_t max_new, const ltea_cache& cache, void* workspace, AppendBuffers* out,
-                               hipStream_t stream);
+size_t append_workspace(const ltea_cfg& cfg, int n_seqs, int64_t total_new, bool feature_keys);
+hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const void* v_new, const void* kf_new,
+                               int64_t stride_tok, int64_t stride_head, const int32_t* cu_new, int n_seqs,
+                               int64_t total_new, int32_t max_new, const ltea_rope* rope, int32_t* status,
+                               const ltea_cache& cache, void* workspace, AppendBuffers* out, hipStream_t stream);
 hipError_t launch_append_keys(const ltea_cfg& cfg, int n_seqs, int64_t total_new, const ltea_cache& cache, int rho,
                               void* workspace, const AppendBuffers& buf, hipStream_t stream);
 hipError_t launch_append_fixup(const ltea_cfg& cfg, const int32_t* cu_new, int n_seqs, int64_t total_new,

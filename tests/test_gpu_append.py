@@ -53,7 +53,7 @@ def device_setup(w):
     return cfg, cnn
 
 
-def check_final_state(w, cache, ref_states, z64, eps):
+def check_final_state(w, cache, ref_states, z64, eps, logit_tol=LOGIT_TOL["bf16"]):
     near = check_sets(cache, z64, w, eps)
     assert len(near) <= max(1, w.n_seqs // 64), f"heads inside the decision margin: {near}"
     rho = w.cnn.rho
@@ -73,7 +73,7 @@ def check_final_state(w, cache, ref_states, z64, eps):
                 np.testing.assert_array_equal(vw[s, h, slot], w.v[lo + p, h])
             for p in range(max(0, n - w.window), max(0, n - rho)):
                 ref = z64[h, lo + p]
-                assert abs(float(zw[s, h, p % w.window]) - ref) <= LOGIT_TOL["bf16"] * max(1.0, abs(ref))
+                assert abs(float(zw[s, h, p % w.window]) - ref) <= logit_tol * max(1.0, abs(ref))
             for r in range(int(cnts[s, h])):
                 np.testing.assert_array_equal(kr[s, h, r], w.k[lo + poss[s, h, r], h])
                 np.testing.assert_array_equal(vr[s, h, r], w.v[lo + poss[s, h, r], h])
@@ -230,3 +230,89 @@ def test_append_to_a_history_shorter_than_the_receptive_field(n_first):
                 err = float(np.abs(out[off: off + m[s], hq] - ref_out[rows, hq]).max())
                 assert err <= OUT_TOL["bf16"] * float(np.abs(ref_out[rows, hq]).max()), (s, hq, err)
         off += m[s]
+
+
+@pytest.mark.parametrize("interleaved,give_k_feat,rot_dim", [(False, True, 64), (True, False, 64), (False, False, 32)])
+def test_append_for_a_rotary_model(interleaved, give_k_feat, rot_dim):
+    """Rotary models cache rotated keys and score unrotated ones.  First chunk: ltea_prefill with k_feat.  Second chunk:
+    ltea_prefill_append_feat with the model's tables; the ring is rotated back for the scoring, the new keys come
+    unrotated from the caller or are rotated back as well.  Oracle: one prefill over the whole history whose logits
+    come from the same keys the device scored (exact ones where the first call scored them, rotated-back and rounded
+    ones afterwards), everything else from the rotated keys."""
+    import dataclasses
+    lens, Hq, Hkv, D, window, budget, sink = [420, 260, 90], 4, 2, 64, 64, 24, 2
+    w = wl.make_prefill("append_rotary", 8800 + rot_dim + int(interleaved), "bf16", lens, Hq, Hkv, D, window, budget, sink,
+                        0.0, cnn_kernel=(3, 3), cnn_channels=(32, 16), cnn_dilation=(2, 1), w_std=0.1)
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    rho = w.cnn.rho
+    cos, sin = wl.rope_tables(max(lens) + 1, rot_dim, 100.0)
+    rope_o = orc.OracleRope(cos.astype(np.float64), sin.astype(np.float64), interleaved)
+    rope_g = B.upload_rope(cos, sin, interleaved)
+    to_bf16 = lambda x: wl.to_storage(np.asarray(x, np.float32), "bf16")
+    cu = w.cu_seqlens
+    cut = [200, 100, 30]                      # ring full / full / still filling (the sequence start is in the ring)
+    k_pre = w.k
+    k_post, k_back = np.zeros_like(k_pre), np.zeros_like(k_pre)
+    for s in range(w.n_seqs):
+        lo = int(cu[s])
+        for p in range(lens[s]):
+            k_post[lo + p] = to_bf16(orc.rope_rotate(k_pre[lo + p], p, rope_o))
+            k_back[lo + p] = to_bf16(orc.rope_rotate(k_post[lo + p].astype(np.float64), p, rope_o, inverse=True))
+    # the keys each logit was scored from
+    feat_late = k_back.copy()
+    if give_k_feat:
+        for s in range(w.n_seqs):
+            feat_late[int(cu[s]) + cut[s]: int(cu[s + 1])] = k_pre[int(cu[s]) + cut[s]: int(cu[s + 1])]
+    z_first = orc.score(k_pre, w.v, ocnn, cu)
+    z_late = orc.score(feat_late, w.v, ocnn, cu)
+    z64 = z_late.copy()
+    for s in range(w.n_seqs):
+        lo = int(cu[s])
+        z64[:, lo: lo + max(0, cut[s] - rho)] = z_first[:, lo: lo + max(0, cut[s] - rho)]
+    wp = dataclasses.replace(w, k=k_post)
+    ref_out = np.zeros((w.total_tokens, Hq, D))
+    for s in range(w.n_seqs):
+        lo, hi = int(cu[s]), int(cu[s + 1])
+        kept = [orc.retain(z64[h, lo:hi], hi - lo, window, budget, sink, 0.0) for h in range(Hkv)]
+        ref_out[lo:hi] = orc.sparse_attention_sequence(w.q[lo:hi], k_post[lo:hi], w.v[lo:hi], ocfg, kept)
+    cfg, cnn = device_setup(w)
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    zero = [0] * w.n_seqs
+    q, k, v, kf = (dev(pack(x, cu, zero, cut), "bf16") for x in (w.q, k_post, w.v, k_pre))
+    B.ltea_prefill(cfg, cnn, q, k, v, torch.from_numpy(cu_of(cut)).cuda(), max(cut), cache, k_feat=kf)
+    m = [lens[s] - cut[s] for s in range(w.n_seqs)]
+    q, k, v, kf = (dev(pack(x, cu, cut, lens), "bf16") for x in (w.q, k_post, w.v, k_pre))
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = to_np(B.ltea_prefill_append(cfg, cnn, q, k, v, torch.from_numpy(cu_of(m)).cuda(), max(m), cache, rope=rope_g,
+                                      k_feat=kf if give_k_feat else None, status=status))
+    assert int(status.item()) == 0
+    skip = check_final_state(wp, cache, None, z64, 2e-4, logit_tol=2e-3)
+    G = Hq // Hkv
+    off = 0
+    for s in range(w.n_seqs):
+        rows = slice(int(cu[s]) + cut[s], int(cu[s]) + lens[s])
+        for hq in range(Hq):
+            if (s, hq // G) not in skip:
+                err = float(np.abs(out[off: off + m[s], hq] - ref_out[rows, hq]).max())
+                assert err <= OUT_TOL["bf16"] * max(1.0, float(np.abs(ref_out[rows, hq]).max())), (s, hq, err)
+        off += m[s]
+
+
+def test_append_rotary_arguments_and_table_range():
+    """k_feat without tables is refused; positions beyond the tables raise the status bit and leave the call defined."""
+    lens = [100]
+    w = wl.make_prefill("append_rotary_args", 31, "bf16", lens, 2, 2, 64, 32, 8, 0, 0.0, cnn_kernel=(3,), cnn_channels=(16,))
+    cfg, cnn = device_setup(w)
+    cache = B.alloc_cache(cfg, 1)
+    q, k, v = (dev(x, "bf16") for x in (w.q, w.k, w.v))
+    cu1 = torch.tensor([0, 60], dtype=torch.int32, device="cuda")
+    B.ltea_prefill(cfg, cnn, q[:60], k[:60], v[:60], cu1, 60, cache)
+    cu2 = torch.tensor([0, 40], dtype=torch.int32, device="cuda")
+    with pytest.raises(RuntimeError):
+        B.ltea_prefill_append(cfg, cnn, q[60:], k[60:], v[60:], cu2, 40, cache, k_feat=k[60:])
+    cos, sin = wl.rope_tables(70, 64, 100.0)              # positions 70..99 are beyond the tables
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = B.ltea_prefill_append(cfg, cnn, q[60:], k[60:], v[60:], cu2, 40, cache, rope=B.upload_rope(cos, sin, False),
+                                status=status)
+    assert int(status.item()) & B.LTEA_ROPE_RANGE
+    assert int(cache.n_seen[0]) == 100 and bool(torch.isfinite(out.float()).all())
