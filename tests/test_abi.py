@@ -169,6 +169,18 @@ def test_append_argument_errors():
     assert call(args(cfg=C.byref(f32))) == B.LTEA_EUNSUPPORTED            # continuation exists on the bf16 path only
     assert L.ltea_append_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 32, 32) > 0
     assert L.ltea_append_workspace_bytes(None, C.byref(cnn), 1, 32, 32) == 0
+    # the rotary form: tables are validated, unrotated keys without tables are refused
+    feat = lambda a, rope, kf: L.ltea_prefill_append_feat(a["cfg"], a["cnn"], rope, a["q"], a["qst"], a["qsh"], a["k"],
+                                                          a["v"], kf, a["st"], a["sh"], a["cu"], a["n_seqs"], a["total"],
+                                                          a["max_new"], a["out"], a["cache"], None, a["ws"],
+                                                          a["ws_bytes"], a["stream"])
+    rope = B.ltea_rope(0x1000, 0x1000, 64, 64, 0)
+    assert feat(args(), None, 0x1000) == B.LTEA_EINVAL
+    assert feat(args(ws=None), C.byref(rope), 0x1000) == B.LTEA_EWORKSPACE     # everything before the workspace passed
+    assert feat(args(), C.byref(B.ltea_rope(0x1000, 0x1000, 64, 24, 0)), None) == B.LTEA_EINVAL   # rot_dim % 16
+    assert feat(args(), C.byref(B.ltea_rope(None, 0x1000, 64, 64, 0)), None) == B.LTEA_EINVAL
+    assert feat(args(), C.byref(rope), 0x1008) == B.LTEA_EINVAL                # misaligned k_feat
+    assert feat(args(n_seqs=0, total=0, max_new=0), C.byref(rope), None) == B.LTEA_OK
 
 
 def test_lazy_argument_errors():
