@@ -259,6 +259,20 @@ size_t ltea_rescore_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, in
 int ltea_rescore(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope_or_null, const ltea_cache *cache,
                  int32_t n_seqs, int32_t *status_or_null, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ltea_decode_step for models that cache rotated keys: the keys in the receptive field of the token being finalised
+ * (ring rows of positions t - 2*rho .. t - 1) are rotated back with `rope` before the CNN sees them; the incoming
+ * token's scoring key is k_feat_or_null (contiguous [n_seqs][Hkv][D], the key before the rotation) or, when NULL, k
+ * rotated back at position t.  k, the rotated key, is what is cached and attended.  Same state and outputs as
+ * ltea_decode_step_lazy followed by ltea_rescore after every step.  rope == NULL scores the keys as they are (then
+ * k_feat must be NULL too).  status_or_null receives LTEA_ROPE_RANGE.  Works for every CNN shape ltea_score
+ * accepts (the windows are packed and scored by the prefill kernels: three more launches than ltea_decode_step).
+ * Workspace: ltea_decode_feat_workspace_bytes. */
+size_t ltea_decode_feat_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs);
+int ltea_decode_step_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope_or_null, const void *q,
+                          const void *k, const void *v, const void *k_feat_or_null, void *out, const ltea_cache *cache,
+                          int32_t n_seqs, int32_t *status_or_null, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
 /* ltea_prefill_append for models that cache rotated keys.  rope (required here): the ring's keys are rotated back at
  * their positions for the scoring CNN, exactly as ltea_rescore does it.  k_feat_or_null: the new tokens' keys as they
  * were before the rotation (same strides as k); NULL rotates the new keys back too (positions n_seen[s] + i), so the

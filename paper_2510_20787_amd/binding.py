@@ -57,7 +57,8 @@ class ltea_rope(C.Structure):
 
 EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_append_workspace_bytes",
-           "ltea_prefill_append", "ltea_prefill_append_feat", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
+           "ltea_prefill_append", "ltea_prefill_append_feat", "ltea_decode_feat_workspace_bytes",
+           "ltea_decode_step_feat", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
            "ltea_lambda_update", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
@@ -109,6 +110,11 @@ def lib() -> C.CDLL:
     L.ltea_prefill_append_feat.restype = C.c_int
     L.ltea_prefill_append_feat.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), vp, i64, i64, vp, vp, vp, i64, i64,
                                            vp, i32, i64, i32, vp, P(ltea_cache), vp, vp, sz, vp]
+    L.ltea_decode_feat_workspace_bytes.restype = sz
+    L.ltea_decode_feat_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32]
+    L.ltea_decode_step_feat.restype = C.c_int
+    L.ltea_decode_step_feat.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), vp, vp, vp, vp, vp, P(ltea_cache), i32,
+                                        vp, vp, sz, vp]
     L.ltea_lazy_period.restype = i32
     L.ltea_lazy_period.argtypes = [P(ltea_cfg), P(ltea_cnn)]
     L.ltea_rescore_workspace_bytes.restype = sz
@@ -398,6 +404,25 @@ def upload_rope(cos, sin, interleaved: bool = False, device="cuda") -> Rope:
     st = torch.as_tensor(sin).to(device=device, dtype=torch.float32).contiguous()
     assert ct.shape == st.shape and ct.dim() == 2
     return Rope(ltea_rope(ct.data_ptr(), st.data_ptr(), ct.shape[0], 2 * ct.shape[1], 1 if interleaved else 0), [ct, st])
+
+
+def ltea_decode_step_feat(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cache: Cache,
+                          rope: Optional[Rope] = None, k_feat: Optional[torch.Tensor] = None,
+                          out: Optional[torch.Tensor] = None, status: Optional[torch.Tensor] = None,
+                          workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eager decode step of a rotary model: k is the rotated key (cached, attended); the scoring sees the ring rotated
+    back and k_feat (the key before the rotation) or, without it, k rotated back."""
+    B = q.shape[0]
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and (k_feat is None or k_feat.is_contiguous())
+    if out is None:
+        out = torch.empty((B, cfg.Hq, cfg.D), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = _workspace(int(lib().ltea_decode_feat_workspace_bytes(C.byref(cfg), C.byref(cnn.struct), B)), q.device)
+    _check(lib().ltea_decode_step_feat(C.byref(cfg), C.byref(cnn.struct), C.byref(rope.struct) if rope else None,
+                                       _ptr(q), _ptr(k), _ptr(v), _ptr(k_feat), _ptr(out), C.byref(cache.struct), B,
+                                       _ptr(status), _ptr(workspace), workspace.numel(), _stream()),
+           "ltea_decode_step_feat")
+    return out
 
 
 def ltea_lazy_period(cfg: ltea_cfg, cnn: Cnn) -> int:

@@ -387,6 +387,44 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
                                        static_cast<hipStream_t>(stream)));
 }
 
+size_t ltea_decode_feat_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0) return 0;
+  const int rho = cnn_rho(cnn);
+  return align_up(decode_workspace(*cfg, n_seqs), 256) + align_up(decode_windows_layout(*cfg, rho, n_seqs, nullptr, nullptr), 256) +
+         score_workspace(*cfg, *cnn, (int64_t)n_seqs * (2 * rho + 1));
+}
+
+int ltea_decode_step_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope, const void* q, const void* k,
+                          const void* v, const void* k_feat, void* out, const ltea_cache* cache, int32_t n_seqs,
+                          int32_t* status, void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_cache(cfg, cache, true);
+  if (st == LTEA_OK && rope) st = check_rope(cfg, rope);
+  if (st != LTEA_OK) return st;
+  if (n_seqs < 0) return LTEA_EINVAL;
+  if (k_feat && !rope) return LTEA_EINVAL;   // no way back from the cached keys without the sinusoids
+  if (n_seqs == 0) return LTEA_OK;
+  if (!q || !k || !v || !out) return LTEA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || (k_feat && !aligned16(k_feat))) return LTEA_EINVAL;
+  const int rho = cnn_rho(cnn);
+  const int64_t rows = (int64_t)n_seqs * (2 * rho + 1);
+  if (rows >= (int64_t)1 << 30) return LTEA_EUNSUPPORTED;
+  const size_t step_ws = align_up(decode_workspace(*cfg, n_seqs), 256);
+  const size_t win_ws = align_up(decode_windows_layout(*cfg, rho, n_seqs, nullptr, nullptr), 256);
+  if (!workspace || workspace_bytes < step_ws + win_ws + score_workspace(*cfg, *cnn, rows)) return LTEA_EWORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  char* base = static_cast<char*>(workspace);
+  DecodeWindows w;
+  decode_windows_layout(*cfg, rho, n_seqs, base + step_ws, &w);
+  st = hip_status(launch_decode_windows(*cfg, rho, k, v, k_feat, rope, status, *cache, n_seqs, w, s));
+  if (st != LTEA_OK) return st;
+  SeqView sv{w.cu2, 2 * n_seqs, rows, 2 * rho + 1};
+  st = do_score(*cfg, *cnn, w.win_k, w.win_v, (int64_t)cfg->Hkv * cfg->D, cfg->D, sv, w.logits, base + step_ws + win_ws, s);
+  if (st != LTEA_OK) return st;
+  return hip_status(launch_decode_step_scored(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace, w.logits, rows, s));
+}
+
 int32_t ltea_lazy_period(const ltea_cfg* cfg, const ltea_cnn* cnn) {
   if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK) return 0;
   return cfg->window - 2 * cnn_rho(cnn);

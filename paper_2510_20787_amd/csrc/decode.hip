@@ -36,6 +36,7 @@
 
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "rope_dev.h"
 
 namespace ltea {
 namespace {
@@ -682,10 +683,14 @@ int lds_row_floats(const ltea_cfg& cfg, const ltea_cnn& cnn) {
 // rows b*R .. b*R + len - 1 (R = 2*rho + 1) holding positions max(0, t - 2*rho) .. t (the ring rows and, last, the
 // incoming token); a second, possibly empty pseudo-sequence covers the unused rest of the R rows so that the packing
 // stays contiguous without a prefix sum over the batch: cu2[2b] = b*R, cu2[2b+1] = b*R + len, cu2[2B] = B*R.
+// Rotary models (rope.cos != null): the ring holds rotated keys, which are rotated back here; the incoming token's
+// scoring key is kf_new when given, else k_new rotated back at position t.
 template <typename T>
 __global__ void __launch_bounds__(256)
-decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, T* __restrict__ win_k,
-                      T* __restrict__ win_v, int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho) {
+decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, const T* __restrict__ kf_new,
+                      RopeDev rope, int32_t* __restrict__ status, T* __restrict__ win_k, T* __restrict__ win_v,
+                      int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho) {
+  constexpr int EPP = Elems<T>::N;
   const int b = blockIdx.x;
   const int R = 2 * rho + 1;
   const int t = C.n_seen[b];
@@ -696,8 +701,9 @@ decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restri
     cu2[2 * b + 1] = b * R + len;
     if (b == B - 1) cu2[2 * B] = B * R;
   }
-  const int pieces = D * (int)sizeof(T) / 16;                 // 16-byte pieces per row
+  const int pieces = D / EPP;                                 // 16-byte pieces per row
   const int items = len * Hkv * pieces;
+  bool out_of_tables = false;
   for (int i = threadIdx.x; i < items; i += 256) {
     const int pc = i % pieces, h = (i / pieces) % Hkv, r = i / (pieces * Hkv);
     const int p = first + r;
@@ -705,9 +711,17 @@ decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restri
     const T* sk = p == t ? k_new + head * D : static_cast<const T*>(C.k_win) + (head * window + p % window) * D;
     const T* sv = p == t ? v_new + head * D : static_cast<const T*>(C.v_win) + (head * window + p % window) * D;
     const int64_t dst = ((int64_t)(b * R + r) * Hkv + h) * D;
-    reinterpret_cast<u32x4*>(win_k + dst)[pc] = reinterpret_cast<const u32x4*>(sk)[pc];
+    u32x4 xk = reinterpret_cast<const u32x4*>(sk)[pc];
+    if (p == t && kf_new != nullptr) {
+      xk = reinterpret_cast<const u32x4*>(kf_new + head * D)[pc];
+    } else if (rope.cos != nullptr && pc * EPP < rope.rot_dim) {
+      if (p >= rope.n_pos) out_of_tables = true;
+      else xk = unrotate_piece<T>(rope, p, pc * EPP, xk, sk);
+    }
+    reinterpret_cast<u32x4*>(win_k + dst)[pc] = xk;
     reinterpret_cast<u32x4*>(win_v + dst)[pc] = reinterpret_cast<const u32x4*>(sv)[pc];
   }
+  if (out_of_tables && status != nullptr) atomicOr(status, LTEA_ROPE_RANGE);
 }
 
 struct PreScore {            // buffers of the window-scoring path, carved from the tail of the workspace
@@ -742,7 +756,8 @@ size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char
 // cnn_or_null == nullptr selects the lazy step (no scoring; `status` receives LTEA_LATE_SCORING).
 template <typename T, int D>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, const void* k, const void* v, void* out,
-               const ltea_cache& c, int n_seqs, void* workspace, bool prescore, int32_t* status, hipStream_t stream) {
+               const ltea_cache& c, int n_seqs, void* workspace, bool prescore, int32_t* status, hipStream_t stream,
+               const float* given_logits = nullptr, int64_t given_total = 0) {
   const bool lazy = cnn_or_null == nullptr;
   ltea_cnn none;
   memset(&none, 0, sizeof(none));
@@ -788,7 +803,8 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
       PreScore ps;
       prescore_bytes(cfg, cnn, n_seqs, static_cast<char*>(workspace) + up256(base_workspace(cfg, n_seqs)), &ps);
       hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
-                         static_cast<const T*>(k), static_cast<const T*>(v), static_cast<T*>(ps.win_k),
+                         static_cast<const T*>(k), static_cast<const T*>(v), static_cast<const T*>(nullptr),
+                         rope_dev(nullptr), static_cast<int32_t*>(nullptr), static_cast<T*>(ps.win_k),
                          static_cast<T*>(ps.win_v), ps.cu2, n_seqs, cfg.Hkv, cfg.D, cfg.window, P.rho);
       hipError_t e0 = hipGetLastError();
       if (e0 != hipSuccess) return e0;
@@ -800,6 +816,12 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
       P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
       lds_bytes = 0;
     }
+  }
+  if (given_logits != nullptr) {   // the caller has scored the windows already (rotary models): only pick the logits
+    P.pre_logits = given_logits;
+    P.pre_total = given_total;
+    P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
+    lds_bytes = 0;
   }
   float* partial = static_cast<float*>(workspace);
   float* ws_logit = partial + partial_floats(cfg, n_seqs, P.nsplit);
@@ -855,6 +877,47 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
   const bool prescore = window_scoring(cfg, cnn) && workspace_bytes >= decode_workspace_full(cfg, cnn, n_seqs);
   return cfg.D == 64 ? run<bf16_t, 64>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, prescore, nullptr, stream)
                      : run<bf16_t, 128>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, prescore, nullptr, stream);
+}
+
+size_t decode_windows_layout(const ltea_cfg& cfg, int rho, int n_seqs, void* base, DecodeWindows* out) {
+  const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
+  const size_t rows = (size_t)n_seqs * (2 * rho + 1);
+  char* p = static_cast<char*>(base);
+  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  void* wk = take(rows * cfg.Hkv * cfg.D * esz);
+  void* wv = take(rows * cfg.Hkv * cfg.D * esz);
+  int32_t* cu2 = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * (size_t)n_seqs + 1)));
+  float* lg = reinterpret_cast<float*>(take(sizeof(float) * rows * cfg.Hkv));
+  if (out) { out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->total = (int64_t)rows; }
+  return (size_t)(p - static_cast<char*>(base));
+}
+
+hipError_t launch_decode_windows(const ltea_cfg& cfg, int rho, const void* k, const void* v, const void* k_feat,
+                                 const ltea_rope* rope, int32_t* status, const ltea_cache& c, int n_seqs,
+                                 const DecodeWindows& w, hipStream_t stream) {
+  CacheDev C{c.k_win, c.v_win, c.win_score, c.k_ret, c.v_ret, c.ret_score, c.ret_pos, c.ret_count, c.n_seen, c.n_scored};
+  auto go = [&](auto tag) {
+    using T = decltype(tag);
+    hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
+                       static_cast<const T*>(k), static_cast<const T*>(v), static_cast<const T*>(k_feat), rope_dev(rope),
+                       status, static_cast<T*>(w.win_k), static_cast<T*>(w.win_v), w.cu2, n_seqs, cfg.Hkv, cfg.D,
+                       cfg.window, rho);
+  };
+  if (cfg.dtype == LTEA_F32) go(float{});
+  else go(bf16_t{});
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_step_scored(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k,
+                                     const void* v, void* out, const ltea_cache& c, int n_seqs, void* workspace,
+                                     const float* logits, int64_t logits_total, hipStream_t stream) {
+  if (n_seqs == 0) return hipSuccess;
+  if (cfg.dtype == LTEA_F32) {
+    return cfg.D == 64 ? run<float, 64>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream, logits, logits_total)
+                       : run<float, 128>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream, logits, logits_total);
+  }
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream, logits, logits_total)
+                     : run<bf16_t, 128>(cfg, &cnn, q, k, v, out, c, n_seqs, workspace, false, nullptr, stream, logits, logits_total);
 }
 
 hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const void* k, const void* v, void* out,

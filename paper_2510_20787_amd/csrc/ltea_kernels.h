@@ -102,6 +102,23 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
                               void* out, const ltea_cache& cache, int n_seqs, void* workspace, size_t workspace_bytes,
                               hipStream_t stream);
 
+// Eager step of a rotary model in three parts: the receptive-field windows of the tokens being finalised are packed
+// (ring keys rotated back, the incoming key from k_feat or rotated back too), any prefill scoring launcher runs over
+// them (2 * n_seqs pseudo-sequences `cu2`, rows of [Hkv][D]), and the step proper picks its logits from `logits`.
+struct DecodeWindows {
+  void* win_k; void* win_v;   // [n_seqs * (2 rho + 1)][Hkv][D]
+  int32_t* cu2;               // [2 * n_seqs + 1]
+  float* logits;              // [Hkv][total]
+  int64_t total;              // n_seqs * (2 rho + 1)
+};
+size_t decode_windows_layout(const ltea_cfg& cfg, int rho, int n_seqs, void* base, DecodeWindows* out);
+hipError_t launch_decode_windows(const ltea_cfg& cfg, int rho, const void* k, const void* v, const void* k_feat,
+                                 const ltea_rope* rope, int32_t* status, const ltea_cache& cache, int n_seqs,
+                                 const DecodeWindows& w, hipStream_t stream);
+hipError_t launch_decode_step_scored(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k,
+                                     const void* v, void* out, const ltea_cache& cache, int n_seqs, void* workspace,
+                                     const float* logits, int64_t logits_total, hipStream_t stream);
+
 hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const void* k, const void* v, void* out,
                                    const ltea_cache& cache, int n_seqs, int32_t* status, void* workspace,
                                    hipStream_t stream);

@@ -183,6 +183,35 @@ def test_append_argument_errors():
     assert feat(args(n_seqs=0, total=0, max_new=0), C.byref(rope), None) == B.LTEA_OK
 
 
+def test_decode_feat_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    cache = B.ltea_cache()
+    for name, _ in cache._fields_:
+        setattr(cache, name, 0x1000)
+    need = L.ltea_decode_feat_workspace_bytes(C.byref(cfg), C.byref(cnn), 4)
+    assert need > L.ltea_decode_workspace_bytes(C.byref(cfg), None, 4)
+    assert L.ltea_decode_feat_workspace_bytes(None, C.byref(cnn), 4) == 0
+    rope = B.ltea_rope(0x1000, 0x1000, 64, 64, 0)
+    call = lambda **kw: (lambda a: L.ltea_decode_step_feat(a["cfg"], a["cnn"], a["rope"], a["q"], a["k"], a["v"], a["kf"],
+                                                            a["out"], a["cache"], a["n"], None, a["ws"], a["wsb"], None))(
+        dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), rope=C.byref(rope), q=0x1000, k=0x1000, v=0x1000, kf=None,
+                  out=0x1000, cache=C.byref(cache), n=4, ws=0x1000, wsb=need), **kw))
+    assert call(cfg=None) == B.LTEA_EINVAL
+    assert call(cnn=None) == B.LTEA_EINVAL
+    assert call(cache=None) == B.LTEA_EINVAL
+    assert call(q=None) == B.LTEA_EINVAL
+    assert call(k=0x1004) == B.LTEA_EINVAL
+    assert call(kf=0x1008) == B.LTEA_EINVAL
+    assert call(rope=None, kf=0x1000) == B.LTEA_EINVAL                     # unrotated keys without tables
+    assert call(rope=C.byref(B.ltea_rope(0x1000, None, 64, 64, 0))) == B.LTEA_EINVAL
+    assert call(rope=C.byref(B.ltea_rope(0x1000, 0x1000, 64, 128, 0))) == B.LTEA_EINVAL   # rot_dim > D
+    assert call(n=-1) == B.LTEA_EINVAL
+    assert call(n=0) == B.LTEA_OK
+    assert call(ws=None) == B.LTEA_EWORKSPACE
+    assert call(wsb=need - 1) == B.LTEA_EWORKSPACE
+
+
 def test_lazy_argument_errors():
     L = B.lib()
     cfg, cnn = good_cfg(), fake_cnn()

@@ -243,5 +243,58 @@ def compare_ring_logits_new(cache, states, w, tol, z_prefill):
         for h in range(w.Hkv):
             for p, zp in st.heads[h].win_z.items():
                 zg = float(cache.win_score[s, h, p % w.window])
-                t = LOGIT_TOL["bf16"] if p < n0 - w.cnn.rho else tol
+                t = LOGIT_TOL[w.dtype] if p < n0 - w.cnn.rho else tol
                 assert abs(zg - zp) <= t * max(1.0, abs(zp)), (s, h, p, zg, zp)
+
+
+@pytest.mark.parametrize("dtype,kernel,channels,dilation,interleaved,give_k_feat",
+                         [("bf16", (5,), (32,), None, False, False), ("bf16", (3, 3), (32, 16), (2, 1), True, False),
+                          ("f32", (3,), (16,), None, False, False), ("bf16", (5,), (32,), None, True, True)])
+def test_rotary_eager_decode(dtype, kernel, channels, dilation, interleaved, give_k_feat):
+    """ltea_decode_step_feat: the eager step of a model that caches rotated keys, on every kind of scoring kernel
+    (single-layer MFMA, fused multi-layer, fp32 layered), from an empty cache and after a prefill.  Oracle: a lazy step
+    followed by a batched scoring with the inverse rotation after every step, which finalises the same logit from
+    the same keys.  With k_feat the incoming token is scored from the exact key instead of the rotated-back one, one
+    rounding less than the oracle's procedure: its logits are compared, not its sets."""
+    lens, Hq, Hkv, D, window, budget, sink = [90, 0, 3], 4, 2, 64, 24, 8, 1
+    w = wl.make_prefill("rotary_eager", 515 + len(kernel) + int(interleaved), dtype, lens, Hq, Hkv, D, window, budget, sink,
+                        0.0, cnn_kernel=kernel, cnn_channels=channels, cnn_dilation=dilation, w_std=0.1)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    n_dec = 45
+    cos, sin = wl.rope_tables(max(lens) + n_dec + 1, 32, 100.0)          # half of the dimensions are rotated
+    rope_o = orc.OracleRope(cos.astype(np.float64), sin.astype(np.float64), interleaved)
+    rope_g = B.upload_rope(cos, sin, interleaved)
+    store = lambda x: wl.to_storage(np.asarray(x, np.float32), dtype)
+    rounder = lambda x: store(x).astype(np.float64)
+    k_pre = w.k
+    k_post = np.zeros_like(k_pre)
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        for p in range(hi - lo):
+            k_post[lo + p] = store(orc.rope_rotate(k_pre[lo + p], p, rope_o))
+    z64 = orc.score(k_pre, w.v, cnn, w.cu_seqlens)
+    states = []
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        kept = [orc.retain(z64[h, lo:hi], hi - lo, window, budget, sink, 0.0) for h in range(Hkv)]
+        states.append(orc.state_after_prefill(k_post[lo:hi], w.v[lo:hi], z64[:, lo:hi], cfg, w.cnn.rho, kept))
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    B.ltea_prefill(d.cfg, d.cnn, d.q, dev(k_post, dtype), d.v, d.cu, d.max_seqlen, cache, logits=logits, k_feat=d.k)
+    eps = logit_eps(to_np(logits), z64, dtype)
+    assert not check_sets(cache, z64, w, eps), "pick another seed: a head sits inside the decision margin"
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for t in range(n_dec):
+        q, k, v = wl.decode_inputs(w.seed, t, dtype, w.n_seqs, Hq, Hkv, D)
+        kp = np.stack([store(orc.rope_rotate(k[s], states[s].n_seen, rope_o)) for s in range(w.n_seqs)])
+        got = to_np(B.ltea_decode_step_feat(d.cfg, d.cnn, dev(q, dtype), dev(kp, dtype), dev(v, dtype), cache, rope=rope_g,
+                                            k_feat=dev(k, dtype) if give_k_feat else None, status=status))
+        ref = np.stack([orc.decode_step_lazy(states[s], q[s], kp[s], v[s], cfg) for s in range(w.n_seqs)])
+        for st in states:
+            orc.rescore(st, cfg, cnn, rope_o, rounder)
+        check_output(got, ref, dtype, f"rotary eager step {t}")
+        compare_ring_logits_new(cache, states, w, LOGIT_TOL_ROPE, z64)
+        if not give_k_feat:
+            compare_sets(cache, states, w, t)
+    assert int(status.item()) == 0
