@@ -731,7 +731,8 @@ struct PreScore {            // buffers of the window-scoring path, carved from 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 size_t base_workspace(const ltea_cfg& cfg, int n_seqs) {
-  return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
+  // sized for the larger of the two split counts
+  return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs, true)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
          (size_t)n_seqs * sizeof(int32_t);
 }
 
@@ -779,7 +780,6 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   P.B = n_seqs; P.Hq = cfg.Hq; P.Hkv = cfg.Hkv; P.D = cfg.D; P.window = cfg.window; P.budget = cfg.budget;
   P.sink = cfg.sink;
   P.rho = cnn_rho(&cnn);
-  P.nsplit = decode_num_splits(cfg, n_seqs);
   P.lds_row_floats = lds_row_floats(cfg, cnn);
   P.tau = cfg.tau_logit;
   P.scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
@@ -817,6 +817,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
       lds_bytes = 0;
     }
   }
+  P.nsplit = decode_num_splits(cfg, n_seqs, !lazy && P.pre_logits == nullptr && given_logits == nullptr);
   if (given_logits != nullptr) {   // the caller has scored the windows already (rotary models): only pick the logits
     P.pre_logits = given_logits;
     P.pre_total = given_total;
@@ -845,10 +846,16 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
 
 }  // namespace
 
-int decode_num_splits(const ltea_cfg& cfg, int n_seqs) {
+// Shares of a head's rows (one workgroup each).  Measured on MI355X: when the scoring runs inside the main launch
+// (single-layer bf16 CNN: a few long-running scoring workgroups) about 4096 streaming workgroups hide it best; when
+// the launch only streams (lazy steps, scores computed beforehand) about 1024 fat workgroups are faster, because the
+// per-workgroup prologue (eviction decision, query loads) and epilogue (cross-wave merge) then weigh less:
+// decode_bf16 lazy 136 -> 129 us/step, paper stack B=32 lazy 43 -> 29 us/step, B=128 lazy 90 -> 67 us/step.
+int decode_num_splits(const ltea_cfg& cfg, int n_seqs, bool scoring_inside) {
   const long heads = (long)n_seqs * cfg.Hkv;
   const int rows = cfg.window + cfg.budget;
-  int by_fill = (int)((4096 + heads - 1) / (heads > 0 ? heads : 1));  // aim for >= 4096 workgroups
+  const long target = scoring_inside ? 4096 : 1024;
+  int by_fill = (int)((target + heads - 1) / (heads > 0 ? heads : 1));
   int by_rows = (rows + 127) / 128;                                   // at least 128 rows per split
   int n = by_fill < by_rows ? by_fill : by_rows;
   if (n < 1) n = 1;

@@ -95,7 +95,7 @@ hipError_t launch_append_fixup(const ltea_cfg& cfg, const int32_t* cu_new, int n
                                const ltea_cache& cache, int rho, void* workspace, hipStream_t stream);
 
 // ---- (d) decode step -------------------------------------------------------------------------------
-int decode_num_splits(const ltea_cfg& cfg, int n_seqs);
+int decode_num_splits(const ltea_cfg& cfg, int n_seqs, bool scoring_inside);
 size_t decode_workspace(const ltea_cfg& cfg, int n_seqs);                               // minimum
 size_t decode_workspace_full(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs);     // enables every path
 hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* q, const void* k, const void* v,
