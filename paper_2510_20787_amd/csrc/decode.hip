@@ -392,7 +392,9 @@ __device__ __forceinline__ void score_new_tokens_mfma(const CnnDev& cnn, const S
 // Partial record per (sequence, query head, split): [max, sum, acc[D]] floats.
 // GT = query heads of a KV group handled per pass over the rows (1, 2 or 4): every K/V row is loaded once per pass
 // and used for GT queries, so grouped-query configurations do not re-stream the cache once per query head.
-template <typename T, int D, int GT>
+// SK = kernel size of the batched MFMA scoring role compiled into this instance (3, 5 or 7), 0 for none: the role's
+// register needs grow with the kernel size, and one instance holding all three would carry the largest one's spills.
+template <typename T, int D, int GT, int SK>
 __global__ void __launch_bounds__(kThreads, 4)
 decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q, const T* __restrict__ k_new,
                    const T* __restrict__ v_new, float* __restrict__ partial, float* __restrict__ ws_logit,
@@ -428,14 +430,12 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
       }
       return;
     }
-    if constexpr (sizeof(T) == 2) {
-      if (P.score_mfma) {
+    if constexpr (sizeof(T) == 2 && SK > 0) {
+      if (P.score_mfma) {   // == SK (the launcher picks the instance)
         const int h = blockIdx.x % Hkv, sg = blockIdx.x / Hkv;
         float* red = &red_acc[0][0][0];
         static_assert(sizeof(red_acc) >= 2048 * sizeof(float), "cross-wave scoring sums need 2048 floats");
-        if (P.score_mfma == 3) score_new_tokens_mfma<D, 3>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
-        else if (P.score_mfma == 5) score_new_tokens_mfma<D, 5>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
-        else score_new_tokens_mfma<D, 7>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
+        score_new_tokens_mfma<D, SK>(cnn, P, C, k_new, v_new, h, 64 * sg, red, ws_logit, ws_t);
         return;
       }
     }
@@ -829,14 +829,25 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   int32_t* ws_t = reinterpret_cast<int32_t*>(ws_logit + heads);
   const unsigned grid = (unsigned)P.n_score_blocks + heads * (unsigned)P.nsplit;
   const int G = cfg.Hq / cfg.Hkv;
-  auto launch_main = [&](auto gt) {
-    hipLaunchKernelGGL((decode_main_kernel<T, D, decltype(gt)::value>), dim3(grid), dim3(kThreads), lds_bytes, stream,
-                       cd, C, P, static_cast<const T*>(q), static_cast<const T*>(k), static_cast<const T*>(v), partial,
-                       ws_logit, ws_t);
+  auto launch_main = [&](auto gt, auto sk) {
+    hipLaunchKernelGGL((decode_main_kernel<T, D, decltype(gt)::value, decltype(sk)::value>), dim3(grid), dim3(kThreads),
+                       lds_bytes, stream, cd, C, P, static_cast<const T*>(q), static_cast<const T*>(k),
+                       static_cast<const T*>(v), partial, ws_logit, ws_t);
   };
-  if (G % 4 == 0) launch_main(std::integral_constant<int, 4>{});
-  else if (G % 2 == 0) launch_main(std::integral_constant<int, 2>{});
-  else launch_main(std::integral_constant<int, 1>{});
+  auto launch_gt = [&](auto sk) {
+    if (G % 4 == 0) launch_main(std::integral_constant<int, 4>{}, sk);
+    else if (G % 2 == 0) launch_main(std::integral_constant<int, 2>{}, sk);
+    else launch_main(std::integral_constant<int, 1>{}, sk);
+  };
+  const int sk_run = (P.pre_logits == nullptr && !lazy) ? P.score_mfma : 0;
+  if constexpr (sizeof(T) == 2) {
+    if (sk_run == 3) launch_gt(std::integral_constant<int, 3>{});
+    else if (sk_run == 5) launch_gt(std::integral_constant<int, 5>{});
+    else if (sk_run == 7) launch_gt(std::integral_constant<int, 7>{});
+    else launch_gt(std::integral_constant<int, 0>{});
+  } else {
+    launch_gt(std::integral_constant<int, 0>{});
+  }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(heads), dim3(kThreads), 0, stream, C, P,
