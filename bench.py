@@ -472,9 +472,99 @@ def bench_seqlen_sweep(args):
             del cache
         rows.append(row)
         del q, k, v, out
-    return {"workload": f"attention kernel alone, B={batch}, Hq={Hq} on Hkv={Hkv}, D={D}, window={window}, {kept} kept "
-                        f"entries per head (artificial, budget {budget}); lte = window + kept, swa = window only, "
-                        "full = causal", "rows": rows}
+    res = {"workload": f"attention kernel alone, B={batch}, Hq={Hq} on Hkv={Hkv}, D={D}, window={window}, {kept} kept "
+                       f"entries per head (artificial, budget {budget}); lte = window + kept, swa = window only, "
+                       "full = causal", "rows": rows}
+    res["layer"] = bench_paper_layer(args)
+    return res
+
+
+def bench_paper_layer(args):
+    """The whole token mixer of the paper's LTE layers (Section 4.3, Figure 4b/4c): 3 x (k=3, dilation 2) CNN, Hq=32 on
+    Hkv=8, D=64, window 768, budget 512, sink 4, batch 32.  Prefill (scoring + retention + cache fill + attention)
+    against the sequence length, then decode steps after a 4096-token prompt: eager (one logit finalised per step)
+    and lazy (one batched scoring per ltea_lazy_period() steps, amortised).  With the seeded random weights a head keeps
+    about 260 entries on N(0,1) inputs (reported), close to the mean the paper observed on its trained models.
+    Q, K, V are drawn on the device (timing only)."""
+    import torch
+    from paper_2510_20787_amd import binding as B
+    from paper_2510_20787_amd import workloads as wl
+    batch = 32
+    w = wl.config_paper_stack_bf16(n=64, B=1)          # the CNN weights and the shape
+    cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, "bf16")
+    c = w.cnn
+    cnn = B.prepare_cnn(cfg, B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, "bf16"))
+    gen = torch.Generator(device="cuda").manual_seed(6)
+    draw = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.bfloat16)
+    prefill = []
+    cache = B.alloc_cache(cfg, batch)
+    for n in (2048, 4096, 8192, 16384):
+        T = batch * n
+        q, k, v = draw(T, w.Hq, w.D), draw(T, w.Hkv, w.D), draw(T, w.Hkv, w.D)
+        out = torch.empty_like(q)
+        cu = torch.arange(batch + 1, dtype=torch.int32, device="cuda") * n
+        ws = torch.empty(B.ltea_workspace_bytes(cfg, cnn, batch, T, n), dtype=torch.uint8, device="cuda")
+        B.ltea_prefill(cfg, cnn, q, k, v, cu, n, cache, out=out, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            B.ltea_prefill(cfg, cnn, q, k, v, cu, n, cache, out=out, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 3
+        prefill.append({"n": n, "ms": ms, "tokens_per_s": T / (ms * 1e-3)})
+        log(f"[bench] paper layer prefill B={batch} n={n}: {ms:.3f} ms, {T / (ms * 1e-3) / 1e6:.1f} M tokens/s")
+        if n != 4096:
+            continue
+        # decode after this 4096-token prompt
+        kept = float(cache.ret_count.float().mean().item())
+        snap = {name: getattr(cache, name).clone() for name in ("k_win", "v_win", "win_score", "k_ret", "v_ret",
+                                                                 "ret_score", "ret_pos", "ret_count", "n_seen", "n_scored")}
+        dq, dk, dv = draw(batch, w.Hq, w.D), draw(batch, w.Hkv, w.D), draw(batch, w.Hkv, w.D)
+        dout = torch.empty_like(dq)
+        dws = B.decode_workspace(cfg, cnn, batch)
+        steps = 200
+        def timed(fn):
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / steps * 1e6
+        eager_us = timed(lambda: B.ltea_decode_step(cfg, cnn, dq, dk, dv, cache, out=dout, workspace=dws))
+        period = B.ltea_lazy_period(cfg, cnn)
+        status = torch.zeros(1, dtype=torch.int32, device="cuda")
+        rws = torch.empty(B.ltea_rescore_workspace_bytes(cfg, cnn, batch), dtype=torch.uint8, device="cuda")
+        lws = B.decode_workspace(cfg, None, batch)
+        assert 210 < period
+        lazy_us = timed(lambda: B.ltea_decode_step_lazy(cfg, dq, dk, dv, cache, out=dout, status=status, workspace=lws))
+        # one batched scoring of a full period's worth of positions
+        B.ltea_rescore(cfg, cnn, cache, status=status, workspace=rws)
+        oldest = torch.clamp(cache.n_seen - w.window + c.rho, min=0)
+        rescore_us = 0.0
+        for _ in range(5):
+            cache.n_scored.copy_(oldest)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.ltea_rescore(cfg, cnn, cache, status=status, workspace=rws)
+            torch.cuda.synchronize()
+            rescore_us += (time.perf_counter() - t0) / 5 * 1e6
+        streamed = int(batch * w.Hkv * (w.window + kept) * w.D * 2 * 2)
+        lazy_total = lazy_us + rescore_us / period
+        decode = {"prompt": n, "kept_per_head": kept, "eager_us_per_step": eager_us, "lazy_us_per_step": lazy_us,
+                  "rescore_us": rescore_us, "period": period, "lazy_amortised_us_per_step": lazy_total,
+                  "bytes_streamed_per_step": streamed, "lazy_gbs": streamed / (lazy_total * 1e-6) / 1e9,
+                  "status": int(status.item())}
+        log(f"[bench] paper layer decode B={batch} after {n}: eager {eager_us:.1f} us/step, lazy {lazy_us:.1f} + "
+            f"{rescore_us:.0f}/{period} = {lazy_total:.1f} us/step")
+        for name, t in snap.items():
+            getattr(cache, name).copy_(t)
+        del q, k, v, out, ws
+    return {"workload": f"paper LTE layer: B={batch}, Hq={w.Hq} on Hkv={w.Hkv}, D={w.D}, window={w.window}, "
+                        f"budget={w.budget}, sink={w.sink}, CNN 3 x (k=3, dilation 2), weights re-laid once",
+            "prefill": prefill, "decode": decode}
 
 
 def cpu_baseline(w):
@@ -555,7 +645,9 @@ def main():
                     help="also time the prefill workload fed in this many pieces per sequence (continued prefill)")
     ap.add_argument("--seqlen-sweep", action="store_true",
                     help="also time the attention kernel alone against the sequence length (batch 32, 1.4B head "
-                         "shape, half-full artificial cache) for three index sets: window + kept, window, full causal")
+                         "shape, half-full artificial cache) for three index sets: window + kept, window, full causal; "
+                         "and the paper's whole LTE layer (CNN scoring, retention, attention; decode after a 4096-token "
+                         "prompt) at batch 32")
     ap.add_argument("--workload", choices=["prefill", "long", "varlen", "paper"], default="prefill",
                     help="prefill = the benchmark configuration (default); long / varlen / paper = the other prefill "
                          "configurations, for kernel measurements (no CPU baseline, no decode section)")
