@@ -398,7 +398,7 @@ template <typename T, int D, int GT, int SK>
 __global__ void __launch_bounds__(kThreads, 4)
 decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q, const T* __restrict__ k_new,
                    const T* __restrict__ v_new, float* __restrict__ partial, float* __restrict__ ws_logit,
-                   int32_t* __restrict__ ws_t) {
+                   int32_t* __restrict__ ws_t, int32_t* __restrict__ ws_dst) {
   constexpr int EPL = Piece<T>::N;  // elements per lane
   constexpr int LPR = D / EPL;      // lanes per row
   constexpr int GPW = kWave / LPR;  // row groups per wave
@@ -477,6 +477,8 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
     dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
                           C.ret_pos + head * budget, red64, &slot_lds);
     cnt = cnt_old + (dst == cnt_old ? 1 : 0);
+    // the share that ends the slot space always gets here: it hands the decision to the finishing launch
+    if (split == nsplit - 1 && threadIdx.x == 0) ws_dst[head] = dst;
   }
   const T* k_evicted = kw + (int64_t)slot * D;  // old ring row that moves to compact slot dst
   const T* v_evicted = vw + (int64_t)slot * D;
@@ -594,9 +596,7 @@ template <typename T, int D>
 __global__ void __launch_bounds__(kThreads)
 decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, const T* __restrict__ v_new,
                      const float* __restrict__ partial, const float* __restrict__ ws_logit,
-                     const int32_t* __restrict__ ws_t, T* __restrict__ out) {
-  __shared__ unsigned long long red64[kWaves];
-  __shared__ int slot_lds;
+                     const int32_t* __restrict__ ws_t, const int32_t* __restrict__ ws_dst, T* __restrict__ out) {
   const int Hkv = P.Hkv, window = P.window, budget = P.budget, rho = P.rho;
   const int b = blockIdx.x / Hkv, h = blockIdx.x - b * Hkv;
   const int64_t head = (int64_t)b * Hkv + h;
@@ -643,8 +643,8 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
   }
 
   __syncthreads();  // every thread holds z_e and the old ring row before anything of this head is overwritten
-  const int dst = eviction_target(t, window, budget, P.sink, P.tau, cnt_old, z_e, C.ret_score + head * budget,
-                                  C.ret_pos + head * budget, red64, &slot_lds);
+  // where the token leaving the window goes: decided by the main launch from the same state (eviction_target)
+  const int dst = budget > 0 ? ws_dst[head] : -1;
 
   // ---- cache update: evicted row -> compact slot dst, then token t -> ring slot ------------------------------
   if (dst >= 0) {
@@ -733,7 +733,7 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 size_t base_workspace(const ltea_cfg& cfg, int n_seqs) {
   // sized for the larger of the two split counts
   return (partial_floats(cfg, n_seqs, decode_num_splits(cfg, n_seqs, true)) + (size_t)n_seqs * cfg.Hkv) * sizeof(float) +
-         (size_t)n_seqs * sizeof(int32_t);
+         ((size_t)n_seqs + (size_t)n_seqs * cfg.Hkv) * sizeof(int32_t);
 }
 
 bool window_scoring(const ltea_cfg& cfg, const ltea_cnn& cnn) {
@@ -827,12 +827,13 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   float* partial = static_cast<float*>(workspace);
   float* ws_logit = partial + partial_floats(cfg, n_seqs, P.nsplit);
   int32_t* ws_t = reinterpret_cast<int32_t*>(ws_logit + heads);
+  int32_t* ws_dst = ws_t + n_seqs;
   const unsigned grid = (unsigned)P.n_score_blocks + heads * (unsigned)P.nsplit;
   const int G = cfg.Hq / cfg.Hkv;
   auto launch_main = [&](auto gt, auto sk) {
     hipLaunchKernelGGL((decode_main_kernel<T, D, decltype(gt)::value, decltype(sk)::value>), dim3(grid), dim3(kThreads),
                        lds_bytes, stream, cd, C, P, static_cast<const T*>(q), static_cast<const T*>(k),
-                       static_cast<const T*>(v), partial, ws_logit, ws_t);
+                       static_cast<const T*>(v), partial, ws_logit, ws_t, ws_dst);
   };
   auto launch_gt = [&](auto sk) {
     if (G % 4 == 0) launch_main(std::integral_constant<int, 4>{}, sk);
@@ -851,7 +852,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(heads), dim3(kThreads), 0, stream, C, P,
-                     static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit, ws_t, static_cast<T*>(out));
+                     static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit, ws_t, ws_dst, static_cast<T*>(out));
   return hipGetLastError();
 }
 
