@@ -207,7 +207,7 @@ int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, co
  * whole history: new queries see their window plus the final capped retained set restricted to positions that have
  * left their window; the retained set is re-selected among the old retained entries and the tokens that leave the
  * window now (tokens dropped earlier stay dropped, which is what a one-shot prefill would also have decided).
- * Implemented for cfg->dtype == LTEA_BF16 (LTEA_EUNSUPPORTED otherwise).  Workspace: ltea_append_workspace_bytes. */
+ * Workspace: ltea_append_workspace_bytes. */
 size_t ltea_append_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_new,
                                    int32_t max_new);
 int ltea_prefill_append(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,

@@ -334,8 +334,6 @@ int ltea_prefill_append_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const lte
   const int64_t ext_stride_tok = (int64_t)cfg->Hkv * cfg->D;
   const int64_t ext_len_max = (int64_t)cfg->budget + 2 * (int64_t)cfg->window + max_new;
   if (ext_len_max > INT32_MAX / 2) return LTEA_EUNSUPPORTED;
-  // the continuation's attention stage exists on the bf16 MFMA path only
-  if (!attention_mfma_supported(*cfg, ext_stride_tok, (int32_t)ext_len_max)) return LTEA_EUNSUPPORTED;
   const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
   const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new, rope != nullptr), 256);
   const size_t need = build_ws + score_workspace(*cfg, *cnn, ext);
@@ -363,8 +361,11 @@ int ltea_prefill_append_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const lte
   ltea_cache local = *cache;
   local.ret_pos = buf.local_pos;
   SeqView sv_q{cu_new, n_seqs, total_new, max_new};
-  return hip_status(launch_attention_mfma(*cfg, q, q_stride_tok, q_stride_head, buf.ext_k, buf.ext_v, ext_stride_tok,
-                                          cfg->D, sv_q, local, out, s, buf.kv_start, buf.kv_len));
+  if (attention_mfma_supported(*cfg, ext_stride_tok, (int32_t)ext_len_max))
+    return hip_status(launch_attention_mfma(*cfg, q, q_stride_tok, q_stride_head, buf.ext_k, buf.ext_v, ext_stride_tok,
+                                            cfg->D, sv_q, local, out, s, buf.kv_start, buf.kv_len));
+  return hip_status(launch_attention_generic(*cfg, q, q_stride_tok, q_stride_head, buf.ext_k, buf.ext_v, ext_stride_tok,
+                                             cfg->D, sv_q, local, out, s, nullptr, buf.kv_start, buf.kv_len));
 }
 
 int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, const void* k, const void* v, void* out,

@@ -20,7 +20,8 @@ attention_generic_kernel(const T* __restrict__ q, int64_t q_st, int64_t q_sh, co
                          int n_seqs, int64_t total, int Hq, int Hkv, int window, int budget, float scale,
                          const T* __restrict__ k_ret, const T* __restrict__ v_ret,
                          const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count,
-                         T* __restrict__ out, float* __restrict__ lse) {
+                         T* __restrict__ out, float* __restrict__ lse, const int32_t* __restrict__ kv_start,
+                         const int32_t* __restrict__ kv_len) {
   __shared__ float q_lds[kWavesPerBlock][D];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t item = (int64_t)blockIdx.x * kWavesPerBlock + wave;
@@ -29,8 +30,15 @@ attention_generic_kernel(const T* __restrict__ q, int64_t q_st, int64_t q_sh, co
   const int hq = active ? (int)(item - tok * Hq) : 0;
   const int h = hq / (Hq / Hkv);
   const int s = find_sequence(cu, n_seqs, tok);
-  const int64_t lo = cu[s];
-  const int i = (int)(tok - lo);
+  // cu packs the query / output rows.  Normally it packs the keys as well; with kv_start / kv_len given, the keys of
+  // sequence s are rows kv_start[s] .. kv_start[s] + kv_len[s] - 1 of k / v and the queries are the last
+  // cu[s+1] - cu[s] positions of that key sequence (continuation of a prefill).
+  int64_t lo = cu[s];
+  int i = (int)(tok - lo);
+  if (kv_start != nullptr) {
+    i += kv_len[s] - (int)(cu[s + 1] - lo);
+    lo = kv_start[s];
+  }
   const int wlo = i - window + 1 > 0 ? i - window + 1 : 0;
   const int n_win = i - wlo + 1;
   const int64_t head = (int64_t)s * Hkv + h;
@@ -96,14 +104,14 @@ attention_generic_kernel(const T* __restrict__ q, int64_t q_st, int64_t q_sh, co
 template <typename T, int D>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
                int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out, float scale,
-               float* lse, hipStream_t stream) {
+               float* lse, const int32_t* kv_start, const int32_t* kv_len, hipStream_t stream) {
   const int64_t items = sv.total_tokens * cfg.Hq;
   dim3 grid((unsigned)((items + kWavesPerBlock - 1) / kWavesPerBlock));
   hipLaunchKernelGGL((attention_generic_kernel<T, D>), grid, dim3(kWavesPerBlock * kWave), 0, stream,
                      static_cast<const T*>(q), q_st, q_sh, static_cast<const T*>(k), static_cast<const T*>(v), kv_st,
                      kv_sh, sv.cu_seqlens, sv.n_seqs, sv.total_tokens, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale,
                      static_cast<const T*>(c.k_ret), static_cast<const T*>(c.v_ret), c.ret_pos, c.ret_count,
-                     static_cast<T*>(out), lse);
+                     static_cast<T*>(out), lse, kv_start, kv_len);
   return hipGetLastError();
 }
 
@@ -111,15 +119,16 @@ hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, c
 
 hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k,
                                     const void* v, int64_t kv_st, int64_t kv_sh, const SeqView& sv,
-                                    const ltea_cache& c, void* out, hipStream_t stream, float* lse) {
+                                    const ltea_cache& c, void* out, hipStream_t stream, float* lse,
+                                    const int32_t* kv_start, const int32_t* kv_len) {
   if (sv.total_tokens == 0) return hipSuccess;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
   if (cfg.dtype == LTEA_F32) {
-    return cfg.D == 64 ? run<float, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream)
-                       : run<float, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream);
+    return cfg.D == 64 ? run<float, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, kv_start, kv_len, stream)
+                       : run<float, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, kv_start, kv_len, stream);
   }
-  return cfg.D == 64 ? run<bf16_t, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream)
-                     : run<bf16_t, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, stream);
+  return cfg.D == 64 ? run<bf16_t, 64>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, kv_start, kv_len, stream)
+                     : run<bf16_t, 128>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, scale, lse, kv_start, kv_len, stream);
 }
 
 }  // namespace ltea

@@ -55,7 +55,8 @@ hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k
 hipError_t launch_attention_generic(const ltea_cfg& cfg, const void* q, int64_t q_stride_tok, int64_t q_stride_head,
                                     const void* k, const void* v, int64_t kv_stride_tok, int64_t kv_stride_head,
                                     const SeqView& sv, const ltea_cache& cache, void* out, hipStream_t stream,
-                                    float* lse = nullptr);
+                                    float* lse = nullptr, const int32_t* kv_start = nullptr,
+                                    const int32_t* kv_len = nullptr);
 bool attention_mfma_supported(const ltea_cfg& cfg, int64_t kv_stride_tok, int32_t max_seqlen);
 // sv packs the query / output rows.  With kv_start / kv_len (device, per sequence) the keys of sequence s are rows
 // kv_start[s] .. +kv_len[s]-1 of k / v and its queries are the last positions of that key sequence; without

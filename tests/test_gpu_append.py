@@ -316,3 +316,48 @@ def test_append_rotary_arguments_and_table_range():
                                 status=status)
     assert int(status.item()) & B.LTEA_ROPE_RANGE
     assert int(cache.n_seen[0]) == 100 and bool(torch.isfinite(out.float()).all())
+
+
+@pytest.mark.parametrize("kernel,channels,dilation", [((5,), (16,), None), ((3, 3), (16, 8), (2, 1))])
+def test_append_fp32(kernel, channels, dilation):
+    """fp32 storage goes through the layered scoring kernel and the one-wave-per-row attention kernel; three chunks,
+    the last one of which sees the final kept set."""
+    lens, Hq, Hkv, D, window, budget, sink = [260, 75, 130], 4, 2, 64, 48, 14, 2
+    w = wl.make_prefill("append_f32", 4242 + len(kernel), "f32", lens, Hq, Hkv, D, window, budget, sink, 0.0,
+                        cnn_kernel=kernel, cnn_channels=channels, cnn_dilation=dilation, qkv_scale=1.0, w_std=0.1)
+    ocfg, ocnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    ref_out, ref_states, z64, kept = orc.prefill(w.q, w.k, w.v, ocfg, ocnn, w.cu_seqlens)
+    cfg, cnn = device_setup(w)
+    cu = w.cu_seqlens
+    cuts = [[0, 0, 0], [100, 75, 20], [180, 75, 21], lens]
+    cache = B.alloc_cache(cfg, w.n_seqs)
+    for c in range(3):
+        a, b = cuts[c], cuts[c + 1]
+        m = [b[s] - a[s] for s in range(w.n_seqs)]
+        q, k, v = (dev(pack(x, cu, a, b), "f32") for x in (w.q, w.k, w.v))
+        cu_c = torch.from_numpy(cu_of(m)).cuda()
+        if c == 0:
+            B.ltea_prefill(cfg, cnn, q, k, v, cu_c, max(m), cache)
+        else:
+            out = to_np(B.ltea_prefill_append(cfg, cnn, q, k, v, cu_c, max(m), cache))
+    near = check_sets(cache, z64, w, 1e-5)
+    assert not near, near
+    zw = to_np(cache.win_score)
+    kw = to_np(cache.k_win)
+    for s in range(w.n_seqs):
+        lo, n = int(cu[s]), lens[s]
+        assert int(cache.n_seen[s]) == n and int(cache.n_scored[s]) == max(0, n - w.cnn.rho)
+        for h in range(Hkv):
+            for p in range(max(0, n - window), n):
+                np.testing.assert_array_equal(kw[s, h, p % window], w.k[lo + p, h])
+            for p in range(max(0, n - window), max(0, n - w.cnn.rho)):
+                assert abs(float(zw[s, h, p % window]) - z64[h, lo + p]) <= LOGIT_TOL["f32"] * max(1.0, abs(z64[h, lo + p]))
+    off = 0
+    a = cuts[2]
+    for s in range(w.n_seqs):
+        rows = slice(int(cu[s]) + a[s], int(cu[s]) + lens[s])
+        m_s = lens[s] - a[s]
+        if m_s:
+            err = float(np.abs(out[off: off + m_s] - ref_out[rows]).max())
+            assert err <= OUT_TOL["f32"] * max(1.0, float(np.abs(ref_out[rows]).max())), (s, err)
+        off += m_s
