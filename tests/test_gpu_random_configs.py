@@ -306,6 +306,17 @@ def test_random_rotated_cache(seed):
     """Lazy decoding of a cache that holds rotated keys, from empty, on random configurations: random rotary width
     (a multiple of 16 up to D), either pairing, random cadence of the batched scoring (never later than allowed).
     Reference: the oracle's lazy procedure with its own inverse rotation, rounded to the storage type."""
+    rotated_cache_run(seed, eager=False)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_rotated_cache_eager(seed):
+    """The same caches driven by ltea_decode_step_feat (one logit finalised per step from the ring rotated back).
+    Reference: the oracle's lazy step followed by its batched scoring after every step."""
+    rotated_cache_run(100 + seed, eager=True)
+
+
+def rotated_cache_run(seed, eager):
     c = draw_config(3000 + seed)
     rng = np.random.default_rng(94000 + seed)
     rho = sum(dd * (kk - 1) // 2 for kk, dd in zip(c["kernel"], c["dilation"]))
@@ -332,18 +343,27 @@ def test_random_rotated_cache(seed):
     G = w.Hq // w.Hkv
     since, z_eps, unsure = 0, 1e-6, set()
     tol = OUT_TOL[dt]
+    def scored_both_sides():
+        nonlocal z_eps
+        zw = cache.win_score.cpu().numpy()
+        for s in range(B_):
+            orc.rescore(states[s], cfg, cnn, rope_o, rounder)
+            assert int(cache.n_scored[s]) == states[s].n_scored
+            for h in range(w.Hkv):
+                for p, zp in states[s].heads[h].win_z.items():
+                    z_eps = max(z_eps, abs(float(zw[s, h, p % window]) - zp))
+
     for t in range(n):
-        if since >= period or (since > 0 and rng.random() < 0.15):
+        if not eager and (since >= period or (since > 0 and rng.random() < 0.15)):
             B.ltea_rescore(d.cfg, d.cnn, cache, rope=rope_g, status=status)
-            zw = cache.win_score.cpu().numpy()
-            for s in range(B_):
-                orc.rescore(states[s], cfg, cnn, rope_o, rounder)
-                assert int(cache.n_scored[s]) == states[s].n_scored
-                for h in range(w.Hkv):
-                    for p, zp in states[s].heads[h].win_z.items():
-                        z_eps = max(z_eps, abs(float(zw[s, h, p % window]) - zp))
+            scored_both_sides()
             since = 0
-        got = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache, status=status))
+        if eager:
+            got = to_np(B.ltea_decode_step_feat(d.cfg, d.cnn, dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache,
+                                                rope=rope_g, status=status))
+        else:
+            got = to_np(B.ltea_decode_step_lazy(d.cfg, dev(q3[:, t], dt), dev(k3[:, t], dt), dev(v3[:, t], dt), cache,
+                                                status=status))
         since += 1
         # the oracle's keep decisions of this step, with their margins, before it takes the step
         for s in range(B_):
@@ -367,6 +387,26 @@ def test_random_rotated_cache(seed):
                 err = float(np.max(np.abs(got[s, h * G:(h + 1) * G] - ref[s, h * G:(h + 1) * G])))
                 sc = float(np.max(np.abs(ref[s, h * G:(h + 1) * G])))
                 assert err <= tol and err <= tol * max(sc, 1e-30), (t, s, h, err, sc)
+        if eager:   # the oracle's batched scoring after its lazy step finalises the logit the device just finalised
+            scored_both_sides()
     assert int(status.item()) == 0
     assert z_eps <= (2e-3 if dt == "bf16" else 1e-4) * 4, z_eps
     assert len(unsure) <= max(2, B_ * w.Hkv // 2), unsure
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_rotary_append(seed):
+    """Continued prefill of a rotary model on random configurations: random cut per sequence (empty first or second
+    parts included), random rotary width and pairing, new keys given unrotated or rotated back by the library."""
+    from tests.test_gpu_append import rotary_append_run
+    c = draw_config(5000 + seed)
+    rng = np.random.default_rng(95000 + seed)
+    w = wl.make_prefill(f"random_rotary_append{seed}", 95000 + seed, c["dtype"], c["lens"], c["Hq"], c["Hkv"], c["D"],
+                        c["window"], c["budget"], c["sink"], c["tau"], cnn_kernel=c["kernel"], cnn_channels=c["widths"],
+                        cnn_dilation=c["dilation"], qkv_scale=1.0, w_std=0.08)
+    cut = [int(rng.integers(0, n + 1)) for n in c["lens"]]
+    rot = int(rng.choice([r for r in (16, 32, 48, 64, 96, 128) if r <= c["D"]]))
+    inter, give = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    print(f"[random rotary append {seed}] cut {cut} rot {rot} interleaved {inter} k_feat {give} {c}", flush=True)
+    near = rotary_append_run(w, cut, rot, inter, give)
+    assert len(near) <= max(1, w.n_seqs * w.Hkv // 3), near
