@@ -174,7 +174,8 @@ int ltea_prefill(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_
 /* ltea_prefill for models whose cached keys differ from the keys the scoring CNN is trained on (rotary position
  * encoding: Section 3.1.1 scores keys as they are before the rotation, the cache holds them after it): k_feat, a view
  * with the strides of k, is what the CNN scores; k is what is cached and attended.  ltea_prefill is this call with
- * k_feat = k.  (For decoding such a cache see ltea_rescore.) */
+ * k_feat = k.  (Such a cache is continued with ltea_prefill_append_feat and decoded with ltea_decode_step_feat or
+ * ltea_decode_step_lazy + ltea_rescore, all of which take the model's rotary tables.) */
 int ltea_prefill_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
                       int64_t q_stride_head, const void *k, const void *v, const void *k_feat, int64_t kv_stride_tok,
                       int64_t kv_stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
@@ -195,7 +196,10 @@ int ltea_prefill_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, i
  * contiguous [n_seqs][Hq][D].  Requires the invariant n_scored = max(0,
  * n_seen - rho) on entry (true after ltea_retain / ltea_prefill / a previous
  * step, and for an all-zero fresh cache).  Concurrent calls on the same cache or
- * the same workspace race. */
+ * the same workspace race.  LTEA_EUNSUPPORTED if the per-step scoring's activation
+ * rows, 2 * (2*rho+1) * max(2*D, widest layer) floats, exceed 48 KB of LDS (the lazy
+ * path and ltea_decode_step_feat score through the prefill kernels and have no such
+ * limit). */
 int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);
@@ -237,9 +241,9 @@ int ltea_prefill_append(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q,
 
 /* Rotary position encoding as the model holds it ("cached sinusoids"): row p of the tables rotates pair i of a
  * key at position p, (a, b) -> (a cos - b sin, a sin + b cos), with pair i = (x[i], x[i + rot_dim/2]), or
- * (x[2i], x[2i+1]) when `interleaved`; features from rot_dim on are not rotated.  Given to ltea_rescore, the cache
- * is taken to hold rotated keys and the scoring CNN sees them rotated back (same tables, negated sines, each row at
- * its own position), rounded to cfg->dtype. */
+ * (x[2i], x[2i+1]) when `interleaved`; features from rot_dim on are not rotated.  Given to ltea_rescore,
+ * ltea_decode_step_feat or ltea_prefill_append_feat, the cache is taken to hold rotated keys and the scoring CNN sees
+ * them rotated back (same tables, negated sines, each row at its own position), rounded to cfg->dtype. */
 typedef struct ltea_rope {
   const float *cos, *sin; /* [n_pos][rot_dim/2] fp32, device                                    */
   int32_t n_pos;          /* table rows; every cached position must be below it                  */
@@ -273,15 +277,15 @@ int ltea_decode_step_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_r
                           int32_t n_seqs, int32_t *status_or_null, void *workspace, size_t workspace_bytes,
                           void *stream);
 
-/* ltea_prefill_append for models that cache rotated keys.  rope (required here): the ring's keys are rotated back at
- * their positions for the scoring CNN, exactly as ltea_rescore does it.  k_feat_or_null: the new tokens' keys as they
+/* ltea_prefill_append for models that cache rotated keys.  rope_or_null: the ring's keys are rotated back at their
+ * positions for the scoring CNN, exactly as ltea_rescore does it.  k_feat_or_null: the new tokens' keys as they
  * were before the rotation (same strides as k); NULL rotates the new keys back too (positions n_seen[s] + i), so the
  * caller need not keep them.  k, the rotated keys, are what is cached and attended.  Results equal ltea_prefill_feat
  * over the whole history up to the rounding of the keys that are rotated back.  status_or_null receives
  * LTEA_ROPE_RANGE when a position lies beyond the tables (that key is scored as cached).  rope == NULL with
  * k_feat == NULL is ltea_prefill_append; k_feat without rope is LTEA_EINVAL.  Requires n_scored = max(0, n_seen - rho)
  * on entry like ltea_prefill_append.  Workspace: ltea_append_workspace_bytes. */
-int ltea_prefill_append_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope, const void *q,
+int ltea_prefill_append_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const ltea_rope *rope_or_null, const void *q,
                              int64_t q_stride_tok, int64_t q_stride_head, const void *k, const void *v,
                              const void *k_feat_or_null, int64_t kv_stride_tok, int64_t kv_stride_head,
                              const int32_t *cu_new, int32_t n_seqs, int64_t total_new, int32_t max_new, void *out,
