@@ -196,10 +196,10 @@ int ltea_prefill_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, i
  * contiguous [n_seqs][Hq][D].  Requires the invariant n_scored = max(0,
  * n_seen - rho) on entry (true after ltea_retain / ltea_prefill / a previous
  * step, and for an all-zero fresh cache).  Concurrent calls on the same cache or
- * the same workspace race.  LTEA_EUNSUPPORTED if the per-step scoring's activation
- * rows, 2 * (2*rho+1) * max(2*D, widest layer) floats, exceed 48 KB of LDS (the lazy
- * path and ltea_decode_step_feat score through the prefill kernels and have no such
- * limit). */
+ * the same workspace race.  A CNN whose per-step activation rows, 2 * (2*rho+1) *
+ * max(2*D, widest layer) floats, exceed 48 KB of LDS is scored through the prefill
+ * kernels instead (as ltea_decode_step_feat does): that needs the workspace
+ * ltea_decode_workspace_bytes(cfg, cnn, n_seqs) reports, LTEA_EWORKSPACE otherwise. */
 int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);

@@ -176,11 +176,27 @@ size_t ltea_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_
   return bytes;
 }
 
+// The per-(sequence, head) scoring of the eager step keeps two generations of (2 rho + 1) activation rows in LDS.
+static bool decode_pyramid_fits(const ltea_cfg* cfg, const ltea_cnn* cnn) {
+  int row_floats = 2 * cfg->D;
+  for (int l = 0; l < cnn->n_layers; ++l) row_floats = cnn->c_out[l] > row_floats ? cnn->c_out[l] : row_floats;
+  return (size_t)2 * (2 * cnn_rho(cnn) + 1) * row_floats * sizeof(float) <= 48 * 1024;
+}
+
+static size_t decode_scored_workspace(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
+  const int rho = cnn_rho(cnn);
+  return align_up(decode_workspace(*cfg, n_seqs), 256) + align_up(decode_windows_layout(*cfg, rho, n_seqs, nullptr, nullptr), 256) +
+         score_workspace(*cfg, *cnn, (int64_t)n_seqs * (2 * rho + 1));
+}
+
 size_t ltea_decode_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
   if (check_cfg(cfg) != LTEA_OK || n_seqs < 0) return 0;
   if (cnn && check_cnn(cfg, cnn) != LTEA_OK) return 0;
-  if (cnn) return align_up(decode_workspace_full(*cfg, *cnn, n_seqs), 256);
-  return align_up(decode_workspace(*cfg, n_seqs), 256);
+  if (!cnn) return align_up(decode_workspace(*cfg, n_seqs), 256);
+  const size_t full = align_up(decode_workspace_full(*cfg, *cnn, n_seqs), 256);
+  if (decode_pyramid_fits(cfg, cnn)) return full;
+  const size_t scored = decode_scored_workspace(cfg, cnn, n_seqs);   // such CNNs are scored through the prefill kernels
+  return scored > full ? scored : full;
 }
 
 int ltea_score(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k, const void* v, int64_t stride_tok,
@@ -378,10 +394,11 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
   if (n_seqs == 0) return LTEA_OK;
   if (!q || !k || !v || !out) return LTEA_EINVAL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return LTEA_EINVAL;
-  int row_floats = 2 * cfg->D;
-  for (int l = 0; l < cnn->n_layers; ++l) row_floats = cnn->c_out[l] > row_floats ? cnn->c_out[l] : row_floats;
-  const size_t lds = (size_t)2 * (2 * cnn_rho(cnn) + 1) * row_floats * sizeof(float);
-  if (lds > 48 * 1024) return LTEA_EUNSUPPORTED;  // activation pyramid of the per-step scoring must fit LDS
+  // A CNN whose per-step activation rows do not fit LDS goes through the packed-window path (needs the workspace
+  // ltea_decode_workspace_bytes(cfg, cnn, n_seqs) reports for it).
+  if (!decode_pyramid_fits(cfg, cnn))
+    return ltea_decode_step_feat(cfg, cnn, nullptr, q, k, v, nullptr, out, cache, n_seqs, nullptr, workspace,
+                                 workspace_bytes, stream);
   const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
   return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace, workspace_bytes,
@@ -390,9 +407,7 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
 
 size_t ltea_decode_feat_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
   if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || n_seqs < 0) return 0;
-  const int rho = cnn_rho(cnn);
-  return align_up(decode_workspace(*cfg, n_seqs), 256) + align_up(decode_windows_layout(*cfg, rho, n_seqs, nullptr, nullptr), 256) +
-         score_workspace(*cfg, *cnn, (int64_t)n_seqs * (2 * rho + 1));
+  return decode_scored_workspace(cfg, cnn, n_seqs);
 }
 
 int ltea_decode_step_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope, const void* q, const void* k,

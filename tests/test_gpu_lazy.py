@@ -298,3 +298,34 @@ def test_rotary_eager_decode(dtype, kernel, channels, dilation, interleaved, giv
         if not give_k_feat:
             compare_sets(cache, states, w, t)
     assert int(status.item()) == 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_eager_decode_with_a_receptive_field_too_wide_for_lds(dtype):
+    """Two k=7, dilation-2 layers at D=128: rho = 12, and the per-step scoring's 2 x 25 activation rows of 256 floats
+    do not fit 48 KB of LDS.  ltea_decode_step then scores through the packed-window path; the reference is the
+    oracle's ordinary per-step decode."""
+    lens, Hq, Hkv, D, window, budget, sink = [70, 5], 2, 1, 128, 40, 9, 1
+    w = wl.make_prefill("wide_rf", 66, dtype, lens, Hq, Hkv, D, window, budget, sink, 0.0, cnn_kernel=(7, 7),
+                        cnn_channels=(32, 16), cnn_dilation=(2, 2), w_std=0.05)
+    assert w.cnn.rho == 12
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    logits = torch.empty((Hkv, w.total_tokens), dtype=torch.float32, device="cuda")
+    B.ltea_prefill(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen, cache, logits=logits)
+    _, states, z64, _ = orc.prefill(w.q, w.k, w.v, cfg, cnn, w.cu_seqlens)
+    eps = logit_eps(to_np(logits), z64, dtype)
+    assert not check_sets(cache, z64, w, eps), "pick another seed: a head sits inside the decision margin"
+    ws = B.decode_workspace(d.cfg, d.cnn, w.n_seqs)
+    small = torch.empty(B.ltea_decode_workspace_bytes(d.cfg, None, w.n_seqs), dtype=torch.uint8, device="cuda")
+    q, k, v = wl.decode_inputs(w.seed, 0, dtype, w.n_seqs, Hq, Hkv, D)
+    with pytest.raises(B.LteaError):       # the basic workspace is not enough for this CNN
+        B.ltea_decode_step(d.cfg, d.cnn, dev(q, dtype), dev(k, dtype), dev(v, dtype), cache, workspace=small)
+    for t in range(60):
+        q, k, v = wl.decode_inputs(w.seed, t, dtype, w.n_seqs, Hq, Hkv, D)
+        got = to_np(B.ltea_decode_step(d.cfg, d.cnn, dev(q, dtype), dev(k, dtype), dev(v, dtype), cache, workspace=ws))
+        ref = np.stack([orc.decode_step(states[s], q[s], k[s], v[s], cfg, cnn) for s in range(w.n_seqs)])
+        check_output(got, ref, dtype, f"wide receptive field step {t}")
+        compare_sets(cache, states, w, t)
+    compare_ring_logits(cache, states, w, 5 * LOGIT_TOL[dtype])
