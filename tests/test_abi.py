@@ -117,10 +117,13 @@ def test_decode_and_prefill_argument_errors():
     assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(bad), 2, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
     assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), None, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
     assert L.ltea_decode_step(C.byref(cfg), C.byref(cnn), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), -1, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
-    # per-step scoring pyramid too large for LDS
+    # per-step scoring pyramid too large for LDS: scored through the packed-window path, which needs the larger workspace
     big = fake_cnn(kernel=(63,), c_out=(16,))
     cfgw = good_cfg(window=256, D=128)
-    assert L.ltea_decode_step(C.byref(cfgw), C.byref(big), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, 1 << 30, None) == B.LTEA_EUNSUPPORTED
+    basic = L.ltea_decode_workspace_bytes(C.byref(cfgw), None, 2)
+    full = L.ltea_decode_workspace_bytes(C.byref(cfgw), C.byref(big), 2)
+    assert full > basic and full >= L.ltea_decode_feat_workspace_bytes(C.byref(cfgw), C.byref(big), 2)
+    assert L.ltea_decode_step(C.byref(cfgw), C.byref(big), 0x1000, 0x1000, 0x1000, 0x1000, C.byref(cache), 2, 0x1000, basic, None) == B.LTEA_EWORKSPACE
     # prefill: null out
     assert L.ltea_prefill(C.byref(cfg), C.byref(cnn), 0x1000, 256, 64, 0x1000, 0x1000, 128, 64, 0x1000, 1, 32, 32, None,
                           C.byref(cache), None, 0x1000, 1 << 30, None) == B.LTEA_EINVAL
