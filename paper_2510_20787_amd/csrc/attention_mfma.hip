@@ -210,18 +210,20 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     // exponentials of the other (scores of block 1 beside the softmax of block 0, P.V of block 0 beside the
     // softmax of block 1), because a wave issues in order: only MFMAs that sit between VALU instructions in
     // the instruction stream run concurrently with them.
-    auto score_block = [&](int kb, f32x16 (&sc)[QB]) {
+    auto load_k_ops = [&](int kb, bf16x8 (&a)[D / 16]) {
+#pragma unroll
+      for (int ks = 0; ks < D / 16; ++ks) a[ks] = *reinterpret_cast<const bf16x8*>(a_k + 32 * kb * KS + 16 * ks);
+    };
+    auto score_block = [&](const bf16x8 (&a)[D / 16], f32x16 (&sc)[QB]) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) sc[qb][r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(a_k + 32 * kb * KS + 16 * ks);
+      for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb)
-          sc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[qb][ks], sc[qb], 0, 0, 0);
-      }
+          sc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qreg[qb][ks], sc[qb], 0, 0, 0);
     };
     // mask (register r is local key 32*kb + 16*(r/8) + 8*hb + r%8), then raise the running maximum if needed.
     // Returns whether any lane raised it; the factors the output accumulators still have to be scaled by are left
@@ -326,9 +328,13 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     f32x16 s0[QB], s1[QB];
     bf16x8 p0[QB][2], p1[QB][2];
     float alpha[QB];
-    score_block(0, s0);
+    bf16x8 ak0[D / 16], ak1[D / 16];
+    load_k_ops(0, ak0);
+    load_k_ops(1, ak1);        // requested together with block 0's operands: their LDS latency passes under block 0
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (D / 16), 0);   // all operand reads first
+    score_block(ak0, s0);
     if (mask_and_max(0, s0, alpha)) rescale(alpha);
-    score_block(1, s1);
+    score_block(ak1, s1);
     exp_block(s0, p0);
     const bool grew = mask_and_max(1, s1, alpha);   // p0 was formed under the previous maximum:
     pv_block(0, p0);                                //   its product goes in before the accumulators are scaled
