@@ -312,19 +312,26 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
         pb[qb][1] = __builtin_bit_cast(bf16x8, w1);
       }
     };
-    auto pv_block = [&](int kb, const bf16x8 (&pb)[QB][2]) {   // O^T += V^T P^T
+    auto load_v_ops = [&](int kb, bf16x8 (&av)[D / 32][2]) {
 #pragma unroll
       for (int db = 0; db < D / 32; ++db) {
         const bf16_t* ap = a_v + 32 * kb * VS + ((db ^ tr_swz) << 5);
-        const bf16x8 a0 = load_transposed(ap, VS);
-        const bf16x8 a1 = load_transposed(ap + 16 * VS, VS);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, pb[qb][0], o[qb][db], 0, 0, 0);
-          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, pb[qb][1], o[qb][db], 0, 0, 0);
-        }
+        av[db][0] = load_transposed(ap, VS);
+        av[db][1] = load_transposed(ap + 16 * VS, VS);
       }
     };
+    auto pv_block = [&](const bf16x8 (&av)[D / 32][2], const bf16x8 (&pb)[QB][2]) {   // O^T += V^T P^T
+#pragma unroll
+      for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[db][0], pb[qb][0], o[qb][db], 0, 0, 0);
+          o[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[db][1], pb[qb][1], o[qb][db], 0, 0, 0);
+        }
+    };
+    // Where the value operands are requested: at D = 128 ahead of the exponentials that hide their LDS latency
+    // (measured +1 %), at D = 64 next to their MFMAs (the earlier request costs more there than it hides).
+    constexpr bool kEarlyV = D == 128;
     f32x16 s0[QB], s1[QB];
     bf16x8 p0[QB][2], p1[QB][2];
     float alpha[QB];
@@ -335,12 +342,17 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     score_block(ak0, s0);
     if (mask_and_max(0, s0, alpha)) rescale(alpha);
     score_block(ak1, s1);
+    bf16x8 av0[D / 32][2], av1[D / 32][2];
+    if constexpr (kEarlyV) load_v_ops(0, av0);
     exp_block(s0, p0);
     const bool grew = mask_and_max(1, s1, alpha);   // p0 was formed under the previous maximum:
-    pv_block(0, p0);                                //   its product goes in before the accumulators are scaled
+    if constexpr (kEarlyV) load_v_ops(1, av1);
+    else load_v_ops(0, av0);
+    pv_block(av0, p0);                              //   its product goes in before the accumulators are scaled
     exp_block(s1, p1);
     if (grew) rescale(alpha);
-    pv_block(1, p1);
+    if constexpr (!kEarlyV) load_v_ops(1, av1);
+    pv_block(av1, p1);
   };
 
   // ---- software pipeline: tile t is computed from LDS buffer t&1 while tile t+1 is being stored into the other
