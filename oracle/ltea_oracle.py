@@ -560,3 +560,79 @@ def lambda_update(lam: np.ndarray, c_bar: np.ndarray, cap: float, alpha: float) 
     lam[lam < 1e-9] = 0.0
     lam[(c_bar > cap) & (lam == 0.0)] = 1e-9
     return lam
+
+
+# --------------------------------------------------------------------------
+# O9: backward of the scoring CNN (Section 3.1.1 module, trained through the gradient of Section 3.1.2)
+# --------------------------------------------------------------------------
+def silu_grad(y: np.ndarray) -> np.ndarray:
+    """d/dy of y * sigmoid(y)."""
+    s = 1.0 / (1.0 + np.exp(-y))
+    return s * (1.0 + y * (1.0 - s))
+
+
+def score_backward_sequence(k_seq: np.ndarray, v_seq: np.ndarray, cnn: OracleCnn, dz_seq: np.ndarray):
+    """Gradients of L = sum_{h,j} dz[h, j] * z[h, j] for one sequence, z = score_sequence(k_seq, v_seq, cnn).
+    Returns (dw list [Hkv, C_out, C_in, kernel], dbias list [Hkv, C_out], dw_out [Hkv, C_last], db_out [Hkv],
+    dk [n, Hkv, D], dv [n, Hkv, D]).  The chain rule through the layers of score_sequence, in reverse order."""
+    k_seq = np.asarray(k_seq, dtype=np.float64)
+    v_seq = np.asarray(v_seq, dtype=np.float64)
+    n, Hkv, D = k_seq.shape
+    L = len(cnn.kernel)
+    dw = [np.zeros_like(w) for w in cnn.w]
+    dbias = [np.zeros_like(b) for b in cnn.bias]
+    dw_out, db_out = np.zeros_like(cnn.w_out), np.zeros_like(cnn.b_out)
+    dk, dv = np.zeros_like(k_seq), np.zeros_like(v_seq)
+    for h in range(Hkv):
+        acts = [np.concatenate([k_seq[:, h, :], v_seq[:, h, :]], axis=1)]       # inputs of each layer
+        pre = []                                                                # pre-activations of each layer
+        for l, (ks, dil) in enumerate(zip(cnn.kernel, cnn.dilation)):
+            W = cnn.w[l][h]
+            y = np.tile(cnn.bias[l][h][None, :], (n, 1))
+            for t in range(ks):
+                off = (t - (ks - 1) // 2) * dil
+                lo, hi = max(0, -off), min(n, n - off)
+                if hi > lo:
+                    y[lo:hi] += acts[l][lo + off:hi + off] @ W[:, :, t].T
+            pre.append(y)
+            acts.append(silu(y))
+        g = np.asarray(dz_seq[h], dtype=np.float64)                             # [n]
+        dw_out[h] = g @ acts[L]
+        db_out[h] = g.sum()
+        da = g[:, None] * cnn.w_out[h][None, :]                                 # d L / d output of the last layer
+        for l in reversed(range(L)):
+            ks, dil = cnn.kernel[l], cnn.dilation[l]
+            W = cnn.w[l][h]
+            dy = da * silu_grad(pre[l])                                         # [n, C_out]
+            dbias[l][h] = dy.sum(axis=0)
+            da_prev = np.zeros_like(acts[l])
+            for t in range(ks):
+                off = (t - (ks - 1) // 2) * dil
+                lo, hi = max(0, -off), min(n, n - off)
+                if hi > lo:
+                    dw[l][h][:, :, t] = dy[lo:hi].T @ acts[l][lo + off:hi + off]
+                    da_prev[lo + off:hi + off] += dy[lo:hi] @ W[:, :, t]
+            da = da_prev
+        dk[:, h, :] = da[:, :D]
+        dv[:, h, :] = da[:, D:]
+    return dw, dbias, dw_out, db_out, dk, dv
+
+
+def score_backward(k: np.ndarray, v: np.ndarray, cnn: OracleCnn, cu_seqlens: Sequence[int], dz: np.ndarray):
+    """score_backward_sequence over packed sequences: weight gradients summed over the sequences."""
+    T, Hkv, D = k.shape
+    dw = [np.zeros_like(w) for w in cnn.w]
+    dbias = [np.zeros_like(b) for b in cnn.bias]
+    dw_out, db_out = np.zeros_like(cnn.w_out), np.zeros_like(cnn.b_out)
+    dk, dv = np.zeros((T, Hkv, D)), np.zeros((T, Hkv, D))
+    for s in range(len(cu_seqlens) - 1):
+        lo, hi = int(cu_seqlens[s]), int(cu_seqlens[s + 1])
+        if hi > lo:
+            g = score_backward_sequence(k[lo:hi], v[lo:hi], cnn, np.asarray(dz)[:, lo:hi])
+            for l in range(len(dw)):
+                dw[l] += g[0][l]
+                dbias[l] += g[1][l]
+            dw_out += g[2]
+            db_out += g[3]
+            dk[lo:hi], dv[lo:hi] = g[4], g[5]
+    return dw, dbias, dw_out, db_out, dk, dv

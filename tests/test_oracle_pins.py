@@ -592,3 +592,70 @@ def test_p17_penalty_weight_feedback_follows_algorithm_1():
     np.testing.assert_allclose(orc.lambda_update(np.array([1.5e-9]), np.array([10.0]), 512.0, 2.0), [0.0])
     # moving average: coefficient 2 / (1 + u/2)
     np.testing.assert_allclose(orc.ema_count(np.array([100.0]), np.array([200.0]), 32), [2 / 17 * 100 + 15 / 17 * 200])
+
+
+# --------------------------------------------------------------------------
+# P18: backward of the scoring CNN
+# --------------------------------------------------------------------------
+def _tiny_cnn(rng, Hkv, D, kernel, channels, dilation):
+    w, bias, cin = [], [], 2 * D
+    for ks, c in zip(kernel, channels):
+        w.append(rng.normal(0, 0.3, (Hkv, c, cin, ks)))
+        bias.append(rng.normal(0, 0.3, (Hkv, c)))
+        cin = c
+    return orc.cnn_from_arrays(kernel, dilation, w, bias, rng.normal(0, 0.5, (Hkv, cin)), rng.normal(0, 0.5, (Hkv,)))
+
+
+def test_p18_cnn_backward_matches_finite_differences():
+    """L = sum dz * z with z from the forward oracle; every gradient family is checked by central differences on
+    random entries (two sequences, so that the sequence boundary is exercised: no gradient crosses it)."""
+    rng = np.random.default_rng(18)
+    Hkv, D = 2, 4
+    cnn = _tiny_cnn(rng, Hkv, D, (3, 5), (6, 3), (2, 1))
+    cu = [0, 9, 14]
+    k, v = rng.normal(0, 1, (14, Hkv, D)), rng.normal(0, 1, (14, Hkv, D))
+    dz = rng.normal(0, 1, (Hkv, 14))
+    loss = lambda: float(np.sum(dz * orc.score(k, v, cnn, cu)))
+    dw, dbias, dw_out, db_out, dk, dv = orc.score_backward(k, v, cnn, cu, dz)
+
+    def check(arr, grad, n=12, eps=1e-6):
+        for _ in range(n):
+            idx = tuple(int(rng.integers(0, s)) for s in arr.shape)
+            old = arr[idx]
+            arr[idx] = old + eps; up = loss()
+            arr[idx] = old - eps; dn = loss()
+            arr[idx] = old
+            assert abs((up - dn) / (2 * eps) - grad[idx]) <= 1e-6 * max(1.0, abs(grad[idx])), idx
+
+    for l in range(2):
+        check(cnn.w[l], dw[l])
+        check(cnn.bias[l], dbias[l])
+    check(cnn.w_out, dw_out)
+    check(cnn.b_out, db_out, n=2)
+    check(k, dk)
+    check(v, dv)
+    # a token of the second sequence does not feel the first sequence's logits
+    dz2 = dz.copy(); dz2[:, 9:] = 0.0
+    g = orc.score_backward(k, v, cnn, cu, dz2)
+    assert np.all(g[4][9:] == 0.0) and np.all(g[5][9:] == 0.0)
+
+
+def test_p18_cnn_backward_of_a_pointwise_layer_is_the_textbook_rule():
+    """kernel 1: the CNN is a per-token MLP.  d w_out = sum_j dz_j * silu(y_j); d bias = sum_j dz_j w_out silu'(y_j);
+    d input = W^T (dz_j w_out silu'(y_j)), written out independently of the oracle's loops."""
+    rng = np.random.default_rng(181)
+    D, n = 3, 7
+    cnn = _tiny_cnn(rng, 1, D, (1,), (4,), (1,))
+    k, v = rng.normal(0, 1, (n, 1, D)), rng.normal(0, 1, (n, 1, D))
+    dz = rng.normal(0, 1, (1, n))
+    dw, dbias, dw_out, db_out, dk, dv = orc.score_backward(k, v, cnn, [0, n], dz)
+    x = np.concatenate([k[:, 0], v[:, 0]], axis=1)                 # [n, 2D]
+    W, b, wo = cnn.w[0][0][:, :, 0], cnn.bias[0][0], cnn.w_out[0]
+    y = x @ W.T + b
+    sig = 1 / (1 + np.exp(-y))
+    dy = dz[0][:, None] * wo[None, :] * (sig * (1 + y * (1 - sig)))
+    np.testing.assert_allclose(dw_out[0], dz[0] @ (y * sig), rtol=1e-12)
+    np.testing.assert_allclose(dbias[0][0], dy.sum(0), rtol=1e-12)
+    np.testing.assert_allclose(dw[0][0][:, :, 0], dy.T @ x, rtol=1e-12)
+    np.testing.assert_allclose(np.concatenate([dk[:, 0], dv[:, 0]], axis=1), dy @ W, rtol=1e-12)
+    assert abs(db_out[0] - dz.sum()) < 1e-12
