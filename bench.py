@@ -356,6 +356,15 @@ def bench_train(args):
         if it > 0:
             fwd_ms += ev[0].elapsed_time(ev[1]) / reps
             bwd_ms += ev[1].elapsed_time(ev[2]) / reps
+    # the scoring CNN's own backward on the d logits just produced (fp32 VALU kernels; not part of tokens_per_s)
+    cws = torch.empty(int(B.lib().ltea_cnn_backward_workspace_bytes(B.C.byref(cfg), B.C.byref(cnn.struct), w.total_tokens)),
+                      dtype=torch.uint8, device="cuda")
+    B.ltea_cnn_backward(cfg, cnn, k, v, cu, w.max_seqlen, grads[3], workspace=cws)
+    ev[0].record()
+    B.ltea_cnn_backward(cfg, cnn, k, v, cu, w.max_seqlen, grads[3], workspace=cws)
+    ev[1].record()
+    torch.cuda.synchronize()
+    cnn_bwd_ms = ev[0].elapsed_time(ev[1])
     z = logits.cpu().numpy()
     G = w.Hq // w.Hkv
     pairs = 0
@@ -375,7 +384,7 @@ def bench_train(args):
     tf = flops_bwd / (bwd_ms * 1e-3) / 1e12
     return dict(workload="paper_stack_bf16 without the cap (training): B=4 x n=4096, Hq=32 on Hkv=8, D=64, window=768, "
                          f"output biases shifted so that every head keeps {share:.3f} of its tokens (measured {kept_frac:.3f})", forward_ms=fwd_ms, backward_ms=bwd_ms,
-                tokens_per_s=w.total_tokens / ((fwd_ms + bwd_ms) * 1e-3), pairs=pairs,
+                cnn_backward_ms=cnn_bwd_ms, tokens_per_s=w.total_tokens / ((fwd_ms + bwd_ms) * 1e-3), pairs=pairs,
                 roofline=dict(bound="mfma", kernel="train_dq_mfma_kernel + train_dkv_mfma_kernel (both passes)",
                               achieved=tf, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=tf / PEAK_BF16_TFLOPS, traffic=None,
                               note="algorithmic flops = 10 D per (query, key) pair (S, dP, dV, dK, dQ); the two kernels "

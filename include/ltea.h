@@ -302,8 +302,8 @@ int ltea_decode_step_lazy(const ltea_cfg *cfg, const void *q, const void *k, con
  * During training no cap applies: query i sees its window plus every candidate (sink, or logit > tau_logit) that
  * has left it; cfg->budget is ignored by these entry points.  The forward is ltea_prefill's pipeline with the cap
  * lifted and also returns the softmax normalisers; the state it leaves in `workspace` (the compacted candidates)
- * must reach ltea_train_backward unchanged.  The CNN's own backward (d logits -> d weights, d features) and its
- * dropout are not part of this library. */
+ * must reach ltea_train_backward unchanged.  The CNN's own backward (d logits -> d weights, d features) is
+ * ltea_cnn_backward below; its dropout is not part of this library. */
 /* cnn may be NULL (logits supplied by the caller). */
 size_t ltea_train_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
                                   int32_t max_seqlen);
@@ -333,6 +333,27 @@ int ltea_train_backward(const ltea_cfg *cfg, const void *q, int64_t q_stride_tok
                         const void *out, const void *dout, const float *lse, const float *logits, const float *lambda,
                         void *dq, void *dk, void *dv, float *dz, int32_t *counts, void *workspace,
                         size_t workspace_bytes, void *stream);
+
+/* Backward of the scoring CNN (the module of Section 3.1.1, trained through the d logits above): gradients of
+ * L = sum_{h,t} dz[h][t] * logit[h][t] with respect to every parameter and to the input features.  `grad` holds device
+ * fp32 arrays of the shapes of the weights (w[l]: [Hkv][c_out][c_in][kernel], bias[l]: [Hkv][c_out], w_out:
+ * [Hkv][c_out of the last layer], b_out: [Hkv]); they are overwritten, not accumulated into (sums over all tokens of
+ * all sequences, fp32, fixed order).  dk_feat_or_null / dv_or_null: contiguous [total_tokens][Hkv][D] of cfg->dtype,
+ * the gradient that reaches the scored keys and the values through the CNN (to be added to the attention's dk / dv
+ * by a caller that trains them through this path too).  k_feat, v, cu_seqlens: as given to ltea_score /
+ * ltea_train_forward (k_feat = the keys the CNN scores).  cnn->panels is not used.  Plain fp32 arithmetic for every
+ * CNN shape and storage type. */
+typedef struct ltea_cnn_grad {
+  float *w[LTEA_MAX_CNN_LAYERS];
+  float *bias[LTEA_MAX_CNN_LAYERS];
+  float *w_out;
+  float *b_out;
+} ltea_cnn_grad;
+size_t ltea_cnn_backward_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int64_t total_tokens);
+int ltea_cnn_backward(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *k_feat, const void *v, int64_t stride_tok,
+                      int64_t stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                      int32_t max_seqlen, const float *dz, const ltea_cnn_grad *grad, void *dk_feat_or_null,
+                      void *dv_or_null, void *workspace, size_t workspace_bytes, void *stream);
 
 /* One feedback step on n penalty weights (Algorithm 1), on HOST arrays: lambda_i is multiplied by alpha where the
  * averaged count c_bar_i exceeds cap, divided by alpha where it is below 0.95 cap, clamped to <= 1, flushed to 0

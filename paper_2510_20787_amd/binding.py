@@ -50,6 +50,10 @@ class ltea_cache(C.Structure):
                 ("n_scored", C.c_void_p)]
 
 
+class ltea_cnn_grad(C.Structure):
+    _fields_ = [("w", C.c_void_p * 4), ("bias", C.c_void_p * 4), ("w_out", C.c_void_p), ("b_out", C.c_void_p)]
+
+
 class ltea_rope(C.Structure):
     _fields_ = [("cos", C.c_void_p), ("sin", C.c_void_p), ("n_pos", C.c_int32), ("rot_dim", C.c_int32),
                 ("interleaved", C.c_int32)]
@@ -58,7 +62,7 @@ class ltea_rope(C.Structure):
 EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
            "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_append_workspace_bytes",
            "ltea_prefill_append", "ltea_prefill_append_feat", "ltea_decode_feat_workspace_bytes",
-           "ltea_decode_step_feat", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
+           "ltea_decode_step_feat", "ltea_cnn_backward_workspace_bytes", "ltea_cnn_backward", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
            "ltea_lambda_update", "ltea_diag_sink_bytes",
            "ltea_diag_mfma_loop", "ltea_diag_stream_read"]
@@ -115,6 +119,11 @@ def lib() -> C.CDLL:
     L.ltea_decode_step_feat.restype = C.c_int
     L.ltea_decode_step_feat.argtypes = [P(ltea_cfg), P(ltea_cnn), P(ltea_rope), vp, vp, vp, vp, vp, P(ltea_cache), i32,
                                         vp, vp, sz, vp]
+    L.ltea_cnn_backward_workspace_bytes.restype = sz
+    L.ltea_cnn_backward_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i64]
+    L.ltea_cnn_backward.restype = C.c_int
+    L.ltea_cnn_backward.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, i64, i64, vp, i32, i64, i32, vp, P(ltea_cnn_grad),
+                                    vp, vp, vp, sz, vp]
     L.ltea_lazy_period.restype = i32
     L.ltea_lazy_period.argtypes = [P(ltea_cfg), P(ltea_cnn)]
     L.ltea_rescore_workspace_bytes.restype = sz
@@ -510,6 +519,38 @@ def ltea_train_backward(cfg: ltea_cfg, q: torch.Tensor, k: torch.Tensor, v: torc
                                      _ptr(dk), _ptr(dv), _ptr(dz), _ptr(counts), _ptr(workspace), workspace.numel(),
                                      _stream()), "ltea_train_backward")
     return dq, dk, dv, dz, counts
+
+
+def ltea_cnn_backward(cfg: ltea_cfg, cnn: Cnn, k_feat: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor,
+                      max_seqlen: int, dz: torch.Tensor, want_inputs: bool = True, workspace: Optional[torch.Tensor] = None):
+    """Gradients of sum(dz * logits) through the scoring CNN.  Returns (dw list, dbias list, dw_out, db_out, dk_feat,
+    dv); the last two are None without want_inputs."""
+    T = k_feat.shape[0]
+    n_seqs = cu_seqlens.numel() - 1
+    st, sh = _tok_head_strides(k_feat)
+    assert _tok_head_strides(v) == (st, sh)
+    s = cnn.struct
+    dev = k_feat.device
+    f32 = lambda *shape: torch.empty(shape, dtype=torch.float32, device=dev)
+    dw, dbias, cin = [], [], 2 * cfg.D
+    for l in range(s.n_layers):
+        dw.append(f32(cfg.Hkv, s.c_out[l], cin, s.kernel[l]))
+        dbias.append(f32(cfg.Hkv, s.c_out[l]))
+        cin = s.c_out[l]
+    dw_out, db_out = f32(cfg.Hkv, cin), f32(cfg.Hkv)
+    g = ltea_cnn_grad()
+    for l in range(s.n_layers):
+        g.w[l] = dw[l].data_ptr()
+        g.bias[l] = dbias[l].data_ptr()
+    g.w_out, g.b_out = dw_out.data_ptr(), db_out.data_ptr()
+    dk = torch.empty((T, cfg.Hkv, cfg.D), dtype=k_feat.dtype, device=dev) if want_inputs else None
+    dv = torch.empty((T, cfg.Hkv, cfg.D), dtype=k_feat.dtype, device=dev) if want_inputs else None
+    if workspace is None:
+        workspace = _workspace(int(lib().ltea_cnn_backward_workspace_bytes(C.byref(cfg), C.byref(s), T)), dev)
+    _check(lib().ltea_cnn_backward(C.byref(cfg), C.byref(s), _ptr(k_feat), _ptr(v), st, sh, _ptr(cu_seqlens), n_seqs, T,
+                                   max_seqlen, _ptr(dz), C.byref(g), _ptr(dk), _ptr(dv), _ptr(workspace),
+                                   workspace.numel(), _stream()), "ltea_cnn_backward")
+    return dw, dbias, dw_out, db_out, dk, dv
 
 
 def ltea_lambda_update(lam, c_bar, cap: float, alpha: float):

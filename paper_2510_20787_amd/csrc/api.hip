@@ -569,6 +569,35 @@ int ltea_train_backward(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok
                                           static_cast<hipStream_t>(stream)));
 }
 
+size_t ltea_cnn_backward_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int64_t total_tokens) {
+  if (check_cfg(cfg) != LTEA_OK || check_cnn(cfg, cnn) != LTEA_OK || total_tokens < 0) return 0;
+  return align_up(cnn_backward_workspace(*cfg, *cnn, total_tokens), 256);
+}
+
+int ltea_cnn_backward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k_feat, const void* v, int64_t stride_tok,
+                      int64_t stride_head, const int32_t* cu_seqlens, int32_t n_seqs, int64_t total_tokens,
+                      int32_t max_seqlen, const float* dz, const ltea_cnn_grad* grad, void* dk_feat, void* dv,
+                      void* workspace, size_t workspace_bytes, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st == LTEA_OK) st = check_seqs(cu_seqlens, n_seqs, total_tokens, max_seqlen);
+  if (st != LTEA_OK) return st;
+  if (!grad || !grad->w_out || !grad->b_out) return LTEA_EINVAL;
+  for (int l = 0; l < cnn->n_layers; ++l)
+    if (!grad->w[l] || !grad->bias[l]) return LTEA_EINVAL;
+  if (total_tokens >= (int64_t)1 << 31) return LTEA_EUNSUPPORTED;   // token bounds are kept as int32
+  if (total_tokens > 0) {
+    if ((st = check_view(k_feat, stride_tok, stride_head, cfg->D, elem_size(cfg->dtype))) != LTEA_OK) return st;
+    if ((st = check_view(v, stride_tok, stride_head, cfg->D, elem_size(cfg->dtype))) != LTEA_OK) return st;
+    if (!dz) return LTEA_EINVAL;
+    if ((dk_feat && !aligned16(dk_feat)) || (dv && !aligned16(dv))) return LTEA_EINVAL;
+    if (!workspace || workspace_bytes < cnn_backward_workspace(*cfg, *cnn, total_tokens)) return LTEA_EWORKSPACE;
+  }
+  SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
+  return hip_status(launch_cnn_backward(*cfg, *cnn, k_feat, v, stride_tok, stride_head, sv, dz, *grad, dk_feat, dv,
+                                        workspace, static_cast<hipStream_t>(stream)));
+}
+
 int ltea_lambda_update(float* lambda, const float* c_bar, int32_t n, float cap, float alpha) {
   if (!lambda || !c_bar || n < 0 || !(alpha > 0.f) || !(cap >= 0.f)) return LTEA_EINVAL;
   for (int i = 0; i < n; ++i) {

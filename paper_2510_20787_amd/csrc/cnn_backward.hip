@@ -1,0 +1,418 @@
+// Backward of the scoring CNN of the LTE module (paper Section 3.1.1; trained through the gradient of the logits
+// that Section 3.1.2 defines): from d(loss)/d(logit) to the gradients of every conv weight, bias, the output
+// projection and the input features.  fp32 VALU arithmetic for any depth and either storage type, as LDS-tiled
+// products (64 x 64 results per workgroup, 4 x 4 per thread): the module is small next to the attention (paper
+// stack: 65 kflop per token-head forward).  Everything is summed in a fixed order: same bits every run.
+//
+//   1. forward again, keeping the pre-activations y_l and the activations a_l = silu(y_l) of every layer
+//      (fp32 [Hkv][T][C_l] each); the features of layer 0 are copied to a dense fp32 array first;
+//   2. d y_L = dz * w_out * silu'(y_L);  d w_out = sum_t dz * silu(y_L),  d b_out = sum_t dz;
+//   3. for l = L .. 1:  d bias_l = sum_t d y_l;
+//                       d W_l[c][m][tap] = sum_t d y_l[t][c] * a_{l-1}[t + off(tap)][m]      (inside the sequence)
+//                       d a_{l-1}[t][m]  = sum_{tap, c} W_l[c][m][tap] * d y_l[t - off(tap)][c]
+//                       d y_{l-1} = d a_{l-1} * silu'(y_{l-1})        (l > 1)   or   dk, dv = d a_0   (l = 1).
+// Sums over tokens are taken in two stages: per chunk of kTokChunk tokens into a partial array, then over the chunks.
+#include "ltea_common.h"
+#include "ltea_kernels.h"
+
+namespace ltea {
+namespace {
+
+constexpr int kTokChunk = 1024;
+
+__device__ __forceinline__ float silu_grad_f32(float y) {
+  const float s = 1.0f / (1.0f + expf(-y));
+  return s * (1.0f + y * (1.0f - s));
+}
+
+// seq_lo[t], seq_hi[t]: bounds of the sequence token t belongs to.
+__global__ void __launch_bounds__(256)
+token_bounds_kernel(const int32_t* __restrict__ cu, int n_seqs, int64_t total, int32_t* __restrict__ seq_lo,
+                    int32_t* __restrict__ seq_hi) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= total) return;
+  const int s = find_sequence(cu, n_seqs, t);
+  seq_lo[t] = cu[s];
+  seq_hi[t] = cu[s + 1];
+}
+
+// d y_L[h][t][c] = dz[h][t] * w_out[h][c] * silu'(y_L[h][t][c])
+template <typename T>
+__global__ void __launch_bounds__(256)
+out_proj_backward_kernel(const float* __restrict__ dz, const T* __restrict__ w_out, const float* __restrict__ pre, int C,
+                         int64_t total, float* __restrict__ dpre) {
+  const int h = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t tok = idx / C;
+  const int c = (int)(idx - tok * C);
+  if (tok >= total) return;
+  const int64_t i = ((int64_t)h * total + tok) * C + c;
+  dpre[i] = dz[(int64_t)h * total + tok] * to_f32(w_out[(int64_t)h * C + c]) * silu_grad_f32(pre[i]);
+}
+
+// Layer-0 input as a dense fp32 array: a0[h][t][m] = concat(key, value) features of token t.
+template <typename T>
+__global__ void __launch_bounds__(256)
+features_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stride_tok, int64_t stride_head, int D,
+                int64_t total, float* __restrict__ a0) {
+  const int h = blockIdx.y;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t tok = idx / (2 * D);
+  const int m = (int)(idx - tok * 2 * D);
+  if (tok >= total) return;
+  const T* src = (m < D ? k : v) + tok * stride_tok + (int64_t)h * stride_head + (m < D ? m : m - D);
+  a0[((int64_t)h * total + tok) * 2 * D + m] = to_f32(*src);
+}
+
+// The weights of one layer as two fp32 panels per head: wf[h][tap][m][c] (contraction over the input channels m: the
+// forward) and wb[h][tap][c][m] (contraction over the output channels c: the backward towards the input).
+template <typename T>
+__global__ void __launch_bounds__(256)
+weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t n, float* __restrict__ wf,
+                     float* __restrict__ wb) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over [h][c][m][tap]
+  if (i >= n) return;
+  const int tap = (int)(i % ks);
+  const int m = (int)((i / ks) % Cin);
+  const int c = (int)((i / ((int64_t)ks * Cin)) % Cout);
+  const int64_t h = i / ((int64_t)ks * Cin * Cout);
+  const float w = to_f32(W[i]);
+  wf[((h * ks + tap) * Cin + m) * Cout + c] = w;
+  wb[((h * ks + tap) * Cout + c) * Cin + m] = w;
+}
+
+constexpr int TM = 64, TN = 64, KC = 16;   // tile of the tiled fp32 products below; 256 threads, 4 x 4 results each
+
+// out[t][n] = sum_tap sum_k in[t + sign * off(tap)][k] * wt[tap][k][n]   (rows outside t's sequence count as zero)
+// for one head, as a tiled fp32 product: TM tokens x TN outputs per workgroup, the contraction in slices of KC per tap
+// through LDS.  What is done with the result:
+//   mode 0 (forward)          pre = out + bias, act = silu(pre)
+//   mode 1 (hidden backward)  dpre_out = out * silu'(pre_prev)
+//   mode 2 (input backward)   dk / dv [T][Hkv][D] of the storage type (n < D: key part)
+template <typename T>
+__global__ void __launch_bounds__(256)
+conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, int K, int N, int ks, int dil, int sign,
+                    const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
+                    int mode, const float* __restrict__ bias, const float* __restrict__ pre_prev,
+                    float* __restrict__ out0, float* __restrict__ out1, T* __restrict__ dk, T* __restrict__ dv, int D) {
+  __shared__ float a_s[KC][TM + 4];
+  __shared__ float b_s[KC][TN + 4];
+  const int h = blockIdx.z;
+  const int64_t t0 = (int64_t)blockIdx.x * TM;
+  const int n0 = blockIdx.y * TN;
+  const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
+  const int lrow = tid / 4, lq = tid % 4;          // loader role: row lrow, four consecutive contraction indices
+  const int64_t lt = t0 + lrow;
+  const bool lt_ok = lt < total;
+  const int64_t lo = lt_ok ? seq_lo[lt] : 0, hi = lt_ok ? seq_hi[lt] : 0;
+  const float* in_h = in + (int64_t)h * total * K;
+  const float* wt_h = wt + (int64_t)h * ks * K * N;
+  const int half = (ks - 1) / 2;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int tap = 0; tap < ks; ++tap) {
+    const int64_t p = lt + (int64_t)sign * (tap - half) * dil;
+    const bool p_ok = lt_ok && p >= lo && p < hi;
+    for (int k0 = 0; k0 < K; k0 += KC) {
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int kk = lq * 4 + j;
+        a_s[kk][lrow] = (p_ok && k0 + kk < K) ? in_h[p * K + k0 + kk] : 0.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int e = tid + 256 * j;                 // 0 .. KC*TN-1: (kk, n) with n fastest
+        const int kk = e / TN, n = e % TN;
+        b_s[kk][n] = (k0 + kk < K && n0 + n < N) ? wt_h[((int64_t)tap * K + k0 + kk) * N + n0 + n] : 0.f;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < KC; ++kk) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = a_s[kk][ty * 4 + i];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[j] = b_s[kk][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t t = t0 + ty * 4 + i;
+    if (t >= total) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n >= N) continue;
+      const int64_t o = ((int64_t)h * total + t) * N + n;
+      if (mode == 0) {
+        const float y = acc[i][j] + bias[(int64_t)h * N + n];
+        out0[o] = y;
+        out1[o] = silu_f32(y);
+      } else if (mode == 1) {
+        out0[o] = acc[i][j] * silu_grad_f32(pre_prev[o]);
+      } else if (n < D) {
+        if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[i][j]);
+      } else {
+        if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[i][j]);
+      }
+    }
+  }
+}
+
+// Stage 1 of d W_l: partial[chunk][h][c][m][tap] = sum over the chunk's tokens t of a_{l-1}[t + off][m] * d y_l[t][c],
+// a tiled fp32 product with the tokens as the contraction index (slices of KC tokens through LDS).
+__global__ void __launch_bounds__(256)
+weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
+                      const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
+                      int tiles_n, float* __restrict__ partial) {
+  __shared__ float a_s[KC][TM + 4];
+  __shared__ float b_s[KC][TN + 4];
+  const int m0 = (blockIdx.x / tiles_n) * TM, c0 = (blockIdx.x % tiles_n) * TN;
+  const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
+  const int chunk = blockIdx.z;
+  const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
+  const int off = (tap - (ks - 1) / 2) * dil;
+  const int64_t tb = (int64_t)chunk * kTokChunk;
+  const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
+  const float* a_h = act_in + (int64_t)h * total * Cin;
+  const float* g_h = dpre + (int64_t)h * total * Cout;
+  float acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+  for (int64_t t0 = tb; t0 < te; t0 += KC) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int e = tid + 256 * j;                   // (token of the slice, channel) with the channel fastest
+      const int tt = e / TM, x = e % TM;
+      const int64_t t = t0 + tt;
+      const bool t_ok = t < te;
+      const int64_t p = t + off;
+      const bool p_ok = t_ok && p >= seq_lo[t_ok ? t : tb] && p < seq_hi[t_ok ? t : tb];
+      a_s[tt][x] = (p_ok && m0 + x < Cin) ? a_h[p * Cin + m0 + x] : 0.f;
+      b_s[tt][x] = (t_ok && c0 + x < Cout) ? g_h[t * Cout + c0 + x] : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int tt = 0; tt < KC; ++tt) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = a_s[tt][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = b_s[tt][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+  }
+  const int64_t per_head = (int64_t)Cout * Cin * ks;
+  float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= Cin) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int c = c0 + tx * 4 + j;
+      if (c < Cout) out[((int64_t)c * Cin + m) * ks + tap] = acc[i][j];     // the layout of the weights: [c][m][tap]
+    }
+  }
+}
+
+// Stage 2: out[i] = sum over chunks of partial[chunk][i], in chunk order.
+__global__ void __launch_bounds__(256)
+chunk_sum_kernel(const float* __restrict__ partial, int64_t n, int chunks, float* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int ch = 0; ch < chunks; ++ch) acc += partial[(int64_t)ch * n + i];
+  out[i] = acc;
+}
+
+// Column sums over the tokens: out[h][c] = sum_t x[h][t][c] (mode 0), sum_t dz[h][t] * x[h][t][c] (mode 1),
+// or, with C = 1, sum_t dz[h][t] (mode 2).  One workgroup per (h, c); each thread sums a strided share in order,
+// the shares meet in a fixed-shape tree.
+__global__ void __launch_bounds__(256)
+column_sum_kernel(const float* __restrict__ x, const float* __restrict__ dz, int C, int64_t total, int mode,
+                  float* __restrict__ out) {
+  __shared__ float red[256];
+  const int h = blockIdx.y, c = blockIdx.x;
+  float acc = 0.f;
+  for (int64_t t = threadIdx.x; t < total; t += 256) {
+    const float g = dz != nullptr ? dz[(int64_t)h * total + t] : 1.0f;
+    if (mode == 2) acc += g;
+    else {
+      const float xv = x[((int64_t)h * total + t) * C + c];
+      acc += mode == 1 ? g * xv : xv;
+    }
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[(int64_t)h * C + c] = red[0];
+}
+
+size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+struct Layout {
+  int32_t *seq_lo, *seq_hi;
+  float* a0;                                  // [Hkv][T][2D] input features as fp32
+  float* pre[LTEA_MAX_CNN_LAYERS];            // [Hkv][T][C_l]
+  float* act[LTEA_MAX_CNN_LAYERS];
+  float* dpre[2];                             // [Hkv][T][widest layer], ping-pong
+  float *wf, *wb;                             // weight panels of the layer at hand (largest layer's size)
+  float* partial;                             // [chunks][Hkv][largest layer's weights]
+  size_t bytes;
+};
+
+Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base) {
+  Layout L;
+  char* p = static_cast<char*>(base);
+  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  const size_t rows = (size_t)cfg.Hkv * (size_t)total;
+  L.seq_lo = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)total));
+  L.seq_hi = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)total));
+  L.a0 = reinterpret_cast<float*>(take(sizeof(float) * rows * 2 * cfg.D));
+  int cmax = 0;
+  size_t wmax = 0;
+  int cin = 2 * cfg.D;
+  for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) L.pre[l] = L.act[l] = nullptr;
+  for (int l = 0; l < cnn.n_layers; ++l) {
+    L.pre[l] = reinterpret_cast<float*>(take(sizeof(float) * rows * cnn.c_out[l]));
+    L.act[l] = reinterpret_cast<float*>(take(sizeof(float) * rows * cnn.c_out[l]));
+    cmax = cnn.c_out[l] > cmax ? cnn.c_out[l] : cmax;
+    const size_t w = (size_t)cnn.c_out[l] * cin * cnn.kernel[l];
+    wmax = w > wmax ? w : wmax;
+    cin = cnn.c_out[l];
+  }
+  for (int i = 0; i < 2; ++i) L.dpre[i] = reinterpret_cast<float*>(take(sizeof(float) * rows * cmax));
+  L.wf = reinterpret_cast<float*>(take(sizeof(float) * cfg.Hkv * wmax));
+  L.wb = reinterpret_cast<float*>(take(sizeof(float) * cfg.Hkv * wmax));
+  const size_t chunks = (size_t)((total + kTokChunk - 1) / kTokChunk);
+  L.partial = reinterpret_cast<float*>(take(sizeof(float) * chunks * cfg.Hkv * wmax));
+  L.bytes = (size_t)(p - static_cast<char*>(base));
+  return L;
+}
+
+template <typename T>
+hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t stride_tok,
+               int64_t stride_head, const SeqView& sv, const float* dz, const ltea_cnn_grad& g, void* dk, void* dv,
+               void* workspace, hipStream_t stream) {
+  const int64_t total = sv.total_tokens;
+  const int Hkv = cfg.Hkv, nl = cnn.n_layers, D = cfg.D;
+  const Layout L = carve(cfg, cnn, total, workspace);
+  hipError_t e;
+  const unsigned tok_tiles = (unsigned)((total + TM - 1) / TM);
+  auto blocks = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
+  auto cin_of = [&](int l) { return l == 0 ? 2 * D : cnn.c_out[l - 1]; };
+  auto in_of = [&](int l) -> const float* { return l == 0 ? L.a0 : L.act[l - 1]; };
+  auto panels = [&](int l) {
+    const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
+    hipLaunchKernelGGL(weight_panels_kernel<T>, blocks(n), dim3(256), 0, stream, static_cast<const T*>(cnn.w[l]), cin_of(l),
+                       cnn.c_out[l], cnn.kernel[l], n, L.wf, L.wb);
+    return hipGetLastError();
+  };
+  hipLaunchKernelGGL(token_bounds_kernel, blocks(total), dim3(256), 0, stream, sv.cu_seqlens, sv.n_seqs, total, L.seq_lo,
+                     L.seq_hi);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(features_kernel<T>, dim3((unsigned)((total * 2 * D + 255) / 256), (unsigned)Hkv), dim3(256), 0, stream,
+                     static_cast<const T*>(k), static_cast<const T*>(v), stride_tok, stride_head, D, total, L.a0);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // 1. forward, pre-activations and activations kept
+  for (int l = 0; l < nl; ++l) {
+    if ((e = panels(l)) != hipSuccess) return e;
+    const int N = cnn.c_out[l];
+    hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
+                       stream, in_of(l), L.wf, cin_of(l), N, cnn.kernel[l], cnn.dilation[l], 1, L.seq_lo, L.seq_hi, total,
+                       Hkv, 0, cnn.bias[l], static_cast<const float*>(nullptr), L.pre[l], L.act[l], static_cast<T*>(nullptr),
+                       static_cast<T*>(nullptr), D);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
+  // 2. output projection
+  const int CL = cnn.c_out[nl - 1];
+  hipLaunchKernelGGL(out_proj_backward_kernel<T>, dim3((unsigned)((total * CL + 255) / 256), (unsigned)Hkv), dim3(256), 0,
+                     stream, dz, static_cast<const T*>(cnn.w_out), L.pre[nl - 1], CL, total, L.dpre[0]);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)CL, (unsigned)Hkv), dim3(256), 0, stream, L.act[nl - 1], dz, CL,
+                     total, 1, g.w_out);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(column_sum_kernel, dim3(1u, (unsigned)Hkv), dim3(256), 0, stream,
+                     static_cast<const float*>(nullptr), dz, 1, total, 2, g.b_out);
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  // 3. layers in reverse
+  const int chunks = (int)((total + kTokChunk - 1) / kTokChunk);
+  int cur = 0;
+  for (int l = nl - 1; l >= 0; --l) {
+    const int Cout = cnn.c_out[l], Cin = cin_of(l), ks = cnn.kernel[l];
+    const float* dpre = L.dpre[cur];
+    hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)Cout, (unsigned)Hkv), dim3(256), 0, stream, dpre,
+                       static_cast<const float*>(nullptr), Cout, total, 0, g.bias[l]);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int tiles_m = (Cin + TM - 1) / TM, tiles_n = (Cout + TN - 1) / TN;
+    hipLaunchKernelGGL(weight_product_kernel, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
+                       dim3(256), 0, stream, in_of(l), dpre, Cin, Cout, ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv,
+                       tiles_n, L.partial);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const int64_t n_w = (int64_t)Cout * Cin * ks * Hkv;
+    hipLaunchKernelGGL(chunk_sum_kernel, blocks(n_w), dim3(256), 0, stream, L.partial, n_w, chunks, g.w[l]);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (l > 0 || dk != nullptr || dv != nullptr) {
+      if ((e = panels(l)) != hipSuccess) return e;
+      // towards the input: contraction over this layer's output channels, taps mirrored
+      hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
+                         stream, dpre, L.wb, Cout, Cin, ks, cnn.dilation[l], -1, L.seq_lo, L.seq_hi, total, Hkv,
+                         l > 0 ? 1 : 2, static_cast<const float*>(nullptr),
+                         l > 0 ? L.pre[l - 1] : static_cast<const float*>(nullptr), L.dpre[cur ^ 1],
+                         static_cast<float*>(nullptr), static_cast<T*>(dk), static_cast<T*>(dv), D);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    cur ^= 1;
+  }
+  return hipSuccess;
+}
+
+}  // namespace
+
+size_t cnn_backward_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total_tokens) {
+  return carve(cfg, cnn, total_tokens, nullptr).bytes;
+}
+
+hipError_t launch_cnn_backward(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                               int64_t stride_tok, int64_t stride_head, const SeqView& sv, const float* dz,
+                               const ltea_cnn_grad& grad, void* dk, void* dv, void* workspace, hipStream_t stream) {
+  if (sv.total_tokens == 0) {   // no tokens: every gradient is zero (a sum over no chunks)
+    auto zero = [&](float* out, int64_t n) {
+      hipLaunchKernelGGL(chunk_sum_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                         static_cast<const float*>(nullptr), n, 0, out);
+    };
+    int cin = 2 * cfg.D;
+    for (int l = 0; l < cnn.n_layers; ++l) {
+      zero(grad.w[l], (int64_t)cfg.Hkv * cnn.c_out[l] * cin * cnn.kernel[l]);
+      zero(grad.bias[l], (int64_t)cfg.Hkv * cnn.c_out[l]);
+      cin = cnn.c_out[l];
+    }
+    zero(grad.w_out, (int64_t)cfg.Hkv * cin);
+    zero(grad.b_out, cfg.Hkv);
+    return hipGetLastError();
+  }
+  if (cfg.dtype == LTEA_F32)
+    return run<float>(cfg, cnn, k, v, stride_tok, stride_head, sv, dz, grad, dk, dv, workspace, stream);
+  return run<bf16_t>(cfg, cnn, k, v, stride_tok, stride_head, sv, dz, grad, dk, dv, workspace, stream);
+}
+
+}  // namespace ltea

@@ -124,6 +124,12 @@ hipError_t launch_decode_step_lazy(const ltea_cfg& cfg, const void* q, const voi
                                    const ltea_cache& cache, int n_seqs, int32_t* status, void* workspace,
                                    hipStream_t stream);
 
+// ---- backward of the scoring CNN (cnn_backward.hip) ---------------------------------------------------------
+size_t cnn_backward_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total_tokens);
+hipError_t launch_cnn_backward(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                               int64_t stride_tok, int64_t stride_head, const SeqView& sv, const float* dz,
+                               const ltea_cnn_grad& grad, void* dk, void* dv, void* workspace, hipStream_t stream);
+
 // ---- training-side backward --------------------------------------------------------------------------------
 // kept: the compact arrays the retention launcher leaves when run with budget = kept_capacity and a cap that never
 // binds (ascending kept out-of-window positions per (sequence, KV head) and their K / V rows).

@@ -213,6 +213,33 @@ def test_decode_feat_argument_errors():
     assert call(wsb=need - 1) == B.LTEA_EWORKSPACE
 
 
+def test_cnn_backward_argument_errors():
+    L = B.lib()
+    cfg, cnn = good_cfg(), fake_cnn()
+    g = B.ltea_cnn_grad()
+    for l in range(4):
+        g.w[l] = 0x1000
+        g.bias[l] = 0x1000
+    g.w_out, g.b_out = 0x1000, 0x1000
+    need = L.ltea_cnn_backward_workspace_bytes(C.byref(cfg), C.byref(cnn), 1000)
+    assert need > 1000 * cfg.Hkv * 2 * cfg.D * 4 and L.ltea_cnn_backward_workspace_bytes(None, C.byref(cnn), 1000) == 0
+    call = lambda **kw: (lambda a: L.ltea_cnn_backward(a["cfg"], a["cnn"], a["k"], a["v"], 128, 64, a["cu"], 1, a["T"], a["T"],
+                                                        a["dz"], a["g"], a["dk"], None, a["ws"], a["wsb"], None))(
+        dict(dict(cfg=C.byref(cfg), cnn=C.byref(cnn), k=0x1000, v=0x1000, cu=0x1000, T=1000, dz=0x1000, g=C.byref(g),
+                  dk=0x1000, ws=0x1000, wsb=need), **kw))
+    assert call(cfg=None) == B.LTEA_EINVAL
+    assert call(cnn=None) == B.LTEA_EINVAL
+    assert call(k=None) == B.LTEA_EINVAL
+    assert call(cu=None) == B.LTEA_EINVAL
+    assert call(dz=None) == B.LTEA_EINVAL
+    assert call(g=None) == B.LTEA_EINVAL
+    assert call(dk=0x1004) == B.LTEA_EINVAL
+    assert call(ws=None) == B.LTEA_EWORKSPACE
+    assert call(wsb=need - 1) == B.LTEA_EWORKSPACE
+    bad = B.ltea_cnn_grad()
+    assert call(g=C.byref(bad)) == B.LTEA_EINVAL
+
+
 def test_lazy_argument_errors():
     L = B.lib()
     cfg, cnn = good_cfg(), fake_cnn()

@@ -126,3 +126,42 @@ def test_train_with_logits_supplied_by_the_caller():
             scale = float(np.max(np.abs(ref)))
             assert max_err(to_np(got), ref) <= GRAD_TOL[dt] * scale, (s, what)
         np.testing.assert_array_equal(counts[s].cpu().numpy(), c_ref)
+
+
+@pytest.mark.parametrize("dtype,kernel,channels,dilation,lens",
+                         [("f32", (5,), (16,), None, [70, 0, 33]), ("bf16", (3, 3, 3), (64, 32, 16), (2, 2, 2), [300, 41]),
+                          ("bf16", (7,), (32,), None, [1500, 900, 1]), ("f32", (3, 1), (8, 24), (2, 1), [5, 2])])
+def test_cnn_backward(dtype, kernel, channels, dilation, lens):
+    """Gradients of sum(dz * logits) through the scoring CNN against the oracle's chain rule: every conv weight and
+    bias, the output projection, and the scored keys / values.  Shapes cover one to three layers, both storage types,
+    more than one token chunk of the two-stage sums, empty and one-token sequences."""
+    Hq, Hkv, D = 4, 2, 64
+    w = wl.make_prefill("cnn_bwd", 1800 + len(kernel) + len(lens), dtype, lens, Hq, Hkv, D, 2 * 13 + 1, 4, 0, 0.0,
+                        cnn_kernel=kernel, cnn_channels=channels, cnn_dilation=dilation, w_std=0.1)
+    ocnn = oracle_cnn(w.cnn)
+    rng = np.random.default_rng(77)
+    dz = rng.standard_normal((Hkv, w.total_tokens)).astype(np.float32)
+    ref = orc.score_backward(w.k, w.v, ocnn, w.cu_seqlens, dz)
+    d = DeviceWorkload(w)
+    got = B.ltea_cnn_backward(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen, torch.from_numpy(dz).cuda())
+    torch.cuda.synchronize()
+
+    def close(a, b, what, rel):
+        a, b = a.float().cpu().numpy().astype(np.float64), np.asarray(b, np.float64)
+        scale = max(float(np.abs(b).max()), 1e-30)
+        err = float(np.abs(a - b).max())
+        assert err <= rel * scale, (what, err, scale)
+
+    # fp32 sums of up to a few thousand terms; the storage type only enters through the rounded inputs (identical on
+    # both sides) and, for dk / dv, through the rounding of the result
+    for l in range(len(kernel)):
+        close(got[0][l], ref[0][l], f"dw[{l}]", 2e-5)
+        close(got[1][l], ref[1][l], f"dbias[{l}]", 2e-5)
+    close(got[2], ref[2], "dw_out", 2e-5)
+    close(got[3], ref[3], "db_out", 2e-5)
+    out_rel = 2e-5 if dtype == "f32" else 2 ** -8
+    close(got[4], ref[4], "dk", out_rel)
+    close(got[5], ref[5], "dv", out_rel)
+    # the same bits on a second run (fixed summation order), and parameter gradients alone on request
+    again = B.ltea_cnn_backward(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen, torch.from_numpy(dz).cuda(), want_inputs=False)
+    assert again[4] is None and torch.equal(again[0][0], got[0][0]) and torch.equal(again[2], got[2])
