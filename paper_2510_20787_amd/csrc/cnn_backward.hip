@@ -242,29 +242,37 @@ chunk_sum_kernel(const float* __restrict__ partial, int64_t n, int chunks, float
 }
 
 // Column sums over the tokens: out[h][c] = sum_t x[h][t][c] (mode 0), sum_t dz[h][t] * x[h][t][c] (mode 1),
-// or, with C = 1, sum_t dz[h][t] (mode 2).  One workgroup per (h, c); each thread sums a strided share in order,
-// the shares meet in a fixed-shape tree.
+// or, with C = 1, sum_t dz[h][t] (mode 2).  One workgroup per (h, tile of c_tile channels, c_tile a power of two
+// <= 64) and chunk of kTokChunk tokens: 256 / c_tile token lanes each sum a strided share in order (neighbouring
+// threads read neighbouring channels of one token), then the lanes of a channel are added in lane order; the chunks
+// are added by chunk_sum_kernel.
 __global__ void __launch_bounds__(256)
-column_sum_kernel(const float* __restrict__ x, const float* __restrict__ dz, int C, int64_t total, int mode,
-                  float* __restrict__ out) {
+column_sum_kernel(const float* __restrict__ x, const float* __restrict__ dz, int C, int c_tile, int64_t total, int mode,
+                  int Hkv, float* __restrict__ partial) {
   __shared__ float red[256];
-  const int h = blockIdx.y, c = blockIdx.x;
+  const int h = blockIdx.y;
+  const int lanes = 256 / c_tile;
+  const int c = blockIdx.x * c_tile + (int)threadIdx.x % c_tile, tl = (int)threadIdx.x / c_tile;
   float acc = 0.f;
-  for (int64_t t = threadIdx.x; t < total; t += 256) {
-    const float g = dz != nullptr ? dz[(int64_t)h * total + t] : 1.0f;
-    if (mode == 2) acc += g;
-    else {
-      const float xv = x[((int64_t)h * total + t) * C + c];
-      acc += mode == 1 ? g * xv : xv;
+  if (c < C) {
+    const int64_t tb = (int64_t)blockIdx.z * kTokChunk;
+    const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
+    for (int64_t t = tb + tl; t < te; t += lanes) {
+      const float g = dz != nullptr ? dz[(int64_t)h * total + t] : 1.0f;
+      if (mode == 2) acc += g;
+      else {
+        const float xv = x[((int64_t)h * total + t) * C + c];
+        acc += mode == 1 ? g * xv : xv;
+      }
     }
   }
   red[threadIdx.x] = acc;
   __syncthreads();
-  for (int s = 128; s > 0; s >>= 1) {
-    if ((int)threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
-    __syncthreads();
+  if (tl == 0 && c < C) {
+    float sum = 0.f;
+    for (int j = 0; j < lanes; ++j) sum += red[j * c_tile + (int)threadIdx.x];
+    partial[((int64_t)blockIdx.z * Hkv + h) * C + c] = sum;
   }
-  if (threadIdx.x == 0) out[(int64_t)h * C + c] = red[0];
 }
 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -348,21 +356,25 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   hipLaunchKernelGGL(out_proj_backward_kernel<T>, dim3((unsigned)((total * CL + 255) / 256), (unsigned)Hkv), dim3(256), 0,
                      stream, dz, static_cast<const T*>(cnn.w_out), L.pre[nl - 1], CL, total, L.dpre[0]);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)CL, (unsigned)Hkv), dim3(256), 0, stream, L.act[nl - 1], dz, CL,
-                     total, 1, g.w_out);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(column_sum_kernel, dim3(1u, (unsigned)Hkv), dim3(256), 0, stream,
-                     static_cast<const float*>(nullptr), dz, 1, total, 2, g.b_out);
-  if ((e = hipGetLastError()) != hipSuccess) return e;
-  // 3. layers in reverse
+  auto c_tile_of = [](int C) { int t = 1; while (t < C && t < 64) t *= 2; return t; };
   const int chunks = (int)((total + kTokChunk - 1) / kTokChunk);
+  auto column_sum = [&](const float* x, const float* dzp, int C, int mode, float* out) {
+    const int ct = c_tile_of(C);
+    hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)((C + ct - 1) / ct), (unsigned)Hkv, (unsigned)chunks), dim3(256), 0,
+                       stream, x, dzp, C, ct, total, mode, Hkv, L.partial);
+    hipError_t ee = hipGetLastError();
+    if (ee != hipSuccess) return ee;
+    hipLaunchKernelGGL(chunk_sum_kernel, blocks((int64_t)Hkv * C), dim3(256), 0, stream, L.partial, (int64_t)Hkv * C, chunks, out);
+    return hipGetLastError();
+  };
+  if ((e = column_sum(L.act[nl - 1], dz, CL, 1, g.w_out)) != hipSuccess) return e;
+  if ((e = column_sum(nullptr, dz, 1, 2, g.b_out)) != hipSuccess) return e;
+  // 3. layers in reverse
   int cur = 0;
   for (int l = nl - 1; l >= 0; --l) {
     const int Cout = cnn.c_out[l], Cin = cin_of(l), ks = cnn.kernel[l];
     const float* dpre = L.dpre[cur];
-    hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)Cout, (unsigned)Hkv), dim3(256), 0, stream, dpre,
-                       static_cast<const float*>(nullptr), Cout, total, 0, g.bias[l]);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = column_sum(dpre, nullptr, Cout, 0, g.bias[l])) != hipSuccess) return e;
     const int tiles_m = (Cin + TM - 1) / TM, tiles_n = (Cout + TN - 1) / TN;
     hipLaunchKernelGGL(weight_product_kernel, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
                        dim3(256), 0, stream, in_of(l), dpre, Cin, Cout, ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv,
