@@ -20,7 +20,10 @@ Also reported on the same JSON line:
                 kernel's achieved HBM bandwidth; `lazy`: the same steps without per-step scoring plus one
                 batched scoring per ltea_lazy_period() steps.
   train         training-side forward + backward (no cap) on the paper's module shape, every head keeping
-                budget/N of its tokens; ms per pass and the backward kernels against the bf16 MFMA peak.
+                budget/N of its tokens; ms per pass and the backward kernels against the bf16 MFMA peak; the scoring
+                CNN's own backward is timed beside it (cnn_backward_ms).
+  seqlen_sweep  (--seqlen-sweep) the attention kernel alone and the paper's whole LTE layer against the sequence
+                length at batch 32 (the shapes of the paper's efficiency figures).
   cpu_baseline  the fp64 NumPy oracle timed on this machine's host cores on a bounded sample.
 """
 from __future__ import annotations
