@@ -1,7 +1,7 @@
 // Backward of the scoring CNN of the LTE module (paper Section 3.1.1; trained through the gradient of the logits
 // that Section 3.1.2 defines): from d(loss)/d(logit) to the gradients of every conv weight, bias, the output
-// projection and the input features.  fp32 VALU arithmetic for any depth and either storage type, as LDS-tiled
-// products (64 x 64 results per workgroup, 4 x 4 per thread): the module is small next to the attention (paper
+// projection and the input features.  fp32 arithmetic for any depth and either storage type, as LDS-tiled products
+// on the fp32 matrix instruction (64 x 64 results per workgroup): the module is small next to the attention (paper
 // stack: 65 kflop per token-head forward).  Everything is summed in a fixed order: same bits every run.
 //
 //   1. forward again, keeping the pre-activations y_l and the activations a_l = silu(y_l) of every layer
@@ -81,7 +81,12 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
   wb[((h * ks + tap) * Cout + c) * Cin + m] = w;
 }
 
-constexpr int TM = 64, TN = 64, KC = 16;   // tile of the tiled fp32 products below; 256 threads, 4 x 4 results each
+// Tile of the fp32 products below: 64 x 64 results per workgroup, the contraction in slices of KC through LDS.  Each of
+// the four waves owns a 32 x 32 quarter and runs it on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per
+// instruction: lane l supplies row / column l % 32 of step l / 32).  LDS rows are 96 floats apart so that the two
+// lane halves of an operand read land in different banks.
+constexpr int TM = 64, TN = 64, KC = 16, LS = 96;
+constexpr int PER = KC * TM / 256;   // elements of each operand tile a thread moves per stage
 
 // out[t][n] = sum_tap sum_k in[t + sign * off(tap)][k] * wt[tap][k][n]   (rows outside t's sequence count as zero)
 // for one head, as a tiled fp32 product: TM tokens x TN outputs per workgroup, the contraction in slices of KC per tap
@@ -95,75 +100,73 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
                     const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                     int mode, const float* __restrict__ bias, const float* __restrict__ pre_prev,
                     float* __restrict__ out0, float* __restrict__ out1, T* __restrict__ dk, T* __restrict__ dv, int D) {
-  __shared__ float a_s[KC][TM + 4];
-  __shared__ float b_s[KC][TN + 4];
+  __shared__ float a_s[KC][LS];
+  __shared__ float b_s[KC][LS];
   const int h = blockIdx.z;
   const int64_t t0 = (int64_t)blockIdx.x * TM;
   const int n0 = blockIdx.y * TN;
-  const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
-  const int lrow = tid / 4, lq = tid % 4;          // loader role: row lrow, four consecutive contraction indices
+  const int tid = threadIdx.x;
+  const int lrow = tid / 4, lq = tid % 4;          // loader role: row lrow, PER consecutive contraction indices
   const int64_t lt = t0 + lrow;
   const bool lt_ok = lt < total;
   const int64_t lo = lt_ok ? seq_lo[lt] : 0, hi = lt_ok ? seq_hi[lt] : 0;
   const float* in_h = in + (int64_t)h * total * K;
   const float* wt_h = wt + (int64_t)h * ks * K * N;
   const int half = (ks - 1) / 2;
-  float acc[4][4];
+  const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
+  f32x16 acc;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-  for (int tap = 0; tap < ks; ++tap) {
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // Stages = (tap, contraction slice) pairs; the next stage's operands are fetched into registers while the current
+  // one is multiplied, so the global latency passes under the matrix work.
+  const int slices = (K + KC - 1) / KC, stages = ks * slices;
+  float ra[PER], rb[PER];
+  auto fetch = [&](int stage) {
+    const int tap = stage / slices, k0 = (stage - tap * slices) * KC;
     const int64_t p = lt + (int64_t)sign * (tap - half) * dil;
     const bool p_ok = lt_ok && p >= lo && p < hi;
-    for (int k0 = 0; k0 < K; k0 += KC) {
-      __syncthreads();
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int kk = lq * 4 + j;
-        a_s[kk][lrow] = (p_ok && k0 + kk < K) ? in_h[p * K + k0 + kk] : 0.f;
-      }
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int e = tid + 256 * j;                 // 0 .. KC*TN-1: (kk, n) with n fastest
-        const int kk = e / TN, n = e % TN;
-        b_s[kk][n] = (k0 + kk < K && n0 + n < N) ? wt_h[((int64_t)tap * K + k0 + kk) * N + n0 + n] : 0.f;
-      }
-      __syncthreads();
-#pragma unroll
-      for (int kk = 0; kk < KC; ++kk) {
-        float a[4], b[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) a[i] = a_s[kk][ty * 4 + i];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) b[j] = b_s[kk][tx * 4 + j];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-      }
+    for (int j = 0; j < PER; ++j) {
+      const int kk = lq * PER + j;
+      ra[j] = (p_ok && k0 + kk < K) ? in_h[p * K + k0 + kk] : 0.f;
     }
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+      const int e = tid + 256 * j;                   // 0 .. KC*TN-1: (kk, n) with n fastest
+      const int kk = e / TN, n = e % TN;
+      rb[j] = (k0 + kk < K && n0 + n < N) ? wt_h[((int64_t)tap * K + k0 + kk) * N + n0 + n] : 0.f;
+    }
+  };
+  fetch(0);
+  for (int stage = 0; stage < stages; ++stage) {
+    __syncthreads();     // the previous stage's tiles are no longer read
+#pragma unroll
+    for (int j = 0; j < PER; ++j) a_s[lq * PER + j][lrow] = ra[j];
+#pragma unroll
+    for (int j = 0; j < PER; ++j) b_s[(tid + 256 * j) / TN][(tid + 256 * j) % TN] = rb[j];
+    __syncthreads();
+    if (stage + 1 < stages) fetch(stage + 1);
+#pragma unroll
+    for (int kk = 0; kk < KC; kk += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s[kk + hb][32 * mi + ql], b_s[kk + hb][32 * ni + ql], acc, 0, 0, 0);
   }
+  // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the quarter, output column ql
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t t = t0 + ty * 4 + i;
-    if (t >= total) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int n = n0 + tx * 4 + j;
-      if (n >= N) continue;
-      const int64_t o = ((int64_t)h * total + t) * N + n;
-      if (mode == 0) {
-        const float y = acc[i][j] + bias[(int64_t)h * N + n];
-        out0[o] = y;
-        out1[o] = silu_f32(y);
-      } else if (mode == 1) {
-        out0[o] = acc[i][j] * silu_grad_f32(pre_prev[o]);
-      } else if (n < D) {
-        if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[i][j]);
-      } else {
-        if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[i][j]);
-      }
+  for (int r = 0; r < 16; ++r) {
+    const int64_t t = t0 + 32 * mi + 8 * (r / 4) + 4 * hb + (r % 4);
+    const int n = n0 + 32 * ni + ql;
+    if (t >= total || n >= N) continue;
+    const int64_t o = ((int64_t)h * total + t) * N + n;
+    if (mode == 0) {
+      const float y = acc[r] + bias[(int64_t)h * N + n];
+      out0[o] = y;
+      out1[o] = silu_f32(y);
+    } else if (mode == 1) {
+      out0[o] = acc[r] * silu_grad_f32(pre_prev[o]);
+    } else if (n < D) {
+      if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[r]);
+    } else {
+      if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[r]);
     }
   }
 }
@@ -174,60 +177,57 @@ __global__ void __launch_bounds__(256)
 weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
                       const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                       int tiles_n, float* __restrict__ partial) {
-  __shared__ float a_s[KC][TM + 4];
-  __shared__ float b_s[KC][TN + 4];
+  __shared__ float a_s[KC][LS];
+  __shared__ float b_s[KC][LS];
   const int m0 = (blockIdx.x / tiles_n) * TM, c0 = (blockIdx.x % tiles_n) * TN;
   const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
   const int chunk = blockIdx.z;
-  const int tid = threadIdx.x, ty = tid / 16, tx = tid % 16;
+  const int tid = threadIdx.x;
   const int off = (tap - (ks - 1) / 2) * dil;
   const int64_t tb = (int64_t)chunk * kTokChunk;
   const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
   const float* a_h = act_in + (int64_t)h * total * Cin;
   const float* g_h = dpre + (int64_t)h * total * Cout;
-  float acc[4][4];
+  const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
+  f32x16 acc;
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  float ra[PER], rb[PER];
+  auto fetch = [&](int64_t t0) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
-  for (int64_t t0 = tb; t0 < te; t0 += KC) {
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < PER; ++j) {
       const int e = tid + 256 * j;                   // (token of the slice, channel) with the channel fastest
       const int tt = e / TM, x = e % TM;
       const int64_t t = t0 + tt;
       const bool t_ok = t < te;
       const int64_t p = t + off;
       const bool p_ok = t_ok && p >= seq_lo[t_ok ? t : tb] && p < seq_hi[t_ok ? t : tb];
-      a_s[tt][x] = (p_ok && m0 + x < Cin) ? a_h[p * Cin + m0 + x] : 0.f;
-      b_s[tt][x] = (t_ok && c0 + x < Cout) ? g_h[t * Cout + c0 + x] : 0.f;
+      ra[j] = (p_ok && m0 + x < Cin) ? a_h[p * Cin + m0 + x] : 0.f;
+      rb[j] = (t_ok && c0 + x < Cout) ? g_h[t * Cout + c0 + x] : 0.f;
     }
+  };
+  fetch(tb);
+  for (int64_t t0 = tb; t0 < te; t0 += KC) {
     __syncthreads();
 #pragma unroll
-    for (int tt = 0; tt < KC; ++tt) {
-      float a[4], b[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) a[i] = a_s[tt][ty * 4 + i];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) b[j] = b_s[tt][tx * 4 + j];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    for (int j = 0; j < PER; ++j) {
+      const int e = tid + 256 * j;
+      a_s[e / TM][e % TM] = ra[j];
+      b_s[e / TM][e % TM] = rb[j];
     }
+    __syncthreads();
+    if (t0 + KC < te) fetch(t0 + KC);   // the next slice's operands travel while this one is multiplied
+#pragma unroll
+    for (int tt = 0; tt < KC; tt += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s[tt + hb][32 * mi + ql], b_s[tt + hb][32 * ni + ql], acc, 0, 0, 0);
   }
   const int64_t per_head = (int64_t)Cout * Cin * ks;
   float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int m = m0 + ty * 4 + i;
-    if (m >= Cin) continue;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int c = c0 + tx * 4 + j;
-      if (c < Cout) out[((int64_t)c * Cin + m) * ks + tap] = acc[i][j];     // the layout of the weights: [c][m][tap]
-    }
+  for (int r = 0; r < 16; ++r) {
+    const int m = m0 + 32 * mi + 8 * (r / 4) + 4 * hb + (r % 4);
+    const int c = c0 + 32 * ni + ql;
+    if (m < Cin && c < Cout) out[((int64_t)c * Cin + m) * ks + tap] = acc[r];     // the layout of the weights: [c][m][tap]
   }
 }
 
