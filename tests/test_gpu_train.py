@@ -165,3 +165,40 @@ def test_cnn_backward(dtype, kernel, channels, dilation, lens):
     # the same bits on a second run (fixed summation order), and parameter gradients alone on request
     again = B.ltea_cnn_backward(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen, torch.from_numpy(dz).cuda(), want_inputs=False)
     assert again[4] is None and torch.equal(again[0][0], got[0][0]) and torch.equal(again[2], got[2])
+
+
+@pytest.mark.parametrize("name", ["f32_d64", "f32_d128_deep", "bf16_d64_deep"])
+def test_training_chain_from_dout_to_the_cnn_weights(name):
+    """The three training entry points chained the way a training step uses them: forward, attention backward (which
+    hands over d logits), CNN backward on those d logits.  Reference: the oracle's three functions chained the same
+    way.  The weight gradients then carry the d-logit error of the attention backward, so the bar is GRAD_TOL relative
+    to the largest entry of each gradient array."""
+    dt, lens, Hq, Hkv, D, window, sink, ker, ch, dil, w_std = CASES[name]
+    w = wl.make_prefill(name, sum(map(ord, name)), dt, lens, Hq, Hkv, D, window, 1, sink, 0.0, cnn_kernel=ker,
+                        cnn_channels=ch, cnn_dilation=dil, qkv_scale=1.0, w_std=w_std)
+    cfg, cnn = oracle_cfg(w), oracle_cnn(w.cnn)
+    rng = np.random.default_rng(w.seed + 99)
+    dout = wl.to_storage(rng.standard_normal((w.total_tokens, Hq, D), dtype=np.float32), dt)
+    lam = np.abs(rng.standard_normal(Hkv)).astype(np.float32) * np.float32(0.1)
+    z64 = orc.score(w.k, w.v, cnn, w.cu_seqlens)
+    dz_ref = np.zeros((Hkv, w.total_tokens))
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        if hi > lo:
+            dz_ref[:, lo:hi] = orc.train_backward_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], z64[:, lo:hi], dout[lo:hi],
+                                                           cfg, lam.astype(np.float64))[3]
+    ref = orc.score_backward(w.k, w.v, cnn, w.cu_seqlens, dz_ref)
+    d = DeviceWorkload(w)
+    out, lse, logits, ws = B.ltea_train_forward(d.cfg, d.cnn, d.q, d.k, d.v, d.cu, d.max_seqlen)
+    grads = B.ltea_train_backward(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, out, dev(dout, dt), lse, logits,
+                                  torch.from_numpy(lam).cuda(), ws)
+    got = B.ltea_cnn_backward(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen, grads[3])
+    torch.cuda.synchronize()
+    tol = GRAD_TOL[dt]
+    names = [f"dw[{l}]" for l in range(len(ker))] + [f"dbias[{l}]" for l in range(len(ker))] + ["dw_out", "db_out", "dk", "dv"]
+    arrays_g = list(got[0]) + list(got[1]) + [got[2], got[3], got[4], got[5]]
+    arrays_r = list(ref[0]) + list(ref[1]) + [ref[2], ref[3], ref[4], ref[5]]
+    for nm, a, b in zip(names, arrays_g, arrays_r):
+        a = a.float().cpu().numpy().astype(np.float64)
+        scale = max(float(np.abs(b).max()), 1e-30)
+        assert float(np.abs(a - b).max()) <= tol * scale, (nm, float(np.abs(a - b).max()), scale)
