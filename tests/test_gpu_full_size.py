@@ -336,6 +336,19 @@ def test_full_train_paper_stack_bf16():
             zh = z64[h, lo:hi]
             unsure = int((np.abs(zh) <= 2 * eps).sum())
             assert abs(int(cnt_g[s, h]) - int((zh.astype(np.float32) > 0).sum())) <= unsure
+    # the scoring CNN's backward at this size (16 token chunks of the two-stage sums), on a random d logits so that the
+    # comparison does not inherit the attention backward's error: every parameter and input gradient, all heads
+    dz_in = rng.standard_normal((w.Hkv, w.total_tokens)).astype(np.float32)
+    got = B.ltea_cnn_backward(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen, torch.from_numpy(dz_in).cuda())
+    ref = orc.score_backward(w.k, w.v, cnn, w.cu_seqlens, dz_in)
+    flat_g = list(got[0]) + list(got[1]) + [got[2], got[3]]
+    flat_r = list(ref[0]) + list(ref[1]) + [ref[2], ref[3]]
+    for i, (a, b) in enumerate(zip(flat_g, flat_r)):
+        a = a.float().cpu().numpy().astype(np.float64)
+        assert float(np.abs(a - b).max()) <= 1e-4 * float(np.abs(b).max()), (i, float(np.abs(a - b).max()), float(np.abs(b).max()))
+    for a, b, what in ((got[4], ref[4], "dk"), (got[5], ref[5], "dv")):
+        a = a.float().cpu().numpy().astype(np.float64)
+        assert float(np.abs(a - b).max()) <= 2 ** -7 * float(np.abs(b).max()), what
 
 
 @pytest.mark.parametrize("lazy", [False, True])
