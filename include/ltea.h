@@ -312,7 +312,9 @@ size_t ltea_train_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int3
  * the keys query i sees; logits: [Hkv][total_tokens] fp32.  With `cnn` given the logits are computed and written
  * (rho is ignored).  With cnn == NULL the logits are an INPUT: a framework that runs the scoring CNN under its own
  * autograd passes its logits here (and rho, the CNN's look-ahead, which must satisfy window >= 2*rho + 1) and feeds
- * the d logits of ltea_train_backward back into its graph.  Other arguments as ltea_prefill. */
+ * the d logits of ltea_train_backward back into its graph; a rotary model passes the logits ltea_score gives for its
+ * unrotated keys, k here being the rotated ones (and hands the same unrotated keys to ltea_cnn_backward).  Other
+ * arguments as ltea_prefill. */
 int ltea_train_forward(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, int64_t q_stride_tok,
                        int64_t q_stride_head, const void *k, const void *v, int64_t kv_stride_tok,
                        int64_t kv_stride_head, const int32_t *cu_seqlens, int32_t n_seqs, int64_t total_tokens,
