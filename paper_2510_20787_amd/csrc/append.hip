@@ -44,9 +44,8 @@ struct AppendPlan {        // device arrays in the workspace, one entry per sequ
   int32_t* local_pos;      // [n_seqs][Hkv][budget] kept positions in the ring + new frame (for the attention kernel)
 };
 
-__global__ void __launch_bounds__(256)
-append_plan_kernel(AppendPlan P, const int32_t* __restrict__ cu_new, const int32_t* __restrict__ n_seen, int n_seqs,
-                   int window, int budget) {
+__device__ __forceinline__ void plan_body(const AppendPlan& P, const int32_t* __restrict__ cu_new,
+                                          const int32_t* __restrict__ n_seen, int n_seqs, int window, int budget) {
   // one workgroup: sequential prefix sum over the sequences (a handful to a few thousand)
   __shared__ int carry;
   if (threadIdx.x == 0) carry = 0;
@@ -95,10 +94,9 @@ append_plan_kernel(AppendPlan P, const int32_t* __restrict__ cu_new, const int32
 }
 
 // Rank of every old kept entry by position (positions are distinct): O(count^2 / threads), count <= budget.
-__global__ void __launch_bounds__(256)
-append_rank_kernel(AppendPlan P, const int32_t* __restrict__ ret_pos, const int32_t* __restrict__ ret_count, int budget,
-                   int32_t* __restrict__ old_count) {
-  const int64_t head = blockIdx.x;
+__device__ __forceinline__ void rank_body(const AppendPlan& P, int64_t head, const int32_t* __restrict__ ret_pos,
+                                          const int32_t* __restrict__ ret_count, int budget,
+                                          int32_t* __restrict__ old_count) {
   const int cnt = budget > 0 ? ret_count[head] : 0;
   if (threadIdx.x == 0) old_count[head] = cnt;   // the retention stage overwrites ret_count; the translation stage needs this
   const int32_t* pos = ret_pos + head * budget;
@@ -109,6 +107,15 @@ append_rank_kernel(AppendPlan P, const int32_t* __restrict__ ret_pos, const int3
     P.sorted_pos[head * budget + rank] = p;
     P.sorted_slot[head * budget + rank] = i;
   }
+}
+
+// One launch for both preparations (they do not depend on each other): workgroup 0 plans, workgroup 1 + head ranks.
+__global__ void __launch_bounds__(256)
+append_plan_rank_kernel(AppendPlan P, const int32_t* __restrict__ cu_new, const int32_t* __restrict__ n_seen, int n_seqs,
+                        int window, int budget, const int32_t* __restrict__ ret_pos,
+                        const int32_t* __restrict__ ret_count, int32_t* __restrict__ old_count) {
+  if (blockIdx.x == 0) plan_body(P, cu_new, n_seen, n_seqs, window, budget);
+  else rank_body(P, (int64_t)blockIdx.x - 1, ret_pos, ret_count, budget, old_count);
 }
 
 struct BuildArgs {
@@ -296,12 +303,9 @@ hipError_t launch_append_build(const ltea_cfg& cfg, const void* k_new, const voi
   char* ext_kf = feature_keys ? static_cast<char*>(workspace) + used : nullptr;
   const int64_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   const unsigned heads = (unsigned)n_seqs * (unsigned)cfg.Hkv;
-  hipLaunchKernelGGL(append_plan_kernel, dim3(1), dim3(256), 0, stream, P, cu_new, c.n_seen, n_seqs, cfg.window, cfg.budget);
+  hipLaunchKernelGGL(append_plan_rank_kernel, dim3(1u + heads), dim3(256), 0, stream, P, cu_new, c.n_seen, n_seqs, cfg.window,
+                     cfg.budget, c.ret_pos, c.ret_count, old_count);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(append_rank_kernel, dim3(heads), dim3(256), 0, stream, P, c.ret_pos, c.ret_count, cfg.budget,
-                     old_count);
-  e = hipGetLastError();
   if (e != hipSuccess) return e;
   BuildArgs a;
   a.k_new = static_cast<const char*>(k_new); a.v_new = static_cast<const char*>(v_new);
