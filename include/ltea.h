@@ -114,7 +114,9 @@ const char *ltea_strerror(int status);
 
 /* Bytes of device workspace ltea_score / ltea_retain / ltea_sparse_attention /
  * ltea_prefill need for these sizes (0 is a valid answer).  Returns 0 on
- * invalid arguments as well; the entry points report those themselves. */
+ * invalid arguments as well; the entry points report those themselves.
+ * Every workspace pointer of this library, here and below, must be 256-byte
+ * aligned (device allocations are); a misaligned one is LTEA_EINVAL. */
 size_t ltea_workspace_bytes(const ltea_cfg *cfg, const ltea_cnn *cnn, int32_t n_seqs, int64_t total_tokens,
                             int32_t max_seqlen);
 

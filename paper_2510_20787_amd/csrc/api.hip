@@ -17,6 +17,8 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int elem_size(int dtype) { return dtype == LTEA_F32 ? 4 : 2; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+// workspaces are carved into 256-byte aligned parts that the kernels move in 16-byte pieces
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 int check_cfg(const ltea_cfg* cfg) {
   if (!cfg) return LTEA_EINVAL;
@@ -213,6 +215,7 @@ int ltea_score(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k, const vo
   if (!logits) return LTEA_EINVAL;
   const size_t need = score_workspace(*cfg, *cnn, total_tokens);
   if (need > 0 && (!workspace || workspace_bytes < need)) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
   return do_score(*cfg, *cnn, k, v, stride_tok, stride_head, sv, logits, workspace, static_cast<hipStream_t>(stream));
 }
@@ -282,6 +285,7 @@ int ltea_prefill_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, i
   const size_t score_ws = score_workspace(*cfg, *cnn, total_tokens);
   const size_t need = (logits_or_null ? 0 : logits_bytes) + score_ws;
   if (need > 0 && (!workspace || workspace_bytes < need)) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   char* ws = static_cast<char*>(workspace);
   float* logits = logits_or_null;
   if (!logits) { logits = reinterpret_cast<float*>(ws); ws += logits_bytes; }
@@ -354,6 +358,7 @@ int ltea_prefill_append_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const lte
   const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new, rope != nullptr), 256);
   const size_t need = build_ws + score_workspace(*cfg, *cnn, ext);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int rho = cnn_rho(cnn);
   AppendBuffers buf;
@@ -401,6 +406,7 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
                                  workspace_bytes, stream);
   const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace, workspace_bytes,
                                        static_cast<hipStream_t>(stream)));
 }
@@ -429,6 +435,7 @@ int ltea_decode_step_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_r
   const size_t step_ws = align_up(decode_workspace(*cfg, n_seqs), 256);
   const size_t win_ws = align_up(decode_windows_layout(*cfg, rho, n_seqs, nullptr, nullptr), 256);
   if (!workspace || workspace_bytes < step_ws + win_ws + score_workspace(*cfg, *cnn, rows)) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   char* base = static_cast<char*>(workspace);
   DecodeWindows w;
@@ -466,6 +473,7 @@ int ltea_rescore(const ltea_cfg* cfg, const ltea_cnn* cnn, const ltea_rope* rope
   const size_t pack_ws = align_up(rescore_workspace(*cfg, n_seqs, nullptr, nullptr), 256);
   const size_t need = pack_ws + score_workspace(*cfg, *cnn, total);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   RescoreBuffers buf;
   rescore_workspace(*cfg, n_seqs, &buf, workspace);
@@ -490,6 +498,7 @@ int ltea_decode_step_lazy(const ltea_cfg* cfg, const void* q, const void* k, con
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return LTEA_EINVAL;
   const size_t need = align_up(decode_workspace(*cfg, n_seqs), 256);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   return hip_status(launch_decode_step_lazy(*cfg, q, k, v, out, *cache, n_seqs, status, workspace,
                                             static_cast<hipStream_t>(stream)));
 }
@@ -525,6 +534,7 @@ int ltea_train_forward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, 
   const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
   const size_t need = saved + (cnn ? score_workspace(*cfg, *cnn, total_tokens) : 0);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   ltea_cache cache;
   carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, nullptr);
   ltea_cfg open = *cfg;
@@ -559,6 +569,7 @@ int ltea_train_backward(const ltea_cfg* cfg, const void* q, int64_t q_stride_tok
   }
   const size_t saved = carve_train(*cfg, n_seqs, total_tokens, max_seqlen, nullptr, nullptr, nullptr);
   if (!workspace || workspace_bytes < saved) return LTEA_EWORKSPACE;
+  if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   ltea_cache cache;
   float *delta = nullptr, *far_dk = nullptr, *far_dv = nullptr;
   carve_train(*cfg, n_seqs, total_tokens, max_seqlen, workspace, &cache, &delta, &far_dk, &far_dv);
@@ -592,6 +603,7 @@ int ltea_cnn_backward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k_fe
     if (!dz) return LTEA_EINVAL;
     if ((dk_feat && !aligned16(dk_feat)) || (dv && !aligned16(dv))) return LTEA_EINVAL;
     if (!workspace || workspace_bytes < cnn_backward_workspace(*cfg, *cnn, total_tokens)) return LTEA_EWORKSPACE;
+    if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   }
   SeqView sv{cu_seqlens, n_seqs, total_tokens, max_seqlen};
   return hip_status(launch_cnn_backward(*cfg, *cnn, k_feat, v, stride_tok, stride_head, sv, dz, *grad, dk_feat, dv,

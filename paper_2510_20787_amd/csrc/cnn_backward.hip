@@ -14,11 +14,13 @@
 // Sums over tokens are taken in two stages: per chunk of kTokChunk tokens into a partial array, then over the chunks.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "rope_dev.h"
 
 namespace ltea {
 namespace {
 
-constexpr int kTokChunk = 1024;
+constexpr int kTokChunk = 512;   // tokens per partial of the weight products
+constexpr int kColChunk = 128;   // tokens per partial of the column sums
 
 __device__ __forceinline__ float silu_grad_f32(float y) {
   const float s = 1.0f / (1.0f + expf(-y));
@@ -50,18 +52,25 @@ out_proj_backward_kernel(const float* __restrict__ dz, const T* __restrict__ w_o
   dpre[i] = dz[(int64_t)h * total + tok] * to_f32(w_out[(int64_t)h * C + c]) * silu_grad_f32(pre[i]);
 }
 
-// Layer-0 input as a dense fp32 array: a0[h][t][m] = concat(key, value) features of token t.
+// Layer-0 input as a dense fp32 array: a0[h][t][m] = concat(key, value) features of token t, moved in 16-byte pieces of
+// the storage type (rows of D elements are whole pieces).
 template <typename T>
 __global__ void __launch_bounds__(256)
 features_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stride_tok, int64_t stride_head, int D,
                 int64_t total, float* __restrict__ a0) {
+  constexpr int EPP = Elems<T>::N;
   const int h = blockIdx.y;
+  const int pieces = 2 * D / EPP;
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t tok = idx / (2 * D);
-  const int m = (int)(idx - tok * 2 * D);
+  const int64_t tok = idx / pieces;
+  const int m = (int)(idx - tok * pieces) * EPP;
   if (tok >= total) return;
   const T* src = (m < D ? k : v) + tok * stride_tok + (int64_t)h * stride_head + (m < D ? m : m - D);
-  a0[((int64_t)h * total + tok) * 2 * D + m] = to_f32(*src);
+  float x[EPP];
+  Elems<T>::unpack(*reinterpret_cast<const u32x4*>(src), x);
+  float4* dst = reinterpret_cast<float4*>(a0 + ((int64_t)h * total + tok) * 2 * D + m);
+#pragma unroll
+  for (int i = 0; i < EPP / 4; ++i) dst[i] = make_float4(x[4 * i], x[4 * i + 1], x[4 * i + 2], x[4 * i + 3]);
 }
 
 // The weights of one layer as two fp32 panels per head: wf[h][tap][m][c] (contraction over the input channels m: the
@@ -87,10 +96,32 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
 // lane halves of an operand read land in different banks.
 constexpr int TM = 64, TN = 64, KC = 16, LS = 96;
 constexpr int PER = KC * TM / 256;   // elements of each operand tile a thread moves per stage
+// conv products: TMC tokens per workgroup (two 32-token sub-tiles per wave), contraction slices of KCC channels, up
+// to GT taps per stage whose rows reach at most HALO past the tile; LDS row strides RSA / RSB keep the 16-byte operand
+// reads of 16 neighbouring lanes, and the two lane halves' weight reads, on different banks
+constexpr int TMC = 128, KCC = 16, HALO = 64, GT = 3, RSA = KCC + 4, RSB = 72;
+constexpr int A_ROWS = TMC + HALO, PA = A_ROWS * (KCC / 4) / 256, PB = GT * KCC * (TN / 4) / 256;
+static_assert(A_ROWS * (KCC / 4) % 256 == 0 && GT * KCC * (TN / 4) % 256 == 0, "whole quads per thread");
+constexpr int KCW = 32, PERW = KCW * TM / 256;   // weight products: tokens per contraction slice
+
+// row[x .. x+3] of a row of `limit` floats; elements at or past the limit, or the whole quad when !ok, read as zero.
+// vec: limit % 4 == 0 and the row starts on a 16-byte boundary, so a quad is inside or outside as a whole.
+__device__ __forceinline__ float4 load_quad(const float* __restrict__ row, int x, int limit, bool ok, bool vec) {
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (!ok || x >= limit) return v;
+  if (vec) return *reinterpret_cast<const float4*>(row + x);
+  v.x = row[x];
+  if (x + 1 < limit) v.y = row[x + 1];
+  if (x + 2 < limit) v.z = row[x + 2];
+  if (x + 3 < limit) v.w = row[x + 3];
+  return v;
+}
 
 // out[t][n] = sum_tap sum_k in[t + sign * off(tap)][k] * wt[tap][k][n]   (rows outside t's sequence count as zero)
-// for one head, as a tiled fp32 product: TM tokens x TN outputs per workgroup, the contraction in slices of KC per tap
-// through LDS.  What is done with the result:
+// for one head, as a tiled fp32 product: TMC tokens x TN outputs per workgroup.  A stage brings one contraction slice
+// of KCC channels into LDS: the input rows of the tile plus the extra rows that a group of up to GT taps reaches
+// (at most HALO), and those taps' weight rows; every staged input row then serves all taps of the group.  Whether a
+// tap's row lies in the token's own sequence is decided where the operand is read.  What is done with the result:
 //   mode 0 (forward)          pre = out + bias, act = silu(pre)
 //   mode 1 (hidden backward)  dpre_out = out * silu'(pre_prev)
 //   mode 2 (input backward)   dk / dv [T][Hkv][D] of the storage type (n < D: key part)
@@ -100,85 +131,142 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
                     const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                     int mode, const float* __restrict__ bias, const float* __restrict__ pre_prev,
                     float* __restrict__ out0, float* __restrict__ out1, T* __restrict__ dk, T* __restrict__ dv, int D) {
-  __shared__ float a_s[KC][LS];
-  __shared__ float b_s[KC][LS];
+  __shared__ __align__(16) float a_s[A_ROWS][RSA];     // [staged input row][channel of the slice]
+  __shared__ __align__(16) float b_s[GT * KCC][RSB];   // [tap of the group][channel of the slice][output]
   const int h = blockIdx.z;
-  const int64_t t0 = (int64_t)blockIdx.x * TM;
+  const int64_t t0 = (int64_t)blockIdx.x * TMC;
   const int n0 = blockIdx.y * TN;
   const int tid = threadIdx.x;
-  const int lrow = tid / 4, lq = tid % 4;          // loader role: row lrow, PER consecutive contraction indices
-  const int64_t lt = t0 + lrow;
-  const bool lt_ok = lt < total;
-  const int64_t lo = lt_ok ? seq_lo[lt] : 0, hi = lt_ok ? seq_hi[lt] : 0;
   const float* in_h = in + (int64_t)h * total * K;
   const float* wt_h = wt + (int64_t)h * ks * K * N;
+  const bool vec_a = K % 4 == 0, vec_b = N % 4 == 0;
   const int half = (ks - 1) / 2;
   const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
-  f32x16 acc;
+  // the wave's two token rows per lane, and the bounds of their sequences
+  int64_t tok[2];
+  int lo[2], hi[2];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  // Stages = (tap, contraction slice) pairs; the next stage's operands are fetched into registers while the current
-  // one is multiplied, so the global latency passes under the matrix work.
-  const int slices = (K + KC - 1) / KC, stages = ks * slices;
-  float ra[PER], rb[PER];
+  for (int u = 0; u < 2; ++u) {
+    tok[u] = t0 + 64 * mi + 32 * u + ql;
+    const bool ok = tok[u] < total;
+    lo[u] = ok ? seq_lo[tok[u]] : 0;
+    hi[u] = ok ? seq_hi[tok[u]] : 0;
+  }
+  f32x16 acc[2];         // two token sub-tiles of 32 per wave: every weight operand read serves two MFMAs
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+  const int per_group = min(GT, 1 + HALO / dil);       // taps whose rows fit the staged halo
+  const int groups = (ks + per_group - 1) / per_group;
+  const int slices = (K + KCC - 1) / KCC, stages = groups * slices;
+  // of a stage: first tap, number of taps, and the offset of the first staged row from the tile's first token
+  auto stage_taps = [&](int stage, int& tap0, int& ntap, int& k0, int& base_off) {
+    const int g = stage / slices;
+    k0 = (stage - g * slices) * KCC;
+    tap0 = g * per_group;
+    ntap = min(per_group, ks - tap0);
+    base_off = sign > 0 ? (tap0 - half) * dil : -(tap0 + ntap - 1 - half) * dil;
+  };
+  // The next stage's operands are fetched into registers while the current one is multiplied.
+  float4 ra[PA], rb[PB];
   auto fetch = [&](int stage) {
-    const int tap = stage / slices, k0 = (stage - tap * slices) * KC;
-    const int64_t p = lt + (int64_t)sign * (tap - half) * dil;
-    const bool p_ok = lt_ok && p >= lo && p < hi;
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
+    const int rows = TMC + (ntap - 1) * dil;
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int kk = lq * PER + j;
-      ra[j] = (p_ok && k0 + kk < K) ? in_h[p * K + k0 + kk] : 0.f;
+    for (int i = 0; i < PA; ++i) {
+      const int e = tid + 256 * i, row = e / (KCC / 4), q = e % (KCC / 4);
+      const int64_t p = t0 + row + base_off;
+      const bool ok = row < rows && p >= 0 && p < total;
+      ra[i] = load_quad(in_h + (ok ? p : 0) * K, k0 + 4 * q, K, ok, vec_a);
     }
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int e = tid + 256 * j;                   // 0 .. KC*TN-1: (kk, n) with n fastest
-      const int kk = e / TN, n = e % TN;
-      rb[j] = (k0 + kk < K && n0 + n < N) ? wt_h[((int64_t)tap * K + k0 + kk) * N + n0 + n] : 0.f;
+    for (int i = 0; i < PB; ++i) {
+      const int e = tid + 256 * i, jrow = e / (TN / 4), q = e % (TN / 4);
+      const int j = jrow / KCC, kk = jrow % KCC;
+      const bool ok = j < ntap && k0 + kk < K;
+      rb[i] = load_quad(wt_h + (ok ? ((int64_t)(tap0 + j) * K + k0 + kk) * N : 0), n0 + 4 * q, N, ok, vec_b);
     }
   };
   fetch(0);
   for (int stage = 0; stage < stages; ++stage) {
     __syncthreads();     // the previous stage's tiles are no longer read
 #pragma unroll
-    for (int j = 0; j < PER; ++j) a_s[lq * PER + j][lrow] = ra[j];
+    for (int i = 0; i < PA; ++i) {
+      const int e = tid + 256 * i;
+      *reinterpret_cast<float4*>(&a_s[e / (KCC / 4)][4 * (e % (KCC / 4))]) = ra[i];
+    }
 #pragma unroll
-    for (int j = 0; j < PER; ++j) b_s[(tid + 256 * j) / TN][(tid + 256 * j) % TN] = rb[j];
+    for (int i = 0; i < PB; ++i) {
+      const int e = tid + 256 * i;
+      *reinterpret_cast<float4*>(&b_s[e / (TN / 4)][4 * (e % (TN / 4))]) = rb[i];
+    }
     __syncthreads();
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
     if (stage + 1 < stages) fetch(stage + 1);
+    const int kgroups = (min(KCC, K - k0) + 7) / 8;
+    for (int j = 0; j < ntap; ++j) {
+      const int off = sign * (tap0 + j - half) * dil;
+      const int shift = off - base_off;                 // 0 .. (ntap-1)*dil
+      bool valid[2];
 #pragma unroll
-    for (int kk = 0; kk < KC; kk += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s[kk + hb][32 * mi + ql], b_s[kk + hb][32 * ni + ql], acc, 0, 0, 0);
+      for (int u = 0; u < 2; ++u) valid[u] = tok[u] + off >= lo[u] && tok[u] + off < hi[u];
+      // Lane half hb takes channels 8g + 4hb .. 8g + 4hb + 3 of each group of eight, one per MFMA, from both operands.
+      for (int g = 0; g < kgroups; ++g) {
+        float4 a[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          a[u] = *reinterpret_cast<const float4*>(&a_s[64 * mi + 32 * u + ql + shift][8 * g + 4 * hb]);
+          if (!valid[u]) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        const float* bp = &b_s[j * KCC + 8 * g + 4 * hb][32 * ni + ql];
+        const float b0 = bp[0], b1 = bp[RSB], b2 = bp[2 * RSB], b3 = bp[3 * RSB];
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].x, b0, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].x, b0, acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].y, b1, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].y, b1, acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].z, b2, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].z, b2, acc[1], 0, 0, 0);
+        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].w, b3, acc[0], 0, 0, 0);
+        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].w, b3, acc[1], 0, 0, 0);
+      }
+    }
   }
-  // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the quarter, output column ql
+  // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the sub-tile, output column ql
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int64_t t = t0 + 32 * mi + 8 * (r / 4) + 4 * hb + (r % 4);
+  for (int ur = 0; ur < 32; ++ur) {
+    const int u = ur / 16, r = ur % 16;
+    const int64_t t = t0 + 64 * mi + 32 * u + 8 * (r / 4) + 4 * hb + (r % 4);
     const int n = n0 + 32 * ni + ql;
     if (t >= total || n >= N) continue;
     const int64_t o = ((int64_t)h * total + t) * N + n;
     if (mode == 0) {
-      const float y = acc[r] + bias[(int64_t)h * N + n];
+      const float y = acc[u][r] + bias[(int64_t)h * N + n];
       out0[o] = y;
       out1[o] = silu_f32(y);
     } else if (mode == 1) {
-      out0[o] = acc[r] * silu_grad_f32(pre_prev[o]);
+      out0[o] = acc[u][r] * silu_grad_f32(pre_prev[o]);
     } else if (n < D) {
-      if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[r]);
+      if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[u][r]);
     } else {
-      if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[r]);
+      if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[u][r]);
     }
   }
 }
 
 // Stage 1 of d W_l: partial[chunk][h][c][m][tap] = sum over the chunk's tokens t of a_{l-1}[t + off][m] * d y_l[t][c],
-// a tiled fp32 product with the tokens as the contraction index (slices of KC tokens through LDS).
+// a tiled fp32 product with the tokens as the contraction index (slices of KCW tokens through LDS).  The chunk's
+// sequence bounds are staged in LDS first, so a slice's operands need one round of global loads, not two dependent
+// ones; the output channels are the rows of the matrix tiles, so neighbouring lanes write neighbouring m.
 __global__ void __launch_bounds__(256)
 weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
                       const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                       int tiles_n, float* __restrict__ partial) {
-  __shared__ float a_s[KC][LS];
-  __shared__ float b_s[KC][LS];
+  __shared__ float a_s[KCW][LS];       // activations: [token of the slice][m]
+  __shared__ float b_s[KCW][LS];       // d y:         [token of the slice][c]
+  __shared__ int32_t lo_s[kTokChunk], hi_s[kTokChunk];
   const int m0 = (blockIdx.x / tiles_n) * TM, c0 = (blockIdx.x % tiles_n) * TN;
   const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
   const int chunk = blockIdx.z;
@@ -188,45 +276,52 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
   const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
   const float* a_h = act_in + (int64_t)h * total * Cin;
   const float* g_h = dpre + (int64_t)h * total * Cout;
-  const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
+  const int lane = tid & 63, wv = tid >> 6, ci = wv >> 1, mi = wv & 1, ql = lane & 31, hb = lane >> 5;
+  for (int i = tid; i < kTokChunk; i += 256) {
+    const bool ok = tb + i < te;
+    lo_s[i] = ok ? seq_lo[tb + i] : 0;
+    hi_s[i] = ok ? seq_hi[tb + i] : 0;   // an empty range: rows past the chunk's end contribute nothing
+  }
+  __syncthreads();
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-  float ra[PER], rb[PER];
+  float ra[PERW], rb[PERW];
   auto fetch = [&](int64_t t0) {
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
+    for (int j = 0; j < PERW; ++j) {
       const int e = tid + 256 * j;                   // (token of the slice, channel) with the channel fastest
       const int tt = e / TM, x = e % TM;
       const int64_t t = t0 + tt;
+      const int i = (int)(t - tb);
       const bool t_ok = t < te;
       const int64_t p = t + off;
-      const bool p_ok = t_ok && p >= seq_lo[t_ok ? t : tb] && p < seq_hi[t_ok ? t : tb];
+      const bool p_ok = t_ok && p >= lo_s[t_ok ? i : 0] && p < hi_s[t_ok ? i : 0];
       ra[j] = (p_ok && m0 + x < Cin) ? a_h[p * Cin + m0 + x] : 0.f;
       rb[j] = (t_ok && c0 + x < Cout) ? g_h[t * Cout + c0 + x] : 0.f;
     }
   };
   fetch(tb);
-  for (int64_t t0 = tb; t0 < te; t0 += KC) {
+  for (int64_t t0 = tb; t0 < te; t0 += KCW) {
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {
+    for (int j = 0; j < PERW; ++j) {
       const int e = tid + 256 * j;
       a_s[e / TM][e % TM] = ra[j];
       b_s[e / TM][e % TM] = rb[j];
     }
     __syncthreads();
-    if (t0 + KC < te) fetch(t0 + KC);   // the next slice's operands travel while this one is multiplied
+    if (t0 + KCW < te) fetch(t0 + KCW);   // the next slice's operands travel while this one is multiplied
 #pragma unroll
-    for (int tt = 0; tt < KC; tt += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_s[tt + hb][32 * mi + ql], b_s[tt + hb][32 * ni + ql], acc, 0, 0, 0);
+    for (int tt = 0; tt < KCW; tt += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b_s[tt + hb][32 * ci + ql], a_s[tt + hb][32 * mi + ql], acc, 0, 0, 0);
   }
   const int64_t per_head = (int64_t)Cout * Cin * ks;
   float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    const int m = m0 + 32 * mi + 8 * (r / 4) + 4 * hb + (r % 4);
-    const int c = c0 + 32 * ni + ql;
+    const int c = c0 + 32 * ci + 8 * (r / 4) + 4 * hb + (r % 4);
+    const int m = m0 + 32 * mi + ql;
     if (m < Cin && c < Cout) out[((int64_t)c * Cin + m) * ks + tap] = acc[r];     // the layout of the weights: [c][m][tap]
   }
 }
@@ -237,13 +332,14 @@ chunk_sum_kernel(const float* __restrict__ partial, int64_t n, int chunks, float
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
   float acc = 0.f;
+#pragma unroll 8
   for (int ch = 0; ch < chunks; ++ch) acc += partial[(int64_t)ch * n + i];
   out[i] = acc;
 }
 
 // Column sums over the tokens: out[h][c] = sum_t x[h][t][c] (mode 0), sum_t dz[h][t] * x[h][t][c] (mode 1),
 // or, with C = 1, sum_t dz[h][t] (mode 2).  One workgroup per (h, tile of c_tile channels, c_tile a power of two
-// <= 64) and chunk of kTokChunk tokens: 256 / c_tile token lanes each sum a strided share in order (neighbouring
+// <= 64) and chunk of kColChunk tokens: 256 / c_tile token lanes each sum a strided share in order (neighbouring
 // threads read neighbouring channels of one token), then the lanes of a channel are added in lane order; the chunks
 // are added by chunk_sum_kernel.
 __global__ void __launch_bounds__(256)
@@ -255,8 +351,9 @@ column_sum_kernel(const float* __restrict__ x, const float* __restrict__ dz, int
   const int c = blockIdx.x * c_tile + (int)threadIdx.x % c_tile, tl = (int)threadIdx.x / c_tile;
   float acc = 0.f;
   if (c < C) {
-    const int64_t tb = (int64_t)blockIdx.z * kTokChunk;
-    const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
+    const int64_t tb = (int64_t)blockIdx.z * kColChunk;
+    const int64_t te = tb + kColChunk < total ? tb + kColChunk : total;
+#pragma unroll 8
     for (int64_t t = tb + tl; t < te; t += lanes) {
       const float g = dz != nullptr ? dz[(int64_t)h * total + t] : 1.0f;
       if (mode == 2) acc += g;
@@ -283,7 +380,7 @@ struct Layout {
   float* pre[LTEA_MAX_CNN_LAYERS];            // [Hkv][T][C_l]
   float* act[LTEA_MAX_CNN_LAYERS];
   float* dpre[2];                             // [Hkv][T][widest layer], ping-pong
-  float *wf, *wb;                             // weight panels of the layer at hand (largest layer's size)
+  float *wf[LTEA_MAX_CNN_LAYERS], *wb[LTEA_MAX_CNN_LAYERS];   // fp32 weight panels of every layer
   float* partial;                             // [chunks][Hkv][largest layer's weights]
   size_t bytes;
 };
@@ -309,10 +406,18 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
     cin = cnn.c_out[l];
   }
   for (int i = 0; i < 2; ++i) L.dpre[i] = reinterpret_cast<float*>(take(sizeof(float) * rows * cmax));
-  L.wf = reinterpret_cast<float*>(take(sizeof(float) * cfg.Hkv * wmax));
-  L.wb = reinterpret_cast<float*>(take(sizeof(float) * cfg.Hkv * wmax));
+  cin = 2 * cfg.D;
+  for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) L.wf[l] = L.wb[l] = nullptr;
+  for (int l = 0; l < cnn.n_layers; ++l) {
+    const size_t w = (size_t)cfg.Hkv * cnn.c_out[l] * cin * cnn.kernel[l];
+    L.wf[l] = reinterpret_cast<float*>(take(sizeof(float) * w));
+    L.wb[l] = reinterpret_cast<float*>(take(sizeof(float) * w));
+    cin = cnn.c_out[l];
+  }
   const size_t chunks = (size_t)((total + kTokChunk - 1) / kTokChunk);
-  L.partial = reinterpret_cast<float*>(take(sizeof(float) * chunks * cfg.Hkv * wmax));
+  const size_t col_chunks = (size_t)((total + kColChunk - 1) / kColChunk);
+  const size_t part_w = chunks * cfg.Hkv * wmax, part_c = col_chunks * cfg.Hkv * (size_t)cmax;
+  L.partial = reinterpret_cast<float*>(take(sizeof(float) * (part_w > part_c ? part_w : part_c)));
   L.bytes = (size_t)(p - static_cast<char*>(base));
   return L;
 }
@@ -325,20 +430,20 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   const int Hkv = cfg.Hkv, nl = cnn.n_layers, D = cfg.D;
   const Layout L = carve(cfg, cnn, total, workspace);
   hipError_t e;
-  const unsigned tok_tiles = (unsigned)((total + TM - 1) / TM);
+  const unsigned tok_tiles = (unsigned)((total + TMC - 1) / TMC);
   auto blocks = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
   auto cin_of = [&](int l) { return l == 0 ? 2 * D : cnn.c_out[l - 1]; };
   auto in_of = [&](int l) -> const float* { return l == 0 ? L.a0 : L.act[l - 1]; };
   auto panels = [&](int l) {
     const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
     hipLaunchKernelGGL(weight_panels_kernel<T>, blocks(n), dim3(256), 0, stream, static_cast<const T*>(cnn.w[l]), cin_of(l),
-                       cnn.c_out[l], cnn.kernel[l], n, L.wf, L.wb);
+                       cnn.c_out[l], cnn.kernel[l], n, L.wf[l], L.wb[l]);
     return hipGetLastError();
   };
   hipLaunchKernelGGL(token_bounds_kernel, blocks(total), dim3(256), 0, stream, sv.cu_seqlens, sv.n_seqs, total, L.seq_lo,
                      L.seq_hi);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(features_kernel<T>, dim3((unsigned)((total * 2 * D + 255) / 256), (unsigned)Hkv), dim3(256), 0, stream,
+  hipLaunchKernelGGL(features_kernel<T>, dim3((unsigned)((total * (2 * D / Elems<T>::N) + 255) / 256), (unsigned)Hkv), dim3(256), 0, stream,
                      static_cast<const T*>(k), static_cast<const T*>(v), stride_tok, stride_head, D, total, L.a0);
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // 1. forward, pre-activations and activations kept
@@ -346,7 +451,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     if ((e = panels(l)) != hipSuccess) return e;
     const int N = cnn.c_out[l];
     hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
-                       stream, in_of(l), L.wf, cin_of(l), N, cnn.kernel[l], cnn.dilation[l], 1, L.seq_lo, L.seq_hi, total,
+                       stream, in_of(l), L.wf[l], cin_of(l), N, cnn.kernel[l], cnn.dilation[l], 1, L.seq_lo, L.seq_hi, total,
                        Hkv, 0, cnn.bias[l], static_cast<const float*>(nullptr), L.pre[l], L.act[l], static_cast<T*>(nullptr),
                        static_cast<T*>(nullptr), D);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -358,13 +463,15 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   if ((e = hipGetLastError()) != hipSuccess) return e;
   auto c_tile_of = [](int C) { int t = 1; while (t < C && t < 64) t *= 2; return t; };
   const int chunks = (int)((total + kTokChunk - 1) / kTokChunk);
+  const int col_chunks = (int)((total + kColChunk - 1) / kColChunk);
   auto column_sum = [&](const float* x, const float* dzp, int C, int mode, float* out) {
     const int ct = c_tile_of(C);
-    hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)((C + ct - 1) / ct), (unsigned)Hkv, (unsigned)chunks), dim3(256), 0,
-                       stream, x, dzp, C, ct, total, mode, Hkv, L.partial);
+    hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)((C + ct - 1) / ct), (unsigned)Hkv, (unsigned)col_chunks), dim3(256),
+                       0, stream, x, dzp, C, ct, total, mode, Hkv, L.partial);
     hipError_t ee = hipGetLastError();
     if (ee != hipSuccess) return ee;
-    hipLaunchKernelGGL(chunk_sum_kernel, blocks((int64_t)Hkv * C), dim3(256), 0, stream, L.partial, (int64_t)Hkv * C, chunks, out);
+    hipLaunchKernelGGL(chunk_sum_kernel, blocks((int64_t)Hkv * C), dim3(256), 0, stream, L.partial, (int64_t)Hkv * C, col_chunks,
+                       out);
     return hipGetLastError();
   };
   if ((e = column_sum(L.act[nl - 1], dz, CL, 1, g.w_out)) != hipSuccess) return e;
@@ -384,10 +491,9 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     hipLaunchKernelGGL(chunk_sum_kernel, blocks(n_w), dim3(256), 0, stream, L.partial, n_w, chunks, g.w[l]);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (l > 0 || dk != nullptr || dv != nullptr) {
-      if ((e = panels(l)) != hipSuccess) return e;
       // towards the input: contraction over this layer's output channels, taps mirrored
       hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
-                         stream, dpre, L.wb, Cout, Cin, ks, cnn.dilation[l], -1, L.seq_lo, L.seq_hi, total, Hkv,
+                         stream, dpre, L.wb[l], Cout, Cin, ks, cnn.dilation[l], -1, L.seq_lo, L.seq_hi, total, Hkv,
                          l > 0 ? 1 : 2, static_cast<const float*>(nullptr),
                          l > 0 ? L.pre[l - 1] : static_cast<const float*>(nullptr), L.dpre[cur ^ 1],
                          static_cast<float*>(nullptr), static_cast<T*>(dk), static_cast<T*>(dv), D);

@@ -236,6 +236,7 @@ def test_cnn_backward_argument_errors():
     assert call(dk=0x1004) == B.LTEA_EINVAL
     assert call(ws=None) == B.LTEA_EWORKSPACE
     assert call(wsb=need - 1) == B.LTEA_EWORKSPACE
+    assert call(ws=0x1010) == B.LTEA_EINVAL          # workspaces are 256-byte aligned
     bad = B.ltea_cnn_grad()
     assert call(g=C.byref(bad)) == B.LTEA_EINVAL
 
