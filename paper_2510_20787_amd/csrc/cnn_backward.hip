@@ -1,7 +1,7 @@
 // Backward of the scoring CNN of the LTE module (paper Section 3.1.1; trained through the gradient of the logits
 // that Section 3.1.2 defines): from d(loss)/d(logit) to the gradients of every conv weight, bias, the output
 // projection and the input features.  fp32 arithmetic for any depth and either storage type, as LDS-tiled products
-// on the fp32 matrix instruction (64 x 64 results per workgroup): the module is small next to the attention (paper
+// on the fp32 matrix instruction: the module is small next to the attention (paper
 // stack: 65 kflop per token-head forward).  Everything is summed in a fixed order: same bits every run.
 //
 //   1. forward again, keeping the pre-activations y_l and the activations a_l = silu(y_l) of every layer
@@ -11,7 +11,8 @@
 //                       d W_l[c][m][tap] = sum_t d y_l[t][c] * a_{l-1}[t + off(tap)][m]      (inside the sequence)
 //                       d a_{l-1}[t][m]  = sum_{tap, c} W_l[c][m][tap] * d y_l[t - off(tap)][c]
 //                       d y_{l-1} = d a_{l-1} * silu'(y_{l-1})        (l > 1)   or   dk, dv = d a_0   (l = 1).
-// Sums over tokens are taken in two stages: per chunk of kTokChunk tokens into a partial array, then over the chunks.
+// Sums over tokens are taken in two stages: per chunk of kTokChunk (weights) or kColChunk (column sums) tokens into a
+// partial array, then over the chunks.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 #include "rope_dev.h"
@@ -90,12 +91,10 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
   wb[((h * ks + tap) * Cout + c) * Cin + m] = w;
 }
 
-// Tile of the fp32 products below: 64 x 64 results per workgroup, the contraction in slices of KC through LDS.  Each of
-// the four waves owns a 32 x 32 quarter and runs it on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per
-// instruction: lane l supplies row / column l % 32 of step l / 32).  LDS rows are 96 floats apart so that the two
-// lane halves of an operand read land in different banks.
-constexpr int TM = 64, TN = 64, KC = 16, LS = 96;
-constexpr int PER = KC * TM / 256;   // elements of each operand tile a thread moves per stage
+// The fp32 products below run on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per instruction: lane l
+// supplies row / column l % 32 of step l / 32), their operands staged through LDS.  Weight products: TM input channels
+// x TN output channels per workgroup, each of the four waves owning a 32 x 32 quarter; conv products: TN outputs wide.
+constexpr int TM = 64, TN = 64;
 // conv products: TMC tokens per workgroup (two 32-token sub-tiles per wave), contraction slices of KCC channels, up
 // to GT taps per stage whose rows reach at most HALO past the tile; LDS row strides RSA / RSB keep the 16-byte operand
 // reads of 16 neighbouring lanes, and the two lane halves' weight reads, on different banks
@@ -104,17 +103,36 @@ constexpr int A_ROWS = TMC + HALO, PA = A_ROWS * (KCC / 4) / 256, PB = GT * KCC 
 static_assert(A_ROWS * (KCC / 4) % 256 == 0 && GT * KCC * (TN / 4) % 256 == 0, "whole quads per thread");
 constexpr int KCW = 32, PERW = KCW * TM / 256;   // weight products: tokens per contraction slice
 
-// row[x .. x+3] of a row of `limit` floats; elements at or past the limit, or the whole quad when !ok, read as zero.
-// vec: limit % 4 == 0 and the row starts on a 16-byte boundary, so a quad is inside or outside as a whole.
-__device__ __forceinline__ float4 load_quad(const float* __restrict__ row, int x, int limit, bool ok, bool vec) {
-  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (!ok || x >= limit) return v;
-  if (vec) return *reinterpret_cast<const float4*>(row + x);
-  v.x = row[x];
-  if (x + 1 < limit) v.y = row[x + 1];
-  if (x + 2 < limit) v.z = row[x + 2];
-  if (x + 3 < limit) v.w = row[x + 3];
-  return v;
+// row[x .. x+3] of a readable row of `limit` floats, loaded unconditionally from addresses clamped into the row, with
+// a 4-bit mask of the elements that count (those below the limit, none when !ok).  The caller zeroes the others where
+// it consumes the quad, so that a thread's loads of a stage are all in flight together and none is waited for before
+// then.  VEC: limit % 4 == 0 and the row starts on a 16-byte boundary, so a quad is inside or outside as a whole.
+template <bool VEC>
+__device__ __forceinline__ float4 load_quad(const float* __restrict__ row, int x, int limit, bool ok, unsigned& mask4) {
+  if constexpr (VEC) {
+    mask4 = (ok && x < limit) ? 0xFu : 0u;
+    return *reinterpret_cast<const float4*>(row + min(x, limit - 4));
+  } else {
+    const int last = limit - 1;
+    mask4 = 0u;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) mask4 |= (ok && x + c < limit) ? 1u << c : 0u;
+    return make_float4(row[min(x, last)], row[min(x + 1, last)], row[min(x + 2, last)], row[min(x + 3, last)]);
+  }
+}
+
+// v if keep, else zero.  The empty asm makes the loaded value needed either way, so the load stays where it was issued
+// instead of moving under a condition (and being waited for at once).
+__device__ __forceinline__ float masked_value(float v, bool keep) {
+  asm volatile("" : "+v"(v));
+  return keep ? v : 0.f;
+}
+
+// The quad with the elements outside the mask zeroed.  The empty asm makes the loaded value needed whatever the mask
+// says, so the load stays where it was issued instead of moving under a condition.
+__device__ __forceinline__ float4 masked_quad(float4 v, unsigned mask4) {
+  asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+  return make_float4(mask4 & 1u ? v.x : 0.f, mask4 & 2u ? v.y : 0.f, mask4 & 4u ? v.z : 0.f, mask4 & 8u ? v.w : 0.f);
 }
 
 // out[t][n] = sum_tap sum_k in[t + sign * off(tap)][k] * wt[tap][k][n]   (rows outside t's sequence count as zero)
@@ -125,8 +143,8 @@ __device__ __forceinline__ float4 load_quad(const float* __restrict__ row, int x
 //   mode 0 (forward)          pre = out + bias, act = silu(pre)
 //   mode 1 (hidden backward)  dpre_out = out * silu'(pre_prev)
 //   mode 2 (input backward)   dk / dv [T][Hkv][D] of the storage type (n < D: key part)
-template <typename T>
-__global__ void __launch_bounds__(256)
+template <typename T, bool VEC>
+__global__ void __launch_bounds__(256, 4)
 conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, int K, int N, int ks, int dil, int sign,
                     const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                     int mode, const float* __restrict__ bias, const float* __restrict__ pre_prev,
@@ -139,7 +157,6 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
   const int tid = threadIdx.x;
   const float* in_h = in + (int64_t)h * total * K;
   const float* wt_h = wt + (int64_t)h * ks * K * N;
-  const bool vec_a = K % 4 == 0, vec_b = N % 4 == 0;
   const int half = (ks - 1) / 2;
   const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
   // the wave's two token rows per lane, and the bounds of their sequences
@@ -170,23 +187,29 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
   };
   // The next stage's operands are fetched into registers while the current one is multiplied.
   float4 ra[PA], rb[PB];
+  unsigned mask_a, mask_b;       // four bits per quad: which of its elements count
   auto fetch = [&](int stage) {
     int tap0, ntap, k0, base_off;
     stage_taps(stage, tap0, ntap, k0, base_off);
     const int rows = TMC + (ntap - 1) * dil;
+    mask_a = mask_b = 0u;
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const int e = tid + 256 * i, row = e / (KCC / 4), q = e % (KCC / 4);
       const int64_t p = t0 + row + base_off;
       const bool ok = row < rows && p >= 0 && p < total;
-      ra[i] = load_quad(in_h + (ok ? p : 0) * K, k0 + 4 * q, K, ok, vec_a);
+      unsigned m4;
+      ra[i] = load_quad<VEC>(in_h + (ok ? p : 0) * K, k0 + 4 * q, K, ok, m4);
+      mask_a |= m4 << (4 * i);
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       const int e = tid + 256 * i, jrow = e / (TN / 4), q = e % (TN / 4);
       const int j = jrow / KCC, kk = jrow % KCC;
       const bool ok = j < ntap && k0 + kk < K;
-      rb[i] = load_quad(wt_h + (ok ? ((int64_t)(tap0 + j) * K + k0 + kk) * N : 0), n0 + 4 * q, N, ok, vec_b);
+      unsigned m4;
+      rb[i] = load_quad<VEC>(wt_h + (ok ? ((int64_t)(tap0 + j) * K + k0 + kk) * N : 0), n0 + 4 * q, N, ok, m4);
+      mask_b |= m4 << (4 * i);
     }
   };
   fetch(0);
@@ -195,12 +218,12 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
 #pragma unroll
     for (int i = 0; i < PA; ++i) {
       const int e = tid + 256 * i;
-      *reinterpret_cast<float4*>(&a_s[e / (KCC / 4)][4 * (e % (KCC / 4))]) = ra[i];
+      *reinterpret_cast<float4*>(&a_s[e / (KCC / 4)][4 * (e % (KCC / 4))]) = masked_quad(ra[i], mask_a >> (4 * i));
     }
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       const int e = tid + 256 * i;
-      *reinterpret_cast<float4*>(&b_s[e / (TN / 4)][4 * (e % (TN / 4))]) = rb[i];
+      *reinterpret_cast<float4*>(&b_s[e / (TN / 4)][4 * (e % (TN / 4))]) = masked_quad(rb[i], mask_b >> (4 * i));
     }
     __syncthreads();
     int tap0, ntap, k0, base_off;
@@ -217,12 +240,12 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
       for (int g = 0; g < kgroups; ++g) {
         float4 a[2];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < 2; ++u)
           a[u] = *reinterpret_cast<const float4*>(&a_s[64 * mi + 32 * u + ql + shift][8 * g + 4 * hb]);
-          if (!valid[u]) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
         const float* bp = &b_s[j * KCC + 8 * g + 4 * hb][32 * ni + ql];
         const float b0 = bp[0], b1 = bp[RSB], b2 = bp[2 * RSB], b3 = bp[3 * RSB];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) a[u] = masked_quad(a[u], valid[u] ? 0xFu : 0u);
         acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].x, b0, acc[0], 0, 0, 0);
         acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].x, b0, acc[1], 0, 0, 0);
         acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].y, b1, acc[0], 0, 0, 0);
@@ -235,23 +258,46 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
     }
   }
   // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the sub-tile, output column ql
+  const int n = n0 + 32 * ni + ql;
+  const bool n_ok = n < N;
+  auto token_of = [&](int ur) { return t0 + 64 * mi + 32 * (ur / 16) + 8 * ((ur % 16) / 4) + 4 * hb + (ur % 4); };
+  if (mode == 0) {
+    const float bv = n_ok ? bias[(int64_t)h * N + n] : 0.f;
 #pragma unroll
-  for (int ur = 0; ur < 32; ++ur) {
-    const int u = ur / 16, r = ur % 16;
-    const int64_t t = t0 + 64 * mi + 32 * u + 8 * (r / 4) + 4 * hb + (r % 4);
-    const int n = n0 + 32 * ni + ql;
-    if (t >= total || n >= N) continue;
-    const int64_t o = ((int64_t)h * total + t) * N + n;
-    if (mode == 0) {
-      const float y = acc[u][r] + bias[(int64_t)h * N + n];
+    for (int ur = 0; ur < 32; ++ur) {
+      const int64_t t = token_of(ur);
+      if (t >= total || !n_ok) continue;
+      const int64_t o = ((int64_t)h * total + t) * N + n;
+      const float y = acc[ur / 16][ur % 16] + bv;
       out0[o] = y;
       out1[o] = silu_f32(y);
-    } else if (mode == 1) {
-      out0[o] = acc[u][r] * silu_grad_f32(pre_prev[o]);
-    } else if (n < D) {
-      if (dk != nullptr) dk[(t * Hkv + h) * D + n] = from_f32<T>(acc[u][r]);
-    } else {
-      if (dv != nullptr) dv[(t * Hkv + h) * D + (n - D)] = from_f32<T>(acc[u][r]);
+    }
+  } else if (mode == 1) {
+    // per sub-tile, all of the lane's pre-activations are requested before the first is used
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      float pp[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t t = token_of(16 * u + r);
+        pp[r] = pre_prev[(t < total && n_ok) ? ((int64_t)h * total + t) * N + n : 0];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t t = token_of(16 * u + r);
+        if (t >= total || !n_ok) continue;
+        out0[((int64_t)h * total + t) * N + n] = acc[u][r] * silu_grad_f32(pp[r]);
+      }
+    }
+  } else {
+    T* dst = n < D ? dk : dv;
+    const int col = n < D ? n : n - D;
+    if (dst != nullptr && n_ok) {
+#pragma unroll
+      for (int ur = 0; ur < 32; ++ur) {
+        const int64_t t = token_of(ur);
+        if (t < total) dst[(t * Hkv + h) * D + col] = from_f32<T>(acc[ur / 16][ur % 16]);
+      }
     }
   }
 }
@@ -264,8 +310,10 @@ __global__ void __launch_bounds__(256)
 weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
                       const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                       int tiles_n, float* __restrict__ partial) {
-  __shared__ float a_s[KCW][LS];       // activations: [token of the slice][m]
-  __shared__ float b_s[KCW][LS];       // d y:         [token of the slice][c]
+  // [token of the slice][channel ^ 32 * (token & 1)]: the two lane halves of an operand read take neighbouring tokens,
+  // and the swap of the row halves on odd tokens puts them on different banks without padding the rows
+  __shared__ float a_s[KCW][TM];       // activations, channel = m
+  __shared__ float b_s[KCW][TN];       // d y, channel = c
   __shared__ int32_t lo_s[kTokChunk], hi_s[kTokChunk];
   const int m0 = (blockIdx.x / tiles_n) * TM, c0 = (blockIdx.x % tiles_n) * TN;
   const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
@@ -286,35 +334,45 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
   f32x16 acc;
 #pragma unroll
   for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // A thread moves channel x of tokens wv, wv + 4, ... of a slice.  Token indices are kept relative to the chunk, in
+  // 32 bits (the token count fits: the bounds are int32), so that a load costs little address arithmetic.
+  const int x = tid & 63;
+  const bool m_ok = m0 + x < Cin, c_ok = c0 + x < Cout;
+  const float* a_col = a_h + tb * Cin + min(m0 + x, Cin - 1);
+  const float* g_col = g_h + tb * Cout + min(c0 + x, Cout - 1);
+  const int len = (int)(te - tb), tb32 = (int)tb;
   float ra[PERW], rb[PERW];
-  auto fetch = [&](int64_t t0) {
+  unsigned keep_a, keep_b;     // one bit per loaded value: does it count
+  auto fetch = [&](int i0) {
+    keep_a = keep_b = 0u;
 #pragma unroll
     for (int j = 0; j < PERW; ++j) {
-      const int e = tid + 256 * j;                   // (token of the slice, channel) with the channel fastest
-      const int tt = e / TM, x = e % TM;
-      const int64_t t = t0 + tt;
-      const int i = (int)(t - tb);
-      const bool t_ok = t < te;
-      const int64_t p = t + off;
-      const bool p_ok = t_ok && p >= lo_s[t_ok ? i : 0] && p < hi_s[t_ok ? i : 0];
-      ra[j] = (p_ok && m0 + x < Cin) ? a_h[p * Cin + m0 + x] : 0.f;
-      rb[j] = (t_ok && c0 + x < Cout) ? g_h[t * Cout + c0 + x] : 0.f;
+      const int i = i0 + wv + 4 * j;                 // token of the chunk
+      const bool t_ok = i < len;
+      const int ic = t_ok ? i : 0;
+      const int p = tb32 + ic + off;
+      const bool p_ok = t_ok & (p >= lo_s[ic]) & (p < hi_s[ic]);
+      // unconditional loads from rows inside the arrays; what does not count is zeroed where the value is consumed
+      ra[j] = a_col[(int64_t)(p_ok ? ic + off : 0) * Cin];
+      rb[j] = g_col[(int64_t)ic * Cout];
+      keep_a |= (p_ok && m_ok) ? 1u << j : 0u;
+      keep_b |= (t_ok && c_ok) ? 1u << j : 0u;
     }
   };
-  fetch(tb);
-  for (int64_t t0 = tb; t0 < te; t0 += KCW) {
+  fetch(0);
+  for (int i0 = 0; i0 < len; i0 += KCW) {
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < PERW; ++j) {
-      const int e = tid + 256 * j;
-      a_s[e / TM][e % TM] = ra[j];
-      b_s[e / TM][e % TM] = rb[j];
+      a_s[wv + 4 * j][x ^ ((wv & 1) << 5)] = masked_value(ra[j], keep_a >> j & 1u);      // token parity = wv & 1
+      b_s[wv + 4 * j][x ^ ((wv & 1) << 5)] = masked_value(rb[j], keep_b >> j & 1u);
     }
     __syncthreads();
-    if (t0 + KCW < te) fetch(t0 + KCW);   // the next slice's operands travel while this one is multiplied
+    if (i0 + KCW < len) fetch(i0 + KCW);   // the next slice's operands travel while this one is multiplied
 #pragma unroll
     for (int tt = 0; tt < KCW; tt += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b_s[tt + hb][32 * ci + ql], a_s[tt + hb][32 * mi + ql], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b_s[tt + hb][(32 * ci + ql) ^ (hb << 5)],
+                                                 a_s[tt + hb][(32 * mi + ql) ^ (hb << 5)], acc, 0, 0, 0);   // tt is even
   }
   const int64_t per_head = (int64_t)Cout * Cin * ks;
   float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
@@ -434,6 +492,10 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   auto blocks = [](int64_t n) { return dim3((unsigned)((n + 255) / 256)); };
   auto cin_of = [&](int l) { return l == 0 ? 2 * D : cnn.c_out[l - 1]; };
   auto in_of = [&](int l) -> const float* { return l == 0 ? L.a0 : L.act[l - 1]; };
+  // rows of both operands in whole, 16-byte aligned quads: the vector-load instance
+  auto conv_product = [](int K, int N) {
+    return K % 4 == 0 && N % 4 == 0 ? conv_product_kernel<T, true> : conv_product_kernel<T, false>;
+  };
   auto panels = [&](int l) {
     const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
     hipLaunchKernelGGL(weight_panels_kernel<T>, blocks(n), dim3(256), 0, stream, static_cast<const T*>(cnn.w[l]), cin_of(l),
@@ -450,7 +512,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   for (int l = 0; l < nl; ++l) {
     if ((e = panels(l)) != hipSuccess) return e;
     const int N = cnn.c_out[l];
-    hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
+    hipLaunchKernelGGL(conv_product(cin_of(l), N), dim3(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
                        stream, in_of(l), L.wf[l], cin_of(l), N, cnn.kernel[l], cnn.dilation[l], 1, L.seq_lo, L.seq_hi, total,
                        Hkv, 0, cnn.bias[l], static_cast<const float*>(nullptr), L.pre[l], L.act[l], static_cast<T*>(nullptr),
                        static_cast<T*>(nullptr), D);
@@ -492,7 +554,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (l > 0 || dk != nullptr || dv != nullptr) {
       // towards the input: contraction over this layer's output channels, taps mirrored
-      hipLaunchKernelGGL(conv_product_kernel<T>, dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
+      hipLaunchKernelGGL(conv_product(Cout, Cin), dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
                          stream, dpre, L.wb[l], Cout, Cin, ks, cnn.dilation[l], -1, L.seq_lo, L.seq_hi, total, Hkv,
                          l > 0 ? 1 : 2, static_cast<const float*>(nullptr),
                          l > 0 ? L.pre[l - 1] : static_cast<const float*>(nullptr), L.dpre[cur ^ 1],
