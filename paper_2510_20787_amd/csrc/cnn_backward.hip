@@ -92,8 +92,8 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
 }
 
 // The fp32 products below run on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per instruction: lane l
-// supplies row / column l % 32 of step l / 32), their operands staged through LDS.  Weight products: TM input channels
-// x TN output channels per workgroup, each of the four waves owning a 32 x 32 quarter; conv products: TN outputs wide.
+// supplies row / column l % 32 of step l / 32), their operands staged through LDS.  Weight products: up to TM input
+// channels x TN output channels per workgroup in 32 x 32 pieces per wave; conv products: TN outputs wide.
 constexpr int TM = 64, TN = 64;
 // conv products: TMC tokens per workgroup (two 32-token sub-tiles per wave), contraction slices of KCC channels, up
 // to GT taps per stage whose rows reach at most HALO past the tile; LDS row strides RSA / RSB keep the 16-byte operand
@@ -143,7 +143,7 @@ __device__ __forceinline__ float4 masked_quad(float4 v, unsigned mask4) {
 //   mode 0 (forward)          pre = out + bias, act = silu(pre)
 //   mode 1 (hidden backward)  dpre_out = out * silu'(pre_prev)
 //   mode 2 (input backward)   dk / dv [T][Hkv][D] of the storage type (n < D: key part)
-template <typename T, bool VEC>
+template <typename T, bool VEC, bool NARROW>
 __global__ void __launch_bounds__(256, 4)
 conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, int K, int N, int ks, int dil, int sign,
                     const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
@@ -158,20 +158,24 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
   const float* in_h = in + (int64_t)h * total * K;
   const float* wt_h = wt + (int64_t)h * ks * K * N;
   const int half = (ks - 1) / 2;
-  const int lane = tid & 63, wv = tid >> 6, mi = wv >> 1, ni = wv & 1, ql = lane & 31, hb = lane >> 5;
+  const int lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
+  // Wave roles.  Wide: the waves form 2 x 2, each with two 32-token sub-tiles and one 32-column half of the outputs.
+  // NARROW (N <= 32): the four waves take 32 tokens each and the one column half there is.
+  constexpr int U = NARROW ? 1 : 2;
+  const int row0 = NARROW ? 32 * wv : 64 * (wv >> 1), col0 = NARROW ? 0 : 32 * (wv & 1);
   // the wave's two token rows per lane, and the bounds of their sequences
-  int64_t tok[2];
-  int lo[2], hi[2];
+  int64_t tok[U];
+  int lo[U], hi[U];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    tok[u] = t0 + 64 * mi + 32 * u + ql;
+  for (int u = 0; u < U; ++u) {
+    tok[u] = t0 + row0 + 32 * u + ql;
     const bool ok = tok[u] < total;
     lo[u] = ok ? seq_lo[tok[u]] : 0;
     hi[u] = ok ? seq_hi[tok[u]] : 0;
   }
-  f32x16 acc[2];         // two token sub-tiles of 32 per wave: every weight operand read serves two MFMAs
+  f32x16 acc[U];         // wide: two token sub-tiles of 32 per wave, every weight operand read serves two MFMAs
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int u = 0; u < U; ++u)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
   const int per_group = min(GT, 1 + HALO / dil);       // taps whose rows fit the staged halo
@@ -233,38 +237,38 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
     for (int j = 0; j < ntap; ++j) {
       const int off = sign * (tap0 + j - half) * dil;
       const int shift = off - base_off;                 // 0 .. (ntap-1)*dil
-      bool valid[2];
+      bool valid[U];
 #pragma unroll
-      for (int u = 0; u < 2; ++u) valid[u] = tok[u] + off >= lo[u] && tok[u] + off < hi[u];
+      for (int u = 0; u < U; ++u) valid[u] = tok[u] + off >= lo[u] && tok[u] + off < hi[u];
       // Lane half hb takes channels 8g + 4hb .. 8g + 4hb + 3 of each group of eight, one per MFMA, from both operands.
       for (int g = 0; g < kgroups; ++g) {
-        float4 a[2];
+        float4 a[U];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-          a[u] = *reinterpret_cast<const float4*>(&a_s[64 * mi + 32 * u + ql + shift][8 * g + 4 * hb]);
-        const float* bp = &b_s[j * KCC + 8 * g + 4 * hb][32 * ni + ql];
+        for (int u = 0; u < U; ++u)
+          a[u] = *reinterpret_cast<const float4*>(&a_s[row0 + 32 * u + ql + shift][8 * g + 4 * hb]);
+        const float* bp = &b_s[j * KCC + 8 * g + 4 * hb][col0 + ql];
         const float b0 = bp[0], b1 = bp[RSB], b2 = bp[2 * RSB], b3 = bp[3 * RSB];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) a[u] = masked_quad(a[u], valid[u] ? 0xFu : 0u);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].x, b0, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].x, b0, acc[1], 0, 0, 0);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].y, b1, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].y, b1, acc[1], 0, 0, 0);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].z, b2, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].z, b2, acc[1], 0, 0, 0);
-        acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0].w, b3, acc[0], 0, 0, 0);
-        acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1].w, b3, acc[1], 0, 0, 0);
+        for (int u = 0; u < U; ++u) a[u] = masked_quad(a[u], valid[u] ? 0xFu : 0u);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].x, b0, acc[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].y, b1, acc[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].z, b2, acc[u], 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[u].w, b3, acc[u], 0, 0, 0);
       }
     }
   }
   // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the sub-tile, output column ql
-  const int n = n0 + 32 * ni + ql;
+  const int n = n0 + col0 + ql;
   const bool n_ok = n < N;
-  auto token_of = [&](int ur) { return t0 + 64 * mi + 32 * (ur / 16) + 8 * ((ur % 16) / 4) + 4 * hb + (ur % 4); };
+  auto token_of = [&](int ur) { return t0 + row0 + 32 * (ur / 16) + 8 * ((ur % 16) / 4) + 4 * hb + (ur % 4); };
   if (mode == 0) {
     const float bv = n_ok ? bias[(int64_t)h * N + n] : 0.f;
 #pragma unroll
-    for (int ur = 0; ur < 32; ++ur) {
+    for (int ur = 0; ur < 16 * U; ++ur) {
       const int64_t t = token_of(ur);
       if (t >= total || !n_ok) continue;
       const int64_t o = ((int64_t)h * total + t) * N + n;
@@ -275,7 +279,7 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
   } else if (mode == 1) {
     // per sub-tile, all of the lane's pre-activations are requested before the first is used
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < U; ++u) {
       float pp[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -294,7 +298,7 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
     const int col = n < D ? n : n - D;
     if (dst != nullptr && n_ok) {
 #pragma unroll
-      for (int ur = 0; ur < 32; ++ur) {
+      for (int ur = 0; ur < 16 * U; ++ur) {
         const int64_t t = token_of(ur);
         if (t < total) dst[(t * Hkv + h) * D + col] = from_f32<T>(acc[ur / 16][ur % 16]);
       }
@@ -306,16 +310,18 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
 // a tiled fp32 product with the tokens as the contraction index (slices of KCW tokens through LDS).  The chunk's
 // sequence bounds are staged in LDS first, so a slice's operands need one round of global loads, not two dependent
 // ones; the output channels are the rows of the matrix tiles, so neighbouring lanes write neighbouring m.
+template <int WC, int WM>
 __global__ void __launch_bounds__(256)
 weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
                       const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
                       int tiles_n, float* __restrict__ partial) {
-  // [token of the slice][channel ^ 32 * (token & 1)]: the two lane halves of an operand read take neighbouring tokens,
-  // and the swap of the row halves on odd tokens puts them on different banks without padding the rows
-  __shared__ float a_s[KCW][TM];       // activations, channel = m
-  __shared__ float b_s[KCW][TN];       // d y, channel = c
+  // [operand][token of the slice][channel ^ 32 * (token & 1)]: the two lane halves of an operand read take neighbouring
+  // tokens, and the swap of the row halves on odd tokens puts them on different banks without padding the rows
+  __shared__ float ab_s[2][KCW][64];
+  float (*a_s)[64] = ab_s[0];          // activations, channel = m
+  float (*b_s)[64] = ab_s[1];          // d y, channel = c
   __shared__ int32_t lo_s[kTokChunk], hi_s[kTokChunk];
-  const int m0 = (blockIdx.x / tiles_n) * TM, c0 = (blockIdx.x % tiles_n) * TN;
+  const int m0 = (blockIdx.x / tiles_n) * (32 * WM), c0 = (blockIdx.x % tiles_n) * (32 * WC);
   const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
   const int chunk = blockIdx.z;
   const int tid = threadIdx.x;
@@ -324,7 +330,11 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
   const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
   const float* a_h = act_in + (int64_t)h * total * Cin;
   const float* g_h = dpre + (int64_t)h * total * Cout;
-  const int lane = tid & 63, wv = tid >> 6, ci = wv >> 1, mi = wv & 1, ql = lane & 31, hb = lane >> 5;
+  const int lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
+  // Wave roles: WC x WM waves tile the output (32 output channels x 32 input channels each); when that takes fewer than
+  // four, the S waves of a tile take every S-th pair of tokens of a slice and their sums are added in wave order.
+  constexpr int S = 4 / (WC * WM);
+  const int wq = wv % (WC * WM), sp = wv / (WC * WM), ci = wq / WM, mi = wq % WM;
   for (int i = tid; i < kTokChunk; i += 256) {
     const bool ok = tb + i < te;
     lo_s[i] = ok ? seq_lo[tb + i] : 0;
@@ -337,7 +347,7 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
   // A thread moves channel x of tokens wv, wv + 4, ... of a slice.  Token indices are kept relative to the chunk, in
   // 32 bits (the token count fits: the bounds are int32), so that a load costs little address arithmetic.
   const int x = tid & 63;
-  const bool m_ok = m0 + x < Cin, c_ok = c0 + x < Cout;
+  const bool m_ok = x < 32 * WM && m0 + x < Cin, c_ok = x < 32 * WC && c0 + x < Cout;
   const float* a_col = a_h + tb * Cin + min(m0 + x, Cin - 1);
   const float* g_col = g_h + tb * Cout + min(c0 + x, Cout - 1);
   const int len = (int)(te - tb), tb32 = (int)tb;
@@ -370,9 +380,22 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
     __syncthreads();
     if (i0 + KCW < len) fetch(i0 + KCW);   // the next slice's operands travel while this one is multiplied
 #pragma unroll
-    for (int tt = 0; tt < KCW; tt += 2)
+    for (int tt = 2 * sp; tt < KCW; tt += 2 * S)
       acc = __builtin_amdgcn_mfma_f32_32x32x2f32(b_s[tt + hb][(32 * ci + ql) ^ (hb << 5)],
                                                  a_s[tt + hb][(32 * mi + ql) ^ (hb << 5)], acc, 0, 0, 0);   // tt is even
+  }
+  if constexpr (S > 1) {
+    float* red = &ab_s[0][0][0];       // (S - 1) * WC * WM accumulator tiles of 1024 floats fit the operand tiles
+    __syncthreads();
+    if (sp > 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((sp - 1) * WC * WM + wq) * 1024 + r * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (sp > 0) return;
+    for (int k = 1; k < S; ++k)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] += red[((k - 1) * WC * WM + wq) * 1024 + r * 64 + lane];
   }
   const int64_t per_head = (int64_t)Cout * Cin * ks;
   float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
@@ -494,7 +517,9 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   auto in_of = [&](int l) -> const float* { return l == 0 ? L.a0 : L.act[l - 1]; };
   // rows of both operands in whole, 16-byte aligned quads: the vector-load instance
   auto conv_product = [](int K, int N) {
-    return K % 4 == 0 && N % 4 == 0 ? conv_product_kernel<T, true> : conv_product_kernel<T, false>;
+    const bool vec = K % 4 == 0 && N % 4 == 0;
+    if (N <= 32) return vec ? conv_product_kernel<T, true, true> : conv_product_kernel<T, false, true>;
+    return vec ? conv_product_kernel<T, true, false> : conv_product_kernel<T, false, false>;
   };
   auto panels = [&](int l) {
     const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
@@ -544,8 +569,12 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     const int Cout = cnn.c_out[l], Cin = cin_of(l), ks = cnn.kernel[l];
     const float* dpre = L.dpre[cur];
     if ((e = column_sum(dpre, nullptr, Cout, 0, g.bias[l])) != hipSuccess) return e;
-    const int tiles_m = (Cin + TM - 1) / TM, tiles_n = (Cout + TN - 1) / TN;
-    hipLaunchKernelGGL(weight_product_kernel, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
+    // 32-wide halves of the 64 x 64 tile that a narrow layer would leave empty go to sharing the tokens instead
+    const int wc = Cout <= 32 ? 1 : 2, wm = Cin <= 32 ? 1 : 2;
+    const int tiles_m = (Cin + 32 * wm - 1) / (32 * wm), tiles_n = (Cout + 32 * wc - 1) / (32 * wc);
+    auto weight_product = wc == 2 ? (wm == 2 ? weight_product_kernel<2, 2> : weight_product_kernel<2, 1>)
+                                  : (wm == 2 ? weight_product_kernel<1, 2> : weight_product_kernel<1, 1>);
+    hipLaunchKernelGGL(weight_product, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
                        dim3(256), 0, stream, in_of(l), dpre, Cin, Cout, ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv,
                        tiles_n, L.partial);
     if ((e = hipGetLastError()) != hipSuccess) return e;
