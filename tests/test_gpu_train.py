@@ -131,12 +131,14 @@ def test_train_with_logits_supplied_by_the_caller():
 @pytest.mark.parametrize("dtype,kernel,channels,dilation,lens",
                          [("f32", (5,), (16,), None, [70, 0, 33]), ("bf16", (3, 3, 3), (64, 32, 16), (2, 2, 2), [300, 41]),
                           ("bf16", (7,), (32,), None, [1500, 900, 1]), ("f32", (3, 1), (8, 24), (2, 1), [5, 2]),
-                          ("f32", (3, 5), (10, 6), (40, 9), [200, 0, 90, 130])])
+                          ("f32", (3, 5), (10, 6), (40, 9), [200, 0, 90, 130]),
+                          ("bf16", (3, 3), (16, 48), (1, 3), [257, 64])])
 def test_cnn_backward(dtype, kernel, channels, dilation, lens):
     """Gradients of sum(dz * logits) through the scoring CNN against the oracle's chain rule: every conv weight and
     bias, the output projection, and the scored keys / values.  Shapes cover one to three layers, both storage types,
     more than one token chunk of the two-stage sums, empty and one-token sequences, channel counts that are not
-    multiples of four, and dilations beyond and within the rows a tile stages for a group of taps."""
+    multiples of four, dilations beyond and within the rows a tile stages for a group of taps, and every combination
+    of narrow (<= 32) and wide channel counts on the two sides of a layer."""
     Hq, Hkv, D = 4, 2, 64
     rho = sum(d * (k - 1) // 2 for k, d in zip(kernel, dilation or [1] * len(kernel)))
     w = wl.make_prefill("cnn_bwd", 1800 + len(kernel) + len(lens), dtype, lens, Hq, Hkv, D, max(27, 2 * rho + 3), 4, 0, 0.0,
