@@ -65,6 +65,7 @@ def score_status(cfg, cnn, k=0x1000, v=0x1000, st=128, sh=64, cu=0x1000, n_seqs=
     ("small_stride", B.LTEA_EINVAL), ("odd_stride", B.LTEA_EINVAL), ("misaligned", B.LTEA_EINVAL),
     ("null_logits", B.LTEA_EINVAL), ("no_workspace", B.LTEA_EWORKSPACE), ("neg_total", B.LTEA_EINVAL),
     ("total_gt_cap", B.LTEA_EINVAL), ("bad_dtype", B.LTEA_EINVAL), ("null_weight", B.LTEA_EINVAL),
+    ("misaligned_workspace", B.LTEA_EINVAL),
 ])
 def test_score_argument_errors(case, expect):
     cfg, cnn, kw = good_cfg(), fake_cnn(), {}
@@ -89,6 +90,7 @@ def test_score_argument_errors(case, expect):
     elif case == "total_gt_cap": kw = dict(total=64, max_len=32)
     elif case == "bad_dtype": cfg = good_cfg(); cfg.dtype = 7
     elif case == "null_weight": cnn = fake_cnn(); cnn.w[0] = None
+    elif case == "misaligned_workspace": kw = dict(ws=0x1040)         # workspaces are 256-byte aligned
     assert score_status(cfg, cnn, **kw) == expect
 
 
