@@ -418,6 +418,21 @@ chunk_sum_kernel(const float* __restrict__ partial, int64_t n, int chunks, float
   out[i] = acc;
 }
 
+// Stage 2 of every sum of a call in one launch: blockIdx.y picks the sum, out[i] = sum over its chunks in chunk order.
+constexpr int kMaxSums = 2 * LTEA_MAX_CNN_LAYERS + 2;
+struct SumSeg { const float* partial; float* out; int64_t n; int chunks; };
+struct SumSegs { SumSeg s[kMaxSums]; };
+__global__ void __launch_bounds__(256)
+chunk_sum_all_kernel(const SumSegs S) {
+  const SumSeg seg = S.s[blockIdx.y];
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= seg.n) return;
+  float acc = 0.f;
+#pragma unroll 8
+  for (int ch = 0; ch < seg.chunks; ++ch) acc += seg.partial[(int64_t)ch * seg.n + i];
+  seg.out[i] = acc;
+}
+
 // Column sums over the tokens: out[h][c] = sum_t x[h][t][c] (mode 0), sum_t dz[h][t] * x[h][t][c] (mode 1),
 // or, with C = 1, sum_t dz[h][t] (mode 2).  One workgroup per (h, tile of c_tile channels, c_tile a power of two
 // <= 64) and chunk of kColChunk tokens: 256 / c_tile token lanes each sum a strided share in order (neighbouring
@@ -462,7 +477,9 @@ struct Layout {
   float* act[LTEA_MAX_CNN_LAYERS];
   float* dpre[2];                             // [Hkv][T][widest layer], ping-pong
   float *wf[LTEA_MAX_CNN_LAYERS], *wb[LTEA_MAX_CNN_LAYERS];   // fp32 weight panels of every layer
-  float* partial;                             // [chunks][Hkv][largest layer's weights]
+  float* part_w[LTEA_MAX_CNN_LAYERS];         // [chunks][Hkv][C_l][C_{l-1}][k]: partial weight gradients
+  float* part_b[LTEA_MAX_CNN_LAYERS];         // [column chunks][Hkv][C_l]: partial bias gradients
+  float *part_wout, *part_bout;               // [column chunks][Hkv][C_L], [column chunks][Hkv]
   size_t bytes;
 };
 
@@ -475,15 +492,12 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
   L.seq_hi = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)total));
   L.a0 = reinterpret_cast<float*>(take(sizeof(float) * rows * 2 * cfg.D));
   int cmax = 0;
-  size_t wmax = 0;
   int cin = 2 * cfg.D;
   for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) L.pre[l] = L.act[l] = nullptr;
   for (int l = 0; l < cnn.n_layers; ++l) {
     L.pre[l] = reinterpret_cast<float*>(take(sizeof(float) * rows * cnn.c_out[l]));
     L.act[l] = reinterpret_cast<float*>(take(sizeof(float) * rows * cnn.c_out[l]));
     cmax = cnn.c_out[l] > cmax ? cnn.c_out[l] : cmax;
-    const size_t w = (size_t)cnn.c_out[l] * cin * cnn.kernel[l];
-    wmax = w > wmax ? w : wmax;
     cin = cnn.c_out[l];
   }
   for (int i = 0; i < 2; ++i) L.dpre[i] = reinterpret_cast<float*>(take(sizeof(float) * rows * cmax));
@@ -497,8 +511,15 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
   }
   const size_t chunks = (size_t)((total + kTokChunk - 1) / kTokChunk);
   const size_t col_chunks = (size_t)((total + kColChunk - 1) / kColChunk);
-  const size_t part_w = chunks * cfg.Hkv * wmax, part_c = col_chunks * cfg.Hkv * (size_t)cmax;
-  L.partial = reinterpret_cast<float*>(take(sizeof(float) * (part_w > part_c ? part_w : part_c)));
+  cin = 2 * cfg.D;
+  for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) L.part_w[l] = L.part_b[l] = nullptr;
+  for (int l = 0; l < cnn.n_layers; ++l) {
+    L.part_w[l] = reinterpret_cast<float*>(take(sizeof(float) * chunks * cfg.Hkv * cnn.c_out[l] * cin * cnn.kernel[l]));
+    L.part_b[l] = reinterpret_cast<float*>(take(sizeof(float) * col_chunks * cfg.Hkv * cnn.c_out[l]));
+    cin = cnn.c_out[l];
+  }
+  L.part_wout = reinterpret_cast<float*>(take(sizeof(float) * col_chunks * cfg.Hkv * cin));
+  L.part_bout = reinterpret_cast<float*>(take(sizeof(float) * col_chunks * cfg.Hkv));
   L.bytes = (size_t)(p - static_cast<char*>(base));
   return L;
 }
@@ -551,24 +572,29 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   auto c_tile_of = [](int C) { int t = 1; while (t < C && t < 64) t *= 2; return t; };
   const int chunks = (int)((total + kTokChunk - 1) / kTokChunk);
   const int col_chunks = (int)((total + kColChunk - 1) / kColChunk);
-  auto column_sum = [&](const float* x, const float* dzp, int C, int mode, float* out) {
+  // every sum's second stage runs in one launch at the end
+  SumSegs sums;
+  int n_sums = 0;
+  int64_t n_sum_max = 0;
+  auto second_stage = [&](const float* partial, float* out, int64_t n, int n_chunks) {
+    sums.s[n_sums++] = SumSeg{partial, out, n, n_chunks};
+    n_sum_max = n > n_sum_max ? n : n_sum_max;
+  };
+  auto column_sum = [&](const float* x, const float* dzp, int C, int mode, float* partial, float* out) {
     const int ct = c_tile_of(C);
     hipLaunchKernelGGL(column_sum_kernel, dim3((unsigned)((C + ct - 1) / ct), (unsigned)Hkv, (unsigned)col_chunks), dim3(256),
-                       0, stream, x, dzp, C, ct, total, mode, Hkv, L.partial);
-    hipError_t ee = hipGetLastError();
-    if (ee != hipSuccess) return ee;
-    hipLaunchKernelGGL(chunk_sum_kernel, blocks((int64_t)Hkv * C), dim3(256), 0, stream, L.partial, (int64_t)Hkv * C, col_chunks,
-                       out);
+                       0, stream, x, dzp, C, ct, total, mode, Hkv, partial);
+    second_stage(partial, out, (int64_t)Hkv * C, col_chunks);
     return hipGetLastError();
   };
-  if ((e = column_sum(L.act[nl - 1], dz, CL, 1, g.w_out)) != hipSuccess) return e;
-  if ((e = column_sum(nullptr, dz, 1, 2, g.b_out)) != hipSuccess) return e;
+  if ((e = column_sum(L.act[nl - 1], dz, CL, 1, L.part_wout, g.w_out)) != hipSuccess) return e;
+  if ((e = column_sum(nullptr, dz, 1, 2, L.part_bout, g.b_out)) != hipSuccess) return e;
   // 3. layers in reverse
   int cur = 0;
   for (int l = nl - 1; l >= 0; --l) {
     const int Cout = cnn.c_out[l], Cin = cin_of(l), ks = cnn.kernel[l];
     const float* dpre = L.dpre[cur];
-    if ((e = column_sum(dpre, nullptr, Cout, 0, g.bias[l])) != hipSuccess) return e;
+    if ((e = column_sum(dpre, nullptr, Cout, 0, L.part_b[l], g.bias[l])) != hipSuccess) return e;
     // 32-wide halves of the 64 x 64 tile that a narrow layer would leave empty go to sharing the tokens instead
     const int wc = Cout <= 32 ? 1 : 2, wm = Cin <= 32 ? 1 : 2;
     const int tiles_m = (Cin + 32 * wm - 1) / (32 * wm), tiles_n = (Cout + 32 * wc - 1) / (32 * wc);
@@ -576,11 +602,9 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
                                   : (wm == 2 ? weight_product_kernel<1, 2> : weight_product_kernel<1, 1>);
     hipLaunchKernelGGL(weight_product, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
                        dim3(256), 0, stream, in_of(l), dpre, Cin, Cout, ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv,
-                       tiles_n, L.partial);
+                       tiles_n, L.part_w[l]);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const int64_t n_w = (int64_t)Cout * Cin * ks * Hkv;
-    hipLaunchKernelGGL(chunk_sum_kernel, blocks(n_w), dim3(256), 0, stream, L.partial, n_w, chunks, g.w[l]);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    second_stage(L.part_w[l], g.w[l], (int64_t)Cout * Cin * ks * Hkv, chunks);
     if (l > 0 || dk != nullptr || dv != nullptr) {
       // towards the input: contraction over this layer's output channels, taps mirrored
       hipLaunchKernelGGL(conv_product(Cout, Cin), dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
@@ -592,7 +616,8 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     }
     cur ^= 1;
   }
-  return hipSuccess;
+  hipLaunchKernelGGL(chunk_sum_all_kernel, dim3((unsigned)((n_sum_max + 255) / 256), (unsigned)n_sums), dim3(256), 0, stream, sums);
+  return hipGetLastError();
 }
 
 }  // namespace
