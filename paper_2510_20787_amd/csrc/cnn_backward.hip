@@ -314,16 +314,22 @@ template <int WC, int WM>
 __global__ void __launch_bounds__(256)
 weight_product_kernel(const float* __restrict__ act_in, const float* __restrict__ dpre, int Cin, int Cout, int ks, int dil,
                       const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
-                      int tiles_n, float* __restrict__ partial) {
+                      int tiles_n, int tiles, int n_work, float* __restrict__ partial) {
   // [operand][token of the slice][channel ^ 32 * (token & 1)]: the two lane halves of an operand read take neighbouring
   // tokens, and the swap of the row halves on odd tokens puts them on different banks without padding the rows
   __shared__ float ab_s[2][KCW][64];
   float (*a_s)[64] = ab_s[0];          // activations, channel = m
   float (*b_s)[64] = ab_s[1];          // d y, channel = c
   __shared__ int32_t lo_s[kTokChunk], hi_s[kTokChunk];
-  const int m0 = (blockIdx.x / tiles_n) * (32 * WM), c0 = (blockIdx.x % tiles_n) * (32 * WC);
-  const int h = blockIdx.y / ks, tap = blockIdx.y % ks;
-  const int chunk = blockIdx.z;
+  // Workgroups are dealt round-robin to the 8 XCDs; each XCD gets a contiguous range of work items, ordered (tile,
+  // tap, head, chunk), so that the tiles and taps of one (head, chunk), which read the same rows, meet in one L2.
+  const int per_xcd = (n_work + 7) / 8;
+  const int work = ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+  if (work >= n_work) return;
+  const int tile = work % tiles, head_tap = (work / tiles) % (Hkv * ks);
+  const int m0 = (tile / tiles_n) * (32 * WM), c0 = (tile % tiles_n) * (32 * WC);
+  const int h = head_tap / ks, tap = head_tap % ks;
+  const int chunk = work / (tiles * Hkv * ks);
   const int tid = threadIdx.x;
   const int off = (tap - (ks - 1) / 2) * dil;
   const int64_t tb = (int64_t)chunk * kTokChunk;
@@ -600,9 +606,10 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     const int tiles_m = (Cin + 32 * wm - 1) / (32 * wm), tiles_n = (Cout + 32 * wc - 1) / (32 * wc);
     auto weight_product = wc == 2 ? (wm == 2 ? weight_product_kernel<2, 2> : weight_product_kernel<2, 1>)
                                   : (wm == 2 ? weight_product_kernel<1, 2> : weight_product_kernel<1, 1>);
-    hipLaunchKernelGGL(weight_product, dim3((unsigned)(tiles_m * tiles_n), (unsigned)(Hkv * ks), (unsigned)chunks),
-                       dim3(256), 0, stream, in_of(l), dpre, Cin, Cout, ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv,
-                       tiles_n, L.part_w[l]);
+    const int64_t n_work = (int64_t)tiles_m * tiles_n * Hkv * ks * chunks;
+    if (n_work > (int64_t)1 << 30) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(weight_product, dim3((unsigned)((n_work + 7) / 8 * 8)), dim3(256), 0, stream, in_of(l), dpre, Cin, Cout,
+                       ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv, tiles_n, tiles_m * tiles_n, (int)n_work, L.part_w[l]);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     second_stage(L.part_w[l], g.w[l], (int64_t)Cout * Cin * ks * Hkv, chunks);
     if (l > 0 || dk != nullptr || dv != nullptr) {
