@@ -13,6 +13,8 @@
 //                       d y_{l-1} = d a_{l-1} * silu'(y_{l-1})        (l > 1)   or   dk, dv = d a_0   (l = 1).
 // Sums over tokens are taken in two stages: per chunk of kTokChunk (weights) or kColChunk (column sums) tokens into a
 // partial array, then over the chunks.
+#include <type_traits>
+
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 #include "rope_dev.h"
@@ -75,11 +77,12 @@ features_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stride
 }
 
 // The weights of one layer as two fp32 panels per head: wf[h][tap][m][c] (contraction over the input channels m: the
-// forward) and wb[h][tap][c][m] (contraction over the output channels c: the backward towards the input).
+// forward) and wb[h][tap][c][m] (contraction over the output channels c: the backward towards the input);
+// wq, when given, is wb's order in the storage type (the operand of the first layer's forward on bf16 storage).
 template <typename T>
 __global__ void __launch_bounds__(256)
 weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t n, float* __restrict__ wf,
-                     float* __restrict__ wb) {
+                     float* __restrict__ wb, T* __restrict__ wq) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over [h][c][m][tap]
   if (i >= n) return;
   const int tap = (int)(i % ks);
@@ -89,6 +92,7 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
   const float w = to_f32(W[i]);
   wf[((h * ks + tap) * Cin + m) * Cout + c] = w;
   wb[((h * ks + tap) * Cout + c) * Cin + m] = w;
+  if (wq != nullptr) wq[((h * ks + tap) * Cout + c) * Cin + m] = W[i];     // wb's order in the storage type
 }
 
 // The fp32 products below run on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per instruction: lane l
@@ -306,6 +310,141 @@ conv_product_kernel(const float* __restrict__ in, const float* __restrict__ wt, 
   }
 }
 
+// Forward of the first layer on bf16 storage: pre = bias + sum_tap sum_m x[t + off(tap)][m] * W[c][m][tap] with x the
+// token's key and value features.  Both operands are bf16 values, so their products are exact in fp32 and the bf16
+// matrix instruction (v_mfma_f32_32x32x16_bf16, fp32 accumulation) gives what the fp32 one would at 16 times the rate.
+// Same tiling as conv_product_kernel: TMC tokens x TN outputs per workgroup, slices of KCB channels (a slice lies in
+// the keys or in the values), the rows of a group of taps staged once; rows are read straight from k / v.
+constexpr int KCB = 32, RSQ = KCB + 8;     // channels per slice; LDS row stride in elements (16-byte reads of 16 lanes
+                                           // then cover all banks)
+constexpr int PQA = A_ROWS * (KCB / 8) / 256, PQB = GT * TN * (KCB / 8) / 256;
+static_assert(A_ROWS * (KCB / 8) % 256 == 0 && GT * TN * (KCB / 8) % 256 == 0, "whole 16-byte pieces per thread");
+
+template <bool NARROW>
+__global__ void __launch_bounds__(256, 4)
+conv_first_bf16_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int64_t stride_tok, int64_t stride_head,
+                       const bf16_t* __restrict__ wq, int D, int N, int ks, int dil, const int32_t* __restrict__ seq_lo,
+                       const int32_t* __restrict__ seq_hi, int64_t total, const float* __restrict__ bias,
+                       float* __restrict__ pre, float* __restrict__ act) {
+  __shared__ __align__(16) bf16_t a_s[A_ROWS][RSQ];       // [staged token row][channel of the slice]
+  __shared__ __align__(16) bf16_t b_s[GT][TN][RSQ];       // [tap of the group][output][channel of the slice]
+  const int K = 2 * D;
+  const int h = blockIdx.z;
+  const int64_t t0 = (int64_t)blockIdx.x * TMC;
+  const int n0 = blockIdx.y * TN;
+  const int tid = threadIdx.x;
+  const bf16_t* w_h = wq + (int64_t)h * ks * N * K;
+  const int half = (ks - 1) / 2;
+  const int lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
+  constexpr int U = NARROW ? 1 : 2;                       // wave roles as in conv_product_kernel
+  const int row0 = NARROW ? 32 * wv : 64 * (wv >> 1), col0 = NARROW ? 0 : 32 * (wv & 1);
+  int64_t tok[U];
+  int lo[U], hi[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    tok[u] = t0 + row0 + 32 * u + ql;
+    const bool ok = tok[u] < total;
+    lo[u] = ok ? seq_lo[tok[u]] : 0;
+    hi[u] = ok ? seq_hi[tok[u]] : 0;
+  }
+  f32x16 acc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+  const int per_group = min(GT, 1 + HALO / dil);
+  const int groups = (ks + per_group - 1) / per_group;
+  const int slices = K / KCB, stages = groups * slices;   // D is a multiple of KCB
+  auto stage_taps = [&](int stage, int& tap0, int& ntap, int& k0, int& base_off) {
+    const int g = stage / slices;
+    k0 = (stage - g * slices) * KCB;
+    tap0 = g * per_group;
+    ntap = min(per_group, ks - tap0);
+    base_off = (tap0 - half) * dil;
+  };
+  u32x4 ra[PQA], rb[PQB];
+  unsigned keep_a, keep_b;       // one bit per 16-byte piece: does it count
+  auto fetch = [&](int stage) {
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
+    const int rows = TMC + (ntap - 1) * dil;
+    const bf16_t* src = (k0 < D ? k + k0 : v + (k0 - D)) + (int64_t)h * stride_head;
+    keep_a = keep_b = 0u;
+#pragma unroll
+    for (int i = 0; i < PQA; ++i) {
+      const int e = tid + 256 * i, row = e / (KCB / 8), q = e % (KCB / 8);
+      const int64_t p = t0 + row + base_off;
+      const bool ok = row < rows && p >= 0 && p < total;
+      ra[i] = *reinterpret_cast<const u32x4*>(src + (ok ? p : 0) * stride_tok + 8 * q);   // unconditional, inside the array
+      keep_a |= ok ? 1u << i : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < PQB; ++i) {
+      const int e = tid + 256 * i, jn = e / (KCB / 8), q = e % (KCB / 8);
+      const int j = jn / TN, n = jn % TN;
+      const bool ok = j < ntap && n0 + n < N;
+      rb[i] = *reinterpret_cast<const u32x4*>(w_h + (ok ? ((int64_t)(tap0 + j) * N + n0 + n) * K : 0) + k0 + 8 * q);
+      keep_b |= ok ? 1u << i : 0u;
+    }
+  };
+  auto masked_piece = [](u32x4 x, bool keep) {
+    asm volatile("" : "+v"(x));      // the loaded value is needed whatever the mask says: the load stays unconditional
+    return keep ? x : u32x4{0u, 0u, 0u, 0u};
+  };
+  fetch(0);
+  for (int stage = 0; stage < stages; ++stage) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PQA; ++i) {
+      const int e = tid + 256 * i;
+      *reinterpret_cast<u32x4*>(&a_s[e / (KCB / 8)][8 * (e % (KCB / 8))]) = masked_piece(ra[i], keep_a >> i & 1u);
+    }
+#pragma unroll
+    for (int i = 0; i < PQB; ++i) {
+      const int e = tid + 256 * i, jn = e / (KCB / 8);
+      *reinterpret_cast<u32x4*>(&b_s[jn / TN][jn % TN][8 * (e % (KCB / 8))]) = masked_piece(rb[i], keep_b >> i & 1u);
+    }
+    __syncthreads();
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
+    if (stage + 1 < stages) fetch(stage + 1);
+    for (int j = 0; j < ntap; ++j) {
+      const int off = (tap0 + j - half) * dil;
+      const int shift = off - base_off;
+      bool valid[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) valid[u] = tok[u] + off >= lo[u] && tok[u] + off < hi[u];
+      // lane half hb supplies channels 16 s + 8 hb .. + 7 of its row (tokens) / column (outputs) to step s
+#pragma unroll
+      for (int sk = 0; sk < KCB / 16; ++sk) {
+        u32x4 a[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[u] = *reinterpret_cast<const u32x4*>(&a_s[row0 + 32 * u + ql + shift][16 * sk + 8 * hb]);
+        const u32x4 b = *reinterpret_cast<const u32x4*>(&b_s[j][col0 + ql][16 * sk + 8 * hb]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          a[u] = masked_piece(a[u], valid[u]);
+          acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[u]), __builtin_bit_cast(bf16x8, b),
+                                                          acc[u], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the sub-tile, output column ql
+  const int n = n0 + col0 + ql;
+  if (n >= N) return;
+  const float bv = bias[(int64_t)h * N + n];
+#pragma unroll
+  for (int ur = 0; ur < 16 * U; ++ur) {
+    const int64_t t = t0 + row0 + 32 * (ur / 16) + 8 * ((ur % 16) / 4) + 4 * hb + (ur % 4);
+    if (t >= total) continue;
+    const int64_t o = ((int64_t)h * total + t) * N + n;
+    const float y = acc[ur / 16][ur % 16] + bv;
+    pre[o] = y;
+    act[o] = silu_f32(y);
+  }
+}
+
 // Stage 1 of d W_l: partial[chunk][h][c][m][tap] = sum over the chunk's tokens t of a_{l-1}[t + off][m] * d y_l[t][c],
 // a tiled fp32 product with the tokens as the contraction index (slices of KCW tokens through LDS).  The chunk's
 // sequence bounds are staged in LDS first, so a slice's operands need one round of global loads, not two dependent
@@ -483,6 +622,7 @@ struct Layout {
   float* act[LTEA_MAX_CNN_LAYERS];
   float* dpre[2];                             // [Hkv][T][widest layer], ping-pong
   float *wf[LTEA_MAX_CNN_LAYERS], *wb[LTEA_MAX_CNN_LAYERS];   // fp32 weight panels of every layer
+  void* wq0;                                  // first layer's weights [Hkv][k][C_0][2D] in the storage type (bf16 only)
   float* part_w[LTEA_MAX_CNN_LAYERS];         // [chunks][Hkv][C_l][C_{l-1}][k]: partial weight gradients
   float* part_b[LTEA_MAX_CNN_LAYERS];         // [column chunks][Hkv][C_l]: partial bias gradients
   float *part_wout, *part_bout;               // [column chunks][Hkv][C_L], [column chunks][Hkv]
@@ -515,6 +655,7 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
     L.wb[l] = reinterpret_cast<float*>(take(sizeof(float) * w));
     cin = cnn.c_out[l];
   }
+  L.wq0 = cfg.dtype == LTEA_F32 ? nullptr : take(sizeof(bf16_t) * (size_t)cfg.Hkv * cnn.c_out[0] * 2 * cfg.D * cnn.kernel[0]);
   const size_t chunks = (size_t)((total + kTokChunk - 1) / kTokChunk);
   const size_t col_chunks = (size_t)((total + kColChunk - 1) / kColChunk);
   cin = 2 * cfg.D;
@@ -551,7 +692,8 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   auto panels = [&](int l) {
     const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
     hipLaunchKernelGGL(weight_panels_kernel<T>, blocks(n), dim3(256), 0, stream, static_cast<const T*>(cnn.w[l]), cin_of(l),
-                       cnn.c_out[l], cnn.kernel[l], n, L.wf[l], L.wb[l]);
+                       cnn.c_out[l], cnn.kernel[l], n, L.wf[l], L.wb[l],
+                       l == 0 ? static_cast<T*>(L.wq0) : static_cast<T*>(nullptr));
     return hipGetLastError();
   };
   hipLaunchKernelGGL(token_bounds_kernel, blocks(total), dim3(256), 0, stream, sv.cu_seqlens, sv.n_seqs, total, L.seq_lo,
@@ -564,6 +706,17 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   for (int l = 0; l < nl; ++l) {
     if ((e = panels(l)) != hipSuccess) return e;
     const int N = cnn.c_out[l];
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      if (l == 0) {     // both operands are bf16 values: the bf16 matrix instruction gives the fp32 result
+        const dim3 grid(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv);
+        hipLaunchKernelGGL(N <= 32 ? conv_first_bf16_kernel<true> : conv_first_bf16_kernel<false>, grid, dim3(256), 0, stream,
+                           static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), stride_tok, stride_head,
+                           static_cast<const bf16_t*>(L.wq0), D, N, cnn.kernel[0], cnn.dilation[0], L.seq_lo, L.seq_hi, total,
+                           cnn.bias[0], L.pre[0], L.act[0]);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        continue;
+      }
+    }
     hipLaunchKernelGGL(conv_product(cin_of(l), N), dim3(tok_tiles, (unsigned)((N + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
                        stream, in_of(l), L.wf[l], cin_of(l), N, cnn.kernel[l], cnn.dilation[l], 1, L.seq_lo, L.seq_hi, total,
                        Hkv, 0, cnn.bias[l], static_cast<const float*>(nullptr), L.pre[l], L.act[l], static_cast<T*>(nullptr),
