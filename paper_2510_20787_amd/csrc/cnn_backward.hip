@@ -78,11 +78,12 @@ features_kernel(const T* __restrict__ k, const T* __restrict__ v, int64_t stride
 
 // The weights of one layer as two fp32 panels per head: wf[h][tap][m][c] (contraction over the input channels m: the
 // forward) and wb[h][tap][c][m] (contraction over the output channels c: the backward towards the input);
-// wq, when given, is wb's order in the storage type (the operand of the first layer's forward on bf16 storage).
+// wq and wqf, when given, are wb's and wf's order in the storage type (operands of the bf16 matrix instruction on
+// bf16 storage: the first layer's forward, and the products towards the input).
 template <typename T>
 __global__ void __launch_bounds__(256)
 weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t n, float* __restrict__ wf,
-                     float* __restrict__ wb, T* __restrict__ wq) {
+                     float* __restrict__ wb, T* __restrict__ wq, T* __restrict__ wqf) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;     // over [h][c][m][tap]
   if (i >= n) return;
   const int tap = (int)(i % ks);
@@ -93,6 +94,7 @@ weight_panels_kernel(const T* __restrict__ W, int Cin, int Cout, int ks, int64_t
   wf[((h * ks + tap) * Cin + m) * Cout + c] = w;
   wb[((h * ks + tap) * Cout + c) * Cin + m] = w;
   if (wq != nullptr) wq[((h * ks + tap) * Cout + c) * Cin + m] = W[i];     // wb's order in the storage type
+  if (wqf != nullptr) wqf[((h * ks + tap) * Cin + m) * Cout + c] = W[i];   // wf's order in the storage type
 }
 
 // The fp32 products below run on v_mfma_f32_32x32x2_f32 (fp32 operands, two contraction steps per instruction: lane l
@@ -445,6 +447,176 @@ conv_first_bf16_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ 
   }
 }
 
+// Towards the input on bf16 storage: out[t][m] = sum_tap sum_c d y[t - off(tap)][c] * W[c][m][tap].  The weights are
+// bf16 values; the fp32 d y is split into three bf16 terms (x = hi + mid + lo up to 2^-24 of x), whose products with
+// the weights are exact in fp32, so three bf16 matrix instructions give the fp32 product at about five times the fp32
+// instruction's rate.  Tiling as conv_product_kernel, slices of KCS channels; used when K and N are multiples of 8.
+// mode 1: dpre_out = out * silu'(pre_prev);  mode 2: dk / dv [T][Hkv][D] (n < D: key part).
+constexpr int KCS = 16, RSS = KCS + 8;     // channels per slice; LDS row stride in elements
+constexpr int PSA = A_ROWS * (KCS / 4) / 256, PSB = (GT * TN * (KCS / 8) + 255) / 256;
+static_assert(A_ROWS * (KCS / 4) % 256 == 0, "whole quads per thread");
+
+template <bool NARROW>
+__global__ void __launch_bounds__(256, 4)
+conv_back_bf16_kernel(const float* __restrict__ in, const bf16_t* __restrict__ wqf, int K, int N, int ks, int dil,
+                      const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
+                      int mode, const float* __restrict__ pre_prev, float* __restrict__ out0, bf16_t* __restrict__ dk,
+                      bf16_t* __restrict__ dv, int D) {
+  __shared__ __align__(16) bf16_t a_s[3][A_ROWS][RSS];    // [term of the split][staged token row][channel of the slice]
+  __shared__ __align__(16) bf16_t b_s[GT][TN][RSS];       // [tap of the group][output][channel of the slice]
+  const int h = blockIdx.z;
+  const int64_t t0 = (int64_t)blockIdx.x * TMC;
+  const int n0 = blockIdx.y * TN;
+  const int tid = threadIdx.x;
+  const float* in_h = in + (int64_t)h * total * K;
+  const bf16_t* w_h = wqf + (int64_t)h * ks * N * K;
+  const int half = (ks - 1) / 2;
+  const int lane = tid & 63, wv = tid >> 6, ql = lane & 31, hb = lane >> 5;
+  constexpr int U = NARROW ? 1 : 2;                       // wave roles as in conv_product_kernel
+  const int row0 = NARROW ? 32 * wv : 64 * (wv >> 1), col0 = NARROW ? 0 : 32 * (wv & 1);
+  int64_t tok[U];
+  int lo[U], hi[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    tok[u] = t0 + row0 + 32 * u + ql;
+    const bool ok = tok[u] < total;
+    lo[u] = ok ? seq_lo[tok[u]] : 0;
+    hi[u] = ok ? seq_hi[tok[u]] : 0;
+  }
+  f32x16 acc[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[u][r] = 0.f;
+  const int per_group = min(GT, 1 + HALO / dil);
+  const int groups = (ks + per_group - 1) / per_group;
+  const int slices = (K + KCS - 1) / KCS, stages = groups * slices;
+  // taps are mirrored: tap j of a group reads row t - (tap - half) * dil; the group's lowest row belongs to its last tap
+  auto stage_taps = [&](int stage, int& tap0, int& ntap, int& k0, int& base_off) {
+    const int g = stage / slices;
+    k0 = (stage - g * slices) * KCS;
+    tap0 = g * per_group;
+    ntap = min(per_group, ks - tap0);
+    base_off = -(tap0 + ntap - 1 - half) * dil;
+  };
+  float4 ra[PSA];
+  u32x4 rb[PSB];
+  unsigned keep_a, keep_b;
+  auto fetch = [&](int stage) {
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
+    const int rows = TMC + (ntap - 1) * dil;
+    keep_a = keep_b = 0u;
+#pragma unroll
+    for (int i = 0; i < PSA; ++i) {
+      const int e = tid + 256 * i, row = e / (KCS / 4), q = e % (KCS / 4);
+      const int64_t p = t0 + row + base_off;
+      const bool ok = row < rows && p >= 0 && p < total && k0 + 4 * q < K;          // K % 4 == 0: whole quads
+      ra[i] = *reinterpret_cast<const float4*>(in_h + (ok ? p : 0) * K + min(k0 + 4 * q, K - 4));
+      keep_a |= ok ? 1u << i : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < PSB; ++i) {
+      const int e = tid + 256 * i, jn = e / (KCS / 8), q = e % (KCS / 8);
+      const int j = jn / TN, n = jn % TN;
+      const bool ok = e < GT * TN * (KCS / 8) && j < ntap && n0 + n < N && k0 + 8 * q < K;   // K % 8 == 0: whole pieces
+      rb[i] = *reinterpret_cast<const u32x4*>(w_h + (ok ? ((int64_t)(tap0 + j) * N + n0 + n) * K : 0) + min(k0 + 8 * q, K - 8));
+      keep_b |= ok ? 1u << i : 0u;
+    }
+  };
+  auto masked_piece = [](u32x4 x, bool keep) {
+    asm volatile("" : "+v"(x));      // the loaded value is needed whatever the mask says: the load stays unconditional
+    return keep ? x : u32x4{0u, 0u, 0u, 0u};
+  };
+  auto bits = [](float x) { return (uint32_t)__builtin_bit_cast(uint16_t, from_f32<bf16_t>(x)); };
+  fetch(0);
+  for (int stage = 0; stage < stages; ++stage) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < PSA; ++i) {
+      const int e = tid + 256 * i, row = e / (KCS / 4), q = e % (KCS / 4);
+      const float4 x = masked_quad(ra[i], (keep_a >> i & 1u) ? 0xFu : 0u);
+      const float xs[4] = {x.x, x.y, x.z, x.w};
+      uint32_t t[3][4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bf16_t b0 = from_f32<bf16_t>(xs[c]);
+        const float r1 = xs[c] - static_cast<float>(b0);       // exact
+        const bf16_t b1 = from_f32<bf16_t>(r1);
+        const float r2 = r1 - static_cast<float>(b1);           // exact
+        t[0][c] = (uint32_t)__builtin_bit_cast(uint16_t, b0);
+        t[1][c] = (uint32_t)__builtin_bit_cast(uint16_t, b1);
+        t[2][c] = bits(r2);
+      }
+#pragma unroll
+      for (int m = 0; m < 3; ++m)
+        *reinterpret_cast<uint2*>(&a_s[m][row][4 * q]) = make_uint2(t[m][0] | t[m][1] << 16, t[m][2] | t[m][3] << 16);
+    }
+#pragma unroll
+    for (int i = 0; i < PSB; ++i) {
+      const int e = tid + 256 * i, jn = e / (KCS / 8);
+      if (e < GT * TN * (KCS / 8))
+        *reinterpret_cast<u32x4*>(&b_s[jn / TN][jn % TN][8 * (e % (KCS / 8))]) = masked_piece(rb[i], keep_b >> i & 1u);
+    }
+    __syncthreads();
+    int tap0, ntap, k0, base_off;
+    stage_taps(stage, tap0, ntap, k0, base_off);
+    if (stage + 1 < stages) fetch(stage + 1);
+    for (int j = 0; j < ntap; ++j) {
+      const int off = -(tap0 + j - half) * dil;
+      const int shift = off - base_off;
+      bool valid[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) valid[u] = tok[u] + off >= lo[u] && tok[u] + off < hi[u];
+      // lane half hb supplies channels 8 hb .. 8 hb + 7 of its row (tokens) / column (outputs)
+      u32x4 a[3][U];
+#pragma unroll
+      for (int m = 0; m < 3; ++m)
+#pragma unroll
+        for (int u = 0; u < U; ++u) a[m][u] = *reinterpret_cast<const u32x4*>(&a_s[m][row0 + 32 * u + ql + shift][8 * hb]);
+      const u32x4 b = *reinterpret_cast<const u32x4*>(&b_s[j][col0 + ql][8 * hb]);
+#pragma unroll
+      for (int m = 2; m >= 0; --m)        // smallest terms first
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          a[m][u] = masked_piece(a[m][u], valid[u]);
+          acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[m][u]), __builtin_bit_cast(bf16x8, b),
+                                                          acc[u], 0, 0, 0);
+        }
+    }
+  }
+  // accumulator register r of lane half hb: token row 8*(r/4) + 4*hb + r%4 of the sub-tile, output column ql
+  const int n = n0 + col0 + ql;
+  if (n >= N) return;
+  auto token_of = [&](int ur) { return t0 + row0 + 32 * (ur / 16) + 8 * ((ur % 16) / 4) + 4 * hb + (ur % 4); };
+  if (mode == 1) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float pp[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t t = token_of(16 * u + r);
+        pp[r] = pre_prev[t < total ? ((int64_t)h * total + t) * N + n : 0];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t t = token_of(16 * u + r);
+        if (t < total) out0[((int64_t)h * total + t) * N + n] = acc[u][r] * silu_grad_f32(pp[r]);
+      }
+    }
+  } else {
+    bf16_t* dst = n < D ? dk : dv;
+    const int col = n < D ? n : n - D;
+    if (dst != nullptr) {
+#pragma unroll
+      for (int ur = 0; ur < 16 * U; ++ur) {
+        const int64_t t = token_of(ur);
+        if (t < total) dst[(t * Hkv + h) * D + col] = from_f32<bf16_t>(acc[ur / 16][ur % 16]);
+      }
+    }
+  }
+}
+
 // Stage 1 of d W_l: partial[chunk][h][c][m][tap] = sum over the chunk's tokens t of a_{l-1}[t + off][m] * d y_l[t][c],
 // a tiled fp32 product with the tokens as the contraction index (slices of KCW tokens through LDS).  The chunk's
 // sequence bounds are staged in LDS first, so a slice's operands need one round of global loads, not two dependent
@@ -623,6 +795,7 @@ struct Layout {
   float* dpre[2];                             // [Hkv][T][widest layer], ping-pong
   float *wf[LTEA_MAX_CNN_LAYERS], *wb[LTEA_MAX_CNN_LAYERS];   // fp32 weight panels of every layer
   void* wq0;                                  // first layer's weights [Hkv][k][C_0][2D] in the storage type (bf16 only)
+  void* wqf[LTEA_MAX_CNN_LAYERS];             // every layer's weights [Hkv][k][C_{l-1}][C_l] in the storage type (bf16 only)
   float* part_w[LTEA_MAX_CNN_LAYERS];         // [chunks][Hkv][C_l][C_{l-1}][k]: partial weight gradients
   float* part_b[LTEA_MAX_CNN_LAYERS];         // [column chunks][Hkv][C_l]: partial bias gradients
   float *part_wout, *part_bout;               // [column chunks][Hkv][C_L], [column chunks][Hkv]
@@ -653,6 +826,12 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
     const size_t w = (size_t)cfg.Hkv * cnn.c_out[l] * cin * cnn.kernel[l];
     L.wf[l] = reinterpret_cast<float*>(take(sizeof(float) * w));
     L.wb[l] = reinterpret_cast<float*>(take(sizeof(float) * w));
+    cin = cnn.c_out[l];
+  }
+  cin = 2 * cfg.D;
+  for (int l = 0; l < LTEA_MAX_CNN_LAYERS; ++l) L.wqf[l] = nullptr;
+  for (int l = 0; l < cnn.n_layers; ++l) {
+    if (cfg.dtype != LTEA_F32) L.wqf[l] = take(sizeof(bf16_t) * (size_t)cfg.Hkv * cnn.c_out[l] * cin * cnn.kernel[l]);
     cin = cnn.c_out[l];
   }
   L.wq0 = cfg.dtype == LTEA_F32 ? nullptr : take(sizeof(bf16_t) * (size_t)cfg.Hkv * cnn.c_out[0] * 2 * cfg.D * cnn.kernel[0]);
@@ -693,7 +872,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     const int64_t n = (int64_t)Hkv * cnn.c_out[l] * cin_of(l) * cnn.kernel[l];
     hipLaunchKernelGGL(weight_panels_kernel<T>, blocks(n), dim3(256), 0, stream, static_cast<const T*>(cnn.w[l]), cin_of(l),
                        cnn.c_out[l], cnn.kernel[l], n, L.wf[l], L.wb[l],
-                       l == 0 ? static_cast<T*>(L.wq0) : static_cast<T*>(nullptr));
+                       l == 0 ? static_cast<T*>(L.wq0) : static_cast<T*>(nullptr), static_cast<T*>(L.wqf[l]));
     return hipGetLastError();
   };
   hipLaunchKernelGGL(token_bounds_kernel, blocks(total), dim3(256), 0, stream, sv.cu_seqlens, sv.n_seqs, total, L.seq_lo,
@@ -767,12 +946,26 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     second_stage(L.part_w[l], g.w[l], (int64_t)Cout * Cin * ks * Hkv, chunks);
     if (l > 0 || dk != nullptr || dv != nullptr) {
       // towards the input: contraction over this layer's output channels, taps mirrored
+      bool done = false;
+      if constexpr (std::is_same<T, bf16_t>::value) {
+        if (Cout % 8 == 0 && Cin % 8 == 0) {   // bf16 weights, d y split into three bf16 terms
+          const dim3 grid(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv);
+          hipLaunchKernelGGL(Cin <= 32 ? conv_back_bf16_kernel<true> : conv_back_bf16_kernel<false>, grid, dim3(256), 0, stream,
+                             dpre, static_cast<const bf16_t*>(L.wqf[l]), Cout, Cin, ks, cnn.dilation[l], L.seq_lo, L.seq_hi,
+                             total, Hkv, l > 0 ? 1 : 2, l > 0 ? L.pre[l - 1] : static_cast<const float*>(nullptr),
+                             L.dpre[cur ^ 1], static_cast<bf16_t*>(dk), static_cast<bf16_t*>(dv), D);
+          if ((e = hipGetLastError()) != hipSuccess) return e;
+          done = true;
+        }
+      }
+      if (!done) {
       hipLaunchKernelGGL(conv_product(Cout, Cin), dim3(tok_tiles, (unsigned)((Cin + TN - 1) / TN), (unsigned)Hkv), dim3(256), 0,
                          stream, dpre, L.wb[l], Cout, Cin, ks, cnn.dilation[l], -1, L.seq_lo, L.seq_hi, total, Hkv,
                          l > 0 ? 1 : 2, static_cast<const float*>(nullptr),
                          l > 0 ? L.pre[l - 1] : static_cast<const float*>(nullptr), L.dpre[cur ^ 1],
                          static_cast<float*>(nullptr), static_cast<T*>(dk), static_cast<T*>(dv), D);
       if ((e = hipGetLastError()) != hipSuccess) return e;
+      }
     }
     cur ^= 1;
   }
