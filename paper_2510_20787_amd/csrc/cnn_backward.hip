@@ -18,6 +18,7 @@
 #include "ltea_common.h"
 #include "ltea_kernels.h"
 #include "rope_dev.h"
+#include "mfma_tiles.h"
 
 namespace ltea {
 namespace {
@@ -724,6 +725,143 @@ weight_product_kernel(const float* __restrict__ act_in, const float* __restrict_
   }
 }
 
+// Stage 1 of d W_0 on bf16 storage: the input features are bf16 values, so with d y split into three bf16 terms (as in
+// conv_back_bf16_kernel) three bf16 matrix instructions give the fp32 product.  The contraction runs over the tokens,
+// i.e. over the rows of the staged [token][channel] tiles: both operands are fetched with transposing LDS loads
+// (eight consecutive tokens of one channel per lane).  Rows are 96 elements apart, which spreads the four rows a
+// 16-lane group reads over different banks.  Work order, wave roles and output as in weight_product_kernel with
+// WM = 2 (2 D >= 128 input channels); a 64-channel tile of input channels lies in the keys or in the values.
+constexpr int KCT = 64, RST = 96;            // tokens per slice, LDS row stride in elements
+template <int WC>
+__global__ void __launch_bounds__(256)
+weight_first_bf16_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int64_t stride_tok, int64_t stride_head,
+                         const float* __restrict__ dpre, int D, int Cout, int ks, int dil,
+                         const int32_t* __restrict__ seq_lo, const int32_t* __restrict__ seq_hi, int64_t total, int Hkv,
+                         int tiles_n, int tiles, int n_work, float* __restrict__ partial) {
+  __shared__ __align__(16) bf16_t x_s[KCT][RST];          // features: [token of the slice][m]
+  __shared__ __align__(16) bf16_t g_s[3][KCT][RST];       // d y, term of the split: [token of the slice][c]
+  __shared__ int32_t lo_s[kTokChunk], hi_s[kTokChunk];
+  constexpr int WM = 2, S = 4 / (WC * WM);
+  const int Cin = 2 * D;
+  const int per_xcd = (n_work + 7) / 8;
+  const int work = ((int)blockIdx.x % 8) * per_xcd + (int)blockIdx.x / 8;
+  if (work >= n_work) return;
+  const int tile = work % tiles, head_tap = (work / tiles) % (Hkv * ks);
+  const int m0 = (tile / tiles_n) * 64, c0 = (tile % tiles_n) * (32 * WC);
+  const int h = head_tap / ks, tap = head_tap % ks;
+  const int chunk = work / (tiles * Hkv * ks);
+  const int tid = threadIdx.x;
+  const int off = (tap - (ks - 1) / 2) * dil;
+  const int64_t tb = (int64_t)chunk * kTokChunk;
+  const int64_t te = tb + kTokChunk < total ? tb + kTokChunk : total;
+  const int len = (int)(te - tb), tb32 = (int)tb;
+  const bf16_t* x_h = (m0 < D ? k + m0 : v + (m0 - D)) + (int64_t)h * stride_head;
+  const float* g_h = dpre + ((int64_t)h * total + tb) * Cout;
+  const int lane = tid & 63, wv = tid >> 6, hb = lane >> 5;
+  const int wq = wv % (WC * WM), sp = wv / (WC * WM), ci = wq / WM, mi = wq % WM;
+  for (int i = tid; i < kTokChunk; i += 256) {
+    const bool ok = i < len;
+    lo_s[i] = ok ? seq_lo[tb + i] : 0;
+    hi_s[i] = ok ? seq_hi[tb + i] : 0;
+  }
+  __syncthreads();
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+  // loader roles: features as 16-byte pieces (8 per token row), d y as quads of floats (16 per token row)
+  constexpr int PX = KCT * 8 / 256, PG = KCT * 16 / 256;
+  u32x4 rx[PX];
+  float4 rg[PG];
+  unsigned keep_x, keep_g;
+  auto fetch = [&](int i0) {
+    keep_x = keep_g = 0u;
+#pragma unroll
+    for (int j = 0; j < PX; ++j) {
+      const int e = tid + 256 * j, i = i0 + e / 8, q = e % 8;
+      const bool t_ok = i < len;
+      const int ic = t_ok ? i : 0;
+      const int p = tb32 + ic + off;
+      const bool p_ok = t_ok & (p >= lo_s[ic]) & (p < hi_s[ic]);
+      rx[j] = *reinterpret_cast<const u32x4*>(x_h + (int64_t)(p_ok ? p : tb32) * stride_tok + 8 * q);
+      keep_x |= p_ok ? 1u << j : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < PG; ++j) {
+      const int e = tid + 256 * j, i = i0 + e / 16, q = e % 16;
+      const bool ok = i < len && c0 + 4 * q < Cout && 4 * q < 32 * WC;                // Cout % 4 == 0: whole quads
+      rg[j] = *reinterpret_cast<const float4*>(g_h + (int64_t)(i < len ? i : 0) * Cout + min(c0 + 4 * q, Cout - 4));
+      keep_g |= ok ? 1u << j : 0u;
+    }
+  };
+  auto masked_piece = [](u32x4 x, bool keep) {
+    asm volatile("" : "+v"(x));      // the loaded value is needed whatever the mask says: the load stays unconditional
+    return keep ? x : u32x4{0u, 0u, 0u, 0u};
+  };
+  // transposing loads: in each group of 16 lanes, lane j points at row j / 4, columns 4 * (j % 4) .. of its 16 columns
+  const int tr_row = 8 * hb + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  fetch(0);
+  for (int i0 = 0; i0 < len; i0 += KCT) {
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < PX; ++j) {
+      const int e = tid + 256 * j;
+      *reinterpret_cast<u32x4*>(&x_s[e / 8][8 * (e % 8)]) = masked_piece(rx[j], keep_x >> j & 1u);
+    }
+#pragma unroll
+    for (int j = 0; j < PG; ++j) {
+      const int e = tid + 256 * j, row = e / 16, q = e % 16;
+      const float4 y = masked_quad(rg[j], (keep_g >> j & 1u) ? 0xFu : 0u);
+      const float ys[4] = {y.x, y.y, y.z, y.w};
+      uint32_t t[3][4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const bf16_t b0 = from_f32<bf16_t>(ys[c]);
+        const float r1 = ys[c] - static_cast<float>(b0);        // exact
+        const bf16_t b1 = from_f32<bf16_t>(r1);
+        const float r2 = r1 - static_cast<float>(b1);            // exact
+        t[0][c] = (uint32_t)__builtin_bit_cast(uint16_t, b0);
+        t[1][c] = (uint32_t)__builtin_bit_cast(uint16_t, b1);
+        t[2][c] = (uint32_t)__builtin_bit_cast(uint16_t, from_f32<bf16_t>(r2));
+      }
+#pragma unroll
+      for (int m = 0; m < 3; ++m)
+        *reinterpret_cast<uint2*>(&g_s[m][row][4 * q]) = make_uint2(t[m][0] | t[m][1] << 16, t[m][2] | t[m][3] << 16);
+    }
+    __syncthreads();
+    if (i0 + KCT < len) fetch(i0 + KCT);
+#pragma unroll
+    for (int st = sp; st < KCT / 16; st += S) {              // steps of 16 tokens, shared among the S waves of a tile
+      const bf16x8 b = load_transposed(&x_s[16 * st + tr_row][32 * mi + tr_col], RST);
+#pragma unroll
+      for (int m = 2; m >= 0; --m)                           // smallest terms first
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_transposed(&g_s[m][16 * st + tr_row][32 * ci + tr_col], RST), b,
+                                                      acc, 0, 0, 0);
+    }
+  }
+  if constexpr (S > 1) {
+    float* red = reinterpret_cast<float*>(&g_s[0][0][0]);   // (S - 1) * WC * WM accumulator tiles of 1024 floats
+    __syncthreads();
+    if (sp > 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) red[((sp - 1) * WC * WM + wq) * 1024 + r * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (sp > 0) return;
+    for (int kk = 1; kk < S; ++kk)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] += red[((kk - 1) * WC * WM + wq) * 1024 + r * 64 + lane];
+  }
+  const int64_t per_head = (int64_t)Cout * Cin * ks;
+  float* out = partial + ((int64_t)chunk * Hkv + h) * per_head;
+  const int ql = lane & 31;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int c = c0 + 32 * ci + 8 * (r / 4) + 4 * hb + (r % 4);
+    const int m = m0 + 32 * mi + ql;
+    if (m < Cin && c < Cout) out[((int64_t)c * Cin + m) * ks + tap] = acc[r];
+  }
+}
+
 // Stage 2: out[i] = sum over chunks of partial[chunk][i], in chunk order.
 __global__ void __launch_bounds__(256)
 chunk_sum_kernel(const float* __restrict__ partial, int64_t n, int chunks, float* __restrict__ out) {
@@ -878,8 +1016,11 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   hipLaunchKernelGGL(token_bounds_kernel, blocks(total), dim3(256), 0, stream, sv.cu_seqlens, sv.n_seqs, total, L.seq_lo,
                      L.seq_hi);
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(features_kernel<T>, dim3((unsigned)((total * (2 * D / Elems<T>::N) + 255) / 256), (unsigned)Hkv), dim3(256), 0, stream,
-                     static_cast<const T*>(k), static_cast<const T*>(v), stride_tok, stride_head, D, total, L.a0);
+  // on bf16 storage the first layer's kernels read k / v themselves, unless its weight product takes the fp32 route
+  if (!(std::is_same<T, bf16_t>::value && cnn.c_out[0] % 4 == 0)) {
+    hipLaunchKernelGGL(features_kernel<T>, dim3((unsigned)((total * (2 * D / Elems<T>::N) + 255) / 256), (unsigned)Hkv), dim3(256),
+                       0, stream, static_cast<const T*>(k), static_cast<const T*>(v), stride_tok, stride_head, D, total, L.a0);
+  }
   if ((e = hipGetLastError()) != hipSuccess) return e;
   // 1. forward, pre-activations and activations kept
   for (int l = 0; l < nl; ++l) {
@@ -940,10 +1081,22 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
                                   : (wm == 2 ? weight_product_kernel<1, 2> : weight_product_kernel<1, 1>);
     const int64_t n_work = (int64_t)tiles_m * tiles_n * Hkv * ks * chunks;
     if (n_work > (int64_t)1 << 30) return hipErrorInvalidValue;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      if (l == 0 && Cout % 4 == 0) {   // bf16 features, d y split into three bf16 terms
+        hipLaunchKernelGGL(wc == 2 ? weight_first_bf16_kernel<2> : weight_first_bf16_kernel<1>, dim3((unsigned)((n_work + 7) / 8 * 8)),
+                           dim3(256), 0, stream, static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), stride_tok,
+                           stride_head, dpre, D, Cout, ks, cnn.dilation[0], L.seq_lo, L.seq_hi, total, Hkv, tiles_n,
+                           tiles_m * tiles_n, (int)n_work, L.part_w[0]);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        second_stage(L.part_w[0], g.w[0], (int64_t)Cout * Cin * ks * Hkv, chunks);
+        goto weights_done;
+      }
+    }
     hipLaunchKernelGGL(weight_product, dim3((unsigned)((n_work + 7) / 8 * 8)), dim3(256), 0, stream, in_of(l), dpre, Cin, Cout,
                        ks, cnn.dilation[l], L.seq_lo, L.seq_hi, total, Hkv, tiles_n, tiles_m * tiles_n, (int)n_work, L.part_w[l]);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     second_stage(L.part_w[l], g.w[l], (int64_t)Cout * Cin * ks * Hkv, chunks);
+  weights_done:
     if (l > 0 || dk != nullptr || dv != nullptr) {
       // towards the input: contraction over this layer's output channels, taps mirrored
       bool done = false;

@@ -132,13 +132,15 @@ def test_train_with_logits_supplied_by_the_caller():
                          [("f32", (5,), (16,), None, [70, 0, 33]), ("bf16", (3, 3, 3), (64, 32, 16), (2, 2, 2), [300, 41]),
                           ("bf16", (7,), (32,), None, [1500, 900, 1]), ("f32", (3, 1), (8, 24), (2, 1), [5, 2]),
                           ("f32", (3, 5), (10, 6), (40, 9), [200, 0, 90, 130]),
-                          ("bf16", (3, 3), (16, 48), (1, 3), [257, 64])])
+                          ("bf16", (3, 3), (16, 48), (1, 3), [257, 64]), ("bf16", (3, 3), (10, 6), (2, 1), [150, 77])])
 def test_cnn_backward(dtype, kernel, channels, dilation, lens):
     """Gradients of sum(dz * logits) through the scoring CNN against the oracle's chain rule: every conv weight and
     bias, the output projection, and the scored keys / values.  Shapes cover one to three layers, both storage types,
     more than one token chunk of the two-stage sums, empty and one-token sequences, channel counts that are not
     multiples of four, dilations beyond and within the rows a tile stages for a group of taps, and every combination
-    of narrow (<= 32) and wide channel counts on the two sides of a layer."""
+    of narrow (<= 32) and wide channel counts on the two sides of a layer.  On bf16 storage the first layer's forward,
+    its weight gradient and the products towards the input run on the bf16 matrix instruction (exact products, the
+    fp32 operand split into three bf16 terms) when the channel counts allow; the last case takes the fp32 routes."""
     Hq, Hkv, D = 4, 2, 64
     rho = sum(d * (k - 1) // 2 for k, d in zip(kernel, dilation or [1] * len(kernel)))
     w = wl.make_prefill("cnn_bwd", 1800 + len(kernel) + len(lens), dtype, lens, Hq, Hkv, D, max(27, 2 * rho + 3), 4, 0, 0.0,
