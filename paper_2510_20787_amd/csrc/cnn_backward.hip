@@ -1,11 +1,13 @@
 // Backward of the scoring CNN of the LTE module (paper Section 3.1.1; trained through the gradient of the logits
 // that Section 3.1.2 defines): from d(loss)/d(logit) to the gradients of every conv weight, bias, the output
-// projection and the input features.  fp32 arithmetic for any depth and either storage type, as LDS-tiled products
-// on the fp32 matrix instruction: the module is small next to the attention (paper
-// stack: 65 kflop per token-head forward).  Everything is summed in a fixed order: same bits every run.
+// projection and the input features.  fp32-accurate arithmetic for any depth and either storage type, as LDS-tiled
+// products on the fp32 matrix instruction, or, on bf16 storage where one operand is a bf16 value, on the bf16 one with
+// the fp32 operand split into three bf16 terms.  The module is small next to the attention (paper stack: 65 kflop
+// per token-head forward).  Everything is summed in a fixed order: same bits every run.
 //
 //   1. forward again, keeping the pre-activations y_l and the activations a_l = silu(y_l) of every layer
-//      (fp32 [Hkv][T][C_l] each); the features of layer 0 are copied to a dense fp32 array first;
+//      (fp32 [Hkv][T][C_l] each); the features of layer 0 are copied to a dense fp32 array first unless the bf16
+//      kernels read k / v themselves;
 //   2. d y_L = dz * w_out * silu'(y_L);  d w_out = sum_t dz * silu(y_L),  d b_out = sum_t dz;
 //   3. for l = L .. 1:  d bias_l = sum_t d y_l;
 //                       d W_l[c][m][tap] = sum_t d y_l[t][c] * a_{l-1}[t + off(tap)][m]      (inside the sequence)
