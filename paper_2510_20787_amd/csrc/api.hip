@@ -89,8 +89,12 @@ int hip_status(hipError_t e) { return e == hipSuccess ? LTEA_OK : LTEA_EHIP; }
 
 int do_score(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
              const SeqView& sv, float* logits, void* ws, hipStream_t stream) {
-  if (use_score_mfma(cfg, cnn)) return hip_status(launch_score_mfma(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
-  if (score_deep_supported(cfg, cnn)) return hip_status(launch_score_deep(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
+  // The matrix-core kernels are chosen from (cfg, cnn) alone, which is also what sizes their workspace; a token
+  // stride beyond their 32-bit row offsets (above a million elements) is refused rather than scored wrongly.
+  const bool mfma = use_score_mfma(cfg, cnn), deep = !mfma && score_deep_supported(cfg, cnn);
+  if ((mfma || deep) && !score_stride_ok(st)) return LTEA_EUNSUPPORTED;
+  if (mfma) return hip_status(launch_score_mfma(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
+  if (deep) return hip_status(launch_score_deep(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
   return hip_status(launch_score_generic(cfg, cnn, k, v, st, sh, sv, logits, ws, stream));
 }
 
@@ -355,6 +359,7 @@ int ltea_prefill_append_feat(const ltea_cfg* cfg, const ltea_cnn* cnn, const lte
   const int64_t ext_len_max = (int64_t)cfg->budget + 2 * (int64_t)cfg->window + max_new;
   if (ext_len_max > INT32_MAX / 2) return LTEA_EUNSUPPORTED;
   const int64_t ext = append_ext_tokens(*cfg, n_seqs, total_new);
+  if (ext >= (int64_t)1 << 31) return LTEA_EUNSUPPORTED;   // the packed extended sequences are indexed by int32 prefix sums
   const size_t build_ws = align_up(append_workspace(*cfg, n_seqs, total_new, rope != nullptr), 256);
   const size_t need = build_ws + score_workspace(*cfg, *cnn, ext);
   if (!workspace || workspace_bytes < need) return LTEA_EWORKSPACE;
@@ -612,16 +617,18 @@ int ltea_cnn_backward(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* k_fe
 
 int ltea_lambda_update(float* lambda, const float* c_bar, int32_t n, float cap, float alpha) {
   if (!lambda || !c_bar || n < 0 || !(alpha > 0.f) || !(cap >= 0.f)) return LTEA_EINVAL;
+  // The multiplier lives in fp32, so the floor is the fp32 image of 1e-9: a head that sits at the floor and whose
+  // count is inside the dead band [0.95 cap, cap] stays at the floor instead of being flushed to zero by the
+  // rounding of the floor itself.  Direction first (grow above the cap, shrink below 95 % of it, else hold), then
+  // the clamps: at most 1, zero below the floor, and back to the floor when a zero head overshoots the cap.
+  const float floor_l = 1e-9f;
   for (int i = 0; i < n; ++i) {
-    // in double so that the 1e-9 and 0.95 cap thresholds are the decimal ones
-    double l = lambda[i];
     const double c = c_bar[i];
-    if (c > (double)cap) l *= (double)alpha;
-    else if (c < 0.95 * (double)cap) l /= (double)alpha;
-    if (l > 1.0) l = 1.0;
-    if (l < 1e-9) l = 0.0;
-    if (c > (double)cap && l == 0.0) l = 1e-9;
-    lambda[i] = (float)l;
+    const bool over = c > (double)cap, under = c < 0.95 * (double)cap;
+    const double step = over ? (double)alpha : under ? 1.0 / (double)alpha : 1.0;
+    float l = (float)fmin((double)lambda[i] * step, 1.0);
+    if (l < floor_l) l = over ? floor_l : 0.0f;
+    lambda[i] = l;
   }
   return LTEA_OK;
 }

@@ -22,6 +22,13 @@ inline int cnn_rho(const ltea_cnn* c) {
 }
 
 // ---- (a) scoring -------------------------------------------------------------------------------
+// The matrix-core scoring kernels address the K/V rows of one workgroup (a group of token tiles plus halo, never
+// more than this many rows) with 32-bit byte offsets from a 64-bit base of their own, so a sequence may be of any
+// length; only the token stride is bounded.
+constexpr int kScoreRowsPerDescriptor = 1024;
+inline bool score_stride_ok(int64_t stride_tok) {
+  return stride_tok * 2 * kScoreRowsPerDescriptor < ((int64_t)1 << 31);
+}
 // Generic layered path (any depth, fp32 or bf16 storage, VALU): needs 2 * Hkv * T * max(c_out) floats
 // of scratch when n_layers > 1, Hkv * T * c_out[0] floats when n_layers == 1.
 size_t score_generic_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total_tokens);

@@ -126,12 +126,14 @@ retain_kernel(const RetainArgs a) {
 #pragma unroll
       for (int e = 0; e < kItems; ++e) held[c][e] = fetch(c * kChunk + tid * kItems + e);
   }
-  int n_chunks = (n_out + kChunk - 1) / kChunk;
-  if (CH > 0 && n_chunks > CH) n_chunks = CH;   // only if max_seqlen understated the lengths
+  const int n_chunks = (n_out + kChunk - 1) / kChunk;
+  // A sequence longer than the caller's max_seqlen (which picked CH) does not fit the held registers: its keys are
+  // re-read from memory in every pass instead (a workgroup-uniform choice), so the result stays exact.
+  const bool use_held = CH > 0 && n_chunks <= CH;
   auto chunk_keys = [&](int c, uint32_t (&u)[kItems]) {
-    if constexpr (CH > 0) {
+    if (use_held) {
 #pragma unroll
-      for (int cc = 0; cc < CH; ++cc)
+      for (int cc = 0; cc < kHeld; ++cc)
         if (cc == c) {
 #pragma unroll
           for (int e = 0; e < kItems; ++e) u[e] = held[cc][e];

@@ -82,10 +82,15 @@ score_deep_kernel(const DeepArgs a) {
   const int ks1 = a.ks[0], dil1 = a.dil[0], cp1 = a.cp[0], c2 = a.cin[0], D = c2 / 2;
   bf16_t* x_lds = lds + a.lds_r1;
   bf16_t* w_lds = x_lds + a.x_rows * XS1;
+  // Descriptors start at the first row this tile reads (the sequence start when the halo reaches before it: those
+  // rows wrap to huge offsets) and end at the last one or at the sequence end: 32-bit byte offsets span one tile.
   const uint32_t row_bytes = (uint32_t)a.st * 2u;
-  const uint32_t seq_bytes = (uint32_t)(n - 1) * row_bytes + (uint32_t)(D * 2);
-  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.k + lo * a.st + (int64_t)h * a.sh), 0, seq_bytes, 0x00020000);
-  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.v + lo * a.st + (int64_t)h * a.sh), 0, seq_bytes, 0x00020000);
+  const int base_row = j0 >= a.h0 ? j0 - a.h0 : 0;
+  const int rows_here = n - base_row < a.x_rows ? n - base_row : a.x_rows;
+  const uint32_t seq_bytes = (uint32_t)(rows_here - 1) * row_bytes + (uint32_t)(D * 2);
+  const int64_t base_el = (lo + base_row) * a.st + (int64_t)h * a.sh;
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.k + base_el), 0, seq_bytes, 0x00020000);
+  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(a.v + base_el), 0, seq_bytes, 0x00020000);
   const uint32_t w1_bytes = (uint32_t)(ks1 * cp1 * c2) * 2u;
   const auto rs_w = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<bf16_t*>(a.panels + a.panel_off[0] + (int64_t)h * a.panel_head[0]), 0, w1_bytes, 0x00020000);
@@ -99,7 +104,7 @@ score_deep_kernel(const DeepArgs a) {
     for (int i = 0; i < kMaxXPieces; ++i) {
       const int p = tid + i * kThreads, r = p >> 2, pc = p & 3;
       // rows before the sequence wrap to huge offsets and rows past its end are beyond the range: both read zeros
-      const uint32_t off = (uint32_t)(j0 - a.h0 + r) * row_bytes + col + (uint32_t)pc * 16u;
+      const uint32_t off = (uint32_t)(j0 - a.h0 + r - base_row) * row_bytes + col + (uint32_t)pc * 16u;
       xreg[i] = from_v ? __builtin_amdgcn_raw_buffer_load_b128(rs_v, off, 0, 0)
                        : __builtin_amdgcn_raw_buffer_load_b128(rs_k, off, 0, 0);
     }
@@ -303,6 +308,7 @@ DeepPlan plan(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   p.TM = kPos - 2 * h1;
   p.x_rows = kPos + 2 * reach1;
   if (p.TM < 32) return p;
+  if (kMaxXPieces * kThreads / 4 > kScoreRowsPerDescriptor) return p;   // rows one workgroup addresses
   if (p.x_rows * (CK / 8) > kMaxXPieces * kThreads) return p;
   if (cnn.kernel[0] * p.cp[0] * (CK / 8) > kMaxWPieces * kThreads) return p;
   // LDS regions (elements): A = activations of layers 1, 3; R1 = layer 1's chunk buffers, then activations of

@@ -104,16 +104,22 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   constexpr int PPH = D == 64 ? 8 : 16;                   // 16-byte pieces of that part per row
   const int t_in = tid % HT, piece = t_in % PPH, r_in = t_in / PPH;   // 16 rows per pass either way
   const bool v_wave = D == 64 && __builtin_amdgcn_readfirstlane(tid / HT) == 1;
+  // The descriptors start at the first row this workgroup reads (the sequence start for the first group, whose
+  // halo rows then wrap to huge offsets) and end at the last one or at the sequence end, so that 32-bit byte
+  // offsets only ever span one group of tiles however long the sequence is.
   const uint32_t row_bytes = (uint32_t)st * 2u;
-  const uint32_t seq_bytes = (uint32_t)(n - 1) * row_bytes + (uint32_t)(D * 2);
-  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k + lo * st + (int64_t)h * sh), 0, seq_bytes, 0x00020000);
-  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v + lo * st + (int64_t)h * sh), 0, seq_bytes, 0x00020000);
+  const int base_row = g0 > 0 ? g0 - rho : 0;
+  const int rows_here = n - base_row < NT * TM + 2 * kMaxRho ? n - base_row : NT * TM + 2 * kMaxRho;
+  const uint32_t seq_bytes = (uint32_t)(rows_here - 1) * row_bytes + (uint32_t)(D * 2);
+  const int64_t base_el = (lo + base_row) * st + (int64_t)h * sh;
+  const auto rs_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(k + base_el), 0, seq_bytes, 0x00020000);
+  const auto rs_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t*>(v + base_el), 0, seq_bytes, 0x00020000);
   const int lds_col = (v_wave ? D : 0) + piece * 8;
   u32x4 xreg[XREG];
   auto load_tokens = [&](int chunk, int tile) {
     const bool is_v = D == 64 ? v_wave : chunk == 1;
     const int j0 = g0 + tile * TM;
-    const uint32_t off0 = (uint32_t)(j0 - rho + r_in) * row_bytes + (uint32_t)piece * 16u;   // wraps for rows < 0
+    const uint32_t off0 = (uint32_t)(j0 - rho + r_in - base_row) * row_bytes + (uint32_t)piece * 16u;   // wraps for rows < 0
 #pragma unroll
     for (int i = 0; i < XREG; ++i) {
       const uint32_t off = off0 + (uint32_t)(i * RPP) * row_bytes;
@@ -234,6 +240,7 @@ bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   if (cfg.dtype != LTEA_BF16 || cnn.n_layers != 1 || cnn.c_out[0] > CP) return false;
   if (cfg.D != 64 && cfg.D != 128) return false;
   if ((cnn.kernel[0] - 1) / 2 * cnn.dilation[0] > kMaxRho) return false;
+  static_assert(NT * TM + 2 * kMaxRho + 16 <= kScoreRowsPerDescriptor, "rows one workgroup addresses");
   return lds_bytes(cnn.kernel[0], cnn.dilation[0]) <= 150 * 1024;
 }
 

@@ -83,6 +83,22 @@ def check_sets(cache, z64: np.ndarray, w, eps: float):
     return near
 
 
+def check_sets_strict(cache, z_gpu: np.ndarray, w):
+    """Level-1 check, no margin: the keep rule of eq. 5 + the cap (Section 3.1.3) applied by the oracle to the
+    device's OWN fp32 logits must give the device's retained set on EVERY (sequence, KV head).  This isolates
+    selection, tie-break and compaction from the scoring arithmetic."""
+    n_heads = 0
+    for s in range(w.n_seqs):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        for h in range(w.Hkv):
+            ref = orc.retain(z_gpu[h, lo:hi], hi - lo, w.window, w.budget, w.sink, w.tau)
+            cnt, pos = gpu_retained_sets(cache, s, h)
+            assert cnt == len(ref) and np.array_equal(np.sort(pos), ref), \
+                f"retained set of seq {s} head {h} differs from the keep rule on the device's own logits"
+            n_heads += 1
+    return n_heads
+
+
 def check_output(got: np.ndarray, ref: np.ndarray, dtype: str, what: str = "output"):
     tol = OUT_TOL[dtype]
     err = float(np.max(np.abs(got.astype(np.float64) - ref)))

@@ -65,7 +65,7 @@ def score_status(cfg, cnn, k=0x1000, v=0x1000, st=128, sh=64, cu=0x1000, n_seqs=
     ("small_stride", B.LTEA_EINVAL), ("odd_stride", B.LTEA_EINVAL), ("misaligned", B.LTEA_EINVAL),
     ("null_logits", B.LTEA_EINVAL), ("no_workspace", B.LTEA_EWORKSPACE), ("neg_total", B.LTEA_EINVAL),
     ("total_gt_cap", B.LTEA_EINVAL), ("bad_dtype", B.LTEA_EINVAL), ("null_weight", B.LTEA_EINVAL),
-    ("misaligned_workspace", B.LTEA_EINVAL),
+    ("misaligned_workspace", B.LTEA_EINVAL), ("huge_token_stride", B.LTEA_EUNSUPPORTED),
 ])
 def test_score_argument_errors(case, expect):
     cfg, cnn, kw = good_cfg(), fake_cnn(), {}
@@ -91,6 +91,7 @@ def test_score_argument_errors(case, expect):
     elif case == "bad_dtype": cfg = good_cfg(); cfg.dtype = 7
     elif case == "null_weight": cnn = fake_cnn(); cnn.w[0] = None
     elif case == "misaligned_workspace": kw = dict(ws=0x1040)         # workspaces are 256-byte aligned
+    elif case == "huge_token_stride": kw = dict(st=1 << 21)           # the matrix-core kernels' 32-bit row offsets
     assert score_status(cfg, cnn, **kw) == expect
 
 
@@ -170,6 +171,9 @@ def test_append_argument_errors():
     assert call(args(ws=None)) == B.LTEA_EWORKSPACE
     assert call(args(ws_bytes=16)) == B.LTEA_EWORKSPACE
     assert call(args(n_seqs=0, total=0, max_new=0)) == B.LTEA_OK          # nothing to do
+    # the packed extended sequences (budget + 2 window + new tokens per sequence) are indexed by int32 prefix sums
+    big = good_cfg(window=1 << 20, budget=1 << 20)
+    assert call(args(cfg=C.byref(big), n_seqs=1000, total=1000, max_new=1)) == B.LTEA_EUNSUPPORTED
     assert L.ltea_append_workspace_bytes(C.byref(cfg), C.byref(cnn), 1, 32, 32) > 0
     assert L.ltea_append_workspace_bytes(None, C.byref(cnn), 1, 32, 32) == 0
     # the rotary form: tables are validated, unrotated keys without tables are refused
@@ -289,15 +293,36 @@ def test_lambda_update_matches_the_oracle():
     """Host-side entry point: runs without a GPU."""
     from oracle import ltea_oracle as orc
     rng = np.random.default_rng(5)
-    lam = np.concatenate([np.array([1e-9, 0.5, 0.9, 2e-9, 0.0, 0.0, 1e-3, 1.5e-9], np.float32),
-                          (10.0 ** rng.uniform(-10, 0.3, size=200)).astype(np.float32)])
+    # the hand-set entries reach the oracle as the decimal values (2e-9 halves to exactly the floor 1e-9 and stays);
+    # the library sees their fp32 images
+    lam64 = np.concatenate([np.array([1e-9, 0.5, 0.9, 2e-9, 0.0, 0.0, 1e-3, 1.5e-9]),
+                            (10.0 ** rng.uniform(-10, 0.3, size=200)).astype(np.float32).astype(np.float64)])
+    lam = lam64.astype(np.float32)
     cbar = np.concatenate([np.array([600, 600, 600, 100, 600, 100, 500, 10], np.float32),
                            rng.uniform(300, 700, size=200).astype(np.float32)])
-    ref = orc.lambda_update(lam.astype(np.float64), cbar.astype(np.float64), 512.0, 2.0)
+    ref = orc.lambda_update(lam64, cbar.astype(np.float64), 512.0, 2.0)
     got = B.ltea_lambda_update(lam.copy(), cbar, 512.0, 2.0)
     np.testing.assert_allclose(got, ref, rtol=1e-6, atol=0)
     assert np.array_equal(got == 0, ref == 0)
     assert (ref == 0).sum() > 3 and (ref == 1.0).sum() > 3 and (ref == 1e-9).sum() >= 1
+
+
+def test_lambda_update_keeps_the_floor_inside_the_dead_band():
+    """Algorithm 1 starts and restarts the multiplier at 1e-9 and zeroes it only below that.  Stored in fp32 the
+    floor is 9.9999997e-10; a head at the floor whose count lies between 95 % of the cap and the cap must stay
+    there (the oracle, given the decimal 1e-9, leaves it), also over repeated updates, and still restart from zero."""
+    from oracle import ltea_oracle as orc
+    lam = np.array([1e-9, 1e-9, 0.0, 1e-9], np.float32)
+    cbar = np.array([500.0, 490.0, 600.0, 100.0], np.float32)          # dead band, dead band, overshoot, undershoot
+    ref = orc.lambda_update(np.array([1e-9, 1e-9, 0.0, 1e-9]), cbar.astype(np.float64), 512.0, 2.0)
+    got = lam.copy()
+    for _ in range(3):
+        got = B.ltea_lambda_update(got, np.array([500.0, 490.0, 500.0, 500.0], np.float32) if _ else cbar, 512.0, 2.0)
+        if _ == 0:
+            np.testing.assert_array_equal(got, ref.astype(np.float32))
+    assert got[0] == np.float32(1e-9) and got[1] == np.float32(1e-9)    # never flushed
+    assert got[2] == np.float32(1e-9)                                   # restarted once, then held in the dead band
+    assert got[3] == 0.0                                                # shrunk below the floor: flushed
 
 
 def test_train_argument_errors():

@@ -248,6 +248,20 @@ def test_p8_paper_stack_receptive_field():
     assert set(changed) >= {20 - cnn.rho, 20, 20 + cnn.rho}
 
 
+def test_lazy_period_of_the_paper_shape_against_the_printed_cadence():
+    """Section 3.1.3 (lazy scoring) prints one batched scoring per w - R steps; for the paper's w = 768, R = 13 that is
+    755.  The reading taken here (scoring is due when the next token would overwrite the left context of the oldest
+    unscored position) allows one step more, w - 2*rho = w - R + 1 = 756; the difference is the paper counting the
+    step that triggers the scoring."""
+    with open(os.path.join(GOLDEN, "paper_hyperparameters.json")) as f:
+        hp = json.load(f)
+    ks, dil = hp["lte_cnn"]["kernel"], hp["lte_cnn"]["dilation"]
+    cnn = orc.cnn_from_arrays(ks, dil, [np.zeros((1, 2, 2, k)) for k in ks], [np.zeros((1, 2))] * 3, np.zeros((1, 2)), np.zeros(1))
+    cfg = orc.OracleCfg(1, 1, 1, hp["window"]["w"], hp["budget"]["b"], hp["sink"]["s"], hp["threshold"]["logit"])
+    assert hp["window"]["w"] - hp["lte_cnn"]["receptive_field"] == hp["lazy_scoring_period"]["steps"]
+    assert orc.lazy_period(cfg, cnn) == hp["lazy_scoring_period"]["steps"] + 1
+
+
 # ---- P9: closed forms of the softmax ----------------------------------------------------------
 def test_p9_softmax_closed_forms():
     n, window, D = 30, 6, 4
