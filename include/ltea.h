@@ -10,7 +10,8 @@
  * retained set.
  *
  * General rules of this boundary
- *   - plain C: no C++ types, no exceptions, no global state; reentrant.
+ *   - plain C: no C++ types, no exceptions, no global state; reentrant
+ *     (one documented exception: ltea_decode_step_static).
  *   - every pointer that is not a pointer to one of the config structs below is
  *     a DEVICE pointer, allocated, owned and freed by the caller.  The config
  *     structs themselves (ltea_cfg, ltea_cnn, ltea_cache) live in HOST memory
@@ -205,6 +206,20 @@ int ltea_prefill_feat(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, i
 int ltea_decode_step(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
                      void *out, const ltea_cache *cache, int32_t n_seqs, void *workspace, size_t workspace_bytes,
                      void *stream);
+
+/* ltea_decode_step for callers that cannot allocate device memory or pass a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * ltea_decode_step, minus the workspace: the step's scratch (split partials, finalised logits, step indices) is a
+ * fixed device array of LTEA_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the process
+ * ends.  This is the one entry point with state of its own, so unlike the rest of the boundary it is not
+ * reentrant: every call on a GPU shares that GPU's array, and calls that overlap in time on one GPU (different
+ * streams or threads) race.  Nothing is carried from one call to the next.  Calls no hipMalloc, hipFree or other
+ * allocating routine; the first call on a device looks the array's device address up once.
+ * Returns LTEA_EWORKSPACE, before anything is launched, when ltea_decode_workspace_bytes(cfg, cnn, n_seqs) exceeds
+ * LTEA_STATIC_SCRATCH_BYTES (decode_bf16's 64 sequences x 16 heads x D = 128 need about 2.2 MB). */
+#define LTEA_STATIC_SCRATCH_BYTES (8u << 20)
+int ltea_decode_step_static(const ltea_cfg *cfg, const ltea_cnn *cnn, const void *q, const void *k, const void *v,
+                            void *out, const ltea_cache *cache, int32_t n_seqs, void *stream);
 
 /* Continues a prefill on an existing cache state (the chunked / multi-token form of (a)+(b)+(c)): sequence s of
  * `cache` holds n_seen[s] tokens (from ltea_prefill, ltea_decode_step or an earlier call of this function) and

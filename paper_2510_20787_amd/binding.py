@@ -60,7 +60,8 @@ class ltea_rope(C.Structure):
 
 
 EXPORTS = ["ltea_strerror", "ltea_cnn_panels_bytes", "ltea_cnn_prepare", "ltea_workspace_bytes", "ltea_decode_workspace_bytes", "ltea_score", "ltea_retain",
-           "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_append_workspace_bytes",
+           "ltea_sparse_attention", "ltea_prefill", "ltea_prefill_feat", "ltea_decode_step", "ltea_decode_step_static",
+           "ltea_append_workspace_bytes",
            "ltea_prefill_append", "ltea_prefill_append_feat", "ltea_decode_feat_workspace_bytes",
            "ltea_decode_step_feat", "ltea_cnn_backward_workspace_bytes", "ltea_cnn_backward", "ltea_lazy_period", "ltea_rescore_workspace_bytes", "ltea_rescore",
            "ltea_decode_step_lazy", "ltea_train_workspace_bytes", "ltea_train_forward", "ltea_train_backward",
@@ -106,6 +107,8 @@ def lib() -> C.CDLL:
                                     P(ltea_cache), vp, vp, sz, vp]
     L.ltea_decode_step.restype = C.c_int
     L.ltea_decode_step.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp, sz, vp]
+    L.ltea_decode_step_static.restype = C.c_int
+    L.ltea_decode_step_static.argtypes = [P(ltea_cfg), P(ltea_cnn), vp, vp, vp, vp, P(ltea_cache), i32, vp]
     L.ltea_append_workspace_bytes.restype = sz
     L.ltea_append_workspace_bytes.argtypes = [P(ltea_cfg), P(ltea_cnn), i32, i64, i32]
     L.ltea_prefill_append.restype = C.c_int
@@ -397,6 +400,15 @@ def ltea_decode_step(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, 
     _check(lib().ltea_decode_step(C.byref(cfg), C.byref(cnn.struct), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
                                   C.byref(cache.struct), B, _ptr(workspace), workspace.numel(), _stream()),
            "ltea_decode_step")
+    return out
+
+
+def ltea_decode_step_static(cfg: ltea_cfg, cnn: Cnn, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cache: Cache,
+                            out: torch.Tensor) -> torch.Tensor:
+    """The decode step on the library's own fixed scratch.  `out` is the caller's: nothing is allocated here."""
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    _check(lib().ltea_decode_step_static(C.byref(cfg), C.byref(cnn.struct), _ptr(q), _ptr(k), _ptr(v), _ptr(out),
+                                         C.byref(cache.struct), q.shape[0], _stream()), "ltea_decode_step_static")
     return out
 
 

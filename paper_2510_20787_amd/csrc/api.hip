@@ -5,6 +5,8 @@
 
 #include <limits.h>
 
+#include <atomic>
+
 #include "ltea_kernels.h"
 #include "train_common.h"
 
@@ -163,7 +165,7 @@ const char* ltea_strerror(int status) {
     case LTEA_OK: return "ok";
     case LTEA_EINVAL: return "invalid argument (null pointer, size, stride, alignment or inconsistent config)";
     case LTEA_EUNSUPPORTED: return "configuration not supported by the gfx950 kernels";
-    case LTEA_EWORKSPACE: return "workspace missing or too small";
+    case LTEA_EWORKSPACE: return "workspace missing or too small (or the request exceeds the fixed scratch of a *_static entry point)";
     case LTEA_EHIP: return "HIP runtime rejected a kernel launch";
     default: return "unknown ltea status";
   }
@@ -414,6 +416,50 @@ int ltea_decode_step(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, co
   if (workspace && !aligned256(workspace)) return LTEA_EINVAL;
   return hip_status(launch_decode_step(*cfg, *cnn, q, k, v, out, *cache, n_seqs, workspace, workspace_bytes,
                                        static_cast<hipStream_t>(stream)));
+}
+
+// ---- the decode step for callers that cannot allocate ----------------------------------------------------------
+// Its scratch (split partials, finalised logits, step indices: everything ltea_decode_step carves from a caller
+// workspace) lives in a file-scope device array.  Host code never passes the array's name to a kernel: the name is a
+// host-side stand-in, the device address comes from hipGetSymbolAddress, looked up once per device (each GPU holds
+// its own copy at its own address) with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[LTEA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device; nullptr (and *err set) if the runtime refuses.
+void* static_scratch(hipError_t* err) {
+  int dev = -1;
+  *err = hipGetDevice(&dev);
+  if (*err != hipSuccess) return nullptr;
+  if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (*err != hipSuccess) return nullptr;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // racing first calls store the same address
+  }
+  return p;
+}
+}  // namespace
+
+int ltea_decode_step_static(const ltea_cfg* cfg, const ltea_cnn* cnn, const void* q, const void* k, const void* v,
+                            void* out, const ltea_cache* cache, int32_t n_seqs, void* stream) {
+  int st = check_cfg(cfg);
+  if (st == LTEA_OK) st = check_cnn(cfg, cnn);
+  if (st != LTEA_OK) return st;
+  if (n_seqs < 0) return LTEA_EINVAL;
+  // beyond the fixed scratch: refused here, before anything is looked up or launched
+  if (ltea_decode_workspace_bytes(cfg, cnn, n_seqs) > (size_t)LTEA_STATIC_SCRATCH_BYTES) return LTEA_EWORKSPACE;
+  if (n_seqs == 0) return ltea_decode_step(cfg, cnn, q, k, v, out, cache, 0, nullptr, 0, stream);
+  hipError_t e = hipSuccess;
+  void* ws = static_scratch(&e);
+  if (ws == nullptr) return LTEA_EHIP;
+  // nothing in the scratch has to start at zero: every part is written by the step's first launch before its
+  // second launch reads it
+  return ltea_decode_step(cfg, cnn, q, k, v, out, cache, n_seqs, ws, (size_t)LTEA_STATIC_SCRATCH_BYTES, stream);
 }
 
 size_t ltea_decode_feat_workspace_bytes(const ltea_cfg* cfg, const ltea_cnn* cnn, int32_t n_seqs) {
