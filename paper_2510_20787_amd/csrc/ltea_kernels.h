@@ -25,7 +25,7 @@ inline int cnn_rho(const ltea_cnn* c) {
 // The matrix-core scoring kernels address the K/V rows of one workgroup (a group of token tiles plus halo, never
 // more than this many rows) with 32-bit byte offsets from a 64-bit base of their own, so a sequence may be of any
 // length; only the token stride is bounded.
-constexpr int kScoreRowsPerDescriptor = 1024;
+constexpr int kScoreRowsPerDescriptor = 2304;
 inline bool score_stride_ok(int64_t stride_tok) {
   return stride_tok * 2 * kScoreRowsPerDescriptor < ((int64_t)1 << 31);
 }
@@ -43,6 +43,15 @@ hipError_t launch_score_mfma_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, vo
 hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
                              void* workspace, hipStream_t stream);
+
+// The same layer with the weights held in registers and the tokens loaded straight into LDS (D = 64, kernel 3 or 5).
+// Its panels have the same size but are ordered as the registers hold them; launch_score_mfma and
+// launch_score_mfma_panels hand over to these where they apply.
+bool score_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
+hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t stride_tok,
+                            int64_t stride_head, const SeqView& sv, float* logits, const void* panels,
+                            hipStream_t stream);
 
 // Multi-layer bf16 path on MFMA (all layers fused, activations in LDS as hi + lo bf16 pairs); the workspace holds
 // every layer's weights re-laid as tap-major panels.

@@ -62,8 +62,9 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   constexpr int XREG = (TM + 2 * kMaxRho + RPP - 1) / RPP;   // staging passes (registers) per tile
   extern __shared__ __align__(16) unsigned char smem[];
   const int half = (ks - 1) / 2, rho = half * dil;
+  const int tile_rows = TM + 2 * rho;              // rows of the token tile actually used (at most kTileRows)
   bf16_t* x_lds = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* w_lds = x_lds + (size_t)kTileRows * XS;  // ks panels of CP x XS (all taps of the current chunk)
+  bf16_t* w_lds = x_lds + (size_t)tile_rows * XS;  // ks panels of CP x XS (all taps of the current chunk)
 
   const int h = blockIdx.y;
   int grp, s, n, lo32;
@@ -130,7 +131,7 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   auto store_tokens = [&]() {
 #pragma unroll
     for (int i = 0; i < XREG; ++i)
-      if ((i + 1) * RPP <= kTileRows || r_in + i * RPP < kTileRows)   // only the last pass can be partial
+      if (r_in + i * RPP < tile_rows)   // the token tile ends where the weight panels begin
         *reinterpret_cast<u32x4*>(&x_lds[(r_in + i * RPP) * XS + lds_col]) = xreg[i];
   };
 
@@ -204,10 +205,10 @@ score_mfma_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, in
   }
 }
 
+// Token tile sized by the actual reach: 79.4 KB for kernel 5 / dilation 1, so that two workgroups share a CU.
 size_t lds_bytes(int ks, int dil) {
   const int rho = (ks - 1) / 2 * dil;
-  (void)rho;
-  return ((size_t)kTileRows + (size_t)ks * CP) * XS * sizeof(uint16_t);
+  return ((size_t)(TM + 2 * rho) + (size_t)ks * CP) * XS * sizeof(uint16_t);
 }
 
 template <int D>
@@ -221,6 +222,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
     if (e != hipSuccess) return e;
     panels = workspace;
   }
+  if (score_reg_supported(cfg, cnn)) return launch_score_reg(cfg, cnn, k, v, st, sh, sv, logits, panels, stream);
   const size_t lds = lds_bytes(ks, cnn.dilation[0]);
   e = hipFuncSetAttribute(reinterpret_cast<const void*>(&score_mfma_kernel<D>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -245,6 +247,7 @@ bool score_mfma_supported(const ltea_cfg& cfg, const ltea_cnn& cnn) {
 }
 
 hipError_t launch_score_mfma_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream) {
+  if (score_reg_supported(cfg, cnn)) return launch_score_reg_panels(cfg, cnn, panels, stream);   // its own order, same size
   const int ks = cnn.kernel[0], C2 = 2 * cfg.D;
   const int64_t panel_elems = (int64_t)cfg.Hkv * ks * CP * C2;
   hipLaunchKernelGGL(score_weight_panels_kernel, dim3((unsigned)((panel_elems + 255) / 256)), dim3(256), 0, stream,

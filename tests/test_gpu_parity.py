@@ -70,6 +70,18 @@ def test_score(name):
     logit_eps(zg, z64, w.dtype)
 
 
+@pytest.mark.parametrize("kernel,dilation", [((5,), None), ((3,), (2,))])
+def test_score_long_groups_of_tiles(kernel, dilation):
+    """Enough tiles per head that a workgroup of the register-stationary kernel takes its maximum of 16 in a row,
+    with a ragged end of the first sequence and a second one that ends inside a group."""
+    w = wl.make_prefill("long_groups", 77, "bf16", [20000 + 77, 12800 + 5], 16, 16, 64, 64, 16, 0, 0.0,
+                        cnn_kernel=kernel, cnn_channels=(32,), cnn_dilation=dilation, qkv_scale=0.125, w_std=0.05)
+    z64 = orc.score(w.k, w.v, oracle_cnn(w.cnn), w.cu_seqlens)
+    d = DeviceWorkload(w)
+    zg = to_np(B.ltea_score(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen))
+    logit_eps(zg, z64, w.dtype)
+
+
 def test_score_strided_views():
     """K and V as strided views of one packed [T, 3, H, D] buffer."""
     w, cfg, cnn, (out, states, z64, kept) = oracle_prefill("bf16_d64")
