@@ -8,13 +8,16 @@ H=16, D=64, window 512, budget 256, CNN width 5 / 32 channels): ltea_prefill (sc
 retention + cache fill -> window + retained attention) followed by one ltea_decode_step that continues
 every sequence by one token on the cache just produced.  Inputs are synthetic, seeded, and resident in HBM
 before the timed region; four rotating copies of the inputs keep the 256 MB Infinity Cache from standing
-in for HBM.  `value` = tokens (prefill + decoded) per second over exactly K timed steps.
+in for HBM.  `value` = tokens (prefill + decoded) per second over blocks of exactly K timed steps, each between two
+synchronizations, repeated until 100 ms are timed (`timing` holds the block and per-step-event minima and medians).
 
 Also reported on the same JSON line:
   roofline      the dominant kernel of the step (the prefill attention kernel) against the bf16 MFMA peak:
                 algorithmic FLOPs (4*D per unmasked query-key pair, counted from the actual retained sets)
                 / its average duration measured with HIP events on the launch stream in an instrumented
                 repeat of the same steps (entry points called one by one).
+  configs       the long_prefill_bf16, varlen_prefill_bf16 and paper_stack_bf16 configurations through the same
+                step, each with its own attention and scoring roofline objects (fewer steps; --no-other-configs skips).
   decode        the decode_bf16 workload (B=64, H=16, D=128, window 1024 + 512 retained, n_seen 8192):
                 256 consecutive steps timed as a whole; us/step, us/token, and the streaming attention
                 kernel's achieved HBM bandwidth; `lazy`: the same steps without per-step scoring plus one
@@ -92,19 +95,60 @@ def attention_pairs(w, ret_pos, ret_count):
     return pairs
 
 
-def bench_prefill(args):
+TRAFFIC_SOURCE = ("profiles/traffic_per_launch.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, scaled by "
+                  "a plain copy of known size, committed with the sources; not measured in this run")
+
+
+def timed_blocks(step, steps, warmup, min_region_ms):
+    """`warmup` untimed steps, then blocks of exactly `steps` steps, each bracketed by a synchronize on both sides,
+    repeated until the blocks add up to `min_region_ms` (a single block of a 0.15 ms step is shorter than the noise of
+    its own two synchronizations).  Returns (mean ms per step over all blocks, ms per step of every block, steps run)."""
+    import torch
+    for i in range(warmup):
+        step(i)
+    blocks, total, n = [], 0.0, 0
+    while not blocks or total < min_region_ms:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(n + i)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) * 1e3
+        blocks.append(dt / steps)
+        total += dt
+        n += steps
+    return total / n, blocks, n
+
+
+def per_step_events(step, steps):
+    """Every step between two events of its own on the launch stream: (median, min) ms."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i, (a, b) in enumerate(evs):
+        a.record()
+        step(i)
+        b.record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in evs)
+    return ts[len(ts) // 2], ts[0]
+
+
+def bench_prefill(workload, steps, warmup, min_region_ms=100.0):
     import torch
     from paper_2510_20787_amd import binding as B
     from paper_2510_20787_amd import workloads as wl
 
     w = {"prefill": wl.config_prefill_bf16, "long": wl.config_long_prefill_bf16,
-         "varlen": wl.config_varlen_prefill_bf16, "paper": wl.config_paper_stack_bf16}[args.workload]()
+         "varlen": wl.config_varlen_prefill_bf16, "paper": wl.config_paper_stack_bf16}[workload]()
     cfg = B.make_cfg(w.Hq, w.Hkv, w.D, w.window, w.budget, w.sink, w.tau, 0.0, w.dtype)
     c = w.cnn
     cnn = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
     cu = torch.from_numpy(w.cu_seqlens).cuda()
     T, nB = w.total_tokens, w.n_seqs
-    n_copies = 4 if args.workload == "prefill" else 1   # the larger workloads exceed the Infinity Cache on their own
+    # rotating copies of the inputs keep the 256 MB Infinity Cache from standing in for HBM; the larger workloads
+    # exceed it on their own
+    in_bytes = (w.q.size + w.k.size + w.v.size) * 2
+    n_copies = max(1, min(4, int(np.ceil(300e6 / in_bytes))))
     sets = []
     for _ in range(n_copies):
         sets.append(dict(q=up(w.q, w.dtype), k=up(w.k, w.dtype), v=up(w.v, w.dtype),
@@ -122,15 +166,8 @@ def bench_prefill(args):
         B.ltea_prefill(cfg, cnn, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"], workspace=ws)
         B.ltea_decode_step(cfg, cnn, dq, dk, dv, s["cache"], out=dout, workspace=dws)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step, blocks, timed_steps = timed_blocks(step, steps, warmup, min_region_ms)
+    step_median, step_min = per_step_events(step, steps)
     tokens_per_step = T + nB
     value = tokens_per_step / (ms_per_step * 1e-3)
 
@@ -143,20 +180,13 @@ def bench_prefill(args):
         B.ltea_prefill(cfg, cnn_once, s["q"], s["k"], s["v"], cu, w.max_seqlen, s["cache"], out=s["out"], workspace=ws)
         B.ltea_decode_step(cfg, cnn_once, dq, dk, dv, s["cache"], out=dout, workspace=dws)
 
-    for i in range(args.warmup):
-        step_prepared(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step_prepared(i)
-    torch.cuda.synchronize()
-    prepared_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    prepared_ms, _, _ = timed_blocks(step_prepared, steps, warmup, min_region_ms)
 
     # instrumented repeat: same work, entry points one by one, HIP events on the launch stream
     names = ["score", "retain", "attention", "decode_step"]
-    acc = {n: 0.0 for n in names}
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
-    for i in range(args.steps):
+    per = {n: [] for n in names}
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)]
+    for i in range(steps):
         s = sets[i % n_copies]
         e = evs[i]
         e[0].record()
@@ -171,8 +201,9 @@ def bench_prefill(args):
     torch.cuda.synchronize()
     for e in evs:
         for j, n in enumerate(names):
-            acc[n] += e[j].elapsed_time(e[j + 1])
-    kern_ms = {n: acc[n] / args.steps for n in names}
+            per[n].append(e[j].elapsed_time(e[j + 1]))
+    kern_ms = {n: float(np.mean(per[n])) for n in names}
+    kern_min_ms = {n: float(np.min(per[n])) for n in names}
 
     # algorithmic work of the attention kernel from the actual retained sets (after a clean prefill)
     s = sets[0]
@@ -182,16 +213,26 @@ def bench_prefill(args):
     flops = 4.0 * w.D * pairs
     achieved = flops / (kern_ms["attention"] * 1e-3) / 1e12
     score_bytes = 2 * T * w.Hkv * w.D * 2 + 4 * T * w.Hkv
+    traffic = measured_traffic(w.name, "attention_mfma_kernel")
     res = dict(value=value, ms_per_step=ms_per_step, tokens_per_step=tokens_per_step, kern_ms=kern_ms,
-               prepared_ms=prepared_ms,
+               kern_min_ms=kern_min_ms, prepared_ms=prepared_ms, input_copies=n_copies,
+               timing=dict(timed_steps=timed_steps, blocks=len(blocks), block_ms_per_step_min=min(blocks),
+                           block_ms_per_step_median=float(np.median(blocks)), step_event_ms_median=step_median,
+                           step_event_ms_min=step_min,
+                           note=f"`steps` steps per block between two synchronizations, blocks repeated until {min_region_ms:.0f} ms "
+                                "are timed; ms_per_step and value are the mean over all of them; the step_event figures "
+                                "bracket every step of one more block with HIP events of its own"),
                roofline=dict(bound="mfma", kernel="prefill attention (window + retained)", achieved=achieved,
                              peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=achieved / PEAK_BF16_TFLOPS,
-                             traffic=measured_traffic("prefill_bf16", "attention_mfma_kernel") if args.workload == "prefill" else None,
-                             algorithmic_flops=flops, avg_ms=kern_ms["attention"]),
+                             traffic=traffic, traffic_source=TRAFFIC_SOURCE if traffic is not None else None,
+                             algorithmic_flops=flops, avg_ms=kern_ms["attention"], min_ms=kern_min_ms["attention"]),
                scoring=dict(bound="hbm", achieved=score_bytes / (kern_ms["score"] * 1e-3) / 1e9, peak=PEAK_HBM_GBS,
                             unit="GB/s", frac=score_bytes / (kern_ms["score"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                            avg_ms=kern_ms["score"], algorithmic_bytes=score_bytes),
+                            avg_ms=kern_ms["score"], min_ms=kern_min_ms["score"], algorithmic_bytes=score_bytes,
+                            note="ltea_score as the step calls it: weight re-layout + scoring kernel(s)"),
                workload=w)
+    del sets
+    torch.cuda.empty_cache()
     return res
 
 
@@ -359,7 +400,8 @@ def bench_train(args):
         if it > 0:
             fwd_ms += ev[0].elapsed_time(ev[1]) / reps
             bwd_ms += ev[1].elapsed_time(ev[2]) / reps
-    # the scoring CNN's own backward on the d logits just produced (fp32 VALU kernels; not part of tokens_per_s)
+    # the scoring CNN's own backward on the d logits just produced (fp32-accurate products on the fp32 matrix
+    # instruction or, with the fp32 operand split into three bf16 terms, on the bf16 one; not part of tokens_per_s)
     cws = torch.empty(int(B.lib().ltea_cnn_backward_workspace_bytes(B.C.byref(cfg), B.C.byref(cnn.struct), w.total_tokens)),
                       dtype=torch.uint8, device="cuda")
     B.ltea_cnn_backward(cfg, cnn, k, v, cu, w.max_seqlen, grads[3], workspace=cws)
@@ -650,6 +692,8 @@ def main():
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--train", action="store_true", help="(default) also time the training-side forward + backward")
     ap.add_argument("--no-train", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the long / varlen / paper prefill configurations that the default run reports under `configs`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device-to-device copies (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -682,8 +726,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    pre = bench_prefill(args)
-    log(f"[bench] prefill step {pre['ms_per_step']:.3f} ms; kernels (ms): {pre['kern_ms']}")
+    pre = bench_prefill(args.workload, args.steps, args.warmup)
+    log(f"[bench] {args.workload} step {pre['ms_per_step']:.3f} ms over {pre['timing']['timed_steps']} steps; kernels (ms): {pre['kern_ms']}")
     w = pre.pop("workload")
     line = {
         "metric": "SWA+LTE prefill tokens/s (scoring + retention + attention + one decode step per sequence)",
@@ -691,9 +735,14 @@ def main():
         "ms_per_step": pre["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload],
-                   "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": 4 if args.workload == "prefill" else 1},
+                   "tokens_per_step": pre["tokens_per_step"], "input_copies_rotated": pre["input_copies"]},
+        "timing": pre["timing"],
         "roofline": pre["roofline"],
         "kernel_ms": pre["kern_ms"],
+        "kernel_min_ms": pre["kern_min_ms"],
+        "kernel_ms_note": "the four entry points called one by one with an event between them; their sum exceeds "
+                          "ms_per_step because ltea_prefill enqueues the same kernels without the host gaps between "
+                          "separate calls",
         "prepared_cnn": {"ms_per_step": pre["prepared_ms"], "tokens_per_s": pre["tokens_per_step"] / (pre["prepared_ms"] * 1e-3),
                          "note": "same steps with the conv weights re-laid once by ltea_cnn_prepare instead of on every call"},
         "scoring_roofline": pre["scoring"],
@@ -703,6 +752,22 @@ def main():
     line["ceilings"] = ceilings
     add_measured_fraction(line["roofline"], ceilings)
     add_measured_fraction(line["scoring_roofline"], ceilings)
+    if args.workload == "prefill" and not args.no_other_configs:
+        # the other prefill configurations, fewer steps each: the same step, the same two roofline objects
+        line["configs"] = {}
+        for name in ("long", "varlen", "paper"):
+            o = bench_prefill(name, max(5, args.steps // 5), 3, min_region_ms=50.0)
+            ow = o.pop("workload")
+            add_measured_fraction(o["roofline"], ceilings)
+            add_measured_fraction(o["scoring"], ceilings)
+            line["configs"][ow.name] = {
+                "workload": WORKLOAD_TEXT[name], "tokens_per_step": o["tokens_per_step"], "value": o["value"],
+                "unit": "tokens/s", "ms_per_step": o["ms_per_step"], "timing": o["timing"], "kernel_ms": o["kern_ms"],
+                "kernel_min_ms": o["kern_min_ms"], "prepared_cnn_ms_per_step": o["prepared_ms"],
+                "roofline": o["roofline"], "scoring_roofline": o["scoring"]}
+            log(f"[bench] {ow.name}: step {o['ms_per_step']:.3f} ms; kernels (ms): {o['kern_ms']}; attention "
+                f"{o['roofline']['frac']:.3f} of MFMA peak, scoring {o['scoring']['frac']:.3f} of HBM peak")
+            del ow, o
     if not args.no_decode:
         dec = bench_decode(args)
         log(f"[bench] decode {dec['us_per_step']:.1f} us/step ({dec['graph_us_per_step']:.1f} replayed from a graph); lazy {dec['lazy']['us_per_step']:.1f} us/step + "

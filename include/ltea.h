@@ -360,8 +360,9 @@ int ltea_train_backward(const ltea_cfg *cfg, const void *q, int64_t q_stride_tok
  * all sequences, fp32, fixed order).  dk_feat_or_null / dv_or_null: contiguous [total_tokens][Hkv][D] of cfg->dtype,
  * the gradient that reaches the scored keys and the values through the CNN (to be added to the attention's dk / dv
  * by a caller that trains them through this path too).  k_feat, v, cu_seqlens: as given to ltea_score /
- * ltea_train_forward (k_feat = the keys the CNN scores).  cnn->panels is not used.  Plain fp32 arithmetic for every
- * CNN shape and storage type. */
+ * ltea_train_forward (k_feat = the keys the CNN scores).  cnn->panels is not used.  fp32-accurate arithmetic for every
+ * CNN shape and storage type: products on the fp32 matrix instruction, or, on bf16 storage where one operand is a
+ * bf16 value, on the bf16 one with the fp32 operand split into three bf16 terms. */
 typedef struct ltea_cnn_grad {
   float *w[LTEA_MAX_CNN_LAYERS];
   float *bias[LTEA_MAX_CNN_LAYERS];
