@@ -55,6 +55,14 @@ hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void
 
 // Multi-layer bf16 path on MFMA (all layers fused, activations in LDS as hi + lo bf16 pairs); the workspace holds
 // every layer's weights re-laid as tap-major panels.
+// The paper's own stack (D = 64, three kernel-3 layers of 64 / 32 / 16 channels) with every layer's weights held in
+// registers and the tokens loaded straight into LDS; its panels have the size of the general kernel's but are ordered
+// as the registers hold them.  launch_score_deep and launch_score_deep_panels hand over to these where they apply.
+bool score_deep_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+hipError_t launch_score_deep_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
+hipError_t launch_score_deep_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
+                                 int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
+                                 const void* panels, hipStream_t stream);
 bool score_deep_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
 size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
 hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);

@@ -344,6 +344,7 @@ size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn) {
 hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream) {
   const DeepPlan p = plan(cfg, cnn);
   if (!p.ok) return hipErrorInvalidValue;
+  if (score_deep_reg_supported(cfg, cnn)) return launch_score_deep_reg_panels(cfg, cnn, panels, stream);   // same size
   int cin = 2 * cfg.D;
   PanelArgs pa;
   int64_t most = 0;
@@ -371,6 +372,7 @@ hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
     if (e != hipSuccess) return e;
     panels = workspace;
   }
+  if (score_deep_reg_supported(cfg, cnn)) return launch_score_deep_reg(cfg, cnn, k, v, st, sh, sv, logits, panels, stream);
   DeepArgs a;
   a.k = static_cast<const bf16_t*>(k); a.v = static_cast<const bf16_t*>(v); a.st = st; a.sh = sh;
   a.panels = static_cast<const bf16_t*>(panels);

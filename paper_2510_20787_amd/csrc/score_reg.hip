@@ -23,6 +23,7 @@
 // the tile loads, which a fixed s_waitcnt vmcnt(N) can then tell apart.
 #include "ltea_common.h"
 #include "ltea_kernels.h"
+#include "score_dma.h"
 
 namespace ltea {
 namespace {
@@ -40,29 +41,6 @@ constexpr int kMaxGroupTiles = 16;
 constexpr int kInstrPerArray = (kRowsMax + 7) / 8;                 // wave instructions that cover one array: 17
 constexpr int kLdsB = kBufs * kBufB + kMaxGroupTiles * TM * 4;     // 144 KB: the workgroup's logits behind the buffers
 constexpr int kLoadsPerWave = 2 * ((kInstrPerArray + 3) / 4);      // per tile and wave, keys + values: 10
-
-// 16 bytes per lane from a buffer straight into LDS: lane l's piece lands at lds_addr + 16 * l.
-__device__ __forceinline__ void dma16(u32x4 rsrc, uint32_t lds_addr, uint32_t voff) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory");
-}
-// s_waitcnt vmcnt(0) through the builtin, so that the compiler's own wait-count bookkeeping sees it (it cannot see
-// into the asm statement above).
-__device__ __forceinline__ void wait_loads() {
-  __builtin_amdgcn_s_waitcnt(0x0F70);
-  asm volatile("" ::: "memory");
-}
-// s_waitcnt vmcnt(N) for the two depths the pipeline needs besides 0 (the immediate has to be a constant; the other
-// counters stay at their maxima = not waited for; vmcnt's upper two bits sit in bits 15:14)
-template <int N> __device__ __forceinline__ void wait_loads_but() {
-  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
-  asm volatile("" ::: "memory");
-}
-
-// y * sigmoid(y) with the hardware's exp2 and reciprocal (1 ulp each)
-__device__ __forceinline__ float silu(float y) {
-  return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * y));
-}
 
 template <int KS>
 __global__ void __launch_bounds__(kThreads, 1)
@@ -111,16 +89,8 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
   const int base_row = g0 > 0 ? g0 - rho : 0;
   const int rows_here = n - base_row < kMaxGroupTiles * TM + 2 * kMaxRho ? n - base_row : kMaxGroupTiles * TM + 2 * kMaxRho;
   const uint32_t span = (uint32_t)(rows_here - 1) * row_bytes + (uint32_t)(D * 2);
-  auto make_rsrc = [&](const bf16_t* p) {
-    const uint64_t a = reinterpret_cast<uint64_t>(p + (lo + base_row) * st + (int64_t)h * sh);
-    u32x4 r;
-    r[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
-    r[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xFFFFu);
-    r[2] = __builtin_amdgcn_readfirstlane(span);
-    r[3] = 0x00020000u;
-    return r;
-  };
-  const u32x4 rs_k = make_rsrc(k), rs_v = make_rsrc(v);
+  const u32x4 rs_k = make_raw_rsrc(k + (lo + base_row) * st + (int64_t)h * sh, span);
+  const u32x4 rs_v = make_raw_rsrc(v + (lo + base_row) * st + (int64_t)h * sh, span);
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
   // A wave instruction covers 8 rows of one array (8 pieces each); instruction j = wv + 4*i covers rows 8j .. 8j+7.
   // Row r keeps piece p in slot p ^ ((r >> 1) & 7): 16 consecutive rows read together then cover all 64 banks.
@@ -144,12 +114,7 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
   };
   // The head's weight panels (KS * 8 KB, already in register order [tap][slice][lane][8]) go through LDS as well, once
   // per workgroup: into the fourth tile buffer and the logit area behind it, both idle until the first tile is done.
-  const uint64_t pa = reinterpret_cast<uint64_t>(panels + (int64_t)h * KS * NSL * kWave * 8);
-  u32x4 rs_w;
-  rs_w[0] = __builtin_amdgcn_readfirstlane((uint32_t)pa);
-  rs_w[1] = __builtin_amdgcn_readfirstlane((uint32_t)(pa >> 32) & 0xFFFFu);
-  rs_w[2] = (uint32_t)(KS * NSL * 1024);
-  rs_w[3] = 0x00020000u;
+  const u32x4 rs_w = make_raw_rsrc(panels + (int64_t)h * KS * NSL * kWave * 8, (uint32_t)(KS * NSL * 1024));
   constexpr int kWeightBase = (kBufs - 1) * kBufB;
   static_assert(kWeightBase + KS * NSL * 1024 <= kLdsB, "weight panels fit behind the third tile buffer");
   static_assert(2 * KS + 2 * kLoadsPerWave <= 63, "loads in flight fit the vmcnt counter");
@@ -217,13 +182,13 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
           acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[tap][sl], b[tap & 1][sl], (tap == 0 && sl == 0) ? zero : acc0, 0, 0, 0);
           acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wreg[tap][sl + 1], b[tap & 1][sl + 1], (tap == 0 && sl == 0) ? zero : acc1, 0, 0, 0);
           const int e = tap * (NSL / 2) + sl / 2;
-          if (e < 16) z = fmaf(silu(yprev[e]), wo[e], z);
+          if (e < 16) z = fmaf(silu_fast(yprev[e]), wo[e], z);
           __builtin_amdgcn_sched_barrier(0);   // keep the interleaving as written
         }
       }
       static_assert(KS * (NSL / 2) >= 12, "pairs to spread the epilogue over");
 #pragma unroll
-      for (int e = KS * (NSL / 2); e < 16; ++e) z = fmaf(silu(yprev[e]), wo[e], z);
+      for (int e = KS * (NSL / 2); e < 16; ++e) z = fmaf(silu_fast(yprev[e]), wo[e], z);
       z = z + __shfl_xor(z, 32, kWave) + bo;
       if (hb == 0 && t > 0) zmine[(t - 1) * TM] = z;
 #pragma unroll
@@ -233,7 +198,7 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
   {
     float z = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) z = fmaf(silu(yprev[r]), wo[r], z);
+    for (int r = 0; r < 16; ++r) z = fmaf(silu_fast(yprev[r]), wo[r], z);
     z = z + __shfl_xor(z, 32, kWave) + bo;
     if (hb == 0) zmine[(n_tiles - 1) * TM] = z;
   }
@@ -261,19 +226,10 @@ score_reg_panels_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ p
   panels[idx] = c < C ? W[((h * C + c) * C2 + m) * ks + tap] : (uint16_t)0;
 }
 
-// Tiles per workgroup: as many as make the grid about one workgroup per CU, at most kMaxGroupTiles.
-int pick_group_tiles(const ltea_cfg& cfg, const SeqView& sv) {
-  const int64_t tiles = (sv.total_tokens + TM - 1) / TM * cfg.Hkv;
-  int64_t g = tiles / 256;
-  if (g < 1) g = 1;
-  if (g > kMaxGroupTiles) g = kMaxGroupTiles;
-  return (int)g;
-}
-
 template <int KS>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
                const SeqView& sv, float* logits, const void* panels, hipStream_t stream) {
-  const int gt = pick_group_tiles(cfg, sv);
+  const int gt = pick_group_tiles(sv, cfg.Hkv, TM, kMaxGroupTiles);
   const int64_t groups_upper = (sv.total_tokens + gt * TM - 1) / (gt * TM) + sv.n_seqs;
   hipLaunchKernelGGL(score_reg_kernel<KS>, dim3((unsigned)(groups_upper * cfg.Hkv)), dim3(kThreads), 0, stream,
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), st, sh,
