@@ -9,8 +9,17 @@ from paper_2510_20787_amd import binding as B
 # Output tolerances (max-abs vs the fp64 oracle, absolute and relative to the largest reference magnitude).
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
 # Logit tolerance: |z_gpu - z_oracle| <= LOGIT_TOL * max(1, |z|). Inputs and weights are exactly representable,
-# products are exact in fp32, so the difference is fp32 accumulation order plus the fp32 Swish.
+# products are exact in fp32, so the difference is fp32 accumulation order plus the fp32 Swish (and, in the
+# multi-layer bf16 kernels, the 16-bit hi + lo activations).  Measured maxima of that ratio per scoring kernel on one
+# MI355X (prefill_bf16, long_prefill_bf16 / varlen_prefill_bf16, paper_stack_bf16, a 2-layer D=128 stack, fp32 stacks):
+LOGIT_EPS_MEASURED = {"score_reg_kernel": 3.4e-8, "score_mfma_kernel": 1.1e-6, "score_deep_reg_kernel": 2.5e-7,
+                      "score_deep_kernel": 7.9e-7, "score_generic": 8.6e-8}
+# The bar is about ten times the largest of them.
 LOGIT_TOL = {"f32": 1e-5, "bf16": 1e-5}
+assert all(e * 9 <= LOGIT_TOL["bf16"] for e in LOGIT_EPS_MEASURED.values())
+# The random-configuration sweeps (and the training forward, which shifts the output biases) draw wider stacks, larger
+# weights and logits of several units; their bar is five times wider.
+LOGIT_TOL_SWEEP = {dt: 5 * t for dt, t in LOGIT_TOL.items()}
 
 
 def dev(x: np.ndarray, dtype: str) -> torch.Tensor:

@@ -13,7 +13,7 @@ import torch
 from oracle import ltea_oracle as orc
 from paper_2510_20787_amd import binding as B
 from paper_2510_20787_amd import workloads as wl
-from tests.gpu_util import LOGIT_TOL, DeviceWorkload, dev, to_np
+from tests.gpu_util import LOGIT_TOL_SWEEP, DeviceWorkload, dev, to_np
 from tests.helpers import oracle_cfg, oracle_cnn
 
 pytestmark = pytest.mark.gpu
@@ -57,7 +57,7 @@ def test_train_forward_backward(name):
     zg = to_np(logits)
     # the multi-layer bf16 kernel carries activations as bf16 hi + lo pairs: allow it a few 1e-5 at these weights
     eps = float(np.max(np.abs(zg - z64)))
-    assert np.all(np.abs(zg - z64) <= 5 * LOGIT_TOL[dt] * np.maximum(1.0, np.abs(z64)))
+    assert np.all(np.abs(zg - z64) <= LOGIT_TOL_SWEEP[dt] * np.maximum(1.0, np.abs(z64)))
     assert np.min(np.abs(z64)) > 2 * eps, "a logit sits inside the scoring error of the threshold: pick another seed"
     tol = GRAD_TOL[dt]
     out_g, lse_g, dq_g, dk_g, dv_g, dz_g = (to_np(x) for x in (out, lse, dq, dk, dv, dz))
