@@ -115,8 +115,9 @@ size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqle
   const size_t esz = (size_t)elem_size(cfg.dtype);
   const size_t heads = (size_t)n_seqs * cfg.Hkv;
   const size_t cap = (size_t)(max_seqlen > 1 ? max_seqlen : 1);
-  char* p = static_cast<char*>(base);
-  auto take = [&](size_t bytes) { char* r = p; p += align_up(bytes > 0 ? bytes : 1, 256); return r; };
+  // integer arithmetic: a size query carves from a null base
+  uintptr_t p = reinterpret_cast<uintptr_t>(base);
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += align_up(bytes > 0 ? bytes : 1, 256); return r; };
   void* k_ret = take(heads * cap * cfg.D * esz);
   void* v_ret = take(heads * cap * cfg.D * esz);
   float* ret_score = reinterpret_cast<float*>(take(heads * cap * 4));
@@ -134,7 +135,7 @@ size_t carve_train(const ltea_cfg& cfg, int n_seqs, int64_t total, int max_seqle
   if (far_dv) *far_dv = fv;
   if (c) *c = ltea_cache{k_win, v_win, win_score, k_ret, v_ret, ret_score, ret_pos, ret_count, n_seen, n_scored};
   if (delta) *delta = d;
-  return (size_t)(p - static_cast<char*>(base));
+  return (size_t)(p - reinterpret_cast<uintptr_t>(base));
 }
 
 }  // namespace
@@ -454,6 +455,7 @@ int ltea_decode_step_static(const ltea_cfg* cfg, const ltea_cnn* cnn, const void
   // beyond the fixed scratch: refused here, before anything is looked up or launched
   if (ltea_decode_workspace_bytes(cfg, cnn, n_seqs) > (size_t)LTEA_STATIC_SCRATCH_BYTES) return LTEA_EWORKSPACE;
   if (n_seqs == 0) return ltea_decode_step(cfg, cnn, q, k, v, out, cache, 0, nullptr, 0, stream);
+  if (!q || !k || !v || !out || !cache) return LTEA_EINVAL;     // before the device is asked for the array's address
   hipError_t e = hipSuccess;
   void* ws = static_scratch(&e);
   if (ws == nullptr) return LTEA_EHIP;

@@ -266,8 +266,8 @@ static size_t carve(const ltea_cfg& cfg, int n_seqs, int64_t total_new, char* ws
                     char*& ext_v, float*& ext_logits, int32_t*& old_count) {
   const int64_t ext = append_ext_tokens(cfg, n_seqs, total_new);
   const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
-  char* p = ws;
-  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  uintptr_t p = reinterpret_cast<uintptr_t>(ws);   // integer arithmetic: a size query carves from a null base
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
   const size_t per_seq = sizeof(int32_t) * (size_t)(n_seqs + 1);
   P.n_old = reinterpret_cast<int32_t*>(take(per_seq));
   P.w_old = reinterpret_cast<int32_t*>(take(per_seq));
@@ -285,7 +285,7 @@ static size_t carve(const ltea_cfg& cfg, int n_seqs, int64_t total_new, char* ws
   ext_v = take((size_t)ext * cfg.Hkv * cfg.D * esz);
   ext_logits = reinterpret_cast<float*>(take((size_t)ext * cfg.Hkv * sizeof(float)));
   // an optional third key buffer (scoring keys) follows; launch_append_build takes it from here
-  return (size_t)(p - ws);
+  return (size_t)(p - reinterpret_cast<uintptr_t>(ws));
 }
 
 // Stage 1 of the continuation: plan, ranks, extended K/V.  Returns the device arrays later stages need.

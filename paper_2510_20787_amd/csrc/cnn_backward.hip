@@ -944,8 +944,8 @@ struct Layout {
 
 Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base) {
   Layout L;
-  char* p = static_cast<char*>(base);
-  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  uintptr_t p = reinterpret_cast<uintptr_t>(base);   // integer arithmetic: a size query carves from a null base
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
   const size_t rows = (size_t)cfg.Hkv * (size_t)total;
   L.seq_lo = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)total));
   L.seq_hi = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (size_t)total));
@@ -986,7 +986,7 @@ Layout carve(const ltea_cfg& cfg, const ltea_cnn& cnn, int64_t total, void* base
   }
   L.part_wout = reinterpret_cast<float*>(take(sizeof(float) * col_chunks * cfg.Hkv * cin));
   L.part_bout = reinterpret_cast<float*>(take(sizeof(float) * col_chunks * cfg.Hkv));
-  L.bytes = (size_t)(p - static_cast<char*>(base));
+  L.bytes = (size_t)(p - reinterpret_cast<uintptr_t>(base));
   return L;
 }
 

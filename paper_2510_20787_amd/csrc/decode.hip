@@ -743,15 +743,15 @@ bool window_scoring(const ltea_cfg& cfg, const ltea_cnn& cnn) {
 size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char* base, PreScore* out) {
   const int R = 2 * cnn_rho(&cnn) + 1;
   const size_t rows = (size_t)n_seqs * R;
-  char* p = base;
-  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  uintptr_t p = reinterpret_cast<uintptr_t>(base);   // integer arithmetic: a size query carves from a null base
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
   void* wk = take(rows * cfg.Hkv * cfg.D * 2);
   void* wv = take(rows * cfg.Hkv * cfg.D * 2);
   int32_t* cu2 = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * (size_t)n_seqs + 1)));
   float* lg = reinterpret_cast<float*>(take(sizeof(float) * rows * cfg.Hkv));
   void* sws = take(score_deep_workspace(cfg, cnn));
   if (out) { out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->score_ws = sws; out->total = (int64_t)rows; }
-  return (size_t)(p - base);
+  return (size_t)(p - reinterpret_cast<uintptr_t>(base));
 }
 
 // cnn_or_null == nullptr selects the lazy step (no scoring; `status` receives LTEA_LATE_SCORING).
@@ -901,14 +901,14 @@ hipError_t launch_decode_step(const ltea_cfg& cfg, const ltea_cnn& cnn, const vo
 size_t decode_windows_layout(const ltea_cfg& cfg, int rho, int n_seqs, void* base, DecodeWindows* out) {
   const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   const size_t rows = (size_t)n_seqs * (2 * rho + 1);
-  char* p = static_cast<char*>(base);
-  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  uintptr_t p = reinterpret_cast<uintptr_t>(base);
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
   void* wk = take(rows * cfg.Hkv * cfg.D * esz);
   void* wv = take(rows * cfg.Hkv * cfg.D * esz);
   int32_t* cu2 = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * (size_t)n_seqs + 1)));
   float* lg = reinterpret_cast<float*>(take(sizeof(float) * rows * cfg.Hkv));
   if (out) { out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->total = (int64_t)rows; }
-  return (size_t)(p - static_cast<char*>(base));
+  return (size_t)(p - reinterpret_cast<uintptr_t>(base));
 }
 
 hipError_t launch_decode_windows(const ltea_cfg& cfg, int rho, const void* k, const void* v, const void* k_feat,

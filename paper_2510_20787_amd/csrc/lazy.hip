@@ -109,15 +109,15 @@ size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 size_t rescore_workspace(const ltea_cfg& cfg, int n_seqs, RescoreBuffers* out, void* base) {
   const size_t esz = cfg.dtype == LTEA_F32 ? 4 : 2;
   const size_t rows = (size_t)n_seqs * cfg.window;
-  char* p = static_cast<char*>(base);
-  auto take = [&](size_t bytes) { char* r = p; p += up256(bytes); return r; };
+  uintptr_t p = reinterpret_cast<uintptr_t>(base);   // integer arithmetic: a size query carves from a null base
+  auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
   void* pk = take(rows * cfg.Hkv * cfg.D * esz);
   void* pv = take(rows * cfg.Hkv * cfg.D * esz);
   float* lg = reinterpret_cast<float*>(take(rows * cfg.Hkv * sizeof(float)));
   int32_t* cu = reinterpret_cast<int32_t*>(take(((size_t)n_seqs + 1) * sizeof(int32_t)));
   int32_t* plan = reinterpret_cast<int32_t*>(take((size_t)n_seqs * 3 * sizeof(int32_t)));
   if (out) { out->pk = pk; out->pv = pv; out->logits = lg; out->cu = cu; out->plan = plan; out->total = (int64_t)rows; }
-  return (size_t)(p - static_cast<char*>(base));
+  return (size_t)(p - reinterpret_cast<uintptr_t>(base));
 }
 
 hipError_t launch_rescore_pack(const ltea_cfg& cfg, const ltea_rope* rope, const ltea_cache& c, int n_seqs, int rho,
