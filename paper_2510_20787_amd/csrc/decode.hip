@@ -70,6 +70,7 @@ struct StepParams {
   // sequence b occupies rows b*(2*rho+1) .. of pre_logits[h][.], its first row is position max(0, t - 2*rho).
   const float* pre_logits;
   int64_t pre_total;
+  int pre_stride;            // rows per sequence in pre_logits (2*rho+1, or more when the windows are packed with gaps)
   // Lazy mode (scores come from separate batched launches between steps): nothing is scored here, n_scored is
   // left alone, and a token that leaves the window without a final logit is reported through `status`.
   int lazy;
@@ -426,7 +427,7 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
         if (h == 0) ws_t[b] = t;
         const int first = t - 2 * P.rho > 0 ? t - 2 * P.rho : 0;
         if (t - P.rho >= 0)
-          ws_logit[head] = P.pre_logits[(int64_t)h * P.pre_total + (int64_t)b * (2 * P.rho + 1) + (t - P.rho - first)];
+          ws_logit[head] = P.pre_logits[(int64_t)h * P.pre_total + (int64_t)b * P.pre_stride + (t - P.rho - first)];
       }
       return;
     }
@@ -689,19 +690,33 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, const T* __restrict__ kf_new,
                       RopeDev rope, int32_t* __restrict__ status, T* __restrict__ win_k, T* __restrict__ win_v,
-                      int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho) {
+                      int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho, int stride_rows,
+                      uint8_t* __restrict__ row_valid) {
   constexpr int EPP = Elems<T>::N;
   const int b = blockIdx.x;
-  const int R = 2 * rho + 1;
+  const int R = stride_rows;     // 2*rho + 1, or more: windows mode (row_valid given), the rows in between are zeros
   const int t = C.n_seen[b];
   const int first = t - 2 * rho > 0 ? t - 2 * rho : 0;
   const int len = t - first + 1;
-  if (threadIdx.x == 0) {
-    cu2[2 * b] = b * R;
-    cu2[2 * b + 1] = b * R + len;
-    if (b == B - 1) cu2[2 * B] = B * R;
-  }
   const int pieces = D / EPP;                                 // 16-byte pieces per row
+  if (row_valid == nullptr) {
+    if (threadIdx.x == 0) {
+      cu2[2 * b] = b * R;
+      cu2[2 * b + 1] = b * R + len;
+      if (b == B - 1) cu2[2 * B] = B * R;
+    }
+  } else {
+    // one sequence of B * R rows; which rows are tokens is said per row, and the others are cleared
+    if (threadIdx.x == 0 && b == 0) { cu2[0] = 0; cu2[1] = B * R; }
+    for (int r = threadIdx.x; r < R; r += 256) row_valid[b * R + r] = r < len ? 1 : 0;
+    const int gap = (R - len) * Hkv * pieces;
+    const int64_t dst0 = (int64_t)(b * R + len) * Hkv * D;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    for (int i = threadIdx.x; i < gap; i += 256) {
+      reinterpret_cast<u32x4*>(win_k + dst0)[i] = zero4;
+      reinterpret_cast<u32x4*>(win_v + dst0)[i] = zero4;
+    }
+  }
   const int items = len * Hkv * pieces;
   bool out_of_tables = false;
   for (int i = threadIdx.x; i < items; i += 256) {
@@ -726,6 +741,8 @@ decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restri
 
 struct PreScore {            // buffers of the window-scoring path, carved from the tail of the workspace
   void* win_k; void* win_v; int32_t* cu2; float* logits; void* score_ws; int64_t total;
+  uint8_t* row_valid;        // windows mode only
+  int stride;                // rows per sequence
 };
 
 size_t up256(size_t x) { return (x + 255) / 256 * 256; }
@@ -740,8 +757,22 @@ bool window_scoring(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   return cfg.dtype == LTEA_BF16 && cnn.n_layers >= 2 && score_deep_supported(cfg, cnn);
 }
 
-size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char* base, PreScore* out) {
+// Rows per sequence of the packed windows: the receptive field, and where the register-stationary kernel scores them
+// (windows mode: all windows of the batch as one sequence) as many rows of zeros as the widest dilation reaches, so that
+// no tap crosses from one window into the next.
+int prescore_stride(const ltea_cfg& cfg, const ltea_cnn& cnn, bool* windows_mode) {
   const int R = 2 * cnn_rho(&cnn) + 1;
+  const bool wm = score_deep_reg_supported(cfg, cnn);
+  if (windows_mode) *windows_mode = wm;
+  if (!wm) return R;
+  int gap = 0;
+  for (int l = 0; l < cnn.n_layers; ++l) gap = cnn.dilation[l] > gap ? cnn.dilation[l] : gap;
+  return R + gap;
+}
+
+size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char* base, PreScore* out) {
+  bool wm = false;
+  const int R = prescore_stride(cfg, cnn, &wm);
   const size_t rows = (size_t)n_seqs * R;
   uintptr_t p = reinterpret_cast<uintptr_t>(base);   // integer arithmetic: a size query carves from a null base
   auto take = [&](size_t bytes) { char* r = reinterpret_cast<char*>(p); p += up256(bytes); return r; };
@@ -750,7 +781,11 @@ size_t prescore_bytes(const ltea_cfg& cfg, const ltea_cnn& cnn, int n_seqs, char
   int32_t* cu2 = reinterpret_cast<int32_t*>(take(sizeof(int32_t) * (2 * (size_t)n_seqs + 1)));
   float* lg = reinterpret_cast<float*>(take(sizeof(float) * rows * cfg.Hkv));
   void* sws = take(score_deep_workspace(cfg, cnn));
-  if (out) { out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->score_ws = sws; out->total = (int64_t)rows; }
+  uint8_t* rv = wm ? reinterpret_cast<uint8_t*>(take(rows)) : nullptr;
+  if (out) {
+    out->win_k = wk; out->win_v = wv; out->cu2 = cu2; out->logits = lg; out->score_ws = sws; out->total = (int64_t)rows;
+    out->row_valid = rv; out->stride = R;
+  }
   return (size_t)(p - reinterpret_cast<uintptr_t>(base));
 }
 
@@ -790,6 +825,7 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   size_t lds_bytes = P.score_mfma ? 0 : (size_t)2 * (2 * P.rho + 1) * P.lds_row_floats * sizeof(float);
   P.pre_logits = nullptr;
   P.pre_total = 0;
+  P.pre_stride = 2 * P.rho + 1;
   P.lazy = lazy ? 1 : 0;
   P.status = status;
   if (lazy) {
@@ -805,14 +841,19 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
       hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
                          static_cast<const T*>(k), static_cast<const T*>(v), static_cast<const T*>(nullptr),
                          rope_dev(nullptr), static_cast<int32_t*>(nullptr), static_cast<T*>(ps.win_k),
-                         static_cast<T*>(ps.win_v), ps.cu2, n_seqs, cfg.Hkv, cfg.D, cfg.window, P.rho);
+                         static_cast<T*>(ps.win_v), ps.cu2, n_seqs, cfg.Hkv, cfg.D, cfg.window, P.rho, ps.stride,
+                         ps.row_valid);
       hipError_t e0 = hipGetLastError();
       if (e0 != hipSuccess) return e0;
-      SeqView sv{ps.cu2, 2 * n_seqs, ps.total, 2 * P.rho + 1};
-      e0 = launch_score_deep(cfg, cnn, ps.win_k, ps.win_v, (int64_t)cfg.Hkv * cfg.D, cfg.D, sv, ps.logits, ps.score_ws, stream);
+      // windows mode: the whole batch is one sequence of n_seqs * stride rows; else two sequences per window
+      const SeqView sv = ps.row_valid ? SeqView{ps.cu2, 1, ps.total, (int32_t)ps.total}
+                                      : SeqView{ps.cu2, 2 * n_seqs, ps.total, 2 * P.rho + 1};
+      e0 = launch_score_deep(cfg, cnn, ps.win_k, ps.win_v, (int64_t)cfg.Hkv * cfg.D, cfg.D, sv, ps.logits, ps.score_ws, stream,
+                             ps.row_valid);
       if (e0 != hipSuccess) return e0;
       P.pre_logits = ps.logits;
       P.pre_total = ps.total;
+      P.pre_stride = ps.stride;
       P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
       lds_bytes = 0;
     }
@@ -920,7 +961,7 @@ hipError_t launch_decode_windows(const ltea_cfg& cfg, int rho, const void* k, co
     hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
                        static_cast<const T*>(k), static_cast<const T*>(v), static_cast<const T*>(k_feat), rope_dev(rope),
                        status, static_cast<T*>(w.win_k), static_cast<T*>(w.win_v), w.cu2, n_seqs, cfg.Hkv, cfg.D,
-                       cfg.window, rho);
+                       cfg.window, rho, 2 * rho + 1, static_cast<uint8_t*>(nullptr));
   };
   if (cfg.dtype == LTEA_F32) go(float{});
   else go(bf16_t{});

@@ -60,15 +60,18 @@ hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void
 // as the registers hold them.  launch_score_deep and launch_score_deep_panels hand over to these where they apply.
 bool score_deep_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
 hipError_t launch_score_deep_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
+// row_valid (optional, device, one byte per token row): windows mode for the decode step.  The rows are many
+// independent short windows laid end to end with at least max(dilation) rows of zeros between them; a 0 byte marks a
+// row that is not a token, whose activations are then zero at every layer, as outside a sequence.
 hipError_t launch_score_deep_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                                  int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
-                                 const void* panels, hipStream_t stream);
+                                 const void* panels, hipStream_t stream, const uint8_t* row_valid = nullptr);
 bool score_deep_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
 size_t score_deep_workspace(const ltea_cfg& cfg, const ltea_cnn& cnn);
 hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
 hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v,
                              int64_t stride_tok, int64_t stride_head, const SeqView& sv, float* logits,
-                             void* workspace, hipStream_t stream);
+                             void* workspace, hipStream_t stream, const uint8_t* row_valid = nullptr);
 
 // ---- (b) retention + cache fill -------------------------------------------------------------------
 hipError_t launch_retain(const ltea_cfg& cfg, const float* logits, const void* k, const void* v,

@@ -361,8 +361,10 @@ hipError_t launch_score_deep_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, vo
   return hipGetLastError();
 }
 
+// row_valid: windows mode of the register-stationary kernel (see its launcher); only valid where that kernel applies.
 hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
-                             int64_t sh, const SeqView& sv, float* logits, void* workspace, hipStream_t stream) {
+                             int64_t sh, const SeqView& sv, float* logits, void* workspace, hipStream_t stream,
+                             const uint8_t* row_valid) {
   if (sv.total_tokens == 0) return hipSuccess;
   const DeepPlan p = plan(cfg, cnn);
   if (!p.ok) return hipErrorInvalidValue;
@@ -372,7 +374,9 @@ hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
     if (e != hipSuccess) return e;
     panels = workspace;
   }
-  if (score_deep_reg_supported(cfg, cnn)) return launch_score_deep_reg(cfg, cnn, k, v, st, sh, sv, logits, panels, stream);
+  if (score_deep_reg_supported(cfg, cnn))
+    return launch_score_deep_reg(cfg, cnn, k, v, st, sh, sv, logits, panels, stream, row_valid);
+  if (row_valid != nullptr) return hipErrorInvalidValue;
   DeepArgs a;
   a.k = static_cast<const bf16_t*>(k); a.v = static_cast<const bf16_t*>(v); a.st = st; a.sh = sh;
   a.panels = static_cast<const bf16_t*>(panels);

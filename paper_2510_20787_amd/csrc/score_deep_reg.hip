@@ -41,7 +41,10 @@ constexpr int kOffActA = kBufs * kBufB;
 constexpr int kOffActB = kOffActA + kActAB;
 constexpr int kOffConst = kOffActB + kActBB;
 constexpr int kOffZ = kOffConst + kConsts * 4;
-constexpr int kLdsB = kOffZ + kMaxGroupTiles * kPos * 4;
+constexpr int kOffValid = kOffZ + kMaxGroupTiles * kPos * 4;
+constexpr int kMostRows = kMaxGroupTiles * kPos + 2 * kMaxD1;      // rows one workgroup's descriptor spans at most
+constexpr int kValidWords = (kMostRows + 63) / 64 * 2;             // one bit per row
+constexpr int kLdsB = kOffValid + kValidWords * 4;
 static_assert(kLdsB <= 160 * 1024, "one workgroup's LDS");
 constexpr int kInstrPerArray = (kRowsMax + 7) / 8;                 // wave instructions that cover one array: 17
 constexpr int kLoadsPerWave = 2 * ((kInstrPerArray + 3) / 4);      // per tile and wave, keys + values: 10
@@ -57,6 +60,7 @@ struct DeepRegArgs {
   const float* bias1; const float* bias2; const float* bias3; const bf16_t* w_out; const float* b_out;
   int d1, d2, d3;
   const int32_t* cu; int n_seqs; int64_t total; float* logits; int group_tiles, Hkv;
+  const uint8_t* row_valid;   // optional [total]: 0 marks a row that is padding between independent short windows
 };
 
 __global__ void __launch_bounds__(kThreads, 1)
@@ -92,8 +96,19 @@ score_deep_reg_kernel(const DeepRegArgs a) {
   // rows then wrap to huge offsets and read as zeros) and end at the last one or at the sequence end.
   const uint32_t row_bytes = (uint32_t)a.st * 2u;
   const int base_row = g0 > 0 ? g0 - h0 : 0;
-  const int most_rows = kMaxGroupTiles * kPos + 2 * kMaxD1;
-  const int rows_here = n - base_row < most_rows ? n - base_row : most_rows;
+  const int rows_here = n - base_row < kMostRows ? n - base_row : kMostRows;
+  // Windows mode (decode: many independent short windows packed with zero rows between them): one bit per row of this
+  // workgroup's range says whether it is a real token; activations of the others are forced to zero at every layer,
+  // exactly as outside a sequence.  Loaded now, with ordinary loads, before any tile load is in flight.
+  uint32_t* valid_bits = reinterpret_cast<uint32_t*>(lds + kOffValid);
+  if (a.row_valid != nullptr) {
+    for (int r0 = 64 * wv; r0 < rows_here; r0 += 64 * 4) {
+      const int r = base_row + r0 + lane;
+      const uint8_t f = r < n ? a.row_valid[lo + r] : (uint8_t)0;
+      const unsigned long long m = __builtin_amdgcn_ballot_w64(f != 0);
+      if (lane == 0) { valid_bits[r0 >> 5] = (uint32_t)m; valid_bits[(r0 >> 5) + 1] = (uint32_t)(m >> 32); }
+    }
+  }
   const uint32_t span = (uint32_t)(rows_here - 1) * row_bytes + (uint32_t)kRowB;
   const u32x4 rs_k = make_raw_rsrc(a.k + (lo + base_row) * a.st + (int64_t)h * a.sh, span);
   const u32x4 rs_v = make_raw_rsrc(a.v + (lo + base_row) * a.st + (int64_t)h * a.sh, span);
@@ -171,6 +186,16 @@ score_deep_reg_kernel(const DeepRegArgs a) {
 #pragma unroll
   for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
+  // 1 for a position whose activations exist, 0 for one outside the sequence (or, in windows mode, on a padding row)
+  auto inside_factor = [&](int pos) -> float {
+    bool in = pos >= 0 && pos < n;
+    if (a.row_valid != nullptr) {
+      const int rel = in ? pos - base_row : 0;
+      in = in && ((valid_bits[rel >> 5] >> (rel & 31)) & 1u);
+    }
+    return in ? 1.0f : 0.0f;
+  };
+
   int buf = 0;
 #pragma unroll 1
   for (int t = 0; t < n_tiles; ++t) {
@@ -214,8 +239,7 @@ score_deep_reg_kernel(const DeepRegArgs a) {
     // Swish(acc), zero outside the sequence, as hi + lo bf16: the four channels of a group are half of 16-byte piece
     // 4*mb + g4 of this position's row.
     {
-      const int pos = j0 - h1 + row;
-      const float inside = pos >= 0 && pos < n ? 1.0f : 0.0f;     // a factor, not a branch around the activation
+      const float inside = inside_factor(j0 - h1 + row);          // a factor, not a branch around the activation
       const int f = (row >> 1) & 7;
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
@@ -261,8 +285,7 @@ score_deep_reg_kernel(const DeepRegArgs a) {
       }
     }
     {
-      const int pos = j0 - a.d3 + row;
-      const float inside = pos >= 0 && pos < n ? 1.0f : 0.0f;
+      const float inside = inside_factor(j0 - a.d3 + row);
       const int f = (row >> 2) & 3;            // 64-byte rows: four rows span the banks, so the swizzle steps every four
 #pragma unroll
       for (int g4 = 0; g4 < 4; ++g4) {
@@ -363,7 +386,8 @@ hipError_t launch_score_deep_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn
 }
 
 hipError_t launch_score_deep_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
-                                 int64_t sh, const SeqView& sv, float* logits, const void* panels, hipStream_t stream) {
+                                 int64_t sh, const SeqView& sv, float* logits, const void* panels, hipStream_t stream,
+                                 const uint8_t* row_valid) {
   if (sv.total_tokens == 0) return hipSuccess;
   DeepRegArgs a;
   a.k = static_cast<const bf16_t*>(k); a.v = static_cast<const bf16_t*>(v); a.st = st; a.sh = sh;
@@ -372,6 +396,7 @@ hipError_t launch_score_deep_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const
   a.w_out = static_cast<const bf16_t*>(cnn.w_out); a.b_out = cnn.b_out;
   a.d1 = cnn.dilation[0]; a.d2 = cnn.dilation[1]; a.d3 = cnn.dilation[2];
   a.cu = sv.cu_seqlens; a.n_seqs = sv.n_seqs; a.total = sv.total_tokens; a.logits = logits;
+  a.row_valid = row_valid;
   const int TMv = kPos - 2 * (a.d2 + a.d3);
   a.group_tiles = pick_group_tiles(sv, cfg.Hkv, TMv, kMaxGroupTiles);
   a.Hkv = cfg.Hkv;
