@@ -74,16 +74,31 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 
   // ---- which (query head, sequence, query tile) is this workgroup? ------------------------------------
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work items so
-  // that neighbouring query tiles of one head (which share most of their keys) meet in the same L2.
+  // that neighbouring query tiles of one head (which share most of their keys) meet in the same L2.  When the heads
+  // divide evenly over the XCDs, an XCD takes whole heads and walks them tile by tile, heads fastest, long tiles first:
+  // the first tiles of every sequence, whose window is still filling, come last and fill the gaps when the grid drains.
   const int per_xcd = (n_work + 7) / 8;
   const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (work >= n_work) return;
-  const int hq = work / tiles_upper;
+  int hq, flat_tile;
+  const bool whole_heads = Hq % 8 == 0;
+  if (whole_heads) {
+    const int hpx = Hq / 8, in_xcd = blockIdx.x / 8;         // per_xcd == hpx * tiles_upper
+    hq = (blockIdx.x % 8) * hpx + in_xcd % hpx;
+    flat_tile = in_xcd / hpx;
+  } else {
+    hq = work / tiles_upper;
+    flat_tile = work - hq * tiles_upper;
+  }
   // cu packs the query / output rows.  Normally it packs the keys as well; with kv_start / kv_len given, the keys
   // of sequence s are rows kv_start[s] .. kv_start[s] + kv_len[s] - 1 of k / v and the queries are the last
   // cu[s+1] - cu[s] positions of that key sequence (continuation of a prefill).
   int tile, s, n, lo_q;
-  if (!locate_tile(cu, n_seqs, BM, work - hq * tiles_upper, s, tile, lo_q, n)) return;
+  if (whole_heads && kv_start == nullptr) {
+    if (!locate_tile_late_first(cu, n_seqs, BM, (window + BM - 1) / BM, flat_tile, s, tile, lo_q, n)) return;
+  } else {
+    if (!locate_tile(cu, n_seqs, BM, flat_tile, s, tile, lo_q, n)) return;
+  }
   int64_t lo = lo_q;
   int q_begin = 0;
   if (kv_start != nullptr) {

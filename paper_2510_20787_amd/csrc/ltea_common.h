@@ -103,4 +103,44 @@ __device__ __forceinline__ bool locate_tile(const int32_t* __restrict__ cu, int 
   return false;
 }
 
+// The same enumeration in two parts: first every sequence's tiles from index `first_late` on, then the tiles before it
+// (the first tiles of a sequence see a window that is still filling: a kernel whose work per tile grows with the number
+// of keys in reach puts them last, where they fill the gaps that the long tiles leave when the grid drains).  The
+// counts of flat indices are the same as locate_tile's: ceil(len / tile_len) per sequence.
+__device__ __forceinline__ bool locate_tile_late_first(const int32_t* __restrict__ cu, int n_seqs, int tile_len,
+                                                       int first_late, int flat, int& seq, int& tile, int& lo, int& len) {
+  const int lane = threadIdx.x & (kWave - 1);
+#pragma unroll 1
+  for (int part = 0; part < 2; ++part) {
+    for (int s0 = 0; s0 < n_seqs; s0 += kWave) {
+      const int i = s0 + lane;
+      const int ic = i < n_seqs ? i : n_seqs - 1;
+      const int a = cu[ic], b = cu[ic + 1];
+      const int all = i < n_seqs ? (b - a + tile_len - 1) / tile_len : 0;
+      const int early = all < first_late ? all : first_late;
+      const int nt = part == 0 ? all - early : early;
+      int inc = nt;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int t = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += t;
+      }
+      const int total = __builtin_amdgcn_readfirstlane(__shfl(inc, kWave - 1, kWave));
+      if (flat < total) {
+        const unsigned long long m = __builtin_amdgcn_ballot_w64(inc > flat);
+        const int l = __builtin_ctzll(m);
+        seq = s0 + l;
+        lo = __builtin_amdgcn_readfirstlane(__shfl(a, l, kWave));
+        len = __builtin_amdgcn_readfirstlane(__shfl(b, l, kWave)) - lo;
+        const int within = flat - __builtin_amdgcn_readfirstlane(__shfl(inc, l, kWave) - __shfl(nt, l, kWave));
+        const int early_l = __builtin_amdgcn_readfirstlane(__shfl(early, l, kWave));
+        tile = part == 0 ? early_l + within : within;
+        return true;
+      }
+      flat -= total;
+    }
+  }
+  return false;
+}
+
 }  // namespace ltea
