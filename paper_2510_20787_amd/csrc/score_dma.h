@@ -41,18 +41,22 @@ __device__ __forceinline__ float silu_fast(float y) {
   return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * y));
 }
 
-// Consecutive tiles per workgroup for a kernel that runs one workgroup per CU: the smallest number with which the
-// grid is at most one workgroup per CU (256), so that no CU gets a second workgroup while others idle; `max_tiles` if
-// even that many leave more.  The count of groups is exact for a batch of equal lengths, an upper bound otherwise.
+// Consecutive tiles per workgroup for a kernel that runs one workgroup per CU (256 of them): the number that makes the
+// launch shortest when a workgroup costs its tiles plus about three tiles' worth of start-up and the grid runs in
+// rounds of 256 workgroups.  The count of groups is exact for a batch of equal lengths, an upper bound otherwise.
 inline int pick_group_tiles(const SeqView& sv, int Hkv, int tile_tokens, int max_tiles) {
+  int best = 1;
+  int64_t best_cost = -1;
   for (int g = 1; g <= max_tiles; ++g) {
     const int64_t span = (int64_t)g * tile_tokens;
     const int64_t groups = (int64_t)sv.n_seqs * sv.max_seqlen == sv.total_tokens
                                ? (int64_t)sv.n_seqs * ((sv.max_seqlen + span - 1) / span)
                                : sv.total_tokens / span + sv.n_seqs;
-    if (groups * Hkv <= 256) return g;
+    const int64_t rounds = (groups * Hkv + 255) / 256;
+    const int64_t cost = rounds * (g + 3);
+    if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = g; }
   }
-  return max_tiles;
+  return best;
 }
 
 }  // namespace ltea

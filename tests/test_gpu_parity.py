@@ -70,11 +70,12 @@ def test_score(name):
     logit_eps(zg, z64, w.dtype)
 
 
-@pytest.mark.parametrize("kernel,dilation", [((5,), None), ((3,), (2,))])
-def test_score_long_groups_of_tiles(kernel, dilation):
-    """Enough tiles per head that a workgroup of the register-stationary kernel takes its maximum of 16 in a row,
-    with a ragged end of the first sequence and a second one that ends inside a group."""
-    w = wl.make_prefill("long_groups", 77, "bf16", [20000 + 77, 12800 + 5], 16, 16, 64, 64, 16, 0, 0.0,
+@pytest.mark.parametrize("D,Hkv,kernel,dilation", [(64, 16, (5,), None), (64, 16, (3,), (2,)), (128, 8, (7,), None),
+                                                   (128, 8, (5,), (2,)), (128, 8, (3,), (4,))])
+def test_score_long_groups_of_tiles(D, Hkv, kernel, dilation):
+    """Enough tiles per head that a workgroup of the register-stationary kernels takes a long run of them (their
+    maximum at D = 64), with a ragged end of the first sequence and a second one that ends inside a group."""
+    w = wl.make_prefill("long_groups", 77, "bf16", [20000 + 77, 12800 + 5], Hkv, Hkv, D, 64, 16, 0, 0.0,
                         cnn_kernel=kernel, cnn_channels=(32,), cnn_dilation=dilation, qkv_scale=0.125, w_std=0.05)
     z64 = orc.score(w.k, w.v, oracle_cnn(w.cnn), w.cu_seqlens)
     d = DeviceWorkload(w)
