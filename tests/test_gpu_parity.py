@@ -83,6 +83,19 @@ def test_score_long_groups_of_tiles(D, Hkv, kernel, dilation):
     logit_eps(zg, z64, w.dtype)
 
 
+@pytest.mark.parametrize("dilation", [(1, 1, 1), (4, 3, 2), (2, 8, 16), (3, 1, 5)])
+def test_score_paper_stack_dilations(dilation):
+    """The register-stationary three-layer kernel with other dilations than the paper's: the tile anchoring (exact
+    positions per tile 128 - 2*(d2 + d3), halo of d1 + d2 + d3 rows) and the sequence boundaries of three ragged
+    sequences, one shorter than the receptive field."""
+    w = wl.make_prefill("paper_dil", 91, "bf16", [3000 + 11, 700, 9], 4, 2, 64, 128, 16, 2, 0.0, cnn_kernel=(3, 3, 3),
+                        cnn_channels=(64, 32, 16), cnn_dilation=dilation, qkv_scale=1.0, w_std=0.08)
+    z64 = orc.score(w.k, w.v, oracle_cnn(w.cnn), w.cu_seqlens)
+    d = DeviceWorkload(w)
+    zg = to_np(B.ltea_score(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen))
+    logit_eps(zg, z64, w.dtype)
+
+
 def test_score_strided_views():
     """K and V as strided views of one packed [T, 3, H, D] buffer."""
     w, cfg, cnn, (out, states, z64, kept) = oracle_prefill("bf16_d64")
