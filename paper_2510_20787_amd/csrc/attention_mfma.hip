@@ -70,7 +70,6 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   static_assert(2 * kBuf >= BM * G::OS, "epilogue staging must fit in the tile buffers");
   __shared__ __align__(16) bf16_t lds[2 * kBuf];
   __shared__ int pos_lds[2][BN];
-  __shared__ int pos_rng[2][2];   // min / max position of the tile's valid retained entries
 
   // ---- which (query head, sequence, query tile) is this workgroup? ------------------------------------
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work items so
@@ -185,12 +184,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
       *reinterpret_cast<u32x4*>(buf + k_st_off + p * G::RPP * KS) = R.k[p];
       *reinterpret_cast<u32x4*>(buf + v_st_off + p * G::RPP * VS) = R.v[p];
     }
-    if (t >= n_win_tiles && wv == 0) {   // wave 0 holds the tile's 64 positions (INT_MAX past ret_count)
-      pos_lds[t & 1][lane] = R.pos;
-      const int mn = wave_min_i(R.pos);
-      const int mx = wave_max_i(R.pos == 0x7FFFFFFF ? (int)0x80000000 : R.pos);
-      if (lane == 0) { pos_rng[t & 1][0] = mn; pos_rng[t & 1][1] = mx; }
-    }
+    if (t >= n_win_tiles && wv == 0) pos_lds[t & 1][lane] = R.pos;   // the tile's 64 positions (INT_MAX past ret_count)
   };
 
   // operand load offsets inside a tile buffer
@@ -386,11 +380,12 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
         if (!(jt > r_hi || jt + BN - 1 < r0 - window + 1))
           mode = ((jt + BN - 1 <= r0) && (jt >= r_hi - window + 1)) ? 0 : 1;
       } else {
-        const int pmin = pos_rng[t & 1][0], pmax = pos_rng[t & 1][1];
-        if (pmin <= r_hi - window) {                     // some entry has left one of this wave's windows
-          const bool full = (t - n_win_tiles + 1) * BN <= cnt;
-          mode = (full && pmax <= r0 - window) ? 0 : 2;
-        }
+        // every wave looks at the tile's positions itself (one LDS word per lane, two compares): an entry counts for
+        // this wave once it has left the window of the wave's last row, and needs no mask once it has left the window
+        // of the first; the filler positions of a ragged last tile never do
+        const int pv = pos_lds[t & 1][lane];
+        if (__builtin_amdgcn_ballot_w64(pv <= r_hi - window) != 0ull)
+          mode = __builtin_amdgcn_ballot_w64(pv > r0 - window) == 0ull ? 0 : 2;
       }
     }
     mode = __builtin_amdgcn_readfirstlane(mode);
