@@ -71,7 +71,7 @@ __global__ void __launch_bounds__(kSelThreads)
 retain_kernel(const RetainArgs a) {
   __shared__ int scan_scratch[kSelWaves + 1];
   __shared__ __align__(16) int hist[256 * kSub];
-  __shared__ int sel_digit, sel_need, sel_total;
+  __shared__ int sel_digit, sel_need, sel_total, sel_exact;
 
   const int b = blockIdx.x / a.Hkv, h = blockIdx.x - b * a.Hkv;
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
@@ -189,6 +189,7 @@ retain_kernel(const RetainArgs a) {
           if (running < need && need <= running + cnt[i]) {
             sel_digit = 255 - 4 * lane - i;
             sel_need = need - running;
+            sel_exact = need == running + cnt[i];   // the whole bucket is kept: the lower digits decide nothing
           }
           running += cnt[i];
         }
@@ -199,6 +200,7 @@ retain_kernel(const RetainArgs a) {
       prefix = (prefix << 8) | (uint32_t)sel_digit;
       need = sel_need;
       if (pass == 3) { thr = prefix; need_eq = need; }
+      else if (sel_exact && (prefix << shift) != 0u) { thr = (prefix << shift) - 1u; break; }   // keep keys >= prefix << shift
       __syncthreads();   // hist and sel_* are rewritten by the next pass
     }
   }
