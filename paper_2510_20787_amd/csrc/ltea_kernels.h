@@ -48,6 +48,9 @@ hipError_t launch_score_mfma(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
 // Its panels have the same size but are ordered as the registers hold them; launch_score_mfma and
 // launch_score_mfma_panels hand over to these where they apply.
 bool score_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+// launch_score_reg with panels == nullptr reads cnn.w[0] as the caller holds it and sorts it inside the kernel;
+// that needs the tensor 16-byte aligned.
+bool score_reg_takes_raw_weights(const ltea_cnn& cnn);
 hipError_t launch_score_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
 hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t stride_tok,
                             int64_t stride_head, const SeqView& sv, float* logits, const void* panels,

@@ -217,6 +217,9 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const vo
   const int ks = cnn.kernel[0];
   const void* panels = cnn.panels;
   hipError_t e = hipSuccess;
+  // the register-stationary kernel sorts unprepared weights itself (no launch for that) when they are 16-byte aligned
+  if (panels == nullptr && score_reg_supported(cfg, cnn) && score_reg_takes_raw_weights(cnn))
+    return launch_score_reg(cfg, cnn, k, v, st, sh, sv, logits, nullptr, stream);
   if (panels == nullptr) {            // not prepared by the caller: re-lay the weights into the workspace now
     e = launch_score_mfma_panels(cfg, cnn, workspace, stream);
     if (e != hipSuccess) return e;

@@ -42,7 +42,9 @@ constexpr int kInstrPerArray = (kRowsMax + 7) / 8;                 // wave instr
 constexpr int kLdsB = kBufs * kBufB + kMaxGroupTiles * TM * 4;     // 144 KB: the workgroup's logits behind the buffers
 constexpr int kLoadsPerWave = 2 * ((kInstrPerArray + 3) / 4);      // per tile and wave, keys + values: 10
 
-template <int KS>
+// RAW: `panels` is the weight tensor as the caller holds it ([Hkv][C][2D][KS]); the workgroup brings its head's rows
+// into LDS and sorts them into register order itself, which saves callers that have not prepared panels a launch.
+template <int KS, bool RAW>
 __global__ void __launch_bounds__(kThreads, 1)
 score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int64_t st, int64_t sh,
                  const bf16_t* __restrict__ panels, const float* __restrict__ bias,
@@ -112,16 +114,37 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
       dma16(rs_v, dst + (uint32_t)kArrayB, voff);
     }
   };
-  // The head's weight panels (KS * 8 KB, already in register order [tap][slice][lane][8]) go through LDS as well, once
-  // per workgroup: into the fourth tile buffer and the logit area behind it, both idle until the first tile is done.
-  const u32x4 rs_w = make_raw_rsrc(panels + (int64_t)h * KS * NSL * kWave * 8, (uint32_t)(KS * NSL * 1024));
+  // The head's weights go through LDS as well, once per workgroup: into the fourth tile buffer and the logit area
+  // behind it, both idle until the first tile is done.  Either the panels (KS * 8 KB, already in register order
+  // [tap][slice][lane][8]), or the caller's rows [c][m][tap]: a row (16 * KS pieces of 16 bytes) is followed by one
+  // piece of padding in LDS, so that the 16-byte reads of 16 lanes (16 channels, same column) cover all banks; which
+  // piece a lane fetches is computed from where it lands, rows past C and the padding are out of range (zeros).
+  constexpr int kRawPieces = 16 * KS;                                // per channel row: 128 inputs x KS taps x 2 bytes
+  constexpr int kRawStrideB = (kRawPieces + 1) * 16;
+  constexpr int kRawInstr = (CP * (kRawPieces + 1) + 63) / 64;       // wave instructions that cover 32 padded rows
+  constexpr int kWeightLoads = RAW ? (kRawInstr + 3) / 4 : 2 * KS;   // per wave
   constexpr int kWeightBase = (kBufs - 1) * kBufB;
   static_assert(kWeightBase + KS * NSL * 1024 <= kLdsB, "weight panels fit behind the third tile buffer");
-  static_assert(2 * KS + 2 * kLoadsPerWave <= 63, "loads in flight fit the vmcnt counter");
+  static_assert(kWeightBase + kRawInstr * 1024 <= kLdsB, "padded weight rows fit behind the third tile buffer");
+  static_assert(kWeightLoads + 3 * kLoadsPerWave <= 63, "loads in flight fit the vmcnt counter");
   issue_tile(0);
+  if constexpr (RAW) {
+    const u32x4 rs_w = make_raw_rsrc(panels + (int64_t)h * C * C2 * KS, (uint32_t)(C * kRawPieces * 16));
 #pragma unroll
-  for (int i = 0; i < 2 * KS; ++i)
-    dma16(rs_w, lds_base + (uint32_t)(kWeightBase + (wv + 4 * i) * 1024), (uint32_t)((wv + 4 * i) * 1024 + lane * 16));
+    for (int i = 0; i < kWeightLoads; ++i) {
+      const int jj = wv + 4 * i;
+      const int j = jj < kRawInstr ? jj : wv;           // a turn past the end fetches the wave's first block again
+      const int q = 64 * j + lane;                      // piece of the padded LDS image
+      const int c = q / (kRawPieces + 1), col = q - c * (kRawPieces + 1);
+      const uint32_t voff = col < kRawPieces ? (uint32_t)(c * kRawPieces + col) * 16u : 0x80000000u;
+      dma16(rs_w, lds_base + (uint32_t)(kWeightBase + j * 1024), voff);
+    }
+  } else {
+    const u32x4 rs_w = make_raw_rsrc(panels + (int64_t)h * KS * NSL * kWave * 8, (uint32_t)(KS * NSL * 1024));
+#pragma unroll
+    for (int i = 0; i < kWeightLoads; ++i)
+      dma16(rs_w, lds_base + (uint32_t)(kWeightBase + (wv + 4 * i) * 1024), (uint32_t)((wv + 4 * i) * 1024 + lane * 16));
+  }
   if (n_tiles > 1) issue_tile(1);
   if (n_tiles > 2) issue_tile(2);
   // first tile and weights: at most the two later tiles may still be in flight
@@ -130,11 +153,30 @@ score_reg_kernel(const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, int
   else wait_loads();
   __syncthreads();
   bf16x8 wreg[KS][NSL];
+  if constexpr (RAW) {
+    // lane (c = ql, hb) owns inputs m = 16*sl + 8*hb .. +7 of every tap: 8 * KS consecutive elements of row c
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    const unsigned char* wrow = lds + kWeightBase + ql * kRawStrideB + hb * (8 * KS * 2);
 #pragma unroll
-  for (int tap = 0; tap < KS; ++tap)
+    for (int sl = 0; sl < NSL; ++sl) {
+      u16x8 run[KS];
 #pragma unroll
-    for (int sl = 0; sl < NSL; ++sl)
-      wreg[tap][sl] = *reinterpret_cast<const bf16x8*>(lds + kWeightBase + (tap * NSL + sl) * 1024 + lane * 16);
+      for (int i = 0; i < KS; ++i) run[i] = *reinterpret_cast<const u16x8*>(wrow + sl * (16 * KS * 2) + 16 * i);
+#pragma unroll
+      for (int tap = 0; tap < KS; ++tap) {
+        u16x8 w;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[e] = run[(e * KS + tap) / 8][(e * KS + tap) % 8];
+        wreg[tap][sl] = __builtin_bit_cast(bf16x8, w);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int tap = 0; tap < KS; ++tap)
+#pragma unroll
+      for (int sl = 0; sl < NSL; ++sl)
+        wreg[tap][sl] = *reinterpret_cast<const bf16x8*>(lds + kWeightBase + (tap * NSL + sl) * 1024 + lane * 16);
+  }
   // Pin the weights into their registers here, before the loop's first barrier lets the fourth buffer be refilled.
 #pragma unroll
   for (int tap = 0; tap < KS; ++tap)
@@ -226,14 +268,14 @@ score_reg_panels_kernel(const uint16_t* __restrict__ W, uint16_t* __restrict__ p
   panels[idx] = c < C ? W[((h * C + c) * C2 + m) * ks + tap] : (uint16_t)0;
 }
 
-template <int KS>
+template <int KS, bool RAW>
 hipError_t run(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st, int64_t sh,
-               const SeqView& sv, float* logits, const void* panels, hipStream_t stream) {
+               const SeqView& sv, float* logits, const void* weights, hipStream_t stream) {
   const int gt = pick_group_tiles(sv, cfg.Hkv, TM, kMaxGroupTiles);
   const int64_t groups_upper = (sv.total_tokens + gt * TM - 1) / (gt * TM) + sv.n_seqs;
-  hipLaunchKernelGGL(score_reg_kernel<KS>, dim3((unsigned)(groups_upper * cfg.Hkv)), dim3(kThreads), 0, stream,
+  hipLaunchKernelGGL((score_reg_kernel<KS, RAW>), dim3((unsigned)(groups_upper * cfg.Hkv)), dim3(kThreads), 0, stream,
                      static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), st, sh,
-                     static_cast<const bf16_t*>(panels), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out), cnn.b_out,
+                     static_cast<const bf16_t*>(weights), cnn.bias[0], static_cast<const bf16_t*>(cnn.w_out), cnn.b_out,
                      cnn.c_out[0], cnn.dilation[0], sv.cu_seqlens, sv.n_seqs, sv.total_tokens, logits, gt, cfg.Hkv);
   return hipGetLastError();
 }
@@ -259,11 +301,18 @@ bool score_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   return (ks - 1) / 2 * cnn.dilation[0] <= kMaxRho;
 }
 
+bool score_reg_takes_raw_weights(const ltea_cnn& cnn) { return (reinterpret_cast<uintptr_t>(cnn.w[0]) & 15u) == 0; }
+
 hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
                             int64_t sh, const SeqView& sv, float* logits, const void* panels, hipStream_t stream) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cnn.kernel[0] == 3 ? run<3>(cfg, cnn, k, v, st, sh, sv, logits, panels, stream)
-                            : run<5>(cfg, cnn, k, v, st, sh, sv, logits, panels, stream);
+  if (panels == nullptr) {   // the kernel sorts the caller's weight rows into register order itself
+    if (!score_reg_takes_raw_weights(cnn)) return hipErrorInvalidValue;
+    return cnn.kernel[0] == 3 ? run<3, true>(cfg, cnn, k, v, st, sh, sv, logits, cnn.w[0], stream)
+                              : run<5, true>(cfg, cnn, k, v, st, sh, sv, logits, cnn.w[0], stream);
+  }
+  return cnn.kernel[0] == 3 ? run<3, false>(cfg, cnn, k, v, st, sh, sv, logits, panels, stream)
+                            : run<5, false>(cfg, cnn, k, v, st, sh, sv, logits, panels, stream);
 }
 
 }  // namespace ltea
