@@ -62,6 +62,9 @@ hipError_t launch_score_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void
 // registers and the tokens loaded straight into LDS; its panels have the size of the general kernel's but are ordered
 // as the registers hold them.  launch_score_deep and launch_score_deep_panels hand over to these where they apply.
 bool score_deep_reg_supported(const ltea_cfg& cfg, const ltea_cnn& cnn);
+// launch_score_deep_reg with panels == nullptr reads cnn.w[0..2] as the caller holds them and sorts them inside the
+// kernel; that needs the three tensors 16-byte aligned.
+bool score_deep_reg_takes_raw_weights(const ltea_cnn& cnn);
 hipError_t launch_score_deep_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn, void* panels, hipStream_t stream);
 // row_valid (optional, device, one byte per token row): windows mode for the decode step.  The rows are many
 // independent short windows laid end to end with at least max(dilation) rows of zeros between them; a 0 byte marks a

@@ -369,6 +369,9 @@ hipError_t launch_score_deep(const ltea_cfg& cfg, const ltea_cnn& cnn, const voi
   const DeepPlan p = plan(cfg, cnn);
   if (!p.ok) return hipErrorInvalidValue;
   const void* panels = cnn.panels;
+  // the register-stationary kernel sorts unprepared weights itself (no launch for that) when they are 16-byte aligned
+  if (panels == nullptr && score_deep_reg_supported(cfg, cnn) && score_deep_reg_takes_raw_weights(cnn))
+    return launch_score_deep_reg(cfg, cnn, k, v, st, sh, sv, logits, nullptr, stream, row_valid);
   if (panels == nullptr) {            // not prepared by the caller: re-lay the weights into the workspace now
     hipError_t e = launch_score_deep_panels(cfg, cnn, workspace, stream);
     if (e != hipSuccess) return e;

@@ -52,11 +52,20 @@ constexpr int kBlocks1 = 3 * 8 * 2, kBlocks2 = 3 * 4, kBlocks3 = 3 * 2;   // 1 K
 constexpr int kBlocks = kBlocks1 + kBlocks2 + kBlocks3;                   // 66 per head
 constexpr int kWeightLoadsPerWave = (kBlocks + 3) / 4;
 static_assert(kBlocks * 1024 <= 2 * kBufB, "the weights pass through the second and third tile buffers");
+// Weights that were not re-laid beforehand come as the caller's rows [c][m][tap] (16-byte pieces: 3 * c_in / 8 per row)
+// and are sorted into operands by the workgroup.  In LDS every row is followed by one piece of padding, which makes the
+// row strides 196, 100 and 52 words: the 16-byte reads of 16 lanes (16 channels, same column) then cover all banks.
+// Each tensor's image is rounded up to whole wave instructions (1 KB); the third layer brings its 16 real rows only.
+constexpr int kRawP1 = 3 * 2 * 64 / 8, kRawP2 = 3 * C1 / 8, kRawP3 = 3 * C2 / 8;        // pieces per row: 48, 24, 12
+constexpr int kRawI1 = (C1 * (kRawP1 + 1) + 63) / 64, kRawI2 = (C2 * (kRawP2 + 1) + 63) / 64,
+              kRawI3 = (C3 * (kRawP3 + 1) + 63) / 64;                                   // wave instructions: 49, 13, 4
+static_assert(kRawI1 + kRawI2 + kRawI3 <= kBlocks, "same number of weight loads per wave either way");
 static_assert(kLoadsPerWave + kWeightLoadsPerWave <= 63 && 2 * kLoadsPerWave <= 63, "loads in flight fit vmcnt");
 
 struct DeepRegArgs {
   const bf16_t* k; const bf16_t* v; int64_t st, sh;
-  const bf16_t* panels;                       // [Hkv][66][64 lanes][8]
+  const bf16_t* panels;                       // [Hkv][66][64 lanes][8], or null: the three tensors below as the caller holds them
+  const bf16_t* w1; const bf16_t* w2; const bf16_t* w3;   // [Hkv][c_out][c_in][3]
   const float* bias1; const float* bias2; const float* bias3; const bf16_t* w_out; const float* b_out;
   int d1, d2, d3;
   const int32_t* cu; int n_seqs; int64_t total; float* logits; int group_tiles, Hkv;
@@ -134,11 +143,32 @@ score_deep_reg_kernel(const DeepRegArgs a) {
     }
   };
   issue_tile(0, 0);
+  const bool raw = a.panels == nullptr;
+  if (!raw) {
 #pragma unroll
-  for (int i = 0; i < kWeightLoadsPerWave; ++i) {
-    const int bb = wv + 4 * i;
-    const int b = bb < kBlocks ? bb : wv;
-    dma16(rs_w, lds_base + (uint32_t)(kBufB + b * 1024), (uint32_t)(b * 1024 + lane * 16));
+    for (int i = 0; i < kWeightLoadsPerWave; ++i) {
+      const int bb = wv + 4 * i;
+      const int b = bb < kBlocks ? bb : wv;
+      dma16(rs_w, lds_base + (uint32_t)(kBufB + b * 1024), (uint32_t)(b * 1024 + lane * 16));
+    }
+  } else {
+    // instruction b fills pieces 64*b .. 64*b+63 of the padded images [layer 1 | layer 2 | layer 3]; which piece of
+    // which row a lane fetches follows from where it lands; padding and rows past the tensor are out of range (zeros)
+    const u32x4 rs_1 = make_raw_rsrc(a.w1 + (int64_t)h * C1 * 2 * 64 * 3, (uint32_t)(C1 * kRawP1 * 16));
+    const u32x4 rs_2 = make_raw_rsrc(a.w2 + (int64_t)h * C2 * C1 * 3, (uint32_t)(C2 * kRawP2 * 16));
+    const u32x4 rs_3 = make_raw_rsrc(a.w3 + (int64_t)h * C3 * C2 * 3, (uint32_t)(C3 * kRawP3 * 16));
+#pragma unroll
+    for (int i = 0; i < kWeightLoadsPerWave; ++i) {
+      const int bb = wv + 4 * i;
+      const int b = bb < kRawI1 + kRawI2 + kRawI3 ? bb : wv;
+      const int layer = b < kRawI1 ? 0 : (b < kRawI1 + kRawI2 ? 1 : 2);
+      const int q = 64 * (b - (layer == 0 ? 0 : (layer == 1 ? kRawI1 : kRawI1 + kRawI2))) + lane;
+      const int pr = layer == 0 ? kRawP1 : (layer == 1 ? kRawP2 : kRawP3);
+      const int c = q / (pr + 1), col = q - c * (pr + 1);
+      const uint32_t voff = col < pr ? (uint32_t)(c * pr + col) * 16u : 0x80000000u;
+      const u32x4 rs = layer == 0 ? rs_1 : (layer == 1 ? rs_2 : rs_3);
+      dma16(rs, lds_base + (uint32_t)(kBufB + b * 1024), voff);
+    }
   }
   wait_loads();
   __syncthreads();
@@ -146,7 +176,35 @@ score_deep_reg_kernel(const DeepRegArgs a) {
   // ---- weights -> registers: A operand of (tap, slice[, channel block]): output channel ql (+ 32 per block), input
   // channels 16*slice + 8*hb .. +7 --------------------------------------------------------------------------------
   bf16x8 w1[3][8][2], w2[3][4], w3[3][2];
-  {
+  if (raw) {
+    // a lane's inputs 16*slice + 8*hb .. +7 of all three taps are 24 consecutive elements of its channel's row
+    typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+    auto sort_taps = [&](const unsigned char* src, bf16x8& t0, bf16x8& t1, bf16x8& t2, bool real) {
+      u16x8 run[3];
+#pragma unroll
+      for (int i = 0; i < 3; ++i) run[i] = *reinterpret_cast<const u16x8*>(src + 16 * i);
+      u16x8 w[3];
+#pragma unroll
+      for (int tap = 0; tap < 3; ++tap)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w[tap][e] = real ? run[(e * 3 + tap) / 8][(e * 3 + tap) % 8] : (unsigned short)0;
+      t0 = __builtin_bit_cast(bf16x8, w[0]); t1 = __builtin_bit_cast(bf16x8, w[1]); t2 = __builtin_bit_cast(bf16x8, w[2]);
+    };
+    const unsigned char* img = lds + kBufB + hb * 48;
+#pragma unroll
+    for (int sl = 0; sl < 8; ++sl)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+        sort_taps(img + (ql + 32 * mb) * ((kRawP1 + 1) * 16) + sl * 96, w1[0][sl][mb], w1[1][sl][mb], w1[2][sl][mb], true);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      sort_taps(img + kRawI1 * 1024 + ql * ((kRawP2 + 1) * 16) + kk * 96, w2[0][kk], w2[1][kk], w2[2][kk], true);
+    // the third layer has 16 channels: the upper half of the MFMA rows is zero
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+      sort_taps(img + (kRawI1 + kRawI2) * 1024 + (ql & (C3 - 1)) * ((kRawP3 + 1) * 16) + kk * 96, w3[0][kk], w3[1][kk],
+                w3[2][kk], ql < C3);
+  } else {
     const unsigned char* wl = lds + kBufB + lane * 16;
 #pragma unroll
     for (int tap = 0; tap < 3; ++tap)
@@ -164,16 +222,16 @@ score_deep_reg_kernel(const DeepRegArgs a) {
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
         w3[tap][kk] = *reinterpret_cast<const bf16x8*>(wl + (kBlocks1 + kBlocks2 + tap * 2 + kk) * 1024);
-    // pin them into their registers before the buffers they came through are refilled
+  }
+  // pin them into their registers before the buffers they came through are refilled
 #pragma unroll
-    for (int tap = 0; tap < 3; ++tap) {
+  for (int tap = 0; tap < 3; ++tap) {
 #pragma unroll
-      for (int sl = 0; sl < 8; ++sl) asm volatile("" : "+v"(w1[tap][sl][0]), "+v"(w1[tap][sl][1]));
+    for (int sl = 0; sl < 8; ++sl) asm volatile("" : "+v"(w1[tap][sl][0]), "+v"(w1[tap][sl][1]));
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(w2[tap][kk]));
+    for (int kk = 0; kk < 4; ++kk) asm volatile("" : "+v"(w2[tap][kk]));
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) asm volatile("" : "+v"(w3[tap][kk]));
-    }
+    for (int kk = 0; kk < 2; ++kk) asm volatile("" : "+v"(w3[tap][kk]));
   }
   __syncthreads();
   if (n_tiles > 1) issue_tile(1, 1);
@@ -385,13 +443,21 @@ hipError_t launch_score_deep_reg_panels(const ltea_cfg& cfg, const ltea_cnn& cnn
   return hipGetLastError();
 }
 
+bool score_deep_reg_takes_raw_weights(const ltea_cnn& cnn) {
+  return ((reinterpret_cast<uintptr_t>(cnn.w[0]) | reinterpret_cast<uintptr_t>(cnn.w[1]) |
+           reinterpret_cast<uintptr_t>(cnn.w[2])) & 15u) == 0;
+}
+
 hipError_t launch_score_deep_reg(const ltea_cfg& cfg, const ltea_cnn& cnn, const void* k, const void* v, int64_t st,
                                  int64_t sh, const SeqView& sv, float* logits, const void* panels, hipStream_t stream,
                                  const uint8_t* row_valid) {
   if (sv.total_tokens == 0) return hipSuccess;
   DeepRegArgs a;
   a.k = static_cast<const bf16_t*>(k); a.v = static_cast<const bf16_t*>(v); a.st = st; a.sh = sh;
-  a.panels = static_cast<const bf16_t*>(panels);
+  a.panels = static_cast<const bf16_t*>(panels);    // null: the kernel sorts the caller's weight rows itself
+  a.w1 = static_cast<const bf16_t*>(cnn.w[0]); a.w2 = static_cast<const bf16_t*>(cnn.w[1]);
+  a.w3 = static_cast<const bf16_t*>(cnn.w[2]);
+  if (panels == nullptr && !score_deep_reg_takes_raw_weights(cnn)) return hipErrorInvalidValue;
   a.bias1 = cnn.bias[0]; a.bias2 = cnn.bias[1]; a.bias3 = cnn.bias[2];
   a.w_out = static_cast<const bf16_t*>(cnn.w_out); a.b_out = cnn.b_out;
   a.d1 = cnn.dilation[0]; a.d2 = cnn.dilation[1]; a.d3 = cnn.dilation[2];

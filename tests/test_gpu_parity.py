@@ -96,6 +96,37 @@ def test_score_paper_stack_dilations(dilation):
     logit_eps(zg, z64, w.dtype)
 
 
+@pytest.mark.parametrize("stack", ["one_layer", "paper"])
+def test_score_weights_prepared_unprepared_and_unaligned(stack):
+    """The register-stationary kernels take their weights three ways: panels prepared beforehand, the caller's
+    tensors sorted inside the kernel (16-byte aligned), and the caller's tensors at an odd 2-byte offset, which go
+    through the re-layout launch.  All three give the same logits bit for bit, and those match the oracle."""
+    if stack == "one_layer":
+        w = wl.make_prefill("wpaths1", 83, "bf16", [1500 + 3, 260], 3, 3, 64, 64, 16, 0, 0.0, cnn_kernel=(5,),
+                            cnn_channels=(24,), cnn_dilation=(1,), qkv_scale=0.125, w_std=0.05)
+    else:
+        w = wl.make_prefill("wpaths3", 84, "bf16", [1500 + 3, 260], 4, 2, 64, 64, 16, 0, 0.0, cnn_kernel=(3, 3, 3),
+                            cnn_channels=(64, 32, 16), cnn_dilation=(2, 2, 2), qkv_scale=1.0, w_std=0.08)
+    z64 = orc.score(w.k, w.v, oracle_cnn(w.cnn), w.cu_seqlens)
+    d = DeviceWorkload(w)
+    z_plain = to_np(B.ltea_score(d.cfg, d.cnn, d.k, d.v, d.cu, d.max_seqlen))
+    logit_eps(z_plain, z64, w.dtype)
+    c = w.cnn
+    prepared = B.prepare_cnn(d.cfg, B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype))
+    z_prep = to_np(B.ltea_score(d.cfg, prepared, d.k, d.v, d.cu, d.max_seqlen))
+    assert np.array_equal(z_plain, z_prep)
+    odd = B.upload_cnn(c.kernel, c.dilation, c.w, c.bias, c.w_out, c.b_out, w.dtype)
+    for l in range(len(c.kernel)):          # the same values one element into a larger allocation
+        src = odd.tensors[2 * l]
+        store = torch.zeros(src.numel() + 8, dtype=src.dtype, device=src.device)
+        store[1:1 + src.numel()] = src.reshape(-1)
+        odd.tensors.append(store)
+        odd.struct.w[l] = store.data_ptr() + src.element_size()
+        assert odd.struct.w[l] % 16 != 0
+    z_odd = to_np(B.ltea_score(d.cfg, odd, d.k, d.v, d.cu, d.max_seqlen))
+    assert np.array_equal(z_plain, z_odd)
+
+
 def test_score_strided_views():
     """K and V as strided views of one packed [T, 3, H, D] buffer."""
     w, cfg, cnn, (out, states, z64, kept) = oracle_prefill("bf16_d64")
