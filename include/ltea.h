@@ -102,8 +102,10 @@ typedef struct ltea_cache {
 } ltea_cache;
 
 /* The matrix-core scoring kernels read the conv weights re-laid as tap-major panels.  By default every call that
- * scores re-lays them into its workspace (a few microseconds); weights that do not change between calls can be
- * prepared once instead: ltea_cnn_prepare fills `panels` (device, ltea_cnn_panels_bytes bytes, 0 if this
+ * scores re-lays them: inside the scoring launch itself where the weights fit the register file (bf16, D = 64: one
+ * layer of kernel size 3 or 5, and the three-layer stack of Appendix A) and the weight tensors are 16-byte aligned,
+ * else with a launch of its own into the workspace (a few microseconds); weights that do not change between calls
+ * can be prepared once instead: ltea_cnn_prepare fills `panels` (device, ltea_cnn_panels_bytes bytes, 0 if this
  * configuration runs on kernels that need none), and a ltea_cnn whose `panels` member points there makes every
  * entry point skip the re-layout.  The caller keeps `panels` alive and redoes the preparation when the weights
  * change; cnn->panels is ignored by ltea_cnn_prepare itself. */
