@@ -55,7 +55,13 @@ template <int D> struct TileRegs {
   int pos;
 };
 
-template <int D, int QB>
+// HW = query heads per workgroup.  1: the four waves take four consecutive blocks of 32 query positions of one head.
+// 4 (grouped-query shapes with a multiple of four query heads per KV head): the four waves take the SAME 32 positions
+// of four query heads that share the KV head.  The K/V tiles are shared either way, but with HW = 4 every wave sees the
+// same window, so a tile is plain, masked or out of reach for all four at once (with HW = 1 the waves' windows are
+// shifted by 32 positions each, the workgroup's key range is 96 positions longer, and whenever one wave has a masked
+// tile the other three wait for it at the tile barrier).
+template <int D, int QB, int HW>
 __global__ void __launch_bounds__(kThreads, D == 64 ? 3 : 2)
 attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, const bf16_t* __restrict__ k,
                       const bf16_t* __restrict__ v, int64_t kv_st, int64_t kv_sh, const int32_t* __restrict__ cu,
@@ -67,6 +73,8 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   using G = Geo<D, QB>;
   using TR = TileRegs<D>;
   constexpr int BM = G::BM, KS = G::KS, VS = G::VS, kBuf = G::kBuf;
+  constexpr int BMQ = BM / HW;     // query positions per workgroup (BM = rows of all its waves)
+  static_assert(HW == 1 || HW == 4, "one head, or one head per wave");
   static_assert(2 * kBuf >= BM * G::OS, "epilogue staging must fit in the tile buffers");
   __shared__ __align__(16) bf16_t lds[2 * kBuf];
   __shared__ int pos_lds[2][BN];
@@ -79,24 +87,25 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int per_xcd = (n_work + 7) / 8;
   const int work = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
   if (work >= n_work) return;
-  int hq, flat_tile;
-  const bool whole_heads = Hq % 8 == 0;
+  int unit, flat_tile;                      // unit = query head (HW = 1) or group of HW query heads
+  const int units = Hq / HW;
+  const bool whole_heads = units % 8 == 0;
   if (whole_heads) {
-    const int hpx = Hq / 8, in_xcd = blockIdx.x / 8;         // per_xcd == hpx * tiles_upper
-    hq = (blockIdx.x % 8) * hpx + in_xcd % hpx;
+    const int hpx = units / 8, in_xcd = blockIdx.x / 8;      // per_xcd == hpx * tiles_upper
+    unit = (blockIdx.x % 8) * hpx + in_xcd % hpx;
     flat_tile = in_xcd / hpx;
   } else {
-    hq = work / tiles_upper;
-    flat_tile = work - hq * tiles_upper;
+    unit = work / tiles_upper;
+    flat_tile = work - unit * tiles_upper;
   }
   // cu packs the query / output rows.  Normally it packs the keys as well; with kv_start / kv_len given, the keys
   // of sequence s are rows kv_start[s] .. kv_start[s] + kv_len[s] - 1 of k / v and the queries are the last
   // cu[s+1] - cu[s] positions of that key sequence (continuation of a prefill).
   int tile, s, n, lo_q;
   if (whole_heads && kv_start == nullptr) {
-    if (!locate_tile_late_first(cu, n_seqs, BM, (window + BM - 1) / BM, flat_tile, s, tile, lo_q, n)) return;
+    if (!locate_tile_late_first(cu, n_seqs, BMQ, (window + BMQ - 1) / BMQ, flat_tile, s, tile, lo_q, n)) return;
   } else {
-    if (!locate_tile(cu, n_seqs, BM, flat_tile, s, tile, lo_q, n)) return;
+    if (!locate_tile(cu, n_seqs, BMQ, flat_tile, s, tile, lo_q, n)) return;
   }
   int64_t lo = lo_q;
   int q_begin = 0;
@@ -106,14 +115,15 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     n = kv_len[s];
     q_begin = n - nq;
   }
-  const int h = hq / (Hq / Hkv);
+  const int h = (unit * HW) / (Hq / Hkv);
   const int64_t head = (int64_t)s * Hkv + h;
-  const int i0 = q_begin + tile * BM;
+  const int i0 = q_begin + tile * BMQ;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, hb = lane >> 5;
-  const int r0 = i0 + 32 * QB * wv;         // first query row of this wave
+  const int hq = HW == 1 ? unit : unit * HW + wv;                 // this wave's query head
+  const int r0 = i0 + (HW == 1 ? 32 * QB * wv : 0);               // first query row of this wave
   const int r_hi = r0 + 32 * QB - 1;        // last query row of this wave
 
   // ---- Q fragments (B operand of S^T): lane holds Q[row][16*ks + 8*hb .. +7] for its QB rows ------------
@@ -128,7 +138,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   }
 
   // ---- tile schedule ------------------------------------------------------------------------------------
-  const int i_last = (i0 + BM < n ? i0 + BM : n) - 1;            // last real query row of the workgroup
+  const int i_last = (i0 + BMQ < n ? i0 + BMQ : n) - 1;          // last real query row of the workgroup
   const int jlo = i0 - window + 1 > 0 ? i0 - window + 1 : 0;
   const int jt0 = (jlo / BN) * BN;
   const int n_win_tiles = (i_last - jt0) / BN + 1;
@@ -405,7 +415,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     const float inv = 1.0f / l_row;
     if (lse != nullptr && hb == 0) {
       // natural-log normaliser of the scaled scores (m_run is kept in the base-2 domain); wanted by a backward pass
-      const int row = 32 * QB * wv + 32 * qb + ql;
+      const int row = (HW == 1 ? 32 * QB * wv : 0) + 32 * qb + ql;
       if (i0 + row < n) lse[(int64_t)hq * lse_stride + lo_q + i0 + row - q_begin] = (m_run[qb] + __log2f(l_row)) * 0.6931471805599453f;
     }
     bf16_t* orow = lds + (32 * QB * wv + 32 * qb + ql) * G::OS + 4 * hb;
@@ -421,28 +431,31 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   }
   __syncthreads();
   {
-    bf16_t* obase = out + ((int64_t)(lo_q + i0 - q_begin) * Hq + hq) * D;
+    // staging row = 32*QB*wave + position block: with HW = 1 all rows are positions of one head, with HW = 4 the
+    // wave index is the head inside the group
+    bf16_t* obase = out + ((int64_t)(lo_q + i0 - q_begin) * Hq + unit * HW) * D;
     const int64_t orow_stride = (int64_t)Hq * D;
 #pragma unroll
     for (int p = 0; p < BM / G::RPP; ++p) {
       const int row = p * G::RPP + k_row;
-      if (i0 + row < n)
-        *reinterpret_cast<u32x4*>(obase + row * orow_stride + k_piece * 8) =
+      const int prow = HW == 1 ? row : row % (32 * QB), hd = HW == 1 ? 0 : row / (32 * QB);
+      if (i0 + prow < n)
+        *reinterpret_cast<u32x4*>(obase + prow * orow_stride + hd * D + k_piece * 8) =
             *reinterpret_cast<const u32x4*>(lds + row * G::OS + k_piece * 8);
     }
   }
 }
 
-template <int D, int QB>
+template <int D, int QB, int HW>
 hipError_t run(const ltea_cfg& cfg, const void* q, int64_t q_st, int64_t q_sh, const void* k, const void* v,
                int64_t kv_st, int64_t kv_sh, const SeqView& sv, const ltea_cache& c, void* out,
                const int32_t* kv_start, const int32_t* kv_len, float* lse, hipStream_t stream) {
-  constexpr int BM = Geo<D, QB>::BM;
+  constexpr int BMQ = Geo<D, QB>::BM / HW;
   const float scale = cfg.softmax_scale > 0.f ? cfg.softmax_scale : 1.0f / sqrtf((float)cfg.D);
-  const int64_t tiles_upper = (sv.total_tokens + BM - 1) / BM + sv.n_seqs;
-  const int64_t n_work = tiles_upper * cfg.Hq;
+  const int64_t tiles_upper = (sv.total_tokens + BMQ - 1) / BMQ + sv.n_seqs;
+  const int64_t n_work = tiles_upper * (cfg.Hq / HW);
   const int64_t grid = (n_work + 7) / 8 * 8;
-  hipLaunchKernelGGL((attention_mfma_kernel<D, QB>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
+  hipLaunchKernelGGL((attention_mfma_kernel<D, QB, HW>), dim3((unsigned)grid), dim3(kThreads), 0, stream,
                      static_cast<const bf16_t*>(q), q_st, q_sh, static_cast<const bf16_t*>(k),
                      static_cast<const bf16_t*>(v), kv_st, kv_sh, sv.cu_seqlens, sv.n_seqs, (int)tiles_upper,
                      (int)n_work, cfg.Hq, cfg.Hkv, cfg.window, cfg.budget, scale * 1.4426950408889634f,
@@ -464,8 +477,13 @@ hipError_t launch_attention_mfma(const ltea_cfg& cfg, const void* q, int64_t q_s
                                  void* out, hipStream_t stream, const int32_t* kv_start, const int32_t* kv_len,
                                  float* lse) {
   if (sv.total_tokens == 0) return hipSuccess;
-  return cfg.D == 64 ? run<64, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream)
-                     : run<128, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream);
+  // grouped-query shapes with a multiple of four query heads per KV head: one query head per wave (see the kernel)
+  const bool by_head = (cfg.Hq / cfg.Hkv) % 4 == 0;
+  if (cfg.D == 64)
+    return by_head ? run<64, 1, 4>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream)
+                   : run<64, 1, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream);
+  return by_head ? run<128, 1, 4>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream)
+                 : run<128, 1, 1>(cfg, q, q_st, q_sh, k, v, kv_st, kv_sh, sv, c, out, kv_start, kv_len, lse, stream);
 }
 
 }  // namespace ltea
