@@ -9,9 +9,10 @@
 //                         one workgroup per (KV head, 64 sequences); the conv over the batch is a small GEMM
 //                         [sequences x taps*2D] . [taps*2D x C] on v_mfma_f32_16x16x32_bf16 with both operands
 //                         read straight from global memory (weights are shared by all sequences of a head).
-//                         Multi-layer bf16 (given the larger workspace): two launches before this one pack the
-//                         receptive-field windows of all sequences as tiny sequences and run the fused prefill
-//                         scoring kernel over them; the role here only picks each window's centre logit.
+//                         Multi-layer bf16 (given the larger workspace): a packing role of this launch (one
+//                         workgroup per sequence) copies the receptive-field windows of all sequences into the
+//                         workspace as tiny sequences; the fused prefill scoring kernel runs over them between
+//                         this launch and the finishing one, which picks each window's centre logit.
 //                         Otherwise (fp32, unusual stacks): one workgroup per (sequence, head), activation pyramid
 //                         in LDS.  These few workgroups are dispatched first and hide under the streaming.
 //     attention role      the memory-bound part: grid (sequence x KV head) x splits; each workgroup streams its
@@ -71,6 +72,8 @@ struct StepParams {
   const float* pre_logits;
   int64_t pre_total;
   int pre_stride;            // rows per sequence in pre_logits (2*rho+1, or more when the windows are packed with gaps)
+  // packing role of the main launch (multi-layer bf16 CNN): where the windows go; n_pack_blocks = 0 switches it off
+  void* pk_k; void* pk_v; int32_t* pk_cu2; uint8_t* pk_row_valid; int n_pack_blocks;
   // Lazy mode (scores come from separate batched launches between steps): nothing is scored here, n_scored is
   // left alone, and a token that leaves the window without a final logit is reported through `status`.
   int lazy;
@@ -390,6 +393,77 @@ __device__ __forceinline__ void score_new_tokens_mfma(const CnnDev& cnn, const S
   }
 }
 
+// Receptive-field windows of the token being finalised, packed for the prefill scoring kernels: sequence b gets
+// rows b*R .. b*R + len - 1 (R = 2*rho + 1) holding positions max(0, t - 2*rho) .. t (the ring rows and, last, the
+// incoming token); a second, possibly empty pseudo-sequence covers the unused rest of the R rows so that the packing
+// stays contiguous without a prefix sum over the batch: cu2[2b] = b*R, cu2[2b+1] = b*R + len, cu2[2B] = B*R.
+// Rotary models (rope.cos != null): the ring holds rotated keys, which are rotated back here; the incoming token's
+// scoring key is kf_new when given, else k_new rotated back at position t.
+// One workgroup of 256 threads per sequence b.  ROT = false compiles the rotary branch out (the main launch's packing role).
+template <typename T, bool ROT>
+__device__ __forceinline__ void pack_window(const CacheDev& C, const T* __restrict__ k_new, const T* __restrict__ v_new,
+                                            const T* __restrict__ kf_new, const RopeDev& rope, int32_t* __restrict__ status,
+                                            T* __restrict__ win_k, T* __restrict__ win_v, int32_t* __restrict__ cu2, int B,
+                                            int Hkv, int D, int window, int rho, int stride_rows,
+                                            uint8_t* __restrict__ row_valid, int b) {
+  constexpr int EPP = Elems<T>::N;
+  const int R = stride_rows;     // 2*rho + 1, or more: windows mode (row_valid given), the rows in between are zeros
+  const int t = C.n_seen[b];
+  const int first = t - 2 * rho > 0 ? t - 2 * rho : 0;
+  const int len = t - first + 1;
+  const int pieces = D / EPP;                                 // 16-byte pieces per row
+  if (row_valid == nullptr) {
+    if (threadIdx.x == 0) {
+      cu2[2 * b] = b * R;
+      cu2[2 * b + 1] = b * R + len;
+      if (b == B - 1) cu2[2 * B] = B * R;
+    }
+  } else {
+    // one sequence of B * R rows; which rows are tokens is said per row, and the others are cleared
+    if (threadIdx.x == 0 && b == 0) { cu2[0] = 0; cu2[1] = B * R; }
+    for (int r = threadIdx.x; r < R; r += 256) row_valid[b * R + r] = r < len ? 1 : 0;
+    const int gap = (R - len) * Hkv * pieces;
+    const int64_t dst0 = (int64_t)(b * R + len) * Hkv * D;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    for (int i = threadIdx.x; i < gap; i += 256) {
+      reinterpret_cast<u32x4*>(win_k + dst0)[i] = zero4;
+      reinterpret_cast<u32x4*>(win_v + dst0)[i] = zero4;
+    }
+  }
+  const int items = len * Hkv * pieces;
+  bool out_of_tables = false;
+  for (int i = threadIdx.x; i < items; i += 256) {
+    const int pc = i % pieces, h = (i / pieces) % Hkv, r = i / (pieces * Hkv);
+    const int p = first + r;
+    const int64_t head = (int64_t)b * Hkv + h;
+    const T* sk = p == t ? k_new + head * D : static_cast<const T*>(C.k_win) + (head * window + p % window) * D;
+    const T* sv = p == t ? v_new + head * D : static_cast<const T*>(C.v_win) + (head * window + p % window) * D;
+    const int64_t dst = ((int64_t)(b * R + r) * Hkv + h) * D;
+    u32x4 xk = reinterpret_cast<const u32x4*>(sk)[pc];
+    if constexpr (ROT) {
+      if (p == t && kf_new != nullptr) {
+        xk = reinterpret_cast<const u32x4*>(kf_new + head * D)[pc];
+      } else if (rope.cos != nullptr && pc * EPP < rope.rot_dim) {
+        if (p >= rope.n_pos) out_of_tables = true;
+        else xk = unrotate_piece<T>(rope, p, pc * EPP, xk, sk);
+      }
+    }
+    reinterpret_cast<u32x4*>(win_k + dst)[pc] = xk;
+    reinterpret_cast<u32x4*>(win_v + dst)[pc] = reinterpret_cast<const u32x4*>(sv)[pc];
+  }
+  if (out_of_tables && status != nullptr) atomicOr(status, LTEA_ROPE_RANGE);
+}
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, const T* __restrict__ kf_new,
+                      RopeDev rope, int32_t* __restrict__ status, T* __restrict__ win_k, T* __restrict__ win_v,
+                      int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho, int stride_rows,
+                      uint8_t* __restrict__ row_valid) {
+  pack_window<T, true>(C, k_new, v_new, kf_new, rope, status, win_k, win_v, cu2, B, Hkv, D, window, rho, stride_rows,
+                       row_valid, (int)blockIdx.x);
+}
+
 // Partial record per (sequence, query head, split): [max, sum, acc[D]] floats.
 // GT = query heads of a KV group handled per pass over the rows (1, 2 or 4): every K/V row is loaded once per pass
 // and used for GT queries, so grouped-query configurations do not re-stream the cache once per query head.
@@ -412,23 +486,11 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
 
   const int Hkv = P.Hkv, window = P.window, budget = P.budget;
   if ((int)blockIdx.x < P.n_score_blocks) {
-    if (P.lazy) {
-      // only the snapshot of the token counts that the finishing launch reads
+    if (P.lazy || P.pre_logits != nullptr) {
+      // only the snapshot of the token counts that the finishing launch reads (logits scored outside this launch
+      // are picked up by the finishing launch itself, so nothing here waits for them)
       const int b = blockIdx.x * kThreads + threadIdx.x;
       if (b < P.B) ws_t[b] = C.n_seen[b];
-      return;
-    }
-    if (P.pre_logits != nullptr) {
-      // one thread per (sequence, head): pick the logit of position t - rho out of the sequence's window
-      const int head = blockIdx.x * kThreads + threadIdx.x;
-      if (head < P.B * Hkv) {
-        const int b = head / Hkv, h = head - b * Hkv;
-        const int t = C.n_seen[b];
-        if (h == 0) ws_t[b] = t;
-        const int first = t - 2 * P.rho > 0 ? t - 2 * P.rho : 0;
-        if (t - P.rho >= 0)
-          ws_logit[head] = P.pre_logits[(int64_t)h * P.pre_total + (int64_t)b * P.pre_stride + (t - P.rho - first)];
-      }
       return;
     }
     if constexpr (sizeof(T) == 2 && SK > 0) {
@@ -447,7 +509,16 @@ decode_main_kernel(CnnDev cnn, CacheDev C, StepParams P, const T* __restrict__ q
                        (int64_t)b * Hkv + h, h, t, dyn_lds, ws_logit);
     return;
   }
-  const int work = blockIdx.x - P.n_score_blocks;
+  if ((int)blockIdx.x < P.n_score_blocks + P.n_pack_blocks) {
+    // packing role (multi-layer bf16 CNN): one workgroup per sequence copies the receptive-field window of the token
+    // being finalised into the buffers that the scoring launch between this one and the finishing one reads
+    if constexpr (sizeof(T) == 2)
+      pack_window<T, false>(C, k_new, v_new, nullptr, RopeDev{}, nullptr, static_cast<T*>(P.pk_k), static_cast<T*>(P.pk_v),
+                            P.pk_cu2, P.B, Hkv, D, window, P.rho, P.pre_stride, P.pk_row_valid,
+                            (int)blockIdx.x - P.n_score_blocks);
+    return;
+  }
+  const int work = blockIdx.x - P.n_score_blocks - P.n_pack_blocks;
   const int nsplit = P.nsplit;
   const int split = work % nsplit;
   const int64_t head = work / nsplit;
@@ -620,7 +691,15 @@ decode_finish_kernel(CacheDev C, StepParams P, const T* __restrict__ k_new, cons
   }
   const int cnt_old = budget > 0 ? C.ret_count[head] : 0;
   const float z_e = t >= window ? C.win_score[head * window + slot] : 0.f;
-  const float z_new = (!P.lazy && t - rho >= 0) ? ws_logit[head] : 0.f;
+  // the finalised logit of position t - rho: parked by the main launch's scoring role, or picked out of the
+  // sequence's scored window (its first row is position max(0, t - 2*rho))
+  float z_new = 0.f;
+  if (!P.lazy && t - rho >= 0) {
+    const int first = t - 2 * rho > 0 ? t - 2 * rho : 0;
+    z_new = P.pre_logits != nullptr
+                ? P.pre_logits[(int64_t)h * P.pre_total + (int64_t)b * P.pre_stride + (t - rho - first)]
+                : ws_logit[head];
+  }
   // lazy mode: the token leaving the window must have been scored by a batched scoring call
   const bool late = P.lazy && t >= window && C.n_scored[b] <= t - window;
 
@@ -678,65 +757,6 @@ int lds_row_floats(const ltea_cfg& cfg, const ltea_cnn& cnn) {
   int row_floats = 2 * cfg.D;
   for (int l = 0; l < cnn.n_layers; ++l) row_floats = cnn.c_out[l] > row_floats ? cnn.c_out[l] : row_floats;
   return row_floats;
-}
-
-// Receptive-field windows of the token being finalised, packed for the prefill scoring kernels: sequence b gets
-// rows b*R .. b*R + len - 1 (R = 2*rho + 1) holding positions max(0, t - 2*rho) .. t (the ring rows and, last, the
-// incoming token); a second, possibly empty pseudo-sequence covers the unused rest of the R rows so that the packing
-// stays contiguous without a prefix sum over the batch: cu2[2b] = b*R, cu2[2b+1] = b*R + len, cu2[2B] = B*R.
-// Rotary models (rope.cos != null): the ring holds rotated keys, which are rotated back here; the incoming token's
-// scoring key is kf_new when given, else k_new rotated back at position t.
-template <typename T>
-__global__ void __launch_bounds__(256)
-decode_windows_kernel(CacheDev C, const T* __restrict__ k_new, const T* __restrict__ v_new, const T* __restrict__ kf_new,
-                      RopeDev rope, int32_t* __restrict__ status, T* __restrict__ win_k, T* __restrict__ win_v,
-                      int32_t* __restrict__ cu2, int B, int Hkv, int D, int window, int rho, int stride_rows,
-                      uint8_t* __restrict__ row_valid) {
-  constexpr int EPP = Elems<T>::N;
-  const int b = blockIdx.x;
-  const int R = stride_rows;     // 2*rho + 1, or more: windows mode (row_valid given), the rows in between are zeros
-  const int t = C.n_seen[b];
-  const int first = t - 2 * rho > 0 ? t - 2 * rho : 0;
-  const int len = t - first + 1;
-  const int pieces = D / EPP;                                 // 16-byte pieces per row
-  if (row_valid == nullptr) {
-    if (threadIdx.x == 0) {
-      cu2[2 * b] = b * R;
-      cu2[2 * b + 1] = b * R + len;
-      if (b == B - 1) cu2[2 * B] = B * R;
-    }
-  } else {
-    // one sequence of B * R rows; which rows are tokens is said per row, and the others are cleared
-    if (threadIdx.x == 0 && b == 0) { cu2[0] = 0; cu2[1] = B * R; }
-    for (int r = threadIdx.x; r < R; r += 256) row_valid[b * R + r] = r < len ? 1 : 0;
-    const int gap = (R - len) * Hkv * pieces;
-    const int64_t dst0 = (int64_t)(b * R + len) * Hkv * D;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    for (int i = threadIdx.x; i < gap; i += 256) {
-      reinterpret_cast<u32x4*>(win_k + dst0)[i] = zero4;
-      reinterpret_cast<u32x4*>(win_v + dst0)[i] = zero4;
-    }
-  }
-  const int items = len * Hkv * pieces;
-  bool out_of_tables = false;
-  for (int i = threadIdx.x; i < items; i += 256) {
-    const int pc = i % pieces, h = (i / pieces) % Hkv, r = i / (pieces * Hkv);
-    const int p = first + r;
-    const int64_t head = (int64_t)b * Hkv + h;
-    const T* sk = p == t ? k_new + head * D : static_cast<const T*>(C.k_win) + (head * window + p % window) * D;
-    const T* sv = p == t ? v_new + head * D : static_cast<const T*>(C.v_win) + (head * window + p % window) * D;
-    const int64_t dst = ((int64_t)(b * R + r) * Hkv + h) * D;
-    u32x4 xk = reinterpret_cast<const u32x4*>(sk)[pc];
-    if (p == t && kf_new != nullptr) {
-      xk = reinterpret_cast<const u32x4*>(kf_new + head * D)[pc];
-    } else if (rope.cos != nullptr && pc * EPP < rope.rot_dim) {
-      if (p >= rope.n_pos) out_of_tables = true;
-      else xk = unrotate_piece<T>(rope, p, pc * EPP, xk, sk);
-    }
-    reinterpret_cast<u32x4*>(win_k + dst)[pc] = xk;
-    reinterpret_cast<u32x4*>(win_v + dst)[pc] = reinterpret_cast<const u32x4*>(sv)[pc];
-  }
-  if (out_of_tables && status != nullptr) atomicOr(status, LTEA_ROPE_RANGE);
 }
 
 struct PreScore {            // buffers of the window-scoring path, carved from the tail of the workspace
@@ -832,29 +852,22 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
     P.n_score_blocks = (n_seqs + kThreads - 1) / kThreads;
     lds_bytes = 0;
   }
+  P.pk_k = nullptr; P.pk_v = nullptr; P.pk_cu2 = nullptr; P.pk_row_valid = nullptr; P.n_pack_blocks = 0;
+  PreScore ps;
+  memset(&ps, 0, sizeof(ps));
   if constexpr (sizeof(T) == 2) {
     if (prescore) {
-      // multi-layer bf16 CNN: pack the receptive-field windows and run the fused prefill scoring kernel over them
-      // (weights staged once per workgroup instead of once per (sequence, head)), then only pick the logits here
-      PreScore ps;
+      // multi-layer bf16 CNN: the main launch packs the receptive-field windows next to its streaming (one more
+      // workgroup per sequence), the fused prefill scoring kernel runs over them between the two launches of the step
+      // (weights staged once per workgroup instead of once per (sequence, head)), and the finishing launch picks the
+      // centre logits
       prescore_bytes(cfg, cnn, n_seqs, static_cast<char*>(workspace) + up256(base_workspace(cfg, n_seqs)), &ps);
-      hipLaunchKernelGGL(decode_windows_kernel<T>, dim3((unsigned)n_seqs), dim3(256), 0, stream, C,
-                         static_cast<const T*>(k), static_cast<const T*>(v), static_cast<const T*>(nullptr),
-                         rope_dev(nullptr), static_cast<int32_t*>(nullptr), static_cast<T*>(ps.win_k),
-                         static_cast<T*>(ps.win_v), ps.cu2, n_seqs, cfg.Hkv, cfg.D, cfg.window, P.rho, ps.stride,
-                         ps.row_valid);
-      hipError_t e0 = hipGetLastError();
-      if (e0 != hipSuccess) return e0;
-      // windows mode: the whole batch is one sequence of n_seqs * stride rows; else two sequences per window
-      const SeqView sv = ps.row_valid ? SeqView{ps.cu2, 1, ps.total, (int32_t)ps.total}
-                                      : SeqView{ps.cu2, 2 * n_seqs, ps.total, 2 * P.rho + 1};
-      e0 = launch_score_deep(cfg, cnn, ps.win_k, ps.win_v, (int64_t)cfg.Hkv * cfg.D, cfg.D, sv, ps.logits, ps.score_ws, stream,
-                             ps.row_valid);
-      if (e0 != hipSuccess) return e0;
+      P.pk_k = ps.win_k; P.pk_v = ps.win_v; P.pk_cu2 = ps.cu2; P.pk_row_valid = ps.row_valid;
+      P.n_pack_blocks = n_seqs;
       P.pre_logits = ps.logits;
       P.pre_total = ps.total;
       P.pre_stride = ps.stride;
-      P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
+      P.n_score_blocks = (n_seqs + kThreads - 1) / kThreads;
       lds_bytes = 0;
     }
   }
@@ -862,14 +875,14 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   if (given_logits != nullptr) {   // the caller has scored the windows already (rotary models): only pick the logits
     P.pre_logits = given_logits;
     P.pre_total = given_total;
-    P.n_score_blocks = (int)((heads + kThreads - 1) / kThreads);
+    P.n_score_blocks = (n_seqs + kThreads - 1) / kThreads;
     lds_bytes = 0;
   }
   float* partial = static_cast<float*>(workspace);
   float* ws_logit = partial + partial_floats(cfg, n_seqs, P.nsplit);
   int32_t* ws_t = reinterpret_cast<int32_t*>(ws_logit + heads);
   int32_t* ws_dst = ws_t + n_seqs;
-  const unsigned grid = (unsigned)P.n_score_blocks + heads * (unsigned)P.nsplit;
+  const unsigned grid = (unsigned)P.n_score_blocks + (unsigned)P.n_pack_blocks + heads * (unsigned)P.nsplit;
   const int G = cfg.Hq / cfg.Hkv;
   auto launch_main = [&](auto gt, auto sk) {
     hipLaunchKernelGGL((decode_main_kernel<T, D, decltype(gt)::value, decltype(sk)::value>), dim3(grid), dim3(kThreads),
@@ -892,6 +905,14 @@ hipError_t run(const ltea_cfg& cfg, const ltea_cnn* cnn_or_null, const void* q, 
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (P.n_pack_blocks > 0) {
+    // windows mode: the whole batch is one sequence of n_seqs * stride rows; else two sequences per window
+    const SeqView sv = ps.row_valid ? SeqView{ps.cu2, 1, ps.total, (int32_t)ps.total}
+                                    : SeqView{ps.cu2, 2 * n_seqs, ps.total, 2 * P.rho + 1};
+    e = launch_score_deep(cfg, cnn, ps.win_k, ps.win_v, (int64_t)cfg.Hkv * cfg.D, cfg.D, sv, ps.logits, ps.score_ws, stream,
+                          ps.row_valid);
+    if (e != hipSuccess) return e;
+  }
   hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(heads), dim3(kThreads), 0, stream, C, P,
                      static_cast<const T*>(k), static_cast<const T*>(v), partial, ws_logit, ws_t, ws_dst, static_cast<T*>(out));
   return hipGetLastError();
