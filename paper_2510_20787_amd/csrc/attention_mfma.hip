@@ -36,7 +36,7 @@ namespace {
 
 constexpr int BN = 64;   // keys per tile
 constexpr int kThreads = 256;
-constexpr float kLazyMax = 8.0f;  // log2 units
+constexpr float kBig = 1.8446744e19f;  // 2^64: a row sum above this (or not a number) sends the workgroup through its tiles again
 
 template <int D, int QB> struct Geo {
   static constexpr int BM = 128 * QB;           // queries per workgroup
@@ -78,6 +78,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   static_assert(2 * kBuf >= BM * G::OS, "epilogue staging must fit in the tile buffers");
   __shared__ __align__(16) bf16_t lds[2 * kBuf];
   __shared__ int pos_lds[2][BN];
+  __shared__ int redo_flag;
 
   // ---- which (query head, sequence, query tile) is this workgroup? ------------------------------------
   // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of work items so
@@ -208,16 +209,22 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
 
   // ---- online softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
   float m_run[QB], l_part[QB];
+  bool all_have_m = false;     // wave-uniform: every row of the wave has a reference value (m_run finite)
+  bool exact_pass = false;     // workgroup-uniform: second run over the tiles, with the running maximum in every block
   f32x16 o[QB][D / 32];
+  auto reset_rows = [&]() {
+    all_have_m = false;
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = -INFINITY;
-    l_part[qb] = 0.f;
+    for (int qb = 0; qb < QB; ++qb) {
+      m_run[qb] = -INFINITY;
+      l_part[qb] = 0.f;
 #pragma unroll
-    for (int db = 0; db < D / 32; ++db)
+      for (int db = 0; db < D / 32; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
-  }
+        for (int r = 0; r < 16; ++r) o[qb][db][r] = 0.f;
+    }
+  };
+  reset_rows();
 
   // mode: 0 = plain, 1 = window-edge mask (keys jt..), 2 = retained mask (positions in pos_lds).
   // The 64-key tile is consumed as two 32-key halves, each with its own softmax update, so that only one
@@ -244,11 +251,8 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
         for (int qb = 0; qb < QB; ++qb)
           sc[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], qreg[qb][ks], sc[qb], 0, 0, 0);
     };
-    // mask (register r is local key 32*kb + 16*(r/8) + 8*hb + r%8), then raise the running maximum if needed.
-    // Returns whether any lane raised it; the factors the output accumulators still have to be scaled by are left
-    // in alpha[] (the caller applies them once every P.V product issued under the old maximum is in).
-    auto mask_and_max = [&](int kb, f32x16 (&scs)[QB], float (&alpha)[QB]) -> bool {
-      bool any = false;
+    // mask: register r is local key 32*kb + 16*(r/8) + 8*hb + r%8
+    auto apply_mask = [&](int kb, f32x16 (&scs)[QB]) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         f32x16& sc = scs[qb];
@@ -276,31 +280,38 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
             for (int e = 0; e < 8; ++e) sc[8 * r8 + e] = (pp[e] <= lim) ? sc[8 * r8 + e] : -INFINITY;
           }
         }
+      }
+    };
+    // The reference value m of a row (probabilities are exp2(score - m)) only has to keep the exponentials in range,
+    // so it is not the running maximum: a row takes the maximum of the first block in which it sees a key and keeps it
+    // (l is then at least the 1 of that block, and the softmax is the same function of the scores for any m).  Scores
+    // that later exceed m by more than the exponent range allows show up as a huge or non-finite row sum when the
+    // tiles are done; the workgroup then runs its tiles a second time with the exact running maximum in every block.
+    auto raise_reference = [&](const f32x16 (&scs)[QB]) {
+      bool still_none = false;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const f32x16& sc = scs[qb];
         float mx = fmaxf(sc[0], sc[1]);
 #pragma unroll
         for (int r = 2; r < 16; r += 2) mx = fmaxf(fmaxf(mx, sc[r]), sc[r + 1]);
         mx = pair_max(mx);
-        const float mcand = mx * scale_log2e;
-        const bool grow = mcand > m_run[qb] + kLazyMax;   // true on the first visible keys (m_run = -inf)
-        alpha[qb] = 1.0f;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
-          any = true;
-          alpha[qb] = grow ? __builtin_amdgcn_exp2f(m_run[qb] - mcand) : 1.0f;
-          m_run[qb] = grow ? mcand : m_run[qb];
-          l_part[qb] *= alpha[qb];
+        const float m_new = fmaxf(m_run[qb], mx * scale_log2e);
+        // nothing visible so far and nothing now: m stays -inf, and the factor must not become exp2(nan)
+        const float a = (m_new == m_run[qb]) ? 1.0f : __builtin_amdgcn_exp2f(m_run[qb] - m_new);
+        m_run[qb] = m_new;
+        l_part[qb] *= a;
+        if (__builtin_amdgcn_ballot_w64(a != 1.0f) != 0ull) {
+#pragma unroll
+          for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[qb][db][r] *= a;
         }
+        still_none = still_none || (m_new == -INFINITY);
       }
-      return any;
+      all_have_m = __builtin_amdgcn_ballot_w64(still_none) == 0ull;
     };
-    auto rescale = [&](const float (&alpha)[QB]) {
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[qb][db][r] *= alpha[qb];
-    };
-    auto exp_block = [&](const f32x16 (&scs)[QB], bf16x8 (&pb)[QB][2]) {
+    auto exp_block = [&](const f32x16 (&scs)[QB], bf16x8 (&pb)[QB][2], float (&psum)[QB]) {
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         const float m_use = (m_run[qb] == -INFINITY) ? 0.f : m_run[qb];
@@ -322,13 +333,23 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
           psum0 = __builtin_amdgcn_fdot2_f32_bf16(e0, ones, psum0, false);
           psum1 = __builtin_amdgcn_fdot2_f32_bf16(e1, ones, psum1, false);
         }
-        l_part[qb] += psum0 + psum1;
+        psum[qb] = psum0 + psum1;
+      }
+    };
+    // Softmax of one 32-key block whose (masked) scores are in s: probabilities to p, row sums to l_part
+    auto softmax_block = [&](int kb, f32x16 (&s)[QB], bf16x8 (&p)[QB][2]) {
+      float psum[QB];
+      if (!all_have_m || exact_pass) raise_reference(s);
+      exp_block(s, p, psum);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        l_part[qb] += psum[qb];
         // Pin the packed probabilities here: without a use in this block the compiler sinks the exponentials
         // past the following branches, away from the MFMAs they are meant to overlap with.
-        u32x4 w0 = __builtin_bit_cast(u32x4, pb[qb][0]), w1 = __builtin_bit_cast(u32x4, pb[qb][1]);
+        u32x4 w0 = __builtin_bit_cast(u32x4, p[qb][0]), w1 = __builtin_bit_cast(u32x4, p[qb][1]);
         asm volatile("" : "+v"(w0), "+v"(w1), "+v"(l_part[qb]));
-        pb[qb][0] = __builtin_bit_cast(bf16x8, w0);
-        pb[qb][1] = __builtin_bit_cast(bf16x8, w1);
+        p[qb][0] = __builtin_bit_cast(bf16x8, w0);
+        p[qb][1] = __builtin_bit_cast(bf16x8, w1);
       }
     };
     auto load_v_ops = [&](int kb, bf16x8 (&av)[D / 32][2]) {
@@ -353,23 +374,21 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     constexpr bool kEarlyV = D == 128;
     f32x16 s0[QB], s1[QB];
     bf16x8 p0[QB][2], p1[QB][2];
-    float alpha[QB];
     bf16x8 ak0[D / 16], ak1[D / 16];
     load_k_ops(0, ak0);
     load_k_ops(1, ak1);        // requested together with block 0's operands: their LDS latency passes under block 0
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * (D / 16), 0);   // all operand reads first
     score_block(ak0, s0);
-    if (mask_and_max(0, s0, alpha)) rescale(alpha);
+    apply_mask(0, s0);
     score_block(ak1, s1);
     bf16x8 av0[D / 32][2], av1[D / 32][2];
     if constexpr (kEarlyV) load_v_ops(0, av0);
-    exp_block(s0, p0);
-    const bool grew = mask_and_max(1, s1, alpha);   // p0 was formed under the previous maximum:
+    softmax_block(0, s0, p0);
+    apply_mask(1, s1);
     if constexpr (kEarlyV) load_v_ops(1, av1);
     else load_v_ops(0, av0);
-    pv_block(av0, p0);                              //   its product goes in before the accumulators are scaled
-    exp_block(s1, p1);
-    if (grew) rescale(alpha);
+    pv_block(av0, p0);
+    softmax_block(1, s1, p1);   // if it scales the accumulators, block 0's product (formed under the old m) is in them
     if constexpr (!kEarlyV) load_v_ops(1, av1);
     pv_block(av1, p1);
   };
@@ -401,11 +420,25 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
     mode = __builtin_amdgcn_readfirstlane(mode);
     if (mode >= 0) compute(mode, buf, pos_lds[t & 1], jt);
   };
-  TR regs;
-  load_tile(0, regs);
-  store_tile(0, regs);
-  if (n_tiles > 1) load_tile(1, regs);
-  for (int t = 0; t < n_tiles; ++t) step(t, regs);
+  if (tid == 0) redo_flag = 0;
+#pragma unroll 1
+  for (int pass = 0; pass < 2; ++pass) {
+    TR regs;
+    load_tile(0, regs);
+    store_tile(0, regs);
+    if (n_tiles > 1) load_tile(1, regs);
+    for (int t = 0; t < n_tiles; ++t) step(t, regs);
+    if (exact_pass) break;
+    // did a row's reference value fall so far below its scores that its sums left the range?
+    bool bad = false;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) bad = bad || !(l_part[qb] <= kBig);
+    if (__builtin_amdgcn_ballot_w64(bad) != 0ull && lane == 0) redo_flag = 1;
+    __syncthreads();  // also: tile buffers are free
+    if (redo_flag == 0) break;
+    exact_pass = true;
+    reset_rows();
+  }
 
   // ---- epilogue: normalise, stage through LDS, store rows coalesced -------------------------------------------
   __syncthreads();  // tile buffers are free

@@ -249,6 +249,50 @@ def test_sparse_attention_uniform_keep(dtype, D, G):
         check_output(out[lo:hi], ref, dtype, f"seq {s}")
 
 
+@pytest.mark.parametrize("D,G", [(64, 1), (64, 4), (128, 1), (128, 4)])
+def test_sparse_attention_scores_far_above_the_first_block(D, G):
+    """Keys that grow 64-fold later in the sequence: a row's later scores exceed the maximum of the first block it
+    sees by hundreds of binary orders, more than the exponent range covers.  The MFMA kernel keeps the reference
+    value of a row from that first block; such rows must come out right all the same (it runs the workgroup's
+    tiles again with the running maximum).  Softmax rows are then nearly one-hot, so the output is the value row of
+    the best key."""
+    lens = [700, 333, 64]
+    w = wl.make_prefill("late_big", 53 + D + G, "bf16", lens, 2 * G, 2, D, 128, 40, qkv_scale=1.0)
+    for s, n in enumerate(lens):
+        lo = int(w.cu_seqlens[s])
+        j = np.arange(n)
+        big = (j >= 90) & ((j % 3 == 0) | (j > n // 2))
+        w.k[lo:lo + n][big] *= 64.0          # a power of two: the values stay on the bf16 grid
+    d = DeviceWorkload(w)
+    cache = d.new_cache()
+    ocfg = oracle_cfg(w)
+    keep = {}
+    pos = np.zeros((w.n_seqs, w.Hkv, w.budget), np.int32)
+    cnt = np.zeros((w.n_seqs, w.Hkv), np.int32)
+    kq, vq = to_np(d.k), to_np(d.v)
+    kr = np.zeros((w.n_seqs, w.Hkv, w.budget, D), np.float32)
+    vr = np.zeros_like(kr)
+    for s, n in enumerate(lens):
+        lo = int(w.cu_seqlens[s])
+        for h in range(w.Hkv):
+            p = np.arange(h, n, 11 + 2 * h)[: w.budget]
+            keep[(s, h)] = p
+            cnt[s, h] = len(p)
+            pos[s, h, :len(p)] = p
+            kr[s, h, :len(p)] = kq[lo + p, h]
+            vr[s, h, :len(p)] = vq[lo + p, h]
+    cache.ret_pos.copy_(torch.from_numpy(pos))
+    cache.ret_count.copy_(torch.from_numpy(cnt))
+    cache.k_ret.copy_(dev(kr, "bf16"))
+    cache.v_ret.copy_(dev(vr, "bf16"))
+    out = to_np(B.ltea_sparse_attention(d.cfg, d.q, d.k, d.v, d.cu, d.max_seqlen, cache))
+    assert np.isfinite(out).all()
+    for s, n in enumerate(lens):
+        lo, hi = int(w.cu_seqlens[s]), int(w.cu_seqlens[s + 1])
+        ref = orc.sparse_attention_sequence(w.q[lo:hi], w.k[lo:hi], w.v[lo:hi], ocfg, [keep[(s, h)] for h in range(w.Hkv)])
+        check_output(out[lo:hi], ref, "bf16", f"seq {s}")
+
+
 # ------------------------------------------------------------------------------------------------
 # (a)+(b)+(c) prefill end to end
 # ------------------------------------------------------------------------------------------------
