@@ -7,13 +7,14 @@
 // only tiles that straddle a window edge, the causal diagonal, the sequence end or the visibility frontier of
 // the retained entries pay for masking.
 //
-// Work split: one workgroup = 128 consecutive queries of one (sequence, query head); 4 waves, each owning a
-// block of 32 queries.  MFMA shapes (v_mfma_f32_32x32x16_bf16, wave64):
+// Work split: one workgroup = 128 consecutive queries of one (sequence, query head), 4 waves each owning a block
+// of 32 queries; or, for grouped-query shapes, the same 32 queries of four query heads that share a KV head, one
+// head per wave.  MFMA shapes (v_mfma_f32_32x32x16_bf16, wave64):
 //   S^T[key, query] = K[key, :] . Q[query, :]   A = K tile rows from LDS, B = Q fragment held in registers
 //   O^T[d, query]  += V^T[d, key] . P^T[key, query]   A = V^T fragments from LDS, B = P^T straight from S^T's
 //                                                     accumulator registers (no shuffle, no LDS round trip)
-// In the 32x32 accumulator layout a lane owns one query column, so the online-softmax statistics are
-// per-lane scalars (the two lanes sharing a query exchange one value per 32 keys).  The contraction index of
+// In the 32x32 accumulator layout a lane owns one query column, so the softmax statistics are per-lane scalars
+// (the two lanes sharing a query keep separate partial sums and meet once, in the epilogue).  The contraction index of
 // the second product is the key index; the rows of the K tile are fed to the first MFMA in a permuted
 // order so that each lane's eight P values per MFMA are eight consecutive keys.  V stays row-major in LDS
 // and its A operand (eight consecutive keys of one column per lane) comes out of the transposing LDS load
@@ -21,9 +22,11 @@
 // staging stores spread over the 64 banks without padding.
 // K/V tiles are double-buffered in LDS and prefetched one tile ahead through registers, one barrier per tile
 // (three workgroups share a CU at D = 64, two at D = 128; a 128-VGPR build of the D = 64 kernel reaches four but
-// spills, which costs HBM traffic and gains no time).  The running maximum is only raised when a block of
-// scores exceeds it by more than 2^8 (the result does not depend on the stabiliser), which keeps the accumulator
-// rescale off the common path.  Inside a tile the matrix work of one 32-key block is placed next to the
+// spills, which costs HBM traffic and gains no time).  There is no running maximum: a row's exponentials are taken
+// relative to the maximum of the first block in which it sees a key (the result does not depend on that reference
+// value as long as the exponentials stay in range; a workgroup whose row sums leave the range repeats its tiles with
+// the exact running maximum), which keeps the row-maximum reduction and the accumulator rescale off the common path.
+// Inside a tile the matrix work of one 32-key block is placed next to the
 // exponentials of the other, so that they overlap within the wave's in-order instruction stream.
 #include <type_traits>
 
@@ -207,7 +210,7 @@ attention_mfma_kernel(const bf16_t* __restrict__ q, int64_t q_st, int64_t q_sh, 
   const int tr_swz = chunk_swizzle<D>(tr_key);                  // unchanged by adding multiples of 4 to the key
   const int a_v_off = BN * KS + tr_key * VS + tr_col;
 
-  // ---- online softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
+  // ---- softmax state (per lane = per query; the two lane halves keep separate partial sums) ------
   float m_run[QB], l_part[QB];
   bool all_have_m = false;     // wave-uniform: every row of the wave has a reference value (m_run finite)
   bool exact_pass = false;     // workgroup-uniform: second run over the tiles, with the running maximum in every block
