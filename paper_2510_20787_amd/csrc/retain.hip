@@ -121,10 +121,24 @@ retain_kernel(const RetainArgs a) {
   constexpr int kHeld = CH > 0 ? CH : 1;
   uint32_t held[kHeld][kItems];
   if constexpr (CH > 0) {
+    // a thread's four logits of a chunk are consecutive: one 16-byte load where the head's row allows it
+    static_assert(kItems == 4, "one float4 per thread and chunk");
+    const bool quads = (reinterpret_cast<uintptr_t>(z) & 15u) == 0;
+    auto key_of = [&](float zj, int j) -> uint32_t {
+      return ((j < a.sink) || (zj > a.tau)) ? order_key(select_key(zj, j, a.sink)) : 0u;
+    };
 #pragma unroll
-    for (int c = 0; c < CH; ++c)
+    for (int c = 0; c < CH; ++c) {
+      const int j0 = c * kChunk + tid * kItems;
+      if (quads && j0 + kItems <= n_out) {
+        const float4 z4 = *reinterpret_cast<const float4*>(z + j0);
+        held[c][0] = key_of(z4.x, j0); held[c][1] = key_of(z4.y, j0 + 1);
+        held[c][2] = key_of(z4.z, j0 + 2); held[c][3] = key_of(z4.w, j0 + 3);
+      } else {
 #pragma unroll
-      for (int e = 0; e < kItems; ++e) held[c][e] = fetch(c * kChunk + tid * kItems + e);
+        for (int e = 0; e < kItems; ++e) held[c][e] = fetch(j0 + e);
+      }
+    }
   }
   const int n_chunks = (n_out + kChunk - 1) / kChunk;
   // A sequence longer than the caller's max_seqlen (which picked CH) does not fit the held registers: its keys are
@@ -245,11 +259,33 @@ retain_kernel(const RetainArgs a) {
   // ---- gather the kept rows (positions written above by this workgroup) ----
   __threadfence_block();
   __syncthreads();
-  for (int i = tid; i < kept_before * pieces; i += kSelThreads) {
-    const int r = i / pieces, pc = i - r * pieces;
-    const int p = a.ret_pos[head * a.budget + r];
-    copy_piece(a, (lo + p) * a.tok_bytes + h * a.head_bytes, a.k_ret + (head * a.budget + r) * a.row_bytes,
-               a.v_ret + (head * a.budget + r) * a.row_bytes, pc);
+  // four pieces per thread in flight: positions first, then all the row loads, then the stores
+  constexpr int kGather = 4;
+  const int n_pieces = kept_before * pieces;
+  for (int i0 = tid; i0 < n_pieces; i0 += kGather * kSelThreads) {
+    int r[kGather], pc[kGather], p[kGather];
+#pragma unroll
+    for (int u = 0; u < kGather; ++u) {
+      const int i = i0 + u * kSelThreads;
+      const int ic = i < n_pieces ? i : i0;          // past the end: this thread's first piece once more, not stored
+      r[u] = ic / pieces;
+      pc[u] = ic - r[u] * pieces;
+      p[u] = a.ret_pos[head * a.budget + r[u]];
+    }
+    u32x4 xk[kGather], xv[kGather];
+#pragma unroll
+    for (int u = 0; u < kGather; ++u) {
+      const int64_t src = (lo + p[u]) * a.tok_bytes + h * a.head_bytes;
+      xk[u] = reinterpret_cast<const u32x4*>(a.k + src)[pc[u]];
+      xv[u] = reinterpret_cast<const u32x4*>(a.v + src)[pc[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < kGather; ++u) {
+      if (i0 + u * kSelThreads < n_pieces) {
+        reinterpret_cast<u32x4*>(a.k_ret + (head * a.budget + r[u]) * a.row_bytes)[pc[u]] = xk[u];
+        reinterpret_cast<u32x4*>(a.v_ret + (head * a.budget + r[u]) * a.row_bytes)[pc[u]] = xv[u];
+      }
+    }
   }
 }
 
